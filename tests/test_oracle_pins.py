@@ -1,0 +1,402 @@
+"""Pins of the CPU oracle against facts that do not come from the oracle itself:
+brute force, closed forms, the quantizer's error bound, invariances, numpy
+library routines and exact rational arithmetic.  The paper prints no worked
+numerical example for this path (its per-layer SQNR / MSE curves are figures),
+so no printed value is available as a fixture."""
+import itertools
+import math
+from fractions import Fraction
+
+import numpy as np
+import pytest
+
+from oracle import reference as orc
+
+A, S, C = orc.ASYM_TENSOR, orc.SYM_TENSOR, orc.SYM_CHANNEL
+
+
+# ----------------------------------------------------------------------------
+# min / max (Sec. 2.1 Eq. 1-2)
+# ----------------------------------------------------------------------------
+def test_minmax_bruteforce_permutations():
+    vals = [-1.5, -1.5, 0.0, -0.0, 2.25, 7.0]
+    for r in range(1, 6):
+        for combo in itertools.permutations(vals, r):
+            mn, mx = orc.minmax(np.array(combo, np.float32))
+            assert mn == min(combo) and mx == max(combo)
+            # -0.0 is reported as +0.0
+            assert not (mn == 0 and math.copysign(1.0, float(mn)) < 0)
+            assert not (mx == 0 and math.copysign(1.0, float(mx)) < 0)
+            i, j = orc.argminmax(np.array(combo, np.float32))
+            assert combo[i] == min(combo) and combo[j] == max(combo)
+            assert i == min(k for k, v in enumerate(combo) if v == min(combo))
+            assert j == min(k for k, v in enumerate(combo) if v == max(combo))
+
+
+def test_minmax_numpy_and_nan():
+    rng = np.random.default_rng(1)
+    x = rng.standard_normal(100_003).astype(np.float32)
+    mn, mx = orc.minmax(x)
+    assert mn == x.min() and mx == x.max()
+    i, j = orc.argminmax(x)
+    assert i == int(np.argmin(x)) and j == int(np.argmax(x))
+    y = x.copy()
+    y[::7] = np.nan                       # NaNs are ignored
+    mn, mx = orc.minmax(y)
+    assert mn == np.nanmin(y) and mx == np.nanmax(y)
+    mn, mx = orc.minmax(np.array([3.5], np.float32))
+    assert mn == 3.5 and mx == 3.5
+
+
+# ----------------------------------------------------------------------------
+# scale / zero-point closed forms (Eq. 2 with N = 256; Sec. 4 Eq. 4 with b = 8)
+# ----------------------------------------------------------------------------
+def test_params_closed_forms():
+    # x in {-8, ..., 7.9375} step 2^-4: hi - lo = 15.9375, step 0.0625 exactly, zp = 0
+    sc, inv, zp = orc.params(-8.0, 7.9375, A)
+    assert sc == np.float32(0.0625) and inv == np.float32(16.0) and zp == 0
+    # ReLU6 range [0, 6]
+    sc, inv, zp = orc.params(0.0, 6.0, A)
+    assert sc == np.float32(6.0) / np.float32(255.0)
+    assert inv == np.float32(1.0) / sc and zp == -128
+    # all-negative tensor: range widened to contain 0 -> zero maps to the top code
+    sc, inv, zp = orc.params(-3.0, -1.0, A)
+    assert sc == np.float32(3.0) / np.float32(255.0) and zp == 127
+    # all-positive tensor: lo = 0
+    sc, inv, zp = orc.params(2.0, 5.0, A)
+    assert sc == np.float32(5.0) / np.float32(255.0) and zp == -128
+    # symmetric: absmax 127 -> unit step
+    for scheme in (S, C):
+        sc, inv, zp = orc.params(-127.0, 3.0, scheme)
+        assert sc == 1.0 and inv == 1.0 and zp == 0
+        sc, inv, zp = orc.params(-1.0, 63.5, scheme)
+        assert sc == 0.5 and inv == 2.0 and zp == 0
+    # degenerate: all zeros, or a sub-normal step
+    for scheme in (A, S):
+        assert orc.params(0.0, 0.0, scheme) == (1.0, 1.0, 0)
+        assert orc.params(0.0, 1e-40, scheme) == (1.0, 1.0, 0)
+
+
+def test_zero_is_exact_and_zp_in_range():
+    rng = np.random.default_rng(2)
+    for _ in range(200):
+        lo, hi = sorted(rng.standard_normal(2) * 10.0 ** rng.integers(-3, 4))
+        sc, inv, zp = orc.params(lo, hi, A)
+        assert -128 <= zp <= 127
+        q = orc.quantize(np.zeros(1, np.float32), inv, zp)
+        assert q[0] == zp
+        assert orc.dequantize(q, sc, zp)[0] == 0.0
+
+
+# ----------------------------------------------------------------------------
+# int8 codes (Eq. 1 / Eq. 5) and dequantization (Eq. 3)
+# ----------------------------------------------------------------------------
+@pytest.mark.parametrize("zp,scale", [(0, 0.0625), (-128, 0.5), (-3, 2.0 ** -10), (100, 4.0)])
+def test_int8_grid_gives_zero_error(zp, scale):
+    k = np.arange(-128, 128, dtype=np.int32)
+    x = ((k - zp).astype(np.float32) * np.float32(scale)).astype(np.float32)
+    cal = orc.calibrate(x, A)
+    # the calibrated step is the grid's own step (255 * 2^k / 255), so the grid is reproduced
+    assert cal.scale[0] == np.float32(scale) and cal.zp[0] == zp
+    fq = orc.fakequant(x, cal, A, keep_xhat=True)
+    assert np.array_equal(fq.codes.astype(np.int32), k)
+    assert np.array_equal(fq.xhat, x)
+    m = orc.tensor_metrics(x, cal, fq)
+    assert m.mse == 0.0 and m.sqnr_db == math.inf
+
+
+def test_idempotence_and_power_of_two_invariance():
+    rng = np.random.default_rng(3)
+    x = (rng.standard_normal(50_000) * 0.7).astype(np.float32)
+    cal = orc.calibrate(x, A)
+    fq = orc.fakequant(x, cal, A, keep_xhat=True)
+    # quantizing the dequantized tensor with the same parameters is the identity
+    fq2 = orc.fakequant(fq.xhat, cal, A, keep_xhat=True)
+    assert np.array_equal(fq2.codes, fq.codes) and fq2.sum_e2[0] == 0.0
+    base = orc.tensor_metrics(x, cal, fq)
+    for k in (-7, 5):
+        y = (x * np.float32(2.0 ** k)).astype(np.float32)
+        cy = orc.calibrate(y, A)
+        fy = orc.fakequant(y, cy, A)
+        assert cy.zp[0] == cal.zp[0] and cy.scale[0] == cal.scale[0] * np.float32(2.0 ** k)
+        assert np.array_equal(fy.codes, fq.codes)
+        my = orc.tensor_metrics(y, cy, fy)
+        assert my.mse == pytest.approx(base.mse * 4.0 ** k, rel=1e-12)
+        assert my.sqnr_db == pytest.approx(base.sqnr_db, abs=1e-9)
+
+
+@pytest.mark.parametrize("scheme", [A, S])
+def test_codes_are_nearest_grid_point_exact_arithmetic(scheme):
+    """Against the definition in exact rationals: the code is the grid point
+    nearest to x (ties aside), clamped to int8."""
+    rng = np.random.default_rng(4)
+    x = (rng.standard_normal(3000) * 1.3).astype(np.float32)
+    cal = orc.calibrate(x, scheme)
+    q = orc.fakequant(x, cal, scheme).codes.astype(int)
+    sc, zp = Fraction(float(cal.scale[0])), int(cal.zp[0])
+    n_edge = 0
+    for xi, qi in zip(x.tolist(), q.tolist()):
+        t = Fraction(xi) / sc + zp                 # exact position on the code axis
+        near = max(-128, min(127, math.floor(t + Fraction(1, 2))))
+        frac = abs((t - math.floor(t)) - Fraction(1, 2))
+        if frac < Fraction(1, 10_000):              # fp32 multiply may tip a near-tie
+            n_edge += 1
+            assert abs(qi - near) <= 1
+        else:
+            assert qi == near
+    assert n_edge < 20
+    assert q.min() >= -128 and q.max() <= 127
+    if scheme == A:
+        assert q.min() == -128 and q.max() == 127   # the full range is used
+
+
+def test_round_half_to_even_and_clamp():
+    # step 1, zp 0: ties go to the even code; out-of-range values saturate
+    x = np.array([0.5, 1.5, 2.5, -0.5, -1.5, -2.5, 126.5, 127.5, 1e6, -128.5, -129.5, -1e30],
+                 np.float32)
+    q = orc.quantize(x, 1.0, 0)
+    assert q.tolist() == [0, 2, 2, 0, -2, -2, 126, 127, 127, -128, -128, -128]
+    # zero-point is added after rounding: rne(0.5) + 1 = 1, not rne(1.5) = 2
+    assert orc.quantize(np.array([0.5], np.float32), 1.0, 1).tolist() == [1]
+    xh = orc.dequantize(np.array([-128, 0, 5, 127], np.int8), 0.25, 5)
+    assert xh.tolist() == [-33.25, -1.25, 0.0, 30.5]
+
+
+# ----------------------------------------------------------------------------
+# MSE (Eq. 7): error bound of the method, numpy, cross-check
+# ----------------------------------------------------------------------------
+@pytest.mark.parametrize("scheme", [A, S])
+def test_error_bound_and_uniform_noise_model(scheme):
+    rng = np.random.default_rng(5)
+    x = (rng.standard_normal(400_000) * 2.0).astype(np.float32)
+    cal = orc.calibrate(x, scheme)
+    fq = orc.fakequant(x, cal, scheme, keep_xhat=True)
+    sc = float(cal.scale[0])
+    err = np.abs(x.astype(np.float64) - fq.xhat.astype(np.float64))
+    assert err.max() <= sc * (1.0 + 1e-6)            # range ends (rounded zero-point)
+    inner = (fq.codes > -128) & (fq.codes < 127)
+    assert err[inner].max() <= sc * 0.5 * (1.0 + 1e-5)
+    m = orc.tensor_metrics(x, cal, fq)
+    assert m.mse <= sc * sc / 4.0
+    assert m.mse == pytest.approx(sc * sc / 12.0, rel=0.02)
+    # numpy float64 library routine
+    ref = np.mean((x.astype(np.float64) - fq.xhat.astype(np.float64)) ** 2)
+    assert m.mse == pytest.approx(ref, rel=1e-12)
+    # pair metrics on (x, dequantized x) equal the quantizer's own error sums
+    p = orc.pair_metrics(x, fq.xhat)
+    assert p.sum_d2 == fq.sum_e2[0] and p.sum_ref2 == fq.sum_x2[0]
+    assert p.mse == m.mse and p.sqnr_db == m.sqnr_db
+
+
+def test_pair_metrics_numpy_and_asymmetry():
+    rng = np.random.default_rng(6)
+    a = rng.standard_normal(10_001).astype(np.float32)
+    b = (a + 0.01 * rng.standard_normal(10_001)).astype(np.float32)
+    p = orc.pair_metrics(a, b)
+    a64, b64 = a.astype(np.float64), b.astype(np.float64)
+    assert p.sum_ref2 == pytest.approx(np.sum(a64 * a64), rel=1e-13)
+    assert p.sum_d2 == pytest.approx(np.sum((a64 - b64) ** 2), rel=1e-13)
+    assert p.sqnr_db == pytest.approx(10 * np.log10(np.sum(a64 * a64) / np.sum((a64 - b64) ** 2)), abs=1e-10)
+    # the signal is the first argument: swapping changes the signal energy only
+    p2 = orc.pair_metrics(b, a)
+    assert p2.sum_d2 == pytest.approx(p.sum_d2, rel=1e-13)
+    assert p2.sum_ref2 == pytest.approx(np.sum(b64 * b64), rel=1e-13)
+    # a constant offset c gives MSE = c^2 exactly
+    c = orc.pair_metrics(a, a + np.float32(0.5))
+    assert c.mse == pytest.approx(0.25, rel=1e-6)
+
+
+# ----------------------------------------------------------------------------
+# SQNR closed forms (Eq. 6)
+# ----------------------------------------------------------------------------
+def _sqnr(x, scheme=A):
+    cal = orc.calibrate(x, scheme)
+    fq = orc.fakequant(x, cal, scheme)
+    return orc.tensor_metrics(x, cal, fq).sqnr_db, cal
+
+
+def test_sqnr_uniform_closed_form():
+    rng = np.random.default_rng(7)
+    x = rng.uniform(-1.0, 1.0, 2_000_000).astype(np.float32)
+    s, _ = _sqnr(x)
+    # P_s = 1/3, P_n = (2/255)^2 / 12  ->  20 log10(255) = 48.13 dB
+    assert s == pytest.approx(20 * math.log10(255.0), abs=0.05)
+
+
+def test_sqnr_sine_closed_form():
+    t = np.arange(4_000_000, dtype=np.float64)
+    x = np.sin(t * 0.001234567).astype(np.float32)
+    s, _ = _sqnr(x)
+    # full-scale sine: 1.76 dB above the uniform input (6.02 * 8 + 1.76 neighbourhood)
+    assert s == pytest.approx(20 * math.log10(255.0) + 10 * math.log10(1.5), abs=0.25)
+
+
+@pytest.mark.parametrize("sigma", [0.5, 1.3, 2.0])
+def test_sqnr_relu_gaussian_formula(sigma):
+    rng = np.random.default_rng(8)
+    x = np.maximum(rng.standard_normal(2_000_000) * sigma, 0).astype(np.float32)
+    s, cal = _sqnr(x)
+    mx = float(cal.max[0])
+    # P_s = sigma^2 / 2, P_n = (max/255)^2 / 12 on the non-zero half (zeros are exact)
+    expect = 10 * math.log10((sigma ** 2 / 2) / (0.5 * (mx / 255) ** 2 / 12))
+    assert s == pytest.approx(expect, abs=0.05)
+
+
+def test_sqnr_edge_values():
+    assert orc.sqnr_db(1.0, 0.0) == math.inf
+    assert orc.sqnr_db(0.0, 0.0) == math.inf
+    assert orc.sqnr_db(0.0, 1.0) == -math.inf
+    assert orc.sqnr_db(100.0, 1.0) == pytest.approx(20.0, abs=1e-12)
+    assert orc.mse(6.0, 4) == 1.5
+
+
+# ----------------------------------------------------------------------------
+# tensor statistics vs numpy
+# ----------------------------------------------------------------------------
+def test_statistics_numpy():
+    rng = np.random.default_rng(9)
+    x = (rng.standard_normal(123_457) * 3 + 0.7).astype(np.float32)
+    sx, sx2 = orc.moments(x)
+    x64 = x.astype(np.float64)
+    assert sx == pytest.approx(x64.sum(), rel=1e-12)
+    assert sx2 == pytest.approx((x64 * x64).sum(), rel=1e-12)
+    assert orc.variance(x) == pytest.approx(x64.var(), rel=1e-12)
+    cal = orc.calibrate(x, A)
+    m = orc.tensor_metrics(x, cal, orc.fakequant(x, cal, A))
+    assert m.mean == pytest.approx(x64.mean(), rel=1e-12)
+    assert m.var == pytest.approx(x64.var(), rel=1e-12)
+    assert m.absmax == np.abs(x).max() and m.min == x.min() and m.max == x.max()
+
+
+# ----------------------------------------------------------------------------
+# per-output-channel scheme: each channel is an independent per-tensor problem
+# ----------------------------------------------------------------------------
+def test_per_channel_equals_per_row_problems():
+    rng = np.random.default_rng(10)
+    w = (rng.laplace(0, 0.05, (12, 27))).astype(np.float32)
+    w[3] *= 20
+    w[5] = 0.0                                       # a dead channel is degenerate
+    cal = orc.calibrate(w, C, 12)
+    fq = orc.fakequant(w, cal, C, 12)
+    for c in range(12):
+        rc = orc.calibrate(w[c], S)
+        rf = orc.fakequant(w[c], rc, S)
+        assert cal.scale[c] == rc.scale[0] and cal.zp[c] == 0
+        assert cal.min[c] == w[c].min() and cal.max[c] == w[c].max()
+        assert np.array_equal(fq.codes.reshape(12, 27)[c], rf.codes)
+        assert fq.sum_e2[c] == rf.sum_e2[0]
+    assert cal.scale[5] == 1.0 and fq.sum_e2[5] == 0.0
+    m = orc.tensor_metrics(w, cal, fq)
+    assert m.mse == pytest.approx(fq.sum_e2.sum() / w.size, rel=1e-13)
+    # per-channel steps never lose to the single per-tensor step on outlier channels
+    ct = orc.calibrate(w, S)
+    mt = orc.tensor_metrics(w, ct, orc.fakequant(w, ct, S))
+    assert m.mse < mt.mse
+    with pytest.raises(ValueError):
+        orc.calibrate(w, C, 5)
+
+
+# ----------------------------------------------------------------------------
+# SQNR delta (Sec. 6.4 Eq. 16)
+# ----------------------------------------------------------------------------
+def test_sqnr_delta_hand_worked():
+    s = [40.0, 37.0, 43.0, 43.0, 20.0]
+    assert orc.sqnr_deltas(s) == [0.0, -3.0, 6.0, 0.0, -23.0]
+    assert np.allclose(orc.sqnr_deltas(s)[1:], np.diff(s))
+    # real graph positions: the difference is divided by the distance
+    assert orc.sqnr_deltas(s, [0, 2, 5, 6, 16]) == [0.0, -1.5, 2.0, 0.0, -2.3]
+    # infinite SQNR is clamped before differencing
+    assert orc.sqnr_deltas([math.inf, 50.0, -math.inf], cap_db=200.0) == [0.0, -150.0, -250.0]
+    with pytest.raises(ValueError):
+        orc.sqnr_deltas(s, [0, 1, 1, 2, 3])
+
+
+# ----------------------------------------------------------------------------
+# Algorithm 2 (RankLayersBySensitivity)
+# ----------------------------------------------------------------------------
+def test_rank_equals_stable_argsort_without_outliers():
+    rng = np.random.default_rng(11)
+    for _ in range(50):
+        n = int(rng.integers(1, 40))
+        w = rng.uniform(20, 50, n).round(0)           # rounded -> ties occur
+        a = rng.uniform(20, 50, n).round(0)
+        flat = np.ones(n)
+        order, G = orc.rank_layers(w, a, flat, flat)
+        dw = np.concatenate([[0.0], np.diff(w)])
+        da = np.concatenate([[0.0], np.diff(a)])
+        g = 0.6 * dw + 0.4 * da
+        assert np.allclose(G, g, rtol=0, atol=1e-12)
+        assert order == list(np.argsort(np.asarray(G), kind="stable"))
+
+
+def test_rank_hand_worked_outliers():
+    w = [40.0, 38.0, 45.0, 30.0, 31.0, 50.0]
+    a = [30.0, 30.0, 30.0, 30.0, 30.0, 30.0]
+    # weight deltas: 0 -2 7 -15 1 19 ; score = 0.6 * delta
+    flat = [1.0] * 6
+    order, G = orc.rank_layers(w, a, flat, flat)
+    assert order == [3, 1, 0, 4, 2, 5]
+    assert G == pytest.approx([0.0, -1.2, 4.2, -9.0, 0.6, 11.4])
+    # one activation-MSE outlier (layer 5: 100 > 5 * mean 17.5): moved to the front
+    m1 = [1.0, 1.0, 1.0, 1.0, 1.0, 100.0]
+    assert orc.rank_layers(w, a, flat, m1)[0] == [5, 3, 1, 0, 4, 2]
+    # exactly 5x the mean is not an outlier (strict inequality): mean 2, m = 10
+    m_eq = [10.0, 0.0, 0.5, 0.5, 0.5, 0.5]
+    assert orc.rank_layers(w, a, flat, m_eq)[0] == [3, 1, 0, 4, 2, 5]
+    # two outliers among 12 layers: the larger MSE comes first
+    w12 = [40.0 - i for i in range(12)]
+    a12 = [30.0] * 12
+    m2 = [1.0] * 12
+    m2[4], m2[9] = 60.0, 90.0                         # mean 13.33, threshold 66.7 -> only 9
+    assert orc.rank_layers(w12, a12, m2, m2)[0][:1] == [9]
+    m2[4], m2[9] = 200.0, 300.0                       # mean 42.5, threshold 212.5 -> only 9
+    assert orc.rank_layers(w12, a12, m2, m2)[0][0] == 9
+    m3 = [1.0] * 30
+    m3[7], m3[20] = 50.0, 80.0                        # mean 5.27, threshold 26.3 -> both
+    order = orc.rank_layers([40.0] * 30, [30.0] * 30, m3, m3)[0]
+    assert order[:2] == [20, 7] and order[2:] == [i for i in range(30) if i not in (7, 20)]
+    # outlier that is already first stays first; equal outliers: lower index first
+    m4 = [1.0] * 30
+    m4[3] = m4[11] = 70.0
+    order = orc.rank_layers([40.0] * 30, [30.0] * 30, m4, m4)[0]
+    assert order[:3] == [3, 11, 0]
+
+
+def test_rank_mse_sources_and_gains():
+    w = [40.0, 30.0, 35.0, 20.0]
+    a = [40.0, 45.0, 25.0, 44.0]
+    wm = [1.0] * 20
+    am = [1.0] * 20
+    w20 = w + [20.0] * 16
+    a20 = a + [44.0] * 16
+    wm[2] = 100.0
+    am[1] = 100.0
+    cfg = orc.RankConfig
+    assert orc.rank_layers(w20, a20, wm, am, cfg=cfg(mse_source=0))[0][0] == 1
+    assert orc.rank_layers(w20, a20, wm, am, cfg=cfg(mse_source=1))[0][0] == 2
+    o2 = orc.rank_layers(w20, a20, wm, am, cfg=cfg(mse_source=2))[0]
+    assert set(o2[:2]) == {1, 2} and o2[:2] == [1, 2]      # equal ratios: lower index first
+    # activation gain 0 reproduces a weight-delta-only list
+    o = orc.rank_layers(w, a, [1.0] * 4, [1.0] * 4, cfg=cfg(alpha_w=1.0, alpha_a=0.0))[0]
+    assert o == [3, 1, 0, 2]                                # deltas 0 -10 5 -15
+    o = orc.rank_layers(w, a, [1.0] * 4, [1.0] * 4, cfg=cfg(alpha_w=0.0, alpha_a=1.0))[0]
+    assert o == [2, 0, 1, 3]                                # deltas 0 5 -20 19
+    with pytest.raises(ValueError):
+        orc.rank_layers(w, a, [1.0] * 4, [1.0, math.nan, 1.0, 1.0])
+
+
+def test_rank_bruteforce_properties():
+    rng = np.random.default_rng(12)
+    for _ in range(200):
+        n = int(rng.integers(1, 60))
+        w = rng.uniform(10, 60, n)
+        a = rng.uniform(10, 60, n)
+        m = rng.lognormal(0, 2.0, n)                  # heavy tail -> outliers happen
+        order, G = orc.rank_layers(w, a, m, m)
+        assert sorted(order) == list(range(n))        # a permutation
+        out = [i for i in range(n) if m[i] > 5 * (math.fsum(m) / n)]
+        k = len(out)
+        assert set(order[:k]) == set(out)             # outliers form the prefix ...
+        assert all(m[order[i]] >= m[order[i + 1]] for i in range(k - 1))   # ... by descending MSE
+        rest = order[k:]
+        assert all((G[rest[i]], rest[i]) <= (G[rest[i + 1]], rest[i + 1]) for i in range(len(rest) - 1))
