@@ -1,0 +1,238 @@
+#!/usr/bin/env python3
+"""Benchmark of the QuantuneV2 sensitivity pass on one MI355X.
+
+One step = one pass of the whole hot path over the layer table: calibrate
+(min/max, statistics, scale, zero-point) -> fake-quantize (int8 codes, error
+energies) -> pair metrics (fp32-run vs quantized-run activations) -> copy the
+per-segment records to the host -> finalize (MSE, SQNR, mean, var) -> SQNR
+delta and ranking.  Inputs are synthetic, seeded, and resident in HBM before
+the timed region starts.
+
+Workload at N=1: ResNet-50 v1 shapes, batch 256, 224x224 (54 weights,
+per-output-channel symmetric; 54 activations with their quantized-run partners,
+per-tensor asymmetric).
+
+Prints ONE JSON line.  `value` is algorithmic bytes per pass / time per pass:
+4 B/element for calibrate, 5 for fake-quant (4 read + 1 code written), 8 for the
+pair metrics, i.e. 9 B per weight element and 17 B per activation element.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0   # MI355X published HBM3E bandwidth
+
+# HBM bytes per k_pair_stream launch on the resnet50 b256 workload from rocprofv3 --pmc
+# (FETCH_SIZE and WRITE_SIZE runs, each scaled by a copy kernel of known size); see
+# profiles/.  None until measured.
+PAIR_KERNEL_TRAFFIC_BYTES = None
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="resnet50", choices=["resnet50", "resnet18", "vgg16", "mobilenetv2"])
+    ap.add_argument("--batch", type=int, default=None, help="override the workload's batch (smaller = not the headline config)")
+    ap.add_argument("--fused", action="store_true", help="BN-folded weight variant of resnet50")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample-elems", type=int, default=600_000_000)
+    return ap.parse_args()
+
+
+def build_workload(args, dev):
+    import torch
+    from paper_2501_07161_amd import binding as qb
+    from paper_2501_07161_amd import synth
+
+    defaults = {"resnet50": 256, "resnet18": 32, "vgg16": 16, "mobilenetv2": 64}
+    batch = args.batch or defaults[args.workload]
+    if args.workload == "resnet50":
+        specs = synth.config_resnet50(batch, fused=args.fused)
+    elif args.workload == "vgg16":
+        specs = synth.config_vgg16(batch, per_channel=True)
+    else:
+        specs = synth.CONFIGS[args.workload](batch)
+    xs = [synth.materialize(s, dev) for s in specs]
+    codes = [torch.empty(x.numel(), dtype=torch.int8, device=dev) for x in xs]
+
+    # quantized-run partners: dequant(quant(ref)) + N(0, (0.01 std(ref))^2).  Built here with
+    # the library's own calibrate / fake-quant (untimed set-up) and plain torch arithmetic.
+    rows0 = [qb.TensorArg(x=x, numel=x.numel(), scheme=s.scheme, channels=s.channels, codes=c,
+                          kind=s.kind, layer=s.layer) for x, s, c in zip(xs, specs, codes)]
+    plan0 = qb.qv2_plan_create(rows0)
+    buf0 = qb.Buffers(plan0, dev)
+    qb.qv2_calibrate(plan0, buf0.params, buf0.sums, buf0.workspace)
+    qb.qv2_fakequant_metrics(plan0, buf0.params, buf0.sums, buf0.workspace)
+    torch.cuda.synchronize()
+    params, _, _ = buf0.host()
+    qruns = []
+    for t, (s, x, c) in enumerate(zip(specs, xs, codes)):
+        if not s.has_pair:
+            qruns.append(None)
+            continue
+        p = params[plan0.segment_begin[t]]
+        q = c.view(x.shape).to(torch.float32).sub_(float(p["zp"])).mul_(float(p["scale"]))
+        q.add_(synth.unit_noise(s, dev), alpha=0.01 * float(x.std(unbiased=False)))
+        qruns.append(q)
+    plan0.close()
+    del buf0
+    rows = [qb.TensorArg(x=x, numel=x.numel(), scheme=s.scheme, channels=s.channels, qrun=q, codes=c,
+                         kind=s.kind, layer=s.layer) for x, s, q, c in zip(xs, specs, qruns, codes)]
+    return specs, xs, qruns, codes, rows, batch
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print(f"bench.py: this build runs on ONE GPU; --gpus {args.gpus} is not supported "
+              "(no collectives or sharding are part of it).", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    from paper_2501_07161_amd import binding as qb
+    from paper_2501_07161_amd import synth
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(3)
+    qb.lib()                                  # raises if libqv2.so has not been built
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+
+    specs, xs, qruns, codes, rows, batch = build_workload(args, dev)
+    plan = qb.qv2_plan_create(rows)
+    buf = qb.Buffers(plan, dev)
+    n_layers = max(s.layer for s in specs) + 1
+    n_w = sum(s.numel for s in specs if s.kind == synth.WEIGHT)
+    n_a = sum(s.numel for s in specs if s.kind == synth.ACTIVATION)
+    n_pair = sum(s.numel for s, q in zip(specs, qruns) if q is not None)
+    n_all = n_w + n_a
+    bytes_cal, bytes_fq, bytes_pair = 4 * n_all, 5 * n_all, 8 * n_pair
+    bytes_pass = bytes_cal + bytes_fq + bytes_pair
+
+    w_idx = [t for t, s in enumerate(specs) if s.kind == synth.WEIGHT]
+    a_idx = [t for t, s in enumerate(specs) if s.kind == synth.ACTIVATION]
+    w_layer = np.array([specs[t].layer for t in w_idx])
+    a_layer = np.array([specs[t].layer for t in a_idx])
+    # pinned host mirrors of the small result records
+    h_params = torch.empty(buf.params.shape, dtype=torch.uint8, pin_memory=True)
+    h_sums = torch.empty(buf.sums.shape, dtype=torch.uint8, pin_memory=True)
+    h_pair = torch.empty(buf.pair.shape, dtype=torch.uint8, pin_memory=True)
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
+    last = {}
+
+    def step(events=None):
+        if events:
+            events[0].record()
+        qb.qv2_calibrate(plan, buf.params, buf.sums, buf.workspace)
+        if events:
+            events[1].record()
+        qb.qv2_fakequant_metrics(plan, buf.params, buf.sums, buf.workspace)
+        if events:
+            events[2].record()
+        qb.qv2_pair_metrics(plan, buf.pair, buf.workspace)
+        if events:
+            events[3].record()
+        h_params.copy_(buf.params, non_blocking=True)
+        h_sums.copy_(buf.sums, non_blocking=True)
+        h_pair.copy_(buf.pair, non_blocking=True)
+        torch.cuda.current_stream().synchronize()
+        met = qb.qv2_finalize(plan, h_params.numpy().view(qb.QPARAMS), h_sums.numpy().view(qb.SUMS))
+        pmse, psqnr = qb.qv2_pair_finalize(h_pair.numpy().view(qb.PAIR_SUMS))
+        w_sqnr = np.empty(n_layers); w_mse = np.empty(n_layers)
+        a_sqnr = np.empty(n_layers); a_mse = np.empty(n_layers)
+        w_sqnr[w_layer], w_mse[w_layer] = met["sqnr_db"][w_idx], met["mse"][w_idx]
+        a_sqnr[a_layer], a_mse[a_layer] = psqnr[a_idx], pmse[a_idx]
+        order, score = qb.qv2_rank(w_sqnr, a_sqnr, w_mse, a_mse)
+        last.update(order=order, score=score, met=met)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(args.steps):
+        step(ev[k])
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = dt / args.steps * 1e3
+
+    ms_cal = float(np.mean([e[0].elapsed_time(e[1]) for e in ev]))
+    ms_fq = float(np.mean([e[1].elapsed_time(e[2]) for e in ev]))
+    ms_pair = float(np.mean([e[2].elapsed_time(e[3]) for e in ev]))
+    value = bytes_pass / (dt / args.steps) / 1e9
+    pair_gbps = bytes_pair / (ms_pair * 1e-3) / 1e9
+
+    out = {
+        "metric": "sensitivity_pass_GBps", "value": round(value, 2), "unit": "GB/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"{args.workload}_b{batch}" + ("_bnfold" if args.fused else ""),
+                   "tensors": len(specs), "layers": n_layers, "weight_elements": n_w,
+                   "activation_elements": n_a, "schemes": "weights per-channel symmetric int8, "
+                   "activations per-tensor asymmetric int8" if args.workload != "resnet18" else "per-tensor asymmetric int8",
+                   "algorithmic_bytes_per_pass": bytes_pass},
+        "frac_of_hbm_peak": round(value / HBM_PEAK_GBPS, 4),
+        "layers_per_s": round(n_layers / (dt / args.steps), 1),
+        "calls": {"calibrate": {"ms": round(ms_cal, 4), "GBps": round(bytes_cal / ms_cal / 1e6, 1)},
+                  "fakequant_metrics": {"ms": round(ms_fq, 4), "GBps": round(bytes_fq / ms_fq / 1e6, 1)},
+                  "pair_metrics": {"ms": round(ms_pair, 4), "GBps": round(pair_gbps, 1)}},
+        "roofline": {"bound": "hbm", "kernel": "k_pair_stream", "achieved": round(pair_gbps, 1),
+                     "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(pair_gbps / HBM_PEAK_GBPS, 4),
+                     "traffic": PAIR_KERNEL_TRAFFIC_BYTES,
+                     "algorithmic_bytes_per_launch": bytes_pair, "avg_launch_ms": round(ms_pair, 4)},
+        "min_adjacent_score_gap": float(np.min(np.diff(np.sort(last["score"])))) if n_layers > 1 else None,
+    }
+
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(specs, xs, qruns, args.cpu_sample_elems)
+        out["oracle_speedup"] = round(value / out["cpu_baseline"]["value"], 1)
+    print(json.dumps(out), flush=True)
+
+
+def cpu_baseline(specs, xs, qruns, budget):
+    """The CPU oracle as it stands (one thread), timed on a bounded sample of the same
+    workload: tensors taken in table order while they fit the element budget."""
+    from oracle import reference as orc
+    from paper_2501_07161_amd import synth
+    orc.lib()
+    picked, left = [], budget
+    for t, s in enumerate(specs):
+        if s.numel <= left:
+            picked.append(t)
+            left -= s.numel
+    host = [(xs[t].cpu().numpy().reshape(-1), None if qruns[t] is None else qruns[t].cpu().numpy().reshape(-1))
+            for t in picked]
+    nbytes, t0 = 0, time.perf_counter()
+    for t, (x, q) in zip(picked, host):
+        s = specs[t]
+        cal = orc.calibrate(x, s.scheme, s.channels)
+        fq = orc.fakequant(x, cal, s.scheme, s.channels)
+        orc.tensor_metrics(x, cal, fq)
+        nbytes += 9 * x.size
+        if q is not None:
+            orc.pair_metrics(x, q)
+            nbytes += 8 * x.size
+    dt = time.perf_counter() - t0
+    n_w = sum(1 for t in picked if specs[t].kind == synth.WEIGHT)
+    return {"value": round(nbytes / dt / 1e9, 4), "unit": "GB/s", "cores": 1, "kind": "oracle",
+            "seconds": round(dt, 2),
+            "sample": f"{len(picked)} of {len(specs)} tensors of the same workload in table order within "
+                      f"{budget} elements ({n_w} weights, {len(picked) - n_w} activations with pairs, "
+                      f"{sum(specs[t].numel for t in picked)} elements)"}
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,214 @@
+/*
+ * qv2 -- the per-layer local-metric sensitivity pass of QuantuneV2
+ * (arXiv 2501.07161) for AMD MI355X (gfx950).  C ABI.
+ *
+ * The pass follows the paper's execution process (Sec. 4, steps 1-4):
+ *   1. calibration: min / max and tensor statistics of every weight and
+ *      activation tensor                                   -> qv2_calibrate
+ *   2. scale / zero-point and uniform int8 quantization of all layers
+ *      (Sec. 2.1 Eq. 1-3, Sec. 4 Eq. 4-5)                   -> qv2_calibrate,
+ *                                                              qv2_fakequant_metrics
+ *   3. local metrics SQNR and MSE per layer (Sec. 6.1 Eq. 6-7), for a tensor
+ *      against its own dequantized form                     -> qv2_fakequant_metrics
+ *      and for a layer's output in the fp32 inference against the same output
+ *      in the quantized inference (Algorithm 2, D[i] vs Q[i]) -> qv2_pair_metrics
+ *   4. SQNR delta (Sec. 6.4 Eq. 16) and the sensitivity list
+ *      (Algorithm 2, RankLayersBySensitivity)               -> qv2_rank
+ *
+ * Conventions
+ *  - Pointers named d_* are DEVICE pointers, h_* are HOST pointers.  Every
+ *    device buffer (tensors, codes, params, sums, workspace) is allocated and
+ *    freed by the caller.  The library owns only the opaque qv2_plan (host
+ *    tables plus a small device copy of them, released by qv2_plan_destroy).
+ *  - Device calls only enqueue work on `hip_stream` (a hipStream_t passed as
+ *    void*; NULL = the default stream) and never synchronise it, except that
+ *    the first device call on a plan uploads the plan's tables with a blocking
+ *    copy.  Outputs are valid once the caller has synchronised the stream.
+ *  - Every call returns a qv2_status.  Arguments are validated on the host
+ *    before anything is launched; nothing aborts or throws across the ABI.
+ *  - Identical inputs give bit-identical outputs (no floating-point atomics;
+ *    every reduction has a fixed order).
+ *  - Inputs must be finite.  NaNs are ignored by min / max but poison sums.
+ *
+ * Quantizer (fixed by this library; fp32 arithmetic, one rounding per step):
+ *   asymmetric (Eq. 2, N = 256, range widened to contain 0):
+ *      lo = min(min,0)  hi = max(max,0)  scale = (hi-lo)/255
+ *      inv_scale = 1/scale     zp = clamp(rne(-128 - lo*inv_scale), -128, 127)
+ *   symmetric (Eq. 4, b = 8):  scale = max(|min|,|max|)/127, inv_scale = 1/scale, zp = 0
+ *   degenerate (scale below the smallest normal float): scale = inv_scale = 1, zp = 0
+ *   code  = clamp(rne(x*inv_scale) + zp, -128, 127)       (round half to even)
+ *   xhat  = (code - zp) * scale
+ */
+#ifndef QV2_H
+#define QV2_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  QV2_OK = 0,
+  QV2_ERR_NULL = -1,       /* a required pointer is NULL                         */
+  QV2_ERR_SHAPE = -2,      /* bad numel / channels / count / layer positions     */
+  QV2_ERR_SCHEME = -3,     /* unknown qv2_scheme                                 */
+  QV2_ERR_WORKSPACE = -4,  /* workspace smaller than qv2_workspace_bytes()       */
+  QV2_ERR_NONFINITE = -5,  /* NaN / Inf where a finite value is required         */
+  QV2_ERR_HIP = -6,        /* a HIP runtime call or kernel launch failed         */
+  QV2_ERR_ALIGN = -7       /* a device pointer is not aligned as required        */
+} qv2_status;
+
+typedef enum {
+  QV2_ASYM_TENSOR = 0,     /* Sec. 2.1 Eq. 1-3 over the whole tensor             */
+  QV2_SYM_TENSOR = 1,      /* Sec. 4 Eq. 4-5 over the whole tensor               */
+  QV2_SYM_CHANNEL = 2      /* Sec. 4 Eq. 4-5 per slice of dim 0 (output channel) */
+} qv2_scheme;
+
+/* One row of the layer table (host memory, caller-owned, copied by the plan). */
+typedef struct {
+  const float* x;      /* DEVICE, contiguous fp32, 4-byte aligned (16-byte: fast path) */
+  const float* qrun;   /* DEVICE or NULL: the same tensor taken from the quantized
+                          inference (Algorithm 2's Q[i]); enables pair metrics      */
+  int8_t* codes;       /* DEVICE or NULL: receives numel int8 codes                 */
+  int64_t numel;       /* > 0                                                       */
+  int32_t channels;    /* QV2_SYM_CHANNEL: number of dim-0 slices, must divide
+                          numel; other schemes: must be 1                           */
+  int32_t scheme;      /* qv2_scheme                                                */
+  int32_t kind;        /* 0 weight, 1 activation; informational                     */
+  int32_t layer;       /* layer index this tensor belongs to; informational         */
+} qv2_tensor;
+
+/* Per segment (a whole tensor, or one output channel).  This array is the
+ * "calibration cache" of Sec. 5: it may be saved and handed back to
+ * qv2_fakequant_metrics without recalibrating. */
+typedef struct {
+  float min, max;          /* -0.0 is reported as +0.0                            */
+  float scale, inv_scale;
+  int32_t zp;
+  int32_t _pad;
+} qv2_qparams;
+
+/* Per segment.  qv2_calibrate writes sum_x, sum_x2, n and clears sum_e2;
+ * qv2_fakequant_metrics writes sum_e2 and rewrites sum_x2 and n from the data
+ * it quantized (so SQNR is consistent when cached params are used). */
+typedef struct {
+  double sum_x, sum_x2, sum_e2;
+  int64_t n;
+} qv2_sums;
+
+/* Per tensor of the plan (entries of tensors without qrun are zero). */
+typedef struct {
+  double sum_ref2;         /* sum x^2          (signal energy, Eq. 6)             */
+  double sum_d2;           /* sum (x - qrun)^2 (noise energy, Eq. 6-7)            */
+  int64_t n;
+  int64_t _pad;
+} qv2_pair_sums;
+
+/* Per tensor, host, fp64. */
+typedef struct {
+  double mse;              /* Eq. 7: sum_e2 / numel                               */
+  double sqnr_db;          /* Eq. 6: 10 log10(sum_x2 / sum_e2); +inf if sum_e2==0 */
+  double mean, var;        /* population variance                                 */
+  float absmax, min, max;
+  int32_t _pad;
+} qv2_metrics;
+
+/* Constants of the ranking.  The paper says only that the weight SQNR delta
+ * gets more gain than the activation one; 0.6 / 0.4 are this library's defaults. */
+typedef struct {
+  double alpha_w;          /* default 0.6                                         */
+  double alpha_a;          /* default 0.4                                         */
+  double mse_factor;       /* default 5 (Algorithm 2: MSE > 5 x mean MSE)         */
+  double sqnr_cap_db;      /* default 200: |SQNR| is clamped before differencing  */
+  int32_t mse_source;      /* 0 activation-pair MSE (default), 1 weight MSE,
+                              2 either, each against its own mean                 */
+  int32_t _pad;
+} qv2_rank_config;
+
+typedef struct qv2_plan qv2_plan;
+
+/* ---- plan (host only; needs no GPU) ------------------------------------- */
+
+/* Validates the layer table and cuts it into tiles: one flat tile table over all
+ * tensors, so that one launch covers every layer whatever its size.
+ * Errors: NULL table or out -> ERR_NULL; n_tensors <= 0, numel <= 0, channels
+ * not dividing numel (or != 1 for per-tensor schemes), more than 2^31-1 tiles
+ * or segments -> ERR_SHAPE; unknown scheme -> ERR_SCHEME; x (or qrun) not
+ * 4-byte aligned -> ERR_ALIGN; x NULL -> ERR_NULL. */
+qv2_status qv2_plan_create(const qv2_tensor* h_tensors, int32_t n_tensors, qv2_plan** out);
+void qv2_plan_destroy(qv2_plan* plan);
+
+int32_t qv2_plan_num_tensors(const qv2_plan* plan);
+/* Total segments; params / sums arrays have this many entries, tensor after
+ * tensor in table order, channel after channel. */
+int64_t qv2_plan_num_segments(const qv2_plan* plan);
+/* Index of the first segment of tensor `t` (-1 if out of range). */
+int64_t qv2_plan_segment_begin(const qv2_plan* plan, int32_t t);
+/* Tile counts, for diagnostics and tests. */
+int64_t qv2_plan_num_tiles(const qv2_plan* plan);
+int64_t qv2_plan_num_pair_tiles(const qv2_plan* plan);
+/* Bytes of device workspace any device call on this plan needs (256-byte
+ * aligned base).  Calls that may overlap in time need separate workspaces. */
+size_t qv2_workspace_bytes(const qv2_plan* plan);
+
+/* ---- device passes ------------------------------------------------------- */
+
+/* Step 1-2 (Sec. 4; Sec. 5 calibration stage; Eq. 2, Eq. 4): per segment
+ * min, max, sum x, sum x^2, then scale / inv_scale / zero-point.
+ * d_params[num_segments], d_sums[num_segments]: DEVICE, written. */
+qv2_status qv2_calibrate(qv2_plan* plan, qv2_qparams* d_params, qv2_sums* d_sums,
+                         void* d_workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Step 2-3 (Eq. 1, 3, 5; Eq. 6-7): quantize every element with its segment's
+ * parameters, write the int8 code (where codes != NULL), dequantize and
+ * accumulate sum x^2 and sum (x - xhat)^2 per segment.
+ * d_params: DEVICE, read.  d_sums: DEVICE, sum_e2 / sum_x2 / n written. */
+qv2_status qv2_fakequant_metrics(qv2_plan* plan, const qv2_qparams* d_params, qv2_sums* d_sums,
+                                 void* d_workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Step 3 on the two-inference protocol (Algorithm 2, CalculateSQNR /
+ * CalculateMSE on D[i], Q[i]): for every tensor with qrun != NULL the energies
+ * sum x^2 and sum (x - qrun)^2.  d_pair_sums[num_tensors]: DEVICE, written. */
+qv2_status qv2_pair_metrics(qv2_plan* plan, qv2_pair_sums* d_pair_sums,
+                            void* d_workspace, size_t workspace_bytes, void* hip_stream);
+
+/* ---- host finalize and ranking (need no GPU) ----------------------------- */
+
+/* Eq. 6-7 and the tensor statistics from host copies of params and sums; a
+ * per-channel tensor's metrics come from the sums of its channels' sums.
+ * h_out[num_tensors].  ERR_NONFINITE if any sum is NaN / Inf (outputs still
+ * written). */
+qv2_status qv2_finalize(const qv2_plan* plan, const qv2_qparams* h_params,
+                        const qv2_sums* h_sums, qv2_metrics* h_out);
+
+/* MSE and SQNR (dB) of n pair-sum records; entries with n == 0 give 0 and +inf. */
+qv2_status qv2_pair_finalize(const qv2_pair_sums* h_pair, int32_t n,
+                             double* h_mse, double* h_sqnr_db);
+
+void qv2_rank_config_default(qv2_rank_config* cfg);
+
+/* Step 4 (Eq. 16; Algorithm 2).  Per layer i (0..n_layers-1, in graph order):
+ *   delta_i = (SQNR_i - SQNR_{i-1}) / (L_i - L_{i-1}), delta_0 = 0, for the weight
+ *   and the activation series; score_i = alpha_w*delta^w_i + alpha_a*delta^a_i;
+ *   layers whose MSE exceeds mse_factor x the mean MSE come first, largest MSE
+ *   first; the rest follow in ascending score; equal keys keep layer order.
+ * w_sqnr_db / a_sqnr_db: either may be NULL (its deltas count as 0), not both.
+ * w_mse / a_mse: the one(s) cfg->mse_source selects must be non-NULL, finite, >= 0.
+ * layer_pos: graph positions L_i, strictly increasing; NULL = 0..n-1.
+ * order_out[n_layers]: layer indices, most sensitive (keep in fp32) first.
+ * score_out[n_layers] (may be NULL): the scores, indexed by layer.
+ * Errors: ERR_NULL, ERR_SHAPE (n_layers <= 0, positions not increasing,
+ * mse_source out of range), ERR_NONFINITE (NaN SQNR, non-finite or negative MSE). */
+qv2_status qv2_rank(const double* w_sqnr_db, const double* a_sqnr_db,
+                    const double* w_mse, const double* a_mse,
+                    const int32_t* layer_pos, int32_t n_layers,
+                    const qv2_rank_config* cfg, int32_t* order_out, double* score_out);
+
+const char* qv2_status_string(qv2_status s);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* QV2_H */

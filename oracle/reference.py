@@ -319,7 +319,10 @@ def rank_layers(w_sqnr, a_sqnr, w_mse, a_mse, pos=None, cfg: RankConfig | None =
         M = [float(m) for m in M]
         if any(math.isnan(m) or math.isinf(m) or m < 0 for m in M):
             raise ValueError("non-finite MSE")
-        mean = math.fsum(M) / n if n else 0.0
+        total = 0.0
+        for m in M:                 # CalculateAverage: plain running sum
+            total += m
+        mean = total / n if n else 0.0
         for i in range(n):
             if M[i] > cfg.mse_factor * mean:
                 is_out[i] = True

@@ -1,0 +1,265 @@
+"""ctypes binding of libqv2.so: same names as the C ABI, argument marshalling only.
+
+Every step of the sensitivity pass runs inside the native library; PyTorch is
+used for device memory and streams.  There is no fallback: if the library has
+not been built, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass
+from typing import List, Optional, Sequence
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libqv2.so")
+
+QV2_OK = 0
+QV2_ERR_NULL, QV2_ERR_SHAPE, QV2_ERR_SCHEME, QV2_ERR_WORKSPACE = -1, -2, -3, -4
+QV2_ERR_NONFINITE, QV2_ERR_HIP, QV2_ERR_ALIGN = -5, -6, -7
+QV2_ASYM_TENSOR, QV2_SYM_TENSOR, QV2_SYM_CHANNEL = 0, 1, 2
+
+EXPORTS = (
+    "qv2_plan_create", "qv2_plan_destroy", "qv2_plan_num_tensors", "qv2_plan_num_segments",
+    "qv2_plan_segment_begin", "qv2_plan_num_tiles", "qv2_plan_num_pair_tiles",
+    "qv2_workspace_bytes", "qv2_calibrate", "qv2_fakequant_metrics", "qv2_pair_metrics",
+    "qv2_finalize", "qv2_pair_finalize", "qv2_rank_config_default", "qv2_rank",
+    "qv2_status_string",
+)
+
+
+class qv2_tensor(ctypes.Structure):
+    _fields_ = [("x", ctypes.c_void_p), ("qrun", ctypes.c_void_p), ("codes", ctypes.c_void_p),
+                ("numel", ctypes.c_int64), ("channels", ctypes.c_int32), ("scheme", ctypes.c_int32),
+                ("kind", ctypes.c_int32), ("layer", ctypes.c_int32)]
+
+
+class qv2_rank_config(ctypes.Structure):
+    _fields_ = [("alpha_w", ctypes.c_double), ("alpha_a", ctypes.c_double),
+                ("mse_factor", ctypes.c_double), ("sqnr_cap_db", ctypes.c_double),
+                ("mse_source", ctypes.c_int32), ("_pad", ctypes.c_int32)]
+
+
+# numpy views of the POD records the library reads and writes
+QPARAMS = np.dtype([("min", "<f4"), ("max", "<f4"), ("scale", "<f4"), ("inv_scale", "<f4"),
+                    ("zp", "<i4"), ("_pad", "<i4")])
+SUMS = np.dtype([("sum_x", "<f8"), ("sum_x2", "<f8"), ("sum_e2", "<f8"), ("n", "<i8")])
+PAIR_SUMS = np.dtype([("sum_ref2", "<f8"), ("sum_d2", "<f8"), ("n", "<i8"), ("_pad", "<i8")])
+METRICS = np.dtype([("mse", "<f8"), ("sqnr_db", "<f8"), ("mean", "<f8"), ("var", "<f8"),
+                    ("absmax", "<f4"), ("min", "<f4"), ("max", "<f4"), ("_pad", "<i4")])
+assert QPARAMS.itemsize == 24 and SUMS.itemsize == 32 and PAIR_SUMS.itemsize == 32
+assert METRICS.itemsize == 48
+
+_lib = None
+
+
+class QV2Error(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        msg = lib().qv2_status_string(status).decode() if _lib is not None else str(status)
+        super().__init__(f"{where}: {msg} ({status})")
+
+
+def lib():
+    """Load libqv2.so (built by paper_2501_07161_amd/build.py).  Raises if absent."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(
+                f"{LIB_PATH} is missing: build it with `python -m paper_2501_07161_amd.build` "
+                "(there is no CPU fallback)")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, i32, i64, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_size_t
+        L.qv2_plan_create.argtypes = [ctypes.POINTER(qv2_tensor), i32, ctypes.POINTER(vp)]
+        L.qv2_plan_destroy.argtypes = [vp]
+        L.qv2_plan_destroy.restype = None
+        L.qv2_plan_num_tensors.argtypes = [vp]
+        L.qv2_plan_num_tensors.restype = i32
+        for n in ("qv2_plan_num_segments", "qv2_plan_num_tiles", "qv2_plan_num_pair_tiles"):
+            getattr(L, n).argtypes = [vp]
+            getattr(L, n).restype = i64
+        L.qv2_plan_segment_begin.argtypes = [vp, i32]
+        L.qv2_plan_segment_begin.restype = i64
+        L.qv2_workspace_bytes.argtypes = [vp]
+        L.qv2_workspace_bytes.restype = sz
+        L.qv2_calibrate.argtypes = [vp, vp, vp, vp, sz, vp]
+        L.qv2_fakequant_metrics.argtypes = [vp, vp, vp, vp, sz, vp]
+        L.qv2_pair_metrics.argtypes = [vp, vp, vp, sz, vp]
+        L.qv2_finalize.argtypes = [vp, vp, vp, vp]
+        L.qv2_pair_finalize.argtypes = [vp, i32, vp, vp]
+        L.qv2_rank_config_default.argtypes = [ctypes.POINTER(qv2_rank_config)]
+        L.qv2_rank_config_default.restype = None
+        L.qv2_rank.argtypes = [vp, vp, vp, vp, vp, i32, ctypes.POINTER(qv2_rank_config), vp, vp]
+        L.qv2_status_string.argtypes = [ctypes.c_int]
+        L.qv2_status_string.restype = ctypes.c_char_p
+        _lib = L
+    return _lib
+
+
+def _check(st: int, where: str):
+    if st != QV2_OK:
+        raise QV2Error(st, where)
+
+
+def _ptr(buf) -> Optional[int]:
+    """Address of a torch tensor / numpy array / int / None."""
+    if buf is None:
+        return None
+    if isinstance(buf, int):
+        return buf
+    if isinstance(buf, np.ndarray):
+        return buf.ctypes.data
+    return buf.data_ptr()
+
+
+def _stream(stream) -> Optional[int]:
+    if stream is None:
+        import torch
+        return torch.cuda.current_stream().cuda_stream or None
+    if isinstance(stream, int):
+        return stream or None
+    return stream.cuda_stream or None
+
+
+@dataclass
+class TensorArg:
+    """One row of the layer table.  x / qrun / codes are torch device tensors
+    (or raw device addresses); the plan keeps references to them."""
+    x: object
+    numel: int
+    scheme: int = QV2_ASYM_TENSOR
+    channels: int = 1
+    qrun: object = None
+    codes: object = None
+    kind: int = 0
+    layer: int = 0
+
+
+class Plan:
+    """Owner of a native qv2_plan handle."""
+
+    def __init__(self, handle: int, rows: Sequence[TensorArg]):
+        self.handle = handle
+        self.rows = list(rows)            # keeps the device tensors alive
+        L = lib()
+        self.num_tensors = L.qv2_plan_num_tensors(handle)
+        self.num_segments = L.qv2_plan_num_segments(handle)
+        self.num_tiles = L.qv2_plan_num_tiles(handle)
+        self.num_pair_tiles = L.qv2_plan_num_pair_tiles(handle)
+        self.workspace_bytes = L.qv2_workspace_bytes(handle)
+        self.segment_begin = [L.qv2_plan_segment_begin(handle, t) for t in range(self.num_tensors)]
+
+    def close(self):
+        if self.handle:
+            lib().qv2_plan_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def qv2_plan_create(rows: Sequence[TensorArg]) -> Plan:
+    n = len(rows)
+    arr = (qv2_tensor * max(n, 1))()
+    for i, r in enumerate(rows):
+        arr[i] = qv2_tensor(_ptr(r.x), _ptr(r.qrun), _ptr(r.codes), int(r.numel), int(r.channels),
+                            int(r.scheme), int(r.kind), int(r.layer))
+    h = ctypes.c_void_p()
+    _check(lib().qv2_plan_create(arr, n, ctypes.byref(h)), "qv2_plan_create")
+    return Plan(h.value, rows)
+
+
+def qv2_workspace_bytes(plan: Plan) -> int:
+    return lib().qv2_workspace_bytes(plan.handle)
+
+
+def qv2_calibrate(plan: Plan, d_params, d_sums, d_workspace, workspace_bytes=None, stream=None):
+    wb = workspace_bytes if workspace_bytes is not None else d_workspace.numel() * d_workspace.element_size()
+    _check(lib().qv2_calibrate(plan.handle, _ptr(d_params), _ptr(d_sums), _ptr(d_workspace), wb,
+                               _stream(stream)), "qv2_calibrate")
+
+
+def qv2_fakequant_metrics(plan: Plan, d_params, d_sums, d_workspace, workspace_bytes=None, stream=None):
+    wb = workspace_bytes if workspace_bytes is not None else d_workspace.numel() * d_workspace.element_size()
+    _check(lib().qv2_fakequant_metrics(plan.handle, _ptr(d_params), _ptr(d_sums), _ptr(d_workspace), wb,
+                                       _stream(stream)), "qv2_fakequant_metrics")
+
+
+def qv2_pair_metrics(plan: Plan, d_pair_sums, d_workspace, workspace_bytes=None, stream=None):
+    wb = workspace_bytes if workspace_bytes is not None else d_workspace.numel() * d_workspace.element_size()
+    _check(lib().qv2_pair_metrics(plan.handle, _ptr(d_pair_sums), _ptr(d_workspace), wb,
+                                  _stream(stream)), "qv2_pair_metrics")
+
+
+def qv2_finalize(plan: Plan, h_params: np.ndarray, h_sums: np.ndarray, strict: bool = True) -> np.ndarray:
+    """Host fp64 metrics per tensor from host copies of params and sums."""
+    hp = np.ascontiguousarray(h_params, dtype=QPARAMS)
+    hs = np.ascontiguousarray(h_sums, dtype=SUMS)
+    if hp.size != plan.num_segments or hs.size != plan.num_segments:
+        raise QV2Error(QV2_ERR_SHAPE, "qv2_finalize")
+    out = np.zeros(plan.num_tensors, dtype=METRICS)
+    st = lib().qv2_finalize(plan.handle, hp.ctypes.data, hs.ctypes.data, out.ctypes.data)
+    if st != QV2_OK and (strict or st != QV2_ERR_NONFINITE):
+        raise QV2Error(st, "qv2_finalize")
+    return out
+
+
+def qv2_pair_finalize(h_pair: np.ndarray):
+    hp = np.ascontiguousarray(h_pair, dtype=PAIR_SUMS)
+    mse = np.zeros(hp.size, np.float64)
+    sqnr = np.zeros(hp.size, np.float64)
+    _check(lib().qv2_pair_finalize(hp.ctypes.data, hp.size, mse.ctypes.data, sqnr.ctypes.data),
+           "qv2_pair_finalize")
+    return mse, sqnr
+
+
+def qv2_rank_config_default() -> qv2_rank_config:
+    c = qv2_rank_config()
+    lib().qv2_rank_config_default(ctypes.byref(c))
+    return c
+
+
+def _f64(a):
+    return None if a is None else np.ascontiguousarray(a, dtype=np.float64)
+
+
+def qv2_rank(w_sqnr_db, a_sqnr_db, w_mse, a_mse, layer_pos=None, cfg: Optional[qv2_rank_config] = None,
+             n_layers: Optional[int] = None):
+    """Returns (order, score) as numpy arrays; order[0] = most sensitive layer."""
+    ws, as_, wm, am = _f64(w_sqnr_db), _f64(a_sqnr_db), _f64(w_mse), _f64(a_mse)
+    if n_layers is None:
+        n_layers = next((len(a) for a in (ws, as_, wm, am) if a is not None), 0)
+    for a in (ws, as_, wm, am):
+        if a is not None and len(a) != n_layers:
+            raise QV2Error(QV2_ERR_SHAPE, "qv2_rank")
+    pos = None if layer_pos is None else np.ascontiguousarray(layer_pos, dtype=np.int32)
+    if pos is not None and len(pos) != n_layers:
+        raise QV2Error(QV2_ERR_SHAPE, "qv2_rank")
+    order = np.zeros(max(n_layers, 1), np.int32)
+    score = np.zeros(max(n_layers, 1), np.float64)
+    _check(lib().qv2_rank(_ptr(ws), _ptr(as_), _ptr(wm), _ptr(am), _ptr(pos), n_layers,
+                          ctypes.byref(cfg) if cfg is not None else None,
+                          order.ctypes.data, score.ctypes.data), "qv2_rank")
+    return order[:n_layers], score[:n_layers]
+
+
+# ----------------------------------------------------------------------------
+# convenience: device output buffers for a plan (torch is only the allocator)
+# ----------------------------------------------------------------------------
+class Buffers:
+    def __init__(self, plan: Plan, device="cuda"):
+        import torch
+        self.params = torch.zeros(plan.num_segments * QPARAMS.itemsize, dtype=torch.uint8, device=device)
+        self.sums = torch.zeros(plan.num_segments * SUMS.itemsize, dtype=torch.uint8, device=device)
+        self.pair = torch.zeros(plan.num_tensors * PAIR_SUMS.itemsize, dtype=torch.uint8, device=device)
+        self.workspace = torch.zeros(plan.workspace_bytes, dtype=torch.uint8, device=device)
+
+    def host(self):
+        """Blocking copies of the small result records to numpy."""
+        return (self.params.cpu().numpy().view(QPARAMS), self.sums.cpu().numpy().view(SUMS),
+                self.pair.cpu().numpy().view(PAIR_SUMS))

@@ -1,0 +1,300 @@
+// Host side of the qv2 C ABI: the plan builder (layer table -> flat tile
+// table), the fp64 finalize of Sec. 6.1 Eq. 6-7, and the sensitivity ranking of
+// Sec. 6.4 Eq. 16 / Algorithm 2.  No GPU is needed by anything in this file.
+#include <algorithm>
+#include <cmath>
+#include <cstdlib>
+#include <cstring>
+#include <limits>
+#include <new>
+#include <numeric>
+
+#include "qv2_internal.h"
+
+using qv2::PairTensor;
+using qv2::Segment;
+using qv2::TensorDesc;
+using qv2::Tile;
+
+namespace {
+
+size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+int32_t tile_elems_from_env() {
+  const char* e = std::getenv("QV2_TILE_ELEMS");
+  if (!e || !*e) return qv2::kDefaultTile;
+  long v = std::strtol(e, nullptr, 10);
+  if (v < 1024) v = 1024;
+  if (v > (1L << 22)) v = 1L << 22;
+  return static_cast<int32_t>(v / 1024 * 1024);
+}
+
+}  // namespace
+
+extern "C" {
+
+qv2_status qv2_plan_create(const qv2_tensor* h_tensors, int32_t n_tensors, qv2_plan** out) {
+  if (!h_tensors || !out) return QV2_ERR_NULL;
+  *out = nullptr;
+  if (n_tensors <= 0) return QV2_ERR_SHAPE;
+
+  qv2_plan* p = new (std::nothrow) qv2_plan();
+  if (!p) return QV2_ERR_HIP;
+  p->tile_elems = tile_elems_from_env();
+  const int64_t T = p->tile_elems;
+  const int64_t kMax = std::numeric_limits<int32_t>::max();
+
+  std::vector<Tile> row_tiles;
+  int64_t n_parts = 0, n_pair_parts = 0;
+  qv2_status err = QV2_OK;
+
+  for (int32_t t = 0; t < n_tensors && err == QV2_OK; ++t) {
+    const qv2_tensor& in = h_tensors[t];
+    if (!in.x) { err = QV2_ERR_NULL; break; }
+    if (in.numel <= 0) { err = QV2_ERR_SHAPE; break; }
+    if (in.scheme != QV2_ASYM_TENSOR && in.scheme != QV2_SYM_TENSOR &&
+        in.scheme != QV2_SYM_CHANNEL) { err = QV2_ERR_SCHEME; break; }
+    const bool per_channel = in.scheme == QV2_SYM_CHANNEL;
+    if (per_channel ? (in.channels <= 0 || in.numel % in.channels != 0) : in.channels != 1) {
+      err = QV2_ERR_SHAPE; break;
+    }
+    if ((reinterpret_cast<uintptr_t>(in.x) & 3u) ||
+        (in.qrun && (reinterpret_cast<uintptr_t>(in.qrun) & 3u))) { err = QV2_ERR_ALIGN; break; }
+
+    const int64_t nseg = per_channel ? in.channels : 1;
+    const int64_t inner = in.numel / nseg;
+    const int64_t seg0 = static_cast<int64_t>(p->segments.size());
+    if (seg0 + nseg > kMax) { err = QV2_ERR_SHAPE; break; }
+
+    TensorDesc d{};
+    d.x = in.x; d.qrun = in.qrun; d.codes = in.codes; d.numel = in.numel;
+    d.seg0 = static_cast<int32_t>(seg0); d.nseg = static_cast<int32_t>(nseg);
+    d.scheme = in.scheme;
+    p->descs.push_back(d);
+    p->tensors.push_back(in);
+
+    if (per_channel && inner <= qv2::kRowGroupCap) {
+      // whole rows per tile; every row is its own segment with one partial
+      const int64_t rpt = std::min<int64_t>(qv2::kRowGroupMaxRows, qv2::kRowGroupCap / inner);
+      for (int64_t r0 = 0; r0 < nseg; r0 += rpt) {
+        const int64_t rows = std::min(rpt, nseg - r0);
+        Tile tl{};
+        tl.off = r0 * inner; tl.len = static_cast<int32_t>(rows * inner); tl.tensor = t;
+        tl.part0 = static_cast<int32_t>(n_parts + r0); tl.rows = static_cast<int32_t>(rows);
+        tl.seg0 = static_cast<int32_t>(seg0 + r0); tl.inner = static_cast<int32_t>(inner);
+        row_tiles.push_back(tl);
+      }
+      for (int64_t r = 0; r < nseg; ++r) {
+        Segment s{};
+        s.n = inner; s.part0 = static_cast<int32_t>(n_parts + r); s.nparts = 1; s.scheme = in.scheme;
+        p->segments.push_back(s);
+      }
+      n_parts += nseg;
+    } else {
+      const int64_t tiles_per_seg = (inner + T - 1) / T;
+      if (tiles_per_seg > kMax || n_parts + nseg * tiles_per_seg > kMax) { err = QV2_ERR_SHAPE; break; }
+      for (int64_t s = 0; s < nseg; ++s) {
+        Segment sg{};
+        sg.n = inner; sg.part0 = static_cast<int32_t>(n_parts);
+        sg.nparts = static_cast<int32_t>(tiles_per_seg); sg.scheme = in.scheme;
+        p->segments.push_back(sg);
+        for (int64_t k = 0; k < tiles_per_seg; ++k) {
+          Tile tl{};
+          tl.off = s * inner + k * T;
+          tl.len = static_cast<int32_t>(std::min<int64_t>(T, inner - k * T));
+          tl.tensor = t; tl.part0 = static_cast<int32_t>(n_parts++); tl.rows = 0;
+          tl.seg0 = static_cast<int32_t>(seg0 + s); tl.inner = 0;
+          p->tiles.push_back(tl);
+        }
+      }
+    }
+
+    PairTensor pt{};
+    if (in.qrun) {
+      const int64_t nt = (in.numel + T - 1) / T;
+      if (n_pair_parts + nt > kMax) { err = QV2_ERR_SHAPE; break; }
+      pt.n = in.numel; pt.part0 = static_cast<int32_t>(n_pair_parts); pt.nparts = static_cast<int32_t>(nt);
+      for (int64_t k = 0; k < nt; ++k) {
+        Tile tl{};
+        tl.off = k * T; tl.len = static_cast<int32_t>(std::min<int64_t>(T, in.numel - k * T));
+        tl.tensor = t; tl.part0 = static_cast<int32_t>(n_pair_parts++);
+        p->pair_tiles.push_back(tl);
+      }
+    }
+    p->pair_tensors.push_back(pt);
+  }
+
+  if (err == QV2_OK &&
+      static_cast<int64_t>(p->tiles.size() + row_tiles.size()) > kMax) err = QV2_ERR_SHAPE;
+  if (err != QV2_OK) { delete p; return err; }
+
+  p->n_stream_tiles = static_cast<int64_t>(p->tiles.size());
+  p->tiles.insert(p->tiles.end(), row_tiles.begin(), row_tiles.end());
+  p->n_parts = n_parts;
+  const size_t need = std::max(static_cast<size_t>(n_parts) * sizeof(qv2::StatPartial),
+                               static_cast<size_t>(n_pair_parts) * sizeof(qv2::ErrPartial));
+  p->workspace_bytes = std::max<size_t>(256, round_up(need, 256));
+  *out = p;
+  return QV2_OK;
+}
+
+int32_t qv2_plan_num_tensors(const qv2_plan* plan) {
+  return plan ? static_cast<int32_t>(plan->tensors.size()) : 0;
+}
+int64_t qv2_plan_num_segments(const qv2_plan* plan) {
+  return plan ? static_cast<int64_t>(plan->segments.size()) : 0;
+}
+int64_t qv2_plan_segment_begin(const qv2_plan* plan, int32_t t) {
+  if (!plan || t < 0 || t >= static_cast<int32_t>(plan->descs.size())) return -1;
+  return plan->descs[t].seg0;
+}
+int64_t qv2_plan_num_tiles(const qv2_plan* plan) {
+  return plan ? static_cast<int64_t>(plan->tiles.size()) : 0;
+}
+int64_t qv2_plan_num_pair_tiles(const qv2_plan* plan) {
+  return plan ? static_cast<int64_t>(plan->pair_tiles.size()) : 0;
+}
+size_t qv2_workspace_bytes(const qv2_plan* plan) { return plan ? plan->workspace_bytes : 0; }
+
+// ---------------------------------------------------------------------------
+// Sec. 6.1 Eq. 6-7 and the tensor statistics, fp64.
+// ---------------------------------------------------------------------------
+static double sqnr_db_of(double signal, double noise) {
+  if (noise == 0.0) return std::numeric_limits<double>::infinity();
+  return 10.0 * std::log10(signal / noise);
+}
+
+qv2_status qv2_finalize(const qv2_plan* plan, const qv2_qparams* h_params,
+                        const qv2_sums* h_sums, qv2_metrics* h_out) {
+  if (!plan || !h_params || !h_sums || !h_out) return QV2_ERR_NULL;
+  bool finite = true;
+  for (size_t t = 0; t < plan->descs.size(); ++t) {
+    const TensorDesc& d = plan->descs[t];
+    double sx = 0.0, sx2 = 0.0, se2 = 0.0;
+    float mn = std::numeric_limits<float>::infinity(), mx = -mn;
+    for (int32_t s = d.seg0; s < d.seg0 + d.nseg; ++s) {
+      sx += h_sums[s].sum_x; sx2 += h_sums[s].sum_x2; se2 += h_sums[s].sum_e2;
+      mn = std::min(mn, h_params[s].min); mx = std::max(mx, h_params[s].max);
+    }
+    finite = finite && std::isfinite(sx) && std::isfinite(sx2) && std::isfinite(se2);
+    const double n = static_cast<double>(d.numel);
+    qv2_metrics m{};
+    m.mse = se2 / n;
+    m.sqnr_db = sqnr_db_of(sx2, se2);
+    m.mean = sx / n;
+    m.var = std::max(0.0, sx2 / n - m.mean * m.mean);
+    m.min = mn; m.max = mx; m.absmax = std::max(std::fabs(mn), std::fabs(mx));
+    h_out[t] = m;
+  }
+  return finite ? QV2_OK : QV2_ERR_NONFINITE;
+}
+
+qv2_status qv2_pair_finalize(const qv2_pair_sums* h_pair, int32_t n, double* h_mse,
+                             double* h_sqnr_db) {
+  if (!h_pair || !h_mse || !h_sqnr_db) return QV2_ERR_NULL;
+  if (n < 0) return QV2_ERR_SHAPE;
+  bool finite = true;
+  for (int32_t i = 0; i < n; ++i) {
+    finite = finite && std::isfinite(h_pair[i].sum_ref2) && std::isfinite(h_pair[i].sum_d2);
+    h_mse[i] = h_pair[i].n > 0 ? h_pair[i].sum_d2 / static_cast<double>(h_pair[i].n) : 0.0;
+    h_sqnr_db[i] = sqnr_db_of(h_pair[i].sum_ref2, h_pair[i].sum_d2);
+  }
+  return finite ? QV2_OK : QV2_ERR_NONFINITE;
+}
+
+// ---------------------------------------------------------------------------
+// Sec. 6.4 Eq. 16 and Algorithm 2.
+// ---------------------------------------------------------------------------
+void qv2_rank_config_default(qv2_rank_config* cfg) {
+  if (!cfg) return;
+  cfg->alpha_w = 0.6; cfg->alpha_a = 0.4; cfg->mse_factor = 5.0; cfg->sqnr_cap_db = 200.0;
+  cfg->mse_source = 0; cfg->_pad = 0;
+}
+
+// Eq. 16 on one series; returns false on NaN input.
+static bool sqnr_delta_series(const double* sqnr, const int32_t* pos, int32_t n, double cap,
+                              std::vector<double>& delta) {
+  delta.assign(n, 0.0);
+  if (!sqnr) return true;
+  double prev = 0.0;
+  for (int32_t i = 0; i < n; ++i) {
+    if (std::isnan(sqnr[i])) return false;
+    const double cur = std::max(-cap, std::min(cap, sqnr[i]));
+    if (i > 0) {
+      const double dl = pos ? static_cast<double>(pos[i] - pos[i - 1]) : 1.0;
+      delta[i] = (cur - prev) / dl;
+    }
+    prev = cur;
+  }
+  return true;
+}
+
+qv2_status qv2_rank(const double* w_sqnr_db, const double* a_sqnr_db, const double* w_mse,
+                    const double* a_mse, const int32_t* layer_pos, int32_t n_layers,
+                    const qv2_rank_config* cfg, int32_t* order_out, double* score_out) {
+  if (!order_out || (!w_sqnr_db && !a_sqnr_db)) return QV2_ERR_NULL;
+  if (n_layers <= 0) return QV2_ERR_SHAPE;
+  qv2_rank_config c;
+  if (cfg) c = *cfg; else qv2_rank_config_default(&c);
+  if (c.mse_source < 0 || c.mse_source > 2) return QV2_ERR_SHAPE;
+  const double* src[2] = {nullptr, nullptr};
+  int nsrc = 0;
+  if (c.mse_source == 1 || c.mse_source == 2) src[nsrc++] = w_mse;
+  if (c.mse_source == 0 || c.mse_source == 2) src[nsrc++] = a_mse;
+  for (int k = 0; k < nsrc; ++k) if (!src[k]) return QV2_ERR_NULL;
+  if (layer_pos)
+    for (int32_t i = 1; i < n_layers; ++i)
+      if (layer_pos[i] <= layer_pos[i - 1]) return QV2_ERR_SHAPE;
+
+  const int32_t n = n_layers;
+  std::vector<double> dw, da, score(n), key(n, 0.0);
+  if (!sqnr_delta_series(w_sqnr_db, layer_pos, n, c.sqnr_cap_db, dw) ||
+      !sqnr_delta_series(a_sqnr_db, layer_pos, n, c.sqnr_cap_db, da)) return QV2_ERR_NONFINITE;
+  for (int32_t i = 0; i < n; ++i) score[i] = c.alpha_w * dw[i] + c.alpha_a * da[i];
+
+  // outliers: MSE strictly above mse_factor x the arithmetic mean of its list
+  std::vector<char> outlier(n, 0);
+  for (int k = 0; k < nsrc; ++k) {
+    const double* m = src[k];
+    double total = 0.0;
+    for (int32_t i = 0; i < n; ++i) {
+      if (!std::isfinite(m[i]) || m[i] < 0.0) return QV2_ERR_NONFINITE;
+      total += m[i];
+    }
+    const double mean = total / static_cast<double>(n);
+    for (int32_t i = 0; i < n; ++i) {
+      if (m[i] > c.mse_factor * mean) outlier[i] = 1;
+      // one list: order outliers by their MSE; two lists: by MSE relative to the list's mean
+      const double kk = nsrc == 1 ? m[i] : (mean > 0.0 ? m[i] / mean : 0.0);
+      key[i] = std::max(key[i], kk);
+    }
+  }
+
+  std::vector<int32_t> front, rest;
+  for (int32_t i = 0; i < n; ++i) (outlier[i] ? front : rest).push_back(i);
+  std::stable_sort(front.begin(), front.end(),
+                   [&](int32_t a, int32_t b) { return key[a] > key[b]; });
+  std::stable_sort(rest.begin(), rest.end(),
+                   [&](int32_t a, int32_t b) { return score[a] < score[b]; });
+  int32_t w = 0;
+  for (int32_t i : front) order_out[w++] = i;
+  for (int32_t i : rest) order_out[w++] = i;
+  if (score_out) std::memcpy(score_out, score.data(), sizeof(double) * n);
+  return QV2_OK;
+}
+
+const char* qv2_status_string(qv2_status s) {
+  switch (s) {
+    case QV2_OK: return "ok";
+    case QV2_ERR_NULL: return "null pointer";
+    case QV2_ERR_SHAPE: return "bad shape or count";
+    case QV2_ERR_SCHEME: return "unknown quantization scheme";
+    case QV2_ERR_WORKSPACE: return "workspace too small";
+    case QV2_ERR_NONFINITE: return "non-finite value";
+    case QV2_ERR_HIP: return "HIP runtime error";
+    case QV2_ERR_ALIGN: return "misaligned pointer";
+  }
+  return "unknown status";
+}
+
+}  // extern "C"

@@ -1,0 +1,642 @@
+// HIP kernels (gfx950, wave64) and device entry points of the qv2 C ABI.
+//
+// Every pass is one flat launch over a tile table that spans all tensors of
+// the plan: a workgroup owns one tile, reduces it and leaves one partial record
+// per (tile, segment) in the workspace; a second small launch folds each
+// segment's partials in a fixed order.  No floating-point atomics anywhere, so
+// results are bit-stable.  The work is HBM-bound (4, 5 and 8 bytes per element
+// for the three passes); MFMA has no role here.
+//
+// Compiled with -ffp-contract=off: the quantizer's fp32 steps (Sec. 2.1 Eq. 1-3,
+// Sec. 4 Eq. 4-5) must each round once.  Fused multiply-adds appear only where
+// written explicitly (energy accumulation).
+#include <hip/hip_runtime.h>
+
+#include <cfloat>
+#include <cstdint>
+
+#include "qv2_internal.h"
+
+using namespace qv2;
+
+namespace {
+
+constexpr int kWave = 64;
+constexpr int kWaves = kBlock / kWave;
+constexpr int kUnroll = 8;          // independent 16-byte loads in flight per lane
+
+// ---------------------------------------------------------------------------
+// wavefront / workgroup reductions (fixed butterfly order => deterministic)
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ float group_min(float v, int w) {
+  for (int o = w >> 1; o > 0; o >>= 1) v = fminf(v, __shfl_xor(v, o));
+  return v;
+}
+__device__ __forceinline__ float group_max(float v, int w) {
+  for (int o = w >> 1; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o));
+  return v;
+}
+__device__ __forceinline__ double group_sum(double v, int w) {
+  for (int o = w >> 1; o > 0; o >>= 1) v += __shfl_xor(v, o);
+  return v;
+}
+
+// Sum of two doubles over the workgroup; result valid in thread 0.
+__device__ __forceinline__ void block_sum2(double& a, double& b) {
+  __shared__ double sa[kWaves], sb[kWaves];
+  a = group_sum(a, kWave);
+  b = group_sum(b, kWave);
+  const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
+  if (lane == 0) { sa[wave] = a; sb[wave] = b; }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    a = sa[0]; b = sb[0];
+    for (int i = 1; i < kWaves; ++i) { a += sa[i]; b += sb[i]; }
+  }
+}
+
+__device__ __forceinline__ void block_minmax(float& mn, float& mx) {
+  __shared__ float smn[kWaves], smx[kWaves];
+  mn = group_min(mn, kWave);
+  mx = group_max(mx, kWave);
+  const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
+  if (lane == 0) { smn[wave] = mn; smx[wave] = mx; }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    mn = smn[0]; mx = smx[0];
+    for (int i = 1; i < kWaves; ++i) { mn = fminf(mn, smn[i]); mx = fmaxf(mx, smx[i]); }
+  }
+}
+
+// Four independent fp64 accumulators, one per float4 component.  Energies are
+// accumulated in fp64 from the first element on, so the whole fp32 range of
+// inputs is safe (x*x can leave the fp32 range) and no fp32 rounding builds up.
+struct Acc4 {
+  double a = 0.0, b = 0.0, c = 0.0, d = 0.0;
+  __device__ __forceinline__ void add(const float4& v) {
+    a += static_cast<double>(v.x); b += static_cast<double>(v.y);
+    c += static_cast<double>(v.z); d += static_cast<double>(v.w);
+  }
+  __device__ __forceinline__ void add_sq(float x, float y, float z, float w) {
+    const double dx = x, dy = y, dz = z, dw = w;
+    a = fma(dx, dx, a); b = fma(dy, dy, b); c = fma(dz, dz, c); d = fma(dw, dw, d);
+  }
+  __device__ __forceinline__ double total() const { return (a + b) + (c + d); }
+};
+
+// Elements before the first 16-byte boundary of p (0..3, capped by len).
+__device__ __forceinline__ int head_elems(const void* p, int len) {
+  const int h = static_cast<int>(((16u - (reinterpret_cast<uintptr_t>(p) & 15u)) & 15u) >> 2);
+  return h < len ? h : len;
+}
+
+// ---------------------------------------------------------------------------
+// quantizer: Sec. 2.1 Eq. 1 / Sec. 4 Eq. 5 then Eq. 3, each step one fp32 rounding
+// ---------------------------------------------------------------------------
+struct QP { float scale, inv, zpf; };
+
+// Returns the code as a float in [-128,127]; err receives x - xhat.
+__device__ __forceinline__ float quant1(float x, const QP& q, float& err) {
+  const float t = x * q.inv;                       // fp32 multiply
+  const float r = rintf(t);                        // round half to even
+  // integer add of the zero-point: exact in fp32 below 2^24, saturates above
+  const float c = fminf(fmaxf(r + q.zpf, -128.0f), 127.0f);
+  const float xhat = (c - q.zpf) * q.scale;        // exact difference, one multiply
+  err = x - xhat;
+  return c;
+}
+
+__device__ __forceinline__ uint32_t quant4(const float4& v, const QP& q, Acc4& se2, Acc4& sx2) {
+  float e0, e1, e2, e3;
+  const int c0 = static_cast<int>(quant1(v.x, q, e0));
+  const int c1 = static_cast<int>(quant1(v.y, q, e1));
+  const int c2 = static_cast<int>(quant1(v.z, q, e2));
+  const int c3 = static_cast<int>(quant1(v.w, q, e3));
+  se2.add_sq(e0, e1, e2, e3);
+  sx2.add_sq(v.x, v.y, v.z, v.w);
+  return (static_cast<uint32_t>(c0) & 0xffu) | ((static_cast<uint32_t>(c1) & 0xffu) << 8) |
+         ((static_cast<uint32_t>(c2) & 0xffu) << 16) | (static_cast<uint32_t>(c3) << 24);
+}
+
+__device__ __forceinline__ QP load_qp(const qv2_qparams* params, int seg) {
+  const qv2_qparams p = params[seg];
+  return QP{p.scale, p.inv_scale, static_cast<float>(p.zp)};
+}
+
+// ---------------------------------------------------------------------------
+// pass 1 (calibration stage, Sec. 5; x_min / x_max of Eq. 2): stream tiles
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(kBlock) void k_stats_stream(const TensorDesc* __restrict__ descs,
+                                                         const Tile* __restrict__ tiles,
+                                                         StatPartial* __restrict__ parts) {
+  const Tile tl = tiles[blockIdx.x];
+  const float* __restrict__ p = descs[tl.tensor].x + tl.off;
+  const int len = tl.len, tid = threadIdx.x;
+  const int head = head_elems(p, len);
+  const int body = len - head, nvec = body >> 2, tail = body & 3;
+
+  float mn = INFINITY, mx = -INFINITY;
+  double sx = 0.0, sx2 = 0.0;
+  if (tid < head) {
+    const float v = p[tid];
+    mn = fminf(mn, v); mx = fmaxf(mx, v);
+    sx += v; sx2 += static_cast<double>(v) * v;
+  }
+  if (tid < tail) {
+    const float v = p[head + (nvec << 2) + tid];
+    mn = fminf(mn, v); mx = fmaxf(mx, v);
+    sx += v; sx2 += static_cast<double>(v) * v;
+  }
+  const float4* __restrict__ v4 = reinterpret_cast<const float4*>(p + head);
+  float4 mn4 = make_float4(INFINITY, INFINITY, INFINITY, INFINITY);
+  float4 mx4 = make_float4(-INFINITY, -INFINITY, -INFINITY, -INFINITY);
+  Acc4 as, as2;
+  int i = tid;
+  for (; i + (kUnroll - 1) * kBlock < nvec; i += kUnroll * kBlock) {
+    float4 r[kUnroll];
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u) r[u] = v4[i + u * kBlock];
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u) {
+      mn4.x = fminf(mn4.x, r[u].x); mn4.y = fminf(mn4.y, r[u].y);
+      mn4.z = fminf(mn4.z, r[u].z); mn4.w = fminf(mn4.w, r[u].w);
+      mx4.x = fmaxf(mx4.x, r[u].x); mx4.y = fmaxf(mx4.y, r[u].y);
+      mx4.z = fmaxf(mx4.z, r[u].z); mx4.w = fmaxf(mx4.w, r[u].w);
+      as.add(r[u]); as2.add_sq(r[u].x, r[u].y, r[u].z, r[u].w);
+    }
+  }
+  for (; i < nvec; i += kBlock) {
+    const float4 r = v4[i];
+    mn4.x = fminf(mn4.x, r.x); mn4.y = fminf(mn4.y, r.y);
+    mn4.z = fminf(mn4.z, r.z); mn4.w = fminf(mn4.w, r.w);
+    mx4.x = fmaxf(mx4.x, r.x); mx4.y = fmaxf(mx4.y, r.y);
+    mx4.z = fmaxf(mx4.z, r.z); mx4.w = fmaxf(mx4.w, r.w);
+    as.add(r); as2.add_sq(r.x, r.y, r.z, r.w);
+  }
+  sx += as.total(); sx2 += as2.total();
+  mn = fminf(fminf(mn, mn4.x), fminf(fminf(mn4.y, mn4.z), mn4.w));
+  mx = fmaxf(fmaxf(mx, mx4.x), fmaxf(fmaxf(mx4.y, mx4.z), mx4.w));
+
+  block_minmax(mn, mx);
+  block_sum2(sx, sx2);
+  if (tid == 0) {
+    StatPartial o;
+    o.mn = mn; o.mx = mx; o.sx = sx; o.sx2 = sx2;
+    parts[tl.part0] = o;
+  }
+}
+
+// Copies a row-group tile into LDS with 16-byte transfers.  Element e of the
+// tile lands at xs[e + shift]; returns shift (0..3).
+__device__ __forceinline__ int stage_tile(const float* __restrict__ p, int len, float* xs) {
+  const int tid = threadIdx.x;
+  const int head = head_elems(p, len);
+  const int shift = (4 - head) & 3;
+  const int body = len - head, nvec = body >> 2, tail = body & 3;
+  if (tid < head) xs[shift + tid] = p[tid];
+  const float4* __restrict__ v4 = reinterpret_cast<const float4*>(p + head);
+  float4* d4 = reinterpret_cast<float4*>(xs + shift + head);
+  for (int i = tid; i < nvec; i += kBlock) d4[i] = v4[i];
+  if (tid < tail) xs[shift + head + (nvec << 2) + tid] = p[head + (nvec << 2) + tid];
+  return shift;
+}
+
+// Lanes per row of a row-group tile: the power of two >= inner, at most a wavefront.
+__device__ __forceinline__ int row_width(int inner) {
+  int w = 1;
+  while (w < inner && w < kWave) w <<= 1;
+  return w;
+}
+
+// pass 1, row-group tiles: many short segments (output channels) per workgroup
+__global__ __launch_bounds__(kBlock) void k_stats_rows(const TensorDesc* __restrict__ descs,
+                                                       const Tile* __restrict__ tiles,
+                                                       StatPartial* __restrict__ parts) {
+  __shared__ __attribute__((aligned(16))) float xs[kRowGroupCap + 4];
+  const Tile tl = tiles[blockIdx.x];
+  const int shift = stage_tile(descs[tl.tensor].x + tl.off, tl.len, xs);
+  __syncthreads();
+
+  const int inner = tl.inner, w = row_width(inner), gpw = kWave / w;
+  const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
+  const int g = lane >> __builtin_ctz(w), gl = lane & (w - 1);
+  for (int rb = wave * gpw; rb < tl.rows; rb += kWaves * gpw) {     // uniform per wavefront
+    const int r = rb + g;
+    const bool live = r < tl.rows;
+    float mn = INFINITY, mx = -INFINITY;
+    double sx = 0.0, sx2 = 0.0;
+    if (live) {
+      const float* row = xs + shift + r * inner;
+      for (int j = gl; j < inner; j += w) {
+        const float v = row[j];
+        mn = fminf(mn, v); mx = fmaxf(mx, v);
+        sx += v; sx2 = fma(static_cast<double>(v), static_cast<double>(v), sx2);
+      }
+    }
+    mn = group_min(mn, w); mx = group_max(mx, w);
+    sx = group_sum(sx, w); sx2 = group_sum(sx2, w);
+    if (live && gl == 0) {
+      StatPartial o;
+      o.mn = mn; o.mx = mx; o.sx = sx; o.sx2 = sx2;
+      parts[tl.part0 + r] = o;
+    }
+  }
+}
+
+// Scale and zero-point from a segment's range (Eq. 2 with N = 256; Eq. 4 with b = 8).
+__device__ __forceinline__ void make_params(float mn, float mx, int scheme, qv2_qparams& o) {
+  o.min = mn + 0.0f;                               // -0.0 -> +0.0
+  o.max = mx + 0.0f;
+  o._pad = 0;
+  float s, lo = 0.0f;
+  if (scheme == QV2_ASYM_TENSOR) {
+    lo = fminf(mn, 0.0f);
+    const float hi = fmaxf(mx, 0.0f);
+    s = (hi - lo) / 255.0f;
+  } else {
+    s = fmaxf(fabsf(mn), fabsf(mx)) / 127.0f;
+  }
+  if (!(s >= FLT_MIN)) { o.scale = 1.0f; o.inv_scale = 1.0f; o.zp = 0; return; }
+  const float inv = 1.0f / s;
+  o.scale = s; o.inv_scale = inv; o.zp = 0;
+  if (scheme == QV2_ASYM_TENSOR) {
+    const float prod = lo * inv;
+    const float z = rintf(-128.0f - prod);
+    o.zp = static_cast<int>(fminf(fmaxf(z, -128.0f), 127.0f));
+  }
+}
+
+// pass 1, fold: one wavefront per segment walks its partials in a fixed order
+__global__ __launch_bounds__(kBlock) void k_fold_stats(const Segment* __restrict__ segs, int nseg,
+                                                       const StatPartial* __restrict__ parts,
+                                                       qv2_qparams* __restrict__ params,
+                                                       qv2_sums* __restrict__ sums) {
+  const int seg = blockIdx.x * kWaves + (threadIdx.x >> 6);
+  const int lane = threadIdx.x & (kWave - 1);
+  if (seg >= nseg) return;
+  const Segment sg = segs[seg];
+  float mn = INFINITY, mx = -INFINITY;
+  double sx = 0.0, sx2 = 0.0;
+  for (int i = lane; i < sg.nparts; i += kWave) {
+    const StatPartial q = parts[sg.part0 + i];
+    mn = fminf(mn, q.mn); mx = fmaxf(mx, q.mx);
+    sx += q.sx; sx2 += q.sx2;
+  }
+  mn = group_min(mn, kWave); mx = group_max(mx, kWave);
+  sx = group_sum(sx, kWave); sx2 = group_sum(sx2, kWave);
+  if (lane == 0) {
+    qv2_qparams qp;
+    make_params(mn, mx, sg.scheme, qp);
+    params[seg] = qp;
+    qv2_sums o;
+    o.sum_x = sx; o.sum_x2 = sx2; o.sum_e2 = 0.0; o.n = sg.n;
+    sums[seg] = o;
+  }
+}
+
+// ---------------------------------------------------------------------------
+// pass 2 (Eq. 1, 3, 5 and the energies of Eq. 6-7): stream tiles
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(kBlock) void k_quant_stream(const TensorDesc* __restrict__ descs,
+                                                         const Tile* __restrict__ tiles,
+                                                         const qv2_qparams* __restrict__ params,
+                                                         ErrPartial* __restrict__ parts) {
+  const Tile tl = tiles[blockIdx.x];
+  const TensorDesc td = descs[tl.tensor];
+  const float* __restrict__ p = td.x + tl.off;
+  int8_t* __restrict__ c = td.codes ? td.codes + tl.off : nullptr;
+  const QP q = load_qp(params, tl.seg0);
+  const int len = tl.len, tid = threadIdx.x;
+  const int head = head_elems(p, len);
+  const int body = len - head, nvec = body >> 2, tail = body & 3;
+
+  double sx2 = 0.0, se2 = 0.0;
+  if (tid < head || tid < tail) {
+    for (int k = 0; k < 2; ++k) {
+      const bool on = k == 0 ? tid < head : tid < tail;
+      if (!on) continue;
+      const int idx = k == 0 ? tid : head + (nvec << 2) + tid;
+      const float v = p[idx];
+      float e;
+      const float code = quant1(v, q, e);
+      if (c) c[idx] = static_cast<int8_t>(static_cast<int>(code));
+      sx2 += static_cast<double>(v) * v;
+      se2 += static_cast<double>(e) * e;
+    }
+  }
+  const float4* __restrict__ v4 = reinterpret_cast<const float4*>(p + head);
+  // codes of the vector body go out as packed dwords when that address is 4-byte aligned
+  const bool cw_ok = c && ((reinterpret_cast<uintptr_t>(c + head) & 3u) == 0);
+  uint32_t* __restrict__ cw = reinterpret_cast<uint32_t*>(c + head);
+  Acc4 ae2, ax2;
+  int i = tid;
+  for (; i + (kUnroll - 1) * kBlock < nvec; i += kUnroll * kBlock) {
+    float4 r[kUnroll];
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u) r[u] = v4[i + u * kBlock];
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u) {
+      const uint32_t pk = quant4(r[u], q, ae2, ax2);
+      if (cw_ok) {
+        __builtin_nontemporal_store(pk, &cw[i + u * kBlock]);
+      } else if (c) {
+        int8_t* d = c + head + ((i + u * kBlock) << 2);
+        d[0] = static_cast<int8_t>(pk); d[1] = static_cast<int8_t>(pk >> 8);
+        d[2] = static_cast<int8_t>(pk >> 16); d[3] = static_cast<int8_t>(pk >> 24);
+      }
+    }
+  }
+  for (; i < nvec; i += kBlock) {
+    const float4 r = v4[i];
+    const uint32_t pk = quant4(r, q, ae2, ax2);
+    if (cw_ok) {
+      __builtin_nontemporal_store(pk, &cw[i]);
+    } else if (c) {
+      int8_t* d = c + head + (i << 2);
+      d[0] = static_cast<int8_t>(pk); d[1] = static_cast<int8_t>(pk >> 8);
+      d[2] = static_cast<int8_t>(pk >> 16); d[3] = static_cast<int8_t>(pk >> 24);
+    }
+  }
+  se2 += ae2.total(); sx2 += ax2.total();
+  block_sum2(sx2, se2);
+  if (tid == 0) {
+    ErrPartial o;
+    o.sx2 = sx2; o.se2 = se2;
+    parts[tl.part0] = o;
+  }
+}
+
+// pass 2, row-group tiles
+__global__ __launch_bounds__(kBlock) void k_quant_rows(const TensorDesc* __restrict__ descs,
+                                                       const Tile* __restrict__ tiles,
+                                                       const qv2_qparams* __restrict__ params,
+                                                       ErrPartial* __restrict__ parts) {
+  __shared__ __attribute__((aligned(16))) float xs[kRowGroupCap + 4];
+  __shared__ __attribute__((aligned(16))) int8_t cs[kRowGroupCap + 8];
+  const Tile tl = tiles[blockIdx.x];
+  const TensorDesc td = descs[tl.tensor];
+  const int shift = stage_tile(td.x + tl.off, tl.len, xs);
+  int8_t* __restrict__ dst = td.codes ? td.codes + tl.off : nullptr;
+  const int ca = static_cast<int>(reinterpret_cast<uintptr_t>(dst) & 3u);   // code e sits at cs[e + ca]
+  __syncthreads();
+
+  const int inner = tl.inner, w = row_width(inner), gpw = kWave / w;
+  const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
+  const int g = lane >> __builtin_ctz(w), gl = lane & (w - 1);
+  for (int rb = wave * gpw; rb < tl.rows; rb += kWaves * gpw) {
+    const int r = rb + g;
+    const bool live = r < tl.rows;
+    double sx2 = 0.0, se2 = 0.0;
+    if (live) {
+      const QP q = load_qp(params, tl.seg0 + r);
+      const float* row = xs + shift + r * inner;
+      int8_t* crow = cs + ca + r * inner;
+      for (int j = gl; j < inner; j += w) {
+        const float v = row[j];
+        float e;
+        const float code = quant1(v, q, e);
+        crow[j] = static_cast<int8_t>(static_cast<int>(code));
+        sx2 = fma(static_cast<double>(v), static_cast<double>(v), sx2);
+        se2 = fma(static_cast<double>(e), static_cast<double>(e), se2);
+      }
+    }
+    sx2 = group_sum(sx2, w); se2 = group_sum(se2, w);
+    if (live && gl == 0) {
+      ErrPartial o;
+      o.sx2 = sx2; o.se2 = se2;
+      parts[tl.part0 + r] = o;
+    }
+  }
+  if (!dst) return;
+  __syncthreads();
+  // copy the codes out as whole dwords where the destination allows it
+  const int total = tl.len + ca;
+  int8_t* base = dst - ca;
+  for (int k = threadIdx.x; (k << 2) < total; k += kBlock) {
+    const int b0 = k << 2;
+    if (b0 >= ca && b0 + 4 <= total) {
+      *reinterpret_cast<uint32_t*>(base + b0) = *reinterpret_cast<const uint32_t*>(cs + b0);
+    } else {
+      const int lo = b0 > ca ? b0 : ca, hi = b0 + 4 < total ? b0 + 4 : total;
+      for (int b = lo; b < hi; ++b) base[b] = cs[b];
+    }
+  }
+}
+
+__global__ __launch_bounds__(kBlock) void k_fold_err(const Segment* __restrict__ segs, int nseg,
+                                                     const ErrPartial* __restrict__ parts,
+                                                     qv2_sums* __restrict__ sums) {
+  const int seg = blockIdx.x * kWaves + (threadIdx.x >> 6);
+  const int lane = threadIdx.x & (kWave - 1);
+  if (seg >= nseg) return;
+  const Segment sg = segs[seg];
+  double sx2 = 0.0, se2 = 0.0;
+  for (int i = lane; i < sg.nparts; i += kWave) {
+    const ErrPartial q = parts[sg.part0 + i];
+    sx2 += q.sx2; se2 += q.se2;
+  }
+  sx2 = group_sum(sx2, kWave); se2 = group_sum(se2, kWave);
+  if (lane == 0) {
+    sums[seg].sum_x2 = sx2; sums[seg].sum_e2 = se2; sums[seg].n = sg.n;
+  }
+}
+
+// ---------------------------------------------------------------------------
+// pass 3 (Algorithm 2: CalculateSQNR / CalculateMSE on D[i] and Q[i])
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(kBlock) void k_pair_stream(const TensorDesc* __restrict__ descs,
+                                                        const Tile* __restrict__ tiles,
+                                                        ErrPartial* __restrict__ parts) {
+  const Tile tl = tiles[blockIdx.x];
+  const TensorDesc td = descs[tl.tensor];
+  const float* __restrict__ a = td.x + tl.off;
+  const float* __restrict__ b = td.qrun + tl.off;
+  const int len = tl.len, tid = threadIdx.x;
+  double sr2 = 0.0, sd2 = 0.0;
+
+  if (((reinterpret_cast<uintptr_t>(a) ^ reinterpret_cast<uintptr_t>(b)) & 15u) != 0) {
+    // the two tensors sit at different offsets within 16 bytes: element loads
+    for (int i = tid; i < len; i += kBlock) {
+      const float x = a[i], d = x - b[i];
+      sr2 = fma(static_cast<double>(x), static_cast<double>(x), sr2);
+      sd2 = fma(static_cast<double>(d), static_cast<double>(d), sd2);
+    }
+  } else {
+    const int head = head_elems(a, len);
+    const int body = len - head, nvec = body >> 2, tail = body & 3;
+    if (tid < head) {
+      const float x = a[tid], d = x - b[tid];
+      sr2 += static_cast<double>(x) * x; sd2 += static_cast<double>(d) * d;
+    }
+    if (tid < tail) {
+      const int idx = head + (nvec << 2) + tid;
+      const float x = a[idx], d = x - b[idx];
+      sr2 += static_cast<double>(x) * x; sd2 += static_cast<double>(d) * d;
+    }
+    const float4* __restrict__ a4 = reinterpret_cast<const float4*>(a + head);
+    const float4* __restrict__ b4 = reinterpret_cast<const float4*>(b + head);
+    constexpr int U = kUnroll / 2;                 // two streams: same bytes in flight
+    Acc4 ar2, ad2;
+    int i = tid;
+    for (; i + (U - 1) * kBlock < nvec; i += U * kBlock) {
+      float4 ra[U], rb[U];
+#pragma unroll
+      for (int u = 0; u < U; ++u) { ra[u] = a4[i + u * kBlock]; rb[u] = b4[i + u * kBlock]; }
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        ar2.add_sq(ra[u].x, ra[u].y, ra[u].z, ra[u].w);
+        ad2.add_sq(ra[u].x - rb[u].x, ra[u].y - rb[u].y, ra[u].z - rb[u].z, ra[u].w - rb[u].w);
+      }
+    }
+    for (; i < nvec; i += kBlock) {
+      const float4 x = a4[i], y = b4[i];
+      ar2.add_sq(x.x, x.y, x.z, x.w);
+      ad2.add_sq(x.x - y.x, x.y - y.y, x.z - y.z, x.w - y.w);
+    }
+    sr2 += ar2.total(); sd2 += ad2.total();
+  }
+  block_sum2(sr2, sd2);
+  if (tid == 0) {
+    ErrPartial o;
+    o.sx2 = sr2; o.se2 = sd2;
+    parts[tl.part0] = o;
+  }
+}
+
+__global__ __launch_bounds__(kBlock) void k_fold_pair(const PairTensor* __restrict__ pt, int n,
+                                                      const ErrPartial* __restrict__ parts,
+                                                      qv2_pair_sums* __restrict__ out) {
+  const int t = blockIdx.x * kWaves + (threadIdx.x >> 6);
+  const int lane = threadIdx.x & (kWave - 1);
+  if (t >= n) return;
+  const PairTensor p = pt[t];
+  double sr2 = 0.0, sd2 = 0.0;
+  for (int i = lane; i < p.nparts; i += kWave) {
+    const ErrPartial q = parts[p.part0 + i];
+    sr2 += q.sx2; sd2 += q.se2;
+  }
+  sr2 = group_sum(sr2, kWave); sd2 = group_sum(sd2, kWave);
+  if (lane == 0) {
+    qv2_pair_sums o;
+    o.sum_ref2 = sr2; o.sum_d2 = sd2; o.n = p.n; o._pad = 0;
+    out[t] = o;
+  }
+}
+
+// ---------------------------------------------------------------------------
+// host helpers
+// ---------------------------------------------------------------------------
+size_t align256(size_t v) { return (v + 255) & ~static_cast<size_t>(255); }
+
+// First device call on a plan: one allocation holding all tables, blocking copies.
+qv2_status ensure_uploaded(qv2_plan* p) {
+  if (p->d_blob) return QV2_OK;
+  const size_t b_desc = align256(p->descs.size() * sizeof(TensorDesc));
+  const size_t b_tile = align256(p->tiles.size() * sizeof(Tile));
+  const size_t b_seg = align256(p->segments.size() * sizeof(Segment));
+  const size_t b_ptile = align256(p->pair_tiles.size() * sizeof(Tile));
+  const size_t b_pten = align256(p->pair_tensors.size() * sizeof(PairTensor));
+  char* blob = nullptr;
+  if (hipMalloc(reinterpret_cast<void**>(&blob), b_desc + b_tile + b_seg + b_ptile + b_pten + 256) !=
+      hipSuccess) { (void)hipGetLastError(); return QV2_ERR_HIP; }
+  char* q = blob;
+  p->d_descs = reinterpret_cast<TensorDesc*>(q); q += b_desc;
+  p->d_tiles = reinterpret_cast<Tile*>(q); q += b_tile;
+  p->d_segments = reinterpret_cast<Segment*>(q); q += b_seg;
+  p->d_pair_tiles = reinterpret_cast<Tile*>(q); q += b_ptile;
+  p->d_pair_tensors = reinterpret_cast<PairTensor*>(q);
+  bool ok = true;
+  auto put = [&](void* d, const void* h, size_t n) {
+    if (n && hipMemcpy(d, h, n, hipMemcpyHostToDevice) != hipSuccess) ok = false;
+  };
+  put(p->d_descs, p->descs.data(), p->descs.size() * sizeof(TensorDesc));
+  put(p->d_tiles, p->tiles.data(), p->tiles.size() * sizeof(Tile));
+  put(p->d_segments, p->segments.data(), p->segments.size() * sizeof(Segment));
+  put(p->d_pair_tiles, p->pair_tiles.data(), p->pair_tiles.size() * sizeof(Tile));
+  put(p->d_pair_tensors, p->pair_tensors.data(), p->pair_tensors.size() * sizeof(PairTensor));
+  if (!ok) { (void)hipGetLastError(); (void)hipFree(blob); return QV2_ERR_HIP; }
+  p->d_blob = blob;
+  return QV2_OK;
+}
+
+qv2_status check_call(const qv2_plan* plan, const void* a, const void* b, const void* ws,
+                      size_t ws_bytes) {
+  if (!plan || !a || !b || !ws) return QV2_ERR_NULL;
+  if (ws_bytes < plan->workspace_bytes) return QV2_ERR_WORKSPACE;
+  if (reinterpret_cast<uintptr_t>(ws) & 15u) return QV2_ERR_ALIGN;
+  if ((reinterpret_cast<uintptr_t>(a) & 7u) || (reinterpret_cast<uintptr_t>(b) & 7u)) return QV2_ERR_ALIGN;
+  return QV2_OK;
+}
+
+qv2_status launch_status() { return hipGetLastError() == hipSuccess ? QV2_OK : QV2_ERR_HIP; }
+
+}  // namespace
+
+extern "C" {
+
+void qv2_plan_destroy(qv2_plan* plan) {
+  if (!plan) return;
+  if (plan->d_blob) (void)hipFree(plan->d_blob);
+  delete plan;
+}
+
+qv2_status qv2_calibrate(qv2_plan* plan, qv2_qparams* d_params, qv2_sums* d_sums,
+                         void* d_workspace, size_t workspace_bytes, void* hip_stream) {
+  qv2_status st = check_call(plan, d_params, d_sums, d_workspace, workspace_bytes);
+  if (st != QV2_OK) return st;
+  if ((st = ensure_uploaded(plan)) != QV2_OK) return st;
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  StatPartial* parts = static_cast<StatPartial*>(d_workspace);
+  const int n_stream = static_cast<int>(plan->n_stream_tiles);
+  const int n_rows = static_cast<int>(plan->tiles.size()) - n_stream;
+  const int nseg = static_cast<int>(plan->segments.size());
+  if (n_stream > 0)
+    hipLaunchKernelGGL(k_stats_stream, dim3(n_stream), dim3(kBlock), 0, s, plan->d_descs,
+                       plan->d_tiles, parts);
+  if (n_rows > 0)
+    hipLaunchKernelGGL(k_stats_rows, dim3(n_rows), dim3(kBlock), 0, s, plan->d_descs,
+                       plan->d_tiles + n_stream, parts);
+  hipLaunchKernelGGL(k_fold_stats, dim3((nseg + kWaves - 1) / kWaves), dim3(kBlock), 0, s,
+                     plan->d_segments, nseg, parts, d_params, d_sums);
+  return launch_status();
+}
+
+qv2_status qv2_fakequant_metrics(qv2_plan* plan, const qv2_qparams* d_params, qv2_sums* d_sums,
+                                 void* d_workspace, size_t workspace_bytes, void* hip_stream) {
+  qv2_status st = check_call(plan, d_params, d_sums, d_workspace, workspace_bytes);
+  if (st != QV2_OK) return st;
+  if ((st = ensure_uploaded(plan)) != QV2_OK) return st;
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  ErrPartial* parts = static_cast<ErrPartial*>(d_workspace);
+  const int n_stream = static_cast<int>(plan->n_stream_tiles);
+  const int n_rows = static_cast<int>(plan->tiles.size()) - n_stream;
+  const int nseg = static_cast<int>(plan->segments.size());
+  if (n_stream > 0)
+    hipLaunchKernelGGL(k_quant_stream, dim3(n_stream), dim3(kBlock), 0, s, plan->d_descs,
+                       plan->d_tiles, d_params, parts);
+  if (n_rows > 0)
+    hipLaunchKernelGGL(k_quant_rows, dim3(n_rows), dim3(kBlock), 0, s, plan->d_descs,
+                       plan->d_tiles + n_stream, d_params, parts);
+  hipLaunchKernelGGL(k_fold_err, dim3((nseg + kWaves - 1) / kWaves), dim3(kBlock), 0, s,
+                     plan->d_segments, nseg, parts, d_sums);
+  return launch_status();
+}
+
+qv2_status qv2_pair_metrics(qv2_plan* plan, qv2_pair_sums* d_pair_sums, void* d_workspace,
+                            size_t workspace_bytes, void* hip_stream) {
+  qv2_status st = check_call(plan, d_pair_sums, d_pair_sums, d_workspace, workspace_bytes);
+  if (st != QV2_OK) return st;
+  if ((st = ensure_uploaded(plan)) != QV2_OK) return st;
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  ErrPartial* parts = static_cast<ErrPartial*>(d_workspace);
+  const int n_tiles = static_cast<int>(plan->pair_tiles.size());
+  const int nt = static_cast<int>(plan->pair_tensors.size());
+  if (n_tiles > 0)
+    hipLaunchKernelGGL(k_pair_stream, dim3(n_tiles), dim3(kBlock), 0, s, plan->d_descs,
+                       plan->d_pair_tiles, parts);
+  hipLaunchKernelGGL(k_fold_pair, dim3((nt + kWaves - 1) / kWaves), dim3(kBlock), 0, s,
+                     plan->d_pair_tensors, nt, parts, d_pair_sums);
+  return launch_status();
+}
+
+}  // extern "C"

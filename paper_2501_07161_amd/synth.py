@@ -68,7 +68,8 @@ def materialize(spec: TensorSpec, device="cpu") -> torch.Tensor:
             x.clamp_(max=6.0)
     elif spec.dist == "laplace_outlier":
         u = torch.rand(n, generator=g, device=device, dtype=torch.float32).sub_(0.5)
-        mag = torch.log1p(-2.0 * u.abs()).mul_(-spec.sigma)        # Laplace(0, b) by inverse CDF
+        # Laplace(0, b) by inverse CDF; |u| is kept below 1/2 so the draw stays finite
+        mag = torch.log1p(-2.0 * u.abs().clamp_(max=0.49999997)).mul_(-spec.sigma)
         x = torch.sign(u).mul_(mag)
         hit = torch.rand(n, generator=g, device=device, dtype=torch.float32) < 0.01
         x = torch.where(hit, x * 20.0, x)

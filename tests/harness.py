@@ -1,0 +1,221 @@
+"""Shared plumbing of the GPU parity tests: feed the same bytes to the HIP
+library (through the ctypes binding of the C ABI) and to the CPU oracle, and
+compare to the stated bar.
+
+Bar (from the benchmark spec): min, max, scale, zero-point and int8 codes
+bit-exact; MSE within 1e-4 relative; SQNR within 1e-3 dB; ranking identical.
+Added here: sum(x^2) within 1e-6 relative, mean within 1e-6 * absmax, variance
+within 1e-4 relative.
+"""
+from __future__ import annotations
+
+import math
+import os
+from concurrent.futures import ThreadPoolExecutor
+from dataclasses import dataclass, field
+from typing import List, Optional
+
+import numpy as np
+import torch
+
+from oracle import reference as orc
+from paper_2501_07161_amd import binding as qb
+from paper_2501_07161_amd import synth
+
+MSE_RTOL = 1e-4
+SQNR_ATOL_DB = 1e-3
+SX2_RTOL = 1e-6
+VAR_RTOL = 1e-4
+
+
+@dataclass
+class Item:
+    """One tensor of a case: device data plus how to quantize it."""
+    name: str
+    x: torch.Tensor                      # device, fp32 (any view with a valid data_ptr)
+    scheme: int = qb.QV2_ASYM_TENSOR
+    channels: int = 1
+    kind: int = 0
+    layer: int = 0
+    qrun: Optional[torch.Tensor] = None
+    want_codes: bool = True
+    codes: Optional[torch.Tensor] = None  # filled by run_gpu
+    codes_offset: int = 0                 # byte misalignment to give the code buffer (tests)
+
+
+@dataclass
+class GpuResult:
+    plan: qb.Plan
+    params: np.ndarray
+    sums: np.ndarray
+    pair: np.ndarray
+    metrics: np.ndarray
+    pair_mse: np.ndarray
+    pair_sqnr: np.ndarray
+
+
+def workers() -> int:
+    return max(1, min(8, (os.cpu_count() or 1)))
+
+
+def items_from_specs(specs: List[synth.TensorSpec], device="cuda") -> List[Item]:
+    out = []
+    for s in specs:
+        x = synth.materialize(s, device)
+        out.append(Item(s.name, x, s.scheme, s.channels, s.kind, s.layer))
+    return out
+
+
+def attach_pairs(items: List[Item], specs: List[synth.TensorSpec]):
+    """Quantized-run partner of every activation: dequant(quant(ref)) + N(0, (0.01*std(ref))^2),
+    made by the ORACLE from the host copy of ref (never by the HIP path)."""
+    def one(idx):
+        it, sp = items[idx], specs[idx]
+        if not sp.has_pair:
+            return None
+        x = it.x.detach().cpu().numpy().reshape(-1)
+        cal = orc.calibrate(x, it.scheme, it.channels)
+        fq = orc.fakequant(x, cal, it.scheme, it.channels, keep_xhat=True)
+        noise = synth.unit_noise(sp, it.x.device).cpu().numpy().reshape(-1)
+        sigma = np.float32(0.01 * float(np.std(x.astype(np.float64))))
+        return (fq.xhat + sigma * noise).astype(np.float32)
+    with ThreadPoolExecutor(workers()) as ex:
+        res = list(ex.map(one, range(len(items))))
+    for it, q in zip(items, res):
+        if q is not None:
+            it.qrun = torch.from_numpy(q).to(it.x.device).view(it.x.shape)
+
+
+def run_gpu(items: List[Item], params_override: Optional[np.ndarray] = None,
+            do_calibrate: bool = True) -> GpuResult:
+    """calibrate -> fakequant -> pair on the current stream, then host finalize."""
+    dev = items[0].x.device
+    rows = []
+    for it in items:
+        if it.want_codes:
+            raw = torch.full((it.x.numel() + 16,), 0x55, dtype=torch.int8, device=dev)
+            it._raw_codes = raw
+            it.codes = raw[it.codes_offset: it.codes_offset + it.x.numel()]
+        rows.append(qb.TensorArg(x=it.x, numel=it.x.numel(), scheme=it.scheme, channels=it.channels,
+                                 qrun=it.qrun, codes=it.codes if it.want_codes else None,
+                                 kind=it.kind, layer=it.layer))
+    plan = qb.qv2_plan_create(rows)
+    buf = qb.Buffers(plan, dev)
+    if do_calibrate:
+        qb.qv2_calibrate(plan, buf.params, buf.sums, buf.workspace)
+    if params_override is not None:
+        torch.cuda.synchronize()
+        buf.params.copy_(torch.from_numpy(params_override.view(np.uint8)).to(dev))
+    qb.qv2_fakequant_metrics(plan, buf.params, buf.sums, buf.workspace)
+    qb.qv2_pair_metrics(plan, buf.pair, buf.workspace)
+    torch.cuda.synchronize()
+    params, sums, pair = buf.host()
+    metrics = qb.qv2_finalize(plan, params, sums, strict=False)
+    pm, ps = qb.qv2_pair_finalize(pair)
+    res = GpuResult(plan, params, sums, pair, metrics, pm, ps)
+    res.buffers = buf
+    return res
+
+
+def _rel(a, b):
+    return abs(a - b) / max(abs(b), 1e-300)
+
+
+def check_item(t: int, it: Item, res: GpuResult, check_codes: bool = True, cal=None):
+    """Element-by-element comparison of one tensor against the oracle."""
+    x = it.x.detach().cpu().numpy().reshape(-1)
+    cal = cal or orc.calibrate(x, it.scheme, it.channels)
+    fq = orc.fakequant(x, cal, it.scheme, it.channels)
+    s0 = res.plan.segment_begin[t]
+    S = it.channels if it.scheme == qb.QV2_SYM_CHANNEL else 1
+    P, U = res.params[s0:s0 + S], res.sums[s0:s0 + S]
+    tag = f"{it.name} (tensor {t})"
+    # bit-exact part
+    for fld, want in (("min", cal.min), ("max", cal.max), ("scale", cal.scale),
+                      ("inv_scale", cal.inv_scale)):
+        got = P[fld]
+        bad = np.nonzero(got.view(np.uint32) != want.view(np.uint32))[0]
+        assert bad.size == 0, f"{tag}: {fld} differs at segment {bad[:5]}: {got[bad[:5]]} vs {want[bad[:5]]}"
+    assert np.array_equal(P["zp"], cal.zp), f"{tag}: zero-point"
+    assert np.array_equal(U["n"], cal.n), f"{tag}: n"
+    if check_codes and it.want_codes:
+        got = it.codes.cpu().numpy()
+        bad = np.nonzero(got != fq.codes)[0]
+        assert bad.size == 0, (f"{tag}: {bad.size} codes differ, first at {bad[:5]}: "
+                               f"{got[bad[:5]]} vs {fq.codes[bad[:5]]}")
+        raw = it._raw_codes.cpu().numpy()     # nothing written outside the code range
+        assert np.all(raw[:it.codes_offset] == 0x55) and np.all(raw[it.codes_offset + x.size:] == 0x55), \
+            f"{tag}: code buffer overrun"
+    # floating-point part, per segment
+    absmax = np.maximum(np.abs(cal.min), np.abs(cal.max)).astype(np.float64)
+    n = cal.n.astype(np.float64)
+    assert np.all(np.abs(U["sum_x"] - cal.sum_x) / n <= 1e-6 * absmax + 1e-300), f"{tag}: sum_x"
+    assert np.all(np.abs(U["sum_x2"] - fq.sum_x2) <= SX2_RTOL * fq.sum_x2 + 1e-300), f"{tag}: sum_x2"
+    assert np.all(np.abs(U["sum_e2"] - fq.sum_e2) <= MSE_RTOL * fq.sum_e2 + 1e-300), f"{tag}: sum_e2"
+    # per tensor
+    m = orc.tensor_metrics(x, cal, fq)
+    g = res.metrics[t]
+    assert _rel(g["mse"], m.mse) <= MSE_RTOL or (m.mse == 0 and g["mse"] == 0), f"{tag}: mse {g['mse']} vs {m.mse}"
+    if math.isinf(m.sqnr_db):
+        assert g["sqnr_db"] == m.sqnr_db, f"{tag}: sqnr"
+    else:
+        assert abs(g["sqnr_db"] - m.sqnr_db) <= SQNR_ATOL_DB, f"{tag}: sqnr {g['sqnr_db']} vs {m.sqnr_db}"
+    assert abs(g["mean"] - m.mean) <= 1e-6 * m.absmax + 1e-300, f"{tag}: mean"
+    assert abs(g["var"] - m.var) <= VAR_RTOL * m.var + 1e-12, f"{tag}: var {g['var']} vs {m.var}"
+    assert g["absmax"] == np.float32(m.absmax) and g["min"] == np.float32(m.min) and g["max"] == np.float32(m.max)
+    out = {"w_mse": m.mse, "w_sqnr": m.sqnr_db}
+    # pair
+    if it.qrun is not None:
+        pm = orc.pair_metrics(x, it.qrun.detach().cpu().numpy().reshape(-1))
+        rec = res.pair[t]
+        assert rec["n"] == x.size
+        assert _rel(rec["sum_ref2"], pm.sum_ref2) <= SX2_RTOL, f"{tag}: pair sum_ref2"
+        assert _rel(rec["sum_d2"], pm.sum_d2) <= MSE_RTOL or (pm.sum_d2 == 0 and rec["sum_d2"] == 0), \
+            f"{tag}: pair sum_d2"
+        assert _rel(res.pair_mse[t], pm.mse) <= MSE_RTOL or pm.mse == 0
+        if math.isinf(pm.sqnr_db):
+            assert res.pair_sqnr[t] == pm.sqnr_db
+        else:
+            assert abs(res.pair_sqnr[t] - pm.sqnr_db) <= SQNR_ATOL_DB, f"{tag}: pair sqnr"
+        out.update(p_mse=pm.mse, p_sqnr=pm.sqnr_db)
+    else:
+        assert res.pair[t]["n"] == 0 and res.pair[t]["sum_d2"] == 0
+    return out
+
+
+def check_all(items: List[Item], res: GpuResult, parallel: bool = True):
+    idx = range(len(items))
+    if parallel and len(items) > 4:
+        with ThreadPoolExecutor(workers()) as ex:
+            return list(ex.map(lambda t: check_item(t, items[t], res), idx))
+    return [check_item(t, items[t], res) for t in idx]
+
+
+def check_ranking(items: List[Item], res: GpuResult, oracle_rows, cfg_kwargs=None):
+    """Layer table -> per-layer series -> ranking, GPU metrics through qv2_rank
+    against oracle metrics through the oracle's Algorithm 2.  Identical lists."""
+    cfg_kwargs = cfg_kwargs or {}
+    n_layers = max(it.layer for it in items) + 1
+    g = {k: np.full(n_layers, np.nan) for k in ("w_sqnr", "a_sqnr", "w_mse", "a_mse")}
+    o = {k: np.full(n_layers, np.nan) for k in ("w_sqnr", "a_sqnr", "w_mse", "a_mse")}
+    for t, (it, row) in enumerate(zip(items, oracle_rows)):
+        if it.kind == synth.WEIGHT:
+            g["w_sqnr"][it.layer], g["w_mse"][it.layer] = res.metrics[t]["sqnr_db"], res.metrics[t]["mse"]
+            o["w_sqnr"][it.layer], o["w_mse"][it.layer] = row["w_sqnr"], row["w_mse"]
+        elif it.qrun is not None:
+            g["a_sqnr"][it.layer], g["a_mse"][it.layer] = res.pair_sqnr[t], res.pair_mse[t]
+            o["a_sqnr"][it.layer], o["a_mse"][it.layer] = row["p_sqnr"], row["p_mse"]
+    if np.isnan(g["a_sqnr"]).any():        # a layer without an activation pair: weight series only
+        cfg_kwargs = dict(cfg_kwargs, mse_source=1)
+        for d in (g, o):
+            d["a_sqnr"] = d["a_mse"] = None
+    cfg = qb.qv2_rank_config_default()
+    for k, v in cfg_kwargs.items():
+        setattr(cfg, k, v)
+    order, score = qb.qv2_rank(g["w_sqnr"], g["a_sqnr"], g["w_mse"], g["a_mse"], None, cfg)
+    lst = lambda a: None if a is None else list(a)
+    o_order, o_score = orc.rank_layers(lst(o["w_sqnr"]), lst(o["a_sqnr"]), lst(o["w_mse"]),
+                                       lst(o["a_mse"]), None, orc.RankConfig(**cfg_kwargs))
+    assert order.tolist() == o_order, f"ranking differs:\n gpu    {order.tolist()}\n oracle {o_order}"
+    assert np.allclose(score, o_score, rtol=0, atol=2 * SQNR_ATOL_DB)
+    return order.tolist()

@@ -1,0 +1,209 @@
+"""GPU parity: the HIP library (through the C ABI) against the CPU oracle,
+element by element, on seeded synthetic tensor sets with the paper's model
+shapes plus the edge cases of the method."""
+import numpy as np
+import pytest
+import torch
+
+import harness as H
+from oracle import reference as orc
+from paper_2501_07161_amd import binding as qb
+from paper_2501_07161_amd import synth
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda"
+A, S, C = qb.QV2_ASYM_TENSOR, qb.QV2_SYM_TENSOR, qb.QV2_SYM_CHANNEL
+
+
+def _run_config(specs, rank_kwargs=None):
+    items = H.items_from_specs(specs, DEV)
+    H.attach_pairs(items, specs)
+    res = H.run_gpu(items)
+    rows = H.check_all(items, res)
+    order = H.check_ranking(items, res, rows, rank_kwargs)
+    return items, res, order
+
+
+def test_config_tiny():
+    """Three tensors, per-tensor asymmetric: conv weight, ReLU activation with a pair, fc weight."""
+    items, res, order = _run_config(synth.config_tiny())
+    assert res.plan.num_segments == 3 and sorted(order) == [0, 1]
+    # the activation is post-ReLU: min 0, zero-point at the bottom code
+    assert res.params["min"][1] == 0.0 and res.params["zp"][1] == -128
+
+
+def test_config_resnet18_batch32():
+    """ResNet-18 shapes at the stated batch: 21 weights + 21 activations, per-tensor asymmetric."""
+    items, res, order = _run_config(synth.config_resnet18(32))
+    assert len(order) == 21 and sorted(order) == list(range(21))
+
+
+def test_config_mobilenetv2_per_channel():
+    """MobileNetV2 shapes: per-output-channel symmetric weights with rows of 9 / 27 / ...
+    elements, Laplace + outlier values, ReLU6 activations (batch reduced so the oracle stays fast)."""
+    items, res, order = _run_config(synth.config_mobilenetv2(8))
+    assert len(order) == 53
+    dw = [t for t, it in enumerate(items) if it.name.endswith(".dw.w")]
+    assert dw and all(items[t].x.numel() // items[t].channels == 9 for t in dw)
+
+
+@pytest.mark.parametrize("per_channel", [False, True])
+def test_config_vgg16_weights_full_size(per_channel):
+    """All VGG-16 weights at full size (fc6 = 102.8M elements; per-channel rows of 25088
+    elements span two stream tiles each); activations at batch 2."""
+    _run_config(synth.config_vgg16(2, per_channel))
+
+
+@pytest.mark.parametrize("fused", [False, True])
+def test_config_resnet50_small_batch(fused):
+    """ResNet-50 shapes, per-channel weights (plain and BN-folded variants), batch 4."""
+    items, res, order = _run_config(synth.config_resnet50(4, fused))
+    assert len(order) == 54
+
+
+# ----------------------------------------------------------------------------
+# edge cases
+# ----------------------------------------------------------------------------
+def _rand(n, seed, scale=1.0):
+    g = torch.Generator(device=DEV)
+    g.manual_seed(seed)
+    return torch.randn(n, generator=g, device=DEV) * scale
+
+
+def test_ragged_lengths_and_unaligned_pointers():
+    """Lengths around tile and vector boundaries, inputs starting 4 / 8 / 12 bytes past a
+    16-byte boundary, code buffers starting 1..3 bytes past a 4-byte boundary."""
+    items = []
+    lens = [1, 2, 3, 4, 5, 7, 63, 64, 65, 255, 1023, 1025, 4099, 16383, 16384, 16385, 16387,
+            32768 + 5, 100_003]
+    for i, n in enumerate(lens):
+        for off in range(4):
+            base = _rand(n + 8, 100 + i)
+            x = base[off: off + n]
+            scheme = A if (i + off) % 2 == 0 else S
+            q = (x + 0.01 * _rand(n + 4, 900 + i)[off: off + n]) if off % 2 == 0 else None
+            # a pair whose two tensors have different offsets inside 16 bytes
+            if off == 3:
+                q = (_rand(n + 8, 500 + i)[1: 1 + n])
+            items.append(H.Item(f"len{n}.off{off}", x, scheme, 1, 1, len(items), qrun=q,
+                                codes_offset=(i + off) % 4))
+    res = H.run_gpu(items)
+    H.check_all(items, res)
+
+
+def test_per_channel_row_shapes():
+    """Rows of 1, 3, 9, 27, 64, 65, 576, 8191, 8192 (LDS row groups) and 8193, 20001 (rows cut
+    into stream tiles, unaligned row starts), with unaligned bases and code buffers."""
+    items = []
+    shapes = [(7, 1), (5000, 1), (33, 3), (960, 9), (1100, 9), (64, 27), (10, 64), (10, 65),
+              (37, 576), (3, 8191), (5, 8192), (3, 8193), (4, 20001), (1, 17), (2, 40000)]
+    for i, (c, inner) in enumerate(shapes):
+        for off in (0, 1):
+            base = _rand(c * inner + 4, 200 + i, 0.1)
+            x = base[off: off + c * inner]
+            if i % 3 == 0:
+                x.view(c, inner)[c // 2] = 0.0          # a dead channel
+            items.append(H.Item(f"rows{c}x{inner}.off{off}", x, C, c, 0, len(items),
+                                codes_offset=(i + off) % 4))
+    res = H.run_gpu(items)
+    H.check_all(items, res)
+
+
+def test_degenerate_and_special_values():
+    z = torch.zeros(5000, device=DEV)
+    const = torch.full((4097,), 3.25, device=DEV)
+    neg = -torch.rand(9000, device=DEV) - 0.5
+    negzero = torch.zeros(100, device=DEV)
+    negzero[::2] = -0.0
+    tiny = torch.full((300,), 1e-42, device=DEV)           # sub-normal range -> degenerate step
+    grid = ((torch.arange(-128, 128, device=DEV, dtype=torch.float32) + 3) * 0.0625).repeat(70)
+    big = _rand(20000, 7, 1e30)
+    small = _rand(20000, 8, 1e-30)
+    one = torch.tensor([-2.5], device=DEV)
+    items = []
+    for name, x in [("zeros", z), ("const", const), ("neg", neg), ("negzero", negzero),
+                    ("tiny", tiny), ("grid", grid), ("big", big), ("small", small), ("one", one)]:
+        for scheme in (A, S):
+            items.append(H.Item(f"{name}.{scheme}", x, scheme, 1, 0, len(items), qrun=x.clone()))
+    res = H.run_gpu(items)
+    H.check_all(items, res)
+    t = [i for i, it in enumerate(items) if it.name == "grid.0"][0]
+    assert res.metrics[t]["mse"] == 0.0 and np.isinf(res.metrics[t]["sqnr_db"])   # int8-grid fact
+    assert np.all(res.pair["sum_d2"] == 0.0) and np.all(np.isinf(res.pair_sqnr))   # identical pairs
+
+
+def test_cached_params_clip_both_ends():
+    """Parameters handed in by the caller (the calibration cache) instead of calibrating:
+    a range narrower than the data saturates codes at -128 and 127."""
+    x = _rand(50_000, 11, 2.0)
+    w = _rand(64 * 100, 12, 0.3)
+    items = [H.Item("x", x, A, 1, 1, 0), H.Item("w", w, C, 64, 0, 1)]
+    params = np.zeros(65, qb.QPARAMS)
+    sc, inv, zp = orc.params(-1.0, 2.0, orc.ASYM_TENSOR)
+    params[0] = (-1.0, 2.0, sc, inv, zp, 0)
+    for c in range(64):
+        sc, inv, zp = orc.params(-0.01 * (c + 1), 0.01 * (c + 1), orc.SYM_CHANNEL)
+        params[1 + c] = (-0.01 * (c + 1), 0.01 * (c + 1), sc, inv, zp, 0)
+    res = H.run_gpu(items, params_override=params)
+    for t, it in enumerate(items):
+        xh = it.x.cpu().numpy().reshape(-1)
+        s0 = res.plan.segment_begin[t]
+        S_ = it.channels
+        cal = orc.Calibration(params["min"][s0:s0 + S_], params["max"][s0:s0 + S_],
+                              params["scale"][s0:s0 + S_], params["inv_scale"][s0:s0 + S_],
+                              params["zp"][s0:s0 + S_], None, None,
+                              np.full(S_, xh.size // S_, np.int64))
+        fq = orc.fakequant(xh, cal, it.scheme, it.channels)
+        got = it.codes.cpu().numpy()
+        assert np.array_equal(got, fq.codes)
+        assert got.min() == -128 and got.max() == 127
+        U = res.sums[s0:s0 + S_]
+        assert np.all(np.abs(U["sum_e2"] - fq.sum_e2) <= H.MSE_RTOL * fq.sum_e2)
+        assert np.all(np.abs(U["sum_x2"] - fq.sum_x2) <= H.SX2_RTOL * fq.sum_x2)
+
+
+def test_metrics_only_without_code_buffers():
+    x = _rand(70_001, 13)
+    w = _rand(48 * 27, 14, 0.1)
+    with_codes = [H.Item("x", x, A), H.Item("w", w, C, 48)]
+    without = [H.Item("x", x, A, want_codes=False), H.Item("w", w, C, 48, want_codes=False)]
+    r1, r2 = H.run_gpu(with_codes), H.run_gpu(without)
+    assert r1.sums.tobytes() == r2.sums.tobytes() and r1.params.tobytes() == r2.params.tobytes()
+
+
+def test_bit_stable_across_runs():
+    specs = synth.config_resnet50(2)
+    items = H.items_from_specs(specs, DEV)
+    for it in items:
+        if it.kind == synth.ACTIVATION:
+            it.qrun = it.x + 0.01
+    r1 = H.run_gpu(items)
+    c1 = [it.codes.clone() for it in items]
+    r2 = H.run_gpu(items)
+    assert r1.params.tobytes() == r2.params.tobytes()
+    assert r1.sums.tobytes() == r2.sums.tobytes()
+    assert r1.pair.tobytes() == r2.pair.tobytes()
+    assert all(torch.equal(a, it.codes) for a, it in zip(c1, items))
+
+
+def test_cross_kernel_pair_of_dequantized_equals_fakequant_error():
+    """pair(x, dequant(codes)) must reproduce the fake-quant pass's own noise energy."""
+    x = torch.relu(_rand(300_000, 15, 1.5))
+    it = H.Item("x", x, A)
+    r = H.run_gpu([it])
+    sc, zp = float(r.params["scale"][0]), int(r.params["zp"][0])
+    xhat = torch.from_numpy(orc.dequantize(it.codes.cpu().numpy(), sc, zp)).to(DEV)
+    it2 = H.Item("x", x, A, qrun=xhat)
+    r2 = H.run_gpu([it2])
+    assert abs(r2.pair["sum_d2"][0] - r.sums["sum_e2"][0]) <= 1e-9 * r.sums["sum_e2"][0]
+    assert abs(r2.pair["sum_ref2"][0] - r.sums["sum_x2"][0]) <= 1e-9 * r.sums["sum_x2"][0]
+
+
+def test_non_default_stream():
+    x = _rand(123_457, 16)
+    s = torch.cuda.Stream()
+    it = H.Item("x", x, A, qrun=x * 0.99)
+    torch.cuda.synchronize()
+    with torch.cuda.stream(s):
+        res = H.run_gpu([it])
+    H.check_all([it], res)

@@ -1,0 +1,237 @@
+"""CPU-only tests of the C ABI: the library loads and exports every symbol the
+header declares, the plan builder validates and tiles the layer table, and the
+host functions (finalize, rank) agree with the oracle.  No kernel is launched."""
+import ctypes
+import math
+import os
+import re
+
+import numpy as np
+import pytest
+
+from oracle import reference as orc
+from paper_2501_07161_amd import binding as qb
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+FAKE = 0x7F0000000000          # stands in for a device address; never dereferenced on the host
+
+
+def test_library_exports_every_declared_symbol():
+    hdr = open(os.path.join(ROOT, "include", "qv2.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    declared = set(re.findall(r"\b(qv2_[a-z0-9_]+)\s*\(", hdr))
+    assert {"qv2_calibrate", "qv2_fakequant_metrics", "qv2_pair_metrics", "qv2_rank"} <= declared
+    L = ctypes.CDLL(qb.LIB_PATH)
+    for name in declared:
+        assert hasattr(L, name), name
+    assert declared == set(qb.EXPORTS)
+
+
+def test_struct_layouts_match_header_sizes():
+    assert ctypes.sizeof(qb.qv2_tensor) == 48
+    assert ctypes.sizeof(qb.qv2_rank_config) == 40
+    c = qb.qv2_rank_config_default()
+    assert (c.alpha_w, c.alpha_a, c.mse_factor, c.sqnr_cap_db, c.mse_source) == (0.6, 0.4, 5.0, 200.0, 0)
+
+
+def test_status_strings():
+    for st in range(-7, 1):
+        assert qb.lib().qv2_status_string(st)
+    assert b"unknown" in qb.lib().qv2_status_string(-99)
+
+
+def _row(numel, scheme=qb.QV2_ASYM_TENSOR, channels=1, x=FAKE, qrun=None, codes=None):
+    return qb.TensorArg(x=x, numel=numel, scheme=scheme, channels=channels, qrun=qrun, codes=codes)
+
+
+@pytest.mark.parametrize("row,status", [
+    (_row(0), qb.QV2_ERR_SHAPE),
+    (_row(-5), qb.QV2_ERR_SHAPE),
+    (_row(100, channels=2), qb.QV2_ERR_SHAPE),                       # per-tensor needs channels == 1
+    (_row(100, qb.QV2_SYM_CHANNEL, channels=7), qb.QV2_ERR_SHAPE),   # 7 does not divide 100
+    (_row(100, qb.QV2_SYM_CHANNEL, channels=0), qb.QV2_ERR_SHAPE),
+    (_row(100, scheme=3), qb.QV2_ERR_SCHEME),
+    (_row(100, scheme=-1), qb.QV2_ERR_SCHEME),
+    (_row(100, x=None), qb.QV2_ERR_NULL),
+    (_row(100, x=FAKE + 2), qb.QV2_ERR_ALIGN),
+    (_row(100, qrun=FAKE + 1), qb.QV2_ERR_ALIGN),
+])
+def test_plan_rejects_bad_rows(row, status):
+    with pytest.raises(qb.QV2Error) as e:
+        qb.qv2_plan_create([_row(64), row])
+    assert e.value.status == status
+
+
+def test_plan_rejects_empty_and_null():
+    with pytest.raises(qb.QV2Error) as e:
+        qb.qv2_plan_create([])
+    assert e.value.status == qb.QV2_ERR_SHAPE
+    h = ctypes.c_void_p()
+    assert qb.lib().qv2_plan_create(None, 1, ctypes.byref(h)) == qb.QV2_ERR_NULL
+    arr = (qb.qv2_tensor * 1)()
+    assert qb.lib().qv2_plan_create(arr, 1, None) == qb.QV2_ERR_NULL
+    assert qb.lib().qv2_plan_num_segments(None) == 0
+    qb.lib().qv2_plan_destroy(None)
+
+
+def test_plan_tiling_counts():
+    T = 16384
+    rows = [
+        _row(200_704, qrun=FAKE),                               # 13 stream tiles (12 full + 4096)
+        _row(9408),                                             # 1 stream tile
+        _row(32 * 9, qb.QV2_SYM_CHANNEL, 32),                   # 1 row-group tile of 32 rows
+        _row(4096 * 25088, qb.QV2_SYM_CHANNEL, 4096),           # rows longer than a tile: 2 tiles each
+        _row(2048 * 512, qb.QV2_SYM_CHANNEL, 2048),             # 16 rows per row-group tile -> 128 tiles
+        _row(3000 * 3, qb.QV2_SYM_CHANNEL, 3000),               # at most 1024 rows per tile -> 3 tiles
+    ]
+    p = qb.qv2_plan_create(rows)
+    assert p.num_tensors == 6
+    assert p.num_segments == 1 + 1 + 32 + 4096 + 2048 + 3000
+    assert p.segment_begin == [0, 1, 2, 34, 34 + 4096, 34 + 4096 + 2048]
+    assert p.num_tiles == 13 + 1 + 1 + 4096 * 2 + 128 + 3
+    assert p.num_pair_tiles == 13
+    n_parts = 13 + 1 + 32 + 4096 * 2 + 2048 + 3000
+    assert p.workspace_bytes >= n_parts * 24 and p.workspace_bytes % 256 == 0
+    assert qb.lib().qv2_plan_segment_begin(p.handle, 6) == -1
+    p.close()
+    assert (200_704 + T - 1) // T == 13
+
+
+def test_device_calls_validate_before_touching_the_gpu():
+    p = qb.qv2_plan_create([_row(1000)])
+    L = qb.lib()
+    ws = p.workspace_bytes
+    assert L.qv2_calibrate(p.handle, None, FAKE, FAKE, ws, None) == qb.QV2_ERR_NULL
+    assert L.qv2_calibrate(None, FAKE, FAKE, FAKE, ws, None) == qb.QV2_ERR_NULL
+    assert L.qv2_calibrate(p.handle, FAKE, FAKE, FAKE, ws - 1, None) == qb.QV2_ERR_WORKSPACE
+    assert L.qv2_calibrate(p.handle, FAKE, FAKE, FAKE + 4, ws, None) == qb.QV2_ERR_ALIGN
+    assert L.qv2_fakequant_metrics(p.handle, FAKE, None, FAKE, ws, None) == qb.QV2_ERR_NULL
+    assert L.qv2_fakequant_metrics(p.handle, FAKE, FAKE, None, ws, None) == qb.QV2_ERR_NULL
+    assert L.qv2_pair_metrics(p.handle, None, FAKE, ws, None) == qb.QV2_ERR_NULL
+    assert L.qv2_pair_metrics(p.handle, FAKE, FAKE, 0, None) == qb.QV2_ERR_WORKSPACE
+
+
+# ----------------------------------------------------------------------------
+# finalize (Eq. 6-7) against the oracle on oracle-made sums
+# ----------------------------------------------------------------------------
+def test_finalize_matches_oracle():
+    rng = np.random.default_rng(0)
+    a = np.maximum(rng.standard_normal(5000) * 1.7, 0).astype(np.float32)
+    w = rng.laplace(0, 0.05, (16, 27)).astype(np.float32)
+    p = qb.qv2_plan_create([_row(a.size), _row(w.size, qb.QV2_SYM_CHANNEL, 16)])
+    params = np.zeros(p.num_segments, qb.QPARAMS)
+    sums = np.zeros(p.num_segments, qb.SUMS)
+    want = []
+    for t, (x, scheme, ch) in enumerate([(a, orc.ASYM_TENSOR, 1), (w, orc.SYM_CHANNEL, 16)]):
+        cal = orc.calibrate(x, scheme, ch)
+        fq = orc.fakequant(x, cal, scheme, ch)
+        s0 = p.segment_begin[t]
+        sl = slice(s0, s0 + ch)
+        params["min"][sl], params["max"][sl] = cal.min, cal.max
+        params["scale"][sl], params["inv_scale"][sl], params["zp"][sl] = cal.scale, cal.inv_scale, cal.zp
+        sums["sum_x"][sl], sums["sum_x2"][sl], sums["sum_e2"][sl], sums["n"][sl] = \
+            cal.sum_x, fq.sum_x2, fq.sum_e2, cal.n
+        want.append(orc.tensor_metrics(x, cal, fq))
+    got = qb.qv2_finalize(p, params, sums)
+    for g, m in zip(got, want):
+        assert g["mse"] == pytest.approx(m.mse, rel=1e-13)
+        assert g["sqnr_db"] == pytest.approx(m.sqnr_db, abs=1e-10)
+        assert g["mean"] == pytest.approx(m.mean, rel=1e-12, abs=1e-15)
+        assert g["var"] == pytest.approx(m.var, rel=1e-9)
+        assert g["absmax"] == np.float32(m.absmax) and g["min"] == np.float32(m.min)
+        assert g["max"] == np.float32(m.max)
+    # zero noise -> +inf dB; non-finite sums are reported
+    sums["sum_e2"][:] = 0.0
+    assert np.all(np.isinf(qb.qv2_finalize(p, params, sums)["sqnr_db"]))
+    sums["sum_x2"][0] = np.nan
+    with pytest.raises(qb.QV2Error) as e:
+        qb.qv2_finalize(p, params, sums)
+    assert e.value.status == qb.QV2_ERR_NONFINITE
+
+
+def test_pair_finalize():
+    rec = np.zeros(3, qb.PAIR_SUMS)
+    rec["sum_ref2"], rec["sum_d2"], rec["n"] = [100.0, 4.0, 0.0], [1.0, 0.0, 0.0], [10, 4, 0]
+    mse, sqnr = qb.qv2_pair_finalize(rec)
+    assert mse.tolist() == [0.1, 0.0, 0.0]
+    assert sqnr[0] == pytest.approx(20.0) and math.isinf(sqnr[1]) and math.isinf(sqnr[2])
+
+
+# ----------------------------------------------------------------------------
+# rank (Eq. 16, Algorithm 2): identical to the oracle's list
+# ----------------------------------------------------------------------------
+def _cfg(**kw):
+    c = qb.qv2_rank_config_default()
+    for k, v in kw.items():
+        setattr(c, k, v)
+    return c
+
+
+def test_rank_identical_to_oracle_random():
+    rng = np.random.default_rng(21)
+    for trial in range(300):
+        n = int(rng.integers(1, 130))
+        w = rng.uniform(10, 60, n)
+        a = rng.uniform(10, 60, n)
+        if trial % 3 == 0:                            # ties in the scores
+            w, a = w.round(0), a.round(0)
+        if trial % 7 == 0:
+            w[rng.integers(0, n)] = math.inf
+            a[rng.integers(0, n)] = -math.inf
+        wm = rng.lognormal(0, 2.0, n)
+        am = rng.lognormal(0, 2.0, n)
+        if trial % 5 == 0:
+            am[:] = am.round(0)                       # ties among outliers
+        pos = None if trial % 2 else np.cumsum(rng.integers(1, 5, n)).astype(np.int32)
+        src = trial % 3
+        kw = dict(alpha_w=float(rng.uniform(0, 1)), alpha_a=float(rng.uniform(0, 1)),
+                  mse_source=src, mse_factor=float(rng.choice([5.0, 2.0])))
+        order, score = qb.qv2_rank(w, a, wm, am, pos, _cfg(**kw))
+        o_order, o_score = orc.rank_layers(list(w), list(a), list(wm), list(am),
+                                           None if pos is None else list(pos), orc.RankConfig(**kw))
+        assert order.tolist() == o_order
+        assert score.tolist() == o_score
+
+
+def test_rank_defaults_and_optional_series():
+    w = [40.0, 38.0, 45.0, 30.0, 31.0, 50.0]
+    a = [30.0] * 6
+    m = [1.0] * 6
+    order, score = qb.qv2_rank(w, a, m, m)
+    assert order.tolist() == [3, 1, 0, 4, 2, 5]
+    order, _ = qb.qv2_rank(w, None, None, m)
+    assert order.tolist() == [3, 1, 0, 4, 2, 5]
+    order, _ = qb.qv2_rank(None, w, None, m)
+    assert order.tolist() == [3, 1, 0, 4, 2, 5]
+
+
+def test_rank_errors():
+    w = [40.0, 38.0, 45.0]
+    m = [1.0, 1.0, 1.0]
+    L = qb.lib()
+    with pytest.raises(qb.QV2Error) as e:
+        qb.qv2_rank(w, w, m, [1.0, math.nan, 1.0])
+    assert e.value.status == qb.QV2_ERR_NONFINITE
+    with pytest.raises(qb.QV2Error) as e:
+        qb.qv2_rank(w, w, m, [1.0, -1.0, 1.0])
+    assert e.value.status == qb.QV2_ERR_NONFINITE
+    with pytest.raises(qb.QV2Error) as e:
+        qb.qv2_rank([1.0, math.nan, 2.0], w, m, m)
+    assert e.value.status == qb.QV2_ERR_NONFINITE
+    with pytest.raises(qb.QV2Error) as e:
+        qb.qv2_rank(w, w, m, m, layer_pos=[0, 2, 2])
+    assert e.value.status == qb.QV2_ERR_SHAPE
+    with pytest.raises(qb.QV2Error) as e:
+        qb.qv2_rank(w, w, m, None)                    # default source is the activation MSE
+    assert e.value.status == qb.QV2_ERR_NULL
+    with pytest.raises(qb.QV2Error) as e:
+        qb.qv2_rank(w, w, m, m, cfg=_cfg(mse_source=3))
+    assert e.value.status == qb.QV2_ERR_SHAPE
+    order = np.zeros(3, np.int32)
+    arr = np.array(w)
+    assert L.qv2_rank(arr.ctypes.data, None, None, arr.ctypes.data, None, 0, None,
+                      order.ctypes.data, None) == qb.QV2_ERR_SHAPE
+    assert L.qv2_rank(None, None, None, arr.ctypes.data, None, 3, None,
+                      order.ctypes.data, None) == qb.QV2_ERR_NULL
+    assert L.qv2_rank(arr.ctypes.data, None, None, arr.ctypes.data, None, 3, None,
+                      None, None) == qb.QV2_ERR_NULL
