@@ -45,7 +45,10 @@ def parse():
     ap.add_argument("--batch", type=int, default=None, help="override the workload's batch (smaller = not the headline config)")
     ap.add_argument("--fused", action="store_true", help="BN-folded weight variant of resnet50")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-sample-elems", type=int, default=600_000_000)
+    ap.add_argument("--cpu-sample-elems", type=int, default=2_000_000_000)
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="after the timed region also run 3 plain 1 GiB device copies (a kernel of known "
+                         "traffic, used to scale rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
     return ap.parse_args()
 
 
@@ -167,6 +170,14 @@ def main():
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     ms_per_step = dt / args.steps * 1e3
+
+    if args.copy_probe:
+        src = torch.ones(1 << 28, dtype=torch.float32, device=dev)      # 1 GiB
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     ms_cal = float(np.mean([e[0].elapsed_time(e[1]) for e in ev]))
     ms_fq = float(np.mean([e[1].elapsed_time(e[2]) for e in ev]))

@@ -14,7 +14,8 @@ from typing import List, Optional, Sequence
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libqv2.so")
+# QV2_LIB_PATH selects another build of the same library (tuning variants).
+LIB_PATH = os.environ.get("QV2_LIB_PATH") or os.path.join(_HERE, "libqv2.so")
 
 QV2_OK = 0
 QV2_ERR_NULL, QV2_ERR_SHAPE, QV2_ERR_SCHEME, QV2_ERR_WORKSPACE = -1, -2, -3, -4

@@ -19,13 +19,14 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
          "-Wall", "-Wno-unused-command-line-argument"]
 
 
-def build_lib(verbose: bool = False) -> str:
-    cmd = ["hipcc", *FLAGS, "-I", os.path.join(ROOT, "include"), "-I", CSRC,
-           "-x", "hip", *SOURCES, "-o", LIB]
+def build_lib(verbose: bool = False, defines=(), out: str = LIB) -> str:
+    """defines: extra -D options (tuning knobs QV2_UNROLL, QV2_NT_LOADS, QV2_BLOCK)."""
+    cmd = ["hipcc", *FLAGS, *[f"-D{d}" for d in defines], "-I", os.path.join(ROOT, "include"),
+           "-I", CSRC, "-x", "hip", *SOURCES, "-o", out]
     if verbose:
         print(" ".join(cmd), flush=True)
     subprocess.run(cmd, check=True)
-    return LIB
+    return out
 
 
 if __name__ == "__main__":

@@ -128,6 +128,10 @@ qv2_status qv2_plan_create(const qv2_tensor* h_tensors, int32_t n_tensors, qv2_p
       static_cast<int64_t>(p->tiles.size() + row_tiles.size()) > kMax) err = QV2_ERR_SHAPE;
   if (err != QV2_OK) { delete p; return err; }
 
+  for (size_t i = 0; i < p->segments.size(); ++i)
+    if (p->segments[i].nparts > qv2::kFoldWaveMax) p->big_segments.push_back(static_cast<int32_t>(i));
+  for (size_t i = 0; i < p->pair_tensors.size(); ++i)
+    if (p->pair_tensors[i].nparts > qv2::kFoldWaveMax) p->big_pair_tensors.push_back(static_cast<int32_t>(i));
   p->n_stream_tiles = static_cast<int64_t>(p->tiles.size());
   p->tiles.insert(p->tiles.end(), row_tiles.begin(), row_tiles.end());
   p->n_parts = n_parts;

@@ -8,14 +8,20 @@
 
 namespace qv2 {
 
-// Threads per workgroup of every tile kernel (4 wavefronts of 64).
-constexpr int kBlock = 256;
+// Threads per workgroup of every tile kernel (8 wavefronts of 64).
+#ifndef QV2_BLOCK
+#define QV2_BLOCK 512
+#endif
+constexpr int kBlock = QV2_BLOCK;
 // Largest row-group tile in elements: it is staged whole in LDS (32 KiB).
 constexpr int kRowGroupCap = 8192;
 // Most rows one row-group tile may hold.
 constexpr int kRowGroupMaxRows = 1024;
-// Default stream-tile length in elements (64 KiB of fp32).
-constexpr int kDefaultTile = 16384;
+// Default stream-tile length in elements (128 KiB of fp32).
+constexpr int kDefaultTile = 32768;
+// A segment (or pair tensor) with more partials than this is folded by a whole
+// 1024-thread workgroup instead of one wavefront.
+constexpr int kFoldWaveMax = 128;
 
 struct TensorDesc {            // 48 B, device copy indexed by tensor
   const float* x;
@@ -69,6 +75,8 @@ struct qv2_plan {
   std::vector<qv2::Segment> segments;
   std::vector<qv2::Tile> pair_tiles;     // stream tiles over tensors with qrun
   std::vector<qv2::PairTensor> pair_tensors;
+  std::vector<int32_t> big_segments;      // segments with > kFoldWaveMax partials
+  std::vector<int32_t> big_pair_tensors;  // pair tensors with > kFoldWaveMax partials
   int64_t n_stream_tiles = 0;
   int64_t n_parts = 0;
   int32_t tile_elems = qv2::kDefaultTile;
@@ -81,4 +89,6 @@ struct qv2_plan {
   qv2::Segment* d_segments = nullptr;
   qv2::Tile* d_pair_tiles = nullptr;
   qv2::PairTensor* d_pair_tensors = nullptr;
+  int32_t* d_big_segments = nullptr;
+  int32_t* d_big_pair_tensors = nullptr;
 };

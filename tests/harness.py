@@ -77,8 +77,12 @@ def attach_pairs(items: List[Item], specs: List[synth.TensorSpec]):
         cal = orc.calibrate(x, it.scheme, it.channels)
         fq = orc.fakequant(x, cal, it.scheme, it.channels, keep_xhat=True)
         noise = synth.unit_noise(sp, it.x.device).cpu().numpy().reshape(-1)
-        sigma = np.float32(0.01 * float(np.std(x.astype(np.float64))))
-        return (fq.xhat + sigma * noise).astype(np.float32)
+        sigma = np.float32(0.01 * float(np.std(x, dtype=np.float64)))
+        noise *= sigma
+        noise += fq.xhat
+        fq.xhat = None
+        it._oracle = (cal, fq)             # reused by check_item: same oracle, same input bytes
+        return noise
     with ThreadPoolExecutor(workers()) as ex:
         res = list(ex.map(one, range(len(items))))
     for it, q in zip(items, res):
@@ -124,8 +128,11 @@ def _rel(a, b):
 def check_item(t: int, it: Item, res: GpuResult, check_codes: bool = True, cal=None):
     """Element-by-element comparison of one tensor against the oracle."""
     x = it.x.detach().cpu().numpy().reshape(-1)
-    cal = cal or orc.calibrate(x, it.scheme, it.channels)
-    fq = orc.fakequant(x, cal, it.scheme, it.channels)
+    if cal is None and getattr(it, "_oracle", None) is not None:
+        cal, fq = it._oracle
+    else:
+        cal = cal or orc.calibrate(x, it.scheme, it.channels)
+        fq = orc.fakequant(x, cal, it.scheme, it.channels)
     s0 = res.plan.segment_begin[t]
     S = it.channels if it.scheme == qb.QV2_SYM_CHANNEL else 1
     P, U = res.params[s0:s0 + S], res.sums[s0:s0 + S]

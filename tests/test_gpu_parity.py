@@ -75,7 +75,7 @@ def test_ragged_lengths_and_unaligned_pointers():
     16-byte boundary, code buffers starting 1..3 bytes past a 4-byte boundary."""
     items = []
     lens = [1, 2, 3, 4, 5, 7, 63, 64, 65, 255, 1023, 1025, 4099, 16383, 16384, 16385, 16387,
-            32768 + 5, 100_003]
+            32767, 32768, 32769, 65536 + 5, 100_003]
     for i, n in enumerate(lens):
         for off in range(4):
             base = _rand(n + 8, 100 + i)
@@ -92,11 +92,12 @@ def test_ragged_lengths_and_unaligned_pointers():
 
 
 def test_per_channel_row_shapes():
-    """Rows of 1, 3, 9, 27, 64, 65, 576, 8191, 8192 (LDS row groups) and 8193, 20001 (rows cut
-    into stream tiles, unaligned row starts), with unaligned bases and code buffers."""
+    """Rows of 1, 3, 9, 27, 64, 65, 576, 8191, 8192 (LDS row groups) and 8193, 20001, 40000,
+    70001 (rows as one or several stream tiles, unaligned row starts), with unaligned bases and
+    code buffers."""
     items = []
     shapes = [(7, 1), (5000, 1), (33, 3), (960, 9), (1100, 9), (64, 27), (10, 64), (10, 65),
-              (37, 576), (3, 8191), (5, 8192), (3, 8193), (4, 20001), (1, 17), (2, 40000)]
+              (37, 576), (3, 8191), (5, 8192), (3, 8193), (4, 20001), (1, 17), (2, 40000), (3, 70001)]
     for i, (c, inner) in enumerate(shapes):
         for off in (0, 1):
             base = _rand(c * inner + 4, 200 + i, 0.1)

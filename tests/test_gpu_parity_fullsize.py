@@ -1,0 +1,29 @@
+"""Full-size parity in the launch configuration the benchmark times: the ResNet-50 v1
+batch-256 set (54 per-channel weights, 54 activations of 10.8 GB with oracle-made
+quantized-run partners) goes through ONE plan, as in bench.py, and every tensor is
+compared with the CPU oracle: parameters and all 2.7 G int8 codes bit-exact, sums, MSE,
+SQNR and the ranking to the stated bar.  The oracle runs on the host cores in a thread
+pool (one tensor per call), which takes about a minute."""
+import pytest
+import torch
+
+import harness as H
+from paper_2501_07161_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+
+def test_resnet50_batch256_full_pass():
+    specs = synth.config_resnet50(256)
+    items = H.items_from_specs(specs, "cuda")
+    print("oracle: calibrate + fake-quant + quantized-run partners ...", flush=True)
+    H.attach_pairs(items, specs)
+    print("gpu pass ...", flush=True)
+    res = H.run_gpu(items)
+    assert res.plan.num_tensors == 108
+    print("compare ...", flush=True)
+    rows = H.check_all(items, res)
+    order = H.check_ranking(items, res, rows)
+    assert sorted(order) == list(range(54))
+    del items
+    torch.cuda.empty_cache()
