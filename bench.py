@@ -32,8 +32,8 @@ HBM_PEAK_GBPS = 8000.0   # MI355X published HBM3E bandwidth
 
 # HBM bytes per k_pair_stream launch on the resnet50 b256 workload from rocprofv3 --pmc
 # (FETCH_SIZE and WRITE_SIZE runs, each scaled by a copy kernel of known size); see
-# profiles/.  None until measured.
-PAIR_KERNEL_TRAFFIC_BYTES = None
+# profiles/sensitivity_pass_resnet50_b256.txt.
+PAIR_KERNEL_TRAFFIC_BYTES = 21_697_385_665
 
 
 def parse():

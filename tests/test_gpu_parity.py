@@ -50,7 +50,7 @@ def test_config_mobilenetv2_per_channel():
 @pytest.mark.parametrize("per_channel", [False, True])
 def test_config_vgg16_weights_full_size(per_channel):
     """All VGG-16 weights at full size (fc6 = 102.8M elements; per-channel rows of 25088
-    elements span two stream tiles each); activations at batch 2."""
+    elements are one stream tile each); activations at batch 2."""
     _run_config(synth.config_vgg16(2, per_channel))
 
 
