@@ -12,9 +12,13 @@ Workload at N=1: ResNet-50 v1 shapes, batch 256, 224x224 (54 weights,
 per-output-channel symmetric; 54 activations with their quantized-run partners,
 per-tensor asymmetric).
 
-Prints ONE JSON line.  `value` is algorithmic bytes per pass / time per pass:
-4 B/element for calibrate, 5 for fake-quant (4 read + 1 code written), 8 for the
-pair metrics, i.e. 9 B per weight element and 17 B per activation element.
+Prints ONE JSON line.  `value` is algorithmic bytes per pass / time per pass with
+the fixed per-call numerators: 4 B/element for calibrate, 5 for fake-quant (4 read
++ 1 code written), 8 for the pair metrics, i.e. 9 B per weight element and 17 B
+per activation element.  The default pass uses the fused fake-quant + pair call,
+which computes the same results while moving 13 B per activation element; the
+JSON also carries `hbm_GBps` (bytes the pass actually has to move / time) and the
+timing of the pass made of the three separate calls.
 """
 from __future__ import annotations
 
@@ -30,10 +34,10 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBPS = 8000.0   # MI355X published HBM3E bandwidth
 
-# HBM bytes per k_pair_stream launch on the resnet50 b256 workload from rocprofv3 --pmc
-# (FETCH_SIZE and WRITE_SIZE runs, each scaled by a copy kernel of known size); see
+# HBM bytes per launch of the dominant kernel on the resnet50 b256 workload from rocprofv3
+# --pmc (FETCH_SIZE and WRITE_SIZE runs, each scaled by a copy kernel of known size); see
 # profiles/sensitivity_pass_resnet50_b256.txt.
-PAIR_KERNEL_TRAFFIC_BYTES = 21_697_385_665
+TRAFFIC_BYTES = {"k_pair_stream": 21_697_385_665, "k_quantpair_stream": None}
 
 
 def parse():
@@ -44,6 +48,10 @@ def parse():
     ap.add_argument("--workload", default="resnet50", choices=["resnet50", "resnet18", "vgg16", "mobilenetv2"])
     ap.add_argument("--batch", type=int, default=None, help="override the workload's batch (smaller = not the headline config)")
     ap.add_argument("--fused", action="store_true", help="BN-folded weight variant of resnet50")
+    ap.add_argument("--mode", default="fused", choices=["fused", "calls"],
+                    help="fused: calibrate + fused fake-quant/pair call (default); "
+                         "calls: calibrate, fake-quant and pair as three calls")
+    ap.add_argument("--single-mode", action="store_true", help="do not also time the other mode")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-elems", type=int, default=2_000_000_000)
     ap.add_argument("--copy-probe", action="store_true",
@@ -122,6 +130,7 @@ def main():
     n_a = sum(s.numel for s in specs if s.kind == synth.ACTIVATION)
     n_pair = sum(s.numel for s, q in zip(specs, qruns) if q is not None)
     n_all = n_w + n_a
+    n_rowgroup = sum(s.numel for s in specs if s.scheme == synth.SYM_CHANNEL and s.numel // s.channels <= 8192)
     bytes_cal, bytes_fq, bytes_pair = 4 * n_all, 5 * n_all, 8 * n_pair
     bytes_pass = bytes_cal + bytes_fq + bytes_pair
 
@@ -133,25 +142,30 @@ def main():
     h_params = torch.empty(buf.params.shape, dtype=torch.uint8, pin_memory=True)
     h_sums = torch.empty(buf.sums.shape, dtype=torch.uint8, pin_memory=True)
     h_pair = torch.empty(buf.pair.shape, dtype=torch.uint8, pin_memory=True)
-    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
     last = {}
 
-    def step(events=None):
+    def step(mode, events=None):
         if events:
             events[0].record()
         qb.qv2_calibrate(plan, buf.params, buf.sums, buf.workspace)
         if events:
             events[1].record()
-        qb.qv2_fakequant_metrics(plan, buf.params, buf.sums, buf.workspace)
-        if events:
-            events[2].record()
-        qb.qv2_pair_metrics(plan, buf.pair, buf.workspace)
+        if mode == "fused":
+            qb.qv2_fakequant_pair_metrics(plan, buf.params, buf.sums, buf.pair, buf.workspace)
+        else:
+            qb.qv2_fakequant_metrics(plan, buf.params, buf.sums, buf.workspace)
+            if events:
+                events[2].record()
+            qb.qv2_pair_metrics(plan, buf.pair, buf.workspace)
         if events:
             events[3].record()
         h_params.copy_(buf.params, non_blocking=True)
         h_sums.copy_(buf.sums, non_blocking=True)
         h_pair.copy_(buf.pair, non_blocking=True)
         torch.cuda.current_stream().synchronize()
+        if events:       # per-kernel durations from the library's HIP events on the same stream
+            for name in kernel_ms:
+                kernel_ms[name].append(qb.qv2_plan_kernel_ms(plan, name))
         met = qb.qv2_finalize(plan, h_params.numpy().view(qb.QPARAMS), h_sums.numpy().view(qb.SUMS))
         pmse, psqnr = qb.qv2_pair_finalize(h_pair.numpy().view(qb.PAIR_SUMS))
         w_sqnr = np.empty(n_layers); w_mse = np.empty(n_layers)
@@ -161,15 +175,35 @@ def main():
         order, score = qb.qv2_rank(w_sqnr, a_sqnr, w_mse, a_mse)
         last.update(order=order, score=score, met=met)
 
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for k in range(args.steps):
-        step(ev[k])
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
-    ms_per_step = dt / args.steps * 1e3
+    kernel_ms = {}
+    qb.qv2_plan_set_timing(plan, True)
+
+    def timed(mode):
+        ev = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
+        kernel_ms.clear()
+        names = ["k_stats_stream", "k_stats_rows"] + (["k_quantpair_stream", "k_quantpair_rows"] if mode == "fused"
+                                                      else ["k_quant_stream", "k_quant_rows", "k_pair_stream"])
+        kernel_ms.update({n: [] for n in names})
+        for _ in range(args.warmup):
+            step(mode)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for k in range(args.steps):
+            step(mode, ev[k])
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        r = {"ms_per_step": dt / args.steps * 1e3, "order": last["order"].tolist(),
+             "kernels_ms": {n: round(float(np.mean(v)), 4) for n, v in kernel_ms.items()},
+             "ms_cal": float(np.mean([e[0].elapsed_time(e[1]) for e in ev]))}
+        if mode == "fused":
+            r["ms_fqpair"] = float(np.mean([e[1].elapsed_time(e[3]) for e in ev]))
+        else:
+            r["ms_fq"] = float(np.mean([e[1].elapsed_time(e[2]) for e in ev]))
+            r["ms_pair"] = float(np.mean([e[2].elapsed_time(e[3]) for e in ev]))
+        return r
+
+    main_r = timed(args.mode)
+    other = None if args.single_mode else timed("calls" if args.mode == "fused" else "fused")
 
     if args.copy_probe:
         src = torch.ones(1 << 28, dtype=torch.float32, device=dev)      # 1 GiB
@@ -179,11 +213,30 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
-    ms_cal = float(np.mean([e[0].elapsed_time(e[1]) for e in ev]))
-    ms_fq = float(np.mean([e[1].elapsed_time(e[2]) for e in ev]))
-    ms_pair = float(np.mean([e[2].elapsed_time(e[3]) for e in ev]))
-    value = bytes_pass / (dt / args.steps) / 1e9
-    pair_gbps = bytes_pair / (ms_pair * 1e-3) / 1e9
+    ms_per_step = main_r["ms_per_step"]
+    value = bytes_pass / (ms_per_step * 1e-3) / 1e9
+    # bytes the executed pass has to move: the fused call reads x once for steps a3 + a4
+    bytes_fqpair = 5 * n_all + 4 * n_pair
+    moved = bytes_cal + (bytes_fqpair if args.mode == "fused" else bytes_fq + bytes_pair)
+    headline = args.workload == "resnet50" and batch == 256 and not args.fused
+
+    def calls_of(r):
+        c = {"calibrate": {"ms": round(r["ms_cal"], 4), "GBps": round(bytes_cal / r["ms_cal"] / 1e6, 1)}}
+        if "ms_fqpair" in r:
+            c["fakequant_pair_metrics"] = {"ms": round(r["ms_fqpair"], 4), "moved_bytes": bytes_fqpair,
+                                           "GBps": round(bytes_fqpair / r["ms_fqpair"] / 1e6, 1)}
+        else:
+            c["fakequant_metrics"] = {"ms": round(r["ms_fq"], 4), "GBps": round(bytes_fq / r["ms_fq"] / 1e6, 1)}
+            c["pair_metrics"] = {"ms": round(r["ms_pair"], 4), "GBps": round(bytes_pair / r["ms_pair"] / 1e6, 1)}
+        return c
+
+    # dominant kernel: its own algorithmic bytes over its own HIP-event duration
+    if args.mode == "fused":
+        kname, kbytes = "k_quantpair_stream", bytes_fqpair - 5 * n_rowgroup
+    else:
+        kname, kbytes = "k_pair_stream", bytes_pair
+    kms = main_r["kernels_ms"][kname]
+    k_gbps = kbytes / (kms * 1e-3) / 1e9
 
     out = {
         "metric": "sensitivity_pass_GBps", "value": round(value, 2), "unit": "GB/s",
@@ -191,21 +244,28 @@ def main():
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"{args.workload}_b{batch}" + ("_bnfold" if args.fused else ""),
+                   "pass": "calibrate + fused fakequant/pair + finalize + rank" if args.mode == "fused"
+                           else "calibrate + fakequant + pair + finalize + rank",
                    "tensors": len(specs), "layers": n_layers, "weight_elements": n_w,
-                   "activation_elements": n_a, "schemes": "weights per-channel symmetric int8, "
-                   "activations per-tensor asymmetric int8" if args.workload != "resnet18" else "per-tensor asymmetric int8",
-                   "algorithmic_bytes_per_pass": bytes_pass},
-        "frac_of_hbm_peak": round(value / HBM_PEAK_GBPS, 4),
-        "layers_per_s": round(n_layers / (dt / args.steps), 1),
-        "calls": {"calibrate": {"ms": round(ms_cal, 4), "GBps": round(bytes_cal / ms_cal / 1e6, 1)},
-                  "fakequant_metrics": {"ms": round(ms_fq, 4), "GBps": round(bytes_fq / ms_fq / 1e6, 1)},
-                  "pair_metrics": {"ms": round(ms_pair, 4), "GBps": round(pair_gbps, 1)}},
-        "roofline": {"bound": "hbm", "kernel": "k_pair_stream", "achieved": round(pair_gbps, 1),
-                     "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(pair_gbps / HBM_PEAK_GBPS, 4),
-                     "traffic": PAIR_KERNEL_TRAFFIC_BYTES,
-                     "algorithmic_bytes_per_launch": bytes_pair, "avg_launch_ms": round(ms_pair, 4)},
+                   "activation_elements": n_a, "algorithmic_bytes_per_pass": bytes_pass,
+                   "moved_bytes_per_pass": moved},
+        "hbm_GBps": round(moved / (ms_per_step * 1e-3) / 1e9, 2),
+        "frac_of_hbm_peak": round(moved / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
+        "layers_per_s": round(n_layers / (ms_per_step * 1e-3), 1),
+        "calls": calls_of(main_r), "kernels_ms": main_r["kernels_ms"],
+        "roofline": {"bound": "hbm", "kernel": kname, "achieved": round(k_gbps, 1),
+                     "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(k_gbps / HBM_PEAK_GBPS, 4),
+                     "traffic": TRAFFIC_BYTES.get(kname) if headline else None,
+                     "algorithmic_bytes_per_launch": kbytes, "avg_launch_ms": round(kms, 4)},
         "min_adjacent_score_gap": float(np.min(np.diff(np.sort(last["score"])))) if n_layers > 1 else None,
     }
+    if other is not None:
+        o_bytes = bytes_cal + (bytes_fq + bytes_pair if args.mode == "fused" else bytes_fqpair)
+        out["other_pass"] = {"pass": "three separate calls" if args.mode == "fused" else "fused",
+                             "ms_per_step": round(other["ms_per_step"], 4),
+                             "value": round(bytes_pass / other["ms_per_step"] / 1e6, 2),
+                             "hbm_GBps": round(o_bytes / other["ms_per_step"] / 1e6, 2),
+                             "calls": calls_of(other), "kernels_ms": other["kernels_ms"], "same_order": other["order"] == main_r["order"]}
 
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(specs, xs, qruns, args.cpu_sample_elems)

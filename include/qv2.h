@@ -153,6 +153,18 @@ int64_t qv2_plan_num_pair_tiles(const qv2_plan* plan);
  * aligned base).  Calls that may overlap in time need separate workspaces. */
 size_t qv2_workspace_bytes(const qv2_plan* plan);
 
+/* Optional timing of the tile kernels (for benchmarks).  When enabled, every
+ * launch of a tile kernel is bracketed by two HIP events on the call's stream;
+ * after the stream has been synchronised qv2_plan_kernel_ms returns the duration
+ * of the most recent launch of that kernel (0 if it has not run).  Enabling
+ * creates the events (the only allocation outside the first-use table upload). */
+typedef enum {
+  QV2_K_STATS_STREAM = 0, QV2_K_STATS_ROWS = 1, QV2_K_QUANT_STREAM = 2, QV2_K_QUANT_ROWS = 3,
+  QV2_K_PAIR_STREAM = 4, QV2_K_QUANTPAIR_STREAM = 5, QV2_K_QUANTPAIR_ROWS = 6, QV2_K_COUNT = 7
+} qv2_kernel_id;
+qv2_status qv2_plan_set_timing(qv2_plan* plan, int32_t enable);
+qv2_status qv2_plan_kernel_ms(const qv2_plan* plan, int32_t kernel, float* ms_out);
+
 /* ---- device passes ------------------------------------------------------- */
 
 /* Step 1-2 (Sec. 4; Sec. 5 calibration stage; Eq. 2, Eq. 4): per segment
@@ -173,6 +185,19 @@ qv2_status qv2_fakequant_metrics(qv2_plan* plan, const qv2_qparams* d_params, qv
  * sum x^2 and sum (x - qrun)^2.  d_pair_sums[num_tensors]: DEVICE, written. */
 qv2_status qv2_pair_metrics(qv2_plan* plan, qv2_pair_sums* d_pair_sums,
                             void* d_workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Steps 2-3 in one sweep: the result of qv2_fakequant_metrics followed by
+ * qv2_pair_metrics, with every tensor read from HBM once instead of twice
+ * (per element 4 B x + 4 B qrun read, 1 B code written, instead of 5 + 8 B).
+ * Both comparisons of step 3 (tensor vs its dequantized form, Eq. 6-7; fp32-run
+ * vs quantized-run output, Algorithm 2) are taken in the same visit of x.
+ * Arguments as in the two separate calls.  Codes, sum_x2 and sum_e2 are
+ * bit-identical to qv2_fakequant_metrics; the pair sums are bit-identical to
+ * qv2_pair_metrics for per-tensor-scheme tensors whose x and qrun share their
+ * offset within 16 bytes, and equal up to fp64 summation order otherwise. */
+qv2_status qv2_fakequant_pair_metrics(qv2_plan* plan, const qv2_qparams* d_params,
+                                      qv2_sums* d_sums, qv2_pair_sums* d_pair_sums,
+                                      void* d_workspace, size_t workspace_bytes, void* hip_stream);
 
 /* ---- host finalize and ranking (need no GPU) ----------------------------- */
 

@@ -26,6 +26,7 @@ EXPORTS = (
     "qv2_plan_create", "qv2_plan_destroy", "qv2_plan_num_tensors", "qv2_plan_num_segments",
     "qv2_plan_segment_begin", "qv2_plan_num_tiles", "qv2_plan_num_pair_tiles",
     "qv2_workspace_bytes", "qv2_calibrate", "qv2_fakequant_metrics", "qv2_pair_metrics",
+    "qv2_fakequant_pair_metrics", "qv2_plan_set_timing", "qv2_plan_kernel_ms",
     "qv2_finalize", "qv2_pair_finalize", "qv2_rank_config_default", "qv2_rank",
     "qv2_status_string",
 )
@@ -88,6 +89,9 @@ def lib():
         L.qv2_calibrate.argtypes = [vp, vp, vp, vp, sz, vp]
         L.qv2_fakequant_metrics.argtypes = [vp, vp, vp, vp, sz, vp]
         L.qv2_pair_metrics.argtypes = [vp, vp, vp, sz, vp]
+        L.qv2_fakequant_pair_metrics.argtypes = [vp, vp, vp, vp, vp, sz, vp]
+        L.qv2_plan_set_timing.argtypes = [vp, i32]
+        L.qv2_plan_kernel_ms.argtypes = [vp, i32, ctypes.POINTER(ctypes.c_float)]
         L.qv2_finalize.argtypes = [vp, vp, vp, vp]
         L.qv2_pair_finalize.argtypes = [vp, i32, vp, vp]
         L.qv2_rank_config_default.argtypes = [ctypes.POINTER(qv2_rank_config)]
@@ -175,6 +179,22 @@ def qv2_plan_create(rows: Sequence[TensorArg]) -> Plan:
     return Plan(h.value, rows)
 
 
+KERNEL_IDS = {"k_stats_stream": 0, "k_stats_rows": 1, "k_quant_stream": 2, "k_quant_rows": 3,
+              "k_pair_stream": 4, "k_quantpair_stream": 5, "k_quantpair_rows": 6}
+
+
+def qv2_plan_set_timing(plan: Plan, enable: bool):
+    _check(lib().qv2_plan_set_timing(plan.handle, int(bool(enable))), "qv2_plan_set_timing")
+
+
+def qv2_plan_kernel_ms(plan: Plan, kernel) -> float:
+    """Duration of the last launch of a tile kernel (name or id); the stream must be synchronised."""
+    ms = ctypes.c_float()
+    kid = KERNEL_IDS[kernel] if isinstance(kernel, str) else int(kernel)
+    _check(lib().qv2_plan_kernel_ms(plan.handle, kid, ctypes.byref(ms)), "qv2_plan_kernel_ms")
+    return ms.value
+
+
 def qv2_workspace_bytes(plan: Plan) -> int:
     return lib().qv2_workspace_bytes(plan.handle)
 
@@ -195,6 +215,14 @@ def qv2_pair_metrics(plan: Plan, d_pair_sums, d_workspace, workspace_bytes=None,
     wb = workspace_bytes if workspace_bytes is not None else d_workspace.numel() * d_workspace.element_size()
     _check(lib().qv2_pair_metrics(plan.handle, _ptr(d_pair_sums), _ptr(d_workspace), wb,
                                   _stream(stream)), "qv2_pair_metrics")
+
+
+def qv2_fakequant_pair_metrics(plan: Plan, d_params, d_sums, d_pair_sums, d_workspace,
+                               workspace_bytes=None, stream=None):
+    wb = workspace_bytes if workspace_bytes is not None else d_workspace.numel() * d_workspace.element_size()
+    _check(lib().qv2_fakequant_pair_metrics(plan.handle, _ptr(d_params), _ptr(d_sums), _ptr(d_pair_sums),
+                                            _ptr(d_workspace), wb, _stream(stream)),
+           "qv2_fakequant_pair_metrics")
 
 
 def qv2_finalize(plan: Plan, h_params: np.ndarray, h_sums: np.ndarray, strict: bool = True) -> np.ndarray:

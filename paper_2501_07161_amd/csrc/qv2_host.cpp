@@ -65,6 +65,7 @@ qv2_status qv2_plan_create(const qv2_tensor* h_tensors, int32_t n_tensors, qv2_p
     const int64_t inner = in.numel / nseg;
     const int64_t seg0 = static_cast<int64_t>(p->segments.size());
     if (seg0 + nseg > kMax) { err = QV2_ERR_SHAPE; break; }
+    const int64_t tensor_part0 = n_parts;
 
     TensorDesc d{};
     d.x = in.x; d.qrun = in.qrun; d.codes = in.codes; d.numel = in.numel;
@@ -109,6 +110,13 @@ qv2_status qv2_plan_create(const qv2_tensor* h_tensors, int32_t n_tensors, qv2_p
       }
     }
 
+    PairTensor ft{};
+    if (in.qrun) {
+      ft.n = in.numel; ft.part0 = static_cast<int32_t>(tensor_part0);
+      ft.nparts = static_cast<int32_t>(n_parts - tensor_part0);
+    }
+    p->fused_pair_tensors.push_back(ft);
+
     PairTensor pt{};
     if (in.qrun) {
       const int64_t nt = (in.numel + T - 1) / T;
@@ -132,6 +140,9 @@ qv2_status qv2_plan_create(const qv2_tensor* h_tensors, int32_t n_tensors, qv2_p
     if (p->segments[i].nparts > qv2::kFoldWaveMax) p->big_segments.push_back(static_cast<int32_t>(i));
   for (size_t i = 0; i < p->pair_tensors.size(); ++i)
     if (p->pair_tensors[i].nparts > qv2::kFoldWaveMax) p->big_pair_tensors.push_back(static_cast<int32_t>(i));
+  for (size_t i = 0; i < p->fused_pair_tensors.size(); ++i)
+    if (p->fused_pair_tensors[i].nparts > qv2::kFoldWaveMax)
+      p->big_fused_pair_tensors.push_back(static_cast<int32_t>(i));
   p->n_stream_tiles = static_cast<int64_t>(p->tiles.size());
   p->tiles.insert(p->tiles.end(), row_tiles.begin(), row_tiles.end());
   p->n_parts = n_parts;

@@ -65,6 +65,7 @@ struct PairTensor {            // 16 B, one per tensor of the plan
 // Partial records the tile kernels leave in the workspace.
 struct StatPartial { float mn, mx; double sx, sx2; };   // calibrate, 24 B
 struct ErrPartial { double sx2, se2; };                 // fakequant and pair, 16 B
+struct ErrPartial3 { double sx2, se2, sd2; };           // fused fakequant + pair, 24 B
 
 }  // namespace qv2
 
@@ -77,6 +78,10 @@ struct qv2_plan {
   std::vector<qv2::PairTensor> pair_tensors;
   std::vector<int32_t> big_segments;      // segments with > kFoldWaveMax partials
   std::vector<int32_t> big_pair_tensors;  // pair tensors with > kFoldWaveMax partials
+  // fused fake-quant + pair pass: a tensor's pair energy is folded from ALL its partial
+  // slots of the main tile table (they are contiguous per tensor)
+  std::vector<qv2::PairTensor> fused_pair_tensors;
+  std::vector<int32_t> big_fused_pair_tensors;
   int64_t n_stream_tiles = 0;
   int64_t n_parts = 0;
   int32_t tile_elems = qv2::kDefaultTile;
@@ -91,4 +96,12 @@ struct qv2_plan {
   qv2::PairTensor* d_pair_tensors = nullptr;
   int32_t* d_big_segments = nullptr;
   int32_t* d_big_pair_tensors = nullptr;
+  qv2::PairTensor* d_fused_pair_tensors = nullptr;
+  int32_t* d_big_fused_pair_tensors = nullptr;
+
+  // optional per-kernel timing (qv2_plan_set_timing): hipEvent_t handles
+  bool timing = false;
+  void* ev_start[QV2_K_COUNT] = {};
+  void* ev_stop[QV2_K_COUNT] = {};
+  bool ev_used[QV2_K_COUNT] = {};
 };

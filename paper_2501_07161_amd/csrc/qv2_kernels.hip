@@ -29,7 +29,17 @@ constexpr int kWaves = kBlock / kWave;
 #ifndef QV2_NT_LOADS
 #define QV2_NT_LOADS 1             // measured: +12 % HBM rate on the read-only passes
 #endif
+#ifndef QV2_NT_STORES
+#define QV2_NT_STORES 1
+#endif
+#ifndef QV2_PAIR_UNROLL
+#define QV2_PAIR_UNROLL (QV2_UNROLL / 2)
+#endif
 constexpr int kUnroll = QV2_UNROLL;  // independent 16-byte loads in flight per lane
+constexpr int kPairUnroll = QV2_PAIR_UNROLL;  // per stream, in the two-stream kernels
+#ifndef QV2_PIPELINE
+#define QV2_PIPELINE 1
+#endif
 constexpr int kFoldBlock = 1024;    // workgroup that folds one segment with many partials
 constexpr int kFoldWaves = kFoldBlock / kWave;
 
@@ -100,6 +110,15 @@ __device__ __forceinline__ float4 ld4(const float4* p) {
   return make_float4(v.x, v.y, v.z, v.w);
 #else
   return *p;
+#endif
+}
+
+// Packed int8 codes are written once and not read again by this library.
+__device__ __forceinline__ void st_codes(uint32_t* p, uint32_t v) {
+#if QV2_NT_STORES
+  __builtin_nontemporal_store(v, p);
+#else
+  *p = v;
 #endif
 }
 
@@ -358,7 +377,7 @@ __global__ __launch_bounds__(kBlock) void k_quant_stream(const TensorDesc* __res
     for (int u = 0; u < kUnroll; ++u) {
       const uint32_t pk = quant4(r[u], q, ae2, ax2);
       if (cw_ok) {
-        __builtin_nontemporal_store(pk, &cw[i + u * kBlock]);
+        st_codes(&cw[i + u * kBlock], pk);
       } else if (c) {
         int8_t* d = c + head + ((i + u * kBlock) << 2);
         d[0] = static_cast<int8_t>(pk); d[1] = static_cast<int8_t>(pk >> 8);
@@ -370,7 +389,7 @@ __global__ __launch_bounds__(kBlock) void k_quant_stream(const TensorDesc* __res
     const float4 r = ld4(&v4[i]);
     const uint32_t pk = quant4(r, q, ae2, ax2);
     if (cw_ok) {
-      __builtin_nontemporal_store(pk, &cw[i]);
+      st_codes(&cw[i], pk);
     } else if (c) {
       int8_t* d = c + head + (i << 2);
       d[0] = static_cast<int8_t>(pk); d[1] = static_cast<int8_t>(pk >> 8);
@@ -443,8 +462,203 @@ __global__ __launch_bounds__(kBlock) void k_quant_rows(const TensorDesc* __restr
   }
 }
 
+// ---------------------------------------------------------------------------
+// passes 2 + 3 in one sweep: x is read once for the fake-quant energies AND for
+// the pair energies against qrun (Eq. 1, 3, 5, 6-7; Algorithm 2's D[i] vs Q[i]).
+// Per element: 4 B (x) + 4 B (qrun) read, 1 B code written.
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ void put_codes4(int8_t* c, uint32_t* cw, bool cw_ok, int head, int i,
+                                           uint32_t pk) {
+  if (cw_ok) {
+    st_codes(&cw[i], pk);
+  } else if (c) {
+    int8_t* d = c + head + (i << 2);
+    d[0] = static_cast<int8_t>(pk); d[1] = static_cast<int8_t>(pk >> 8);
+    d[2] = static_cast<int8_t>(pk >> 16); d[3] = static_cast<int8_t>(pk >> 24);
+  }
+}
+
+__global__ __launch_bounds__(kBlock) void k_quantpair_stream(const TensorDesc* __restrict__ descs,
+                                                             const Tile* __restrict__ tiles,
+                                                             const qv2_qparams* __restrict__ params,
+                                                             ErrPartial3* __restrict__ parts) {
+  const Tile tl = tiles[blockIdx.x];
+  const TensorDesc td = descs[tl.tensor];
+  const float* __restrict__ p = td.x + tl.off;
+  const float* __restrict__ b = td.qrun ? td.qrun + tl.off : nullptr;
+  int8_t* __restrict__ c = td.codes ? td.codes + tl.off : nullptr;
+  const QP q = load_qp(params, tl.seg0);
+  const int len = tl.len, tid = threadIdx.x;
+  double sx2 = 0.0, se2 = 0.0, sd2 = 0.0;
+
+  // qrun at a different offset inside 16 bytes than x: its energy is taken element-wise
+  const bool b_vec = b && (((reinterpret_cast<uintptr_t>(p) ^ reinterpret_cast<uintptr_t>(b)) & 15u) == 0);
+  if (b && !b_vec) {
+    for (int i = tid; i < len; i += kBlock) {
+      const double d = static_cast<double>(p[i] - b[i]);
+      sd2 = fma(d, d, sd2);
+    }
+  }
+  const int head = head_elems(p, len);
+  const int body = len - head, nvec = body >> 2, tail = body & 3;
+  for (int k = 0; k < 2; ++k) {
+    const bool on = k == 0 ? tid < head : tid < tail;
+    if (!on) continue;
+    const int idx = k == 0 ? tid : head + (nvec << 2) + tid;
+    const float v = p[idx];
+    float e;
+    const float code = quant1(v, q, e);
+    if (c) c[idx] = static_cast<int8_t>(static_cast<int>(code));
+    sx2 += static_cast<double>(v) * v;
+    se2 += static_cast<double>(e) * e;
+    if (b_vec) { const float d = v - b[idx]; sd2 += static_cast<double>(d) * d; }
+  }
+  const float4* __restrict__ v4 = reinterpret_cast<const float4*>(p + head);
+  const float4* __restrict__ b4 = reinterpret_cast<const float4*>(b + head);
+  const bool cw_ok = c && ((reinterpret_cast<uintptr_t>(c + head) & 3u) == 0);
+  uint32_t* __restrict__ cw = reinterpret_cast<uint32_t*>(c + head);
+  Acc4 ae2, ax2, ad2;
+#define PUT(ii, pk) put_codes4(c, cw, cw_ok, head, (ii), (pk))
+  int i = tid;
+  if (b_vec) {
+    constexpr int U = kPairUnroll;
+#if QV2_PIPELINE
+    // Loads and stores share one in-order counter on this ISA: a wave that waits for its
+    // next loads also waits for every store issued before them.  So the next round's loads
+    // are issued BEFORE this round's code stores.
+    if (i + (U - 1) * kBlock < nvec) {
+      float4 r[U], g[U];
+#pragma unroll
+      for (int u = 0; u < U; ++u) { r[u] = ld4(&v4[i + u * kBlock]); g[u] = ld4(&b4[i + u * kBlock]); }
+      for (;;) {
+        const int inext = i + U * kBlock;
+        const bool more = inext + (U - 1) * kBlock < nvec;
+        float4 rn[U], gn[U];
+        if (more) {
+#pragma unroll
+          for (int u = 0; u < U; ++u) { rn[u] = ld4(&v4[inext + u * kBlock]); gn[u] = ld4(&b4[inext + u * kBlock]); }
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+          PUT(i + u * kBlock, quant4(r[u], q, ae2, ax2));
+          ad2.add_sq(r[u].x - g[u].x, r[u].y - g[u].y, r[u].z - g[u].z, r[u].w - g[u].w);
+        }
+        i = inext;
+        if (!more) break;
+#pragma unroll
+        for (int u = 0; u < U; ++u) { r[u] = rn[u]; g[u] = gn[u]; }
+      }
+    }
+#else
+    for (; i + (U - 1) * kBlock < nvec; i += U * kBlock) {
+      float4 r[U], g[U];
+#pragma unroll
+      for (int u = 0; u < U; ++u) { r[u] = ld4(&v4[i + u * kBlock]); g[u] = ld4(&b4[i + u * kBlock]); }
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        PUT(i + u * kBlock, quant4(r[u], q, ae2, ax2));
+        ad2.add_sq(r[u].x - g[u].x, r[u].y - g[u].y, r[u].z - g[u].z, r[u].w - g[u].w);
+      }
+    }
+#endif
+    for (; i < nvec; i += kBlock) {
+      const float4 r = ld4(&v4[i]), g = ld4(&b4[i]);
+      PUT(i, quant4(r, q, ae2, ax2));
+      ad2.add_sq(r.x - g.x, r.y - g.y, r.z - g.z, r.w - g.w);
+    }
+  } else {
+    for (; i + (kUnroll - 1) * kBlock < nvec; i += kUnroll * kBlock) {
+      float4 r[kUnroll];
+#pragma unroll
+      for (int u = 0; u < kUnroll; ++u) r[u] = ld4(&v4[i + u * kBlock]);
+#pragma unroll
+      for (int u = 0; u < kUnroll; ++u)
+        PUT(i + u * kBlock, quant4(r[u], q, ae2, ax2));
+    }
+    for (; i < nvec; i += kBlock)
+      PUT(i, quant4(ld4(&v4[i]), q, ae2, ax2));
+  }
+#undef PUT
+  se2 += ae2.total(); sx2 += ax2.total(); sd2 += ad2.total();
+  double zero = 0.0;
+  block_sum2(sx2, se2);
+  __syncthreads();                                  // block_sum2's LDS slots are reused
+  block_sum2(sd2, zero);
+  if (tid == 0) {
+    ErrPartial3 o;
+    o.sx2 = sx2; o.se2 = se2; o.sd2 = sd2;
+    parts[tl.part0] = o;
+  }
+}
+
+// fused passes 2 + 3, row-group tiles
+__global__ __launch_bounds__(kBlock) void k_quantpair_rows(const TensorDesc* __restrict__ descs,
+                                                           const Tile* __restrict__ tiles,
+                                                           const qv2_qparams* __restrict__ params,
+                                                           ErrPartial3* __restrict__ parts) {
+  __shared__ __attribute__((aligned(16))) float xs[kRowGroupCap + 4];
+  __shared__ __attribute__((aligned(16))) int8_t cs[kRowGroupCap + 8];
+  const Tile tl = tiles[blockIdx.x];
+  const TensorDesc td = descs[tl.tensor];
+  const int shift = stage_tile(td.x + tl.off, tl.len, xs);
+  const float* __restrict__ b = td.qrun ? td.qrun + tl.off : nullptr;
+  int8_t* __restrict__ dst = td.codes ? td.codes + tl.off : nullptr;
+  const int ca = static_cast<int>(reinterpret_cast<uintptr_t>(dst) & 3u);
+  __syncthreads();
+
+  const int inner = tl.inner, w = row_width(inner), gpw = kWave / w;
+  const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
+  const int g = lane >> __builtin_ctz(w), gl = lane & (w - 1);
+  for (int rb = wave * gpw; rb < tl.rows; rb += kWaves * gpw) {
+    const int r = rb + g;
+    const bool live = r < tl.rows;
+    double sx2 = 0.0, se2 = 0.0, sd2 = 0.0;
+    if (live) {
+      const QP q = load_qp(params, tl.seg0 + r);
+      const float* row = xs + shift + r * inner;
+      int8_t* crow = cs + ca + r * inner;
+      for (int j = gl; j < inner; j += w) {
+        const float v = row[j];
+        float e;
+        const float code = quant1(v, q, e);
+        crow[j] = static_cast<int8_t>(static_cast<int>(code));
+        sx2 = fma(static_cast<double>(v), static_cast<double>(v), sx2);
+        se2 = fma(static_cast<double>(e), static_cast<double>(e), se2);
+        if (b) {
+          const double d = static_cast<double>(v - b[r * inner + j]);
+          sd2 = fma(d, d, sd2);
+        }
+      }
+    }
+    sx2 = group_sum(sx2, w); se2 = group_sum(se2, w); sd2 = group_sum(sd2, w);
+    if (live && gl == 0) {
+      ErrPartial3 o;
+      o.sx2 = sx2; o.se2 = se2; o.sd2 = sd2;
+      parts[tl.part0 + r] = o;
+    }
+  }
+  if (!dst) return;
+  __syncthreads();
+  const int total = tl.len + ca;
+  int8_t* base = dst - ca;
+  for (int k = threadIdx.x; (k << 2) < total; k += kBlock) {
+    const int b0 = k << 2;
+    if (b0 >= ca && b0 + 4 <= total) {
+      *reinterpret_cast<uint32_t*>(base + b0) = *reinterpret_cast<const uint32_t*>(cs + b0);
+    } else {
+      const int lo = b0 > ca ? b0 : ca, hi = b0 + 4 < total ? b0 + 4 : total;
+      for (int bb = lo; bb < hi; ++bb) base[bb] = cs[bb];
+    }
+  }
+}
+
+// second energy of a partial record: the pair-noise energy
+__device__ __forceinline__ double pair_energy(const ErrPartial& p) { return p.se2; }
+__device__ __forceinline__ double pair_energy(const ErrPartial3& p) { return p.sd2; }
+
+template <class P>
 __global__ __launch_bounds__(kBlock) void k_fold_err(const Segment* __restrict__ segs, int nseg,
-                                                     const ErrPartial* __restrict__ parts,
+                                                     const P* __restrict__ parts,
                                                      qv2_sums* __restrict__ sums) {
   const int seg = blockIdx.x * kWaves + (threadIdx.x >> 6);
   const int lane = threadIdx.x & (kWave - 1);
@@ -453,7 +667,7 @@ __global__ __launch_bounds__(kBlock) void k_fold_err(const Segment* __restrict__
   if (sg.nparts > kFoldWaveMax) return;            // folded by k_fold_err_big
   double sx2 = 0.0, se2 = 0.0;
   for (int i = lane; i < sg.nparts; i += kWave) {
-    const ErrPartial q = parts[sg.part0 + i];
+    const P q = parts[sg.part0 + i];
     sx2 += q.sx2; se2 += q.se2;
   }
   sx2 = group_sum(sx2, kWave); se2 = group_sum(se2, kWave);
@@ -496,7 +710,7 @@ __global__ __launch_bounds__(kBlock) void k_pair_stream(const TensorDesc* __rest
     }
     const float4* __restrict__ a4 = reinterpret_cast<const float4*>(a + head);
     const float4* __restrict__ b4 = reinterpret_cast<const float4*>(b + head);
-    constexpr int U = kUnroll / 2;                 // two streams: same bytes in flight
+    constexpr int U = kPairUnroll;                 // two streams: same bytes in flight
     Acc4 ar2, ad2;
     int i = tid;
     for (; i + (U - 1) * kBlock < nvec; i += U * kBlock) {
@@ -524,8 +738,9 @@ __global__ __launch_bounds__(kBlock) void k_pair_stream(const TensorDesc* __rest
   }
 }
 
+template <class P>
 __global__ __launch_bounds__(kBlock) void k_fold_pair(const PairTensor* __restrict__ pt, int n,
-                                                      const ErrPartial* __restrict__ parts,
+                                                      const P* __restrict__ parts,
                                                       qv2_pair_sums* __restrict__ out) {
   const int t = blockIdx.x * kWaves + (threadIdx.x >> 6);
   const int lane = threadIdx.x & (kWave - 1);
@@ -534,8 +749,8 @@ __global__ __launch_bounds__(kBlock) void k_fold_pair(const PairTensor* __restri
   if (p.nparts > kFoldWaveMax) return;             // folded by k_fold_pair_big
   double sr2 = 0.0, sd2 = 0.0;
   for (int i = lane; i < p.nparts; i += kWave) {
-    const ErrPartial q = parts[p.part0 + i];
-    sr2 += q.sx2; sd2 += q.se2;
+    const P q = parts[p.part0 + i];
+    sr2 += q.sx2; sd2 += pair_energy(q);
   }
   sr2 = group_sum(sr2, kWave); sd2 = group_sum(sd2, kWave);
   if (lane == 0) {
@@ -593,16 +808,17 @@ __global__ __launch_bounds__(kFoldBlock) void k_fold_stats_big(const Segment* __
   }
 }
 
+template <class P>
 __global__ __launch_bounds__(kFoldBlock) void k_fold_err_big(const Segment* __restrict__ segs,
                                                              const int* __restrict__ ids,
-                                                             const ErrPartial* __restrict__ parts,
+                                                             const P* __restrict__ parts,
                                                              qv2_sums* __restrict__ sums) {
   const int seg = ids[blockIdx.x];
   const Segment sg = segs[seg];
   double sx2 = 0.0, se2 = 0.0;
 #pragma unroll 4
   for (int i = threadIdx.x; i < sg.nparts; i += kFoldBlock) {
-    const ErrPartial q = parts[sg.part0 + i];
+    const P q = parts[sg.part0 + i];
     sx2 += q.sx2; se2 += q.se2;
   }
   fold_block_sum2(sx2, se2);
@@ -611,17 +827,18 @@ __global__ __launch_bounds__(kFoldBlock) void k_fold_err_big(const Segment* __re
   }
 }
 
+template <class P>
 __global__ __launch_bounds__(kFoldBlock) void k_fold_pair_big(const PairTensor* __restrict__ pt,
                                                               const int* __restrict__ ids,
-                                                              const ErrPartial* __restrict__ parts,
+                                                              const P* __restrict__ parts,
                                                               qv2_pair_sums* __restrict__ out) {
   const int t = ids[blockIdx.x];
   const PairTensor p = pt[t];
   double sr2 = 0.0, sd2 = 0.0;
 #pragma unroll 4
   for (int i = threadIdx.x; i < p.nparts; i += kFoldBlock) {
-    const ErrPartial q = parts[p.part0 + i];
-    sr2 += q.sx2; sd2 += q.se2;
+    const P q = parts[p.part0 + i];
+    sr2 += q.sx2; sd2 += pair_energy(q);
   }
   fold_block_sum2(sr2, sd2);
   if (threadIdx.x == 0) {
@@ -646,9 +863,11 @@ qv2_status ensure_uploaded(qv2_plan* p) {
   const size_t b_pten = align256(p->pair_tensors.size() * sizeof(PairTensor));
   const size_t b_bseg = align256(p->big_segments.size() * sizeof(int32_t));
   const size_t b_bpair = align256(p->big_pair_tensors.size() * sizeof(int32_t));
+  const size_t b_ften = align256(p->fused_pair_tensors.size() * sizeof(PairTensor));
+  const size_t b_bften = align256(p->big_fused_pair_tensors.size() * sizeof(int32_t));
   char* blob = nullptr;
-  if (hipMalloc(reinterpret_cast<void**>(&blob),
-                b_desc + b_tile + b_seg + b_ptile + b_pten + b_bseg + b_bpair + 256) !=
+  if (hipMalloc(reinterpret_cast<void**>(&blob), b_desc + b_tile + b_seg + b_ptile + b_pten +
+                                                      b_bseg + b_bpair + b_ften + b_bften + 256) !=
       hipSuccess) { (void)hipGetLastError(); return QV2_ERR_HIP; }
   char* q = blob;
   p->d_descs = reinterpret_cast<TensorDesc*>(q); q += b_desc;
@@ -657,7 +876,9 @@ qv2_status ensure_uploaded(qv2_plan* p) {
   p->d_pair_tiles = reinterpret_cast<Tile*>(q); q += b_ptile;
   p->d_pair_tensors = reinterpret_cast<PairTensor*>(q); q += b_pten;
   p->d_big_segments = reinterpret_cast<int32_t*>(q); q += b_bseg;
-  p->d_big_pair_tensors = reinterpret_cast<int32_t*>(q);
+  p->d_big_pair_tensors = reinterpret_cast<int32_t*>(q); q += b_bpair;
+  p->d_fused_pair_tensors = reinterpret_cast<PairTensor*>(q); q += b_ften;
+  p->d_big_fused_pair_tensors = reinterpret_cast<int32_t*>(q);
   bool ok = true;
   auto put = [&](void* d, const void* h, size_t n) {
     if (n && hipMemcpy(d, h, n, hipMemcpyHostToDevice) != hipSuccess) ok = false;
@@ -669,6 +890,10 @@ qv2_status ensure_uploaded(qv2_plan* p) {
   put(p->d_pair_tensors, p->pair_tensors.data(), p->pair_tensors.size() * sizeof(PairTensor));
   put(p->d_big_segments, p->big_segments.data(), p->big_segments.size() * sizeof(int32_t));
   put(p->d_big_pair_tensors, p->big_pair_tensors.data(), p->big_pair_tensors.size() * sizeof(int32_t));
+  put(p->d_fused_pair_tensors, p->fused_pair_tensors.data(),
+      p->fused_pair_tensors.size() * sizeof(PairTensor));
+  put(p->d_big_fused_pair_tensors, p->big_fused_pair_tensors.data(),
+      p->big_fused_pair_tensors.size() * sizeof(int32_t));
   if (!ok) { (void)hipGetLastError(); (void)hipFree(blob); return QV2_ERR_HIP; }
   p->d_blob = blob;
   return QV2_OK;
@@ -685,6 +910,15 @@ qv2_status check_call(const qv2_plan* plan, const void* a, const void* b, const 
 
 qv2_status launch_status() { return hipGetLastError() == hipSuccess ? QV2_OK : QV2_ERR_HIP; }
 
+// Brackets one kernel launch with the plan's HIP events when timing is enabled.
+struct Timed {
+  qv2_plan* p; int k; hipStream_t s;
+  Timed(qv2_plan* plan, int kernel, hipStream_t st) : p(plan), k(kernel), s(st) {
+    if (p->timing) { (void)hipEventRecord(static_cast<hipEvent_t>(p->ev_start[k]), s); p->ev_used[k] = true; }
+  }
+  ~Timed() { if (p->timing) (void)hipEventRecord(static_cast<hipEvent_t>(p->ev_stop[k]), s); }
+};
+
 }  // namespace
 
 extern "C" {
@@ -692,7 +926,40 @@ extern "C" {
 void qv2_plan_destroy(qv2_plan* plan) {
   if (!plan) return;
   if (plan->d_blob) (void)hipFree(plan->d_blob);
+  for (int k = 0; k < QV2_K_COUNT; ++k) {
+    if (plan->ev_start[k]) (void)hipEventDestroy(static_cast<hipEvent_t>(plan->ev_start[k]));
+    if (plan->ev_stop[k]) (void)hipEventDestroy(static_cast<hipEvent_t>(plan->ev_stop[k]));
+  }
   delete plan;
+}
+
+qv2_status qv2_plan_set_timing(qv2_plan* plan, int32_t enable) {
+  if (!plan) return QV2_ERR_NULL;
+  if (enable && !plan->ev_start[0]) {
+    for (int k = 0; k < QV2_K_COUNT; ++k) {
+      hipEvent_t a = nullptr, b = nullptr;
+      if (hipEventCreate(&a) != hipSuccess || hipEventCreate(&b) != hipSuccess) {
+        (void)hipGetLastError();
+        return QV2_ERR_HIP;
+      }
+      plan->ev_start[k] = a; plan->ev_stop[k] = b;
+    }
+  }
+  plan->timing = enable != 0;
+  return QV2_OK;
+}
+
+qv2_status qv2_plan_kernel_ms(const qv2_plan* plan, int32_t kernel, float* ms_out) {
+  if (!plan || !ms_out) return QV2_ERR_NULL;
+  if (kernel < 0 || kernel >= QV2_K_COUNT) return QV2_ERR_SHAPE;
+  *ms_out = 0.0f;
+  if (!plan->ev_used[kernel]) return QV2_OK;
+  if (hipEventElapsedTime(ms_out, static_cast<hipEvent_t>(plan->ev_start[kernel]),
+                          static_cast<hipEvent_t>(plan->ev_stop[kernel])) != hipSuccess) {
+    (void)hipGetLastError();
+    return QV2_ERR_HIP;
+  }
+  return QV2_OK;
 }
 
 qv2_status qv2_calibrate(qv2_plan* plan, qv2_qparams* d_params, qv2_sums* d_sums,
@@ -705,12 +972,16 @@ qv2_status qv2_calibrate(qv2_plan* plan, qv2_qparams* d_params, qv2_sums* d_sums
   const int n_stream = static_cast<int>(plan->n_stream_tiles);
   const int n_rows = static_cast<int>(plan->tiles.size()) - n_stream;
   const int nseg = static_cast<int>(plan->segments.size());
-  if (n_stream > 0)
+  if (n_stream > 0) {
+    Timed timed(plan, QV2_K_STATS_STREAM, s);
     hipLaunchKernelGGL(k_stats_stream, dim3(n_stream), dim3(kBlock), 0, s, plan->d_descs,
                        plan->d_tiles, parts);
-  if (n_rows > 0)
+  }
+  if (n_rows > 0) {
+    Timed timed(plan, QV2_K_STATS_ROWS, s);
     hipLaunchKernelGGL(k_stats_rows, dim3(n_rows), dim3(kBlock), 0, s, plan->d_descs,
                        plan->d_tiles + n_stream, parts);
+  }
   hipLaunchKernelGGL(k_fold_stats, dim3((nseg + kWaves - 1) / kWaves), dim3(kBlock), 0, s,
                      plan->d_segments, nseg, parts, d_params, d_sums);
   if (const int nb = static_cast<int>(plan->big_segments.size()))
@@ -729,16 +1000,20 @@ qv2_status qv2_fakequant_metrics(qv2_plan* plan, const qv2_qparams* d_params, qv
   const int n_stream = static_cast<int>(plan->n_stream_tiles);
   const int n_rows = static_cast<int>(plan->tiles.size()) - n_stream;
   const int nseg = static_cast<int>(plan->segments.size());
-  if (n_stream > 0)
+  if (n_stream > 0) {
+    Timed timed(plan, QV2_K_QUANT_STREAM, s);
     hipLaunchKernelGGL(k_quant_stream, dim3(n_stream), dim3(kBlock), 0, s, plan->d_descs,
                        plan->d_tiles, d_params, parts);
-  if (n_rows > 0)
+  }
+  if (n_rows > 0) {
+    Timed timed(plan, QV2_K_QUANT_ROWS, s);
     hipLaunchKernelGGL(k_quant_rows, dim3(n_rows), dim3(kBlock), 0, s, plan->d_descs,
                        plan->d_tiles + n_stream, d_params, parts);
-  hipLaunchKernelGGL(k_fold_err, dim3((nseg + kWaves - 1) / kWaves), dim3(kBlock), 0, s,
+  }
+  hipLaunchKernelGGL(k_fold_err<ErrPartial>, dim3((nseg + kWaves - 1) / kWaves), dim3(kBlock), 0, s,
                      plan->d_segments, nseg, parts, d_sums);
   if (const int nb = static_cast<int>(plan->big_segments.size()))
-    hipLaunchKernelGGL(k_fold_err_big, dim3(nb), dim3(kFoldBlock), 0, s, plan->d_segments,
+    hipLaunchKernelGGL(k_fold_err_big<ErrPartial>, dim3(nb), dim3(kFoldBlock), 0, s, plan->d_segments,
                        plan->d_big_segments, parts, d_sums);
   return launch_status();
 }
@@ -752,14 +1027,53 @@ qv2_status qv2_pair_metrics(qv2_plan* plan, qv2_pair_sums* d_pair_sums, void* d_
   ErrPartial* parts = static_cast<ErrPartial*>(d_workspace);
   const int n_tiles = static_cast<int>(plan->pair_tiles.size());
   const int nt = static_cast<int>(plan->pair_tensors.size());
-  if (n_tiles > 0)
+  if (n_tiles > 0) {
+    Timed timed(plan, QV2_K_PAIR_STREAM, s);
     hipLaunchKernelGGL(k_pair_stream, dim3(n_tiles), dim3(kBlock), 0, s, plan->d_descs,
                        plan->d_pair_tiles, parts);
-  hipLaunchKernelGGL(k_fold_pair, dim3((nt + kWaves - 1) / kWaves), dim3(kBlock), 0, s,
+  }
+  hipLaunchKernelGGL(k_fold_pair<ErrPartial>, dim3((nt + kWaves - 1) / kWaves), dim3(kBlock), 0, s,
                      plan->d_pair_tensors, nt, parts, d_pair_sums);
   if (const int nb = static_cast<int>(plan->big_pair_tensors.size()))
-    hipLaunchKernelGGL(k_fold_pair_big, dim3(nb), dim3(kFoldBlock), 0, s, plan->d_pair_tensors,
+    hipLaunchKernelGGL(k_fold_pair_big<ErrPartial>, dim3(nb), dim3(kFoldBlock), 0, s, plan->d_pair_tensors,
                        plan->d_big_pair_tensors, parts, d_pair_sums);
+  return launch_status();
+}
+
+qv2_status qv2_fakequant_pair_metrics(qv2_plan* plan, const qv2_qparams* d_params, qv2_sums* d_sums,
+                                      qv2_pair_sums* d_pair_sums, void* d_workspace,
+                                      size_t workspace_bytes, void* hip_stream) {
+  qv2_status st = check_call(plan, d_params, d_sums, d_workspace, workspace_bytes);
+  if (st != QV2_OK) return st;
+  if (!d_pair_sums) return QV2_ERR_NULL;
+  if (reinterpret_cast<uintptr_t>(d_pair_sums) & 7u) return QV2_ERR_ALIGN;
+  if ((st = ensure_uploaded(plan)) != QV2_OK) return st;
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  ErrPartial3* parts = static_cast<ErrPartial3*>(d_workspace);
+  const int n_stream = static_cast<int>(plan->n_stream_tiles);
+  const int n_rows = static_cast<int>(plan->tiles.size()) - n_stream;
+  const int nseg = static_cast<int>(plan->segments.size());
+  const int nt = static_cast<int>(plan->fused_pair_tensors.size());
+  if (n_stream > 0) {
+    Timed timed(plan, QV2_K_QUANTPAIR_STREAM, s);
+    hipLaunchKernelGGL(k_quantpair_stream, dim3(n_stream), dim3(kBlock), 0, s, plan->d_descs,
+                       plan->d_tiles, d_params, parts);
+  }
+  if (n_rows > 0) {
+    Timed timed(plan, QV2_K_QUANTPAIR_ROWS, s);
+    hipLaunchKernelGGL(k_quantpair_rows, dim3(n_rows), dim3(kBlock), 0, s, plan->d_descs,
+                       plan->d_tiles + n_stream, d_params, parts);
+  }
+  hipLaunchKernelGGL(k_fold_err<ErrPartial3>, dim3((nseg + kWaves - 1) / kWaves), dim3(kBlock), 0, s,
+                     plan->d_segments, nseg, parts, d_sums);
+  if (const int nb = static_cast<int>(plan->big_segments.size()))
+    hipLaunchKernelGGL(k_fold_err_big<ErrPartial3>, dim3(nb), dim3(kFoldBlock), 0, s,
+                       plan->d_segments, plan->d_big_segments, parts, d_sums);
+  hipLaunchKernelGGL(k_fold_pair<ErrPartial3>, dim3((nt + kWaves - 1) / kWaves), dim3(kBlock), 0, s,
+                     plan->d_fused_pair_tensors, nt, parts, d_pair_sums);
+  if (const int nb = static_cast<int>(plan->big_fused_pair_tensors.size()))
+    hipLaunchKernelGGL(k_fold_pair_big<ErrPartial3>, dim3(nb), dim3(kFoldBlock), 0, s,
+                       plan->d_fused_pair_tensors, plan->d_big_fused_pair_tensors, parts, d_pair_sums);
   return launch_status();
 }
 

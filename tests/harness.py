@@ -91,8 +91,9 @@ def attach_pairs(items: List[Item], specs: List[synth.TensorSpec]):
 
 
 def run_gpu(items: List[Item], params_override: Optional[np.ndarray] = None,
-            do_calibrate: bool = True) -> GpuResult:
-    """calibrate -> fakequant -> pair on the current stream, then host finalize."""
+            do_calibrate: bool = True, fused: bool = False) -> GpuResult:
+    """calibrate -> fakequant -> pair (or the fused fakequant+pair call) on the current
+    stream, then host finalize."""
     dev = items[0].x.device
     rows = []
     for it in items:
@@ -110,8 +111,11 @@ def run_gpu(items: List[Item], params_override: Optional[np.ndarray] = None,
     if params_override is not None:
         torch.cuda.synchronize()
         buf.params.copy_(torch.from_numpy(params_override.view(np.uint8)).to(dev))
-    qb.qv2_fakequant_metrics(plan, buf.params, buf.sums, buf.workspace)
-    qb.qv2_pair_metrics(plan, buf.pair, buf.workspace)
+    if fused:
+        qb.qv2_fakequant_pair_metrics(plan, buf.params, buf.sums, buf.pair, buf.workspace)
+    else:
+        qb.qv2_fakequant_metrics(plan, buf.params, buf.sums, buf.workspace)
+        qb.qv2_pair_metrics(plan, buf.pair, buf.workspace)
     torch.cuda.synchronize()
     params, sums, pair = buf.host()
     metrics = qb.qv2_finalize(plan, params, sums, strict=False)

@@ -15,33 +15,36 @@ DEV = "cuda"
 A, S, C = qb.QV2_ASYM_TENSOR, qb.QV2_SYM_TENSOR, qb.QV2_SYM_CHANNEL
 
 
-def _run_config(specs, rank_kwargs=None):
+def _run_config(specs, rank_kwargs=None, fused=False):
     items = H.items_from_specs(specs, DEV)
     H.attach_pairs(items, specs)
-    res = H.run_gpu(items)
+    res = H.run_gpu(items, fused=fused)
     rows = H.check_all(items, res)
     order = H.check_ranking(items, res, rows, rank_kwargs)
     return items, res, order
 
 
-def test_config_tiny():
+@pytest.mark.parametrize("fused", [False, True])
+def test_config_tiny(fused):
     """Three tensors, per-tensor asymmetric: conv weight, ReLU activation with a pair, fc weight."""
-    items, res, order = _run_config(synth.config_tiny())
+    items, res, order = _run_config(synth.config_tiny(), fused=fused)
     assert res.plan.num_segments == 3 and sorted(order) == [0, 1]
     # the activation is post-ReLU: min 0, zero-point at the bottom code
     assert res.params["min"][1] == 0.0 and res.params["zp"][1] == -128
 
 
-def test_config_resnet18_batch32():
+@pytest.mark.parametrize("fused", [False, True])
+def test_config_resnet18_batch32(fused):
     """ResNet-18 shapes at the stated batch: 21 weights + 21 activations, per-tensor asymmetric."""
-    items, res, order = _run_config(synth.config_resnet18(32))
+    items, res, order = _run_config(synth.config_resnet18(32), fused=fused)
     assert len(order) == 21 and sorted(order) == list(range(21))
 
 
-def test_config_mobilenetv2_per_channel():
+@pytest.mark.parametrize("fused", [False, True])
+def test_config_mobilenetv2_per_channel(fused):
     """MobileNetV2 shapes: per-output-channel symmetric weights with rows of 9 / 27 / ...
     elements, Laplace + outlier values, ReLU6 activations (batch reduced so the oracle stays fast)."""
-    items, res, order = _run_config(synth.config_mobilenetv2(8))
+    items, res, order = _run_config(synth.config_mobilenetv2(8), fused=fused)
     assert len(order) == 53
     dw = [t for t, it in enumerate(items) if it.name.endswith(".dw.w")]
     assert dw and all(items[t].x.numel() // items[t].channels == 9 for t in dw)
@@ -54,10 +57,10 @@ def test_config_vgg16_weights_full_size(per_channel):
     _run_config(synth.config_vgg16(2, per_channel))
 
 
-@pytest.mark.parametrize("fused", [False, True])
-def test_config_resnet50_small_batch(fused):
+@pytest.mark.parametrize("bnfold,fused", [(False, False), (True, False), (True, True)])
+def test_config_resnet50_small_batch(bnfold, fused):
     """ResNet-50 shapes, per-channel weights (plain and BN-folded variants), batch 4."""
-    items, res, order = _run_config(synth.config_resnet50(4, fused))
+    items, res, order = _run_config(synth.config_resnet50(4, bnfold), fused=fused)
     assert len(order) == 54
 
 
@@ -70,7 +73,8 @@ def _rand(n, seed, scale=1.0):
     return torch.randn(n, generator=g, device=DEV) * scale
 
 
-def test_ragged_lengths_and_unaligned_pointers():
+@pytest.mark.parametrize("fused", [False, True])
+def test_ragged_lengths_and_unaligned_pointers(fused):
     """Lengths around tile and vector boundaries, inputs starting 4 / 8 / 12 bytes past a
     16-byte boundary, code buffers starting 1..3 bytes past a 4-byte boundary."""
     items = []
@@ -87,11 +91,12 @@ def test_ragged_lengths_and_unaligned_pointers():
                 q = (_rand(n + 8, 500 + i)[1: 1 + n])
             items.append(H.Item(f"len{n}.off{off}", x, scheme, 1, 1, len(items), qrun=q,
                                 codes_offset=(i + off) % 4))
-    res = H.run_gpu(items)
+    res = H.run_gpu(items, fused=fused)
     H.check_all(items, res)
 
 
-def test_per_channel_row_shapes():
+@pytest.mark.parametrize("fused", [False, True])
+def test_per_channel_row_shapes(fused):
     """Rows of 1, 3, 9, 27, 64, 65, 576, 8191, 8192 (LDS row groups) and 8193, 20001, 40000,
     70001 (rows as one or several stream tiles, unaligned row starts), with unaligned bases and
     code buffers."""
@@ -104,13 +109,15 @@ def test_per_channel_row_shapes():
             x = base[off: off + c * inner]
             if i % 3 == 0:
                 x.view(c, inner)[c // 2] = 0.0          # a dead channel
-            items.append(H.Item(f"rows{c}x{inner}.off{off}", x, C, c, 0, len(items),
+            q = (x * 0.97 + 0.001) if i % 2 == 0 else None     # a quantized-run partner of a weight
+            items.append(H.Item(f"rows{c}x{inner}.off{off}", x, C, c, 0, len(items), qrun=q,
                                 codes_offset=(i + off) % 4))
-    res = H.run_gpu(items)
+    res = H.run_gpu(items, fused=fused)
     H.check_all(items, res)
 
 
-def test_degenerate_and_special_values():
+@pytest.mark.parametrize("fused", [False, True])
+def test_degenerate_and_special_values(fused):
     z = torch.zeros(5000, device=DEV)
     const = torch.full((4097,), 3.25, device=DEV)
     neg = -torch.rand(9000, device=DEV) - 0.5
@@ -126,7 +133,7 @@ def test_degenerate_and_special_values():
                     ("tiny", tiny), ("grid", grid), ("big", big), ("small", small), ("one", one)]:
         for scheme in (A, S):
             items.append(H.Item(f"{name}.{scheme}", x, scheme, 1, 0, len(items), qrun=x.clone()))
-    res = H.run_gpu(items)
+    res = H.run_gpu(items, fused=fused)
     H.check_all(items, res)
     t = [i for i, it in enumerate(items) if it.name == "grid.0"][0]
     assert res.metrics[t]["mse"] == 0.0 and np.isinf(res.metrics[t]["sqnr_db"])   # int8-grid fact
@@ -181,6 +188,23 @@ def test_bit_stable_across_runs():
     r1 = H.run_gpu(items)
     c1 = [it.codes.clone() for it in items]
     r2 = H.run_gpu(items)
+    assert r1.params.tobytes() == r2.params.tobytes()
+    assert r1.sums.tobytes() == r2.sums.tobytes()
+    assert r1.pair.tobytes() == r2.pair.tobytes()
+    assert all(torch.equal(a, it.codes) for a, it in zip(c1, items))
+
+
+def test_fused_call_equals_the_two_separate_calls():
+    """qv2_fakequant_pair_metrics against qv2_fakequant_metrics + qv2_pair_metrics: codes and
+    the per-segment sums bit-identical; pair sums bit-identical for per-tensor tensors."""
+    specs = synth.config_resnet50(2)
+    items = H.items_from_specs(specs, DEV)
+    for it in items:
+        if it.kind == synth.ACTIVATION:
+            it.qrun = it.x * 0.98 + 0.003
+    r1 = H.run_gpu(items)
+    c1 = [it.codes.clone() for it in items]
+    r2 = H.run_gpu(items, fused=True)
     assert r1.params.tobytes() == r2.params.tobytes()
     assert r1.sums.tobytes() == r2.sums.tobytes()
     assert r1.pair.tobytes() == r2.pair.tobytes()

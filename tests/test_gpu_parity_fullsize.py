@@ -25,5 +25,12 @@ def test_resnet50_batch256_full_pass():
     rows = H.check_all(items, res)
     order = H.check_ranking(items, res, rows)
     assert sorted(order) == list(range(54))
+    print("fused fake-quant + pair call ...", flush=True)
+    codes = [it.codes for it in items]
+    res2 = H.run_gpu(items, fused=True)            # fresh code buffers
+    assert res2.params.tobytes() == res.params.tobytes()
+    assert res2.sums.tobytes() == res.sums.tobytes()
+    assert res2.pair.tobytes() == res.pair.tobytes()
+    assert all(torch.equal(a, it.codes) for a, it in zip(codes, items))
     del items
     torch.cuda.empty_cache()
