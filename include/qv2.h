@@ -146,8 +146,10 @@ int32_t qv2_plan_num_tensors(const qv2_plan* plan);
 int64_t qv2_plan_num_segments(const qv2_plan* plan);
 /* Index of the first segment of tensor `t` (-1 if out of range). */
 int64_t qv2_plan_segment_begin(const qv2_plan* plan, int32_t t);
-/* Tile counts, for diagnostics and tests. */
+/* Tile counts, for diagnostics and tests: tiles of the calibration pass, of the
+ * quantize passes (shorter stream tiles) and of the pair pass. */
 int64_t qv2_plan_num_tiles(const qv2_plan* plan);
+int64_t qv2_plan_num_quant_tiles(const qv2_plan* plan);
 int64_t qv2_plan_num_pair_tiles(const qv2_plan* plan);
 /* Bytes of device workspace any device call on this plan needs (256-byte
  * aligned base).  Calls that may overlap in time need separate workspaces. */
@@ -192,9 +194,9 @@ qv2_status qv2_pair_metrics(qv2_plan* plan, qv2_pair_sums* d_pair_sums,
  * Both comparisons of step 3 (tensor vs its dequantized form, Eq. 6-7; fp32-run
  * vs quantized-run output, Algorithm 2) are taken in the same visit of x.
  * Arguments as in the two separate calls.  Codes, sum_x2 and sum_e2 are
- * bit-identical to qv2_fakequant_metrics; the pair sums are bit-identical to
- * qv2_pair_metrics for per-tensor-scheme tensors whose x and qrun share their
- * offset within 16 bytes, and equal up to fp64 summation order otherwise. */
+ * bit-identical to qv2_fakequant_metrics; the pair sums equal those of
+ * qv2_pair_metrics up to fp64 summation order (the two passes cut tensors into
+ * tiles of different length). */
 qv2_status qv2_fakequant_pair_metrics(qv2_plan* plan, const qv2_qparams* d_params,
                                       qv2_sums* d_sums, qv2_pair_sums* d_pair_sums,
                                       void* d_workspace, size_t workspace_bytes, void* hip_stream);

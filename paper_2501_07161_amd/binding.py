@@ -24,7 +24,8 @@ QV2_ASYM_TENSOR, QV2_SYM_TENSOR, QV2_SYM_CHANNEL = 0, 1, 2
 
 EXPORTS = (
     "qv2_plan_create", "qv2_plan_destroy", "qv2_plan_num_tensors", "qv2_plan_num_segments",
-    "qv2_plan_segment_begin", "qv2_plan_num_tiles", "qv2_plan_num_pair_tiles",
+    "qv2_plan_segment_begin", "qv2_plan_num_tiles", "qv2_plan_num_quant_tiles",
+    "qv2_plan_num_pair_tiles",
     "qv2_workspace_bytes", "qv2_calibrate", "qv2_fakequant_metrics", "qv2_pair_metrics",
     "qv2_fakequant_pair_metrics", "qv2_plan_set_timing", "qv2_plan_kernel_ms",
     "qv2_finalize", "qv2_pair_finalize", "qv2_rank_config_default", "qv2_rank",
@@ -79,7 +80,8 @@ def lib():
         L.qv2_plan_destroy.restype = None
         L.qv2_plan_num_tensors.argtypes = [vp]
         L.qv2_plan_num_tensors.restype = i32
-        for n in ("qv2_plan_num_segments", "qv2_plan_num_tiles", "qv2_plan_num_pair_tiles"):
+        for n in ("qv2_plan_num_segments", "qv2_plan_num_tiles", "qv2_plan_num_quant_tiles",
+                  "qv2_plan_num_pair_tiles"):
             getattr(L, n).argtypes = [vp]
             getattr(L, n).restype = i64
         L.qv2_plan_segment_begin.argtypes = [vp, i32]
@@ -152,6 +154,7 @@ class Plan:
         self.num_tensors = L.qv2_plan_num_tensors(handle)
         self.num_segments = L.qv2_plan_num_segments(handle)
         self.num_tiles = L.qv2_plan_num_tiles(handle)
+        self.num_quant_tiles = L.qv2_plan_num_quant_tiles(handle)
         self.num_pair_tiles = L.qv2_plan_num_pair_tiles(handle)
         self.workspace_bytes = L.qv2_workspace_bytes(handle)
         self.segment_begin = [L.qv2_plan_segment_begin(handle, t) for t in range(self.num_tensors)]

@@ -13,20 +13,21 @@
 
 using qv2::PairTensor;
 using qv2::Segment;
-using qv2::TensorDesc;
+using qv2::TensorInfo;
 using qv2::Tile;
 
 namespace {
 
 size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
-int32_t tile_elems_from_env() {
-  const char* e = std::getenv("QV2_TILE_ELEMS");
-  if (!e || !*e) return qv2::kDefaultTile;
+// Tile length from an environment variable (tuning sweeps), else the default.
+int32_t tile_from_env(const char* name, int32_t dflt) {
+  const char* e = std::getenv(name);
+  if (!e || !*e) return dflt;
   long v = std::strtol(e, nullptr, 10);
-  if (v < 1024) v = 1024;
+  if (v < 256) v = 256;
   if (v > (1L << 22)) v = 1L << 22;
-  return static_cast<int32_t>(v / 1024 * 1024);
+  return static_cast<int32_t>(v / 4 * 4);
 }
 
 }  // namespace
@@ -37,134 +38,146 @@ qv2_status qv2_plan_create(const qv2_tensor* h_tensors, int32_t n_tensors, qv2_p
   if (!h_tensors || !out) return QV2_ERR_NULL;
   *out = nullptr;
   if (n_tensors <= 0) return QV2_ERR_SHAPE;
+  const int64_t kMax = std::numeric_limits<int32_t>::max();
+
+  // validate, and count the row-group partials: they are numbered first
+  int64_t n_row_parts = 0, n_segments = 0;
+  for (int32_t t = 0; t < n_tensors; ++t) {
+    const qv2_tensor& in = h_tensors[t];
+    if (!in.x) return QV2_ERR_NULL;
+    if (in.numel <= 0) return QV2_ERR_SHAPE;
+    if (in.scheme != QV2_ASYM_TENSOR && in.scheme != QV2_SYM_TENSOR && in.scheme != QV2_SYM_CHANNEL)
+      return QV2_ERR_SCHEME;
+    const bool per_channel = in.scheme == QV2_SYM_CHANNEL;
+    if (per_channel ? (in.channels <= 0 || in.numel % in.channels != 0) : in.channels != 1)
+      return QV2_ERR_SHAPE;
+    if ((reinterpret_cast<uintptr_t>(in.x) & 3u) ||
+        (in.qrun && (reinterpret_cast<uintptr_t>(in.qrun) & 3u))) return QV2_ERR_ALIGN;
+    const int64_t nseg = per_channel ? in.channels : 1;
+    n_segments += nseg;
+    if (per_channel && in.numel / nseg <= qv2::kRowGroupCap) n_row_parts += nseg;
+    if (n_segments > kMax) return QV2_ERR_SHAPE;
+  }
 
   qv2_plan* p = new (std::nothrow) qv2_plan();
   if (!p) return QV2_ERR_HIP;
-  p->tile_elems = tile_elems_from_env();
-  const int64_t T = p->tile_elems;
-  const int64_t kMax = std::numeric_limits<int32_t>::max();
+  p->read_tile = tile_from_env("QV2_TILE_ELEMS", qv2::kDefaultReadTile);
+  p->quant_tile = tile_from_env("QV2_QUANT_TILE_ELEMS", qv2::kDefaultQuantTile);
+  const int64_t TR = p->read_tile, TQ = p->quant_tile;
 
-  std::vector<Tile> row_tiles;
-  int64_t n_parts = 0, n_pair_parts = 0;
+  int64_t row_part = 0;                      // next row-group partial (same in both numberings)
+  int64_t sp = n_row_parts, ep = n_row_parts, pp = 0;   // next stream partial: stats / quantize / pair
   qv2_status err = QV2_OK;
 
-  for (int32_t t = 0; t < n_tensors && err == QV2_OK; ++t) {
-    const qv2_tensor& in = h_tensors[t];
-    if (!in.x) { err = QV2_ERR_NULL; break; }
-    if (in.numel <= 0) { err = QV2_ERR_SHAPE; break; }
-    if (in.scheme != QV2_ASYM_TENSOR && in.scheme != QV2_SYM_TENSOR &&
-        in.scheme != QV2_SYM_CHANNEL) { err = QV2_ERR_SCHEME; break; }
-    const bool per_channel = in.scheme == QV2_SYM_CHANNEL;
-    if (per_channel ? (in.channels <= 0 || in.numel % in.channels != 0) : in.channels != 1) {
-      err = QV2_ERR_SHAPE; break;
-    }
-    if ((reinterpret_cast<uintptr_t>(in.x) & 3u) ||
-        (in.qrun && (reinterpret_cast<uintptr_t>(in.qrun) & 3u))) { err = QV2_ERR_ALIGN; break; }
+  auto make_tile = [](const qv2_tensor& in, int32_t t, int64_t off, int64_t len) {
+    Tile tl{};
+    tl.x = in.x + off;
+    tl.q = in.qrun ? in.qrun + off : nullptr;
+    tl.c = in.codes ? in.codes + off : nullptr;
+    tl.len = static_cast<int32_t>(len);
+    tl.tensor = t;
+    return tl;
+  };
 
+  for (int32_t t = 0; t < n_tensors; ++t) {
+    const qv2_tensor& in = h_tensors[t];
+    const bool per_channel = in.scheme == QV2_SYM_CHANNEL;
     const int64_t nseg = per_channel ? in.channels : 1;
     const int64_t inner = in.numel / nseg;
     const int64_t seg0 = static_cast<int64_t>(p->segments.size());
-    if (seg0 + nseg > kMax) { err = QV2_ERR_SHAPE; break; }
-    const int64_t tensor_part0 = n_parts;
+    p->info.push_back(TensorInfo{in.numel, static_cast<int32_t>(seg0), static_cast<int32_t>(nseg)});
 
-    TensorDesc d{};
-    d.x = in.x; d.qrun = in.qrun; d.codes = in.codes; d.numel = in.numel;
-    d.seg0 = static_cast<int32_t>(seg0); d.nseg = static_cast<int32_t>(nseg);
-    d.scheme = in.scheme;
-    p->descs.push_back(d);
-    p->tensors.push_back(in);
-
+    PairTensor ft{};                         // this tensor's partials in the quantize numbering
     if (per_channel && inner <= qv2::kRowGroupCap) {
       // whole rows per tile; every row is its own segment with one partial
       const int64_t rpt = std::min<int64_t>(qv2::kRowGroupMaxRows, qv2::kRowGroupCap / inner);
+      ft.part0 = static_cast<int32_t>(row_part); ft.nparts = static_cast<int32_t>(nseg);
       for (int64_t r0 = 0; r0 < nseg; r0 += rpt) {
         const int64_t rows = std::min(rpt, nseg - r0);
-        Tile tl{};
-        tl.off = r0 * inner; tl.len = static_cast<int32_t>(rows * inner); tl.tensor = t;
-        tl.part0 = static_cast<int32_t>(n_parts + r0); tl.rows = static_cast<int32_t>(rows);
+        Tile tl = make_tile(in, t, r0 * inner, rows * inner);
+        tl.part0 = static_cast<int32_t>(row_part + r0); tl.rows = static_cast<int32_t>(rows);
         tl.seg0 = static_cast<int32_t>(seg0 + r0); tl.inner = static_cast<int32_t>(inner);
-        row_tiles.push_back(tl);
+        p->row_tiles.push_back(tl);
       }
       for (int64_t r = 0; r < nseg; ++r) {
         Segment s{};
-        s.n = inner; s.part0 = static_cast<int32_t>(n_parts + r); s.nparts = 1; s.scheme = in.scheme;
+        s.n = inner; s.scheme = in.scheme;
+        s.sp0 = s.ep0 = static_cast<int32_t>(row_part + r); s.snp = s.enp = 1;
         p->segments.push_back(s);
       }
-      n_parts += nseg;
+      row_part += nseg;
     } else {
-      const int64_t tiles_per_seg = (inner + T - 1) / T;
-      if (tiles_per_seg > kMax || n_parts + nseg * tiles_per_seg > kMax) { err = QV2_ERR_SHAPE; break; }
+      const int64_t n_read = (inner + TR - 1) / TR, n_quant = (inner + TQ - 1) / TQ;
+      if (sp + nseg * n_read > kMax || ep + nseg * n_quant > kMax) { err = QV2_ERR_SHAPE; break; }
+      ft.part0 = static_cast<int32_t>(ep); ft.nparts = static_cast<int32_t>(nseg * n_quant);
       for (int64_t s = 0; s < nseg; ++s) {
         Segment sg{};
-        sg.n = inner; sg.part0 = static_cast<int32_t>(n_parts);
-        sg.nparts = static_cast<int32_t>(tiles_per_seg); sg.scheme = in.scheme;
+        sg.n = inner; sg.scheme = in.scheme;
+        sg.sp0 = static_cast<int32_t>(sp); sg.snp = static_cast<int32_t>(n_read);
+        sg.ep0 = static_cast<int32_t>(ep); sg.enp = static_cast<int32_t>(n_quant);
         p->segments.push_back(sg);
-        for (int64_t k = 0; k < tiles_per_seg; ++k) {
-          Tile tl{};
-          tl.off = s * inner + k * T;
-          tl.len = static_cast<int32_t>(std::min<int64_t>(T, inner - k * T));
-          tl.tensor = t; tl.part0 = static_cast<int32_t>(n_parts++); tl.rows = 0;
-          tl.seg0 = static_cast<int32_t>(seg0 + s); tl.inner = 0;
-          p->tiles.push_back(tl);
+        for (int64_t k = 0; k < n_read; ++k) {
+          Tile tl = make_tile(in, t, s * inner + k * TR, std::min<int64_t>(TR, inner - k * TR));
+          tl.part0 = static_cast<int32_t>(sp++); tl.seg0 = static_cast<int32_t>(seg0 + s);
+          p->read_tiles.push_back(tl);
+        }
+        for (int64_t k = 0; k < n_quant; ++k) {
+          Tile tl = make_tile(in, t, s * inner + k * TQ, std::min<int64_t>(TQ, inner - k * TQ));
+          tl.part0 = static_cast<int32_t>(ep++); tl.seg0 = static_cast<int32_t>(seg0 + s);
+          p->quant_tiles.push_back(tl);
         }
       }
     }
-
-    PairTensor ft{};
-    if (in.qrun) {
-      ft.n = in.numel; ft.part0 = static_cast<int32_t>(tensor_part0);
-      ft.nparts = static_cast<int32_t>(n_parts - tensor_part0);
-    }
+    if (in.qrun) ft.n = in.numel; else ft = PairTensor{};
     p->fused_pair_tensors.push_back(ft);
 
     PairTensor pt{};
     if (in.qrun) {
-      const int64_t nt = (in.numel + T - 1) / T;
-      if (n_pair_parts + nt > kMax) { err = QV2_ERR_SHAPE; break; }
-      pt.n = in.numel; pt.part0 = static_cast<int32_t>(n_pair_parts); pt.nparts = static_cast<int32_t>(nt);
+      const int64_t nt = (in.numel + TR - 1) / TR;
+      if (pp + nt > kMax) { err = QV2_ERR_SHAPE; break; }
+      pt.n = in.numel; pt.part0 = static_cast<int32_t>(pp); pt.nparts = static_cast<int32_t>(nt);
       for (int64_t k = 0; k < nt; ++k) {
-        Tile tl{};
-        tl.off = k * T; tl.len = static_cast<int32_t>(std::min<int64_t>(T, in.numel - k * T));
-        tl.tensor = t; tl.part0 = static_cast<int32_t>(n_pair_parts++);
+        Tile tl = make_tile(in, t, k * TR, std::min<int64_t>(TR, in.numel - k * TR));
+        tl.part0 = static_cast<int32_t>(pp++);
         p->pair_tiles.push_back(tl);
       }
     }
     p->pair_tensors.push_back(pt);
   }
-
-  if (err == QV2_OK &&
-      static_cast<int64_t>(p->tiles.size() + row_tiles.size()) > kMax) err = QV2_ERR_SHAPE;
   if (err != QV2_OK) { delete p; return err; }
 
-  for (size_t i = 0; i < p->segments.size(); ++i)
-    if (p->segments[i].nparts > qv2::kFoldWaveMax) p->big_segments.push_back(static_cast<int32_t>(i));
-  for (size_t i = 0; i < p->pair_tensors.size(); ++i)
+  for (size_t i = 0; i < p->segments.size(); ++i) {
+    if (p->segments[i].snp > qv2::kFoldWaveMax) p->big_stat_segments.push_back(static_cast<int32_t>(i));
+    if (p->segments[i].enp > qv2::kFoldWaveMax) p->big_err_segments.push_back(static_cast<int32_t>(i));
+  }
+  for (size_t i = 0; i < p->pair_tensors.size(); ++i) {
     if (p->pair_tensors[i].nparts > qv2::kFoldWaveMax) p->big_pair_tensors.push_back(static_cast<int32_t>(i));
-  for (size_t i = 0; i < p->fused_pair_tensors.size(); ++i)
     if (p->fused_pair_tensors[i].nparts > qv2::kFoldWaveMax)
       p->big_fused_pair_tensors.push_back(static_cast<int32_t>(i));
-  p->n_stream_tiles = static_cast<int64_t>(p->tiles.size());
-  p->tiles.insert(p->tiles.end(), row_tiles.begin(), row_tiles.end());
-  p->n_parts = n_parts;
-  const size_t need = std::max(static_cast<size_t>(n_parts) * sizeof(qv2::StatPartial),
-                               static_cast<size_t>(n_pair_parts) * sizeof(qv2::ErrPartial));
+  }
+  const size_t need = std::max({static_cast<size_t>(sp) * sizeof(qv2::StatPartial),
+                                static_cast<size_t>(ep) * sizeof(qv2::ErrPartial3),
+                                static_cast<size_t>(pp) * sizeof(qv2::ErrPartial)});
   p->workspace_bytes = std::max<size_t>(256, round_up(need, 256));
   *out = p;
   return QV2_OK;
 }
 
 int32_t qv2_plan_num_tensors(const qv2_plan* plan) {
-  return plan ? static_cast<int32_t>(plan->tensors.size()) : 0;
+  return plan ? static_cast<int32_t>(plan->info.size()) : 0;
 }
 int64_t qv2_plan_num_segments(const qv2_plan* plan) {
   return plan ? static_cast<int64_t>(plan->segments.size()) : 0;
 }
 int64_t qv2_plan_segment_begin(const qv2_plan* plan, int32_t t) {
-  if (!plan || t < 0 || t >= static_cast<int32_t>(plan->descs.size())) return -1;
-  return plan->descs[t].seg0;
+  if (!plan || t < 0 || t >= static_cast<int32_t>(plan->info.size())) return -1;
+  return plan->info[t].seg0;
 }
 int64_t qv2_plan_num_tiles(const qv2_plan* plan) {
-  return plan ? static_cast<int64_t>(plan->tiles.size()) : 0;
+  return plan ? static_cast<int64_t>(plan->read_tiles.size() + plan->row_tiles.size()) : 0;
+}
+int64_t qv2_plan_num_quant_tiles(const qv2_plan* plan) {
+  return plan ? static_cast<int64_t>(plan->quant_tiles.size() + plan->row_tiles.size()) : 0;
 }
 int64_t qv2_plan_num_pair_tiles(const qv2_plan* plan) {
   return plan ? static_cast<int64_t>(plan->pair_tiles.size()) : 0;
@@ -183,8 +196,8 @@ qv2_status qv2_finalize(const qv2_plan* plan, const qv2_qparams* h_params,
                         const qv2_sums* h_sums, qv2_metrics* h_out) {
   if (!plan || !h_params || !h_sums || !h_out) return QV2_ERR_NULL;
   bool finite = true;
-  for (size_t t = 0; t < plan->descs.size(); ++t) {
-    const TensorDesc& d = plan->descs[t];
+  for (size_t t = 0; t < plan->info.size(); ++t) {
+    const TensorInfo& d = plan->info[t];
     double sx = 0.0, sx2 = 0.0, se2 = 0.0;
     float mn = std::numeric_limits<float>::infinity(), mx = -mn;
     for (int32_t s = d.seg0; s < d.seg0 + d.nseg; ++s) {

@@ -6,52 +6,68 @@
 
 #include "qv2.h"
 
+// Compile-time tuning knobs (defaults are the measured best on MI355X).
+#ifndef QV2_BLOCK_READ
+#define QV2_BLOCK_READ 512     // threads of the read-only stream kernels (stats, pair)
+#endif
+#ifndef QV2_BLOCK_QUANT
+#define QV2_BLOCK_QUANT 256    // threads of the quantize kernels (they also store codes)
+#endif
+#ifndef QV2_BLOCK_ROWS
+#define QV2_BLOCK_ROWS 512     // threads of the row-group kernels
+#endif
+#ifndef QV2_VEC_QUANT
+#define QV2_VEC_QUANT 2        // 16-byte loads per lane and stream in one batch of a quantize kernel
+#endif
+
 namespace qv2 {
 
-// Threads per workgroup of every tile kernel (8 wavefronts of 64).
-#ifndef QV2_BLOCK
-#define QV2_BLOCK 512
-#endif
-constexpr int kBlock = QV2_BLOCK;
+constexpr int kBlockRead = QV2_BLOCK_READ;
+constexpr int kBlockQuant = QV2_BLOCK_QUANT;
+constexpr int kBlockRows = QV2_BLOCK_ROWS;
+constexpr int kVecQuant = QV2_VEC_QUANT;
+
 // Largest row-group tile in elements: it is staged whole in LDS (32 KiB).
 constexpr int kRowGroupCap = 8192;
 // Most rows one row-group tile may hold.
 constexpr int kRowGroupMaxRows = 1024;
-// Default stream-tile length in elements (128 KiB of fp32).
-constexpr int kDefaultTile = 32768;
+// Stream-tile length of the read-only passes (128 KiB of fp32): long tiles amortise the
+// per-workgroup reduction.
+constexpr int kDefaultReadTile = 32768;
+// Stream-tile length of the quantize passes: exactly one batch per lane
+// (block x kVecQuant x 4 elements).  A kernel that mixes code stores into the read stream
+// runs fastest when all in-flight workgroups sweep a narrow address window.
+constexpr int kDefaultQuantTile = kBlockQuant * kVecQuant * 4;
 // A segment (or pair tensor) with more partials than this is folded by a whole
 // 1024-thread workgroup instead of one wavefront.
 constexpr int kFoldWaveMax = 128;
 
-struct TensorDesc {            // 48 B, device copy indexed by tensor
-  const float* x;
-  const float* qrun;
-  int8_t* codes;
-  int64_t numel;
-  int32_t seg0;                // first segment of this tensor
-  int32_t nseg;
-  int32_t scheme;
-  int32_t _pad;
-};
-
-// A tile is a contiguous element range of one tensor.
+// A tile is a contiguous element range of one tensor, addressed absolutely so that a
+// workgroup needs one 64-byte scalar load before it can issue its data loads.
 //  rows == 0 : stream tile, part of ONE segment (seg0); yields one partial (part0).
 //  rows  > 0 : row-group tile, `rows` whole segments of `inner` elements each,
 //              starting at segment seg0; yields `rows` partials from part0.
-struct Tile {                  // 32 B
-  int64_t off;                 // element offset inside the tensor
+struct Tile {                  // 64 B
+  const float* x;              // first element of the tile
+  const float* q;              // same position in the quantized-run tensor, or null
+  int8_t* c;                   // same position in the code buffer, or null
   int32_t len;                 // elements
-  int32_t tensor;
   int32_t part0;
-  int32_t rows;
   int32_t seg0;
+  int32_t rows;
   int32_t inner;
+  int32_t tensor;
+  int32_t _pad[4];
 };
+static_assert(sizeof(Tile) == 64, "Tile must stay one 64-byte record");
 
-struct Segment {               // 24 B
+// Partial slots come in two numberings: `sp` for the calibration pass (read tiles) and
+// `ep` for the quantize passes (quantize tiles).  Row-group partials have the same index
+// in both (they come first); stream partials follow.
+struct Segment {               // 32 B
   int64_t n;                   // elements in the segment
-  int32_t part0;               // its partials, in element order
-  int32_t nparts;
+  int32_t sp0, snp;            // calibration partials, in element order
+  int32_t ep0, enp;            // quantize partials, in element order
   int32_t scheme;
   int32_t _pad;
 };
@@ -62,41 +78,47 @@ struct PairTensor {            // 16 B, one per tensor of the plan
   int32_t nparts;
 };
 
+struct TensorInfo {            // host only
+  int64_t numel;
+  int32_t seg0, nseg;
+};
+
 // Partial records the tile kernels leave in the workspace.
 struct StatPartial { float mn, mx; double sx, sx2; };   // calibrate, 24 B
-struct ErrPartial { double sx2, se2; };                 // fakequant and pair, 16 B
-struct ErrPartial3 { double sx2, se2, sd2; };           // fused fakequant + pair, 24 B
+struct ErrPartial { double sx2, se2; };                 // pair pass, 16 B
+struct ErrPartial3 { double sx2, se2, sd2; };           // quantize passes, 24 B
 
 }  // namespace qv2
 
 struct qv2_plan {
-  std::vector<qv2_tensor> tensors;
-  std::vector<qv2::TensorDesc> descs;
-  std::vector<qv2::Tile> tiles;          // stream tiles first, then row-group tiles
+  std::vector<qv2::TensorInfo> info;
+  std::vector<qv2::Tile> read_tiles;     // calibration: stream tiles (read size)
+  std::vector<qv2::Tile> quant_tiles;    // quantize passes: stream tiles (quantize size)
+  std::vector<qv2::Tile> row_tiles;      // row-group tiles, used by both
+  std::vector<qv2::Tile> pair_tiles;     // pair pass: stream tiles over tensors with qrun
   std::vector<qv2::Segment> segments;
-  std::vector<qv2::Tile> pair_tiles;     // stream tiles over tensors with qrun
-  std::vector<qv2::PairTensor> pair_tensors;
-  std::vector<int32_t> big_segments;      // segments with > kFoldWaveMax partials
-  std::vector<int32_t> big_pair_tensors;  // pair tensors with > kFoldWaveMax partials
-  // fused fake-quant + pair pass: a tensor's pair energy is folded from ALL its partial
-  // slots of the main tile table (they are contiguous per tensor)
-  std::vector<qv2::PairTensor> fused_pair_tensors;
+  std::vector<qv2::PairTensor> pair_tensors;        // partial ranges of the pair pass
+  std::vector<qv2::PairTensor> fused_pair_tensors;  // ranges in the quantize numbering
+  std::vector<int32_t> big_stat_segments;   // segments with > kFoldWaveMax calibration partials
+  std::vector<int32_t> big_err_segments;    // ... quantize partials
+  std::vector<int32_t> big_pair_tensors;
   std::vector<int32_t> big_fused_pair_tensors;
-  int64_t n_stream_tiles = 0;
-  int64_t n_parts = 0;
-  int32_t tile_elems = qv2::kDefaultTile;
+  int32_t read_tile = qv2::kDefaultReadTile;
+  int32_t quant_tile = qv2::kDefaultQuantTile;
   size_t workspace_bytes = 0;
 
   // device copy (made by the first device call, on the device current then)
   void* d_blob = nullptr;
-  qv2::TensorDesc* d_descs = nullptr;
-  qv2::Tile* d_tiles = nullptr;
-  qv2::Segment* d_segments = nullptr;
+  qv2::Tile* d_read_tiles = nullptr;
+  qv2::Tile* d_quant_tiles = nullptr;
+  qv2::Tile* d_row_tiles = nullptr;
   qv2::Tile* d_pair_tiles = nullptr;
+  qv2::Segment* d_segments = nullptr;
   qv2::PairTensor* d_pair_tensors = nullptr;
-  int32_t* d_big_segments = nullptr;
-  int32_t* d_big_pair_tensors = nullptr;
   qv2::PairTensor* d_fused_pair_tensors = nullptr;
+  int32_t* d_big_stat_segments = nullptr;
+  int32_t* d_big_err_segments = nullptr;
+  int32_t* d_big_pair_tensors = nullptr;
   int32_t* d_big_fused_pair_tensors = nullptr;
 
   // optional per-kernel timing (qv2_plan_set_timing): hipEvent_t handles

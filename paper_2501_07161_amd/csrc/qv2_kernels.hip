@@ -4,12 +4,21 @@
 // the plan: a workgroup owns one tile, reduces it and leaves one partial record
 // per (tile, segment) in the workspace; a second small launch folds each
 // segment's partials in a fixed order.  No floating-point atomics anywhere, so
-// results are bit-stable.  The work is HBM-bound (4, 5 and 8 bytes per element
-// for the three passes); MFMA has no role here.
+// results are bit-stable.  The work is HBM-bound (4, 5, 8 and 9 bytes per
+// element for the passes); MFMA has no role here.
 //
 // Compiled with -ffp-contract=off: the quantizer's fp32 steps (Sec. 2.1 Eq. 1-3,
 // Sec. 4 Eq. 4-5) must each round once.  Fused multiply-adds appear only where
-// written explicitly (energy accumulation).
+// written explicitly (fp64 energy accumulation).
+//
+// Two things the code generator needs to be told:
+//  - tensor pointers come out of the tile table, so their address space is
+//    unknown to the compiler; every access casts them to the global address
+//    space, which turns flat_load into global_load and lets the wait-count
+//    pass keep many loads in flight instead of draining them all;
+//  - whether codes are stored as packed dwords, as bytes or not at all is
+//    decided once per tile and selects a fully specialised loop, so the loop
+//    body has no branches and all of a batch's loads are issued up front.
 #include <hip/hip_runtime.h>
 
 #include <cfloat>
@@ -21,27 +30,44 @@ using namespace qv2;
 
 namespace {
 
+#define QV2_GLOBAL __attribute__((address_space(1)))
+
+typedef float f4 __attribute__((ext_vector_type(4)));
+typedef const QV2_GLOBAL f4* gf4_ptr;
+typedef const QV2_GLOBAL float* gf_ptr;
+typedef QV2_GLOBAL uint32_t* gu32_ptr;
+typedef QV2_GLOBAL int8_t* gi8_ptr;
+
 constexpr int kWave = 64;
-constexpr int kWaves = kBlock / kWave;
-#ifndef QV2_UNROLL
-#define QV2_UNROLL 8
+#ifndef QV2_VEC_READ
+#define QV2_VEC_READ 8              // 16-byte loads in flight per lane, read-only kernels
 #endif
 #ifndef QV2_NT_LOADS
-#define QV2_NT_LOADS 1             // measured: +12 % HBM rate on the read-only passes
+#define QV2_NT_LOADS 1              // measured: +12 % HBM rate on the read-only passes
 #endif
 #ifndef QV2_NT_STORES
 #define QV2_NT_STORES 1
 #endif
-#ifndef QV2_PAIR_UNROLL
-#define QV2_PAIR_UNROLL (QV2_UNROLL / 2)
-#endif
-constexpr int kUnroll = QV2_UNROLL;  // independent 16-byte loads in flight per lane
-constexpr int kPairUnroll = QV2_PAIR_UNROLL;  // per stream, in the two-stream kernels
-#ifndef QV2_PIPELINE
-#define QV2_PIPELINE 1
-#endif
+constexpr int kVecRead = QV2_VEC_READ;
 constexpr int kFoldBlock = 1024;    // workgroup that folds one segment with many partials
-constexpr int kFoldWaves = kFoldBlock / kWave;
+
+// 16-byte streaming load of data that is read once per pass.
+__device__ __forceinline__ f4 ld4(gf4_ptr p) {
+#if QV2_NT_LOADS
+  return __builtin_nontemporal_load(p);
+#else
+  return *p;
+#endif
+}
+
+// Packed int8 codes are written once and not read again by this library.
+__device__ __forceinline__ void st_codes(gu32_ptr p, uint32_t v) {
+#if QV2_NT_STORES
+  __builtin_nontemporal_store(v, p);
+#else
+  *p = v;
+#endif
+}
 
 // ---------------------------------------------------------------------------
 // wavefront / workgroup reductions (fixed butterfly order => deterministic)
@@ -59,39 +85,43 @@ __device__ __forceinline__ double group_sum(double v, int w) {
   return v;
 }
 
-// Sum of two doubles over the workgroup; result valid in thread 0.
-__device__ __forceinline__ void block_sum2(double& a, double& b) {
-  __shared__ double sa[kWaves], sb[kWaves];
-  a = group_sum(a, kWave);
-  b = group_sum(b, kWave);
+// Sums of up to three doubles over a workgroup of BLOCK threads; valid in thread 0.
+template <int BLOCK>
+__device__ __forceinline__ void block_sum3(double& a, double& b, double& c) {
+  constexpr int W = BLOCK / kWave;
+  a = group_sum(a, kWave); b = group_sum(b, kWave); c = group_sum(c, kWave);
+  if (W == 1) return;
+  __shared__ double s[3][W];
   const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
-  if (lane == 0) { sa[wave] = a; sb[wave] = b; }
+  if (lane == 0) { s[0][wave] = a; s[1][wave] = b; s[2][wave] = c; }
   __syncthreads();
   if (threadIdx.x == 0) {
-    a = sa[0]; b = sb[0];
-    for (int i = 1; i < kWaves; ++i) { a += sa[i]; b += sb[i]; }
+    a = s[0][0]; b = s[1][0]; c = s[2][0];
+    for (int i = 1; i < W; ++i) { a += s[0][i]; b += s[1][i]; c += s[2][i]; }
   }
 }
 
+template <int BLOCK>
 __device__ __forceinline__ void block_minmax(float& mn, float& mx) {
-  __shared__ float smn[kWaves], smx[kWaves];
-  mn = group_min(mn, kWave);
-  mx = group_max(mx, kWave);
+  constexpr int W = BLOCK / kWave;
+  mn = group_min(mn, kWave); mx = group_max(mx, kWave);
+  if (W == 1) return;
+  __shared__ float s[2][W];
   const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
-  if (lane == 0) { smn[wave] = mn; smx[wave] = mx; }
+  if (lane == 0) { s[0][wave] = mn; s[1][wave] = mx; }
   __syncthreads();
   if (threadIdx.x == 0) {
-    mn = smn[0]; mx = smx[0];
-    for (int i = 1; i < kWaves; ++i) { mn = fminf(mn, smn[i]); mx = fmaxf(mx, smx[i]); }
+    mn = s[0][0]; mx = s[1][0];
+    for (int i = 1; i < W; ++i) { mn = fminf(mn, s[0][i]); mx = fmaxf(mx, s[1][i]); }
   }
 }
 
-// Four independent fp64 accumulators, one per float4 component.  Energies are
+// Four independent fp64 accumulators, one per vector component.  Energies are
 // accumulated in fp64 from the first element on, so the whole fp32 range of
 // inputs is safe (x*x can leave the fp32 range) and no fp32 rounding builds up.
 struct Acc4 {
   double a = 0.0, b = 0.0, c = 0.0, d = 0.0;
-  __device__ __forceinline__ void add(const float4& v) {
+  __device__ __forceinline__ void add(const f4& v) {
     a += static_cast<double>(v.x); b += static_cast<double>(v.y);
     c += static_cast<double>(v.z); d += static_cast<double>(v.w);
   }
@@ -101,26 +131,6 @@ struct Acc4 {
   }
   __device__ __forceinline__ double total() const { return (a + b) + (c + d); }
 };
-
-// 16-byte streaming load of data that is read once per pass.
-__device__ __forceinline__ float4 ld4(const float4* p) {
-#if QV2_NT_LOADS
-  typedef float vf4 __attribute__((ext_vector_type(4)));
-  const vf4 v = __builtin_nontemporal_load(reinterpret_cast<const vf4*>(p));
-  return make_float4(v.x, v.y, v.z, v.w);
-#else
-  return *p;
-#endif
-}
-
-// Packed int8 codes are written once and not read again by this library.
-__device__ __forceinline__ void st_codes(uint32_t* p, uint32_t v) {
-#if QV2_NT_STORES
-  __builtin_nontemporal_store(v, p);
-#else
-  *p = v;
-#endif
-}
 
 // Elements before the first 16-byte boundary of p (0..3, capped by len).
 __device__ __forceinline__ int head_elems(const void* p, int len) {
@@ -144,7 +154,7 @@ __device__ __forceinline__ float quant1(float x, const QP& q, float& err) {
   return c;
 }
 
-__device__ __forceinline__ uint32_t quant4(const float4& v, const QP& q, Acc4& se2, Acc4& sx2) {
+__device__ __forceinline__ uint32_t quant4(const f4& v, const QP& q, Acc4& se2, Acc4& sx2) {
   float e0, e1, e2, e3;
   const int c0 = static_cast<int>(quant1(v.x, q, e0));
   const int c1 = static_cast<int>(quant1(v.y, q, e1));
@@ -156,7 +166,7 @@ __device__ __forceinline__ uint32_t quant4(const float4& v, const QP& q, Acc4& s
          ((static_cast<uint32_t>(c2) & 0xffu) << 16) | (static_cast<uint32_t>(c3) << 24);
 }
 
-__device__ __forceinline__ QP load_qp(const qv2_qparams* params, int seg) {
+__device__ __forceinline__ QP load_qp(const qv2_qparams* __restrict__ params, int seg) {
   const qv2_qparams p = params[seg];
   return QP{p.scale, p.inv_scale, static_cast<float>(p.zp)};
 }
@@ -164,13 +174,13 @@ __device__ __forceinline__ QP load_qp(const qv2_qparams* params, int seg) {
 // ---------------------------------------------------------------------------
 // pass 1 (calibration stage, Sec. 5; x_min / x_max of Eq. 2): stream tiles
 // ---------------------------------------------------------------------------
-__global__ __launch_bounds__(kBlock) void k_stats_stream(const TensorDesc* __restrict__ descs,
-                                                         const Tile* __restrict__ tiles,
-                                                         StatPartial* __restrict__ parts) {
+template <int BLOCK, int V>
+__global__ __launch_bounds__(BLOCK) void k_stats_stream(const Tile* __restrict__ tiles,
+                                                        StatPartial* __restrict__ parts) {
   const Tile tl = tiles[blockIdx.x];
-  const float* __restrict__ p = descs[tl.tensor].x + tl.off;
+  const gf_ptr p = (gf_ptr)tl.x;
   const int len = tl.len, tid = threadIdx.x;
-  const int head = head_elems(p, len);
+  const int head = head_elems(tl.x, len);
   const int body = len - head, nvec = body >> 2, tail = body & 3;
 
   float mn = INFINITY, mx = -INFINITY;
@@ -185,17 +195,17 @@ __global__ __launch_bounds__(kBlock) void k_stats_stream(const TensorDesc* __res
     mn = fminf(mn, v); mx = fmaxf(mx, v);
     sx += v; sx2 += static_cast<double>(v) * v;
   }
-  const float4* __restrict__ v4 = reinterpret_cast<const float4*>(p + head);
-  float4 mn4 = make_float4(INFINITY, INFINITY, INFINITY, INFINITY);
-  float4 mx4 = make_float4(-INFINITY, -INFINITY, -INFINITY, -INFINITY);
+  const gf4_ptr v4 = (gf4_ptr)(tl.x + head);
+  f4 mn4 = {INFINITY, INFINITY, INFINITY, INFINITY};
+  f4 mx4 = {-INFINITY, -INFINITY, -INFINITY, -INFINITY};
   Acc4 as, as2;
-  int i = tid;
-  for (; i + (kUnroll - 1) * kBlock < nvec; i += kUnroll * kBlock) {
-    float4 r[kUnroll];
+  int base = 0;
+  for (; base + V * BLOCK <= nvec; base += V * BLOCK) {          // uniform: whole batches
+    f4 r[V];
 #pragma unroll
-    for (int u = 0; u < kUnroll; ++u) r[u] = ld4(&v4[i + u * kBlock]);
+    for (int u = 0; u < V; ++u) r[u] = ld4(v4 + base + u * BLOCK + tid);
 #pragma unroll
-    for (int u = 0; u < kUnroll; ++u) {
+    for (int u = 0; u < V; ++u) {
       mn4.x = fminf(mn4.x, r[u].x); mn4.y = fminf(mn4.y, r[u].y);
       mn4.z = fminf(mn4.z, r[u].z); mn4.w = fminf(mn4.w, r[u].w);
       mx4.x = fmaxf(mx4.x, r[u].x); mx4.y = fmaxf(mx4.y, r[u].y);
@@ -203,8 +213,8 @@ __global__ __launch_bounds__(kBlock) void k_stats_stream(const TensorDesc* __res
       as.add(r[u]); as2.add_sq(r[u].x, r[u].y, r[u].z, r[u].w);
     }
   }
-  for (; i < nvec; i += kBlock) {
-    const float4 r = ld4(&v4[i]);
+  for (int i = base + tid; i < nvec; i += BLOCK) {
+    const f4 r = ld4(v4 + i);
     mn4.x = fminf(mn4.x, r.x); mn4.y = fminf(mn4.y, r.y);
     mn4.z = fminf(mn4.z, r.z); mn4.w = fminf(mn4.w, r.w);
     mx4.x = fmaxf(mx4.x, r.x); mx4.y = fmaxf(mx4.y, r.y);
@@ -215,8 +225,9 @@ __global__ __launch_bounds__(kBlock) void k_stats_stream(const TensorDesc* __res
   mn = fminf(fminf(mn, mn4.x), fminf(fminf(mn4.y, mn4.z), mn4.w));
   mx = fmaxf(fmaxf(mx, mx4.x), fmaxf(fmaxf(mx4.y, mx4.z), mx4.w));
 
-  block_minmax(mn, mx);
-  block_sum2(sx, sx2);
+  double unused = 0.0;
+  block_minmax<BLOCK>(mn, mx);
+  block_sum3<BLOCK>(sx, sx2, unused);
   if (tid == 0) {
     StatPartial o;
     o.mn = mn; o.mx = mx; o.sx = sx; o.sx2 = sx2;
@@ -226,15 +237,17 @@ __global__ __launch_bounds__(kBlock) void k_stats_stream(const TensorDesc* __res
 
 // Copies a row-group tile into LDS with 16-byte transfers.  Element e of the
 // tile lands at xs[e + shift]; returns shift (0..3).
-__device__ __forceinline__ int stage_tile(const float* __restrict__ p, int len, float* xs) {
+template <int BLOCK>
+__device__ __forceinline__ int stage_tile(const float* x, int len, float* xs) {
   const int tid = threadIdx.x;
-  const int head = head_elems(p, len);
+  const gf_ptr p = (gf_ptr)x;
+  const int head = head_elems(x, len);
   const int shift = (4 - head) & 3;
   const int body = len - head, nvec = body >> 2, tail = body & 3;
   if (tid < head) xs[shift + tid] = p[tid];
-  const float4* __restrict__ v4 = reinterpret_cast<const float4*>(p + head);
-  float4* d4 = reinterpret_cast<float4*>(xs + shift + head);
-  for (int i = tid; i < nvec; i += kBlock) d4[i] = v4[i];
+  const gf4_ptr v4 = (gf4_ptr)(x + head);
+  f4* d4 = reinterpret_cast<f4*>(xs + shift + head);
+  for (int i = tid; i < nvec; i += BLOCK) d4[i] = v4[i];
   if (tid < tail) xs[shift + head + (nvec << 2) + tid] = p[head + (nvec << 2) + tid];
   return shift;
 }
@@ -247,18 +260,19 @@ __device__ __forceinline__ int row_width(int inner) {
 }
 
 // pass 1, row-group tiles: many short segments (output channels) per workgroup
-__global__ __launch_bounds__(kBlock) void k_stats_rows(const TensorDesc* __restrict__ descs,
-                                                       const Tile* __restrict__ tiles,
-                                                       StatPartial* __restrict__ parts) {
+template <int BLOCK>
+__global__ __launch_bounds__(BLOCK) void k_stats_rows(const Tile* __restrict__ tiles,
+                                                      StatPartial* __restrict__ parts) {
+  constexpr int W = BLOCK / kWave;
   __shared__ __attribute__((aligned(16))) float xs[kRowGroupCap + 4];
   const Tile tl = tiles[blockIdx.x];
-  const int shift = stage_tile(descs[tl.tensor].x + tl.off, tl.len, xs);
+  const int shift = stage_tile<BLOCK>(tl.x, tl.len, xs);
   __syncthreads();
 
   const int inner = tl.inner, w = row_width(inner), gpw = kWave / w;
   const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
   const int g = lane >> __builtin_ctz(w), gl = lane & (w - 1);
-  for (int rb = wave * gpw; rb < tl.rows; rb += kWaves * gpw) {     // uniform per wavefront
+  for (int rb = wave * gpw; rb < tl.rows; rb += W * gpw) {     // uniform per wavefront
     const int r = rb + g;
     const bool live = r < tl.rows;
     float mn = INFINITY, mx = -INFINITY;
@@ -304,202 +318,181 @@ __device__ __forceinline__ void make_params(float mn, float mx, int scheme, qv2_
   }
 }
 
-// pass 1, fold: one wavefront per segment walks its partials in a fixed order
-__global__ __launch_bounds__(kBlock) void k_fold_stats(const Segment* __restrict__ segs, int nseg,
-                                                       const StatPartial* __restrict__ parts,
-                                                       qv2_qparams* __restrict__ params,
-                                                       qv2_sums* __restrict__ sums) {
-  const int seg = blockIdx.x * kWaves + (threadIdx.x >> 6);
-  const int lane = threadIdx.x & (kWave - 1);
-  if (seg >= nseg) return;
-  const Segment sg = segs[seg];
-  if (sg.nparts > kFoldWaveMax) return;            // folded by k_fold_stats_big
+// ---------------------------------------------------------------------------
+// folds.  A segment's partials are folded in a fixed order: lane- (or thread-)
+// strided, then a butterfly.  WIDE = false: one wavefront per segment, four
+// segments per 256-thread workgroup, segments with many partials are skipped;
+// WIDE = true: one 1024-thread workgroup per listed segment.
+// ---------------------------------------------------------------------------
+template <bool WIDE>
+struct FoldIdx {
+  int id, lane, stride;
+  bool active;
+  __device__ __forceinline__ FoldIdx(const int* ids, int n) {
+    if (WIDE) {
+      id = ids[blockIdx.x]; lane = threadIdx.x; stride = kFoldBlock; active = true;
+    } else {
+      id = blockIdx.x * 4 + (threadIdx.x >> 6); lane = threadIdx.x & (kWave - 1);
+      stride = kWave; active = id < n;
+    }
+  }
+};
+
+template <bool WIDE>
+__device__ __forceinline__ void fold_sum3(double& a, double& b, double& c) {
+  if (WIDE) {
+    block_sum3<kFoldBlock>(a, b, c);
+  } else {
+    a = group_sum(a, kWave); b = group_sum(b, kWave); c = group_sum(c, kWave);
+  }
+}
+
+template <bool WIDE>
+__global__ __launch_bounds__(WIDE ? kFoldBlock : 256) void k_fold_stats(
+    const Segment* __restrict__ segs, int nseg, const int* __restrict__ ids,
+    const StatPartial* __restrict__ parts, qv2_qparams* __restrict__ params,
+    qv2_sums* __restrict__ sums) {
+  const FoldIdx<WIDE> f(ids, nseg);
+  if (!f.active) return;
+  const Segment sg = segs[f.id];
+  if (!WIDE && sg.snp > kFoldWaveMax) return;      // left to the wide fold
   float mn = INFINITY, mx = -INFINITY;
-  double sx = 0.0, sx2 = 0.0;
-  for (int i = lane; i < sg.nparts; i += kWave) {
-    const StatPartial q = parts[sg.part0 + i];
+  double sx = 0.0, sx2 = 0.0, unused = 0.0;
+#pragma unroll 4
+  for (int i = f.lane; i < sg.snp; i += f.stride) {
+    const StatPartial q = parts[sg.sp0 + i];
     mn = fminf(mn, q.mn); mx = fmaxf(mx, q.mx);
     sx += q.sx; sx2 += q.sx2;
   }
-  mn = group_min(mn, kWave); mx = group_max(mx, kWave);
-  sx = group_sum(sx, kWave); sx2 = group_sum(sx2, kWave);
-  if (lane == 0) {
+  if (WIDE) {
+    block_minmax<kFoldBlock>(mn, mx);
+    __syncthreads();
+  } else {
+    mn = group_min(mn, kWave); mx = group_max(mx, kWave);
+  }
+  fold_sum3<WIDE>(sx, sx2, unused);
+  if (f.lane == 0) {
     qv2_qparams qp;
     make_params(mn, mx, sg.scheme, qp);
-    params[seg] = qp;
+    params[f.id] = qp;
     qv2_sums o;
     o.sum_x = sx; o.sum_x2 = sx2; o.sum_e2 = 0.0; o.n = sg.n;
-    sums[seg] = o;
+    sums[f.id] = o;
+  }
+}
+
+template <bool WIDE>
+__global__ __launch_bounds__(WIDE ? kFoldBlock : 256) void k_fold_err(
+    const Segment* __restrict__ segs, int nseg, const int* __restrict__ ids,
+    const ErrPartial3* __restrict__ parts, qv2_sums* __restrict__ sums) {
+  const FoldIdx<WIDE> f(ids, nseg);
+  if (!f.active) return;
+  const Segment sg = segs[f.id];
+  if (!WIDE && sg.enp > kFoldWaveMax) return;
+  double sx2 = 0.0, se2 = 0.0, unused = 0.0;
+#pragma unroll 4
+  for (int i = f.lane; i < sg.enp; i += f.stride) {
+    const ErrPartial3 q = parts[sg.ep0 + i];
+    sx2 += q.sx2; se2 += q.se2;
+  }
+  fold_sum3<WIDE>(sx2, se2, unused);
+  if (f.lane == 0) {
+    sums[f.id].sum_x2 = sx2; sums[f.id].sum_e2 = se2; sums[f.id].n = sg.n;
+  }
+}
+
+// second energy of a partial record: the pair-noise energy
+__device__ __forceinline__ double pair_energy(const ErrPartial& p) { return p.se2; }
+__device__ __forceinline__ double pair_energy(const ErrPartial3& p) { return p.sd2; }
+
+template <bool WIDE, class P>
+__global__ __launch_bounds__(WIDE ? kFoldBlock : 256) void k_fold_pair(
+    const PairTensor* __restrict__ pt, int n, const int* __restrict__ ids,
+    const P* __restrict__ parts, qv2_pair_sums* __restrict__ out) {
+  const FoldIdx<WIDE> f(ids, n);
+  if (!f.active) return;
+  const PairTensor p = pt[f.id];
+  if (!WIDE && p.nparts > kFoldWaveMax) return;
+  double sr2 = 0.0, sd2 = 0.0, unused = 0.0;
+#pragma unroll 4
+  for (int i = f.lane; i < p.nparts; i += f.stride) {
+    const P q = parts[p.part0 + i];
+    sr2 += q.sx2; sd2 += pair_energy(q);
+  }
+  fold_sum3<WIDE>(sr2, sd2, unused);
+  if (f.lane == 0) {
+    qv2_pair_sums o;
+    o.sum_ref2 = sr2; o.sum_d2 = sd2; o.n = p.n; o._pad = 0;
+    out[f.id] = o;
   }
 }
 
 // ---------------------------------------------------------------------------
-// pass 2 (Eq. 1, 3, 5 and the energies of Eq. 6-7): stream tiles
+// pass 2 (Eq. 1, 3, 5 and the energies of Eq. 6-7), optionally with pass 3
+// (Algorithm 2's D[i] vs Q[i]) in the same sweep: stream tiles.
+// Per element 4 B read + 1 B code written (+ 4 B of qrun read when PAIR).
 // ---------------------------------------------------------------------------
-__global__ __launch_bounds__(kBlock) void k_quant_stream(const TensorDesc* __restrict__ descs,
-                                                         const Tile* __restrict__ tiles,
-                                                         const qv2_qparams* __restrict__ params,
-                                                         ErrPartial* __restrict__ parts) {
-  const Tile tl = tiles[blockIdx.x];
-  const TensorDesc td = descs[tl.tensor];
-  const float* __restrict__ p = td.x + tl.off;
-  int8_t* __restrict__ c = td.codes ? td.codes + tl.off : nullptr;
-  const QP q = load_qp(params, tl.seg0);
-  const int len = tl.len, tid = threadIdx.x;
-  const int head = head_elems(p, len);
-  const int body = len - head, nvec = body >> 2, tail = body & 3;
-
-  double sx2 = 0.0, se2 = 0.0;
-  if (tid < head || tid < tail) {
-    for (int k = 0; k < 2; ++k) {
-      const bool on = k == 0 ? tid < head : tid < tail;
-      if (!on) continue;
-      const int idx = k == 0 ? tid : head + (nvec << 2) + tid;
-      const float v = p[idx];
-      float e;
-      const float code = quant1(v, q, e);
-      if (c) c[idx] = static_cast<int8_t>(static_cast<int>(code));
-      sx2 += static_cast<double>(v) * v;
-      se2 += static_cast<double>(e) * e;
-    }
-  }
-  const float4* __restrict__ v4 = reinterpret_cast<const float4*>(p + head);
-  // codes of the vector body go out as packed dwords when that address is 4-byte aligned
-  const bool cw_ok = c && ((reinterpret_cast<uintptr_t>(c + head) & 3u) == 0);
-  uint32_t* __restrict__ cw = reinterpret_cast<uint32_t*>(c + head);
-  Acc4 ae2, ax2;
-  int i = tid;
-  for (; i + (kUnroll - 1) * kBlock < nvec; i += kUnroll * kBlock) {
-    float4 r[kUnroll];
-#pragma unroll
-    for (int u = 0; u < kUnroll; ++u) r[u] = ld4(&v4[i + u * kBlock]);
-#pragma unroll
-    for (int u = 0; u < kUnroll; ++u) {
-      const uint32_t pk = quant4(r[u], q, ae2, ax2);
-      if (cw_ok) {
-        st_codes(&cw[i + u * kBlock], pk);
-      } else if (c) {
-        int8_t* d = c + head + ((i + u * kBlock) << 2);
-        d[0] = static_cast<int8_t>(pk); d[1] = static_cast<int8_t>(pk >> 8);
-        d[2] = static_cast<int8_t>(pk >> 16); d[3] = static_cast<int8_t>(pk >> 24);
-      }
-    }
-  }
-  for (; i < nvec; i += kBlock) {
-    const float4 r = ld4(&v4[i]);
-    const uint32_t pk = quant4(r, q, ae2, ax2);
-    if (cw_ok) {
-      st_codes(&cw[i], pk);
-    } else if (c) {
-      int8_t* d = c + head + (i << 2);
+// STORE: 0 no code buffer, 1 packed dwords, 2 single bytes (misaligned code buffer)
+template <int BLOCK, int V, int STORE, bool PAIR>
+__device__ __forceinline__ void quant_body(gf4_ptr v4, gf4_ptr b4, gu32_ptr cw, gi8_ptr cb, int nvec,
+                                           const QP& q, Acc4& ae2, Acc4& ax2, Acc4& ad2) {
+  const int tid = threadIdx.x;
+  auto put = [&](int i, uint32_t pk) {
+    if (STORE == 1) {
+      st_codes(cw + i, pk);
+    } else if (STORE == 2) {
+      gi8_ptr d = cb + (i << 2);
       d[0] = static_cast<int8_t>(pk); d[1] = static_cast<int8_t>(pk >> 8);
       d[2] = static_cast<int8_t>(pk >> 16); d[3] = static_cast<int8_t>(pk >> 24);
     }
+  };
+  int base = 0;
+  for (; base + V * BLOCK <= nvec; base += V * BLOCK) {          // uniform: whole batches
+    f4 r[V], g[V];
+#pragma unroll
+    for (int u = 0; u < V; ++u) {
+      r[u] = ld4(v4 + base + u * BLOCK + tid);
+      if (PAIR) g[u] = ld4(b4 + base + u * BLOCK + tid);
+    }
+#pragma unroll
+    for (int u = 0; u < V; ++u) {
+      put(base + u * BLOCK + tid, quant4(r[u], q, ae2, ax2));
+      if (PAIR) ad2.add_sq(r[u].x - g[u].x, r[u].y - g[u].y, r[u].z - g[u].z, r[u].w - g[u].w);
+    }
   }
-  se2 += ae2.total(); sx2 += ax2.total();
-  block_sum2(sx2, se2);
-  if (tid == 0) {
-    ErrPartial o;
-    o.sx2 = sx2; o.se2 = se2;
-    parts[tl.part0] = o;
+  for (int i = base + tid; i < nvec; i += BLOCK) {
+    const f4 r = ld4(v4 + i);
+    put(i, quant4(r, q, ae2, ax2));
+    if (PAIR) {
+      const f4 g = ld4(b4 + i);
+      ad2.add_sq(r.x - g.x, r.y - g.y, r.z - g.z, r.w - g.w);
+    }
   }
 }
 
-// pass 2, row-group tiles
-__global__ __launch_bounds__(kBlock) void k_quant_rows(const TensorDesc* __restrict__ descs,
-                                                       const Tile* __restrict__ tiles,
-                                                       const qv2_qparams* __restrict__ params,
-                                                       ErrPartial* __restrict__ parts) {
-  __shared__ __attribute__((aligned(16))) float xs[kRowGroupCap + 4];
-  __shared__ __attribute__((aligned(16))) int8_t cs[kRowGroupCap + 8];
+template <int BLOCK, int V, bool PAIR>
+__global__ __launch_bounds__(BLOCK) void k_quant_stream(const Tile* __restrict__ tiles,
+                                                        const qv2_qparams* __restrict__ params,
+                                                        ErrPartial3* __restrict__ parts) {
   const Tile tl = tiles[blockIdx.x];
-  const TensorDesc td = descs[tl.tensor];
-  const int shift = stage_tile(td.x + tl.off, tl.len, xs);
-  int8_t* __restrict__ dst = td.codes ? td.codes + tl.off : nullptr;
-  const int ca = static_cast<int>(reinterpret_cast<uintptr_t>(dst) & 3u);   // code e sits at cs[e + ca]
-  __syncthreads();
-
-  const int inner = tl.inner, w = row_width(inner), gpw = kWave / w;
-  const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
-  const int g = lane >> __builtin_ctz(w), gl = lane & (w - 1);
-  for (int rb = wave * gpw; rb < tl.rows; rb += kWaves * gpw) {
-    const int r = rb + g;
-    const bool live = r < tl.rows;
-    double sx2 = 0.0, se2 = 0.0;
-    if (live) {
-      const QP q = load_qp(params, tl.seg0 + r);
-      const float* row = xs + shift + r * inner;
-      int8_t* crow = cs + ca + r * inner;
-      for (int j = gl; j < inner; j += w) {
-        const float v = row[j];
-        float e;
-        const float code = quant1(v, q, e);
-        crow[j] = static_cast<int8_t>(static_cast<int>(code));
-        sx2 = fma(static_cast<double>(v), static_cast<double>(v), sx2);
-        se2 = fma(static_cast<double>(e), static_cast<double>(e), se2);
-      }
-    }
-    sx2 = group_sum(sx2, w); se2 = group_sum(se2, w);
-    if (live && gl == 0) {
-      ErrPartial o;
-      o.sx2 = sx2; o.se2 = se2;
-      parts[tl.part0 + r] = o;
-    }
-  }
-  if (!dst) return;
-  __syncthreads();
-  // copy the codes out as whole dwords where the destination allows it
-  const int total = tl.len + ca;
-  int8_t* base = dst - ca;
-  for (int k = threadIdx.x; (k << 2) < total; k += kBlock) {
-    const int b0 = k << 2;
-    if (b0 >= ca && b0 + 4 <= total) {
-      *reinterpret_cast<uint32_t*>(base + b0) = *reinterpret_cast<const uint32_t*>(cs + b0);
-    } else {
-      const int lo = b0 > ca ? b0 : ca, hi = b0 + 4 < total ? b0 + 4 : total;
-      for (int b = lo; b < hi; ++b) base[b] = cs[b];
-    }
-  }
-}
-
-// ---------------------------------------------------------------------------
-// passes 2 + 3 in one sweep: x is read once for the fake-quant energies AND for
-// the pair energies against qrun (Eq. 1, 3, 5, 6-7; Algorithm 2's D[i] vs Q[i]).
-// Per element: 4 B (x) + 4 B (qrun) read, 1 B code written.
-// ---------------------------------------------------------------------------
-__device__ __forceinline__ void put_codes4(int8_t* c, uint32_t* cw, bool cw_ok, int head, int i,
-                                           uint32_t pk) {
-  if (cw_ok) {
-    st_codes(&cw[i], pk);
-  } else if (c) {
-    int8_t* d = c + head + (i << 2);
-    d[0] = static_cast<int8_t>(pk); d[1] = static_cast<int8_t>(pk >> 8);
-    d[2] = static_cast<int8_t>(pk >> 16); d[3] = static_cast<int8_t>(pk >> 24);
-  }
-}
-
-__global__ __launch_bounds__(kBlock) void k_quantpair_stream(const TensorDesc* __restrict__ descs,
-                                                             const Tile* __restrict__ tiles,
-                                                             const qv2_qparams* __restrict__ params,
-                                                             ErrPartial3* __restrict__ parts) {
-  const Tile tl = tiles[blockIdx.x];
-  const TensorDesc td = descs[tl.tensor];
-  const float* __restrict__ p = td.x + tl.off;
-  const float* __restrict__ b = td.qrun ? td.qrun + tl.off : nullptr;
-  int8_t* __restrict__ c = td.codes ? td.codes + tl.off : nullptr;
   const QP q = load_qp(params, tl.seg0);
+  const gf_ptr p = (gf_ptr)tl.x;
+  const gf_ptr b = (gf_ptr)tl.q;
+  const gi8_ptr c = (gi8_ptr)tl.c;
+  const bool has_c = tl.c != nullptr;
+  const bool has_b = PAIR && tl.q != nullptr;
   const int len = tl.len, tid = threadIdx.x;
   double sx2 = 0.0, se2 = 0.0, sd2 = 0.0;
 
   // qrun at a different offset inside 16 bytes than x: its energy is taken element-wise
-  const bool b_vec = b && (((reinterpret_cast<uintptr_t>(p) ^ reinterpret_cast<uintptr_t>(b)) & 15u) == 0);
-  if (b && !b_vec) {
-    for (int i = tid; i < len; i += kBlock) {
+  const bool b_vec = has_b && (((reinterpret_cast<uintptr_t>(tl.x) ^ reinterpret_cast<uintptr_t>(tl.q)) & 15u) == 0);
+  if (has_b && !b_vec) {
+    for (int i = tid; i < len; i += BLOCK) {
       const double d = static_cast<double>(p[i] - b[i]);
       sd2 = fma(d, d, sd2);
     }
   }
-  const int head = head_elems(p, len);
+  const int head = head_elems(tl.x, len);
   const int body = len - head, nvec = body >> 2, tail = body & 3;
   for (int k = 0; k < 2; ++k) {
     const bool on = k == 0 ? tid < head : tid < tail;
@@ -508,82 +501,28 @@ __global__ __launch_bounds__(kBlock) void k_quantpair_stream(const TensorDesc* _
     const float v = p[idx];
     float e;
     const float code = quant1(v, q, e);
-    if (c) c[idx] = static_cast<int8_t>(static_cast<int>(code));
+    if (has_c) c[idx] = static_cast<int8_t>(static_cast<int>(code));
     sx2 += static_cast<double>(v) * v;
     se2 += static_cast<double>(e) * e;
     if (b_vec) { const float d = v - b[idx]; sd2 += static_cast<double>(d) * d; }
   }
-  const float4* __restrict__ v4 = reinterpret_cast<const float4*>(p + head);
-  const float4* __restrict__ b4 = reinterpret_cast<const float4*>(b + head);
-  const bool cw_ok = c && ((reinterpret_cast<uintptr_t>(c + head) & 3u) == 0);
-  uint32_t* __restrict__ cw = reinterpret_cast<uint32_t*>(c + head);
+  const gf4_ptr v4 = (gf4_ptr)(tl.x + head);
+  const gf4_ptr b4 = (gf4_ptr)(tl.q + head);
+  const gi8_ptr cb = c + head;
+  const gu32_ptr cw = (gu32_ptr)(tl.c + head);
+  const bool cw_ok = has_c && ((reinterpret_cast<uintptr_t>(tl.c + head) & 3u) == 0);
   Acc4 ae2, ax2, ad2;
-#define PUT(ii, pk) put_codes4(c, cw, cw_ok, head, (ii), (pk))
-  int i = tid;
   if (b_vec) {
-    constexpr int U = kPairUnroll;
-#if QV2_PIPELINE
-    // Loads and stores share one in-order counter on this ISA: a wave that waits for its
-    // next loads also waits for every store issued before them.  So the next round's loads
-    // are issued BEFORE this round's code stores.
-    if (i + (U - 1) * kBlock < nvec) {
-      float4 r[U], g[U];
-#pragma unroll
-      for (int u = 0; u < U; ++u) { r[u] = ld4(&v4[i + u * kBlock]); g[u] = ld4(&b4[i + u * kBlock]); }
-      for (;;) {
-        const int inext = i + U * kBlock;
-        const bool more = inext + (U - 1) * kBlock < nvec;
-        float4 rn[U], gn[U];
-        if (more) {
-#pragma unroll
-          for (int u = 0; u < U; ++u) { rn[u] = ld4(&v4[inext + u * kBlock]); gn[u] = ld4(&b4[inext + u * kBlock]); }
-        }
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-          PUT(i + u * kBlock, quant4(r[u], q, ae2, ax2));
-          ad2.add_sq(r[u].x - g[u].x, r[u].y - g[u].y, r[u].z - g[u].z, r[u].w - g[u].w);
-        }
-        i = inext;
-        if (!more) break;
-#pragma unroll
-        for (int u = 0; u < U; ++u) { r[u] = rn[u]; g[u] = gn[u]; }
-      }
-    }
-#else
-    for (; i + (U - 1) * kBlock < nvec; i += U * kBlock) {
-      float4 r[U], g[U];
-#pragma unroll
-      for (int u = 0; u < U; ++u) { r[u] = ld4(&v4[i + u * kBlock]); g[u] = ld4(&b4[i + u * kBlock]); }
-#pragma unroll
-      for (int u = 0; u < U; ++u) {
-        PUT(i + u * kBlock, quant4(r[u], q, ae2, ax2));
-        ad2.add_sq(r[u].x - g[u].x, r[u].y - g[u].y, r[u].z - g[u].z, r[u].w - g[u].w);
-      }
-    }
-#endif
-    for (; i < nvec; i += kBlock) {
-      const float4 r = ld4(&v4[i]), g = ld4(&b4[i]);
-      PUT(i, quant4(r, q, ae2, ax2));
-      ad2.add_sq(r.x - g.x, r.y - g.y, r.z - g.z, r.w - g.w);
-    }
+    if (cw_ok) quant_body<BLOCK, V, 1, PAIR>(v4, b4, cw, cb, nvec, q, ae2, ax2, ad2);
+    else if (has_c) quant_body<BLOCK, V, 2, PAIR>(v4, b4, cw, cb, nvec, q, ae2, ax2, ad2);
+    else quant_body<BLOCK, V, 0, PAIR>(v4, b4, cw, cb, nvec, q, ae2, ax2, ad2);
   } else {
-    for (; i + (kUnroll - 1) * kBlock < nvec; i += kUnroll * kBlock) {
-      float4 r[kUnroll];
-#pragma unroll
-      for (int u = 0; u < kUnroll; ++u) r[u] = ld4(&v4[i + u * kBlock]);
-#pragma unroll
-      for (int u = 0; u < kUnroll; ++u)
-        PUT(i + u * kBlock, quant4(r[u], q, ae2, ax2));
-    }
-    for (; i < nvec; i += kBlock)
-      PUT(i, quant4(ld4(&v4[i]), q, ae2, ax2));
+    if (cw_ok) quant_body<BLOCK, V, 1, false>(v4, b4, cw, cb, nvec, q, ae2, ax2, ad2);
+    else if (has_c) quant_body<BLOCK, V, 2, false>(v4, b4, cw, cb, nvec, q, ae2, ax2, ad2);
+    else quant_body<BLOCK, V, 0, false>(v4, b4, cw, cb, nvec, q, ae2, ax2, ad2);
   }
-#undef PUT
   se2 += ae2.total(); sx2 += ax2.total(); sd2 += ad2.total();
-  double zero = 0.0;
-  block_sum2(sx2, se2);
-  __syncthreads();                                  // block_sum2's LDS slots are reused
-  block_sum2(sd2, zero);
+  block_sum3<BLOCK>(sx2, se2, sd2);
   if (tid == 0) {
     ErrPartial3 o;
     o.sx2 = sx2; o.se2 = se2; o.sd2 = sd2;
@@ -591,25 +530,25 @@ __global__ __launch_bounds__(kBlock) void k_quantpair_stream(const TensorDesc* _
   }
 }
 
-// fused passes 2 + 3, row-group tiles
-__global__ __launch_bounds__(kBlock) void k_quantpair_rows(const TensorDesc* __restrict__ descs,
-                                                           const Tile* __restrict__ tiles,
-                                                           const qv2_qparams* __restrict__ params,
-                                                           ErrPartial3* __restrict__ parts) {
+// pass 2 (+3), row-group tiles
+template <int BLOCK, bool PAIR>
+__global__ __launch_bounds__(BLOCK) void k_quant_rows(const Tile* __restrict__ tiles,
+                                                      const qv2_qparams* __restrict__ params,
+                                                      ErrPartial3* __restrict__ parts) {
+  constexpr int W = BLOCK / kWave;
   __shared__ __attribute__((aligned(16))) float xs[kRowGroupCap + 4];
   __shared__ __attribute__((aligned(16))) int8_t cs[kRowGroupCap + 8];
   const Tile tl = tiles[blockIdx.x];
-  const TensorDesc td = descs[tl.tensor];
-  const int shift = stage_tile(td.x + tl.off, tl.len, xs);
-  const float* __restrict__ b = td.qrun ? td.qrun + tl.off : nullptr;
-  int8_t* __restrict__ dst = td.codes ? td.codes + tl.off : nullptr;
-  const int ca = static_cast<int>(reinterpret_cast<uintptr_t>(dst) & 3u);
+  const int shift = stage_tile<BLOCK>(tl.x, tl.len, xs);
+  const gf_ptr b = (gf_ptr)tl.q;
+  const bool has_b = PAIR && tl.q != nullptr;
+  const int ca = static_cast<int>(reinterpret_cast<uintptr_t>(tl.c) & 3u);   // code e sits at cs[e + ca]
   __syncthreads();
 
   const int inner = tl.inner, w = row_width(inner), gpw = kWave / w;
   const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
   const int g = lane >> __builtin_ctz(w), gl = lane & (w - 1);
-  for (int rb = wave * gpw; rb < tl.rows; rb += kWaves * gpw) {
+  for (int rb = wave * gpw; rb < tl.rows; rb += W * gpw) {
     const int r = rb + g;
     const bool live = r < tl.rows;
     double sx2 = 0.0, se2 = 0.0, sd2 = 0.0;
@@ -624,7 +563,7 @@ __global__ __launch_bounds__(kBlock) void k_quantpair_rows(const TensorDesc* __r
         crow[j] = static_cast<int8_t>(static_cast<int>(code));
         sx2 = fma(static_cast<double>(v), static_cast<double>(v), sx2);
         se2 = fma(static_cast<double>(e), static_cast<double>(e), se2);
-        if (b) {
+        if (has_b) {
           const double d = static_cast<double>(v - b[r * inner + j]);
           sd2 = fma(d, d, sd2);
         }
@@ -637,14 +576,15 @@ __global__ __launch_bounds__(kBlock) void k_quantpair_rows(const TensorDesc* __r
       parts[tl.part0 + r] = o;
     }
   }
-  if (!dst) return;
+  if (!tl.c) return;
   __syncthreads();
+  // copy the codes out as whole dwords where the destination allows it
   const int total = tl.len + ca;
-  int8_t* base = dst - ca;
-  for (int k = threadIdx.x; (k << 2) < total; k += kBlock) {
+  const gi8_ptr base = (gi8_ptr)(tl.c - ca);
+  for (int k = threadIdx.x; (k << 2) < total; k += BLOCK) {
     const int b0 = k << 2;
     if (b0 >= ca && b0 + 4 <= total) {
-      *reinterpret_cast<uint32_t*>(base + b0) = *reinterpret_cast<const uint32_t*>(cs + b0);
+      *(gu32_ptr)(base + b0) = *reinterpret_cast<const uint32_t*>(cs + b0);
     } else {
       const int lo = b0 > ca ? b0 : ca, hi = b0 + 4 < total ? b0 + 4 : total;
       for (int bb = lo; bb < hi; ++bb) base[bb] = cs[bb];
@@ -652,52 +592,27 @@ __global__ __launch_bounds__(kBlock) void k_quantpair_rows(const TensorDesc* __r
   }
 }
 
-// second energy of a partial record: the pair-noise energy
-__device__ __forceinline__ double pair_energy(const ErrPartial& p) { return p.se2; }
-__device__ __forceinline__ double pair_energy(const ErrPartial3& p) { return p.sd2; }
-
-template <class P>
-__global__ __launch_bounds__(kBlock) void k_fold_err(const Segment* __restrict__ segs, int nseg,
-                                                     const P* __restrict__ parts,
-                                                     qv2_sums* __restrict__ sums) {
-  const int seg = blockIdx.x * kWaves + (threadIdx.x >> 6);
-  const int lane = threadIdx.x & (kWave - 1);
-  if (seg >= nseg) return;
-  const Segment sg = segs[seg];
-  if (sg.nparts > kFoldWaveMax) return;            // folded by k_fold_err_big
-  double sx2 = 0.0, se2 = 0.0;
-  for (int i = lane; i < sg.nparts; i += kWave) {
-    const P q = parts[sg.part0 + i];
-    sx2 += q.sx2; se2 += q.se2;
-  }
-  sx2 = group_sum(sx2, kWave); se2 = group_sum(se2, kWave);
-  if (lane == 0) {
-    sums[seg].sum_x2 = sx2; sums[seg].sum_e2 = se2; sums[seg].n = sg.n;
-  }
-}
-
 // ---------------------------------------------------------------------------
-// pass 3 (Algorithm 2: CalculateSQNR / CalculateMSE on D[i] and Q[i])
+// pass 3 alone (Algorithm 2: CalculateSQNR / CalculateMSE on D[i] and Q[i])
 // ---------------------------------------------------------------------------
-__global__ __launch_bounds__(kBlock) void k_pair_stream(const TensorDesc* __restrict__ descs,
-                                                        const Tile* __restrict__ tiles,
-                                                        ErrPartial* __restrict__ parts) {
+template <int BLOCK, int V>
+__global__ __launch_bounds__(BLOCK) void k_pair_stream(const Tile* __restrict__ tiles,
+                                                       ErrPartial* __restrict__ parts) {
   const Tile tl = tiles[blockIdx.x];
-  const TensorDesc td = descs[tl.tensor];
-  const float* __restrict__ a = td.x + tl.off;
-  const float* __restrict__ b = td.qrun + tl.off;
+  const gf_ptr a = (gf_ptr)tl.x;
+  const gf_ptr b = (gf_ptr)tl.q;
   const int len = tl.len, tid = threadIdx.x;
-  double sr2 = 0.0, sd2 = 0.0;
+  double sr2 = 0.0, sd2 = 0.0, unused = 0.0;
 
-  if (((reinterpret_cast<uintptr_t>(a) ^ reinterpret_cast<uintptr_t>(b)) & 15u) != 0) {
+  if (((reinterpret_cast<uintptr_t>(tl.x) ^ reinterpret_cast<uintptr_t>(tl.q)) & 15u) != 0) {
     // the two tensors sit at different offsets within 16 bytes: element loads
-    for (int i = tid; i < len; i += kBlock) {
+    for (int i = tid; i < len; i += BLOCK) {
       const float x = a[i], d = x - b[i];
       sr2 = fma(static_cast<double>(x), static_cast<double>(x), sr2);
       sd2 = fma(static_cast<double>(d), static_cast<double>(d), sd2);
     }
   } else {
-    const int head = head_elems(a, len);
+    const int head = head_elems(tl.x, len);
     const int body = len - head, nvec = body >> 2, tail = body & 3;
     if (tid < head) {
       const float x = a[tid], d = x - b[tid];
@@ -708,143 +623,32 @@ __global__ __launch_bounds__(kBlock) void k_pair_stream(const TensorDesc* __rest
       const float x = a[idx], d = x - b[idx];
       sr2 += static_cast<double>(x) * x; sd2 += static_cast<double>(d) * d;
     }
-    const float4* __restrict__ a4 = reinterpret_cast<const float4*>(a + head);
-    const float4* __restrict__ b4 = reinterpret_cast<const float4*>(b + head);
-    constexpr int U = kPairUnroll;                 // two streams: same bytes in flight
+    const gf4_ptr a4 = (gf4_ptr)(tl.x + head);
+    const gf4_ptr b4 = (gf4_ptr)(tl.q + head);
     Acc4 ar2, ad2;
-    int i = tid;
-    for (; i + (U - 1) * kBlock < nvec; i += U * kBlock) {
-      float4 ra[U], rb[U];
+    int base = 0;
+    for (; base + V * BLOCK <= nvec; base += V * BLOCK) {
+      f4 ra[V], rb[V];
 #pragma unroll
-      for (int u = 0; u < U; ++u) { ra[u] = ld4(&a4[i + u * kBlock]); rb[u] = ld4(&b4[i + u * kBlock]); }
+      for (int u = 0; u < V; ++u) { ra[u] = ld4(a4 + base + u * BLOCK + tid); rb[u] = ld4(b4 + base + u * BLOCK + tid); }
 #pragma unroll
-      for (int u = 0; u < U; ++u) {
+      for (int u = 0; u < V; ++u) {
         ar2.add_sq(ra[u].x, ra[u].y, ra[u].z, ra[u].w);
         ad2.add_sq(ra[u].x - rb[u].x, ra[u].y - rb[u].y, ra[u].z - rb[u].z, ra[u].w - rb[u].w);
       }
     }
-    for (; i < nvec; i += kBlock) {
-      const float4 x = ld4(&a4[i]), y = ld4(&b4[i]);
+    for (int i = base + tid; i < nvec; i += BLOCK) {
+      const f4 x = ld4(a4 + i), y = ld4(b4 + i);
       ar2.add_sq(x.x, x.y, x.z, x.w);
       ad2.add_sq(x.x - y.x, x.y - y.y, x.z - y.z, x.w - y.w);
     }
     sr2 += ar2.total(); sd2 += ad2.total();
   }
-  block_sum2(sr2, sd2);
+  block_sum3<BLOCK>(sr2, sd2, unused);
   if (tid == 0) {
     ErrPartial o;
     o.sx2 = sr2; o.se2 = sd2;
     parts[tl.part0] = o;
-  }
-}
-
-template <class P>
-__global__ __launch_bounds__(kBlock) void k_fold_pair(const PairTensor* __restrict__ pt, int n,
-                                                      const P* __restrict__ parts,
-                                                      qv2_pair_sums* __restrict__ out) {
-  const int t = blockIdx.x * kWaves + (threadIdx.x >> 6);
-  const int lane = threadIdx.x & (kWave - 1);
-  if (t >= n) return;
-  const PairTensor p = pt[t];
-  if (p.nparts > kFoldWaveMax) return;             // folded by k_fold_pair_big
-  double sr2 = 0.0, sd2 = 0.0;
-  for (int i = lane; i < p.nparts; i += kWave) {
-    const P q = parts[p.part0 + i];
-    sr2 += q.sx2; sd2 += pair_energy(q);
-  }
-  sr2 = group_sum(sr2, kWave); sd2 = group_sum(sd2, kWave);
-  if (lane == 0) {
-    qv2_pair_sums o;
-    o.sum_ref2 = sr2; o.sum_d2 = sd2; o.n = p.n; o._pad = 0;
-    out[t] = o;
-  }
-}
-
-// ---------------------------------------------------------------------------
-// folds of segments with many partials (large tensors): one 1024-thread
-// workgroup per segment, thread-strided then a fixed tree => deterministic
-// ---------------------------------------------------------------------------
-__device__ __forceinline__ void fold_block_sum2(double& a, double& b) {
-  __shared__ double sa[kFoldWaves], sb[kFoldWaves];
-  a = group_sum(a, kWave);
-  b = group_sum(b, kWave);
-  const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
-  if (lane == 0) { sa[wave] = a; sb[wave] = b; }
-  __syncthreads();
-  if (threadIdx.x == 0) {
-    a = sa[0]; b = sb[0];
-    for (int i = 1; i < kFoldWaves; ++i) { a += sa[i]; b += sb[i]; }
-  }
-}
-
-__global__ __launch_bounds__(kFoldBlock) void k_fold_stats_big(const Segment* __restrict__ segs,
-                                                               const int* __restrict__ ids,
-                                                               const StatPartial* __restrict__ parts,
-                                                               qv2_qparams* __restrict__ params,
-                                                               qv2_sums* __restrict__ sums) {
-  __shared__ float smn[kFoldWaves], smx[kFoldWaves];
-  const int seg = ids[blockIdx.x];
-  const Segment sg = segs[seg];
-  float mn = INFINITY, mx = -INFINITY;
-  double sx = 0.0, sx2 = 0.0;
-#pragma unroll 4
-  for (int i = threadIdx.x; i < sg.nparts; i += kFoldBlock) {
-    const StatPartial q = parts[sg.part0 + i];
-    mn = fminf(mn, q.mn); mx = fmaxf(mx, q.mx);
-    sx += q.sx; sx2 += q.sx2;
-  }
-  mn = group_min(mn, kWave); mx = group_max(mx, kWave);
-  const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
-  if (lane == 0) { smn[wave] = mn; smx[wave] = mx; }
-  fold_block_sum2(sx, sx2);                         // contains the barrier
-  if (threadIdx.x == 0) {
-    for (int i = 1; i < kFoldWaves; ++i) { mn = fminf(mn, smn[i]); mx = fmaxf(mx, smx[i]); }
-    qv2_qparams qp;
-    make_params(mn, mx, sg.scheme, qp);
-    params[seg] = qp;
-    qv2_sums o;
-    o.sum_x = sx; o.sum_x2 = sx2; o.sum_e2 = 0.0; o.n = sg.n;
-    sums[seg] = o;
-  }
-}
-
-template <class P>
-__global__ __launch_bounds__(kFoldBlock) void k_fold_err_big(const Segment* __restrict__ segs,
-                                                             const int* __restrict__ ids,
-                                                             const P* __restrict__ parts,
-                                                             qv2_sums* __restrict__ sums) {
-  const int seg = ids[blockIdx.x];
-  const Segment sg = segs[seg];
-  double sx2 = 0.0, se2 = 0.0;
-#pragma unroll 4
-  for (int i = threadIdx.x; i < sg.nparts; i += kFoldBlock) {
-    const P q = parts[sg.part0 + i];
-    sx2 += q.sx2; se2 += q.se2;
-  }
-  fold_block_sum2(sx2, se2);
-  if (threadIdx.x == 0) {
-    sums[seg].sum_x2 = sx2; sums[seg].sum_e2 = se2; sums[seg].n = sg.n;
-  }
-}
-
-template <class P>
-__global__ __launch_bounds__(kFoldBlock) void k_fold_pair_big(const PairTensor* __restrict__ pt,
-                                                              const int* __restrict__ ids,
-                                                              const P* __restrict__ parts,
-                                                              qv2_pair_sums* __restrict__ out) {
-  const int t = ids[blockIdx.x];
-  const PairTensor p = pt[t];
-  double sr2 = 0.0, sd2 = 0.0;
-#pragma unroll 4
-  for (int i = threadIdx.x; i < p.nparts; i += kFoldBlock) {
-    const P q = parts[p.part0 + i];
-    sr2 += q.sx2; sd2 += pair_energy(q);
-  }
-  fold_block_sum2(sr2, sd2);
-  if (threadIdx.x == 0) {
-    qv2_pair_sums o;
-    o.sum_ref2 = sr2; o.sum_d2 = sd2; o.n = p.n; o._pad = 0;
-    out[t] = o;
   }
 }
 
@@ -853,47 +657,46 @@ __global__ __launch_bounds__(kFoldBlock) void k_fold_pair_big(const PairTensor* 
 // ---------------------------------------------------------------------------
 size_t align256(size_t v) { return (v + 255) & ~static_cast<size_t>(255); }
 
+template <class T>
+size_t bytes_of(const std::vector<T>& v) { return v.size() * sizeof(T); }
+
 // First device call on a plan: one allocation holding all tables, blocking copies.
 qv2_status ensure_uploaded(qv2_plan* p) {
   if (p->d_blob) return QV2_OK;
-  const size_t b_desc = align256(p->descs.size() * sizeof(TensorDesc));
-  const size_t b_tile = align256(p->tiles.size() * sizeof(Tile));
-  const size_t b_seg = align256(p->segments.size() * sizeof(Segment));
-  const size_t b_ptile = align256(p->pair_tiles.size() * sizeof(Tile));
-  const size_t b_pten = align256(p->pair_tensors.size() * sizeof(PairTensor));
-  const size_t b_bseg = align256(p->big_segments.size() * sizeof(int32_t));
-  const size_t b_bpair = align256(p->big_pair_tensors.size() * sizeof(int32_t));
-  const size_t b_ften = align256(p->fused_pair_tensors.size() * sizeof(PairTensor));
-  const size_t b_bften = align256(p->big_fused_pair_tensors.size() * sizeof(int32_t));
+  size_t total = 256;
+  auto reserve = [&](size_t n) { const size_t at = total; total += align256(n); return at; };
+  const size_t o_read = reserve(bytes_of(p->read_tiles)), o_quant = reserve(bytes_of(p->quant_tiles));
+  const size_t o_row = reserve(bytes_of(p->row_tiles)), o_pair = reserve(bytes_of(p->pair_tiles));
+  const size_t o_seg = reserve(bytes_of(p->segments)), o_pt = reserve(bytes_of(p->pair_tensors));
+  const size_t o_ft = reserve(bytes_of(p->fused_pair_tensors));
+  const size_t o_bs = reserve(bytes_of(p->big_stat_segments)), o_be = reserve(bytes_of(p->big_err_segments));
+  const size_t o_bp = reserve(bytes_of(p->big_pair_tensors)), o_bf = reserve(bytes_of(p->big_fused_pair_tensors));
   char* blob = nullptr;
-  if (hipMalloc(reinterpret_cast<void**>(&blob), b_desc + b_tile + b_seg + b_ptile + b_pten +
-                                                      b_bseg + b_bpair + b_ften + b_bften + 256) !=
-      hipSuccess) { (void)hipGetLastError(); return QV2_ERR_HIP; }
-  char* q = blob;
-  p->d_descs = reinterpret_cast<TensorDesc*>(q); q += b_desc;
-  p->d_tiles = reinterpret_cast<Tile*>(q); q += b_tile;
-  p->d_segments = reinterpret_cast<Segment*>(q); q += b_seg;
-  p->d_pair_tiles = reinterpret_cast<Tile*>(q); q += b_ptile;
-  p->d_pair_tensors = reinterpret_cast<PairTensor*>(q); q += b_pten;
-  p->d_big_segments = reinterpret_cast<int32_t*>(q); q += b_bseg;
-  p->d_big_pair_tensors = reinterpret_cast<int32_t*>(q); q += b_bpair;
-  p->d_fused_pair_tensors = reinterpret_cast<PairTensor*>(q); q += b_ften;
-  p->d_big_fused_pair_tensors = reinterpret_cast<int32_t*>(q);
+  if (hipMalloc(reinterpret_cast<void**>(&blob), total) != hipSuccess) {
+    (void)hipGetLastError();
+    return QV2_ERR_HIP;
+  }
   bool ok = true;
-  auto put = [&](void* d, const void* h, size_t n) {
-    if (n && hipMemcpy(d, h, n, hipMemcpyHostToDevice) != hipSuccess) ok = false;
+  auto put = [&](size_t off, const void* h, size_t n) {
+    if (n && hipMemcpy(blob + off, h, n, hipMemcpyHostToDevice) != hipSuccess) ok = false;
+    return static_cast<void*>(blob + off);
   };
-  put(p->d_descs, p->descs.data(), p->descs.size() * sizeof(TensorDesc));
-  put(p->d_tiles, p->tiles.data(), p->tiles.size() * sizeof(Tile));
-  put(p->d_segments, p->segments.data(), p->segments.size() * sizeof(Segment));
-  put(p->d_pair_tiles, p->pair_tiles.data(), p->pair_tiles.size() * sizeof(Tile));
-  put(p->d_pair_tensors, p->pair_tensors.data(), p->pair_tensors.size() * sizeof(PairTensor));
-  put(p->d_big_segments, p->big_segments.data(), p->big_segments.size() * sizeof(int32_t));
-  put(p->d_big_pair_tensors, p->big_pair_tensors.data(), p->big_pair_tensors.size() * sizeof(int32_t));
-  put(p->d_fused_pair_tensors, p->fused_pair_tensors.data(),
-      p->fused_pair_tensors.size() * sizeof(PairTensor));
-  put(p->d_big_fused_pair_tensors, p->big_fused_pair_tensors.data(),
-      p->big_fused_pair_tensors.size() * sizeof(int32_t));
+  p->d_read_tiles = static_cast<Tile*>(put(o_read, p->read_tiles.data(), bytes_of(p->read_tiles)));
+  p->d_quant_tiles = static_cast<Tile*>(put(o_quant, p->quant_tiles.data(), bytes_of(p->quant_tiles)));
+  p->d_row_tiles = static_cast<Tile*>(put(o_row, p->row_tiles.data(), bytes_of(p->row_tiles)));
+  p->d_pair_tiles = static_cast<Tile*>(put(o_pair, p->pair_tiles.data(), bytes_of(p->pair_tiles)));
+  p->d_segments = static_cast<Segment*>(put(o_seg, p->segments.data(), bytes_of(p->segments)));
+  p->d_pair_tensors = static_cast<PairTensor*>(put(o_pt, p->pair_tensors.data(), bytes_of(p->pair_tensors)));
+  p->d_fused_pair_tensors =
+      static_cast<PairTensor*>(put(o_ft, p->fused_pair_tensors.data(), bytes_of(p->fused_pair_tensors)));
+  p->d_big_stat_segments =
+      static_cast<int32_t*>(put(o_bs, p->big_stat_segments.data(), bytes_of(p->big_stat_segments)));
+  p->d_big_err_segments =
+      static_cast<int32_t*>(put(o_be, p->big_err_segments.data(), bytes_of(p->big_err_segments)));
+  p->d_big_pair_tensors =
+      static_cast<int32_t*>(put(o_bp, p->big_pair_tensors.data(), bytes_of(p->big_pair_tensors)));
+  p->d_big_fused_pair_tensors = static_cast<int32_t*>(
+      put(o_bf, p->big_fused_pair_tensors.data(), bytes_of(p->big_fused_pair_tensors)));
   if (!ok) { (void)hipGetLastError(); (void)hipFree(blob); return QV2_ERR_HIP; }
   p->d_blob = blob;
   return QV2_OK;
@@ -918,6 +721,32 @@ struct Timed {
   }
   ~Timed() { if (p->timing) (void)hipEventRecord(static_cast<hipEvent_t>(p->ev_stop[k]), s); }
 };
+
+int fold_grid(int n) { return (n + 3) / 4; }
+
+// quantize pass over stream and row-group tiles, then the error fold
+template <bool PAIR>
+void launch_quant(qv2_plan* plan, const qv2_qparams* d_params, qv2_sums* d_sums, ErrPartial3* parts,
+                  hipStream_t s) {
+  const int n_stream = static_cast<int>(plan->quant_tiles.size());
+  const int n_rows = static_cast<int>(plan->row_tiles.size());
+  const int nseg = static_cast<int>(plan->segments.size());
+  if (n_stream > 0) {
+    Timed timed(plan, PAIR ? QV2_K_QUANTPAIR_STREAM : QV2_K_QUANT_STREAM, s);
+    hipLaunchKernelGGL((k_quant_stream<kBlockQuant, kVecQuant, PAIR>), dim3(n_stream), dim3(kBlockQuant),
+                       0, s, plan->d_quant_tiles, d_params, parts);
+  }
+  if (n_rows > 0) {
+    Timed timed(plan, PAIR ? QV2_K_QUANTPAIR_ROWS : QV2_K_QUANT_ROWS, s);
+    hipLaunchKernelGGL((k_quant_rows<kBlockRows, PAIR>), dim3(n_rows), dim3(kBlockRows), 0, s,
+                       plan->d_row_tiles, d_params, parts);
+  }
+  hipLaunchKernelGGL(k_fold_err<false>, dim3(fold_grid(nseg)), dim3(256), 0, s, plan->d_segments, nseg,
+                     static_cast<const int*>(nullptr), parts, d_sums);
+  if (const int nb = static_cast<int>(plan->big_err_segments.size()))
+    hipLaunchKernelGGL(k_fold_err<true>, dim3(nb), dim3(kFoldBlock), 0, s, plan->d_segments, nseg,
+                       plan->d_big_err_segments, parts, d_sums);
+}
 
 }  // namespace
 
@@ -969,24 +798,24 @@ qv2_status qv2_calibrate(qv2_plan* plan, qv2_qparams* d_params, qv2_sums* d_sums
   if ((st = ensure_uploaded(plan)) != QV2_OK) return st;
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   StatPartial* parts = static_cast<StatPartial*>(d_workspace);
-  const int n_stream = static_cast<int>(plan->n_stream_tiles);
-  const int n_rows = static_cast<int>(plan->tiles.size()) - n_stream;
+  const int n_stream = static_cast<int>(plan->read_tiles.size());
+  const int n_rows = static_cast<int>(plan->row_tiles.size());
   const int nseg = static_cast<int>(plan->segments.size());
   if (n_stream > 0) {
     Timed timed(plan, QV2_K_STATS_STREAM, s);
-    hipLaunchKernelGGL(k_stats_stream, dim3(n_stream), dim3(kBlock), 0, s, plan->d_descs,
-                       plan->d_tiles, parts);
+    hipLaunchKernelGGL((k_stats_stream<kBlockRead, kVecRead>), dim3(n_stream), dim3(kBlockRead), 0, s,
+                       plan->d_read_tiles, parts);
   }
   if (n_rows > 0) {
     Timed timed(plan, QV2_K_STATS_ROWS, s);
-    hipLaunchKernelGGL(k_stats_rows, dim3(n_rows), dim3(kBlock), 0, s, plan->d_descs,
-                       plan->d_tiles + n_stream, parts);
+    hipLaunchKernelGGL(k_stats_rows<kBlockRows>, dim3(n_rows), dim3(kBlockRows), 0, s,
+                       plan->d_row_tiles, parts);
   }
-  hipLaunchKernelGGL(k_fold_stats, dim3((nseg + kWaves - 1) / kWaves), dim3(kBlock), 0, s,
-                     plan->d_segments, nseg, parts, d_params, d_sums);
-  if (const int nb = static_cast<int>(plan->big_segments.size()))
-    hipLaunchKernelGGL(k_fold_stats_big, dim3(nb), dim3(kFoldBlock), 0, s, plan->d_segments,
-                       plan->d_big_segments, parts, d_params, d_sums);
+  hipLaunchKernelGGL(k_fold_stats<false>, dim3(fold_grid(nseg)), dim3(256), 0, s, plan->d_segments, nseg,
+                     static_cast<const int*>(nullptr), parts, d_params, d_sums);
+  if (const int nb = static_cast<int>(plan->big_stat_segments.size()))
+    hipLaunchKernelGGL(k_fold_stats<true>, dim3(nb), dim3(kFoldBlock), 0, s, plan->d_segments, nseg,
+                       plan->d_big_stat_segments, parts, d_params, d_sums);
   return launch_status();
 }
 
@@ -995,26 +824,8 @@ qv2_status qv2_fakequant_metrics(qv2_plan* plan, const qv2_qparams* d_params, qv
   qv2_status st = check_call(plan, d_params, d_sums, d_workspace, workspace_bytes);
   if (st != QV2_OK) return st;
   if ((st = ensure_uploaded(plan)) != QV2_OK) return st;
-  hipStream_t s = static_cast<hipStream_t>(hip_stream);
-  ErrPartial* parts = static_cast<ErrPartial*>(d_workspace);
-  const int n_stream = static_cast<int>(plan->n_stream_tiles);
-  const int n_rows = static_cast<int>(plan->tiles.size()) - n_stream;
-  const int nseg = static_cast<int>(plan->segments.size());
-  if (n_stream > 0) {
-    Timed timed(plan, QV2_K_QUANT_STREAM, s);
-    hipLaunchKernelGGL(k_quant_stream, dim3(n_stream), dim3(kBlock), 0, s, plan->d_descs,
-                       plan->d_tiles, d_params, parts);
-  }
-  if (n_rows > 0) {
-    Timed timed(plan, QV2_K_QUANT_ROWS, s);
-    hipLaunchKernelGGL(k_quant_rows, dim3(n_rows), dim3(kBlock), 0, s, plan->d_descs,
-                       plan->d_tiles + n_stream, d_params, parts);
-  }
-  hipLaunchKernelGGL(k_fold_err<ErrPartial>, dim3((nseg + kWaves - 1) / kWaves), dim3(kBlock), 0, s,
-                     plan->d_segments, nseg, parts, d_sums);
-  if (const int nb = static_cast<int>(plan->big_segments.size()))
-    hipLaunchKernelGGL(k_fold_err_big<ErrPartial>, dim3(nb), dim3(kFoldBlock), 0, s, plan->d_segments,
-                       plan->d_big_segments, parts, d_sums);
+  launch_quant<false>(plan, d_params, d_sums, static_cast<ErrPartial3*>(d_workspace),
+                      static_cast<hipStream_t>(hip_stream));
   return launch_status();
 }
 
@@ -1029,14 +840,14 @@ qv2_status qv2_pair_metrics(qv2_plan* plan, qv2_pair_sums* d_pair_sums, void* d_
   const int nt = static_cast<int>(plan->pair_tensors.size());
   if (n_tiles > 0) {
     Timed timed(plan, QV2_K_PAIR_STREAM, s);
-    hipLaunchKernelGGL(k_pair_stream, dim3(n_tiles), dim3(kBlock), 0, s, plan->d_descs,
+    hipLaunchKernelGGL((k_pair_stream<kBlockRead, kVecRead / 2>), dim3(n_tiles), dim3(kBlockRead), 0, s,
                        plan->d_pair_tiles, parts);
   }
-  hipLaunchKernelGGL(k_fold_pair<ErrPartial>, dim3((nt + kWaves - 1) / kWaves), dim3(kBlock), 0, s,
-                     plan->d_pair_tensors, nt, parts, d_pair_sums);
+  hipLaunchKernelGGL((k_fold_pair<false, ErrPartial>), dim3(fold_grid(nt)), dim3(256), 0, s,
+                     plan->d_pair_tensors, nt, static_cast<const int*>(nullptr), parts, d_pair_sums);
   if (const int nb = static_cast<int>(plan->big_pair_tensors.size()))
-    hipLaunchKernelGGL(k_fold_pair_big<ErrPartial>, dim3(nb), dim3(kFoldBlock), 0, s, plan->d_pair_tensors,
-                       plan->d_big_pair_tensors, parts, d_pair_sums);
+    hipLaunchKernelGGL((k_fold_pair<true, ErrPartial>), dim3(nb), dim3(kFoldBlock), 0, s,
+                       plan->d_pair_tensors, nt, plan->d_big_pair_tensors, parts, d_pair_sums);
   return launch_status();
 }
 
@@ -1050,30 +861,13 @@ qv2_status qv2_fakequant_pair_metrics(qv2_plan* plan, const qv2_qparams* d_param
   if ((st = ensure_uploaded(plan)) != QV2_OK) return st;
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   ErrPartial3* parts = static_cast<ErrPartial3*>(d_workspace);
-  const int n_stream = static_cast<int>(plan->n_stream_tiles);
-  const int n_rows = static_cast<int>(plan->tiles.size()) - n_stream;
-  const int nseg = static_cast<int>(plan->segments.size());
+  launch_quant<true>(plan, d_params, d_sums, parts, s);
   const int nt = static_cast<int>(plan->fused_pair_tensors.size());
-  if (n_stream > 0) {
-    Timed timed(plan, QV2_K_QUANTPAIR_STREAM, s);
-    hipLaunchKernelGGL(k_quantpair_stream, dim3(n_stream), dim3(kBlock), 0, s, plan->d_descs,
-                       plan->d_tiles, d_params, parts);
-  }
-  if (n_rows > 0) {
-    Timed timed(plan, QV2_K_QUANTPAIR_ROWS, s);
-    hipLaunchKernelGGL(k_quantpair_rows, dim3(n_rows), dim3(kBlock), 0, s, plan->d_descs,
-                       plan->d_tiles + n_stream, d_params, parts);
-  }
-  hipLaunchKernelGGL(k_fold_err<ErrPartial3>, dim3((nseg + kWaves - 1) / kWaves), dim3(kBlock), 0, s,
-                     plan->d_segments, nseg, parts, d_sums);
-  if (const int nb = static_cast<int>(plan->big_segments.size()))
-    hipLaunchKernelGGL(k_fold_err_big<ErrPartial3>, dim3(nb), dim3(kFoldBlock), 0, s,
-                       plan->d_segments, plan->d_big_segments, parts, d_sums);
-  hipLaunchKernelGGL(k_fold_pair<ErrPartial3>, dim3((nt + kWaves - 1) / kWaves), dim3(kBlock), 0, s,
-                     plan->d_fused_pair_tensors, nt, parts, d_pair_sums);
+  hipLaunchKernelGGL((k_fold_pair<false, ErrPartial3>), dim3(fold_grid(nt)), dim3(256), 0, s,
+                     plan->d_fused_pair_tensors, nt, static_cast<const int*>(nullptr), parts, d_pair_sums);
   if (const int nb = static_cast<int>(plan->big_fused_pair_tensors.size()))
-    hipLaunchKernelGGL(k_fold_pair_big<ErrPartial3>, dim3(nb), dim3(kFoldBlock), 0, s,
-                       plan->d_fused_pair_tensors, plan->d_big_fused_pair_tensors, parts, d_pair_sums);
+    hipLaunchKernelGGL((k_fold_pair<true, ErrPartial3>), dim3(nb), dim3(kFoldBlock), 0, s,
+                       plan->d_fused_pair_tensors, nt, plan->d_big_fused_pair_tensors, parts, d_pair_sums);
   return launch_status();
 }
 

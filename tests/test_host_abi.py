@@ -75,12 +75,12 @@ def test_plan_rejects_empty_and_null():
 
 
 def test_plan_tiling_counts():
-    T = 32768                                                   # default stream tile
+    TR, TQ = 32768, 2048                                        # default read / quantize stream tiles
     rows = [
-        _row(200_704, qrun=FAKE),                               # 7 stream tiles (6 full + 4096)
-        _row(9408),                                             # 1 stream tile
+        _row(200_704, qrun=FAKE),                               # 7 read tiles (6 full + 4096), 98 quantize tiles
+        _row(9408),                                             # 1 read tile, 5 quantize tiles
         _row(32 * 9, qb.QV2_SYM_CHANNEL, 32),                   # 1 row-group tile of 32 rows
-        _row(4096 * 40000, qb.QV2_SYM_CHANNEL, 4096),           # rows longer than a tile: 2 tiles each
+        _row(4096 * 40000, qb.QV2_SYM_CHANNEL, 4096),           # rows longer than a tile: 2 / 20 tiles each
         _row(2048 * 512, qb.QV2_SYM_CHANNEL, 2048),             # 16 rows per row-group tile -> 128 tiles
         _row(3000 * 3, qb.QV2_SYM_CHANNEL, 3000),               # at most 1024 rows per tile -> 3 tiles
     ]
@@ -88,13 +88,15 @@ def test_plan_tiling_counts():
     assert p.num_tensors == 6
     assert p.num_segments == 1 + 1 + 32 + 4096 + 2048 + 3000
     assert p.segment_begin == [0, 1, 2, 34, 34 + 4096, 34 + 4096 + 2048]
-    assert p.num_tiles == 7 + 1 + 1 + 4096 * 2 + 128 + 3
+    n_row_tiles = 1 + 128 + 3
+    assert p.num_tiles == 7 + 1 + 4096 * 2 + n_row_tiles
+    assert p.num_quant_tiles == 98 + 5 + 4096 * 20 + n_row_tiles
     assert p.num_pair_tiles == 7
-    n_parts = 7 + 1 + 32 + 4096 * 2 + 2048 + 3000
+    n_parts = 98 + 5 + 4096 * 20 + 32 + 2048 + 3000            # the quantize pass has the most partials
     assert p.workspace_bytes >= n_parts * 24 and p.workspace_bytes % 256 == 0
     assert qb.lib().qv2_plan_segment_begin(p.handle, 6) == -1
     p.close()
-    assert (200_704 + T - 1) // T == 7
+    assert (200_704 + TR - 1) // TR == 7 and (200_704 + TQ - 1) // TQ == 98 and (40000 + TQ - 1) // TQ == 20
 
 
 def test_device_calls_validate_before_touching_the_gpu():
