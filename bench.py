@@ -33,11 +33,12 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0   # MI355X published HBM3E bandwidth
+ROCPROF_NAMES = {"k_quantpair_stream": "k_quant_stream<256, 2, true>", "k_pair_stream": "k_pair_stream<512, 4>"}
 
 # HBM bytes per launch of the dominant kernel on the resnet50 b256 workload from rocprofv3
 # --pmc (FETCH_SIZE and WRITE_SIZE runs, each scaled by a copy kernel of known size); see
 # profiles/sensitivity_pass_resnet50_b256.txt.
-TRAFFIC_BYTES = {"k_pair_stream": 21_697_385_665, "k_quantpair_stream": None}
+TRAFFIC_BYTES = {"k_pair_stream": 21_697_127_098, "k_quantpair_stream": 24_627_581_264}
 
 
 def parse():
@@ -253,7 +254,7 @@ def main():
         "frac_of_hbm_peak": round(moved / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
         "layers_per_s": round(n_layers / (ms_per_step * 1e-3), 1),
         "calls": calls_of(main_r), "kernels_ms": main_r["kernels_ms"],
-        "roofline": {"bound": "hbm", "kernel": kname, "achieved": round(k_gbps, 1),
+        "roofline": {"bound": "hbm", "kernel": kname, "rocprof_name": ROCPROF_NAMES[kname], "achieved": round(k_gbps, 1),
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(k_gbps / HBM_PEAK_GBPS, 4),
                      "traffic": TRAFFIC_BYTES.get(kname) if headline else None,
                      "algorithmic_bytes_per_launch": kbytes, "avg_launch_ms": round(kms, 4)},
