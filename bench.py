@@ -260,6 +260,12 @@ def main():
                      "algorithmic_bytes_per_launch": kbytes, "avg_launch_ms": round(kms, 4)},
         "min_adjacent_score_gap": float(np.min(np.diff(np.sort(last["score"])))) if n_layers > 1 else None,
     }
+    # the step after the ranking (Sec. 7, Eq. 17): layers kept in fp32 per BOPs reduction target
+    tables = {"resnet50": synth.resnet50_layers, "resnet18": synth.resnet18_layers,
+              "vgg16": synth.vgg16_layers, "mobilenetv2": synth.mobilenetv2_layers}
+    macs = synth.layer_macs(tables[args.workload]())
+    out["bops_cut_layers_kept_fp32"] = {str(t): qb.qv2_bops_select(last["order"], macs, float(t))[1]
+                                        for t in (60, 50, 40, 30, 20)}
     if other is not None:
         o_bytes = bytes_cal + (bytes_fq + bytes_pair if args.mode == "fused" else bytes_fqpair)
         out["other_pass"] = {"pass": "three separate calls" if args.mode == "fused" else "fused",

@@ -233,6 +233,35 @@ qv2_status qv2_rank(const double* w_sqnr_db, const double* a_sqnr_db,
                     const int32_t* layer_pos, int32_t n_layers,
                     const qv2_rank_config* cfg, int32_t* order_out, double* score_out);
 
+/* ---- after the ranking: baselines and the BOPs cut (Sec. 7; need no GPU) ---- */
+
+/* Sensitivity lists of the paper's two compile-time baselines, in this library's
+ * convention (index 0 = the layer kept in fp32 first).
+ *  QV2_ORDER_INORDER: quantization proceeds from the first layer on, so the layers
+ *    still in fp32 at any budget are the last ones: n-1, ..., 0 (w_sqnr_db unused).
+ *  QV2_ORDER_WEIGHT_SQNR: ascending weight SQNR, equal values keep layer order.
+ * Errors: ERR_NULL, ERR_SHAPE (n_layers <= 0), ERR_SCHEME (unknown kind),
+ * ERR_NONFINITE (NaN SQNR). */
+typedef enum { QV2_ORDER_INORDER = 0, QV2_ORDER_WEIGHT_SQNR = 1 } qv2_baseline;
+qv2_status qv2_baseline_order(int32_t kind, const double* w_sqnr_db, int32_t n_layers,
+                              int32_t* order_out);
+
+/* Eq. 17: BOPs reduction rate (%) = (1 - sum bits_i*MAC_i / sum 32*MAC_i) * 100 with
+ * bits_i = 32 where keep_fp32[i] != 0, else 8.  macs: finite, >= 0, not all zero
+ * (else ERR_NONFINITE). */
+qv2_status qv2_bops_reduction_pct(const double* macs, const uint8_t* keep_fp32, int32_t n_layers,
+                                  double* pct_out);
+
+/* Cuts a sensitivity list for a target BOPs reduction rate: layers are taken from the
+ * head of `order` and kept in fp32 while the rate stays >= target_pct; the walk stops
+ * at the first layer that would push it below (a prefix of the list is kept).
+ * keep_fp32_out[n_layers] by layer index; n_keep_out / achieved_pct_out may be NULL.
+ * Errors: ERR_NULL, ERR_SHAPE (n_layers <= 0, order not a permutation),
+ * ERR_NONFINITE (bad macs or NaN target). */
+qv2_status qv2_bops_select(const int32_t* order, const double* macs, int32_t n_layers,
+                           double target_pct, uint8_t* keep_fp32_out, int32_t* n_keep_out,
+                           double* achieved_pct_out);
+
 const char* qv2_status_string(qv2_status s);
 
 #ifdef __cplusplus

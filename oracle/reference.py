@@ -339,3 +339,57 @@ def rank_layers(w_sqnr, a_sqnr, w_mse, a_mse, pos=None, cfg: RankConfig | None =
             order.remove(l)
             order.insert(0, l)
     return order, G
+
+
+# ----------------------------------------------------------------------------
+# Sec. 7: baseline orders and the BOPs reduction rate (Eq. 17), plain Python
+# ----------------------------------------------------------------------------
+INORDER = 0
+WEIGHT_SQNR_ORDER = 1
+
+
+def baseline_order(kind: int, w_sqnr=None, n: int | None = None):
+    """Sensitivity lists of the two compile-time baselines, in this library's convention
+    (index 0 = the layer kept in fp32 first).
+    InOrder quantizes from the first layer on, so the layers still in fp32 at any budget are
+    the last ones: n-1, n-2, ..., 0.  Weight SQNR Order lists layers by ascending weight SQNR
+    (equal values keep layer order)."""
+    if kind == INORDER:
+        n = len(w_sqnr) if n is None else n
+        return list(range(n - 1, -1, -1))
+    if kind == WEIGHT_SQNR_ORDER:
+        vals = [float(v) for v in w_sqnr]
+        if any(math.isnan(v) for v in vals):
+            raise ValueError("NaN SQNR")
+        return sorted(range(len(vals)), key=lambda i: (vals[i], i))
+    raise ValueError(f"unknown baseline {kind}")
+
+
+def bops_reduction_pct(macs, keep_fp32) -> float:
+    """Eq. 17: (1 - BOPs(theta) / BOPs_fp32) * 100 with bits(theta_i) in {8, 32}."""
+    total = 0.0
+    mixed = 0.0
+    for m, k in zip(macs, keep_fp32):
+        total += 32.0 * float(m)
+        mixed += (32.0 if k else 8.0) * float(m)
+    return (1.0 - mixed / total) * 100.0
+
+
+def bops_select(order, macs, target_pct: float):
+    """Walk the sensitivity list from its head and keep layers in fp32 while the BOPs
+    reduction rate stays at or above target_pct; stop at the first layer that would push it
+    below.  Returns (keep_fp32 flags by layer, number kept, achieved rate)."""
+    n = len(macs)
+    if sorted(order) != list(range(n)):
+        raise ValueError("order is not a permutation")
+    if any((not math.isfinite(float(m))) or float(m) < 0 for m in macs) or not any(float(m) > 0 for m in macs):
+        raise ValueError("bad MAC counts")
+    keep = [False] * n
+    kept = 0
+    for l in order:
+        keep[l] = True
+        if bops_reduction_pct(macs, keep) < target_pct:
+            keep[l] = False
+            break
+        kept += 1
+    return keep, kept, bops_reduction_pct(macs, keep)

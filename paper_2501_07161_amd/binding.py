@@ -29,6 +29,7 @@ EXPORTS = (
     "qv2_workspace_bytes", "qv2_calibrate", "qv2_fakequant_metrics", "qv2_pair_metrics",
     "qv2_fakequant_pair_metrics", "qv2_plan_set_timing", "qv2_plan_kernel_ms",
     "qv2_finalize", "qv2_pair_finalize", "qv2_rank_config_default", "qv2_rank",
+    "qv2_baseline_order", "qv2_bops_reduction_pct", "qv2_bops_select",
     "qv2_status_string",
 )
 
@@ -99,6 +100,9 @@ def lib():
         L.qv2_rank_config_default.argtypes = [ctypes.POINTER(qv2_rank_config)]
         L.qv2_rank_config_default.restype = None
         L.qv2_rank.argtypes = [vp, vp, vp, vp, vp, i32, ctypes.POINTER(qv2_rank_config), vp, vp]
+        L.qv2_baseline_order.argtypes = [i32, vp, i32, vp]
+        L.qv2_bops_reduction_pct.argtypes = [vp, vp, i32, vp]
+        L.qv2_bops_select.argtypes = [vp, vp, i32, ctypes.c_double, vp, vp, vp]
         L.qv2_status_string.argtypes = [ctypes.c_int]
         L.qv2_status_string.restype = ctypes.c_char_p
         _lib = L
@@ -278,6 +282,41 @@ def qv2_rank(w_sqnr_db, a_sqnr_db, w_mse, a_mse, layer_pos=None, cfg: Optional[q
                           ctypes.byref(cfg) if cfg is not None else None,
                           order.ctypes.data, score.ctypes.data), "qv2_rank")
     return order[:n_layers], score[:n_layers]
+
+
+QV2_ORDER_INORDER, QV2_ORDER_WEIGHT_SQNR = 0, 1
+
+
+def qv2_baseline_order(kind: int, w_sqnr_db=None, n_layers: Optional[int] = None) -> np.ndarray:
+    ws = _f64(w_sqnr_db)
+    n = len(ws) if n_layers is None else n_layers
+    order = np.zeros(max(n, 1), np.int32)
+    _check(lib().qv2_baseline_order(kind, _ptr(ws), n, order.ctypes.data), "qv2_baseline_order")
+    return order[:n]
+
+
+def qv2_bops_reduction_pct(macs, keep_fp32) -> float:
+    m = _f64(macs)
+    k = np.ascontiguousarray(keep_fp32, dtype=np.uint8)
+    if len(k) != len(m):
+        raise QV2Error(QV2_ERR_SHAPE, "qv2_bops_reduction_pct")
+    out = ctypes.c_double()
+    _check(lib().qv2_bops_reduction_pct(m.ctypes.data, k.ctypes.data, len(m), ctypes.addressof(out)),
+           "qv2_bops_reduction_pct")
+    return out.value
+
+
+def qv2_bops_select(order, macs, target_pct: float):
+    """Returns (keep_fp32 flags by layer, number of layers kept, achieved reduction %)."""
+    o = np.ascontiguousarray(order, dtype=np.int32)
+    m = _f64(macs)
+    if len(o) != len(m):
+        raise QV2Error(QV2_ERR_SHAPE, "qv2_bops_select")
+    keep = np.zeros(max(len(m), 1), np.uint8)
+    nk, pct = ctypes.c_int32(), ctypes.c_double()
+    _check(lib().qv2_bops_select(o.ctypes.data, m.ctypes.data, len(m), float(target_pct), keep.ctypes.data,
+                                 ctypes.addressof(nk), ctypes.addressof(pct)), "qv2_bops_select")
+    return keep[:len(m)].astype(bool), nk.value, pct.value
 
 
 # ----------------------------------------------------------------------------

@@ -311,6 +311,79 @@ qv2_status qv2_rank(const double* w_sqnr_db, const double* a_sqnr_db, const doub
   return QV2_OK;
 }
 
+// ---------------------------------------------------------------------------
+// Sec. 7: compile-time baseline orders and the BOPs reduction rate (Eq. 17).
+// ---------------------------------------------------------------------------
+qv2_status qv2_baseline_order(int32_t kind, const double* w_sqnr_db, int32_t n_layers,
+                              int32_t* order_out) {
+  if (!order_out) return QV2_ERR_NULL;
+  if (n_layers <= 0) return QV2_ERR_SHAPE;
+  if (kind == QV2_ORDER_INORDER) {
+    for (int32_t i = 0; i < n_layers; ++i) order_out[i] = n_layers - 1 - i;
+    return QV2_OK;
+  }
+  if (kind != QV2_ORDER_WEIGHT_SQNR) return QV2_ERR_SCHEME;
+  if (!w_sqnr_db) return QV2_ERR_NULL;
+  for (int32_t i = 0; i < n_layers; ++i) {
+    if (std::isnan(w_sqnr_db[i])) return QV2_ERR_NONFINITE;
+    order_out[i] = i;
+  }
+  std::stable_sort(order_out, order_out + n_layers,
+                   [&](int32_t a, int32_t b) { return w_sqnr_db[a] < w_sqnr_db[b]; });
+  return QV2_OK;
+}
+
+// Eq. 17 with bits in {8, 32}; the layers are summed in index order.
+static double bops_reduction(const double* macs, const uint8_t* keep, int32_t n) {
+  double total = 0.0, mixed = 0.0;
+  for (int32_t i = 0; i < n; ++i) {
+    total += 32.0 * macs[i];
+    mixed += (keep[i] ? 32.0 : 8.0) * macs[i];
+  }
+  return (1.0 - mixed / total) * 100.0;
+}
+
+qv2_status qv2_bops_reduction_pct(const double* macs, const uint8_t* keep_fp32, int32_t n_layers,
+                                  double* pct_out) {
+  if (!macs || !keep_fp32 || !pct_out) return QV2_ERR_NULL;
+  if (n_layers <= 0) return QV2_ERR_SHAPE;
+  bool any = false;
+  for (int32_t i = 0; i < n_layers; ++i) {
+    if (!std::isfinite(macs[i]) || macs[i] < 0.0) return QV2_ERR_NONFINITE;
+    any = any || macs[i] > 0.0;
+  }
+  if (!any) return QV2_ERR_NONFINITE;
+  *pct_out = bops_reduction(macs, keep_fp32, n_layers);
+  return QV2_OK;
+}
+
+qv2_status qv2_bops_select(const int32_t* order, const double* macs, int32_t n_layers,
+                           double target_pct, uint8_t* keep_fp32_out, int32_t* n_keep_out,
+                           double* achieved_pct_out) {
+  if (!order || !macs || !keep_fp32_out) return QV2_ERR_NULL;
+  if (n_layers <= 0) return QV2_ERR_SHAPE;
+  std::vector<char> seen(n_layers, 0);
+  bool any = false;
+  for (int32_t i = 0; i < n_layers; ++i) {
+    if (order[i] < 0 || order[i] >= n_layers || seen[order[i]]) return QV2_ERR_SHAPE;
+    seen[order[i]] = 1;
+    if (!std::isfinite(macs[i]) || macs[i] < 0.0) return QV2_ERR_NONFINITE;
+    any = any || macs[i] > 0.0;
+  }
+  if (!any || std::isnan(target_pct)) return QV2_ERR_NONFINITE;
+  std::memset(keep_fp32_out, 0, static_cast<size_t>(n_layers));
+  int32_t kept = 0;
+  for (int32_t k = 0; k < n_layers; ++k) {
+    const int32_t l = order[k];
+    keep_fp32_out[l] = 1;
+    if (bops_reduction(macs, keep_fp32_out, n_layers) < target_pct) { keep_fp32_out[l] = 0; break; }
+    ++kept;
+  }
+  if (n_keep_out) *n_keep_out = kept;
+  if (achieved_pct_out) *achieved_pct_out = bops_reduction(macs, keep_fp32_out, n_layers);
+  return QV2_OK;
+}
+
 const char* qv2_status_string(qv2_status s) {
   switch (s) {
     case QV2_OK: return "ok";

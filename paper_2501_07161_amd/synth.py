@@ -177,6 +177,12 @@ def vgg16_layers():
     return L
 
 
+def layer_macs(layers) -> List[int]:
+    """Multiply-accumulates per image of each row of a shape table:
+    output elements x (input channels per group x kernel area)."""
+    return [math.prod(row[2]) * math.prod(row[1][1:]) for row in layers]
+
+
 def _fan_in(wshape) -> int:
     return math.prod(wshape[1:])
 

@@ -237,3 +237,42 @@ def test_rank_errors():
                       order.ctypes.data, None) == qb.QV2_ERR_NULL
     assert L.qv2_rank(arr.ctypes.data, None, None, arr.ctypes.data, None, 3, None,
                       None, None) == qb.QV2_ERR_NULL
+
+
+# ----------------------------------------------------------------------------
+# baselines and BOPs cut (Sec. 7, Eq. 17): identical to the oracle
+# ----------------------------------------------------------------------------
+def test_bops_and_baselines_match_oracle():
+    rng = np.random.default_rng(31)
+    for trial in range(200):
+        n = int(rng.integers(1, 130))
+        macs = rng.integers(0, 10 ** 9, n).astype(np.float64)
+        macs[rng.integers(0, n)] += 1.0
+        w = rng.uniform(10, 60, n).round(0 if trial % 2 else 6)
+        for kind in (qb.QV2_ORDER_INORDER, qb.QV2_ORDER_WEIGHT_SQNR):
+            order = qb.qv2_baseline_order(kind, w)
+            assert order.tolist() == orc.baseline_order(kind, list(w))
+            tgt = float(rng.uniform(-5, 80))
+            keep, k, pct = qb.qv2_bops_select(order, macs, tgt)
+            o_keep, o_k, o_pct = orc.bops_select(order.tolist(), list(macs), tgt)
+            assert keep.tolist() == o_keep and k == o_k and pct == o_pct
+            assert qb.qv2_bops_reduction_pct(macs, keep) == orc.bops_reduction_pct(list(macs), o_keep)
+    assert qb.qv2_baseline_order(qb.QV2_ORDER_INORDER, None, 4).tolist() == [3, 2, 1, 0]
+
+
+def test_bops_errors():
+    with pytest.raises(qb.QV2Error) as e:
+        qb.qv2_bops_select([0, 0, 1], [1.0, 1.0, 1.0], 50.0)
+    assert e.value.status == qb.QV2_ERR_SHAPE
+    with pytest.raises(qb.QV2Error) as e:
+        qb.qv2_bops_select([0, 1], [0.0, 0.0], 50.0)
+    assert e.value.status == qb.QV2_ERR_NONFINITE
+    with pytest.raises(qb.QV2Error) as e:
+        qb.qv2_bops_select([0, 1], [1.0, -2.0], 50.0)
+    assert e.value.status == qb.QV2_ERR_NONFINITE
+    with pytest.raises(qb.QV2Error) as e:
+        qb.qv2_baseline_order(7, [1.0, 2.0])
+    assert e.value.status == qb.QV2_ERR_SCHEME
+    with pytest.raises(qb.QV2Error) as e:
+        qb.qv2_baseline_order(qb.QV2_ORDER_WEIGHT_SQNR, [1.0, math.nan])
+    assert e.value.status == qb.QV2_ERR_NONFINITE

@@ -400,3 +400,72 @@ def test_rank_bruteforce_properties():
         assert all(m[order[i]] >= m[order[i + 1]] for i in range(k - 1))   # ... by descending MSE
         rest = order[k:]
         assert all((G[rest[i]], rest[i]) <= (G[rest[i + 1]], rest[i + 1]) for i in range(len(rest) - 1))
+
+
+# ----------------------------------------------------------------------------
+# Sec. 7: baselines and the BOPs reduction rate (Eq. 17)
+# ----------------------------------------------------------------------------
+def test_bops_closed_forms():
+    macs = [118_013_952, 115_605_504, 231_211_008, 512_000]
+    # everything int8: 1 - 8/32 = 75 %; everything fp32: 0 %
+    assert orc.bops_reduction_pct(macs, [False] * 4) == pytest.approx(75.0, abs=1e-12)
+    assert orc.bops_reduction_pct(macs, [True] * 4) == pytest.approx(0.0, abs=1e-12)
+    # hand-worked: MACs 1, 1, 2 with the last layer in fp32: 1 - (8 + 8 + 64) / 128 = 37.5 %
+    assert orc.bops_reduction_pct([1, 1, 2], [False, False, True]) == pytest.approx(37.5, abs=1e-12)
+    # the rate depends on MAC shares only
+    assert orc.bops_reduction_pct([3, 3, 6], [False, False, True]) == pytest.approx(37.5, abs=1e-12)
+
+
+def test_bops_select_hand_worked_and_bruteforce():
+    macs = [1.0, 1.0, 2.0, 4.0]                    # shares 12.5 / 12.5 / 25 / 50 %
+    order = [2, 0, 3, 1]
+    # keeping layer 2 costs 0.75 * 25 = 18.75 points, layer 0 a further 9.375, layer 3 37.5
+    assert orc.bops_select(order, macs, 75.0) == ([False] * 4, 0, pytest.approx(75.0))
+    keep, k, pct = orc.bops_select(order, macs, 56.25)
+    assert (keep, k) == ([False, False, True, False], 1) and pct == pytest.approx(56.25)
+    keep, k, pct = orc.bops_select(order, macs, 50.0)
+    assert (keep, k) == ([False, False, True, False], 1)      # 46.875 would be below 50
+    keep, k, pct = orc.bops_select(order, macs, 46.0)
+    assert (keep, k) == ([True, False, True, False], 2) and pct == pytest.approx(46.875)
+    keep, k, pct = orc.bops_select(order, macs, 0.0)
+    assert k == 4 and pct == pytest.approx(0.0, abs=1e-12)
+    # brute force: the kept set is the longest prefix of the list that meets the target
+    rng = np.random.default_rng(13)
+    for _ in range(200):
+        n = int(rng.integers(1, 30))
+        m = rng.integers(1, 1000, n).astype(float)
+        o = list(rng.permutation(n))
+        tgt = float(rng.uniform(-5, 80))
+        keep, k, pct = orc.bops_select(o, m, tgt)
+        best = 0
+        for j in range(n + 1):
+            flags = [i in o[:j] for i in range(n)]
+            if orc.bops_reduction_pct(m, flags) >= tgt:
+                best = j
+            else:
+                break
+        assert k == best and keep == [i in o[:k] for i in range(n)]
+        assert pct >= tgt or k == 0
+    with pytest.raises(ValueError):
+        orc.bops_select([0, 0, 1], [1.0, 1.0, 1.0], 50.0)
+    with pytest.raises(ValueError):
+        orc.bops_select([0, 1], [0.0, 0.0], 50.0)
+
+
+def test_baseline_orders():
+    w = [40.0, 38.0, 45.0, 30.0, 38.0]
+    assert orc.baseline_order(orc.INORDER, n=5) == [4, 3, 2, 1, 0]
+    assert orc.baseline_order(orc.WEIGHT_SQNR_ORDER, w) == [3, 1, 4, 0, 2]
+    assert orc.baseline_order(orc.WEIGHT_SQNR_ORDER, w) == list(np.argsort(w, kind="stable"))
+    # weight gain 1, activation gain 0 on raw SQNR is not the delta list: the two differ
+    assert orc.rank_layers(w, None, [1.0] * 5, None, cfg=orc.RankConfig(1.0, 0.0, mse_source=1))[0] != \
+        orc.baseline_order(orc.WEIGHT_SQNR_ORDER, w)
+
+
+def test_layer_macs_of_the_shape_tables():
+    from paper_2501_07161_amd import synth
+    # published per-image MAC totals: ResNet-18 1.81 G, ResNet-50 (v1, stride on the first 1x1) 3.86 G,
+    # VGG-16 15.47 G, MobileNetV2 0.30 G
+    for fn, want in ((synth.resnet18_layers, 1.814e9), (synth.resnet50_layers, 3.86e9),
+                     (synth.vgg16_layers, 15.47e9), (synth.mobilenetv2_layers, 0.300e9)):
+        assert sum(synth.layer_macs(fn())) == pytest.approx(want, rel=0.02)
