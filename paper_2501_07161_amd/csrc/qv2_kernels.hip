@@ -470,8 +470,11 @@ __device__ __forceinline__ void quant_body(gf4_ptr v4, gf4_ptr b4, gu32_ptr cw, 
   }
 }
 
+#ifndef QV2_QUANT_WAVES_PER_EU
+#define QV2_QUANT_WAVES_PER_EU 1    // occupancy floor asked of the register allocator
+#endif
 template <int BLOCK, int V, bool PAIR>
-__global__ __launch_bounds__(BLOCK) void k_quant_stream(const Tile* __restrict__ tiles,
+__global__ __launch_bounds__(BLOCK, QV2_QUANT_WAVES_PER_EU) void k_quant_stream(const Tile* __restrict__ tiles,
                                                         const qv2_qparams* __restrict__ params,
                                                         ErrPartial3* __restrict__ parts) {
   const Tile tl = tiles[blockIdx.x];
