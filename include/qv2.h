@@ -201,6 +201,19 @@ qv2_status qv2_fakequant_pair_metrics(qv2_plan* plan, const qv2_qparams* d_param
                                       qv2_sums* d_sums, qv2_pair_sums* d_pair_sums,
                                       void* d_workspace, size_t workspace_bytes, void* hip_stream);
 
+/* qv2_fakequant_pair_metrics that also accumulates the cross terms of the cosine
+ * similarity (Sec. 6.1 Eq. 8, one of the paper's four candidate local metrics):
+ *   d_seg_xxhat[num_segments] : sum x * xhat per segment (tensor vs its dequantized form)
+ *   d_pair_xq[num_tensors]    : sum x * qrun per tensor (0 for tensors without qrun)
+ * Both DEVICE, written, 8-byte aligned.  All other outputs as qv2_fakequant_pair_metrics
+ * (codes, sum_x2, sum_e2 bit-identical to it).  The norms of xhat and qrun follow from
+ * the energies already kept: sum b^2 = sum (a-b)^2 - sum a^2 + 2 sum a*b. */
+qv2_status qv2_fakequant_pair_metrics_cos(qv2_plan* plan, const qv2_qparams* d_params,
+                                          qv2_sums* d_sums, qv2_pair_sums* d_pair_sums,
+                                          double* d_seg_xxhat, double* d_pair_xq,
+                                          void* d_workspace, size_t workspace_bytes,
+                                          void* hip_stream);
+
 /* ---- host finalize and ranking (need no GPU) ----------------------------- */
 
 /* Eq. 6-7 and the tensor statistics from host copies of params and sums; a
@@ -213,6 +226,15 @@ qv2_status qv2_finalize(const qv2_plan* plan, const qv2_qparams* h_params,
 /* MSE and SQNR (dB) of n pair-sum records; entries with n == 0 give 0 and +inf. */
 qv2_status qv2_pair_finalize(const qv2_pair_sums* h_pair, int32_t n,
                              double* h_mse, double* h_sqnr_db);
+
+/* Eq. 8 per tensor from host copies of the sums and cross terms:
+ * h_cos_quant[num_tensors] = cos(x, xhat) (a per-channel tensor as one vector),
+ * h_cos_pair[num_tensors] = cos(x, qrun), NaN for tensors without qrun.
+ * A zero vector: 1 when both vectors are zero, else 0 (the paper is silent).
+ * ERR_NONFINITE if any input sum is NaN / Inf (outputs still written). */
+qv2_status qv2_cosine_finalize(const qv2_plan* plan, const qv2_sums* h_sums,
+                               const double* h_seg_xxhat, const qv2_pair_sums* h_pair,
+                               const double* h_pair_xq, double* h_cos_quant, double* h_cos_pair);
 
 void qv2_rank_config_default(qv2_rank_config* cfg);
 

@@ -183,3 +183,20 @@ double orc_sqnr_db(double sum_x2, double sum_e2)
     if (sum_e2 == 0.0) return INFINITY;
     return 10.0 * log10(sum_x2 / sum_e2);
 }
+
+/* Sec. 6.1 Eq. 8: the three sums behind the cosine similarity of two tensors,
+ * sum(a*b), sum(a^2), sum(b^2), fp64. */
+void orc_cosine_sums(const float *a, const float *b, int64_t n,
+                     double *sab, double *saa, double *sbb)
+{
+    double xy = 0.0, xx = 0.0, yy = 0.0;
+    for (int64_t i = 0; i < n; ++i) {
+        double x = (double)a[i], y = (double)b[i];
+        xy += x * y;
+        xx += x * x;
+        yy += y * y;
+    }
+    *sab = xy;
+    *saa = xx;
+    *sbb = yy;
+}

@@ -63,6 +63,8 @@ def lib():
         L.orc_quantize.argtypes = [_F, i64, ctypes.c_float, ctypes.c_int32, _I8]
         L.orc_dequantize.argtypes = [_I8, i64, ctypes.c_float, ctypes.c_int32, _F]
         L.orc_error_sums.argtypes = [_F, _F, i64, _D, _D]
+        L.orc_cosine_sums.argtypes = [_F, _F, i64, _D, _D, _D]
+        L.orc_cosine_sums.restype = None
         L.orc_mse.argtypes = [ctypes.c_double, i64]
         L.orc_mse.restype = ctypes.c_double
         L.orc_sqnr_db.argtypes = [ctypes.c_double, ctypes.c_double]
@@ -146,6 +148,19 @@ def error_sums(x, xhat):
     s2, e2 = ctypes.c_double(), ctypes.c_double()
     lib().orc_error_sums(_fp(a), _fp(b), a.size, ctypes.byref(s2), ctypes.byref(e2))
     return s2.value, e2.value
+
+
+def cosine_similarity(a, b) -> float:
+    """Sec. 6.1 Eq. 8: A.B / (|A| |B|), fp64.  The paper does not say what a zero vector
+    gives; reading taken: two zero vectors are identical (1), one zero vector gives 0."""
+    x, y = _f32(a), _f32(b)
+    if x.size != y.size:
+        raise ValueError("size mismatch")
+    sab, saa, sbb = ctypes.c_double(), ctypes.c_double(), ctypes.c_double()
+    lib().orc_cosine_sums(_fp(x), _fp(y), x.size, ctypes.byref(sab), ctypes.byref(saa), ctypes.byref(sbb))
+    if saa.value == 0.0 or sbb.value == 0.0:
+        return 1.0 if saa.value == sbb.value else 0.0
+    return sab.value / (math.sqrt(saa.value) * math.sqrt(sbb.value))
 
 
 def mse(sum_e2: float, n: int) -> float:

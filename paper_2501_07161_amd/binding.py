@@ -27,7 +27,8 @@ EXPORTS = (
     "qv2_plan_segment_begin", "qv2_plan_num_tiles", "qv2_plan_num_quant_tiles",
     "qv2_plan_num_pair_tiles",
     "qv2_workspace_bytes", "qv2_calibrate", "qv2_fakequant_metrics", "qv2_pair_metrics",
-    "qv2_fakequant_pair_metrics", "qv2_plan_set_timing", "qv2_plan_kernel_ms",
+    "qv2_fakequant_pair_metrics", "qv2_fakequant_pair_metrics_cos", "qv2_cosine_finalize",
+    "qv2_plan_set_timing", "qv2_plan_kernel_ms",
     "qv2_finalize", "qv2_pair_finalize", "qv2_rank_config_default", "qv2_rank",
     "qv2_baseline_order", "qv2_bops_reduction_pct", "qv2_bops_select",
     "qv2_status_string",
@@ -93,6 +94,8 @@ def lib():
         L.qv2_fakequant_metrics.argtypes = [vp, vp, vp, vp, sz, vp]
         L.qv2_pair_metrics.argtypes = [vp, vp, vp, sz, vp]
         L.qv2_fakequant_pair_metrics.argtypes = [vp, vp, vp, vp, vp, sz, vp]
+        L.qv2_fakequant_pair_metrics_cos.argtypes = [vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.qv2_cosine_finalize.argtypes = [vp, vp, vp, vp, vp, vp, vp]
         L.qv2_plan_set_timing.argtypes = [vp, i32]
         L.qv2_plan_kernel_ms.argtypes = [vp, i32, ctypes.POINTER(ctypes.c_float)]
         L.qv2_finalize.argtypes = [vp, vp, vp, vp]
@@ -230,6 +233,32 @@ def qv2_fakequant_pair_metrics(plan: Plan, d_params, d_sums, d_pair_sums, d_work
     _check(lib().qv2_fakequant_pair_metrics(plan.handle, _ptr(d_params), _ptr(d_sums), _ptr(d_pair_sums),
                                             _ptr(d_workspace), wb, _stream(stream)),
            "qv2_fakequant_pair_metrics")
+
+
+def qv2_fakequant_pair_metrics_cos(plan: Plan, d_params, d_sums, d_pair_sums, d_seg_xxhat, d_pair_xq,
+                                   d_workspace, workspace_bytes=None, stream=None):
+    wb = workspace_bytes if workspace_bytes is not None else d_workspace.numel() * d_workspace.element_size()
+    _check(lib().qv2_fakequant_pair_metrics_cos(plan.handle, _ptr(d_params), _ptr(d_sums), _ptr(d_pair_sums),
+                                                _ptr(d_seg_xxhat), _ptr(d_pair_xq), _ptr(d_workspace), wb,
+                                                _stream(stream)), "qv2_fakequant_pair_metrics_cos")
+
+
+def qv2_cosine_finalize(plan: Plan, h_sums, h_seg_xxhat, h_pair, h_pair_xq, strict: bool = True):
+    """Returns (cos(x, xhat), cos(x, qrun)) per tensor."""
+    hs = np.ascontiguousarray(h_sums, dtype=SUMS)
+    hp = np.ascontiguousarray(h_pair, dtype=PAIR_SUMS)
+    sx = _f64(h_seg_xxhat)
+    px = _f64(h_pair_xq)
+    if hs.size != plan.num_segments or sx.size != plan.num_segments or hp.size != plan.num_tensors \
+            or px.size != plan.num_tensors:
+        raise QV2Error(QV2_ERR_SHAPE, "qv2_cosine_finalize")
+    cq = np.zeros(plan.num_tensors, np.float64)
+    cp = np.zeros(plan.num_tensors, np.float64)
+    st = lib().qv2_cosine_finalize(plan.handle, hs.ctypes.data, sx.ctypes.data, hp.ctypes.data,
+                                   px.ctypes.data, cq.ctypes.data, cp.ctypes.data)
+    if st != QV2_OK and (strict or st != QV2_ERR_NONFINITE):
+        raise QV2Error(st, "qv2_cosine_finalize")
+    return cq, cp
 
 
 def qv2_finalize(plan: Plan, h_params: np.ndarray, h_sums: np.ndarray, strict: bool = True) -> np.ndarray:

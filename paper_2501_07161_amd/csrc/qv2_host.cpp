@@ -156,7 +156,7 @@ qv2_status qv2_plan_create(const qv2_tensor* h_tensors, int32_t n_tensors, qv2_p
       p->big_fused_pair_tensors.push_back(static_cast<int32_t>(i));
   }
   const size_t need = std::max({static_cast<size_t>(sp) * sizeof(qv2::StatPartial),
-                                static_cast<size_t>(ep) * sizeof(qv2::ErrPartial3),
+                                static_cast<size_t>(ep) * sizeof(qv2::ErrPartial5),
                                 static_cast<size_t>(pp) * sizeof(qv2::ErrPartial)});
   p->workspace_bytes = std::max<size_t>(256, round_up(need, 256));
   *out = p;
@@ -226,6 +226,36 @@ qv2_status qv2_pair_finalize(const qv2_pair_sums* h_pair, int32_t n, double* h_m
     finite = finite && std::isfinite(h_pair[i].sum_ref2) && std::isfinite(h_pair[i].sum_d2);
     h_mse[i] = h_pair[i].n > 0 ? h_pair[i].sum_d2 / static_cast<double>(h_pair[i].n) : 0.0;
     h_sqnr_db[i] = sqnr_db_of(h_pair[i].sum_ref2, h_pair[i].sum_d2);
+  }
+  return finite ? QV2_OK : QV2_ERR_NONFINITE;
+}
+
+// Sec. 6.1 Eq. 8 from the energies the quantize pass keeps: with d = a - b,
+// sum b^2 = sum d^2 - sum a^2 + 2 sum a*b.
+static double cosine_from(double saa, double sdd, double sab) {
+  const double sbb = std::max(0.0, sdd - saa + 2.0 * sab);
+  if (saa == 0.0 || sbb == 0.0) return saa == sbb ? 1.0 : 0.0;
+  return sab / (std::sqrt(saa) * std::sqrt(sbb));
+}
+
+qv2_status qv2_cosine_finalize(const qv2_plan* plan, const qv2_sums* h_sums, const double* h_seg_xxhat,
+                               const qv2_pair_sums* h_pair, const double* h_pair_xq,
+                               double* h_cos_quant, double* h_cos_pair) {
+  if (!plan || !h_sums || !h_seg_xxhat || !h_pair || !h_pair_xq || !h_cos_quant || !h_cos_pair)
+    return QV2_ERR_NULL;
+  bool finite = true;
+  for (size_t t = 0; t < plan->info.size(); ++t) {
+    const TensorInfo& d = plan->info[t];
+    double sx2 = 0.0, se2 = 0.0, sxh = 0.0;
+    for (int32_t s = d.seg0; s < d.seg0 + d.nseg; ++s) {
+      sx2 += h_sums[s].sum_x2; se2 += h_sums[s].sum_e2; sxh += h_seg_xxhat[s];
+    }
+    finite = finite && std::isfinite(sx2) && std::isfinite(se2) && std::isfinite(sxh) &&
+             std::isfinite(h_pair[t].sum_ref2) && std::isfinite(h_pair[t].sum_d2) &&
+             std::isfinite(h_pair_xq[t]);
+    h_cos_quant[t] = cosine_from(sx2, se2, sxh);
+    h_cos_pair[t] = h_pair[t].n > 0 ? cosine_from(h_pair[t].sum_ref2, h_pair[t].sum_d2, h_pair_xq[t])
+                                    : std::numeric_limits<double>::quiet_NaN();
   }
   return finite ? QV2_OK : QV2_ERR_NONFINITE;
 }

@@ -87,6 +87,7 @@ struct TensorInfo {            // host only
 struct StatPartial { float mn, mx; double sx, sx2; };   // calibrate, 24 B
 struct ErrPartial { double sx2, se2; };                 // pair pass, 16 B
 struct ErrPartial3 { double sx2, se2, sd2; };           // quantize passes, 24 B
+struct ErrPartial5 { double sx2, se2, sd2, sxh, sxq; }; // quantize pass with cosine cross terms, 40 B
 
 }  // namespace qv2
 

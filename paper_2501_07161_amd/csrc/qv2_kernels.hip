@@ -85,20 +85,35 @@ __device__ __forceinline__ double group_sum(double v, int w) {
   return v;
 }
 
-// Sums of up to three doubles over a workgroup of BLOCK threads; valid in thread 0.
-template <int BLOCK>
-__device__ __forceinline__ void block_sum3(double& a, double& b, double& c) {
+// Sums of N doubles over a workgroup of BLOCK threads; valid in thread 0.
+template <int BLOCK, int N>
+__device__ __forceinline__ void block_sum(double (&v)[N]) {
   constexpr int W = BLOCK / kWave;
-  a = group_sum(a, kWave); b = group_sum(b, kWave); c = group_sum(c, kWave);
+#pragma unroll
+  for (int k = 0; k < N; ++k) v[k] = group_sum(v[k], kWave);
   if (W == 1) return;
-  __shared__ double s[3][W];
+  __shared__ double s[N][W];
   const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
-  if (lane == 0) { s[0][wave] = a; s[1][wave] = b; s[2][wave] = c; }
+  if (lane == 0) {
+#pragma unroll
+    for (int k = 0; k < N; ++k) s[k][wave] = v[k];
+  }
   __syncthreads();
   if (threadIdx.x == 0) {
-    a = s[0][0]; b = s[1][0]; c = s[2][0];
-    for (int i = 1; i < W; ++i) { a += s[0][i]; b += s[1][i]; c += s[2][i]; }
+#pragma unroll
+    for (int k = 0; k < N; ++k) {
+      double t = s[k][0];
+      for (int i = 1; i < W; ++i) t += s[k][i];
+      v[k] = t;
+    }
   }
+}
+
+template <int BLOCK>
+__device__ __forceinline__ void block_sum3(double& a, double& b, double& c) {
+  double v[3] = {a, b, c};
+  block_sum<BLOCK, 3>(v);
+  a = v[0]; b = v[1]; c = v[2];
 }
 
 template <int BLOCK>
@@ -129,6 +144,12 @@ struct Acc4 {
     const double dx = x, dy = y, dz = z, dw = w;
     a = fma(dx, dx, a); b = fma(dy, dy, b); c = fma(dz, dz, c); d = fma(dw, dw, d);
   }
+  __device__ __forceinline__ void add_prod(const f4& u, const f4& v) {
+    a = fma(static_cast<double>(u.x), static_cast<double>(v.x), a);
+    b = fma(static_cast<double>(u.y), static_cast<double>(v.y), b);
+    c = fma(static_cast<double>(u.z), static_cast<double>(v.z), c);
+    d = fma(static_cast<double>(u.w), static_cast<double>(v.w), d);
+  }
   __device__ __forceinline__ double total() const { return (a + b) + (c + d); }
 };
 
@@ -143,25 +164,29 @@ __device__ __forceinline__ int head_elems(const void* p, int len) {
 // ---------------------------------------------------------------------------
 struct QP { float scale, inv, zpf; };
 
-// Returns the code as a float in [-128,127]; err receives x - xhat.
-__device__ __forceinline__ float quant1(float x, const QP& q, float& err) {
+// Returns the code as a float in [-128,127]; xhat is the dequantized value, err = x - xhat.
+__device__ __forceinline__ float quant1(float x, const QP& q, float& err, float& xhat) {
   const float t = x * q.inv;                       // fp32 multiply
   const float r = rintf(t);                        // round half to even
   // integer add of the zero-point: exact in fp32 below 2^24, saturates above
   const float c = fminf(fmaxf(r + q.zpf, -128.0f), 127.0f);
-  const float xhat = (c - q.zpf) * q.scale;        // exact difference, one multiply
+  xhat = (c - q.zpf) * q.scale;                    // exact difference, one multiply
   err = x - xhat;
   return c;
 }
 
-__device__ __forceinline__ uint32_t quant4(const f4& v, const QP& q, Acc4& se2, Acc4& sx2) {
-  float e0, e1, e2, e3;
-  const int c0 = static_cast<int>(quant1(v.x, q, e0));
-  const int c1 = static_cast<int>(quant1(v.y, q, e1));
-  const int c2 = static_cast<int>(quant1(v.z, q, e2));
-  const int c3 = static_cast<int>(quant1(v.w, q, e3));
+// COS: also accumulate sum x*xhat (the cross term of the cosine similarity, Sec. 6.1 Eq. 8)
+template <bool COS>
+__device__ __forceinline__ uint32_t quant4(const f4& v, const QP& q, Acc4& se2, Acc4& sx2, Acc4& sxh) {
+  float e0, e1, e2, e3, h0, h1, h2, h3;
+  const int c0 = static_cast<int>(quant1(v.x, q, e0, h0));
+  const int c1 = static_cast<int>(quant1(v.y, q, e1, h1));
+  const int c2 = static_cast<int>(quant1(v.z, q, e2, h2));
+  const int c3 = static_cast<int>(quant1(v.w, q, e3, h3));
+  const f4 h = {h0, h1, h2, h3};
   se2.add_sq(e0, e1, e2, e3);
   sx2.add_sq(v.x, v.y, v.z, v.w);
+  if (COS) sxh.add_prod(v, h);
   return (static_cast<uint32_t>(c0) & 0xffu) | ((static_cast<uint32_t>(c1) & 0xffu) << 8) |
          ((static_cast<uint32_t>(c2) & 0xffu) << 16) | (static_cast<uint32_t>(c3) << 24);
 }
@@ -381,49 +406,59 @@ __global__ __launch_bounds__(WIDE ? kFoldBlock : 256) void k_fold_stats(
   }
 }
 
-template <bool WIDE>
+// cross terms of a partial record (0 where the record has none)
+__device__ __forceinline__ double cross_xh(const ErrPartial3&) { return 0.0; }
+__device__ __forceinline__ double cross_xh(const ErrPartial5& p) { return p.sxh; }
+__device__ __forceinline__ double cross_xq(const ErrPartial&) { return 0.0; }
+__device__ __forceinline__ double cross_xq(const ErrPartial3&) { return 0.0; }
+__device__ __forceinline__ double cross_xq(const ErrPartial5& p) { return p.sxq; }
+
+template <bool WIDE, class P>
 __global__ __launch_bounds__(WIDE ? kFoldBlock : 256) void k_fold_err(
     const Segment* __restrict__ segs, int nseg, const int* __restrict__ ids,
-    const ErrPartial3* __restrict__ parts, qv2_sums* __restrict__ sums) {
+    const P* __restrict__ parts, qv2_sums* __restrict__ sums, double* __restrict__ seg_xxhat) {
   const FoldIdx<WIDE> f(ids, nseg);
   if (!f.active) return;
   const Segment sg = segs[f.id];
   if (!WIDE && sg.enp > kFoldWaveMax) return;
-  double sx2 = 0.0, se2 = 0.0, unused = 0.0;
+  double sx2 = 0.0, se2 = 0.0, sxh = 0.0;
 #pragma unroll 4
   for (int i = f.lane; i < sg.enp; i += f.stride) {
-    const ErrPartial3 q = parts[sg.ep0 + i];
-    sx2 += q.sx2; se2 += q.se2;
+    const P q = parts[sg.ep0 + i];
+    sx2 += q.sx2; se2 += q.se2; sxh += cross_xh(q);
   }
-  fold_sum3<WIDE>(sx2, se2, unused);
+  fold_sum3<WIDE>(sx2, se2, sxh);
   if (f.lane == 0) {
     sums[f.id].sum_x2 = sx2; sums[f.id].sum_e2 = se2; sums[f.id].n = sg.n;
+    if (seg_xxhat) seg_xxhat[f.id] = sxh;
   }
 }
 
 // second energy of a partial record: the pair-noise energy
 __device__ __forceinline__ double pair_energy(const ErrPartial& p) { return p.se2; }
 __device__ __forceinline__ double pair_energy(const ErrPartial3& p) { return p.sd2; }
+__device__ __forceinline__ double pair_energy(const ErrPartial5& p) { return p.sd2; }
 
 template <bool WIDE, class P>
 __global__ __launch_bounds__(WIDE ? kFoldBlock : 256) void k_fold_pair(
     const PairTensor* __restrict__ pt, int n, const int* __restrict__ ids,
-    const P* __restrict__ parts, qv2_pair_sums* __restrict__ out) {
+    const P* __restrict__ parts, qv2_pair_sums* __restrict__ out, double* __restrict__ pair_xq) {
   const FoldIdx<WIDE> f(ids, n);
   if (!f.active) return;
   const PairTensor p = pt[f.id];
   if (!WIDE && p.nparts > kFoldWaveMax) return;
-  double sr2 = 0.0, sd2 = 0.0, unused = 0.0;
+  double sr2 = 0.0, sd2 = 0.0, sxq = 0.0;
 #pragma unroll 4
   for (int i = f.lane; i < p.nparts; i += f.stride) {
     const P q = parts[p.part0 + i];
-    sr2 += q.sx2; sd2 += pair_energy(q);
+    sr2 += q.sx2; sd2 += pair_energy(q); sxq += cross_xq(q);
   }
-  fold_sum3<WIDE>(sr2, sd2, unused);
+  fold_sum3<WIDE>(sr2, sd2, sxq);
   if (f.lane == 0) {
     qv2_pair_sums o;
     o.sum_ref2 = sr2; o.sum_d2 = sd2; o.n = p.n; o._pad = 0;
     out[f.id] = o;
+    if (pair_xq) pair_xq[f.id] = sxq;
   }
 }
 
@@ -433,9 +468,10 @@ __global__ __launch_bounds__(WIDE ? kFoldBlock : 256) void k_fold_pair(
 // Per element 4 B read + 1 B code written (+ 4 B of qrun read when PAIR).
 // ---------------------------------------------------------------------------
 // STORE: 0 no code buffer, 1 packed dwords, 2 single bytes (misaligned code buffer)
-template <int BLOCK, int V, int STORE, bool PAIR>
+template <int BLOCK, int V, int STORE, bool PAIR, bool COS>
 __device__ __forceinline__ void quant_body(gf4_ptr v4, gf4_ptr b4, gu32_ptr cw, gi8_ptr cb, int nvec,
-                                           const QP& q, Acc4& ae2, Acc4& ax2, Acc4& ad2) {
+                                           const QP& q, Acc4& ae2, Acc4& ax2, Acc4& ad2, Acc4& axh,
+                                           Acc4& axq) {
   const int tid = threadIdx.x;
   auto put = [&](int i, uint32_t pk) {
     if (STORE == 1) {
@@ -456,16 +492,18 @@ __device__ __forceinline__ void quant_body(gf4_ptr v4, gf4_ptr b4, gu32_ptr cw, 
     }
 #pragma unroll
     for (int u = 0; u < V; ++u) {
-      put(base + u * BLOCK + tid, quant4(r[u], q, ae2, ax2));
+      put(base + u * BLOCK + tid, quant4<COS>(r[u], q, ae2, ax2, axh));
       if (PAIR) ad2.add_sq(r[u].x - g[u].x, r[u].y - g[u].y, r[u].z - g[u].z, r[u].w - g[u].w);
+      if (PAIR && COS) axq.add_prod(r[u], g[u]);
     }
   }
   for (int i = base + tid; i < nvec; i += BLOCK) {
     const f4 r = ld4(v4 + i);
-    put(i, quant4(r, q, ae2, ax2));
+    put(i, quant4<COS>(r, q, ae2, ax2, axh));
     if (PAIR) {
       const f4 g = ld4(b4 + i);
       ad2.add_sq(r.x - g.x, r.y - g.y, r.z - g.z, r.w - g.w);
+      if (COS) axq.add_prod(r, g);
     }
   }
 }
@@ -473,10 +511,16 @@ __device__ __forceinline__ void quant_body(gf4_ptr v4, gf4_ptr b4, gu32_ptr cw, 
 #ifndef QV2_QUANT_WAVES_PER_EU
 #define QV2_QUANT_WAVES_PER_EU 1    // occupancy floor asked of the register allocator
 #endif
-template <int BLOCK, int V, bool PAIR>
-__global__ __launch_bounds__(BLOCK, QV2_QUANT_WAVES_PER_EU) void k_quant_stream(const Tile* __restrict__ tiles,
-                                                        const qv2_qparams* __restrict__ params,
-                                                        ErrPartial3* __restrict__ parts) {
+// partial record of a quantize pass: 3 energies, plus the 2 cross terms when COS
+template <bool COS> struct ErrRec { typedef ErrPartial3 type; };
+template <> struct ErrRec<true> { typedef ErrPartial5 type; };
+__device__ __forceinline__ void set_cross(ErrPartial3&, double, double) {}
+__device__ __forceinline__ void set_cross(ErrPartial5& o, double sxh, double sxq) { o.sxh = sxh; o.sxq = sxq; }
+
+template <int BLOCK, int V, bool PAIR, bool COS>
+__global__ __launch_bounds__(BLOCK, QV2_QUANT_WAVES_PER_EU) void k_quant_stream(
+    const Tile* __restrict__ tiles, const qv2_qparams* __restrict__ params,
+    typename ErrRec<COS>::type* __restrict__ parts) {
   const Tile tl = tiles[blockIdx.x];
   const QP q = load_qp(params, tl.seg0);
   const gf_ptr p = (gf_ptr)tl.x;
@@ -485,14 +529,16 @@ __global__ __launch_bounds__(BLOCK, QV2_QUANT_WAVES_PER_EU) void k_quant_stream(
   const bool has_c = tl.c != nullptr;
   const bool has_b = PAIR && tl.q != nullptr;
   const int len = tl.len, tid = threadIdx.x;
-  double sx2 = 0.0, se2 = 0.0, sd2 = 0.0;
+  double sx2 = 0.0, se2 = 0.0, sd2 = 0.0, sxh = 0.0, sxq = 0.0;
 
   // qrun at a different offset inside 16 bytes than x: its energy is taken element-wise
   const bool b_vec = has_b && (((reinterpret_cast<uintptr_t>(tl.x) ^ reinterpret_cast<uintptr_t>(tl.q)) & 15u) == 0);
   if (has_b && !b_vec) {
     for (int i = tid; i < len; i += BLOCK) {
-      const double d = static_cast<double>(p[i] - b[i]);
+      const float xv = p[i], qv = b[i];
+      const double d = static_cast<double>(xv - qv);
       sd2 = fma(d, d, sd2);
+      if (COS) sxq = fma(static_cast<double>(xv), static_cast<double>(qv), sxq);
     }
   }
   const int head = head_elems(tl.x, len);
@@ -502,42 +548,52 @@ __global__ __launch_bounds__(BLOCK, QV2_QUANT_WAVES_PER_EU) void k_quant_stream(
     if (!on) continue;
     const int idx = k == 0 ? tid : head + (nvec << 2) + tid;
     const float v = p[idx];
-    float e;
-    const float code = quant1(v, q, e);
+    float e, h;
+    const float code = quant1(v, q, e, h);
     if (has_c) c[idx] = static_cast<int8_t>(static_cast<int>(code));
     sx2 += static_cast<double>(v) * v;
     se2 += static_cast<double>(e) * e;
-    if (b_vec) { const float d = v - b[idx]; sd2 += static_cast<double>(d) * d; }
+    if (COS) sxh = fma(static_cast<double>(v), static_cast<double>(h), sxh);
+    if (b_vec) {
+      const float qv = b[idx], d = v - qv;
+      sd2 += static_cast<double>(d) * d;
+      if (COS) sxq = fma(static_cast<double>(v), static_cast<double>(qv), sxq);
+    }
   }
   const gf4_ptr v4 = (gf4_ptr)(tl.x + head);
   const gf4_ptr b4 = (gf4_ptr)(tl.q + head);
   const gi8_ptr cb = c + head;
   const gu32_ptr cw = (gu32_ptr)(tl.c + head);
   const bool cw_ok = has_c && ((reinterpret_cast<uintptr_t>(tl.c + head) & 3u) == 0);
-  Acc4 ae2, ax2, ad2;
+  Acc4 ae2, ax2, ad2, axh, axq;
   if (b_vec) {
-    if (cw_ok) quant_body<BLOCK, V, 1, PAIR>(v4, b4, cw, cb, nvec, q, ae2, ax2, ad2);
-    else if (has_c) quant_body<BLOCK, V, 2, PAIR>(v4, b4, cw, cb, nvec, q, ae2, ax2, ad2);
-    else quant_body<BLOCK, V, 0, PAIR>(v4, b4, cw, cb, nvec, q, ae2, ax2, ad2);
+    if (cw_ok) quant_body<BLOCK, V, 1, PAIR, COS>(v4, b4, cw, cb, nvec, q, ae2, ax2, ad2, axh, axq);
+    else if (has_c) quant_body<BLOCK, V, 2, PAIR, COS>(v4, b4, cw, cb, nvec, q, ae2, ax2, ad2, axh, axq);
+    else quant_body<BLOCK, V, 0, PAIR, COS>(v4, b4, cw, cb, nvec, q, ae2, ax2, ad2, axh, axq);
   } else {
-    if (cw_ok) quant_body<BLOCK, V, 1, false>(v4, b4, cw, cb, nvec, q, ae2, ax2, ad2);
-    else if (has_c) quant_body<BLOCK, V, 2, false>(v4, b4, cw, cb, nvec, q, ae2, ax2, ad2);
-    else quant_body<BLOCK, V, 0, false>(v4, b4, cw, cb, nvec, q, ae2, ax2, ad2);
+    if (cw_ok) quant_body<BLOCK, V, 1, false, COS>(v4, b4, cw, cb, nvec, q, ae2, ax2, ad2, axh, axq);
+    else if (has_c) quant_body<BLOCK, V, 2, false, COS>(v4, b4, cw, cb, nvec, q, ae2, ax2, ad2, axh, axq);
+    else quant_body<BLOCK, V, 0, false, COS>(v4, b4, cw, cb, nvec, q, ae2, ax2, ad2, axh, axq);
   }
   se2 += ae2.total(); sx2 += ax2.total(); sd2 += ad2.total();
-  block_sum3<BLOCK>(sx2, se2, sd2);
-  if (tid == 0) {
-    ErrPartial3 o;
+  typename ErrRec<COS>::type o;
+  if (COS) {
+    double v[5] = {sx2, se2, sd2, sxh + axh.total(), sxq + axq.total()};
+    block_sum<BLOCK, 5>(v);
+    o.sx2 = v[0]; o.se2 = v[1]; o.sd2 = v[2];
+    set_cross(o, v[3], v[4]);
+  } else {
+    block_sum3<BLOCK>(sx2, se2, sd2);
     o.sx2 = sx2; o.se2 = se2; o.sd2 = sd2;
-    parts[tl.part0] = o;
   }
+  if (tid == 0) parts[tl.part0] = o;
 }
 
 // pass 2 (+3), row-group tiles
-template <int BLOCK, bool PAIR>
+template <int BLOCK, bool PAIR, bool COS>
 __global__ __launch_bounds__(BLOCK) void k_quant_rows(const Tile* __restrict__ tiles,
                                                       const qv2_qparams* __restrict__ params,
-                                                      ErrPartial3* __restrict__ parts) {
+                                                      typename ErrRec<COS>::type* __restrict__ parts) {
   constexpr int W = BLOCK / kWave;
   __shared__ __attribute__((aligned(16))) float xs[kRowGroupCap + 4];
   __shared__ __attribute__((aligned(16))) int8_t cs[kRowGroupCap + 8];
@@ -554,28 +610,33 @@ __global__ __launch_bounds__(BLOCK) void k_quant_rows(const Tile* __restrict__ t
   for (int rb = wave * gpw; rb < tl.rows; rb += W * gpw) {
     const int r = rb + g;
     const bool live = r < tl.rows;
-    double sx2 = 0.0, se2 = 0.0, sd2 = 0.0;
+    double sx2 = 0.0, se2 = 0.0, sd2 = 0.0, sxh = 0.0, sxq = 0.0;
     if (live) {
       const QP q = load_qp(params, tl.seg0 + r);
       const float* row = xs + shift + r * inner;
       int8_t* crow = cs + ca + r * inner;
       for (int j = gl; j < inner; j += w) {
         const float v = row[j];
-        float e;
-        const float code = quant1(v, q, e);
+        float e, h;
+        const float code = quant1(v, q, e, h);
         crow[j] = static_cast<int8_t>(static_cast<int>(code));
         sx2 = fma(static_cast<double>(v), static_cast<double>(v), sx2);
         se2 = fma(static_cast<double>(e), static_cast<double>(e), se2);
+        if (COS) sxh = fma(static_cast<double>(v), static_cast<double>(h), sxh);
         if (has_b) {
-          const double d = static_cast<double>(v - b[r * inner + j]);
+          const float qv = b[r * inner + j];
+          const double d = static_cast<double>(v - qv);
           sd2 = fma(d, d, sd2);
+          if (COS) sxq = fma(static_cast<double>(v), static_cast<double>(qv), sxq);
         }
       }
     }
     sx2 = group_sum(sx2, w); se2 = group_sum(se2, w); sd2 = group_sum(sd2, w);
+    if (COS) { sxh = group_sum(sxh, w); sxq = group_sum(sxq, w); }
     if (live && gl == 0) {
-      ErrPartial3 o;
+      typename ErrRec<COS>::type o;
       o.sx2 = sx2; o.se2 = se2; o.sd2 = sd2;
+      set_cross(o, sxh, sxq);
       parts[tl.part0 + r] = o;
     }
   }
@@ -728,27 +789,42 @@ struct Timed {
 int fold_grid(int n) { return (n + 3) / 4; }
 
 // quantize pass over stream and row-group tiles, then the error fold
-template <bool PAIR>
-void launch_quant(qv2_plan* plan, const qv2_qparams* d_params, qv2_sums* d_sums, ErrPartial3* parts,
-                  hipStream_t s) {
+template <bool PAIR, bool COS>
+void launch_quant(qv2_plan* plan, const qv2_qparams* d_params, qv2_sums* d_sums,
+                  typename ErrRec<COS>::type* parts, double* d_seg_xxhat, hipStream_t s) {
+  typedef typename ErrRec<COS>::type P;
   const int n_stream = static_cast<int>(plan->quant_tiles.size());
   const int n_rows = static_cast<int>(plan->row_tiles.size());
   const int nseg = static_cast<int>(plan->segments.size());
   if (n_stream > 0) {
     Timed timed(plan, PAIR ? QV2_K_QUANTPAIR_STREAM : QV2_K_QUANT_STREAM, s);
-    hipLaunchKernelGGL((k_quant_stream<kBlockQuant, kVecQuant, PAIR>), dim3(n_stream), dim3(kBlockQuant),
-                       0, s, plan->d_quant_tiles, d_params, parts);
+    hipLaunchKernelGGL((k_quant_stream<kBlockQuant, kVecQuant, PAIR, COS>), dim3(n_stream),
+                       dim3(kBlockQuant), 0, s, plan->d_quant_tiles, d_params, parts);
   }
   if (n_rows > 0) {
     Timed timed(plan, PAIR ? QV2_K_QUANTPAIR_ROWS : QV2_K_QUANT_ROWS, s);
-    hipLaunchKernelGGL((k_quant_rows<kBlockRows, PAIR>), dim3(n_rows), dim3(kBlockRows), 0, s,
+    hipLaunchKernelGGL((k_quant_rows<kBlockRows, PAIR, COS>), dim3(n_rows), dim3(kBlockRows), 0, s,
                        plan->d_row_tiles, d_params, parts);
   }
-  hipLaunchKernelGGL(k_fold_err<false>, dim3(fold_grid(nseg)), dim3(256), 0, s, plan->d_segments, nseg,
-                     static_cast<const int*>(nullptr), parts, d_sums);
+  hipLaunchKernelGGL((k_fold_err<false, P>), dim3(fold_grid(nseg)), dim3(256), 0, s, plan->d_segments,
+                     nseg, static_cast<const int*>(nullptr), parts, d_sums, d_seg_xxhat);
   if (const int nb = static_cast<int>(plan->big_err_segments.size()))
-    hipLaunchKernelGGL(k_fold_err<true>, dim3(nb), dim3(kFoldBlock), 0, s, plan->d_segments, nseg,
-                       plan->d_big_err_segments, parts, d_sums);
+    hipLaunchKernelGGL((k_fold_err<true, P>), dim3(nb), dim3(kFoldBlock), 0, s, plan->d_segments, nseg,
+                       plan->d_big_err_segments, parts, d_sums, d_seg_xxhat);
+}
+
+// per-tensor pair fold of a fused quantize pass
+template <class P>
+void launch_fused_pair_fold(qv2_plan* plan, const P* parts, qv2_pair_sums* d_pair_sums,
+                            double* d_pair_xq, hipStream_t s) {
+  const int nt = static_cast<int>(plan->fused_pair_tensors.size());
+  hipLaunchKernelGGL((k_fold_pair<false, P>), dim3(fold_grid(nt)), dim3(256), 0, s,
+                     plan->d_fused_pair_tensors, nt, static_cast<const int*>(nullptr), parts, d_pair_sums,
+                     d_pair_xq);
+  if (const int nb = static_cast<int>(plan->big_fused_pair_tensors.size()))
+    hipLaunchKernelGGL((k_fold_pair<true, P>), dim3(nb), dim3(kFoldBlock), 0, s,
+                       plan->d_fused_pair_tensors, nt, plan->d_big_fused_pair_tensors, parts, d_pair_sums,
+                       d_pair_xq);
 }
 
 }  // namespace
@@ -827,8 +903,8 @@ qv2_status qv2_fakequant_metrics(qv2_plan* plan, const qv2_qparams* d_params, qv
   qv2_status st = check_call(plan, d_params, d_sums, d_workspace, workspace_bytes);
   if (st != QV2_OK) return st;
   if ((st = ensure_uploaded(plan)) != QV2_OK) return st;
-  launch_quant<false>(plan, d_params, d_sums, static_cast<ErrPartial3*>(d_workspace),
-                      static_cast<hipStream_t>(hip_stream));
+  launch_quant<false, false>(plan, d_params, d_sums, static_cast<ErrPartial3*>(d_workspace), nullptr,
+                             static_cast<hipStream_t>(hip_stream));
   return launch_status();
 }
 
@@ -847,10 +923,12 @@ qv2_status qv2_pair_metrics(qv2_plan* plan, qv2_pair_sums* d_pair_sums, void* d_
                        plan->d_pair_tiles, parts);
   }
   hipLaunchKernelGGL((k_fold_pair<false, ErrPartial>), dim3(fold_grid(nt)), dim3(256), 0, s,
-                     plan->d_pair_tensors, nt, static_cast<const int*>(nullptr), parts, d_pair_sums);
+                     plan->d_pair_tensors, nt, static_cast<const int*>(nullptr), parts, d_pair_sums,
+                     static_cast<double*>(nullptr));
   if (const int nb = static_cast<int>(plan->big_pair_tensors.size()))
     hipLaunchKernelGGL((k_fold_pair<true, ErrPartial>), dim3(nb), dim3(kFoldBlock), 0, s,
-                       plan->d_pair_tensors, nt, plan->d_big_pair_tensors, parts, d_pair_sums);
+                       plan->d_pair_tensors, nt, plan->d_big_pair_tensors, parts, d_pair_sums,
+                       static_cast<double*>(nullptr));
   return launch_status();
 }
 
@@ -864,13 +942,25 @@ qv2_status qv2_fakequant_pair_metrics(qv2_plan* plan, const qv2_qparams* d_param
   if ((st = ensure_uploaded(plan)) != QV2_OK) return st;
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   ErrPartial3* parts = static_cast<ErrPartial3*>(d_workspace);
-  launch_quant<true>(plan, d_params, d_sums, parts, s);
-  const int nt = static_cast<int>(plan->fused_pair_tensors.size());
-  hipLaunchKernelGGL((k_fold_pair<false, ErrPartial3>), dim3(fold_grid(nt)), dim3(256), 0, s,
-                     plan->d_fused_pair_tensors, nt, static_cast<const int*>(nullptr), parts, d_pair_sums);
-  if (const int nb = static_cast<int>(plan->big_fused_pair_tensors.size()))
-    hipLaunchKernelGGL((k_fold_pair<true, ErrPartial3>), dim3(nb), dim3(kFoldBlock), 0, s,
-                       plan->d_fused_pair_tensors, nt, plan->d_big_fused_pair_tensors, parts, d_pair_sums);
+  launch_quant<true, false>(plan, d_params, d_sums, parts, nullptr, s);
+  launch_fused_pair_fold(plan, parts, d_pair_sums, nullptr, s);
+  return launch_status();
+}
+
+qv2_status qv2_fakequant_pair_metrics_cos(qv2_plan* plan, const qv2_qparams* d_params, qv2_sums* d_sums,
+                                          qv2_pair_sums* d_pair_sums, double* d_seg_xxhat,
+                                          double* d_pair_xq, void* d_workspace, size_t workspace_bytes,
+                                          void* hip_stream) {
+  qv2_status st = check_call(plan, d_params, d_sums, d_workspace, workspace_bytes);
+  if (st != QV2_OK) return st;
+  if (!d_pair_sums || !d_seg_xxhat || !d_pair_xq) return QV2_ERR_NULL;
+  if ((reinterpret_cast<uintptr_t>(d_pair_sums) | reinterpret_cast<uintptr_t>(d_seg_xxhat) |
+       reinterpret_cast<uintptr_t>(d_pair_xq)) & 7u) return QV2_ERR_ALIGN;
+  if ((st = ensure_uploaded(plan)) != QV2_OK) return st;
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  ErrPartial5* parts = static_cast<ErrPartial5*>(d_workspace);
+  launch_quant<true, true>(plan, d_params, d_sums, parts, d_seg_xxhat, s);
+  launch_fused_pair_fold(plan, parts, d_pair_sums, d_pair_xq, s);
   return launch_status();
 }
 

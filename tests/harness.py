@@ -26,6 +26,7 @@ MSE_RTOL = 1e-4
 SQNR_ATOL_DB = 1e-3
 SX2_RTOL = 1e-6
 VAR_RTOL = 1e-4
+COS_ATOL = 1e-9        # cosine similarity: fp64 sums, norms recovered from energy differences
 
 
 @dataclass
@@ -91,7 +92,7 @@ def attach_pairs(items: List[Item], specs: List[synth.TensorSpec]):
 
 
 def run_gpu(items: List[Item], params_override: Optional[np.ndarray] = None,
-            do_calibrate: bool = True, fused: bool = False) -> GpuResult:
+            do_calibrate: bool = True, fused: bool = False, cos: bool = False) -> GpuResult:
     """calibrate -> fakequant -> pair (or the fused fakequant+pair call) on the current
     stream, then host finalize."""
     dev = items[0].x.device
@@ -111,7 +112,13 @@ def run_gpu(items: List[Item], params_override: Optional[np.ndarray] = None,
     if params_override is not None:
         torch.cuda.synchronize()
         buf.params.copy_(torch.from_numpy(params_override.view(np.uint8)).to(dev))
-    if fused:
+    seg_xxhat = pair_xq = None
+    if cos:
+        seg_xxhat = torch.zeros(plan.num_segments, dtype=torch.float64, device=dev)
+        pair_xq = torch.zeros(plan.num_tensors, dtype=torch.float64, device=dev)
+        qb.qv2_fakequant_pair_metrics_cos(plan, buf.params, buf.sums, buf.pair, seg_xxhat, pair_xq,
+                                          buf.workspace)
+    elif fused:
         qb.qv2_fakequant_pair_metrics(plan, buf.params, buf.sums, buf.pair, buf.workspace)
     else:
         qb.qv2_fakequant_metrics(plan, buf.params, buf.sums, buf.workspace)
@@ -122,6 +129,10 @@ def run_gpu(items: List[Item], params_override: Optional[np.ndarray] = None,
     pm, ps = qb.qv2_pair_finalize(pair)
     res = GpuResult(plan, params, sums, pair, metrics, pm, ps)
     res.buffers = buf
+    res.cos_quant = res.cos_pair = None
+    if cos:
+        res.cos_quant, res.cos_pair = qb.qv2_cosine_finalize(plan, sums, seg_xxhat.cpu().numpy(), pair,
+                                                             pair_xq.cpu().numpy(), strict=False)
     return res
 
 
@@ -175,6 +186,16 @@ def check_item(t: int, it: Item, res: GpuResult, check_codes: bool = True, cal=N
     assert abs(g["var"] - m.var) <= VAR_RTOL * m.var + 1e-12, f"{tag}: var {g['var']} vs {m.var}"
     assert g["absmax"] == np.float32(m.absmax) and g["min"] == np.float32(m.min) and g["max"] == np.float32(m.max)
     out = {"w_mse": m.mse, "w_sqnr": m.sqnr_db}
+    if getattr(res, "cos_quant", None) is not None:         # Eq. 8, tensor vs its dequantized form
+        xhat = np.concatenate([orc.dequantize(fq.codes.reshape(S, -1)[c], cal.scale[c], cal.zp[c])
+                               for c in range(S)])
+        want = orc.cosine_similarity(x, xhat)
+        assert abs(res.cos_quant[t] - want) <= COS_ATOL, f"{tag}: cos(x, xhat) {res.cos_quant[t]} vs {want}"
+        if it.qrun is not None:
+            want = orc.cosine_similarity(x, it.qrun.detach().cpu().numpy().reshape(-1))
+            assert abs(res.cos_pair[t] - want) <= COS_ATOL, f"{tag}: cos(x, qrun) {res.cos_pair[t]} vs {want}"
+        else:
+            assert math.isnan(res.cos_pair[t])
     # pair
     if it.qrun is not None:
         pm = orc.pair_metrics(x, it.qrun.detach().cpu().numpy().reshape(-1))

@@ -213,6 +213,32 @@ def test_fused_call_equals_the_two_separate_calls():
     assert all(torch.equal(a, it.codes) for a, it in zip(c1, items))
 
 
+def test_cosine_similarity_variant():
+    """qv2_fakequant_pair_metrics_cos: cos(x, xhat) and cos(x, qrun) against the oracle's direct
+    definition; every other output bit-identical to the call without the cross terms."""
+    specs = synth.config_mobilenetv2(4) + synth.config_tiny()
+    items = H.items_from_specs(specs, DEV)
+    H.attach_pairs(items, specs)
+    extra = [H.Item("zeros", torch.zeros(5000, device=DEV), A, qrun=torch.zeros(5000, device=DEV)),
+             H.Item("zero_q", _rand(5000, 31), S, qrun=torch.zeros(5000, device=DEV)),
+             H.Item("big", _rand(30_001, 32, 1e25)[1:], A, qrun=_rand(30_000, 33, 1e25)),
+             H.Item("rows_q", _rand(64 * 27, 34, 0.1), C, 64, qrun=_rand(64 * 27, 35, 0.1)),
+             H.Item("neg_q", _rand(70_000, 36), A, qrun=-_rand(70_000, 36))]
+    for it in extra:
+        it._oracle = None
+    items += extra
+    r1 = H.run_gpu(items, fused=True)
+    c1 = [it.codes.clone() for it in items]
+    r2 = H.run_gpu(items, cos=True)
+    H.check_all(items, r2)
+    assert r1.sums.tobytes() == r2.sums.tobytes() and r1.pair.tobytes() == r2.pair.tobytes()
+    assert all(torch.equal(a, it.codes) for a, it in zip(c1, items))
+    names = [it.name for it in items]
+    assert r2.cos_quant[names.index("zeros")] == 1.0 and r2.cos_pair[names.index("zeros")] == 1.0
+    assert r2.cos_pair[names.index("zero_q")] == 0.0
+    assert abs(r2.cos_pair[names.index("neg_q")] + 1.0) < 1e-12
+
+
 def test_cross_kernel_pair_of_dequantized_equals_fakequant_error():
     """pair(x, dequant(codes)) must reproduce the fake-quant pass's own noise energy."""
     x = torch.relu(_rand(300_000, 15, 1.5))

@@ -469,3 +469,35 @@ def test_layer_macs_of_the_shape_tables():
     for fn, want in ((synth.resnet18_layers, 1.814e9), (synth.resnet50_layers, 3.86e9),
                      (synth.vgg16_layers, 15.47e9), (synth.mobilenetv2_layers, 0.300e9)):
         assert sum(synth.layer_macs(fn())) == pytest.approx(want, rel=0.02)
+
+
+# ----------------------------------------------------------------------------
+# cosine similarity (Sec. 6.1 Eq. 8)
+# ----------------------------------------------------------------------------
+def test_cosine_similarity_pins():
+    rng = np.random.default_rng(14)
+    a = rng.standard_normal(20_001).astype(np.float32)
+    b = (a + 0.3 * rng.standard_normal(20_001)).astype(np.float32)
+    a64, b64 = a.astype(np.float64), b.astype(np.float64)
+    want = float(a64 @ b64 / (np.linalg.norm(a64) * np.linalg.norm(b64)))     # library routines
+    assert orc.cosine_similarity(a, b) == pytest.approx(want, abs=1e-13)
+    assert orc.cosine_similarity(a, a) == pytest.approx(1.0, abs=1e-15)
+    assert orc.cosine_similarity(a, -a) == pytest.approx(-1.0, abs=1e-15)
+    assert orc.cosine_similarity(a, b) == pytest.approx(orc.cosine_similarity(b, a), abs=1e-15)
+    # direction only: positive rescaling changes nothing, a power of two exactly nothing
+    assert orc.cosine_similarity(a, b * np.float32(4.0)) == orc.cosine_similarity(a, b)
+    assert orc.cosine_similarity(a * np.float32(3.0), b) == pytest.approx(want, abs=1e-7)
+    # orthogonal and 45-degree vectors
+    assert orc.cosine_similarity([1.0, 0.0, 0.0], [0.0, 2.0, 0.0]) == 0.0
+    assert orc.cosine_similarity([1.0, 0.0], [1.0, 1.0]) == pytest.approx(math.sqrt(0.5), abs=1e-15)
+    assert orc.cosine_similarity([3.0, 4.0], [4.0, 3.0]) == pytest.approx(24.0 / 25.0, abs=1e-15)
+    # zero vectors (reading): both zero -> 1, one zero -> 0
+    assert orc.cosine_similarity([0.0, 0.0], [0.0, 0.0]) == 1.0
+    assert orc.cosine_similarity([0.0, 0.0], [1.0, 0.0]) == 0.0
+    # a quantized tensor stays within a hair of its original: 1 - cos ~ MSE / (2 * mean x^2)
+    x = (rng.standard_normal(200_000) * 0.7).astype(np.float32)
+    cal = orc.calibrate(x, A)
+    fq = orc.fakequant(x, cal, A, keep_xhat=True)
+    m = orc.tensor_metrics(x, cal, fq)
+    c = orc.cosine_similarity(x, fq.xhat)
+    assert 1.0 - c == pytest.approx(m.mse / (2.0 * fq.sum_x2[0] / x.size), rel=0.05)
