@@ -162,7 +162,8 @@ size_t qv2_workspace_bytes(const qv2_plan* plan);
  * creates the events (the only allocation outside the first-use table upload). */
 typedef enum {
   QV2_K_STATS_STREAM = 0, QV2_K_STATS_ROWS = 1, QV2_K_QUANT_STREAM = 2, QV2_K_QUANT_ROWS = 3,
-  QV2_K_PAIR_STREAM = 4, QV2_K_QUANTPAIR_STREAM = 5, QV2_K_QUANTPAIR_ROWS = 6, QV2_K_COUNT = 7
+  QV2_K_PAIR_STREAM = 4, QV2_K_QUANTPAIR_STREAM = 5, QV2_K_QUANTPAIR_ROWS = 6, QV2_K_HIST = 7,
+  QV2_K_COUNT = 8
 } qv2_kernel_id;
 qv2_status qv2_plan_set_timing(qv2_plan* plan, int32_t enable);
 qv2_status qv2_plan_kernel_ms(const qv2_plan* plan, int32_t kernel, float* ms_out);
@@ -214,6 +215,23 @@ qv2_status qv2_fakequant_pair_metrics_cos(qv2_plan* plan, const qv2_qparams* d_p
                                           void* d_workspace, size_t workspace_bytes,
                                           void* hip_stream);
 
+/* Calibration histograms (Sec. 5, calibration stage): for every tensor the counts of x,
+ * and of qrun where present, over nbins equal bins of the tensor's calibrated range
+ * [min, max] (taken from d_params; for a per-channel tensor the range over its channels).
+ * The paper gives no binning rule; this library's, in fp32 with one rounding per step:
+ *   inv_w = nbins / (max - min)   (0 when max - min is not positive and finite)
+ *   bin   = clamp(floor((v - min) * inv_w), 0, nbins - 1)
+ * so values of qrun outside x's range fall into the edge bins.
+ * nbins: 2 .. 4096.  d_hist_x, d_hist_q: DEVICE, num_tensors * nbins uint64 counts each,
+ * written; d_hist_q may be NULL; rows of tensors without qrun are zero.
+ * d_workspace: at least qv2_histogram_workspace_bytes(plan, nbins) bytes (that function
+ * returns 0 for a bad nbins).  Per element 4 B read per stream.
+ * Errors: ERR_NULL, ERR_SHAPE (nbins), ERR_WORKSPACE, ERR_ALIGN, ERR_HIP. */
+size_t qv2_histogram_workspace_bytes(const qv2_plan* plan, int32_t nbins);
+qv2_status qv2_histogram(qv2_plan* plan, const qv2_qparams* d_params, int32_t nbins,
+                         uint64_t* d_hist_x, uint64_t* d_hist_q, void* d_workspace,
+                         size_t workspace_bytes, void* hip_stream);
+
 /* ---- host finalize and ranking (need no GPU) ----------------------------- */
 
 /* Eq. 6-7 and the tensor statistics from host copies of params and sums; a
@@ -235,6 +253,15 @@ qv2_status qv2_pair_finalize(const qv2_pair_sums* h_pair, int32_t n,
 qv2_status qv2_cosine_finalize(const qv2_plan* plan, const qv2_sums* h_sums,
                                const double* h_seg_xxhat, const qv2_pair_sums* h_pair,
                                const double* h_pair_xq, double* h_cos_quant, double* h_cos_pair);
+
+/* Sec. 6.1 Eq. 9: KL(P || Q) = sum_i P_i ln(P_i / Q_i) between two histograms over the same
+ * bins (P: original layer output, Q: quantized layer output), with
+ * P_i = (count_i + eps) / (total + eps * nbins).  eps = 0 is the plain definition: empty P
+ * bins contribute 0, an empty Q bin under a non-empty P bin gives +inf.  The paper names no
+ * smoothing constant; eps is the caller's choice.
+ * Errors: ERR_NULL, ERR_SHAPE (nbins <= 0, an empty histogram), ERR_NONFINITE (eps < 0 / NaN). */
+qv2_status qv2_kl_divergence(const uint64_t* h_hist_p, const uint64_t* h_hist_q, int32_t nbins,
+                             double eps, double* kl_out);
 
 void qv2_rank_config_default(qv2_rank_config* cfg);
 

@@ -200,3 +200,25 @@ void orc_cosine_sums(const float *a, const float *b, int64_t n,
     *saa = xx;
     *sbb = yy;
 }
+
+/* Sec. 5, calibration stage: histogram of a tensor's values over [lo, hi] with
+ * nbins equal bins.  The paper gives no binning rule; reading taken (fp32, one
+ * rounding per step, so that the bin of every element is well defined):
+ *   inv_w = nbins / (hi - lo)          (0 when hi - lo is not a positive finite number)
+ *   bin   = clamp(floor((x - lo) * inv_w), 0, nbins - 1)
+ * Values outside [lo, hi] fall into the edge bins. */
+void orc_histogram(const float *x, int64_t n, float lo, float hi, int32_t nbins, uint64_t *hist)
+{
+    float w = hi - lo;
+    float inv_w = (w > 0.0f && w <= FLT_MAX) ? (float)nbins / w : 0.0f;
+    float top = (float)(nbins - 1);
+    for (int32_t b = 0; b < nbins; ++b) hist[b] = 0;
+    for (int64_t i = 0; i < n; ++i) {
+        float d = x[i] - lo;
+        float t = d * inv_w;
+        float f = floorf(t);
+        if (!(f >= 0.0f)) f = 0.0f;      /* also catches NaN */
+        if (f > top) f = top;
+        hist[(int32_t)f] += 1;
+    }
+}

@@ -63,6 +63,9 @@ def lib():
         L.orc_quantize.argtypes = [_F, i64, ctypes.c_float, ctypes.c_int32, _I8]
         L.orc_dequantize.argtypes = [_I8, i64, ctypes.c_float, ctypes.c_int32, _F]
         L.orc_error_sums.argtypes = [_F, _F, i64, _D, _D]
+        L.orc_histogram.argtypes = [_F, i64, ctypes.c_float, ctypes.c_float, ctypes.c_int32,
+                                    ctypes.POINTER(ctypes.c_uint64)]
+        L.orc_histogram.restype = None
         L.orc_cosine_sums.argtypes = [_F, _F, i64, _D, _D, _D]
         L.orc_cosine_sums.restype = None
         L.orc_mse.argtypes = [ctypes.c_double, i64]
@@ -408,3 +411,43 @@ def bops_select(order, macs, target_pct: float):
             break
         kept += 1
     return keep, kept, bops_reduction_pct(macs, keep)
+
+
+# ----------------------------------------------------------------------------
+# Sec. 5 calibration histograms and the KL divergence of Sec. 6.1 Eq. 9
+# ----------------------------------------------------------------------------
+def histogram(x, lo, hi, nbins: int) -> np.ndarray:
+    """Counts of x over nbins equal bins of [lo, hi] (uint64); out-of-range values go to the edge bins."""
+    a = _f32(x)
+    h = np.zeros(nbins, dtype=np.uint64)
+    lib().orc_histogram(_fp(a), a.size, ctypes.c_float(float(lo)), ctypes.c_float(float(hi)), int(nbins),
+                        h.ctypes.data_as(ctypes.POINTER(ctypes.c_uint64)))
+    return h
+
+
+def kl_divergence(hist_p, hist_q, eps: float = 0.0) -> float:
+    """Eq. 9: sum_x P(x) log(P(x) / Q(x)) (natural log) between two histograms over the same bins,
+    P the original layer output, Q the quantized one.  Probabilities are (count + eps) /
+    (total + eps * nbins); eps = 0 is the plain definition (terms with P = 0 contribute 0, a bin
+    with P > 0 and Q = 0 makes the divergence +inf).  The paper gives no smoothing constant."""
+    cp = [float(c) for c in hist_p]
+    cq = [float(c) for c in hist_q]
+    if len(cp) != len(cq) or not cp:
+        raise ValueError("histograms must have the same, non-zero number of bins")
+    if eps < 0 or math.isnan(eps):
+        raise ValueError("eps must be >= 0")
+    nb = len(cp)
+    tp = sum(cp) + eps * nb
+    tq = sum(cq) + eps * nb
+    if tp <= 0 or tq <= 0:
+        raise ValueError("empty histogram")
+    kl = 0.0
+    for a, b in zip(cp, cq):
+        pa = (a + eps) / tp
+        qb_ = (b + eps) / tq
+        if pa == 0.0:
+            continue
+        if qb_ == 0.0:
+            return math.inf
+        kl += pa * math.log(pa / qb_)
+    return kl

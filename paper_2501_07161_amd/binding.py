@@ -28,7 +28,8 @@ EXPORTS = (
     "qv2_plan_num_pair_tiles",
     "qv2_workspace_bytes", "qv2_calibrate", "qv2_fakequant_metrics", "qv2_pair_metrics",
     "qv2_fakequant_pair_metrics", "qv2_fakequant_pair_metrics_cos", "qv2_cosine_finalize",
-    "qv2_plan_set_timing", "qv2_plan_kernel_ms",
+    "qv2_plan_set_timing", "qv2_plan_kernel_ms", "qv2_histogram_workspace_bytes", "qv2_histogram",
+    "qv2_kl_divergence",
     "qv2_finalize", "qv2_pair_finalize", "qv2_rank_config_default", "qv2_rank",
     "qv2_baseline_order", "qv2_bops_reduction_pct", "qv2_bops_select",
     "qv2_status_string",
@@ -96,6 +97,10 @@ def lib():
         L.qv2_fakequant_pair_metrics.argtypes = [vp, vp, vp, vp, vp, sz, vp]
         L.qv2_fakequant_pair_metrics_cos.argtypes = [vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.qv2_cosine_finalize.argtypes = [vp, vp, vp, vp, vp, vp, vp]
+        L.qv2_histogram_workspace_bytes.argtypes = [vp, i32]
+        L.qv2_histogram_workspace_bytes.restype = sz
+        L.qv2_histogram.argtypes = [vp, vp, i32, vp, vp, vp, sz, vp]
+        L.qv2_kl_divergence.argtypes = [vp, vp, i32, ctypes.c_double, vp]
         L.qv2_plan_set_timing.argtypes = [vp, i32]
         L.qv2_plan_kernel_ms.argtypes = [vp, i32, ctypes.POINTER(ctypes.c_float)]
         L.qv2_finalize.argtypes = [vp, vp, vp, vp]
@@ -190,7 +195,7 @@ def qv2_plan_create(rows: Sequence[TensorArg]) -> Plan:
 
 
 KERNEL_IDS = {"k_stats_stream": 0, "k_stats_rows": 1, "k_quant_stream": 2, "k_quant_rows": 3,
-              "k_pair_stream": 4, "k_quantpair_stream": 5, "k_quantpair_rows": 6}
+              "k_pair_stream": 4, "k_quantpair_stream": 5, "k_quantpair_rows": 6, "k_hist": 7}
 
 
 def qv2_plan_set_timing(plan: Plan, enable: bool):
@@ -259,6 +264,28 @@ def qv2_cosine_finalize(plan: Plan, h_sums, h_seg_xxhat, h_pair, h_pair_xq, stri
     if st != QV2_OK and (strict or st != QV2_ERR_NONFINITE):
         raise QV2Error(st, "qv2_cosine_finalize")
     return cq, cp
+
+
+def qv2_histogram_workspace_bytes(plan: Plan, nbins: int) -> int:
+    return lib().qv2_histogram_workspace_bytes(plan.handle, int(nbins))
+
+
+def qv2_histogram(plan: Plan, d_params, nbins: int, d_hist_x, d_hist_q, d_workspace, workspace_bytes=None,
+                  stream=None):
+    wb = workspace_bytes if workspace_bytes is not None else d_workspace.numel() * d_workspace.element_size()
+    _check(lib().qv2_histogram(plan.handle, _ptr(d_params), int(nbins), _ptr(d_hist_x), _ptr(d_hist_q),
+                               _ptr(d_workspace), wb, _stream(stream)), "qv2_histogram")
+
+
+def qv2_kl_divergence(hist_p, hist_q, eps: float = 0.0) -> float:
+    hp = np.ascontiguousarray(hist_p, dtype=np.uint64)
+    hq = np.ascontiguousarray(hist_q, dtype=np.uint64)
+    if hp.size != hq.size:
+        raise QV2Error(QV2_ERR_SHAPE, "qv2_kl_divergence")
+    out = ctypes.c_double()
+    _check(lib().qv2_kl_divergence(hp.ctypes.data, hq.ctypes.data, hp.size, float(eps), ctypes.addressof(out)),
+           "qv2_kl_divergence")
+    return out.value
 
 
 def qv2_finalize(plan: Plan, h_params: np.ndarray, h_sums: np.ndarray, strict: bool = True) -> np.ndarray:

@@ -146,6 +146,28 @@ qv2_status qv2_plan_create(const qv2_tensor* h_tensors, int32_t n_tensors, qv2_p
   }
   if (err != QV2_OK) { delete p; return err; }
 
+  // histogram pass: about kHistChunks long chunks over all tensors
+  {
+    int64_t total = 0;
+    for (int32_t t = 0; t < n_tensors; ++t) total += h_tensors[t].numel;
+    int64_t chunk = (total + qv2::kHistChunks - 1) / qv2::kHistChunks;
+    chunk = std::max<int64_t>(qv2::kHistMinChunk, (chunk + 4095) / 4096 * 4096);
+    chunk = std::min<int64_t>(chunk, int64_t{1} << 30);
+    for (int32_t t = 0; t < n_tensors; ++t) {
+      const qv2_tensor& in = h_tensors[t];
+      const int64_t nc = (in.numel + chunk - 1) / chunk;
+      qv2::HistTensor ht{static_cast<int32_t>(p->hist_tiles.size()), static_cast<int32_t>(nc),
+                         p->info[t].seg0, p->info[t].nseg};
+      if (static_cast<int64_t>(p->hist_tiles.size()) + nc > kMax) { delete p; return QV2_ERR_SHAPE; }
+      for (int64_t k = 0; k < nc; ++k) {
+        Tile tl = make_tile(in, t, k * chunk, std::min<int64_t>(chunk, in.numel - k * chunk));
+        tl.part0 = static_cast<int32_t>(p->hist_tiles.size());
+        p->hist_tiles.push_back(tl);
+      }
+      p->hist_tensors.push_back(ht);
+    }
+  }
+
   for (size_t i = 0; i < p->segments.size(); ++i) {
     if (p->segments[i].snp > qv2::kFoldWaveMax) p->big_stat_segments.push_back(static_cast<int32_t>(i));
     if (p->segments[i].enp > qv2::kFoldWaveMax) p->big_err_segments.push_back(static_cast<int32_t>(i));
@@ -183,6 +205,13 @@ int64_t qv2_plan_num_pair_tiles(const qv2_plan* plan) {
   return plan ? static_cast<int64_t>(plan->pair_tiles.size()) : 0;
 }
 size_t qv2_workspace_bytes(const qv2_plan* plan) { return plan ? plan->workspace_bytes : 0; }
+
+size_t qv2_histogram_workspace_bytes(const qv2_plan* plan, int32_t nbins) {
+  if (!plan || nbins < 2 || nbins > qv2::kHistMaxBins) return 0;
+  // per-tensor range records, then two partial histograms (x, qrun) per chunk
+  const size_t ranges = round_up(plan->info.size() * 2 * sizeof(float), 256);
+  return ranges + round_up(plan->hist_tiles.size() * 2 * static_cast<size_t>(nbins) * sizeof(uint32_t), 256);
+}
 
 // ---------------------------------------------------------------------------
 // Sec. 6.1 Eq. 6-7 and the tensor statistics, fp64.
@@ -228,6 +257,31 @@ qv2_status qv2_pair_finalize(const qv2_pair_sums* h_pair, int32_t n, double* h_m
     h_sqnr_db[i] = sqnr_db_of(h_pair[i].sum_ref2, h_pair[i].sum_d2);
   }
   return finite ? QV2_OK : QV2_ERR_NONFINITE;
+}
+
+// Sec. 6.1 Eq. 9 between two histograms over the same bins, natural log, fp64.
+qv2_status qv2_kl_divergence(const uint64_t* h_hist_p, const uint64_t* h_hist_q, int32_t nbins,
+                             double eps, double* kl_out) {
+  if (!h_hist_p || !h_hist_q || !kl_out) return QV2_ERR_NULL;
+  if (nbins <= 0) return QV2_ERR_SHAPE;
+  if (!(eps >= 0.0) || !std::isfinite(eps)) return QV2_ERR_NONFINITE;
+  double tp = 0.0, tq = 0.0;
+  for (int32_t i = 0; i < nbins; ++i) {
+    tp += static_cast<double>(h_hist_p[i]);
+    tq += static_cast<double>(h_hist_q[i]);
+  }
+  tp += eps * nbins; tq += eps * nbins;
+  if (!(tp > 0.0) || !(tq > 0.0)) return QV2_ERR_SHAPE;
+  double kl = 0.0;
+  for (int32_t i = 0; i < nbins; ++i) {
+    const double pa = (static_cast<double>(h_hist_p[i]) + eps) / tp;
+    const double qa = (static_cast<double>(h_hist_q[i]) + eps) / tq;
+    if (pa == 0.0) continue;
+    if (qa == 0.0) { *kl_out = std::numeric_limits<double>::infinity(); return QV2_OK; }
+    kl += pa * std::log(pa / qa);
+  }
+  *kl_out = kl;
+  return QV2_OK;
 }
 
 // Sec. 6.1 Eq. 8 from the energies the quantize pass keeps: with d = a - b,

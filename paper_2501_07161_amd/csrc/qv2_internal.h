@@ -38,6 +38,10 @@ constexpr int kDefaultReadTile = 32768;
 // (block x kVecQuant x 4 elements).  A kernel that mixes code stores into the read stream
 // runs fastest when all in-flight workgroups sweep a narrow address window.
 constexpr int kDefaultQuantTile = kBlockQuant * kVecQuant * 4;
+// Histogram pass: a chunk is at least this long; the plan aims at about kHistChunks chunks.
+constexpr int kHistMinChunk = 65536;
+constexpr int kHistChunks = 4096;
+constexpr int kHistMaxBins = 4096;
 // A segment (or pair tensor) with more partials than this is folded by a whole
 // 1024-thread workgroup instead of one wavefront.
 constexpr int kFoldWaveMax = 128;
@@ -78,6 +82,11 @@ struct PairTensor {            // 16 B, one per tensor of the plan
   int32_t nparts;
 };
 
+struct HistTensor {            // 16 B, one per tensor: its chunks of the histogram pass
+  int32_t chunk0, nchunks;
+  int32_t seg0, nseg;
+};
+
 struct TensorInfo {            // host only
   int64_t numel;
   int32_t seg0, nseg;
@@ -97,6 +106,8 @@ struct qv2_plan {
   std::vector<qv2::Tile> quant_tiles;    // quantize passes: stream tiles (quantize size)
   std::vector<qv2::Tile> row_tiles;      // row-group tiles, used by both
   std::vector<qv2::Tile> pair_tiles;     // pair pass: stream tiles over tensors with qrun
+  std::vector<qv2::Tile> hist_tiles;     // histogram pass: long chunks (part0 = chunk index)
+  std::vector<qv2::HistTensor> hist_tensors;
   std::vector<qv2::Segment> segments;
   std::vector<qv2::PairTensor> pair_tensors;        // partial ranges of the pair pass
   std::vector<qv2::PairTensor> fused_pair_tensors;  // ranges in the quantize numbering
@@ -114,6 +125,8 @@ struct qv2_plan {
   qv2::Tile* d_quant_tiles = nullptr;
   qv2::Tile* d_row_tiles = nullptr;
   qv2::Tile* d_pair_tiles = nullptr;
+  qv2::Tile* d_hist_tiles = nullptr;
+  qv2::HistTensor* d_hist_tensors = nullptr;
   qv2::Segment* d_segments = nullptr;
   qv2::PairTensor* d_pair_tensors = nullptr;
   qv2::PairTensor* d_fused_pair_tensors = nullptr;

@@ -717,6 +717,109 @@ __global__ __launch_bounds__(BLOCK) void k_pair_stream(const Tile* __restrict__ 
 }
 
 // ---------------------------------------------------------------------------
+// calibration histograms (Sec. 5, calibration stage), the input of the KL
+// divergence of Sec. 6.1 Eq. 9.  Integer counts only, so any order is exact.
+// ---------------------------------------------------------------------------
+// Per-tensor range from the per-segment calibration: one wavefront per tensor.
+__global__ __launch_bounds__(256) void k_hist_range(const HistTensor* __restrict__ ht, int n,
+                                                    const qv2_qparams* __restrict__ params,
+                                                    float2* __restrict__ range) {
+  const int t = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & (kWave - 1);
+  if (t >= n) return;
+  const HistTensor h = ht[t];
+  float lo = INFINITY, hi = -INFINITY;
+  for (int i = lane; i < h.nseg; i += kWave) {
+    lo = fminf(lo, params[h.seg0 + i].min);
+    hi = fmaxf(hi, params[h.seg0 + i].max);
+  }
+  lo = group_min(lo, kWave); hi = group_max(hi, kWave);
+  if (lane == 0) range[t] = make_float2(lo, hi);
+}
+
+struct Binner { float lo, inv_w, top; int idx0; };
+
+// bin = clamp(floor((x - lo) * inv_w), 0, nbins - 1), each step one fp32 rounding
+__device__ __forceinline__ int bin_of(float x, const Binner& b) {
+  const float t = (x - b.lo) * b.inv_w;
+  float f = floorf(t);
+  f = fminf(fmaxf(f, 0.0f), b.top);                 // maxNum also turns NaN into 0
+  return static_cast<int>(f);
+}
+
+// One stream of a chunk into an LDS histogram.  The bin that holds the value 0 (half of
+// a post-ReLU tensor) is counted in a register and added once per wavefront.
+template <int BLOCK>
+__device__ __forceinline__ void hist_stream(const float* x, int len, const Binner& b, uint32_t* h) {
+  const int tid = threadIdx.x;
+  const gf_ptr p = (gf_ptr)x;
+  const int head = head_elems(x, len);
+  const int body = len - head, nvec = body >> 2, tail = body & 3;
+  uint32_t zeros = 0;
+  auto hit = [&](float v) {
+    const int i = bin_of(v, b);
+    if (i == b.idx0) ++zeros; else atomicAdd(&h[i], 1u);
+  };
+  if (tid < head) hit(p[tid]);
+  if (tid < tail) hit(p[head + (nvec << 2) + tid]);
+  const gf4_ptr v4 = (gf4_ptr)(x + head);
+  constexpr int V = 4;
+  int base = 0;
+  for (; base + V * BLOCK <= nvec; base += V * BLOCK) {
+    f4 r[V];
+#pragma unroll
+    for (int u = 0; u < V; ++u) r[u] = ld4(v4 + base + u * BLOCK + tid);
+#pragma unroll
+    for (int u = 0; u < V; ++u) { hit(r[u].x); hit(r[u].y); hit(r[u].z); hit(r[u].w); }
+  }
+  for (int i = base + tid; i < nvec; i += BLOCK) {
+    const f4 r = ld4(v4 + i);
+    hit(r.x); hit(r.y); hit(r.z); hit(r.w);
+  }
+  for (int o = kWave >> 1; o > 0; o >>= 1) zeros += __shfl_xor(zeros, o);
+  if ((tid & (kWave - 1)) == 0 && zeros) atomicAdd(&h[b.idx0], zeros);
+}
+
+template <int BLOCK>
+__global__ __launch_bounds__(BLOCK) void k_hist(const Tile* __restrict__ tiles,
+                                                const float2* __restrict__ range, int nbins,
+                                                uint32_t* __restrict__ partial) {
+  __shared__ uint32_t h[2][kHistMaxBins];
+  const Tile tl = tiles[blockIdx.x];
+  const float2 r = range[tl.tensor];
+  Binner b;
+  b.lo = r.x;
+  const float w = r.y - r.x;
+  b.inv_w = (w > 0.0f && w <= FLT_MAX) ? static_cast<float>(nbins) / w : 0.0f;
+  b.top = static_cast<float>(nbins - 1);
+  b.idx0 = bin_of(0.0f, b);
+  for (int i = threadIdx.x; i < nbins; i += BLOCK) { h[0][i] = 0; h[1][i] = 0; }
+  __syncthreads();
+  hist_stream<BLOCK>(tl.x, tl.len, b, h[0]);
+  if (tl.q) hist_stream<BLOCK>(tl.q, tl.len, b, h[1]);
+  __syncthreads();
+  uint32_t* out = partial + static_cast<size_t>(tl.part0) * 2 * nbins;
+  for (int i = threadIdx.x; i < nbins; i += BLOCK) { out[i] = h[0][i]; out[nbins + i] = h[1][i]; }
+}
+
+// Sums a tensor's chunk histograms: ceil(nbins / 256) workgroups per tensor.
+__global__ __launch_bounds__(256) void k_hist_fold(const HistTensor* __restrict__ ht, int nbins,
+                                                   const uint32_t* __restrict__ partial,
+                                                   unsigned long long* __restrict__ hist_x,
+                                                   unsigned long long* __restrict__ hist_q) {
+  const int per = (nbins + 255) / 256;
+  const int t = blockIdx.x / per, i = (blockIdx.x % per) * 256 + threadIdx.x;
+  if (i >= nbins) return;
+  const HistTensor h = ht[t];
+  unsigned long long a = 0, b = 0;
+  for (int c = h.chunk0; c < h.chunk0 + h.nchunks; ++c) {
+    const uint32_t* src = partial + static_cast<size_t>(c) * 2 * nbins;
+    a += src[i]; b += src[nbins + i];
+  }
+  hist_x[static_cast<size_t>(t) * nbins + i] = a;
+  if (hist_q) hist_q[static_cast<size_t>(t) * nbins + i] = b;
+}
+
+// ---------------------------------------------------------------------------
 // host helpers
 // ---------------------------------------------------------------------------
 size_t align256(size_t v) { return (v + 255) & ~static_cast<size_t>(255); }
@@ -735,6 +838,7 @@ qv2_status ensure_uploaded(qv2_plan* p) {
   const size_t o_ft = reserve(bytes_of(p->fused_pair_tensors));
   const size_t o_bs = reserve(bytes_of(p->big_stat_segments)), o_be = reserve(bytes_of(p->big_err_segments));
   const size_t o_bp = reserve(bytes_of(p->big_pair_tensors)), o_bf = reserve(bytes_of(p->big_fused_pair_tensors));
+  const size_t o_ht = reserve(bytes_of(p->hist_tiles)), o_hten = reserve(bytes_of(p->hist_tensors));
   char* blob = nullptr;
   if (hipMalloc(reinterpret_cast<void**>(&blob), total) != hipSuccess) {
     (void)hipGetLastError();
@@ -761,6 +865,9 @@ qv2_status ensure_uploaded(qv2_plan* p) {
       static_cast<int32_t*>(put(o_bp, p->big_pair_tensors.data(), bytes_of(p->big_pair_tensors)));
   p->d_big_fused_pair_tensors = static_cast<int32_t*>(
       put(o_bf, p->big_fused_pair_tensors.data(), bytes_of(p->big_fused_pair_tensors)));
+  p->d_hist_tiles = static_cast<Tile*>(put(o_ht, p->hist_tiles.data(), bytes_of(p->hist_tiles)));
+  p->d_hist_tensors =
+      static_cast<HistTensor*>(put(o_hten, p->hist_tensors.data(), bytes_of(p->hist_tensors)));
   if (!ok) { (void)hipGetLastError(); (void)hipFree(blob); return QV2_ERR_HIP; }
   p->d_blob = blob;
   return QV2_OK;
@@ -961,6 +1068,35 @@ qv2_status qv2_fakequant_pair_metrics_cos(qv2_plan* plan, const qv2_qparams* d_p
   ErrPartial5* parts = static_cast<ErrPartial5*>(d_workspace);
   launch_quant<true, true>(plan, d_params, d_sums, parts, d_seg_xxhat, s);
   launch_fused_pair_fold(plan, parts, d_pair_sums, d_pair_xq, s);
+  return launch_status();
+}
+
+qv2_status qv2_histogram(qv2_plan* plan, const qv2_qparams* d_params, int32_t nbins,
+                         uint64_t* d_hist_x, uint64_t* d_hist_q, void* d_workspace,
+                         size_t workspace_bytes, void* hip_stream) {
+  if (!plan || !d_params || !d_hist_x || !d_workspace) return QV2_ERR_NULL;
+  if (nbins < 2 || nbins > kHistMaxBins) return QV2_ERR_SHAPE;
+  if (workspace_bytes < qv2_histogram_workspace_bytes(plan, nbins)) return QV2_ERR_WORKSPACE;
+  if ((reinterpret_cast<uintptr_t>(d_workspace) & 15u) || (reinterpret_cast<uintptr_t>(d_hist_x) & 7u) ||
+      (reinterpret_cast<uintptr_t>(d_hist_q) & 7u)) return QV2_ERR_ALIGN;
+  qv2_status st = ensure_uploaded(plan);
+  if (st != QV2_OK) return st;
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  const int nt = static_cast<int>(plan->info.size());
+  const int n_chunks = static_cast<int>(plan->hist_tiles.size());
+  float2* range = static_cast<float2*>(d_workspace);
+  uint32_t* partial = reinterpret_cast<uint32_t*>(static_cast<char*>(d_workspace) +
+                                                  align256(static_cast<size_t>(nt) * sizeof(float2)));
+  hipLaunchKernelGGL(k_hist_range, dim3(fold_grid(nt)), dim3(256), 0, s, plan->d_hist_tensors, nt,
+                     d_params, range);
+  {
+    Timed timed(plan, QV2_K_HIST, s);
+    hipLaunchKernelGGL(k_hist<kBlockRead>, dim3(n_chunks), dim3(kBlockRead), 0, s, plan->d_hist_tiles,
+                       range, nbins, partial);
+  }
+  hipLaunchKernelGGL(k_hist_fold, dim3(((nbins + 255) / 256) * nt), dim3(256), 0, s, plan->d_hist_tensors,
+                     nbins, partial, reinterpret_cast<unsigned long long*>(d_hist_x),
+                     reinterpret_cast<unsigned long long*>(d_hist_q));
   return launch_status();
 }
 

@@ -239,6 +239,43 @@ def test_cosine_similarity_variant():
     assert abs(r2.cos_pair[names.index("neg_q")] + 1.0) < 1e-12
 
 
+@pytest.mark.parametrize("nbins", [7, 2048, 4096])
+def test_histograms_and_kl_divergence(nbins):
+    """qv2_histogram: counts bit-exact against the oracle (same fp32 binning rule) for x and for
+    qrun over x's calibrated range; KL divergence from those counts."""
+    specs = synth.config_tiny() + synth.config_mobilenetv2(2)
+    items = H.items_from_specs(specs, DEV)
+    H.attach_pairs(items, specs)
+    items += [H.Item("ragged", _rand(200_003, 51)[3:], A, qrun=_rand(200_001, 52)[1:] * 3.0),   # qrun wider than x
+              H.Item("zeros", torch.zeros(70_000, device=DEV), A, qrun=torch.zeros(70_000, device=DEV)),
+              H.Item("rows", _rand(48 * 27, 53, 0.1), C, 48, qrun=_rand(48 * 27, 54, 0.1)),
+              H.Item("long", torch.relu(_rand(1_500_000, 55)), A, qrun=torch.relu(_rand(1_500_000, 55)) + 0.01)]
+    res = H.run_gpu(items, fused=True)
+    plan, buf = res.plan, res.buffers
+    hx = torch.zeros(plan.num_tensors * nbins, dtype=torch.int64, device=DEV)
+    hq = torch.ones(plan.num_tensors * nbins, dtype=torch.int64, device=DEV)
+    ws = torch.zeros(qb.qv2_histogram_workspace_bytes(plan, nbins), dtype=torch.uint8, device=DEV)
+    qb.qv2_histogram(plan, buf.params, nbins, hx, hq, ws)
+    torch.cuda.synchronize()
+    hx = hx.cpu().numpy().astype(np.uint64).reshape(plan.num_tensors, nbins)
+    hq = hq.cpu().numpy().astype(np.uint64).reshape(plan.num_tensors, nbins)
+    for t, it in enumerate(items):
+        x = it.x.cpu().numpy().reshape(-1)
+        lo, hi = np.float32(x.min()) + np.float32(0), np.float32(x.max()) + np.float32(0)
+        want = orc.histogram(x, lo, hi, nbins)
+        assert np.array_equal(hx[t], want), f"{it.name}: x histogram"
+        assert int(hx[t].sum()) == x.size
+        if it.qrun is None:
+            assert not hq[t].any()
+            continue
+        wq = orc.histogram(it.qrun.cpu().numpy().reshape(-1), lo, hi, nbins)
+        assert np.array_equal(hq[t], wq), f"{it.name}: qrun histogram"
+        for eps in (0.0, 1.0):
+            got, ref = qb.qv2_kl_divergence(hx[t], hq[t], eps), orc.kl_divergence(want.tolist(), wq.tolist(), eps)
+            assert got == ref or abs(got - ref) <= 1e-12 * abs(ref) + 1e-15, f"{it.name}: KL"
+    assert qb.qv2_kl_divergence(hx[-3], hq[-3], 0.0) == 0.0        # identical (all-zero) tensors
+
+
 def test_cross_kernel_pair_of_dequantized_equals_fakequant_error():
     """pair(x, dequant(codes)) must reproduce the fake-quant pass's own noise energy."""
     x = torch.relu(_rand(300_000, 15, 1.5))

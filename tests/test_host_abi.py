@@ -276,3 +276,43 @@ def test_bops_errors():
     with pytest.raises(qb.QV2Error) as e:
         qb.qv2_baseline_order(qb.QV2_ORDER_WEIGHT_SQNR, [1.0, math.nan])
     assert e.value.status == qb.QV2_ERR_NONFINITE
+
+
+# ----------------------------------------------------------------------------
+# histograms / KL divergence (Sec. 5, Sec. 6.1 Eq. 9): host parts
+# ----------------------------------------------------------------------------
+def test_kl_divergence_matches_oracle():
+    rng = np.random.default_rng(41)
+    for trial in range(200):
+        nb = int(rng.integers(1, 300))
+        p = rng.integers(0, 10 ** 6, nb).astype(np.uint64)
+        q = rng.integers(0, 10 ** 6, nb).astype(np.uint64)
+        p[rng.integers(0, nb)] += 1
+        q[rng.integers(0, nb)] += 1
+        if trial % 3 == 0:
+            q[rng.integers(0, nb, max(1, nb // 4))] = 0
+        for eps in (0.0, 1.0, 1e-3):
+            got = qb.qv2_kl_divergence(p, q, eps)
+            want = orc.kl_divergence(p.tolist(), q.tolist(), eps)
+            assert got == want or got == pytest.approx(want, rel=1e-12, abs=1e-15)
+    assert qb.qv2_kl_divergence([2, 2], [1, 3]) == pytest.approx(0.5 * math.log(2) + 0.5 * math.log(2 / 3))
+    assert qb.qv2_kl_divergence([1, 3], [0, 4]) == math.inf
+    for bad, st in (((lambda: qb.qv2_kl_divergence([0, 0], [1, 1])), qb.QV2_ERR_SHAPE),
+                    ((lambda: qb.qv2_kl_divergence([1, 1], [1, 1], -1.0)), qb.QV2_ERR_NONFINITE),
+                    ((lambda: qb.qv2_kl_divergence([1, 1], [1, 1, 1])), qb.QV2_ERR_SHAPE)):
+        with pytest.raises(qb.QV2Error) as e:
+            bad()
+        assert e.value.status == st
+
+
+def test_histogram_host_checks():
+    p = qb.qv2_plan_create([_row(1_000_000, qrun=FAKE), _row(300)])
+    assert qb.qv2_histogram_workspace_bytes(p, 1) == 0 and qb.qv2_histogram_workspace_bytes(p, 4097) == 0
+    ws = qb.qv2_histogram_workspace_bytes(p, 2048)
+    # 1e6 elements in chunks of at least 65536 -> 16 chunks, + 1 for the small tensor
+    assert ws >= 17 * 2 * 2048 * 4 and ws % 256 == 0
+    L = qb.lib()
+    assert L.qv2_histogram(p.handle, FAKE, 2048, None, None, FAKE, ws, None) == qb.QV2_ERR_NULL
+    assert L.qv2_histogram(p.handle, FAKE, 1, FAKE, None, FAKE, ws, None) == qb.QV2_ERR_SHAPE
+    assert L.qv2_histogram(p.handle, FAKE, 2048, FAKE, None, FAKE, ws - 1, None) == qb.QV2_ERR_WORKSPACE
+    assert L.qv2_histogram(p.handle, FAKE, 2048, FAKE + 4, None, FAKE, ws, None) == qb.QV2_ERR_ALIGN

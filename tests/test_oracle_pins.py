@@ -501,3 +501,54 @@ def test_cosine_similarity_pins():
     m = orc.tensor_metrics(x, cal, fq)
     c = orc.cosine_similarity(x, fq.xhat)
     assert 1.0 - c == pytest.approx(m.mse / (2.0 * fq.sum_x2[0] / x.size), rel=0.05)
+
+
+# ----------------------------------------------------------------------------
+# calibration histograms (Sec. 5) and KL divergence (Sec. 6.1 Eq. 9)
+# ----------------------------------------------------------------------------
+def test_histogram_pins():
+    rng = np.random.default_rng(15)
+    # bin midpoints of a power-of-two grid: every element is far from an edge -> equal to numpy exactly
+    nb = 256
+    mids = ((np.arange(nb) + 0.5) / nb * 8.0 - 4.0).astype(np.float32)
+    x = rng.choice(mids, 50_000).astype(np.float32)
+    h = orc.histogram(x, -4.0, 4.0, nb)
+    assert np.array_equal(h, np.histogram(x, bins=nb, range=(-4.0, 4.0))[0].astype(np.uint64))
+    # one element per bin, both range ends included (the maximum lands in the last bin)
+    assert orc.histogram(np.concatenate([mids, [-4.0, 4.0]]), -4.0, 4.0, nb).tolist() == \
+        [2] + [1] * (nb - 2) + [2]
+    # random data: total preserved, numpy agrees except for elements within rounding of an edge
+    y = (rng.standard_normal(300_000) * 1.7).astype(np.float32)
+    lo, hi = float(y.min()), float(y.max())
+    for nbins in (7, 2048, 4096):
+        h = orc.histogram(y, lo, hi, nbins)
+        ref = np.histogram(y.astype(np.float64), bins=nbins, range=(lo, hi))[0]
+        assert int(h.sum()) == y.size
+        assert np.abs(np.cumsum(h.astype(np.int64)) - np.cumsum(ref)).max() <= 3
+    # brute force on a tiny case with out-of-range values and a degenerate range
+    z = np.array([-5.0, -1.0, -0.5, 0.0, 0.24, 0.25, 0.99, 1.0, 7.0], np.float32)
+    assert orc.histogram(z, -1.0, 1.0, 8).tolist() == [2, 0, 1, 0, 2, 1, 0, 3]
+    assert orc.histogram(z, 2.0, 2.0, 4).tolist() == [9, 0, 0, 0]
+
+
+def test_kl_divergence_pins():
+    from scipy.special import rel_entr
+    rng = np.random.default_rng(16)
+    p = rng.integers(1, 1000, 64)
+    q = rng.integers(1, 1000, 64)
+    want = float(rel_entr(p / p.sum(), q / q.sum()).sum())        # library routine
+    assert orc.kl_divergence(p, q) == pytest.approx(want, rel=1e-12)
+    assert orc.kl_divergence(p, p) == 0.0
+    assert orc.kl_divergence(p, 3 * p) == pytest.approx(0.0, abs=1e-15)     # counts are normalised
+    assert orc.kl_divergence(p, q) > 0 and orc.kl_divergence(q, p) > 0     # Gibbs
+    assert orc.kl_divergence(p, q) != pytest.approx(orc.kl_divergence(q, p), rel=1e-3)   # not symmetric
+    # two-bin closed form: P = (1/2, 1/2), Q = (1/4, 3/4)
+    assert orc.kl_divergence([2, 2], [1, 3]) == pytest.approx(0.5 * math.log(2) + 0.5 * math.log(2 / 3), rel=1e-14)
+    # empty P bins contribute nothing; an empty Q bin under a non-empty P bin gives +inf
+    assert orc.kl_divergence([0, 4], [1, 3]) == pytest.approx(math.log(4 / 3), rel=1e-14)
+    assert orc.kl_divergence([1, 3], [0, 4]) == math.inf
+    # additive smoothing: (c + eps) / (n + eps * bins)
+    assert orc.kl_divergence([1, 3], [0, 4], eps=1.0) == pytest.approx(
+        (2 / 6) * math.log((2 / 6) / (1 / 6)) + (4 / 6) * math.log((4 / 6) / (5 / 6)), rel=1e-14)
+    with pytest.raises(ValueError):
+        orc.kl_divergence([1, 2], [1, 2, 3])
