@@ -206,6 +206,29 @@ def main():
     main_r = timed(args.mode)
     other = None if args.single_mode else timed("calls" if args.mode == "fused" else "fused")
 
+    # optional metrics outside the headline pass (the paper's other candidate local metrics)
+    extras = {}
+    if not args.single_mode:
+        nb = 2048
+        hx = torch.zeros(plan.num_tensors * nb, dtype=torch.int64, device=dev)
+        hq = torch.zeros(plan.num_tensors * nb, dtype=torch.int64, device=dev)
+        hws = torch.zeros(qb.qv2_histogram_workspace_bytes(plan, nb), dtype=torch.uint8, device=dev)
+        sxh = torch.zeros(plan.num_segments, dtype=torch.float64, device=dev)
+        pxq = torch.zeros(plan.num_tensors, dtype=torch.float64, device=dev)
+        t_h, t_c = [], []
+        for it in range(5):
+            qb.qv2_histogram(plan, buf.params, nb, hx, hq, hws)
+            qb.qv2_fakequant_pair_metrics_cos(plan, buf.params, buf.sums, buf.pair, sxh, pxq, buf.workspace)
+            torch.cuda.synchronize()
+            if it >= 1:
+                t_h.append(qb.qv2_plan_kernel_ms(plan, "k_hist"))
+                t_c.append(qb.qv2_plan_kernel_ms(plan, "k_quantpair_stream"))
+        hist_bytes = 4 * n_all + 4 * n_pair
+        extras = {"histogram_2048_bins": {"kernel_ms": round(float(np.mean(t_h)), 4),
+                                          "GBps": round(hist_bytes / np.mean(t_h) / 1e6, 1)},
+                  "fused_quantize_with_cosine": {"kernel_ms": round(float(np.mean(t_c)), 4)}}
+        del hx, hq, hws
+
     if args.copy_probe:
         src = torch.ones(1 << 28, dtype=torch.float32, device=dev)      # 1 GiB
         dst = torch.empty_like(src)
@@ -266,6 +289,8 @@ def main():
     macs = synth.layer_macs(tables[args.workload]())
     out["bops_cut_layers_kept_fp32"] = {str(t): qb.qv2_bops_select(last["order"], macs, float(t))[1]
                                         for t in (60, 50, 40, 30, 20)}
+    if extras:
+        out["extras"] = extras
     if other is not None:
         o_bytes = bytes_cal + (bytes_fq + bytes_pair if args.mode == "fused" else bytes_fqpair)
         out["other_pass"] = {"pass": "three separate calls" if args.mode == "fused" else "fused",
