@@ -232,6 +232,17 @@ qv2_status qv2_histogram(qv2_plan* plan, const qv2_qparams* d_params, int32_t nb
                          uint64_t* d_hist_x, uint64_t* d_hist_q, void* d_workspace,
                          size_t workspace_bytes, void* hip_stream);
 
+/* Conv + BN folding (Sec. 6.3 Eq. 10-12), the weights of the fused graph IR: per output
+ * channel c, f_c = gamma_c / sqrt(var_c) (no epsilon, as printed), w_out = f_c * w,
+ * bias_out_c = f_c * (bias_c - mean_c) + beta_c; fp32, one rounding per operation.
+ * All pointers DEVICE.  d_w, d_w_out: channels * inner floats (may alias); the per-channel
+ * vectors have `channels` entries.  d_bias may be NULL (taken as 0); d_bias_out may be NULL
+ * (then d_mean and d_beta are not needed).  channels: 1 .. 65535.
+ * Errors: ERR_NULL, ERR_SHAPE, ERR_HIP. */
+qv2_status qv2_bn_fold(const float* d_w, int32_t channels, int64_t inner, const float* d_gamma,
+                       const float* d_var, const float* d_bias, const float* d_mean,
+                       const float* d_beta, float* d_w_out, float* d_bias_out, void* hip_stream);
+
 /* ---- host finalize and ranking (need no GPU) ----------------------------- */
 
 /* Eq. 6-7 and the tensor statistics from host copies of params and sums; a
@@ -310,6 +321,15 @@ qv2_status qv2_bops_reduction_pct(const double* macs, const uint8_t* keep_fp32, 
 qv2_status qv2_bops_select(const int32_t* order, const double* macs, int32_t n_layers,
                            double target_pct, uint8_t* keep_fp32_out, int32_t* n_keep_out,
                            double* achieved_pct_out);
+
+/* Fusion-aware adjustment of a sensitivity list (Sec. 6.5 says only that positions of
+ * fusion-capable operators "can be adjusted"; this is the reading taken): layers with the
+ * same group_id (a convolution and the BN / Add / ReLU neighbours it fuses with) keep one
+ * precision, so each group moves as a block to the position of its most sensitive member;
+ * list order is kept inside a block and between blocks.  order_out may not alias order.
+ * Errors: ERR_NULL, ERR_SHAPE (n_layers <= 0, order not a permutation). */
+qv2_status qv2_regroup_for_fusion(const int32_t* order, const int32_t* group_id, int32_t n_layers,
+                                  int32_t* order_out);
 
 const char* qv2_status_string(qv2_status s);
 

@@ -222,3 +222,23 @@ void orc_histogram(const float *x, int64_t n, float lo, float hi, int32_t nbins,
         hist[(int32_t)f] += 1;
     }
 }
+
+/* Sec. 6.3 Eq. 10-12: folding batch normalisation into the convolution before it.
+ * Per output channel c: f_c = gamma_c / sqrt(var_c) (the paper's sqrt(sigma^2), no epsilon),
+ * A = f_c * W, C = f_c * (B - mu_c) + beta_c.  fp32, one rounding per operation. */
+void orc_bn_fold(const float *w, int64_t channels, int64_t inner, const float *gamma,
+                 const float *var, const float *bias, const float *mean, const float *beta,
+                 float *w_out, float *bias_out)
+{
+    for (int64_t c = 0; c < channels; ++c) {
+        float root = sqrtf(var[c]);
+        float f = gamma[c] / root;
+        for (int64_t j = 0; j < inner; ++j) w_out[c * inner + j] = f * w[c * inner + j];
+        if (bias_out) {
+            float b = bias ? bias[c] : 0.0f;
+            float d = b - mean[c];
+            float p = f * d;
+            bias_out[c] = p + beta[c];
+        }
+    }
+}

@@ -66,6 +66,8 @@ def lib():
         L.orc_histogram.argtypes = [_F, i64, ctypes.c_float, ctypes.c_float, ctypes.c_int32,
                                     ctypes.POINTER(ctypes.c_uint64)]
         L.orc_histogram.restype = None
+        L.orc_bn_fold.argtypes = [_F, i64, i64, _F, _F, _F, _F, _F, _F, _F]
+        L.orc_bn_fold.restype = None
         L.orc_cosine_sums.argtypes = [_F, _F, i64, _D, _D, _D]
         L.orc_cosine_sums.restype = None
         L.orc_mse.argtypes = [ctypes.c_double, i64]
@@ -451,3 +453,38 @@ def kl_divergence(hist_p, hist_q, eps: float = 0.0) -> float:
             return math.inf
         kl += pa * math.log(pa / qb_)
     return kl
+
+
+# ----------------------------------------------------------------------------
+# Sec. 6.3 Eq. 12 (conv + BN folding) and the fusion-aware regrouping of Sec. 6.5
+# ----------------------------------------------------------------------------
+def bn_fold(w, gamma, var, mean, beta, bias=None):
+    """Folded weights A and bias C of Eq. 12 for a weight of shape [channels, ...]."""
+    w = np.ascontiguousarray(w, dtype=np.float32)
+    ch = w.shape[0]
+    inner = w.size // ch
+    g, v, m, b = (np.ascontiguousarray(a, dtype=np.float32) for a in (gamma, var, mean, beta))
+    bi = None if bias is None else np.ascontiguousarray(bias, dtype=np.float32)
+    w_out = np.empty_like(w)
+    b_out = np.empty(ch, np.float32)
+    lib().orc_bn_fold(_fp(w.reshape(-1)), ch, inner, _fp(g), _fp(v), None if bi is None else _fp(bi),
+                      _fp(m), _fp(b), _fp(w_out.reshape(-1)), _fp(b_out))
+    return w_out, b_out
+
+
+def regroup_for_fusion(order, group_id):
+    """Sec. 6.5 says only that positions of fusion-capable operators "can be adjusted".
+    Reading taken: layers with the same group id (a conv and the BN / Add / ReLU neighbours it
+    fuses with) keep one precision, so a group moves as a block to the position of its most
+    sensitive member; inside the block and between blocks the list order is kept."""
+    n = len(order)
+    if sorted(order) != list(range(n)) or len(group_id) != n:
+        raise ValueError("order must be a permutation and group_id one id per layer")
+    out, done = [], set()
+    for l in order:
+        g = group_id[l]
+        if g in done:
+            continue
+        done.add(g)
+        out.extend(m for m in order if group_id[m] == g)
+    return out

@@ -29,7 +29,7 @@ EXPORTS = (
     "qv2_workspace_bytes", "qv2_calibrate", "qv2_fakequant_metrics", "qv2_pair_metrics",
     "qv2_fakequant_pair_metrics", "qv2_fakequant_pair_metrics_cos", "qv2_cosine_finalize",
     "qv2_plan_set_timing", "qv2_plan_kernel_ms", "qv2_histogram_workspace_bytes", "qv2_histogram",
-    "qv2_kl_divergence",
+    "qv2_kl_divergence", "qv2_bn_fold", "qv2_regroup_for_fusion",
     "qv2_finalize", "qv2_pair_finalize", "qv2_rank_config_default", "qv2_rank",
     "qv2_baseline_order", "qv2_bops_reduction_pct", "qv2_bops_select",
     "qv2_status_string",
@@ -101,6 +101,8 @@ def lib():
         L.qv2_histogram_workspace_bytes.restype = sz
         L.qv2_histogram.argtypes = [vp, vp, i32, vp, vp, vp, sz, vp]
         L.qv2_kl_divergence.argtypes = [vp, vp, i32, ctypes.c_double, vp]
+        L.qv2_bn_fold.argtypes = [vp, i32, i64, vp, vp, vp, vp, vp, vp, vp, vp]
+        L.qv2_regroup_for_fusion.argtypes = [vp, vp, i32, vp]
         L.qv2_plan_set_timing.argtypes = [vp, i32]
         L.qv2_plan_kernel_ms.argtypes = [vp, i32, ctypes.POINTER(ctypes.c_float)]
         L.qv2_finalize.argtypes = [vp, vp, vp, vp]
@@ -286,6 +288,24 @@ def qv2_kl_divergence(hist_p, hist_q, eps: float = 0.0) -> float:
     _check(lib().qv2_kl_divergence(hp.ctypes.data, hq.ctypes.data, hp.size, float(eps), ctypes.addressof(out)),
            "qv2_kl_divergence")
     return out.value
+
+
+def qv2_bn_fold(d_w, channels: int, inner: int, d_gamma, d_var, d_w_out, d_bias=None, d_mean=None,
+                d_beta=None, d_bias_out=None, stream=None):
+    _check(lib().qv2_bn_fold(_ptr(d_w), int(channels), int(inner), _ptr(d_gamma), _ptr(d_var), _ptr(d_bias),
+                             _ptr(d_mean), _ptr(d_beta), _ptr(d_w_out), _ptr(d_bias_out), _stream(stream)),
+           "qv2_bn_fold")
+
+
+def qv2_regroup_for_fusion(order, group_id) -> np.ndarray:
+    o = np.ascontiguousarray(order, dtype=np.int32)
+    g = np.ascontiguousarray(group_id, dtype=np.int32)
+    if len(o) != len(g):
+        raise QV2Error(QV2_ERR_SHAPE, "qv2_regroup_for_fusion")
+    out = np.zeros(max(len(o), 1), np.int32)
+    _check(lib().qv2_regroup_for_fusion(o.ctypes.data, g.ctypes.data, len(o), out.ctypes.data),
+           "qv2_regroup_for_fusion")
+    return out[:len(o)]
 
 
 def qv2_finalize(plan: Plan, h_params: np.ndarray, h_sums: np.ndarray, strict: bool = True) -> np.ndarray:

@@ -468,6 +468,29 @@ qv2_status qv2_bops_select(const int32_t* order, const double* macs, int32_t n_l
   return QV2_OK;
 }
 
+// Sec. 6.5: layers of one fusion group move as a block to the position of the group's most
+// sensitive member; list order is kept inside a block and between blocks.
+qv2_status qv2_regroup_for_fusion(const int32_t* order, const int32_t* group_id, int32_t n_layers,
+                                  int32_t* order_out) {
+  if (!order || !group_id || !order_out) return QV2_ERR_NULL;
+  if (n_layers <= 0) return QV2_ERR_SHAPE;
+  std::vector<char> seen(n_layers, 0), placed(n_layers, 0);
+  for (int32_t i = 0; i < n_layers; ++i) {
+    if (order[i] < 0 || order[i] >= n_layers || seen[order[i]]) return QV2_ERR_SHAPE;
+    seen[order[i]] = 1;
+  }
+  int32_t w = 0;
+  for (int32_t i = 0; i < n_layers; ++i) {
+    if (placed[order[i]]) continue;
+    const int32_t g = group_id[order[i]];
+    for (int32_t k = i; k < n_layers; ++k) {
+      const int32_t l = order[k];
+      if (!placed[l] && group_id[l] == g) { order_out[w++] = l; placed[l] = 1; }
+    }
+  }
+  return QV2_OK;
+}
+
 const char* qv2_status_string(qv2_status s) {
   switch (s) {
     case QV2_OK: return "ok";

@@ -21,6 +21,7 @@
 //    body has no branches and all of a batch's loads are issued up front.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cfloat>
 #include <cstdint>
 
@@ -820,6 +821,31 @@ __global__ __launch_bounds__(256) void k_hist_fold(const HistTensor* __restrict_
 }
 
 // ---------------------------------------------------------------------------
+// conv + BN folding (Sec. 6.3 Eq. 12): A = (gamma / sqrt(var)) * W per output channel,
+// C = (gamma / sqrt(var)) * (B - mu) + beta.  One workgroup column per channel.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_bn_fold(const float* w, long long inner,
+                                                 const float* __restrict__ gamma,
+                                                 const float* __restrict__ var,
+                                                 const float* __restrict__ bias,
+                                                 const float* __restrict__ mean,
+                                                 const float* __restrict__ beta,
+                                                 float* w_out, float* __restrict__ bias_out) {
+  const long long c = blockIdx.y;
+  const float f = gamma[c] / sqrtf(var[c]);          // correctly rounded sqrt and divide
+  const float* src = w + c * inner;
+  float* dst = w_out + c * inner;
+  for (long long j = static_cast<long long>(blockIdx.x) * 256 + threadIdx.x; j < inner;
+       j += static_cast<long long>(gridDim.x) * 256)
+    dst[j] = f * src[j];
+  if (bias_out && blockIdx.x == 0 && threadIdx.x == 0) {
+    const float d = (bias ? bias[c] : 0.0f) - mean[c];
+    const float p = f * d;
+    bias_out[c] = p + beta[c];
+  }
+}
+
+// ---------------------------------------------------------------------------
 // host helpers
 // ---------------------------------------------------------------------------
 size_t align256(size_t v) { return (v + 255) & ~static_cast<size_t>(255); }
@@ -1068,6 +1094,19 @@ qv2_status qv2_fakequant_pair_metrics_cos(qv2_plan* plan, const qv2_qparams* d_p
   ErrPartial5* parts = static_cast<ErrPartial5*>(d_workspace);
   launch_quant<true, true>(plan, d_params, d_sums, parts, d_seg_xxhat, s);
   launch_fused_pair_fold(plan, parts, d_pair_sums, d_pair_xq, s);
+  return launch_status();
+}
+
+qv2_status qv2_bn_fold(const float* d_w, int32_t channels, int64_t inner, const float* d_gamma,
+                       const float* d_var, const float* d_bias, const float* d_mean,
+                       const float* d_beta, float* d_w_out, float* d_bias_out, void* hip_stream) {
+  if (!d_w || !d_gamma || !d_var || !d_w_out) return QV2_ERR_NULL;
+  if (d_bias_out && (!d_mean || !d_beta)) return QV2_ERR_NULL;
+  if (channels <= 0 || channels > 65535 || inner <= 0) return QV2_ERR_SHAPE;
+  const int gx = static_cast<int>(std::min<int64_t>((inner + 255) / 256, 1024));
+  hipLaunchKernelGGL(k_bn_fold, dim3(gx, channels), dim3(256), 0, static_cast<hipStream_t>(hip_stream),
+                     d_w, static_cast<long long>(inner), d_gamma, d_var, d_bias, d_mean, d_beta, d_w_out,
+                     d_bias_out);
   return launch_status();
 }
 

@@ -276,6 +276,31 @@ def test_histograms_and_kl_divergence(nbins):
     assert qb.qv2_kl_divergence(hx[-3], hq[-3], 0.0) == 0.0        # identical (all-zero) tensors
 
 
+def test_bn_fold_bit_exact():
+    """Eq. 12 on the device against the oracle: folded weights and bias bit-exact; folding in
+    place; then the folded weight goes through the pass like any other tensor."""
+    g = torch.Generator(device=DEV)
+    g.manual_seed(61)
+    for ch, inner in ((64, 147), (7, 1), (3, 100_003), (512, 4608)):
+        w = torch.randn(ch, inner, generator=g, device=DEV)
+        gamma = torch.rand(ch, generator=g, device=DEV) + 0.5
+        var = torch.rand(ch, generator=g, device=DEV) * 3 + 0.05
+        mean, beta, bias = (torch.randn(ch, generator=g, device=DEV) for _ in range(3))
+        w_out, b_out = torch.empty_like(w), torch.empty(ch, device=DEV)
+        qb.qv2_bn_fold(w, ch, inner, gamma, var, w_out, bias, mean, beta, b_out)
+        torch.cuda.synchronize()
+        a, c = orc.bn_fold(w.cpu().numpy(), gamma.cpu().numpy(), var.cpu().numpy(), mean.cpu().numpy(),
+                           beta.cpu().numpy(), bias.cpu().numpy())
+        assert np.array_equal(w_out.cpu().numpy().view(np.uint32), a.view(np.uint32))
+        assert np.array_equal(b_out.cpu().numpy().view(np.uint32), c.view(np.uint32))
+        w2 = w.clone()
+        qb.qv2_bn_fold(w2, ch, inner, gamma, var, w2)                     # in place, no bias
+        torch.cuda.synchronize()
+        assert torch.equal(w2, w_out)
+    it = H.Item("folded", w_out, C, 512)
+    H.check_all([it], H.run_gpu([it]))
+
+
 def test_cross_kernel_pair_of_dequantized_equals_fakequant_error():
     """pair(x, dequant(codes)) must reproduce the fake-quant pass's own noise energy."""
     x = torch.relu(_rand(300_000, 15, 1.5))

@@ -316,3 +316,20 @@ def test_histogram_host_checks():
     assert L.qv2_histogram(p.handle, FAKE, 1, FAKE, None, FAKE, ws, None) == qb.QV2_ERR_SHAPE
     assert L.qv2_histogram(p.handle, FAKE, 2048, FAKE, None, FAKE, ws - 1, None) == qb.QV2_ERR_WORKSPACE
     assert L.qv2_histogram(p.handle, FAKE, 2048, FAKE + 4, None, FAKE, ws, None) == qb.QV2_ERR_ALIGN
+
+
+def test_regroup_for_fusion_matches_oracle():
+    rng = np.random.default_rng(51)
+    for _ in range(300):
+        n = int(rng.integers(1, 130))
+        o = rng.permutation(n)
+        g = rng.integers(0, max(1, n // 3), n)
+        assert qb.qv2_regroup_for_fusion(o, g).tolist() == orc.regroup_for_fusion(o.tolist(), g.tolist())
+    assert qb.qv2_regroup_for_fusion([4, 1, 5, 0, 3, 2], [7, 7, 8, 8, 9, 10]).tolist() == [4, 1, 0, 5, 3, 2]
+    with pytest.raises(qb.QV2Error) as e:
+        qb.qv2_regroup_for_fusion([0, 0, 1], [1, 1, 1])
+    assert e.value.status == qb.QV2_ERR_SHAPE
+    L = qb.lib()
+    assert L.qv2_bn_fold(None, 4, 9, FAKE, FAKE, None, None, None, FAKE, None, None) == qb.QV2_ERR_NULL
+    assert L.qv2_bn_fold(FAKE, 0, 9, FAKE, FAKE, None, None, None, FAKE, None, None) == qb.QV2_ERR_SHAPE
+    assert L.qv2_bn_fold(FAKE, 4, 9, FAKE, FAKE, None, None, None, FAKE, FAKE, None) == qb.QV2_ERR_NULL

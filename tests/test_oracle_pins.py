@@ -552,3 +552,59 @@ def test_kl_divergence_pins():
         (2 / 6) * math.log((2 / 6) / (1 / 6)) + (4 / 6) * math.log((4 / 6) / (5 / 6)), rel=1e-14)
     with pytest.raises(ValueError):
         orc.kl_divergence([1, 2], [1, 2, 3])
+
+
+# ----------------------------------------------------------------------------
+# conv + BN folding (Sec. 6.3 Eq. 10-12) and fusion-aware regrouping (Sec. 6.5)
+# ----------------------------------------------------------------------------
+def test_bn_fold_pins():
+    rng = np.random.default_rng(17)
+    w = rng.standard_normal((6, 3, 3, 3)).astype(np.float32)
+    gamma = rng.uniform(0.5, 1.5, 6).astype(np.float32)
+    var = rng.uniform(0.1, 4.0, 6).astype(np.float32)
+    mean = rng.standard_normal(6).astype(np.float32)
+    beta = rng.standard_normal(6).astype(np.float32)
+    bias = rng.standard_normal(6).astype(np.float32)
+    a, c = orc.bn_fold(w, gamma, var, mean, beta, bias)
+    # the folded layer computes the same output as conv followed by BN (Eq. 10 vs Eq. 11)
+    x = rng.standard_normal(27)
+    for ch in range(6):
+        conv = float(w[ch].reshape(-1).astype(np.float64) @ x) + float(bias[ch])
+        bn = float(gamma[ch]) * (conv - float(mean[ch])) / math.sqrt(float(var[ch])) + float(beta[ch])
+        fused = float(a[ch].reshape(-1).astype(np.float64) @ x) + float(c[ch])
+        assert fused == pytest.approx(bn, rel=2e-6, abs=2e-6)
+    # closed forms: gamma 2, var 4 -> factor exactly 1; gamma 1, var 0.25 -> factor 2
+    one = np.ones(3, np.float32)
+    a, c = orc.bn_fold(w[:3], 2 * one, 4 * one, 0 * one, 0 * one)
+    assert np.array_equal(a, w[:3]) and np.array_equal(c, 0 * one)
+    a, c = orc.bn_fold(w[:3], one, 0.25 * one, one, 3 * one, bias=2 * one)
+    assert np.array_equal(a, 2 * w[:3]) and c.tolist() == [5.0, 5.0, 5.0]      # 2 * (2 - 1) + 3
+
+
+def test_regroup_for_fusion():
+    order = [4, 1, 5, 0, 3, 2]
+    # singleton groups: nothing moves
+    assert orc.regroup_for_fusion(order, [0, 1, 2, 3, 4, 5]) == order
+    # layers 0 and 1 fuse, 2 and 3 fuse: a block sits where its most sensitive member was
+    assert orc.regroup_for_fusion(order, [7, 7, 8, 8, 9, 10]) == [4, 1, 0, 5, 3, 2]
+    assert orc.regroup_for_fusion(order, [0, 0, 0, 0, 0, 0]) == order
+    rng = np.random.default_rng(18)
+    for _ in range(200):
+        n = int(rng.integers(1, 40))
+        o = list(rng.permutation(n))
+        g = list(rng.integers(0, max(1, n // 2), n))
+        out = orc.regroup_for_fusion(o, g)
+        assert sorted(out) == list(range(n))
+        firsts = []
+        for l in o:
+            if g[l] not in firsts:
+                firsts.append(g[l])
+        blocks = []
+        for l in out:                                   # groups are contiguous, in first-seen order
+            if not blocks or blocks[-1] != g[l]:
+                blocks.append(g[l])
+        assert blocks == firsts
+        for gid in firsts:                              # list order kept inside a block
+            assert [l for l in out if g[l] == gid] == [l for l in o if g[l] == gid]
+    with pytest.raises(ValueError):
+        orc.regroup_for_fusion([0, 0], [1, 1])
