@@ -140,8 +140,8 @@ def main():
     w_layer = np.array([specs[t].layer for t in w_idx])
     a_layer = np.array([specs[t].layer for t in a_idx])
     # pinned host mirrors of the small result records
-    h_params = torch.empty(buf.params.shape, dtype=torch.uint8, pin_memory=True)
-    h_sums = torch.empty(buf.sums.shape, dtype=torch.uint8, pin_memory=True)
+    d_tsums = torch.zeros(plan.num_tensors * qb.TENSOR_SUMS.itemsize, dtype=torch.uint8, device=dev)
+    h_tsums = torch.empty(d_tsums.shape, dtype=torch.uint8, pin_memory=True)
     h_pair = torch.empty(buf.pair.shape, dtype=torch.uint8, pin_memory=True)
     last = {}
 
@@ -160,14 +160,15 @@ def main():
             qb.qv2_pair_metrics(plan, buf.pair, buf.workspace)
         if events:
             events[3].record()
-        h_params.copy_(buf.params, non_blocking=True)
-        h_sums.copy_(buf.sums, non_blocking=True)
+        # per-tensor records are folded on the device: a few KB go to the host, not every segment
+        qb.qv2_tensor_sums_fold(plan, buf.params, buf.sums, d_tsums)
+        h_tsums.copy_(d_tsums, non_blocking=True)
         h_pair.copy_(buf.pair, non_blocking=True)
         torch.cuda.current_stream().synchronize()
         if events:       # per-kernel durations from the library's HIP events on the same stream
             for name in kernel_ms:
                 kernel_ms[name].append(qb.qv2_plan_kernel_ms(plan, name))
-        met = qb.qv2_finalize(plan, h_params.numpy().view(qb.QPARAMS), h_sums.numpy().view(qb.SUMS))
+        met = qb.qv2_finalize_tensors(h_tsums.numpy().view(qb.TENSOR_SUMS))
         pmse, psqnr = qb.qv2_pair_finalize(h_pair.numpy().view(qb.PAIR_SUMS))
         w_sqnr = np.empty(n_layers); w_mse = np.empty(n_layers)
         a_sqnr = np.empty(n_layers); a_mse = np.empty(n_layers)

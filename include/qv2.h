@@ -106,6 +106,15 @@ typedef struct {
   int64_t _pad;
 } qv2_pair_sums;
 
+/* Per tensor: the per-segment records of a tensor folded on the device, so that a caller who
+ * only needs per-tensor metrics copies a few KB to the host instead of every segment. */
+typedef struct {
+  double sum_x, sum_x2, sum_e2;
+  int64_t n;
+  float min, max;
+  int32_t _pad[2];
+} qv2_tensor_sums;
+
 /* Per tensor, host, fp64. */
 typedef struct {
   double mse;              /* Eq. 7: sum_e2 / numel                               */
@@ -243,6 +252,12 @@ qv2_status qv2_bn_fold(const float* d_w, int32_t channels, int64_t inner, const 
                        const float* d_var, const float* d_bias, const float* d_mean,
                        const float* d_beta, float* d_w_out, float* d_bias_out, void* hip_stream);
 
+/* Folds the per-segment params / sums of every tensor into one record per tensor (sums of
+ * the channels' sums, min / max over channels) in a fixed order.
+ * d_params, d_sums: DEVICE, read; d_tensor_sums[num_tensors]: DEVICE, written. */
+qv2_status qv2_tensor_sums_fold(qv2_plan* plan, const qv2_qparams* d_params, const qv2_sums* d_sums,
+                                qv2_tensor_sums* d_tensor_sums, void* hip_stream);
+
 /* ---- host finalize and ranking (need no GPU) ----------------------------- */
 
 /* Eq. 6-7 and the tensor statistics from host copies of params and sums; a
@@ -251,6 +266,10 @@ qv2_status qv2_bn_fold(const float* d_w, int32_t channels, int64_t inner, const 
  * written). */
 qv2_status qv2_finalize(const qv2_plan* plan, const qv2_qparams* h_params,
                         const qv2_sums* h_sums, qv2_metrics* h_out);
+
+/* qv2_finalize from host copies of per-tensor records (qv2_tensor_sums_fold). */
+qv2_status qv2_finalize_tensors(const qv2_tensor_sums* h_tensor_sums, int32_t n_tensors,
+                                qv2_metrics* h_out);
 
 /* MSE and SQNR (dB) of n pair-sum records; entries with n == 0 give 0 and +inf. */
 qv2_status qv2_pair_finalize(const qv2_pair_sums* h_pair, int32_t n,

@@ -29,7 +29,8 @@ EXPORTS = (
     "qv2_workspace_bytes", "qv2_calibrate", "qv2_fakequant_metrics", "qv2_pair_metrics",
     "qv2_fakequant_pair_metrics", "qv2_fakequant_pair_metrics_cos", "qv2_cosine_finalize",
     "qv2_plan_set_timing", "qv2_plan_kernel_ms", "qv2_histogram_workspace_bytes", "qv2_histogram",
-    "qv2_kl_divergence", "qv2_bn_fold", "qv2_regroup_for_fusion",
+    "qv2_kl_divergence", "qv2_bn_fold", "qv2_regroup_for_fusion", "qv2_tensor_sums_fold",
+    "qv2_finalize_tensors",
     "qv2_finalize", "qv2_pair_finalize", "qv2_rank_config_default", "qv2_rank",
     "qv2_baseline_order", "qv2_bops_reduction_pct", "qv2_bops_select",
     "qv2_status_string",
@@ -55,6 +56,9 @@ SUMS = np.dtype([("sum_x", "<f8"), ("sum_x2", "<f8"), ("sum_e2", "<f8"), ("n", "
 PAIR_SUMS = np.dtype([("sum_ref2", "<f8"), ("sum_d2", "<f8"), ("n", "<i8"), ("_pad", "<i8")])
 METRICS = np.dtype([("mse", "<f8"), ("sqnr_db", "<f8"), ("mean", "<f8"), ("var", "<f8"),
                     ("absmax", "<f4"), ("min", "<f4"), ("max", "<f4"), ("_pad", "<i4")])
+TENSOR_SUMS = np.dtype([("sum_x", "<f8"), ("sum_x2", "<f8"), ("sum_e2", "<f8"), ("n", "<i8"),
+                        ("min", "<f4"), ("max", "<f4"), ("_pad", "<i4", (2,))])
+assert TENSOR_SUMS.itemsize == 48
 assert QPARAMS.itemsize == 24 and SUMS.itemsize == 32 and PAIR_SUMS.itemsize == 32
 assert METRICS.itemsize == 48
 
@@ -103,6 +107,8 @@ def lib():
         L.qv2_kl_divergence.argtypes = [vp, vp, i32, ctypes.c_double, vp]
         L.qv2_bn_fold.argtypes = [vp, i32, i64, vp, vp, vp, vp, vp, vp, vp, vp]
         L.qv2_regroup_for_fusion.argtypes = [vp, vp, i32, vp]
+        L.qv2_tensor_sums_fold.argtypes = [vp, vp, vp, vp, vp]
+        L.qv2_finalize_tensors.argtypes = [vp, i32, vp]
         L.qv2_plan_set_timing.argtypes = [vp, i32]
         L.qv2_plan_kernel_ms.argtypes = [vp, i32, ctypes.POINTER(ctypes.c_float)]
         L.qv2_finalize.argtypes = [vp, vp, vp, vp]
@@ -306,6 +312,20 @@ def qv2_regroup_for_fusion(order, group_id) -> np.ndarray:
     _check(lib().qv2_regroup_for_fusion(o.ctypes.data, g.ctypes.data, len(o), out.ctypes.data),
            "qv2_regroup_for_fusion")
     return out[:len(o)]
+
+
+def qv2_tensor_sums_fold(plan: Plan, d_params, d_sums, d_tensor_sums, stream=None):
+    _check(lib().qv2_tensor_sums_fold(plan.handle, _ptr(d_params), _ptr(d_sums), _ptr(d_tensor_sums),
+                                      _stream(stream)), "qv2_tensor_sums_fold")
+
+
+def qv2_finalize_tensors(h_tensor_sums: np.ndarray, strict: bool = True) -> np.ndarray:
+    ht = np.ascontiguousarray(h_tensor_sums, dtype=TENSOR_SUMS)
+    out = np.zeros(ht.size, dtype=METRICS)
+    st = lib().qv2_finalize_tensors(ht.ctypes.data, ht.size, out.ctypes.data)
+    if st != QV2_OK and (strict or st != QV2_ERR_NONFINITE):
+        raise QV2Error(st, "qv2_finalize_tensors")
+    return out
 
 
 def qv2_finalize(plan: Plan, h_params: np.ndarray, h_sums: np.ndarray, strict: bool = True) -> np.ndarray:

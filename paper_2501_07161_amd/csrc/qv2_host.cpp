@@ -246,6 +246,25 @@ qv2_status qv2_finalize(const qv2_plan* plan, const qv2_qparams* h_params,
   return finite ? QV2_OK : QV2_ERR_NONFINITE;
 }
 
+qv2_status qv2_finalize_tensors(const qv2_tensor_sums* h, int32_t n_tensors, qv2_metrics* h_out) {
+  if (!h || !h_out) return QV2_ERR_NULL;
+  if (n_tensors < 0) return QV2_ERR_SHAPE;
+  bool finite = true;
+  for (int32_t t = 0; t < n_tensors; ++t) {
+    finite = finite && std::isfinite(h[t].sum_x) && std::isfinite(h[t].sum_x2) && std::isfinite(h[t].sum_e2);
+    const double n = static_cast<double>(h[t].n);
+    qv2_metrics m{};
+    m.mse = h[t].sum_e2 / n;
+    m.sqnr_db = sqnr_db_of(h[t].sum_x2, h[t].sum_e2);
+    m.mean = h[t].sum_x / n;
+    m.var = std::max(0.0, h[t].sum_x2 / n - m.mean * m.mean);
+    m.min = h[t].min; m.max = h[t].max;
+    m.absmax = std::max(std::fabs(h[t].min), std::fabs(h[t].max));
+    h_out[t] = m;
+  }
+  return finite ? QV2_OK : QV2_ERR_NONFINITE;
+}
+
 qv2_status qv2_pair_finalize(const qv2_pair_sums* h_pair, int32_t n, double* h_mse,
                              double* h_sqnr_db) {
   if (!h_pair || !h_mse || !h_sqnr_db) return QV2_ERR_NULL;

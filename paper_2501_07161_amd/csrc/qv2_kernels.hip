@@ -820,6 +820,34 @@ __global__ __launch_bounds__(256) void k_hist_fold(const HistTensor* __restrict_
   if (hist_q) hist_q[static_cast<size_t>(t) * nbins + i] = b;
 }
 
+// Per-tensor fold of the per-segment results: one wavefront per tensor.
+__global__ __launch_bounds__(256) void k_tensor_fold(const HistTensor* __restrict__ ht, int n,
+                                                     const qv2_qparams* __restrict__ params,
+                                                     const qv2_sums* __restrict__ sums,
+                                                     qv2_tensor_sums* __restrict__ out) {
+  const int t = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & (kWave - 1);
+  if (t >= n) return;
+  const HistTensor h = ht[t];
+  float mn = INFINITY, mx = -INFINITY;
+  double sx = 0.0, sx2 = 0.0, se2 = 0.0;
+  long long cnt = 0;
+  for (int i = lane; i < h.nseg; i += kWave) {
+    const qv2_qparams p = params[h.seg0 + i];
+    const qv2_sums u = sums[h.seg0 + i];
+    mn = fminf(mn, p.min); mx = fmaxf(mx, p.max);
+    sx += u.sum_x; sx2 += u.sum_x2; se2 += u.sum_e2; cnt += u.n;
+  }
+  mn = group_min(mn, kWave); mx = group_max(mx, kWave);
+  sx = group_sum(sx, kWave); sx2 = group_sum(sx2, kWave); se2 = group_sum(se2, kWave);
+  for (int o = kWave >> 1; o > 0; o >>= 1) cnt += __shfl_xor(cnt, o);
+  if (lane == 0) {
+    qv2_tensor_sums o;
+    o.sum_x = sx; o.sum_x2 = sx2; o.sum_e2 = se2; o.n = cnt; o.min = mn; o.max = mx;
+    o._pad[0] = o._pad[1] = 0;
+    out[t] = o;
+  }
+}
+
 // ---------------------------------------------------------------------------
 // conv + BN folding (Sec. 6.3 Eq. 12): A = (gamma / sqrt(var)) * W per output channel,
 // C = (gamma / sqrt(var)) * (B - mu) + beta.  One workgroup column per channel.
@@ -1094,6 +1122,18 @@ qv2_status qv2_fakequant_pair_metrics_cos(qv2_plan* plan, const qv2_qparams* d_p
   ErrPartial5* parts = static_cast<ErrPartial5*>(d_workspace);
   launch_quant<true, true>(plan, d_params, d_sums, parts, d_seg_xxhat, s);
   launch_fused_pair_fold(plan, parts, d_pair_sums, d_pair_xq, s);
+  return launch_status();
+}
+
+qv2_status qv2_tensor_sums_fold(qv2_plan* plan, const qv2_qparams* d_params, const qv2_sums* d_sums,
+                                qv2_tensor_sums* d_tensor_sums, void* hip_stream) {
+  if (!plan || !d_params || !d_sums || !d_tensor_sums) return QV2_ERR_NULL;
+  if (reinterpret_cast<uintptr_t>(d_tensor_sums) & 7u) return QV2_ERR_ALIGN;
+  qv2_status st = ensure_uploaded(plan);
+  if (st != QV2_OK) return st;
+  const int nt = static_cast<int>(plan->info.size());
+  hipLaunchKernelGGL(k_tensor_fold, dim3(fold_grid(nt)), dim3(256), 0, static_cast<hipStream_t>(hip_stream),
+                     plan->d_hist_tensors, nt, d_params, d_sums, d_tensor_sums);
   return launch_status();
 }
 

@@ -123,9 +123,21 @@ def run_gpu(items: List[Item], params_override: Optional[np.ndarray] = None,
     else:
         qb.qv2_fakequant_metrics(plan, buf.params, buf.sums, buf.workspace)
         qb.qv2_pair_metrics(plan, buf.pair, buf.workspace)
+    tsums = torch.zeros(plan.num_tensors * qb.TENSOR_SUMS.itemsize, dtype=torch.uint8, device=dev)
+    qb.qv2_tensor_sums_fold(plan, buf.params, buf.sums, tsums)
     torch.cuda.synchronize()
     params, sums, pair = buf.host()
     metrics = qb.qv2_finalize(plan, params, sums, strict=False)
+    # the device-side per-tensor fold gives the same metrics (channel sums in another order)
+    m2 = qb.qv2_finalize_tensors(tsums.cpu().numpy().view(qb.TENSOR_SUMS), strict=False)
+    for f, rt in (("mse", 1e-12), ("mean", 1e-9), ("var", 1e-8)):
+        assert np.allclose(m2[f], metrics[f], rtol=rt, atol=1e-300, equal_nan=True), f
+    with np.errstate(invalid="ignore"):
+        same = (m2["sqnr_db"] == metrics["sqnr_db"]) | (np.abs(m2["sqnr_db"] - metrics["sqnr_db"]) <= 1e-9) | \
+               (np.isnan(m2["sqnr_db"]) & np.isnan(metrics["sqnr_db"]))
+    assert np.all(same)
+    for f in ("min", "max", "absmax"):
+        assert np.array_equal(m2[f], metrics[f], equal_nan=True), f
     pm, ps = qb.qv2_pair_finalize(pair)
     res = GpuResult(plan, params, sums, pair, metrics, pm, ps)
     res.buffers = buf
