@@ -36,3 +36,23 @@ def test_resnet50_batch256_full_pass():
     assert all(torch.equal(a, it.codes) for a, it in zip(codes, items))
     del items
     torch.cuda.empty_cache()
+
+
+@pytest.mark.timeout(900)
+def test_single_tensor_beyond_int32_elements():
+    """One activation of 2^31 + 4099 elements (8.6 GB) with its quantized-run partner: element
+    offsets, tile counts and segment lengths no longer fit 32 bits.  All codes bit-exact."""
+    n = (1 << 31) + 4099
+    spec = synth.TensorSpec("huge_act", (n,), synth.ACTIVATION, 0, synth.ASYM_TENSOR, 9001, "relu_normal",
+                            sigma=1.3, has_pair=True)
+    items = H.items_from_specs([spec], "cuda")
+    print("oracle: calibrate + fake-quant + partner ...", flush=True)
+    H.attach_pairs(items, [spec])
+    for fused in (False, True):
+        print(f"gpu pass (fused={fused}) ...", flush=True)
+        res = H.run_gpu(items, fused=fused)
+        assert int(res.sums["n"][0]) == n
+        print("compare ...", flush=True)
+        H.check_item(0, items[0], res)
+    del items
+    torch.cuda.empty_cache()
