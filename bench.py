@@ -3,9 +3,9 @@
 
 One step = one pass of the whole hot path over the layer table: calibrate
 (min/max, statistics, scale, zero-point) -> fake-quantize (int8 codes, error
-energies) -> pair metrics (fp32-run vs quantized-run activations) -> copy the
-per-segment records to the host -> finalize (MSE, SQNR, mean, var) -> SQNR
-delta and ranking.  Inputs are synthetic, seeded, and resident in HBM before
+energies) -> pair metrics (fp32-run vs quantized-run activations) -> fold the
+segment records to one per tensor on the device and copy those few KB to the
+host -> finalize (MSE, SQNR, mean, var) -> SQNR delta and ranking.  Inputs are synthetic, seeded, and resident in HBM before
 the timed region starts.
 
 Workload at N=1: ResNet-50 v1 shapes, batch 256, 224x224 (54 weights,
@@ -15,8 +15,10 @@ per-tensor asymmetric).
 Prints ONE JSON line.  `value` is algorithmic bytes per pass / time per pass with
 the fixed per-call numerators: 4 B/element for calibrate, 5 for fake-quant (4 read
 + 1 code written), 8 for the pair metrics, i.e. 9 B per weight element and 17 B
-per activation element.  The default pass uses the fused fake-quant + pair call,
-which computes the same results while moving 13 B per activation element; the
+per activation element.  The default pass is the single call
+qv2_calibrate_fakequant_pair_metrics, which computes the same results while moving
+13 B per activation element (fake-quant and pair comparison share one visit of x)
+and 5 B per element of the per-channel weights (read once, staged in LDS); the
 JSON also carries `hbm_GBps` (bytes the pass actually has to move / time) and the
 timing of the pass made of the three separate calls.
 """
@@ -33,7 +35,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0   # MI355X published HBM3E bandwidth
-ROCPROF_NAMES = {"k_quantpair_stream": "k_quant_stream<256, 2, true>", "k_pair_stream": "k_pair_stream<512, 4>"}
+ROCPROF_NAMES = {"k_quantpair_stream": "k_quant_stream<256, 2, true, false>", "k_pair_stream": "k_pair_stream<512, 4>"}
 
 # HBM bytes per launch of the dominant kernel on the resnet50 b256 workload from rocprofv3
 # --pmc (FETCH_SIZE and WRITE_SIZE runs, each scaled by a copy kernel of known size); see
@@ -49,8 +51,9 @@ def parse():
     ap.add_argument("--workload", default="resnet50", choices=["resnet50", "resnet18", "vgg16", "mobilenetv2"])
     ap.add_argument("--batch", type=int, default=None, help="override the workload's batch (smaller = not the headline config)")
     ap.add_argument("--fused", action="store_true", help="BN-folded weight variant of resnet50")
-    ap.add_argument("--mode", default="fused", choices=["fused", "calls"],
-                    help="fused: calibrate + fused fake-quant/pair call (default); "
+    ap.add_argument("--mode", default="single", choices=["single", "fused", "calls"],
+                    help="single: the one call that calibrates, fake-quantizes and compares with the "
+                         "quantized run (default); fused: calibrate + fused fake-quant/pair call; "
                          "calls: calibrate, fake-quant and pair as three calls")
     ap.add_argument("--single-mode", action="store_true", help="do not also time the other mode")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -148,10 +151,15 @@ def main():
     def step(mode, events=None):
         if events:
             events[0].record()
-        qb.qv2_calibrate(plan, buf.params, buf.sums, buf.workspace)
+        if mode == "single":
+            qb.qv2_calibrate_fakequant_pair_metrics(plan, buf.params, buf.sums, buf.pair, buf.workspace)
+        else:
+            qb.qv2_calibrate(plan, buf.params, buf.sums, buf.workspace)
         if events:
             events[1].record()
-        if mode == "fused":
+        if mode == "single":
+            pass
+        elif mode == "fused":
             qb.qv2_fakequant_pair_metrics(plan, buf.params, buf.sums, buf.pair, buf.workspace)
         else:
             qb.qv2_fakequant_metrics(plan, buf.params, buf.sums, buf.workspace)
@@ -183,8 +191,9 @@ def main():
     def timed(mode):
         ev = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
         kernel_ms.clear()
-        names = ["k_stats_stream", "k_stats_rows"] + (["k_quantpair_stream", "k_quantpair_rows"] if mode == "fused"
-                                                      else ["k_quant_stream", "k_quant_rows", "k_pair_stream"])
+        names = {"single": ["k_stats_stream", "k_quantpair_stream", "k_single_read_rows"],
+                 "fused": ["k_stats_stream", "k_stats_rows", "k_quantpair_stream", "k_quantpair_rows"],
+                 "calls": ["k_stats_stream", "k_stats_rows", "k_quant_stream", "k_quant_rows", "k_pair_stream"]}[mode]
         kernel_ms.update({n: [] for n in names})
         for _ in range(args.warmup):
             step(mode)
@@ -197,7 +206,9 @@ def main():
         r = {"ms_per_step": dt / args.steps * 1e3, "order": last["order"].tolist(),
              "kernels_ms": {n: round(float(np.mean(v)), 4) for n, v in kernel_ms.items()},
              "ms_cal": float(np.mean([e[0].elapsed_time(e[1]) for e in ev]))}
-        if mode == "fused":
+        if mode == "single":
+            r["ms_single"] = r.pop("ms_cal")
+        elif mode == "fused":
             r["ms_fqpair"] = float(np.mean([e[1].elapsed_time(e[3]) for e in ev]))
         else:
             r["ms_fq"] = float(np.mean([e[1].elapsed_time(e[2]) for e in ev]))
@@ -205,7 +216,8 @@ def main():
         return r
 
     main_r = timed(args.mode)
-    other = None if args.single_mode else timed("calls" if args.mode == "fused" else "fused")
+    other_mode = "fused" if args.mode == "calls" else "calls"
+    other = None if args.single_mode else timed(other_mode)
 
     # optional metrics outside the headline pass (the paper's other candidate local metrics)
     extras = {}
@@ -242,10 +254,16 @@ def main():
     value = bytes_pass / (ms_per_step * 1e-3) / 1e9
     # bytes the executed pass has to move: the fused call reads x once for steps a3 + a4
     bytes_fqpair = 5 * n_all + 4 * n_pair
-    moved = bytes_cal + (bytes_fqpair if args.mode == "fused" else bytes_fq + bytes_pair)
+    # ... and the single call reads the tensors made of short channels once for a1 + a3 too
+    bytes_single = bytes_cal + bytes_fqpair - 4 * n_rowgroup
+    moved_of = {"single": bytes_single, "fused": bytes_cal + bytes_fqpair, "calls": bytes_cal + bytes_fq + bytes_pair}
+    moved = moved_of[args.mode]
     headline = args.workload == "resnet50" and batch == 256 and not args.fused
 
     def calls_of(r):
+        if "ms_single" in r:
+            return {"calibrate_fakequant_pair_metrics": {"ms": round(r["ms_single"], 4), "moved_bytes": bytes_single,
+                                                         "GBps": round(bytes_single / r["ms_single"] / 1e6, 1)}}
         c = {"calibrate": {"ms": round(r["ms_cal"], 4), "GBps": round(bytes_cal / r["ms_cal"] / 1e6, 1)}}
         if "ms_fqpair" in r:
             c["fakequant_pair_metrics"] = {"ms": round(r["ms_fqpair"], 4), "moved_bytes": bytes_fqpair,
@@ -256,7 +274,7 @@ def main():
         return c
 
     # dominant kernel: its own algorithmic bytes over its own HIP-event duration
-    if args.mode == "fused":
+    if args.mode in ("single", "fused"):
         kname, kbytes = "k_quantpair_stream", bytes_fqpair - 5 * n_rowgroup
     else:
         kname, kbytes = "k_pair_stream", bytes_pair
@@ -269,8 +287,9 @@ def main():
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"{args.workload}_b{batch}" + ("_bnfold" if args.fused else ""),
-                   "pass": "calibrate + fused fakequant/pair + finalize + rank" if args.mode == "fused"
-                           else "calibrate + fakequant + pair + finalize + rank",
+                   "pass": {"single": "calibrate/fakequant/pair in one call + finalize + rank",
+                            "fused": "calibrate + fused fakequant/pair + finalize + rank",
+                            "calls": "calibrate + fakequant + pair + finalize + rank"}[args.mode],
                    "tensors": len(specs), "layers": n_layers, "weight_elements": n_w,
                    "activation_elements": n_a, "algorithmic_bytes_per_pass": bytes_pass,
                    "moved_bytes_per_pass": moved},
@@ -293,8 +312,8 @@ def main():
     if extras:
         out["extras"] = extras
     if other is not None:
-        o_bytes = bytes_cal + (bytes_fq + bytes_pair if args.mode == "fused" else bytes_fqpair)
-        out["other_pass"] = {"pass": "three separate calls" if args.mode == "fused" else "fused",
+        o_bytes = moved_of[other_mode]
+        out["other_pass"] = {"pass": "three separate calls" if other_mode == "calls" else "calibrate + fused call",
                              "ms_per_step": round(other["ms_per_step"], 4),
                              "value": round(bytes_pass / other["ms_per_step"] / 1e6, 2),
                              "hbm_GBps": round(o_bytes / other["ms_per_step"] / 1e6, 2),

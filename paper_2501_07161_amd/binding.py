@@ -27,7 +27,7 @@ EXPORTS = (
     "qv2_plan_segment_begin", "qv2_plan_num_tiles", "qv2_plan_num_quant_tiles",
     "qv2_plan_num_pair_tiles",
     "qv2_workspace_bytes", "qv2_calibrate", "qv2_fakequant_metrics", "qv2_pair_metrics",
-    "qv2_fakequant_pair_metrics", "qv2_fakequant_pair_metrics_cos", "qv2_cosine_finalize",
+    "qv2_fakequant_pair_metrics", "qv2_calibrate_fakequant_pair_metrics", "qv2_fakequant_pair_metrics_cos", "qv2_cosine_finalize",
     "qv2_plan_set_timing", "qv2_plan_kernel_ms", "qv2_histogram_workspace_bytes", "qv2_histogram",
     "qv2_kl_divergence", "qv2_bn_fold", "qv2_regroup_for_fusion", "qv2_tensor_sums_fold",
     "qv2_finalize_tensors",
@@ -99,6 +99,7 @@ def lib():
         L.qv2_fakequant_metrics.argtypes = [vp, vp, vp, vp, sz, vp]
         L.qv2_pair_metrics.argtypes = [vp, vp, vp, sz, vp]
         L.qv2_fakequant_pair_metrics.argtypes = [vp, vp, vp, vp, vp, sz, vp]
+        L.qv2_calibrate_fakequant_pair_metrics.argtypes = [vp, vp, vp, vp, vp, sz, vp]
         L.qv2_fakequant_pair_metrics_cos.argtypes = [vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.qv2_cosine_finalize.argtypes = [vp, vp, vp, vp, vp, vp, vp]
         L.qv2_histogram_workspace_bytes.argtypes = [vp, i32]
@@ -203,7 +204,8 @@ def qv2_plan_create(rows: Sequence[TensorArg]) -> Plan:
 
 
 KERNEL_IDS = {"k_stats_stream": 0, "k_stats_rows": 1, "k_quant_stream": 2, "k_quant_rows": 3,
-              "k_pair_stream": 4, "k_quantpair_stream": 5, "k_quantpair_rows": 6, "k_hist": 7}
+              "k_pair_stream": 4, "k_quantpair_stream": 5, "k_quantpair_rows": 6, "k_hist": 7,
+              "k_single_read_rows": 8}
 
 
 def qv2_plan_set_timing(plan: Plan, enable: bool):
@@ -246,6 +248,15 @@ def qv2_fakequant_pair_metrics(plan: Plan, d_params, d_sums, d_pair_sums, d_work
     _check(lib().qv2_fakequant_pair_metrics(plan.handle, _ptr(d_params), _ptr(d_sums), _ptr(d_pair_sums),
                                             _ptr(d_workspace), wb, _stream(stream)),
            "qv2_fakequant_pair_metrics")
+
+
+def qv2_calibrate_fakequant_pair_metrics(plan: Plan, d_params, d_sums, d_pair_sums, d_workspace,
+                                         workspace_bytes=None, stream=None):
+    """d_pair_sums may be None (no comparison with qrun)."""
+    wb = workspace_bytes if workspace_bytes is not None else d_workspace.numel() * d_workspace.element_size()
+    _check(lib().qv2_calibrate_fakequant_pair_metrics(
+        plan.handle, _ptr(d_params), _ptr(d_sums), _ptr(d_pair_sums) if d_pair_sums is not None else None,
+        _ptr(d_workspace), wb, _stream(stream)), "qv2_calibrate_fakequant_pair_metrics")
 
 
 def qv2_fakequant_pair_metrics_cos(plan: Plan, d_params, d_sums, d_pair_sums, d_seg_xxhat, d_pair_xq,

@@ -64,6 +64,7 @@ qv2_status qv2_plan_create(const qv2_tensor* h_tensors, int32_t n_tensors, qv2_p
   p->read_tile = tile_from_env("QV2_TILE_ELEMS", qv2::kDefaultReadTile);
   p->quant_tile = tile_from_env("QV2_QUANT_TILE_ELEMS", qv2::kDefaultQuantTile);
   const int64_t TR = p->read_tile, TQ = p->quant_tile;
+  p->n_row_parts = static_cast<int32_t>(n_row_parts);
 
   int64_t row_part = 0;                      // next row-group partial (same in both numberings)
   int64_t sp = n_row_parts, ep = n_row_parts, pp = 0;   // next stream partial: stats / quantize / pair

@@ -117,6 +117,7 @@ struct qv2_plan {
   std::vector<int32_t> big_fused_pair_tensors;
   int32_t read_tile = qv2::kDefaultReadTile;
   int32_t quant_tile = qv2::kDefaultQuantTile;
+  int32_t n_row_parts = 0;               // partial slots 0 .. n_row_parts-1 belong to row-group segments
   size_t workspace_bytes = 0;
 
   // device copy (made by the first device call, on the device current then)

@@ -285,37 +285,108 @@ __device__ __forceinline__ int row_width(int inner) {
   return w;
 }
 
+// How the lanes of a workgroup of W wavefronts share the rows of a row-group tile.
+//  plain: w lanes of one wavefront per row, 64 / w rows per wavefront at a time, the
+//         wavefronts take rounds of rows;
+//  split: a tile of at most W / 2 (long) rows gives every row `wpr` whole wavefronts, whose
+//         partial results are joined through LDS in wavefront order; one round.
+// `rounds` is the same for every thread, so the loop over rounds may hold barriers.
+struct RowMap {
+  int w;        // lanes of a wavefront that share a row (width of the shuffle reductions)
+  int stride;   // lanes that share a row in all
+  int gl;       // index of this lane among them
+  int row0;     // row of this lane in round 0
+  int step;     // rows per round
+  int rounds;
+  int wpr;      // wavefronts per row (1 = plain)
+  int part;     // index of this wavefront among the wpr of its row
+};
+
+template <int W>
+__device__ __forceinline__ RowMap row_map(int rows, int inner) {
+  const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
+  RowMap m;
+  if (rows * 2 <= W) {
+    int wpr = W;
+    while (wpr * rows > W) wpr >>= 1;
+    m.w = kWave; m.stride = kWave * wpr; m.wpr = wpr; m.part = wave % wpr;
+    m.gl = m.part * kWave + lane; m.row0 = wave / wpr; m.step = W / wpr; m.rounds = 1;
+  } else {
+    const int w = row_width(inner), gpw = kWave / w;
+    m.w = w; m.stride = w; m.wpr = 1; m.part = 0;
+    m.gl = lane & (w - 1); m.row0 = wave * gpw + (lane >> __builtin_ctz(w)); m.step = W * gpw;
+    m.rounds = (rows + m.step - 1) / m.step;
+  }
+  return m;
+}
+
+// Range and sums of one row over the lanes that share it; the results are valid in all of
+// them.  N sums; RANGE = false skips mn / mx.  sf / sd: LDS exchange areas of the split
+// form, [2][W] and [N][W].  Every butterfly step moves all values before it combines them,
+// so the steps of the different values overlap instead of forming one long dependent chain.
+template <int W, int N, bool RANGE>
+__device__ __forceinline__ void row_join(const RowMap& m, float& mn, float& mx, double (&v)[N],
+                                         float (*sf)[W], double (*sd)[W]) {
+  for (int o = m.w >> 1; o > 0; o >>= 1) {
+    float a = 0.0f, b = 0.0f;
+    double t[N];
+    if (RANGE) { a = __shfl_xor(mn, o); b = __shfl_xor(mx, o); }
+#pragma unroll
+    for (int k = 0; k < N; ++k) t[k] = __shfl_xor(v[k], o);
+    if (RANGE) { mn = fminf(mn, a); mx = fmaxf(mx, b); }
+#pragma unroll
+    for (int k = 0; k < N; ++k) v[k] += t[k];
+  }
+  if (m.wpr == 1) return;                           // uniform over the workgroup
+  const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
+  if (lane == 0) {
+    if (RANGE) { sf[0][wave] = mn; sf[1][wave] = mx; }
+#pragma unroll
+    for (int k = 0; k < N; ++k) sd[k][wave] = v[k];
+  }
+  __syncthreads();
+  const int w0 = wave - m.part;
+  if (RANGE) { mn = sf[0][w0]; mx = sf[1][w0]; }
+#pragma unroll
+  for (int k = 0; k < N; ++k) v[k] = sd[k][w0];
+  for (int i = 1; i < m.wpr; ++i) {
+    if (RANGE) { mn = fminf(mn, sf[0][w0 + i]); mx = fmaxf(mx, sf[1][w0 + i]); }
+#pragma unroll
+    for (int k = 0; k < N; ++k) v[k] += sd[k][w0 + i];
+  }
+}
+
 // pass 1, row-group tiles: many short segments (output channels) per workgroup
 template <int BLOCK>
 __global__ __launch_bounds__(BLOCK) void k_stats_rows(const Tile* __restrict__ tiles,
                                                       StatPartial* __restrict__ parts) {
   constexpr int W = BLOCK / kWave;
   __shared__ __attribute__((aligned(16))) float xs[kRowGroupCap + 4];
+  __shared__ float sf[2][W];
+  __shared__ double sd[2][W];
   const Tile tl = tiles[blockIdx.x];
   const int shift = stage_tile<BLOCK>(tl.x, tl.len, xs);
   __syncthreads();
 
-  const int inner = tl.inner, w = row_width(inner), gpw = kWave / w;
-  const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
-  const int g = lane >> __builtin_ctz(w), gl = lane & (w - 1);
-  for (int rb = wave * gpw; rb < tl.rows; rb += W * gpw) {     // uniform per wavefront
-    const int r = rb + g;
+  const int inner = tl.inner;
+  const RowMap m = row_map<W>(tl.rows, inner);
+  for (int round = 0; round < m.rounds; ++round) {
+    const int r = m.row0 + round * m.step;
     const bool live = r < tl.rows;
     float mn = INFINITY, mx = -INFINITY;
-    double sx = 0.0, sx2 = 0.0;
+    double v[2] = {0.0, 0.0};                                  // sum x, sum x^2
     if (live) {
       const float* row = xs + shift + r * inner;
-      for (int j = gl; j < inner; j += w) {
-        const float v = row[j];
-        mn = fminf(mn, v); mx = fmaxf(mx, v);
-        sx += v; sx2 = fma(static_cast<double>(v), static_cast<double>(v), sx2);
+      for (int j = m.gl; j < inner; j += m.stride) {
+        const float x = row[j];
+        mn = fminf(mn, x); mx = fmaxf(mx, x);
+        v[0] += x; v[1] = fma(static_cast<double>(x), static_cast<double>(x), v[1]);
       }
     }
-    mn = group_min(mn, w); mx = group_max(mx, w);
-    sx = group_sum(sx, w); sx2 = group_sum(sx2, w);
-    if (live && gl == 0) {
+    row_join<W, 2, true>(m, mn, mx, v, sf, sd);
+    if (live && m.gl == 0) {
       StatPartial o;
-      o.mn = mn; o.mx = mx; o.sx = sx; o.sx2 = sx2;
+      o.mn = mn; o.mx = mx; o.sx = v[0]; o.sx2 = v[1];
       parts[tl.part0 + r] = o;
     }
   }
@@ -345,43 +416,50 @@ __device__ __forceinline__ void make_params(float mn, float mx, int scheme, qv2_
 }
 
 // ---------------------------------------------------------------------------
-// folds.  A segment's partials are folded in a fixed order: lane- (or thread-)
-// strided, then a butterfly.  WIDE = false: one wavefront per segment, four
-// segments per 256-thread workgroup, segments with many partials are skipped;
-// WIDE = true: one 1024-thread workgroup per listed segment.
+// folds.  An item's partials (a segment's, or a tensor's for the pair sums) are folded in a
+// fixed order: lane- (or thread-) strided, then a butterfly.  One launch of 1024-thread
+// workgroups serves all items: the first n_wide workgroups take one listed item each (those
+// with more than kFoldWaveMax partials) with all their threads, every other workgroup takes
+// 16 items, one per wavefront, and leaves the listed ones alone.
 // ---------------------------------------------------------------------------
-template <bool WIDE>
+constexpr int kFoldPerBlock = kFoldBlock / kWave;
+
 struct FoldIdx {
   int id, lane, stride;
-  bool active;
-  __device__ __forceinline__ FoldIdx(const int* ids, int n) {
-    if (WIDE) {
-      id = ids[blockIdx.x]; lane = threadIdx.x; stride = kFoldBlock; active = true;
+  bool wide, active;
+  // b: index of the workgroup within its family of n_wide + ceil(n / 16) workgroups
+  __device__ __forceinline__ FoldIdx(int b, const int* ids, int n_wide, int n) {
+    wide = b < n_wide;
+    if (wide) {
+      id = ids[b]; lane = threadIdx.x; stride = kFoldBlock; active = true;
     } else {
-      id = blockIdx.x * 4 + (threadIdx.x >> 6); lane = threadIdx.x & (kWave - 1);
+      id = (b - n_wide) * kFoldPerBlock + (threadIdx.x >> 6); lane = threadIdx.x & (kWave - 1);
       stride = kWave; active = id < n;
     }
   }
 };
 
-template <bool WIDE>
-__device__ __forceinline__ void fold_sum3(double& a, double& b, double& c) {
-  if (WIDE) {
+int fold_blocks(int n_wide, int n) { return n_wide + (n + kFoldPerBlock - 1) / kFoldPerBlock; }
+
+// `wide` is uniform over the workgroup (the wide form holds barriers)
+__device__ __forceinline__ void fold_sum3(bool wide, double& a, double& b, double& c) {
+  if (wide) {
     block_sum3<kFoldBlock>(a, b, c);
   } else {
     a = group_sum(a, kWave); b = group_sum(b, kWave); c = group_sum(c, kWave);
   }
 }
 
-template <bool WIDE>
-__global__ __launch_bounds__(WIDE ? kFoldBlock : 256) void k_fold_stats(
-    const Segment* __restrict__ segs, int nseg, const int* __restrict__ ids,
+// Calibration fold: range and sums of every segment, then its parameters (Eq. 2, Eq. 4).
+__global__ __launch_bounds__(kFoldBlock) void k_fold_stats(
+    const Segment* __restrict__ segs, int nseg, const int* __restrict__ ids, int n_wide,
     const StatPartial* __restrict__ parts, qv2_qparams* __restrict__ params,
-    qv2_sums* __restrict__ sums) {
-  const FoldIdx<WIDE> f(ids, nseg);
+    qv2_sums* __restrict__ sums, int skip_below) {
+  const FoldIdx f(blockIdx.x, ids, n_wide, nseg);
   if (!f.active) return;
   const Segment sg = segs[f.id];
-  if (!WIDE && sg.snp > kFoldWaveMax) return;      // left to the wide fold
+  if (!f.wide && sg.snp > kFoldWaveMax) return;    // left to its own workgroup
+  if (sg.sp0 < skip_below) return;                 // row-group segment finished by its own kernel
   float mn = INFINITY, mx = -INFINITY;
   double sx = 0.0, sx2 = 0.0, unused = 0.0;
 #pragma unroll 4
@@ -390,13 +468,13 @@ __global__ __launch_bounds__(WIDE ? kFoldBlock : 256) void k_fold_stats(
     mn = fminf(mn, q.mn); mx = fmaxf(mx, q.mx);
     sx += q.sx; sx2 += q.sx2;
   }
-  if (WIDE) {
+  if (f.wide) {
     block_minmax<kFoldBlock>(mn, mx);
     __syncthreads();
   } else {
     mn = group_min(mn, kWave); mx = group_max(mx, kWave);
   }
-  fold_sum3<WIDE>(sx, sx2, unused);
+  fold_sum3(f.wide, sx, sx2, unused);
   if (f.lane == 0) {
     qv2_qparams qp;
     make_params(mn, mx, sg.scheme, qp);
@@ -413,54 +491,85 @@ __device__ __forceinline__ double cross_xh(const ErrPartial5& p) { return p.sxh;
 __device__ __forceinline__ double cross_xq(const ErrPartial&) { return 0.0; }
 __device__ __forceinline__ double cross_xq(const ErrPartial3&) { return 0.0; }
 __device__ __forceinline__ double cross_xq(const ErrPartial5& p) { return p.sxq; }
+// second energy of a partial record: the pair-noise energy
+__device__ __forceinline__ double pair_energy(const ErrPartial& p) { return p.se2; }
+__device__ __forceinline__ double pair_energy(const ErrPartial3& p) { return p.sd2; }
+__device__ __forceinline__ double pair_energy(const ErrPartial5& p) { return p.sd2; }
 
-template <bool WIDE, class P>
-__global__ __launch_bounds__(WIDE ? kFoldBlock : 256) void k_fold_err(
-    const Segment* __restrict__ segs, int nseg, const int* __restrict__ ids,
-    const P* __restrict__ parts, qv2_sums* __restrict__ sums, double* __restrict__ seg_xxhat) {
-  const FoldIdx<WIDE> f(ids, nseg);
+// error energies of one segment
+template <class P>
+__device__ __forceinline__ void fold_err_item(const FoldIdx& f, const Segment* __restrict__ segs,
+                                              const P* __restrict__ parts, qv2_sums* __restrict__ sums,
+                                              double* __restrict__ seg_xxhat, int skip_below) {
   if (!f.active) return;
   const Segment sg = segs[f.id];
-  if (!WIDE && sg.enp > kFoldWaveMax) return;
+  if (!f.wide && sg.enp > kFoldWaveMax) return;
+  if (sg.ep0 < skip_below) return;
   double sx2 = 0.0, se2 = 0.0, sxh = 0.0;
 #pragma unroll 4
   for (int i = f.lane; i < sg.enp; i += f.stride) {
     const P q = parts[sg.ep0 + i];
     sx2 += q.sx2; se2 += q.se2; sxh += cross_xh(q);
   }
-  fold_sum3<WIDE>(sx2, se2, sxh);
+  fold_sum3(f.wide, sx2, se2, sxh);
   if (f.lane == 0) {
     sums[f.id].sum_x2 = sx2; sums[f.id].sum_e2 = se2; sums[f.id].n = sg.n;
     if (seg_xxhat) seg_xxhat[f.id] = sxh;
   }
 }
 
-// second energy of a partial record: the pair-noise energy
-__device__ __forceinline__ double pair_energy(const ErrPartial& p) { return p.se2; }
-__device__ __forceinline__ double pair_energy(const ErrPartial3& p) { return p.sd2; }
-__device__ __forceinline__ double pair_energy(const ErrPartial5& p) { return p.sd2; }
-
-template <bool WIDE, class P>
-__global__ __launch_bounds__(WIDE ? kFoldBlock : 256) void k_fold_pair(
-    const PairTensor* __restrict__ pt, int n, const int* __restrict__ ids,
-    const P* __restrict__ parts, qv2_pair_sums* __restrict__ out, double* __restrict__ pair_xq) {
-  const FoldIdx<WIDE> f(ids, n);
+// pair energies of one tensor
+template <class P>
+__device__ __forceinline__ void fold_pair_item(const FoldIdx& f, const PairTensor* __restrict__ pt,
+                                               const P* __restrict__ parts, qv2_pair_sums* __restrict__ out,
+                                               double* __restrict__ pair_xq) {
   if (!f.active) return;
   const PairTensor p = pt[f.id];
-  if (!WIDE && p.nparts > kFoldWaveMax) return;
+  if (!f.wide && p.nparts > kFoldWaveMax) return;
   double sr2 = 0.0, sd2 = 0.0, sxq = 0.0;
 #pragma unroll 4
   for (int i = f.lane; i < p.nparts; i += f.stride) {
     const P q = parts[p.part0 + i];
     sr2 += q.sx2; sd2 += pair_energy(q); sxq += cross_xq(q);
   }
-  fold_sum3<WIDE>(sr2, sd2, sxq);
+  fold_sum3(f.wide, sr2, sd2, sxq);
   if (f.lane == 0) {
     qv2_pair_sums o;
     o.sum_ref2 = sr2; o.sum_d2 = sd2; o.n = p.n; o._pad = 0;
     out[f.id] = o;
     if (pair_xq) pair_xq[f.id] = sxq;
   }
+}
+
+// What a fold launch after a quantize pass works on: the segments, and (fused passes)
+// the tensors with a quantized-run partner, whose workgroups follow those of the segments.
+template <class P>
+struct QuantFoldArgs {
+  const Segment* segs; int nseg; const int* wide_segs; int n_wide_segs;
+  qv2_sums* sums; double* seg_xxhat; int skip_below;
+  const PairTensor* pt; int nt; const int* wide_pt; int n_wide_pt;     // pair_out == null: none
+  qv2_pair_sums* pair_out; double* pair_xq;
+  const P* parts;
+  int seg_blocks;
+};
+
+template <class P>
+__global__ __launch_bounds__(kFoldBlock) void k_fold_quant(const QuantFoldArgs<P> a) {
+  const int b = blockIdx.x;
+  if (b < a.seg_blocks) {
+    fold_err_item<P>(FoldIdx(b, a.wide_segs, a.n_wide_segs, a.nseg), a.segs, a.parts, a.sums,
+                     a.seg_xxhat, a.skip_below);
+  } else {
+    fold_pair_item<P>(FoldIdx(b - a.seg_blocks, a.wide_pt, a.n_wide_pt, a.nt), a.pt, a.parts,
+                      a.pair_out, a.pair_xq);
+  }
+}
+
+// fold of the separate pair pass
+__global__ __launch_bounds__(kFoldBlock) void k_fold_pair(
+    const PairTensor* __restrict__ pt, int nt, const int* __restrict__ ids, int n_wide,
+    const ErrPartial* __restrict__ parts, qv2_pair_sums* __restrict__ out) {
+  fold_pair_item<ErrPartial>(FoldIdx(blockIdx.x, ids, n_wide, nt), pt, parts, out, nullptr);
 }
 
 // ---------------------------------------------------------------------------
@@ -590,55 +699,89 @@ __global__ __launch_bounds__(BLOCK, QV2_QUANT_WAVES_PER_EU) void k_quant_stream(
   if (tid == 0) parts[tl.part0] = o;
 }
 
-// pass 2 (+3), row-group tiles
-template <int BLOCK, bool PAIR, bool COS>
+// pass 2 (+3), row-group tiles.  CALIB: pass 1 in the same visit - the tile sits in LDS, so
+// every row's range, parameters, codes and energies come from ONE read of it from HBM; the
+// rows' parameter and sum records are written here (same arithmetic and order as the
+// separate kernels and their folds, hence the same bits) instead of by the folds.
+template <int BLOCK, bool PAIR, bool COS, bool CALIB>
 __global__ __launch_bounds__(BLOCK) void k_quant_rows(const Tile* __restrict__ tiles,
+                                                      const Segment* __restrict__ segs,
                                                       const qv2_qparams* __restrict__ params,
+                                                      qv2_qparams* __restrict__ params_out,
+                                                      qv2_sums* __restrict__ sums_out,
                                                       typename ErrRec<COS>::type* __restrict__ parts) {
   constexpr int W = BLOCK / kWave;
   __shared__ __attribute__((aligned(16))) float xs[kRowGroupCap + 4];
   __shared__ __attribute__((aligned(16))) int8_t cs[kRowGroupCap + 8];
+  __shared__ float sf[2][W];                        // exchange areas of the split row form
+  __shared__ double sd1[1][W], sd2[COS ? 5 : 3][W];
   const Tile tl = tiles[blockIdx.x];
   const int shift = stage_tile<BLOCK>(tl.x, tl.len, xs);
   const gf_ptr b = (gf_ptr)tl.q;
   const bool has_b = PAIR && tl.q != nullptr;
   const int ca = static_cast<int>(reinterpret_cast<uintptr_t>(tl.c) & 3u);   // code e sits at cs[e + ca]
+  const int scheme = CALIB ? segs[tl.seg0].scheme : 0;      // one tensor, one scheme per tile
   __syncthreads();
 
-  const int inner = tl.inner, w = row_width(inner), gpw = kWave / w;
-  const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
-  const int g = lane >> __builtin_ctz(w), gl = lane & (w - 1);
-  for (int rb = wave * gpw; rb < tl.rows; rb += W * gpw) {
-    const int r = rb + g;
+  const int inner = tl.inner;
+  const RowMap m = row_map<W>(tl.rows, inner);
+  for (int round = 0; round < m.rounds; ++round) {
+    const int r = m.row0 + round * m.step;
     const bool live = r < tl.rows;
-    double sx2 = 0.0, se2 = 0.0, sd2 = 0.0, sxh = 0.0, sxq = 0.0;
+    const float* row = xs + shift + r * inner;
+    qv2_qparams qp;
+    double sx = 0.0;
+    QP q{1.0f, 1.0f, 0.0f};
+    if (CALIB) {
+      float mn = INFINITY, mx = -INFINITY;
+      double v[1] = {0.0};
+      if (live) {
+        for (int j = m.gl; j < inner; j += m.stride) {
+          const float x = row[j];
+          mn = fminf(mn, x); mx = fmaxf(mx, x);
+          v[0] += x;
+        }
+      }
+      row_join<W, 1, true>(m, mn, mx, v, sf, sd1);
+      sx = v[0];
+      make_params(mn, mx, scheme, qp);
+      q = QP{qp.scale, qp.inv_scale, static_cast<float>(qp.zp)};
+    } else if (live) {
+      q = load_qp(params, tl.seg0 + r);
+    }
+    constexpr int NE = COS ? 5 : 3;
+    double e[NE] = {};                                         // x^2, e^2, d^2 (, x*xhat, x*qrun)
     if (live) {
-      const QP q = load_qp(params, tl.seg0 + r);
-      const float* row = xs + shift + r * inner;
       int8_t* crow = cs + ca + r * inner;
-      for (int j = gl; j < inner; j += w) {
-        const float v = row[j];
-        float e, h;
-        const float code = quant1(v, q, e, h);
+      for (int j = m.gl; j < inner; j += m.stride) {
+        const float x = row[j];
+        float err, h;
+        const float code = quant1(x, q, err, h);
         crow[j] = static_cast<int8_t>(static_cast<int>(code));
-        sx2 = fma(static_cast<double>(v), static_cast<double>(v), sx2);
-        se2 = fma(static_cast<double>(e), static_cast<double>(e), se2);
-        if (COS) sxh = fma(static_cast<double>(v), static_cast<double>(h), sxh);
+        e[0] = fma(static_cast<double>(x), static_cast<double>(x), e[0]);
+        e[1] = fma(static_cast<double>(err), static_cast<double>(err), e[1]);
+        if (COS) e[NE - 2] = fma(static_cast<double>(x), static_cast<double>(h), e[NE - 2]);
         if (has_b) {
           const float qv = b[r * inner + j];
-          const double d = static_cast<double>(v - qv);
-          sd2 = fma(d, d, sd2);
-          if (COS) sxq = fma(static_cast<double>(v), static_cast<double>(qv), sxq);
+          const double d = static_cast<double>(x - qv);
+          e[2] = fma(d, d, e[2]);
+          if (COS) e[NE - 1] = fma(static_cast<double>(x), static_cast<double>(qv), e[NE - 1]);
         }
       }
     }
-    sx2 = group_sum(sx2, w); se2 = group_sum(se2, w); sd2 = group_sum(sd2, w);
-    if (COS) { sxh = group_sum(sxh, w); sxq = group_sum(sxq, w); }
-    if (live && gl == 0) {
+    float u0 = 0.0f, u1 = 0.0f;
+    row_join<W, NE, false>(m, u0, u1, e, sf, sd2);
+    if (live && m.gl == 0) {
       typename ErrRec<COS>::type o;
-      o.sx2 = sx2; o.se2 = se2; o.sd2 = sd2;
-      set_cross(o, sxh, sxq);
+      o.sx2 = e[0]; o.se2 = e[1]; o.sd2 = e[2];
+      set_cross(o, COS ? e[NE - 2] : 0.0, COS ? e[NE - 1] : 0.0);
       parts[tl.part0 + r] = o;
+      if (CALIB) {
+        params_out[tl.seg0 + r] = qp;
+        qv2_sums u;
+        u.sum_x = sx; u.sum_x2 = e[0]; u.sum_e2 = e[1]; u.n = inner;
+        sums_out[tl.seg0 + r] = u;
+      }
     }
   }
   if (!tl.c) return;
@@ -949,43 +1092,72 @@ struct Timed {
 
 int fold_grid(int n) { return (n + 3) / 4; }
 
-// quantize pass over stream and row-group tiles, then the error fold
+// quantize pass over stream and row-group tiles, then ONE fold launch for the segments'
+// error sums and (d_pair_sums != null) the tensors' pair sums.  d_params_out != null: the
+// row-group kernel also calibrates its rows (writes their parameter and sum records), and
+// the fold leaves those segments alone.
 template <bool PAIR, bool COS>
 void launch_quant(qv2_plan* plan, const qv2_qparams* d_params, qv2_sums* d_sums,
-                  typename ErrRec<COS>::type* parts, double* d_seg_xxhat, hipStream_t s) {
+                  typename ErrRec<COS>::type* parts, double* d_seg_xxhat, qv2_pair_sums* d_pair_sums,
+                  double* d_pair_xq, hipStream_t s, qv2_qparams* d_params_out = nullptr) {
   typedef typename ErrRec<COS>::type P;
+  const bool calib_rows = d_params_out != nullptr;
   const int n_stream = static_cast<int>(plan->quant_tiles.size());
   const int n_rows = static_cast<int>(plan->row_tiles.size());
-  const int nseg = static_cast<int>(plan->segments.size());
   if (n_stream > 0) {
     Timed timed(plan, PAIR ? QV2_K_QUANTPAIR_STREAM : QV2_K_QUANT_STREAM, s);
     hipLaunchKernelGGL((k_quant_stream<kBlockQuant, kVecQuant, PAIR, COS>), dim3(n_stream),
                        dim3(kBlockQuant), 0, s, plan->d_quant_tiles, d_params, parts);
   }
   if (n_rows > 0) {
-    Timed timed(plan, PAIR ? QV2_K_QUANTPAIR_ROWS : QV2_K_QUANT_ROWS, s);
-    hipLaunchKernelGGL((k_quant_rows<kBlockRows, PAIR, COS>), dim3(n_rows), dim3(kBlockRows), 0, s,
-                       plan->d_row_tiles, d_params, parts);
+    Timed timed(plan, calib_rows ? QV2_K_SINGLE_READ_ROWS : PAIR ? QV2_K_QUANTPAIR_ROWS : QV2_K_QUANT_ROWS, s);
+    if (calib_rows)
+      hipLaunchKernelGGL((k_quant_rows<kBlockRows, PAIR, COS, true>), dim3(n_rows), dim3(kBlockRows), 0, s,
+                         plan->d_row_tiles, plan->d_segments, d_params, d_params_out, d_sums, parts);
+    else
+      hipLaunchKernelGGL((k_quant_rows<kBlockRows, PAIR, COS, false>), dim3(n_rows), dim3(kBlockRows), 0, s,
+                         plan->d_row_tiles, plan->d_segments, d_params, d_params_out, d_sums, parts);
   }
-  hipLaunchKernelGGL((k_fold_err<false, P>), dim3(fold_grid(nseg)), dim3(256), 0, s, plan->d_segments,
-                     nseg, static_cast<const int*>(nullptr), parts, d_sums, d_seg_xxhat);
-  if (const int nb = static_cast<int>(plan->big_err_segments.size()))
-    hipLaunchKernelGGL((k_fold_err<true, P>), dim3(nb), dim3(kFoldBlock), 0, s, plan->d_segments, nseg,
-                       plan->d_big_err_segments, parts, d_sums, d_seg_xxhat);
+  QuantFoldArgs<P> a{};
+  a.segs = plan->d_segments; a.nseg = static_cast<int>(plan->segments.size());
+  a.wide_segs = plan->d_big_err_segments; a.n_wide_segs = static_cast<int>(plan->big_err_segments.size());
+  a.sums = d_sums; a.seg_xxhat = d_seg_xxhat; a.skip_below = calib_rows ? plan->n_row_parts : 0;
+  a.parts = parts;
+  a.seg_blocks = fold_blocks(a.n_wide_segs, a.nseg);
+  int blocks = a.seg_blocks;
+  if (d_pair_sums) {
+    a.pt = plan->d_fused_pair_tensors; a.nt = static_cast<int>(plan->fused_pair_tensors.size());
+    a.wide_pt = plan->d_big_fused_pair_tensors;
+    a.n_wide_pt = static_cast<int>(plan->big_fused_pair_tensors.size());
+    a.pair_out = d_pair_sums; a.pair_xq = d_pair_xq;
+    blocks += fold_blocks(a.n_wide_pt, a.nt);
+  }
+  hipLaunchKernelGGL(k_fold_quant<P>, dim3(blocks), dim3(kFoldBlock), 0, s, a);
 }
 
-// per-tensor pair fold of a fused quantize pass
-template <class P>
-void launch_fused_pair_fold(qv2_plan* plan, const P* parts, qv2_pair_sums* d_pair_sums,
-                            double* d_pair_xq, hipStream_t s) {
-  const int nt = static_cast<int>(plan->fused_pair_tensors.size());
-  hipLaunchKernelGGL((k_fold_pair<false, P>), dim3(fold_grid(nt)), dim3(256), 0, s,
-                     plan->d_fused_pair_tensors, nt, static_cast<const int*>(nullptr), parts, d_pair_sums,
-                     d_pair_xq);
-  if (const int nb = static_cast<int>(plan->big_fused_pair_tensors.size()))
-    hipLaunchKernelGGL((k_fold_pair<true, P>), dim3(nb), dim3(kFoldBlock), 0, s,
-                       plan->d_fused_pair_tensors, nt, plan->d_big_fused_pair_tensors, parts, d_pair_sums,
-                       d_pair_xq);
+// calibration over the stream tiles (and the row-group tiles unless their own single-read
+// kernel will calibrate them), then the statistics fold
+void launch_stats(qv2_plan* plan, qv2_qparams* d_params, qv2_sums* d_sums, StatPartial* parts,
+                  bool with_rows, hipStream_t s) {
+  const int n_stream = static_cast<int>(plan->read_tiles.size());
+  const int n_rows = static_cast<int>(plan->row_tiles.size());
+  const int nseg = static_cast<int>(plan->segments.size());
+  if (n_stream > 0) {
+    Timed timed(plan, QV2_K_STATS_STREAM, s);
+    hipLaunchKernelGGL((k_stats_stream<kBlockRead, kVecRead>), dim3(n_stream), dim3(kBlockRead), 0, s,
+                       plan->d_read_tiles, parts);
+  }
+  if (with_rows && n_rows > 0) {
+    Timed timed(plan, QV2_K_STATS_ROWS, s);
+    hipLaunchKernelGGL(k_stats_rows<kBlockRows>, dim3(n_rows), dim3(kBlockRows), 0, s,
+                       plan->d_row_tiles, parts);
+  }
+  if (with_rows || n_stream > 0) {
+    const int n_wide = static_cast<int>(plan->big_stat_segments.size());
+    hipLaunchKernelGGL(k_fold_stats, dim3(fold_blocks(n_wide, nseg)), dim3(kFoldBlock), 0, s,
+                       plan->d_segments, nseg, plan->d_big_stat_segments, n_wide, parts, d_params, d_sums,
+                       with_rows ? 0 : plan->n_row_parts);
+  }
 }
 
 }  // namespace
@@ -1036,26 +1208,8 @@ qv2_status qv2_calibrate(qv2_plan* plan, qv2_qparams* d_params, qv2_sums* d_sums
   qv2_status st = check_call(plan, d_params, d_sums, d_workspace, workspace_bytes);
   if (st != QV2_OK) return st;
   if ((st = ensure_uploaded(plan)) != QV2_OK) return st;
-  hipStream_t s = static_cast<hipStream_t>(hip_stream);
-  StatPartial* parts = static_cast<StatPartial*>(d_workspace);
-  const int n_stream = static_cast<int>(plan->read_tiles.size());
-  const int n_rows = static_cast<int>(plan->row_tiles.size());
-  const int nseg = static_cast<int>(plan->segments.size());
-  if (n_stream > 0) {
-    Timed timed(plan, QV2_K_STATS_STREAM, s);
-    hipLaunchKernelGGL((k_stats_stream<kBlockRead, kVecRead>), dim3(n_stream), dim3(kBlockRead), 0, s,
-                       plan->d_read_tiles, parts);
-  }
-  if (n_rows > 0) {
-    Timed timed(plan, QV2_K_STATS_ROWS, s);
-    hipLaunchKernelGGL(k_stats_rows<kBlockRows>, dim3(n_rows), dim3(kBlockRows), 0, s,
-                       plan->d_row_tiles, parts);
-  }
-  hipLaunchKernelGGL(k_fold_stats<false>, dim3(fold_grid(nseg)), dim3(256), 0, s, plan->d_segments, nseg,
-                     static_cast<const int*>(nullptr), parts, d_params, d_sums);
-  if (const int nb = static_cast<int>(plan->big_stat_segments.size()))
-    hipLaunchKernelGGL(k_fold_stats<true>, dim3(nb), dim3(kFoldBlock), 0, s, plan->d_segments, nseg,
-                       plan->d_big_stat_segments, parts, d_params, d_sums);
+  launch_stats(plan, d_params, d_sums, static_cast<StatPartial*>(d_workspace), true,
+               static_cast<hipStream_t>(hip_stream));
   return launch_status();
 }
 
@@ -1065,7 +1219,7 @@ qv2_status qv2_fakequant_metrics(qv2_plan* plan, const qv2_qparams* d_params, qv
   if (st != QV2_OK) return st;
   if ((st = ensure_uploaded(plan)) != QV2_OK) return st;
   launch_quant<false, false>(plan, d_params, d_sums, static_cast<ErrPartial3*>(d_workspace), nullptr,
-                             static_cast<hipStream_t>(hip_stream));
+                             nullptr, nullptr, static_cast<hipStream_t>(hip_stream));
   return launch_status();
 }
 
@@ -1083,13 +1237,9 @@ qv2_status qv2_pair_metrics(qv2_plan* plan, qv2_pair_sums* d_pair_sums, void* d_
     hipLaunchKernelGGL((k_pair_stream<kBlockRead, kVecRead / 2>), dim3(n_tiles), dim3(kBlockRead), 0, s,
                        plan->d_pair_tiles, parts);
   }
-  hipLaunchKernelGGL((k_fold_pair<false, ErrPartial>), dim3(fold_grid(nt)), dim3(256), 0, s,
-                     plan->d_pair_tensors, nt, static_cast<const int*>(nullptr), parts, d_pair_sums,
-                     static_cast<double*>(nullptr));
-  if (const int nb = static_cast<int>(plan->big_pair_tensors.size()))
-    hipLaunchKernelGGL((k_fold_pair<true, ErrPartial>), dim3(nb), dim3(kFoldBlock), 0, s,
-                       plan->d_pair_tensors, nt, plan->d_big_pair_tensors, parts, d_pair_sums,
-                       static_cast<double*>(nullptr));
+  const int n_wide = static_cast<int>(plan->big_pair_tensors.size());
+  hipLaunchKernelGGL(k_fold_pair, dim3(fold_blocks(n_wide, nt)), dim3(kFoldBlock), 0, s, plan->d_pair_tensors,
+                     nt, plan->d_big_pair_tensors, n_wide, parts, d_pair_sums);
   return launch_status();
 }
 
@@ -1103,8 +1253,27 @@ qv2_status qv2_fakequant_pair_metrics(qv2_plan* plan, const qv2_qparams* d_param
   if ((st = ensure_uploaded(plan)) != QV2_OK) return st;
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   ErrPartial3* parts = static_cast<ErrPartial3*>(d_workspace);
-  launch_quant<true, false>(plan, d_params, d_sums, parts, nullptr, s);
-  launch_fused_pair_fold(plan, parts, d_pair_sums, nullptr, s);
+  launch_quant<true, false>(plan, d_params, d_sums, parts, nullptr, d_pair_sums, nullptr, s);
+  return launch_status();
+}
+
+qv2_status qv2_calibrate_fakequant_pair_metrics(qv2_plan* plan, qv2_qparams* d_params, qv2_sums* d_sums,
+                                                qv2_pair_sums* d_pair_sums, void* d_workspace,
+                                                size_t workspace_bytes, void* hip_stream) {
+  qv2_status st = check_call(plan, d_params, d_sums, d_workspace, workspace_bytes);
+  if (st != QV2_OK) return st;
+  if (d_pair_sums && (reinterpret_cast<uintptr_t>(d_pair_sums) & 7u)) return QV2_ERR_ALIGN;
+  if ((st = ensure_uploaded(plan)) != QV2_OK) return st;
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  // stream tiles: statistics, fold (parameters), then the quantize sweep; row-group tiles:
+  // one kernel, after the statistics fold because the partial records share the workspace
+  launch_stats(plan, d_params, d_sums, static_cast<StatPartial*>(d_workspace), false, s);
+  ErrPartial3* parts = static_cast<ErrPartial3*>(d_workspace);
+  if (d_pair_sums) {
+    launch_quant<true, false>(plan, d_params, d_sums, parts, nullptr, d_pair_sums, nullptr, s, d_params);
+  } else {
+    launch_quant<false, false>(plan, d_params, d_sums, parts, nullptr, nullptr, nullptr, s, d_params);
+  }
   return launch_status();
 }
 
@@ -1120,8 +1289,7 @@ qv2_status qv2_fakequant_pair_metrics_cos(qv2_plan* plan, const qv2_qparams* d_p
   if ((st = ensure_uploaded(plan)) != QV2_OK) return st;
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   ErrPartial5* parts = static_cast<ErrPartial5*>(d_workspace);
-  launch_quant<true, true>(plan, d_params, d_sums, parts, d_seg_xxhat, s);
-  launch_fused_pair_fold(plan, parts, d_pair_sums, d_pair_xq, s);
+  launch_quant<true, true>(plan, d_params, d_sums, parts, d_seg_xxhat, d_pair_sums, d_pair_xq, s);
   return launch_status();
 }
 

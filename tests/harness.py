@@ -93,8 +93,9 @@ def attach_pairs(items: List[Item], specs: List[synth.TensorSpec]):
 
 def run_gpu(items: List[Item], params_override: Optional[np.ndarray] = None,
             do_calibrate: bool = True, fused: bool = False, cos: bool = False) -> GpuResult:
-    """calibrate -> fakequant -> pair (or the fused fakequant+pair call) on the current
-    stream, then host finalize."""
+    """calibrate -> fakequant -> pair (fused=True: the fused fakequant+pair call;
+    fused="single": the one call that does all three) on the current stream, then host
+    finalize."""
     dev = items[0].x.device
     rows = []
     for it in items:
@@ -107,7 +108,9 @@ def run_gpu(items: List[Item], params_override: Optional[np.ndarray] = None,
                                  kind=it.kind, layer=it.layer))
     plan = qb.qv2_plan_create(rows)
     buf = qb.Buffers(plan, dev)
-    if do_calibrate:
+    single = fused == "single"
+    assert not (single and (params_override is not None or cos or not do_calibrate))
+    if do_calibrate and not single:
         qb.qv2_calibrate(plan, buf.params, buf.sums, buf.workspace)
     if params_override is not None:
         torch.cuda.synchronize()
@@ -118,6 +121,8 @@ def run_gpu(items: List[Item], params_override: Optional[np.ndarray] = None,
         pair_xq = torch.zeros(plan.num_tensors, dtype=torch.float64, device=dev)
         qb.qv2_fakequant_pair_metrics_cos(plan, buf.params, buf.sums, buf.pair, seg_xxhat, pair_xq,
                                           buf.workspace)
+    elif single:
+        qb.qv2_calibrate_fakequant_pair_metrics(plan, buf.params, buf.sums, buf.pair, buf.workspace)
     elif fused:
         qb.qv2_fakequant_pair_metrics(plan, buf.params, buf.sums, buf.pair, buf.workspace)
     else:

@@ -24,7 +24,7 @@ def _run_config(specs, rank_kwargs=None, fused=False):
     return items, res, order
 
 
-@pytest.mark.parametrize("fused", [False, True])
+@pytest.mark.parametrize("fused", [False, True, "single"])
 def test_config_tiny(fused):
     """Three tensors, per-tensor asymmetric: conv weight, ReLU activation with a pair, fc weight."""
     items, res, order = _run_config(synth.config_tiny(), fused=fused)
@@ -40,7 +40,7 @@ def test_config_resnet18_batch32(fused):
     assert len(order) == 21 and sorted(order) == list(range(21))
 
 
-@pytest.mark.parametrize("fused", [False, True])
+@pytest.mark.parametrize("fused", [False, True, "single"])
 def test_config_mobilenetv2_per_channel(fused):
     """MobileNetV2 shapes: per-output-channel symmetric weights with rows of 9 / 27 / ...
     elements, Laplace + outlier values, ReLU6 activations (batch reduced so the oracle stays fast)."""
@@ -57,7 +57,7 @@ def test_config_vgg16_weights_full_size(per_channel):
     _run_config(synth.config_vgg16(2, per_channel))
 
 
-@pytest.mark.parametrize("bnfold,fused", [(False, False), (True, False), (True, True)])
+@pytest.mark.parametrize("bnfold,fused", [(False, False), (True, False), (True, True), (False, "single")])
 def test_config_resnet50_small_batch(bnfold, fused):
     """ResNet-50 shapes, per-channel weights (plain and BN-folded variants), batch 4."""
     items, res, order = _run_config(synth.config_resnet50(4, bnfold), fused=fused)
@@ -95,7 +95,7 @@ def test_ragged_lengths_and_unaligned_pointers(fused):
     H.check_all(items, res)
 
 
-@pytest.mark.parametrize("fused", [False, True])
+@pytest.mark.parametrize("fused", [False, True, "single"])
 def test_per_channel_row_shapes(fused):
     """Rows of 1, 3, 9, 27, 64, 65, 576, 8191, 8192 (LDS row groups) and 8193, 20001, 40000,
     70001 (rows as one or several stream tiles, unaligned row starts), with unaligned bases and
@@ -210,6 +210,37 @@ def test_fused_call_equals_the_two_separate_calls():
     assert np.array_equal(r1.pair["n"], r2.pair["n"])
     for f in ("sum_ref2", "sum_d2"):
         assert np.allclose(r1.pair[f], r2.pair[f], rtol=1e-12, atol=0)
+    assert all(torch.equal(a, it.codes) for a, it in zip(c1, items))
+
+
+def test_single_call_pass_is_bit_identical_to_the_separate_calls():
+    """qv2_calibrate_fakequant_pair_metrics (row-group tensors read from HBM once) against
+    qv2_calibrate + qv2_fakequant_pair_metrics: parameters, sums, pair sums and codes equal
+    bit for bit; without pair sums it equals qv2_calibrate + qv2_fakequant_metrics."""
+    specs = synth.config_mobilenetv2(2) + synth.config_resnet50(2) + synth.config_tiny()
+    items = H.items_from_specs(specs, DEV)
+    for i, it in enumerate(items):
+        if it.kind == synth.ACTIVATION or i % 5 == 0:       # some weights get a partner too
+            it.qrun = it.x * 0.98 + 0.003
+    items.append(H.Item("rows.unaligned", _rand(960 * 9 + 4, 77, 0.1)[1: 1 + 960 * 9], C, 960, 0, 0,
+                        qrun=_rand(960 * 9 + 4, 78, 0.1)[3: 3 + 960 * 9], codes_offset=3))
+    r1 = H.run_gpu(items, fused=True)
+    c1 = [it.codes.clone() for it in items]
+    r2 = H.run_gpu(items, fused="single")
+    assert r2.plan.num_tiles > r2.plan.num_tensors          # row-group and stream tiles both present
+    assert r1.params.tobytes() == r2.params.tobytes()
+    assert r1.sums.tobytes() == r2.sums.tobytes()
+    assert r1.pair.tobytes() == r2.pair.tobytes()
+    assert all(torch.equal(a, it.codes) for a, it in zip(c1, items))
+    # no pair sums: the plain fake-quant results
+    r3 = H.run_gpu(items)
+    buf = qb.Buffers(r3.plan, torch.device(DEV))
+    for it in items:
+        it.codes.fill_(0x55)
+    qb.qv2_calibrate_fakequant_pair_metrics(r3.plan, buf.params, buf.sums, None, buf.workspace)
+    torch.cuda.synchronize()
+    params, sums, _ = buf.host()
+    assert params.tobytes() == r3.params.tobytes() and sums.tobytes() == r3.sums.tobytes()
     assert all(torch.equal(a, it.codes) for a, it in zip(c1, items))
 
 

@@ -111,6 +111,11 @@ def test_device_calls_validate_before_touching_the_gpu():
     assert L.qv2_fakequant_metrics(p.handle, FAKE, FAKE, None, ws, None) == qb.QV2_ERR_NULL
     assert L.qv2_pair_metrics(p.handle, None, FAKE, ws, None) == qb.QV2_ERR_NULL
     assert L.qv2_pair_metrics(p.handle, FAKE, FAKE, 0, None) == qb.QV2_ERR_WORKSPACE
+    one = L.qv2_calibrate_fakequant_pair_metrics
+    assert one(p.handle, None, FAKE, FAKE, FAKE, ws, None) == qb.QV2_ERR_NULL
+    assert one(p.handle, FAKE, FAKE, None, None, ws, None) == qb.QV2_ERR_NULL      # workspace
+    assert one(p.handle, FAKE, FAKE, None, FAKE, ws - 1, None) == qb.QV2_ERR_WORKSPACE
+    assert one(p.handle, FAKE, FAKE, FAKE + 4, FAKE, ws, None) == qb.QV2_ERR_ALIGN
 
 
 # ----------------------------------------------------------------------------
