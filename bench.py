@@ -174,8 +174,7 @@ def main():
         h_pair.copy_(buf.pair, non_blocking=True)
         torch.cuda.current_stream().synchronize()
         if events:       # per-kernel durations from the library's HIP events on the same stream
-            for name in kernel_ms:
-                kernel_ms[name].append(qb.qv2_plan_kernel_ms(plan, name))
+            kernel_log.append(qb.qv2_plan_kernels_ms(plan).copy())
         met = qb.qv2_finalize_tensors(h_tsums.numpy().view(qb.TENSOR_SUMS))
         pmse, psqnr = qb.qv2_pair_finalize(h_pair.numpy().view(qb.PAIR_SUMS))
         w_sqnr = np.empty(n_layers); w_mse = np.empty(n_layers)
@@ -185,7 +184,7 @@ def main():
         order, score = qb.qv2_rank(w_sqnr, a_sqnr, w_mse, a_mse)
         last.update(order=order, score=score, met=met)
 
-    kernel_ms = {}
+    kernel_ms, kernel_log = {}, []
     qb.qv2_plan_set_timing(plan, True)
 
     def timed(mode):
@@ -194,7 +193,7 @@ def main():
         names = {"single": ["k_stats_stream", "k_quantpair_stream", "k_single_read_rows"],
                  "fused": ["k_stats_stream", "k_stats_rows", "k_quantpair_stream", "k_quantpair_rows"],
                  "calls": ["k_stats_stream", "k_stats_rows", "k_quant_stream", "k_quant_rows", "k_pair_stream"]}[mode]
-        kernel_ms.update({n: [] for n in names})
+        kernel_log.clear()
         for _ in range(args.warmup):
             step(mode)
         torch.cuda.synchronize()
@@ -203,6 +202,7 @@ def main():
             step(mode, ev[k])
         torch.cuda.synchronize()
         dt = time.perf_counter() - t0
+        kernel_ms.update({n: [row[qb.KERNEL_IDS[n]] for row in kernel_log] for n in names})
         r = {"ms_per_step": dt / args.steps * 1e3, "order": last["order"].tolist(),
              "kernels_ms": {n: round(float(np.mean(v)), 4) for n, v in kernel_ms.items()},
              "ms_cal": float(np.mean([e[0].elapsed_time(e[1]) for e in ev]))}

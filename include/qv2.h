@@ -177,6 +177,8 @@ typedef enum {
 } qv2_kernel_id;
 qv2_status qv2_plan_set_timing(qv2_plan* plan, int32_t enable);
 qv2_status qv2_plan_kernel_ms(const qv2_plan* plan, int32_t kernel, float* ms_out);
+/* All QV2_K_COUNT durations in one call: ms_out[QV2_K_COUNT], HOST, written. */
+qv2_status qv2_plan_kernels_ms(const qv2_plan* plan, float* ms_out);
 
 /* ---- device passes ------------------------------------------------------- */
 

@@ -28,7 +28,7 @@ EXPORTS = (
     "qv2_plan_num_pair_tiles",
     "qv2_workspace_bytes", "qv2_calibrate", "qv2_fakequant_metrics", "qv2_pair_metrics",
     "qv2_fakequant_pair_metrics", "qv2_calibrate_fakequant_pair_metrics", "qv2_fakequant_pair_metrics_cos", "qv2_cosine_finalize",
-    "qv2_plan_set_timing", "qv2_plan_kernel_ms", "qv2_histogram_workspace_bytes", "qv2_histogram",
+    "qv2_plan_set_timing", "qv2_plan_kernel_ms", "qv2_plan_kernels_ms", "qv2_histogram_workspace_bytes", "qv2_histogram",
     "qv2_kl_divergence", "qv2_bn_fold", "qv2_regroup_for_fusion", "qv2_tensor_sums_fold",
     "qv2_finalize_tensors",
     "qv2_finalize", "qv2_pair_finalize", "qv2_rank_config_default", "qv2_rank",
@@ -112,6 +112,7 @@ def lib():
         L.qv2_finalize_tensors.argtypes = [vp, i32, vp]
         L.qv2_plan_set_timing.argtypes = [vp, i32]
         L.qv2_plan_kernel_ms.argtypes = [vp, i32, ctypes.POINTER(ctypes.c_float)]
+        L.qv2_plan_kernels_ms.argtypes = [vp, vp]
         L.qv2_finalize.argtypes = [vp, vp, vp, vp]
         L.qv2_pair_finalize.argtypes = [vp, i32, vp, vp]
         L.qv2_rank_config_default.argtypes = [ctypes.POINTER(qv2_rank_config)]
@@ -218,6 +219,16 @@ def qv2_plan_kernel_ms(plan: Plan, kernel) -> float:
     kid = KERNEL_IDS[kernel] if isinstance(kernel, str) else int(kernel)
     _check(lib().qv2_plan_kernel_ms(plan.handle, kid, ctypes.byref(ms)), "qv2_plan_kernel_ms")
     return ms.value
+
+
+def qv2_plan_kernels_ms(plan: Plan, out=None):
+    """Durations of the most recent launch of every tile kernel, indexed by KERNEL_IDS
+    (float32 array of len(KERNEL_IDS); `out` is reused when given)."""
+    import numpy as np
+    if out is None:
+        out = np.zeros(len(KERNEL_IDS), dtype=np.float32)
+    _check(lib().qv2_plan_kernels_ms(plan.handle, out.ctypes.data), "qv2_plan_kernels_ms")
+    return out
 
 
 def qv2_workspace_bytes(plan: Plan) -> int:

@@ -1203,6 +1203,15 @@ qv2_status qv2_plan_kernel_ms(const qv2_plan* plan, int32_t kernel, float* ms_ou
   return QV2_OK;
 }
 
+qv2_status qv2_plan_kernels_ms(const qv2_plan* plan, float* ms_out) {
+  if (!plan || !ms_out) return QV2_ERR_NULL;
+  for (int k = 0; k < QV2_K_COUNT; ++k) {
+    const qv2_status st = qv2_plan_kernel_ms(plan, k, ms_out + k);
+    if (st != QV2_OK) return st;
+  }
+  return QV2_OK;
+}
+
 qv2_status qv2_calibrate(qv2_plan* plan, qv2_qparams* d_params, qv2_sums* d_sums,
                          void* d_workspace, size_t workspace_bytes, void* hip_stream) {
   qv2_status st = check_call(plan, d_params, d_sums, d_workspace, workspace_bytes);
