@@ -91,7 +91,14 @@ qv2_status qv2_plan_create(const qv2_tensor* h_tensors, int32_t n_tensors, qv2_p
     PairTensor ft{};                         // this tensor's partials in the quantize numbering
     if (per_channel && inner <= qv2::kRowGroupCap) {
       // whole rows per tile; every row is its own segment with one partial
-      const int64_t rpt = std::min<int64_t>(qv2::kRowGroupMaxRows, qv2::kRowGroupCap / inner);
+      // rows per tile: what fits the LDS copy, but no more than a few rounds of the row
+      // kernels (a round = one row per lane group of every wavefront), so that a tile of
+      // very short rows does not become the longest-running workgroup of the launch
+      int64_t lanes = 1;
+      while (lanes < inner && lanes < 64) lanes <<= 1;
+      const int64_t per_round = (qv2::kBlockRows / 64) * (64 / lanes);
+      const int64_t rpt = std::min<int64_t>({qv2::kRowGroupMaxRows, qv2::kRowGroupCap / inner,
+                                             qv2::kRowGroupRounds * per_round});
       ft.part0 = static_cast<int32_t>(row_part); ft.nparts = static_cast<int32_t>(nseg);
       for (int64_t r0 = 0; r0 < nseg; r0 += rpt) {
         const int64_t rows = std::min(rpt, nseg - r0);

@@ -31,6 +31,10 @@ constexpr int kVecQuant = QV2_VEC_QUANT;
 constexpr int kRowGroupCap = 8192;
 // Most rows one row-group tile may hold.
 constexpr int kRowGroupMaxRows = 1024;
+// ... and most rounds of the row kernels one tile may take (a round = one row per lane group
+// of every wavefront): measured, a tile of 910 nine-element rows (29 rounds) alone made the
+// MobileNetV2 launch twice as long as four-round tiles do.
+constexpr int kRowGroupRounds = 4;
 // Stream-tile length of the read-only passes (128 KiB of fp32): long tiles amortise the
 // per-workgroup reduction.
 constexpr int kDefaultReadTile = 32768;

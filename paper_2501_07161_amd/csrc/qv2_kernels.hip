@@ -273,7 +273,18 @@ __device__ __forceinline__ int stage_tile(const float* x, int len, float* xs) {
   if (tid < head) xs[shift + tid] = p[tid];
   const gf4_ptr v4 = (gf4_ptr)(x + head);
   f4* d4 = reinterpret_cast<f4*>(xs + shift + head);
-  for (int i = tid; i < nvec; i += BLOCK) d4[i] = v4[i];
+  constexpr int kPer = (kRowGroupCap / 4 + BLOCK - 1) / BLOCK;   // all loads of a lane go out before its LDS stores
+  f4 r[kPer];
+#pragma unroll
+  for (int u = 0; u < kPer; ++u) {
+    const int i = tid + u * BLOCK;
+    if (i < nvec) r[u] = ld4(v4 + i);
+  }
+#pragma unroll
+  for (int u = 0; u < kPer; ++u) {
+    const int i = tid + u * BLOCK;
+    if (i < nvec) d4[i] = r[u];
+  }
   if (tid < tail) xs[shift + head + (nvec << 2) + tid] = p[head + (nvec << 2) + tid];
   return shift;
 }
@@ -377,11 +388,16 @@ __global__ __launch_bounds__(BLOCK) void k_stats_rows(const Tile* __restrict__ t
     double v[2] = {0.0, 0.0};                                  // sum x, sum x^2
     if (live) {
       const float* row = xs + shift + r * inner;
-      for (int j = m.gl; j < inner; j += m.stride) {
-        const float x = row[j];
+      auto take = [&](float x) {
         mn = fminf(mn, x); mx = fmaxf(mx, x);
         v[0] += x; v[1] = fma(static_cast<double>(x), static_cast<double>(x), v[1]);
+      };
+      int j = m.gl;
+      for (; j + 3 * m.stride < inner; j += 4 * m.stride) {      // four LDS reads in flight
+        const float x0 = row[j], x1 = row[j + m.stride], x2 = row[j + 2 * m.stride], x3 = row[j + 3 * m.stride];
+        take(x0); take(x1); take(x2); take(x3);
       }
+      for (; j < inner; j += m.stride) take(row[j]);
     }
     row_join<W, 2, true>(m, mn, mx, v, sf, sd);
     if (live && m.gl == 0) {
@@ -736,11 +752,13 @@ __global__ __launch_bounds__(BLOCK) void k_quant_rows(const Tile* __restrict__ t
       float mn = INFINITY, mx = -INFINITY;
       double v[1] = {0.0};
       if (live) {
-        for (int j = m.gl; j < inner; j += m.stride) {
-          const float x = row[j];
-          mn = fminf(mn, x); mx = fmaxf(mx, x);
-          v[0] += x;
+        auto take = [&](float x) { mn = fminf(mn, x); mx = fmaxf(mx, x); v[0] += x; };
+        int j = m.gl;
+        for (; j + 3 * m.stride < inner; j += 4 * m.stride) {    // four LDS reads in flight
+          const float x0 = row[j], x1 = row[j + m.stride], x2 = row[j + 2 * m.stride], x3 = row[j + 3 * m.stride];
+          take(x0); take(x1); take(x2); take(x3);
         }
+        for (; j < inner; j += m.stride) take(row[j]);
       }
       row_join<W, 1, true>(m, mn, mx, v, sf, sd1);
       sx = v[0];
@@ -753,8 +771,8 @@ __global__ __launch_bounds__(BLOCK) void k_quant_rows(const Tile* __restrict__ t
     double e[NE] = {};                                         // x^2, e^2, d^2 (, x*xhat, x*qrun)
     if (live) {
       int8_t* crow = cs + ca + r * inner;
-      for (int j = m.gl; j < inner; j += m.stride) {
-        const float x = row[j];
+      const gf_ptr brow = b + r * inner;
+      auto take = [&](int j, float x, float qv) {
         float err, h;
         const float code = quant1(x, q, err, h);
         crow[j] = static_cast<int8_t>(static_cast<int>(code));
@@ -762,12 +780,20 @@ __global__ __launch_bounds__(BLOCK) void k_quant_rows(const Tile* __restrict__ t
         e[1] = fma(static_cast<double>(err), static_cast<double>(err), e[1]);
         if (COS) e[NE - 2] = fma(static_cast<double>(x), static_cast<double>(h), e[NE - 2]);
         if (has_b) {
-          const float qv = b[r * inner + j];
           const double d = static_cast<double>(x - qv);
           e[2] = fma(d, d, e[2]);
           if (COS) e[NE - 1] = fma(static_cast<double>(x), static_cast<double>(qv), e[NE - 1]);
         }
+      };
+      int j = m.gl;
+      for (; j + 3 * m.stride < inner; j += 4 * m.stride) {      // four reads in flight per stream
+        const int j1 = j + m.stride, j2 = j + 2 * m.stride, j3 = j + 3 * m.stride;
+        const float x0 = row[j], x1 = row[j1], x2 = row[j2], x3 = row[j3];
+        float q0 = 0.0f, q1 = 0.0f, q2 = 0.0f, q3 = 0.0f;
+        if (has_b) { q0 = brow[j]; q1 = brow[j1]; q2 = brow[j2]; q3 = brow[j3]; }
+        take(j, x0, q0); take(j1, x1, q1); take(j2, x2, q2); take(j3, x3, q3);
       }
+      for (; j < inner; j += m.stride) take(j, row[j], has_b ? brow[j] : 0.0f);
     }
     float u0 = 0.0f, u1 = 0.0f;
     row_join<W, NE, false>(m, u0, u1, e, sf, sd2);
