@@ -2,8 +2,9 @@
 batch-256 set (54 per-channel weights, 54 activations of 10.8 GB with oracle-made
 quantized-run partners) goes through ONE plan, as in bench.py, and every tensor is
 compared with the CPU oracle: parameters and all 2.7 G int8 codes bit-exact, sums, MSE,
-SQNR and the ranking to the stated bar.  The oracle runs on the host cores in a thread
-pool (one tensor per call), which takes about a minute."""
+SQNR and the ranking to the stated bar; the fused call and the single call (the pass the
+benchmark times) must then reproduce those records and codes.  The oracle runs on the host
+cores in a thread pool (one tensor per call), which takes about a minute."""
 import pytest
 import torch
 
@@ -34,6 +35,14 @@ def test_resnet50_batch256_full_pass():
     for f in ("sum_ref2", "sum_d2"):
         assert np.allclose(res2.pair[f], res.pair[f], rtol=1e-12, atol=0)
     assert all(torch.equal(a, it.codes) for a, it in zip(codes, items))
+    print("single call (the pass bench.py times) ...", flush=True)
+    del res, codes
+    codes2 = [it.codes for it in items]
+    res3 = H.run_gpu(items, fused="single")        # fresh code buffers
+    assert res3.params.tobytes() == res2.params.tobytes()
+    assert res3.sums.tobytes() == res2.sums.tobytes()
+    assert res3.pair.tobytes() == res2.pair.tobytes()
+    assert all(torch.equal(a, it.codes) for a, it in zip(codes2, items))
     del items
     torch.cuda.empty_cache()
 
