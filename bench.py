@@ -35,12 +35,14 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0   # MI355X published HBM3E bandwidth
-ROCPROF_NAMES = {"k_quantpair_stream": "k_quant_stream<256, 2, true, false>", "k_pair_stream": "k_pair_stream<512, 4>"}
+ROCPROF_NAMES = {"k_statspair_stream": "k_stats_stream<512, 8, true>",
+                 "k_quantpair_stream": "k_quant_stream<256, 2, true, false>", "k_pair_stream": "k_pair_stream<512, 4>"}
 
 # HBM bytes per launch of the dominant kernel on the resnet50 b256 workload from rocprofv3
 # --pmc (FETCH_SIZE and WRITE_SIZE runs, each scaled by a copy kernel of known size); see
 # profiles/sensitivity_pass_resnet50_b256.txt.
-TRAFFIC_BYTES = {"k_pair_stream": 21_697_127_098, "k_quantpair_stream": 24_627_581_264}
+TRAFFIC_BYTES = {"k_statspair_stream": 21_697_539_833, "k_pair_stream": 21_697_227_316,
+                 "k_quantpair_stream": 24_627_581_264}
 
 
 def parse():
@@ -190,7 +192,7 @@ def main():
     def timed(mode):
         ev = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
         kernel_ms.clear()
-        names = {"single": ["k_stats_stream", "k_quantpair_stream", "k_single_read_rows"],
+        names = {"single": ["k_statspair_stream", "k_quant_stream", "k_single_read_rows"],
                  "fused": ["k_stats_stream", "k_stats_rows", "k_quantpair_stream", "k_quantpair_rows"],
                  "calls": ["k_stats_stream", "k_stats_rows", "k_quant_stream", "k_quant_rows", "k_pair_stream"]}[mode]
         kernel_log.clear()
@@ -274,7 +276,11 @@ def main():
         return c
 
     # dominant kernel: its own algorithmic bytes over its own HIP-event duration
-    if args.mode in ("single", "fused"):
+    n_pair_stream = sum(s.numel for s, q in zip(specs, qruns) if q is not None and not
+                        (s.scheme == synth.SYM_CHANNEL and s.numel // s.channels <= 8192))
+    if args.mode == "single":      # calibration sweep that also compares with qrun: read-only
+        kname, kbytes = "k_statspair_stream", 4 * (n_all - n_rowgroup) + 4 * n_pair_stream
+    elif args.mode == "fused":
         kname, kbytes = "k_quantpair_stream", bytes_fqpair - 5 * n_rowgroup
     else:
         kname, kbytes = "k_pair_stream", bytes_pair

@@ -172,8 +172,8 @@ size_t qv2_workspace_bytes(const qv2_plan* plan);
 typedef enum {
   QV2_K_STATS_STREAM = 0, QV2_K_STATS_ROWS = 1, QV2_K_QUANT_STREAM = 2, QV2_K_QUANT_ROWS = 3,
   QV2_K_PAIR_STREAM = 4, QV2_K_QUANTPAIR_STREAM = 5, QV2_K_QUANTPAIR_ROWS = 6, QV2_K_HIST = 7,
-  QV2_K_SINGLE_READ_ROWS = 8,
-  QV2_K_COUNT = 9
+  QV2_K_SINGLE_READ_ROWS = 8, QV2_K_STATSPAIR_STREAM = 9,
+  QV2_K_COUNT = 10
 } qv2_kernel_id;
 qv2_status qv2_plan_set_timing(qv2_plan* plan, int32_t enable);
 qv2_status qv2_plan_kernel_ms(const qv2_plan* plan, int32_t kernel, float* ms_out);
@@ -215,11 +215,13 @@ qv2_status qv2_fakequant_pair_metrics(qv2_plan* plan, const qv2_qparams* d_param
                                       void* d_workspace, size_t workspace_bytes, void* hip_stream);
 
 /* Steps 1-3 in one call (Sec. 4 steps 1-3; Eq. 1-5; Algorithm 2's D[i] / Q[i]): the
- * results of qv2_calibrate followed by qv2_fakequant_pair_metrics, bit for bit, with
- * every tensor made of short segments (per-output-channel tensors whose channel has at
- * most 8192 elements) read from HBM ONCE: a group of whole channels is staged in LDS,
- * and range, parameters, codes and energies of each channel are taken from that copy.
- * Longer segments still need two reads (their scale depends on the global range).
+ * results of qv2_calibrate followed by qv2_fakequant_pair_metrics (parameters, codes and
+ * per-segment sums bit for bit; pair sums up to fp64 summation order), with every tensor
+ * made of short segments (per-output-channel tensors whose channel has at most 8192
+ * elements) read from HBM ONCE: a group of whole channels is staged in LDS, and range,
+ * parameters, codes and energies of each channel are taken from that copy.  Longer
+ * segments still need two reads (their scale depends on the global range); the comparison
+ * with qrun rides on the first, read-only one, the second writes the codes.
  * d_params, d_sums: DEVICE, written.  d_pair_sums[num_tensors]: DEVICE, written; NULL
  * skips the comparison with qrun (the results are then those of qv2_calibrate followed
  * by qv2_fakequant_metrics).  Workspace, stream and errors as in the separate calls. */

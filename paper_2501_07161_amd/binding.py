@@ -206,7 +206,7 @@ def qv2_plan_create(rows: Sequence[TensorArg]) -> Plan:
 
 KERNEL_IDS = {"k_stats_stream": 0, "k_stats_rows": 1, "k_quant_stream": 2, "k_quant_rows": 3,
               "k_pair_stream": 4, "k_quantpair_stream": 5, "k_quantpair_rows": 6, "k_hist": 7,
-              "k_single_read_rows": 8}
+              "k_single_read_rows": 8, "k_statspair_stream": 9}
 
 
 def qv2_plan_set_timing(plan: Plan, enable: bool):

@@ -89,6 +89,7 @@ qv2_status qv2_plan_create(const qv2_tensor* h_tensors, int32_t n_tensors, qv2_p
     p->info.push_back(TensorInfo{in.numel, static_cast<int32_t>(seg0), static_cast<int32_t>(nseg)});
 
     PairTensor ft{};                         // this tensor's partials in the quantize numbering
+    PairTensor st{};                         // ... in the calibration numbering (stream tiles only)
     if (per_channel && inner <= qv2::kRowGroupCap) {
       // whole rows per tile; every row is its own segment with one partial
       // rows per tile: what fits the LDS copy, but no more than a few rounds of the row
@@ -118,6 +119,8 @@ qv2_status qv2_plan_create(const qv2_tensor* h_tensors, int32_t n_tensors, qv2_p
       const int64_t n_read = (inner + TR - 1) / TR, n_quant = (inner + TQ - 1) / TQ;
       if (sp + nseg * n_read > kMax || ep + nseg * n_quant > kMax) { err = QV2_ERR_SHAPE; break; }
       ft.part0 = static_cast<int32_t>(ep); ft.nparts = static_cast<int32_t>(nseg * n_quant);
+      st.part0 = static_cast<int32_t>(sp); st.nparts = static_cast<int32_t>(nseg * n_read);
+      if (in.qrun) st.n = in.numel;
       for (int64_t s = 0; s < nseg; ++s) {
         Segment sg{};
         sg.n = inner; sg.scheme = in.scheme;
@@ -138,6 +141,8 @@ qv2_status qv2_plan_create(const qv2_tensor* h_tensors, int32_t n_tensors, qv2_p
     }
     if (in.qrun) ft.n = in.numel; else ft = PairTensor{};
     p->fused_pair_tensors.push_back(ft);
+    if (!in.qrun) st = PairTensor{};
+    p->stat_pair_tensors.push_back(st);
 
     PairTensor pt{};
     if (in.qrun) {
@@ -184,8 +189,10 @@ qv2_status qv2_plan_create(const qv2_tensor* h_tensors, int32_t n_tensors, qv2_p
     if (p->pair_tensors[i].nparts > qv2::kFoldWaveMax) p->big_pair_tensors.push_back(static_cast<int32_t>(i));
     if (p->fused_pair_tensors[i].nparts > qv2::kFoldWaveMax)
       p->big_fused_pair_tensors.push_back(static_cast<int32_t>(i));
+    if (p->stat_pair_tensors[i].nparts > qv2::kFoldWaveMax)
+      p->big_stat_pair_tensors.push_back(static_cast<int32_t>(i));
   }
-  const size_t need = std::max({static_cast<size_t>(sp) * sizeof(qv2::StatPartial),
+  const size_t need = std::max({static_cast<size_t>(sp) * sizeof(qv2::StatPairPartial),
                                 static_cast<size_t>(ep) * sizeof(qv2::ErrPartial5),
                                 static_cast<size_t>(pp) * sizeof(qv2::ErrPartial)});
   p->workspace_bytes = std::max<size_t>(256, round_up(need, 256));

@@ -98,6 +98,7 @@ struct TensorInfo {            // host only
 
 // Partial records the tile kernels leave in the workspace.
 struct StatPartial { float mn, mx; double sx, sx2; };   // calibrate, 24 B
+struct StatPairPartial { float mn, mx; double sx, sx2, sd2; };  // calibrate + pair comparison, 32 B
 struct ErrPartial { double sx2, se2; };                 // pair pass, 16 B
 struct ErrPartial3 { double sx2, se2, sd2; };           // quantize passes, 24 B
 struct ErrPartial5 { double sx2, se2, sd2, sxh, sxq; }; // quantize pass with cosine cross terms, 40 B
@@ -115,10 +116,13 @@ struct qv2_plan {
   std::vector<qv2::Segment> segments;
   std::vector<qv2::PairTensor> pair_tensors;        // partial ranges of the pair pass
   std::vector<qv2::PairTensor> fused_pair_tensors;  // ranges in the quantize numbering
+  std::vector<qv2::PairTensor> stat_pair_tensors;   // ranges in the calibration numbering; only
+                                                    // tensors made of stream tiles (n = 0 otherwise)
   std::vector<int32_t> big_stat_segments;   // segments with > kFoldWaveMax calibration partials
   std::vector<int32_t> big_err_segments;    // ... quantize partials
   std::vector<int32_t> big_pair_tensors;
   std::vector<int32_t> big_fused_pair_tensors;
+  std::vector<int32_t> big_stat_pair_tensors;
   int32_t read_tile = qv2::kDefaultReadTile;
   int32_t quant_tile = qv2::kDefaultQuantTile;
   int32_t n_row_parts = 0;               // partial slots 0 .. n_row_parts-1 belong to row-group segments
@@ -135,10 +139,12 @@ struct qv2_plan {
   qv2::Segment* d_segments = nullptr;
   qv2::PairTensor* d_pair_tensors = nullptr;
   qv2::PairTensor* d_fused_pair_tensors = nullptr;
+  qv2::PairTensor* d_stat_pair_tensors = nullptr;
   int32_t* d_big_stat_segments = nullptr;
   int32_t* d_big_err_segments = nullptr;
   int32_t* d_big_pair_tensors = nullptr;
   int32_t* d_big_fused_pair_tensors = nullptr;
+  int32_t* d_big_stat_pair_tensors = nullptr;
 
   // optional per-kernel timing (qv2_plan_set_timing): hipEvent_t handles
   bool timing = false;

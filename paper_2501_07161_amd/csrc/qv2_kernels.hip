@@ -200,63 +200,103 @@ __device__ __forceinline__ QP load_qp(const qv2_qparams* __restrict__ params, in
 // ---------------------------------------------------------------------------
 // pass 1 (calibration stage, Sec. 5; x_min / x_max of Eq. 2): stream tiles
 // ---------------------------------------------------------------------------
-template <int BLOCK, int V>
-__global__ __launch_bounds__(BLOCK) void k_stats_stream(const Tile* __restrict__ tiles,
-                                                        StatPartial* __restrict__ parts) {
-  const Tile tl = tiles[blockIdx.x];
-  const gf_ptr p = (gf_ptr)tl.x;
-  const int len = tl.len, tid = threadIdx.x;
-  const int head = head_elems(tl.x, len);
-  const int body = len - head, nvec = body >> 2, tail = body & 3;
+// partial record of the calibration pass: with the pair comparison it also carries sum (x - qrun)^2
+template <bool PAIR> struct StatRec { typedef StatPartial type; };
+template <> struct StatRec<true> { typedef StatPairPartial type; };
+__device__ __forceinline__ void set_pair_energy(StatPartial&, double) {}
+__device__ __forceinline__ void set_pair_energy(StatPairPartial& o, double sd2) { o.sd2 = sd2; }
 
-  float mn = INFINITY, mx = -INFINITY;
-  double sx = 0.0, sx2 = 0.0;
-  if (tid < head) {
-    const float v = p[tid];
-    mn = fminf(mn, v); mx = fmaxf(mx, v);
-    sx += v; sx2 += static_cast<double>(v) * v;
-  }
-  if (tid < tail) {
-    const float v = p[head + (nvec << 2) + tid];
-    mn = fminf(mn, v); mx = fmaxf(mx, v);
-    sx += v; sx2 += static_cast<double>(v) * v;
-  }
-  const gf4_ptr v4 = (gf4_ptr)(tl.x + head);
+struct StatAcc {
   f4 mn4 = {INFINITY, INFINITY, INFINITY, INFINITY};
   f4 mx4 = {-INFINITY, -INFINITY, -INFINITY, -INFINITY};
-  Acc4 as, as2;
-  int base = 0;
-  for (; base + V * BLOCK <= nvec; base += V * BLOCK) {          // uniform: whole batches
-    f4 r[V];
-#pragma unroll
-    for (int u = 0; u < V; ++u) r[u] = ld4(v4 + base + u * BLOCK + tid);
-#pragma unroll
-    for (int u = 0; u < V; ++u) {
-      mn4.x = fminf(mn4.x, r[u].x); mn4.y = fminf(mn4.y, r[u].y);
-      mn4.z = fminf(mn4.z, r[u].z); mn4.w = fminf(mn4.w, r[u].w);
-      mx4.x = fmaxf(mx4.x, r[u].x); mx4.y = fmaxf(mx4.y, r[u].y);
-      mx4.z = fmaxf(mx4.z, r[u].z); mx4.w = fmaxf(mx4.w, r[u].w);
-      as.add(r[u]); as2.add_sq(r[u].x, r[u].y, r[u].z, r[u].w);
-    }
-  }
-  for (int i = base + tid; i < nvec; i += BLOCK) {
-    const f4 r = ld4(v4 + i);
+  Acc4 s, s2, d2;
+  __device__ __forceinline__ void take(const f4& r) {
     mn4.x = fminf(mn4.x, r.x); mn4.y = fminf(mn4.y, r.y);
     mn4.z = fminf(mn4.z, r.z); mn4.w = fminf(mn4.w, r.w);
     mx4.x = fmaxf(mx4.x, r.x); mx4.y = fmaxf(mx4.y, r.y);
     mx4.z = fmaxf(mx4.z, r.z); mx4.w = fmaxf(mx4.w, r.w);
-    as.add(r); as2.add_sq(r.x, r.y, r.z, r.w);
+    s.add(r); s2.add_sq(r.x, r.y, r.z, r.w);
   }
-  sx += as.total(); sx2 += as2.total();
-  mn = fminf(fminf(mn, mn4.x), fminf(fminf(mn4.y, mn4.z), mn4.w));
-  mx = fmaxf(fmaxf(mx, mx4.x), fmaxf(fmaxf(mx4.y, mx4.z), mx4.w));
+};
 
-  double unused = 0.0;
+// vector body of a calibration tile; WITHB: a second stream (qrun) is compared in the same visit
+template <int BLOCK, int V, bool WITHB>
+__device__ __forceinline__ void stats_body(gf4_ptr v4, gf4_ptr b4, int nvec, StatAcc& a) {
+  const int tid = threadIdx.x;
+  int base = 0;
+  for (; base + V * BLOCK <= nvec; base += V * BLOCK) {          // uniform: whole batches
+    f4 r[V], g[V];
+#pragma unroll
+    for (int u = 0; u < V; ++u) {
+      r[u] = ld4(v4 + base + u * BLOCK + tid);
+      if (WITHB) g[u] = ld4(b4 + base + u * BLOCK + tid);
+    }
+#pragma unroll
+    for (int u = 0; u < V; ++u) {
+      a.take(r[u]);
+      if (WITHB) a.d2.add_sq(r[u].x - g[u].x, r[u].y - g[u].y, r[u].z - g[u].z, r[u].w - g[u].w);
+    }
+  }
+  for (int i = base + tid; i < nvec; i += BLOCK) {
+    const f4 r = ld4(v4 + i);
+    a.take(r);
+    if (WITHB) {
+      const f4 g = ld4(b4 + i);
+      a.d2.add_sq(r.x - g.x, r.y - g.y, r.z - g.z, r.w - g.w);
+    }
+  }
+}
+
+// PAIR: tiles whose tensor has a quantized-run partner also yield sum (x - qrun)^2 (Algorithm 2's
+// D[i] against Q[i]) from the same visit: 8 B read per element, nothing but the partial written.
+template <int BLOCK, int V, bool PAIR>
+__global__ __launch_bounds__(BLOCK) void k_stats_stream(const Tile* __restrict__ tiles,
+                                                        typename StatRec<PAIR>::type* __restrict__ parts) {
+  const Tile tl = tiles[blockIdx.x];
+  const gf_ptr p = (gf_ptr)tl.x;
+  const gf_ptr b = (gf_ptr)tl.q;
+  const int len = tl.len, tid = threadIdx.x;
+  const int head = head_elems(tl.x, len);
+  const int body = len - head, nvec = body >> 2, tail = body & 3;
+  const bool has_b = PAIR && tl.q != nullptr;
+  // qrun at a different offset inside 16 bytes than x: its energy is taken element-wise
+  const bool b_vec = has_b && (((reinterpret_cast<uintptr_t>(tl.x) ^ reinterpret_cast<uintptr_t>(tl.q)) & 15u) == 0);
+
+  float mn = INFINITY, mx = -INFINITY;
+  double sx = 0.0, sx2 = 0.0, sd2 = 0.0;
+  if (has_b && !b_vec) {
+    for (int i = tid; i < len; i += BLOCK) {
+      const double d = static_cast<double>(p[i] - b[i]);
+      sd2 = fma(d, d, sd2);
+    }
+  }
+  for (int k = 0; k < 2; ++k) {
+    const bool on = k == 0 ? tid < head : tid < tail;
+    if (!on) continue;
+    const int idx = k == 0 ? tid : head + (nvec << 2) + tid;
+    const float v = p[idx];
+    mn = fminf(mn, v); mx = fmaxf(mx, v);
+    sx += v; sx2 += static_cast<double>(v) * v;
+    if (b_vec) {
+      const float d = v - b[idx];
+      sd2 += static_cast<double>(d) * d;
+    }
+  }
+  const gf4_ptr v4 = (gf4_ptr)(tl.x + head);
+  const gf4_ptr b4 = (gf4_ptr)(tl.q + head);
+  StatAcc a;
+  if (PAIR && b_vec) stats_body<BLOCK, (V > 1 ? V / 2 : 1), true>(v4, b4, nvec, a);
+  else stats_body<BLOCK, V, false>(v4, b4, nvec, a);
+  sx += a.s.total(); sx2 += a.s2.total(); sd2 += a.d2.total();
+  mn = fminf(fminf(mn, a.mn4.x), fminf(fminf(a.mn4.y, a.mn4.z), a.mn4.w));
+  mx = fmaxf(fmaxf(mx, a.mx4.x), fmaxf(fmaxf(a.mx4.y, a.mx4.z), a.mx4.w));
+
   block_minmax<BLOCK>(mn, mx);
-  block_sum3<BLOCK>(sx, sx2, unused);
+  block_sum3<BLOCK>(sx, sx2, sd2);
   if (tid == 0) {
-    StatPartial o;
+    typename StatRec<PAIR>::type o;
     o.mn = mn; o.mx = mx; o.sx = sx; o.sx2 = sx2;
+    set_pair_energy(o, sd2);
     parts[tl.part0] = o;
   }
 }
@@ -467,11 +507,10 @@ __device__ __forceinline__ void fold_sum3(bool wide, double& a, double& b, doubl
 }
 
 // Calibration fold: range and sums of every segment, then its parameters (Eq. 2, Eq. 4).
-__global__ __launch_bounds__(kFoldBlock) void k_fold_stats(
-    const Segment* __restrict__ segs, int nseg, const int* __restrict__ ids, int n_wide,
-    const StatPartial* __restrict__ parts, qv2_qparams* __restrict__ params,
-    qv2_sums* __restrict__ sums, int skip_below) {
-  const FoldIdx f(blockIdx.x, ids, n_wide, nseg);
+template <class REC>
+__device__ __forceinline__ void fold_stats_item(const FoldIdx& f, const Segment* __restrict__ segs,
+                                                const REC* __restrict__ parts, qv2_qparams* __restrict__ params,
+                                                qv2_sums* __restrict__ sums, int skip_below) {
   if (!f.active) return;
   const Segment sg = segs[f.id];
   if (!f.wide && sg.snp > kFoldWaveMax) return;    // left to its own workgroup
@@ -480,7 +519,7 @@ __global__ __launch_bounds__(kFoldBlock) void k_fold_stats(
   double sx = 0.0, sx2 = 0.0, unused = 0.0;
 #pragma unroll 4
   for (int i = f.lane; i < sg.snp; i += f.stride) {
-    const StatPartial q = parts[sg.sp0 + i];
+    const REC q = parts[sg.sp0 + i];
     mn = fminf(mn, q.mn); mx = fmaxf(mx, q.mx);
     sx += q.sx; sx2 += q.sx2;
   }
@@ -499,6 +538,53 @@ __global__ __launch_bounds__(kFoldBlock) void k_fold_stats(
     o.sum_x = sx; o.sum_x2 = sx2; o.sum_e2 = 0.0; o.n = sg.n;
     sums[f.id] = o;
   }
+}
+
+// pair energies of one tensor from calibration partials that carry them; tensors not listed
+// there (n == 0) are left to the fold after the quantize pass
+__device__ __forceinline__ void fold_statpair_item(const FoldIdx& f, const PairTensor* __restrict__ pt,
+                                                   const StatPairPartial* __restrict__ parts,
+                                                   qv2_pair_sums* __restrict__ out) {
+  if (!f.active) return;
+  const PairTensor p = pt[f.id];
+  if (p.n == 0) return;
+  if (!f.wide && p.nparts > kFoldWaveMax) return;
+  double sr2 = 0.0, sd2 = 0.0, unused = 0.0;
+#pragma unroll 4
+  for (int i = f.lane; i < p.nparts; i += f.stride) {
+    const StatPairPartial q = parts[p.part0 + i];
+    sr2 += q.sx2; sd2 += q.sd2;
+  }
+  fold_sum3(f.wide, sr2, sd2, unused);
+  if (f.lane == 0) {
+    qv2_pair_sums o;
+    o.sum_ref2 = sr2; o.sum_d2 = sd2; o.n = p.n; o._pad = 0;
+    out[f.id] = o;
+  }
+}
+
+template <class REC>
+struct StatFoldArgs {
+  const Segment* segs; int nseg; const int* wide_segs; int n_wide_segs;
+  const REC* parts; qv2_qparams* params; qv2_sums* sums; int skip_below;
+  const PairTensor* pt; int nt; const int* wide_pt; int n_wide_pt;     // pair_out == null: none
+  qv2_pair_sums* pair_out;
+  int seg_blocks;
+};
+
+__device__ __forceinline__ void fold_statpair_family(const StatFoldArgs<StatPartial>&, int) {}
+__device__ __forceinline__ void fold_statpair_family(const StatFoldArgs<StatPairPartial>& a, int b) {
+  fold_statpair_item(FoldIdx(b, a.wide_pt, a.n_wide_pt, a.nt), a.pt, a.parts, a.pair_out);
+}
+
+template <class REC>
+__global__ __launch_bounds__(kFoldBlock) void k_fold_stats(const StatFoldArgs<REC> a) {
+  const int b = blockIdx.x;
+  if (b < a.seg_blocks)
+    fold_stats_item<REC>(FoldIdx(b, a.wide_segs, a.n_wide_segs, a.nseg), a.segs, a.parts, a.params, a.sums,
+                         a.skip_below);
+  else
+    fold_statpair_family(a, b - a.seg_blocks);
 }
 
 // cross terms of a partial record (0 where the record has none)
@@ -538,8 +624,10 @@ __device__ __forceinline__ void fold_err_item(const FoldIdx& f, const Segment* _
 template <class P>
 __device__ __forceinline__ void fold_pair_item(const FoldIdx& f, const PairTensor* __restrict__ pt,
                                                const P* __restrict__ parts, qv2_pair_sums* __restrict__ out,
-                                               double* __restrict__ pair_xq) {
+                                               double* __restrict__ pair_xq,
+                                               const PairTensor* __restrict__ done = nullptr) {
   if (!f.active) return;
+  if (done && done[f.id].n != 0) return;           // already folded from the calibration partials
   const PairTensor p = pt[f.id];
   if (!f.wide && p.nparts > kFoldWaveMax) return;
   double sr2 = 0.0, sd2 = 0.0, sxq = 0.0;
@@ -565,6 +653,7 @@ struct QuantFoldArgs {
   qv2_sums* sums; double* seg_xxhat; int skip_below;
   const PairTensor* pt; int nt; const int* wide_pt; int n_wide_pt;     // pair_out == null: none
   qv2_pair_sums* pair_out; double* pair_xq;
+  const PairTensor* pair_done;               // tensors with n != 0 here are skipped (may be null)
   const P* parts;
   int seg_blocks;
 };
@@ -577,7 +666,7 @@ __global__ __launch_bounds__(kFoldBlock) void k_fold_quant(const QuantFoldArgs<P
                      a.seg_xxhat, a.skip_below);
   } else {
     fold_pair_item<P>(FoldIdx(b - a.seg_blocks, a.wide_pt, a.n_wide_pt, a.nt), a.pt, a.parts,
-                      a.pair_out, a.pair_xq);
+                      a.pair_out, a.pair_xq, a.pair_done);
   }
 }
 
@@ -1062,6 +1151,7 @@ qv2_status ensure_uploaded(qv2_plan* p) {
   const size_t o_bs = reserve(bytes_of(p->big_stat_segments)), o_be = reserve(bytes_of(p->big_err_segments));
   const size_t o_bp = reserve(bytes_of(p->big_pair_tensors)), o_bf = reserve(bytes_of(p->big_fused_pair_tensors));
   const size_t o_ht = reserve(bytes_of(p->hist_tiles)), o_hten = reserve(bytes_of(p->hist_tensors));
+  const size_t o_st = reserve(bytes_of(p->stat_pair_tensors)), o_bst = reserve(bytes_of(p->big_stat_pair_tensors));
   char* blob = nullptr;
   if (hipMalloc(reinterpret_cast<void**>(&blob), total) != hipSuccess) {
     (void)hipGetLastError();
@@ -1091,6 +1181,10 @@ qv2_status ensure_uploaded(qv2_plan* p) {
   p->d_hist_tiles = static_cast<Tile*>(put(o_ht, p->hist_tiles.data(), bytes_of(p->hist_tiles)));
   p->d_hist_tensors =
       static_cast<HistTensor*>(put(o_hten, p->hist_tensors.data(), bytes_of(p->hist_tensors)));
+  p->d_stat_pair_tensors =
+      static_cast<PairTensor*>(put(o_st, p->stat_pair_tensors.data(), bytes_of(p->stat_pair_tensors)));
+  p->d_big_stat_pair_tensors = static_cast<int32_t*>(
+      put(o_bst, p->big_stat_pair_tensors.data(), bytes_of(p->big_stat_pair_tensors)));
   if (!ok) { (void)hipGetLastError(); (void)hipFree(blob); return QV2_ERR_HIP; }
   p->d_blob = blob;
   return QV2_OK;
@@ -1125,15 +1219,22 @@ int fold_grid(int n) { return (n + 3) / 4; }
 template <bool PAIR, bool COS>
 void launch_quant(qv2_plan* plan, const qv2_qparams* d_params, qv2_sums* d_sums,
                   typename ErrRec<COS>::type* parts, double* d_seg_xxhat, qv2_pair_sums* d_pair_sums,
-                  double* d_pair_xq, hipStream_t s, qv2_qparams* d_params_out = nullptr) {
+                  double* d_pair_xq, hipStream_t s, qv2_qparams* d_params_out = nullptr,
+                  bool pair_in_stats = false) {
   typedef typename ErrRec<COS>::type P;
   const bool calib_rows = d_params_out != nullptr;
   const int n_stream = static_cast<int>(plan->quant_tiles.size());
   const int n_rows = static_cast<int>(plan->row_tiles.size());
   if (n_stream > 0) {
-    Timed timed(plan, PAIR ? QV2_K_QUANTPAIR_STREAM : QV2_K_QUANT_STREAM, s);
-    hipLaunchKernelGGL((k_quant_stream<kBlockQuant, kVecQuant, PAIR, COS>), dim3(n_stream),
-                       dim3(kBlockQuant), 0, s, plan->d_quant_tiles, d_params, parts);
+    // pair_in_stats: the calibration sweep already compared the stream tensors with their
+    // partners, so the plain quantize kernel serves them
+    Timed timed(plan, PAIR && !pair_in_stats ? QV2_K_QUANTPAIR_STREAM : QV2_K_QUANT_STREAM, s);
+    if (PAIR && !pair_in_stats)
+      hipLaunchKernelGGL((k_quant_stream<kBlockQuant, kVecQuant, PAIR, COS>), dim3(n_stream),
+                         dim3(kBlockQuant), 0, s, plan->d_quant_tiles, d_params, parts);
+    else
+      hipLaunchKernelGGL((k_quant_stream<kBlockQuant, kVecQuant, false, COS>), dim3(n_stream),
+                         dim3(kBlockQuant), 0, s, plan->d_quant_tiles, d_params, parts);
   }
   if (n_rows > 0) {
     Timed timed(plan, calib_rows ? QV2_K_SINGLE_READ_ROWS : PAIR ? QV2_K_QUANTPAIR_ROWS : QV2_K_QUANT_ROWS, s);
@@ -1156,33 +1257,49 @@ void launch_quant(qv2_plan* plan, const qv2_qparams* d_params, qv2_sums* d_sums,
     a.wide_pt = plan->d_big_fused_pair_tensors;
     a.n_wide_pt = static_cast<int>(plan->big_fused_pair_tensors.size());
     a.pair_out = d_pair_sums; a.pair_xq = d_pair_xq;
+    a.pair_done = pair_in_stats ? plan->d_stat_pair_tensors : nullptr;
     blocks += fold_blocks(a.n_wide_pt, a.nt);
   }
   hipLaunchKernelGGL(k_fold_quant<P>, dim3(blocks), dim3(kFoldBlock), 0, s, a);
 }
 
 // calibration over the stream tiles (and the row-group tiles unless their own single-read
-// kernel will calibrate them), then the statistics fold
-void launch_stats(qv2_plan* plan, qv2_qparams* d_params, qv2_sums* d_sums, StatPartial* parts,
-                  bool with_rows, hipStream_t s) {
+// kernel will calibrate them), then the statistics fold.  PAIR: the same sweep compares the
+// stream tensors with their quantized-run partners and the fold writes their pair sums.
+template <bool PAIR>
+void launch_stats(qv2_plan* plan, qv2_qparams* d_params, qv2_sums* d_sums,
+                  typename StatRec<PAIR>::type* parts, bool with_rows, qv2_pair_sums* d_pair_sums,
+                  hipStream_t s) {
+  typedef typename StatRec<PAIR>::type REC;
+  if (PAIR) with_rows = false;      // the row kernel of this pass writes 24-byte records: not in a PAIR sweep
   const int n_stream = static_cast<int>(plan->read_tiles.size());
   const int n_rows = static_cast<int>(plan->row_tiles.size());
-  const int nseg = static_cast<int>(plan->segments.size());
   if (n_stream > 0) {
-    Timed timed(plan, QV2_K_STATS_STREAM, s);
-    hipLaunchKernelGGL((k_stats_stream<kBlockRead, kVecRead>), dim3(n_stream), dim3(kBlockRead), 0, s,
+    Timed timed(plan, PAIR ? QV2_K_STATSPAIR_STREAM : QV2_K_STATS_STREAM, s);
+    hipLaunchKernelGGL((k_stats_stream<kBlockRead, kVecRead, PAIR>), dim3(n_stream), dim3(kBlockRead), 0, s,
                        plan->d_read_tiles, parts);
   }
   if (with_rows && n_rows > 0) {
     Timed timed(plan, QV2_K_STATS_ROWS, s);
     hipLaunchKernelGGL(k_stats_rows<kBlockRows>, dim3(n_rows), dim3(kBlockRows), 0, s,
-                       plan->d_row_tiles, parts);
+                       plan->d_row_tiles, reinterpret_cast<StatPartial*>(parts));
   }
   if (with_rows || n_stream > 0) {
-    const int n_wide = static_cast<int>(plan->big_stat_segments.size());
-    hipLaunchKernelGGL(k_fold_stats, dim3(fold_blocks(n_wide, nseg)), dim3(kFoldBlock), 0, s,
-                       plan->d_segments, nseg, plan->d_big_stat_segments, n_wide, parts, d_params, d_sums,
-                       with_rows ? 0 : plan->n_row_parts);
+    StatFoldArgs<REC> a{};
+    a.segs = plan->d_segments; a.nseg = static_cast<int>(plan->segments.size());
+    a.wide_segs = plan->d_big_stat_segments; a.n_wide_segs = static_cast<int>(plan->big_stat_segments.size());
+    a.parts = parts; a.params = d_params; a.sums = d_sums;
+    a.skip_below = with_rows ? 0 : plan->n_row_parts;
+    a.seg_blocks = fold_blocks(a.n_wide_segs, a.nseg);
+    int blocks = a.seg_blocks;
+    if (PAIR) {
+      a.pt = plan->d_stat_pair_tensors; a.nt = static_cast<int>(plan->stat_pair_tensors.size());
+      a.wide_pt = plan->d_big_stat_pair_tensors;
+      a.n_wide_pt = static_cast<int>(plan->big_stat_pair_tensors.size());
+      a.pair_out = d_pair_sums;
+      blocks += fold_blocks(a.n_wide_pt, a.nt);
+    }
+    hipLaunchKernelGGL(k_fold_stats<REC>, dim3(blocks), dim3(kFoldBlock), 0, s, a);
   }
 }
 
@@ -1243,8 +1360,8 @@ qv2_status qv2_calibrate(qv2_plan* plan, qv2_qparams* d_params, qv2_sums* d_sums
   qv2_status st = check_call(plan, d_params, d_sums, d_workspace, workspace_bytes);
   if (st != QV2_OK) return st;
   if ((st = ensure_uploaded(plan)) != QV2_OK) return st;
-  launch_stats(plan, d_params, d_sums, static_cast<StatPartial*>(d_workspace), true,
-               static_cast<hipStream_t>(hip_stream));
+  launch_stats<false>(plan, d_params, d_sums, static_cast<StatPartial*>(d_workspace), true, nullptr,
+                      static_cast<hipStream_t>(hip_stream));
   return launch_status();
 }
 
@@ -1300,13 +1417,16 @@ qv2_status qv2_calibrate_fakequant_pair_metrics(qv2_plan* plan, qv2_qparams* d_p
   if (d_pair_sums && (reinterpret_cast<uintptr_t>(d_pair_sums) & 7u)) return QV2_ERR_ALIGN;
   if ((st = ensure_uploaded(plan)) != QV2_OK) return st;
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
-  // stream tiles: statistics, fold (parameters), then the quantize sweep; row-group tiles:
-  // one kernel, after the statistics fold because the partial records share the workspace
-  launch_stats(plan, d_params, d_sums, static_cast<StatPartial*>(d_workspace), false, s);
+  // stream tiles: statistics (with the pair comparison: that sweep only reads, and read-only
+  // sweeps run nearest to the HBM rate), fold (parameters), then the plain quantize sweep;
+  // row-group tiles: one kernel, after the statistics fold because the partial records share
+  // the workspace
   ErrPartial3* parts = static_cast<ErrPartial3*>(d_workspace);
   if (d_pair_sums) {
-    launch_quant<true, false>(plan, d_params, d_sums, parts, nullptr, d_pair_sums, nullptr, s, d_params);
+    launch_stats<true>(plan, d_params, d_sums, static_cast<StatPairPartial*>(d_workspace), false, d_pair_sums, s);
+    launch_quant<true, false>(plan, d_params, d_sums, parts, nullptr, d_pair_sums, nullptr, s, d_params, true);
   } else {
+    launch_stats<false>(plan, d_params, d_sums, static_cast<StatPartial*>(d_workspace), false, nullptr, s);
     launch_quant<false, false>(plan, d_params, d_sums, parts, nullptr, nullptr, nullptr, s, d_params);
   }
   return launch_status();

@@ -213,10 +213,11 @@ def test_fused_call_equals_the_two_separate_calls():
     assert all(torch.equal(a, it.codes) for a, it in zip(c1, items))
 
 
-def test_single_call_pass_is_bit_identical_to_the_separate_calls():
+def test_single_call_pass_equals_the_separate_calls():
     """qv2_calibrate_fakequant_pair_metrics (row-group tensors read from HBM once) against
-    qv2_calibrate + qv2_fakequant_pair_metrics: parameters, sums, pair sums and codes equal
-    bit for bit; without pair sums it equals qv2_calibrate + qv2_fakequant_metrics."""
+    qv2_calibrate + qv2_fakequant_pair_metrics: parameters, sums and codes equal bit for bit,
+    pair sums up to fp64 summation order; without pair sums it equals qv2_calibrate +
+    qv2_fakequant_metrics."""
     specs = synth.config_mobilenetv2(2) + synth.config_resnet50(2) + synth.config_tiny()
     items = H.items_from_specs(specs, DEV)
     for i, it in enumerate(items):
@@ -230,7 +231,9 @@ def test_single_call_pass_is_bit_identical_to_the_separate_calls():
     assert r2.plan.num_tiles > r2.plan.num_tensors          # row-group and stream tiles both present
     assert r1.params.tobytes() == r2.params.tobytes()
     assert r1.sums.tobytes() == r2.sums.tobytes()
-    assert r1.pair.tobytes() == r2.pair.tobytes()
+    assert np.array_equal(r1.pair["n"], r2.pair["n"])
+    for f in ("sum_ref2", "sum_d2"):        # taken in the calibration sweep: other tile lengths
+        assert np.allclose(r1.pair[f], r2.pair[f], rtol=1e-12, atol=0)
     assert all(torch.equal(a, it.codes) for a, it in zip(c1, items))
     # no pair sums: the plain fake-quant results
     r3 = H.run_gpu(items)
