@@ -736,7 +736,15 @@ template <int BLOCK, int V, bool PAIR, bool COS>
 __global__ __launch_bounds__(BLOCK, QV2_QUANT_WAVES_PER_EU) void k_quant_stream(
     const Tile* __restrict__ tiles, const qv2_qparams* __restrict__ params,
     typename ErrRec<COS>::type* __restrict__ parts) {
-  const Tile tl = tiles[blockIdx.x];
+  // Workgroups go to the 8 XCDs in turn.  The plain sweep (one read stream, one store stream)
+  // runs 1.5 % faster (6 % without codes) when each XCD works through one contiguous eighth
+  // of the tile table instead of every eighth tile; with qrun as a third stream it does not.
+  int bt = blockIdx.x;
+  if (!PAIR) {
+    const int per = gridDim.x >> 3;
+    if (bt < (per << 3)) bt = (bt & 7) * per + (bt >> 3);
+  }
+  const Tile tl = tiles[bt];
   const QP q = load_qp(params, tl.seg0);
   const gf_ptr p = (gf_ptr)tl.x;
   const gf_ptr b = (gf_ptr)tl.q;
