@@ -14,6 +14,8 @@
  *      in the quantized inference (Algorithm 2, D[i] vs Q[i]) -> qv2_pair_metrics
  *   4. SQNR delta (Sec. 6.4 Eq. 16) and the sensitivity list
  *      (Algorithm 2, RankLayersBySensitivity)               -> qv2_rank
+ * Steps 1-3 are also available as one call that visits every tensor as few
+ * times as the method allows       -> qv2_calibrate_fakequant_pair_metrics
  *
  * Conventions
  *  - Pointers named d_* are DEVICE pointers, h_* are HOST pointers.  Every

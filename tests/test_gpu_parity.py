@@ -33,7 +33,7 @@ def test_config_tiny(fused):
     assert res.params["min"][1] == 0.0 and res.params["zp"][1] == -128
 
 
-@pytest.mark.parametrize("fused", [False, True])
+@pytest.mark.parametrize("fused", [False, True, "single"])
 def test_config_resnet18_batch32(fused):
     """ResNet-18 shapes at the stated batch: 21 weights + 21 activations, per-tensor asymmetric."""
     items, res, order = _run_config(synth.config_resnet18(32), fused=fused)
@@ -73,7 +73,7 @@ def _rand(n, seed, scale=1.0):
     return torch.randn(n, generator=g, device=DEV) * scale
 
 
-@pytest.mark.parametrize("fused", [False, True])
+@pytest.mark.parametrize("fused", [False, True, "single"])
 def test_ragged_lengths_and_unaligned_pointers(fused):
     """Lengths around tile and vector boundaries, inputs starting 4 / 8 / 12 bytes past a
     16-byte boundary, code buffers starting 1..3 bytes past a 4-byte boundary."""
@@ -116,7 +116,7 @@ def test_per_channel_row_shapes(fused):
     H.check_all(items, res)
 
 
-@pytest.mark.parametrize("fused", [False, True])
+@pytest.mark.parametrize("fused", [False, True, "single"])
 def test_degenerate_and_special_values(fused):
     z = torch.zeros(5000, device=DEV)
     const = torch.full((4097,), 3.25, device=DEV)
