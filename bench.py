@@ -60,6 +60,9 @@ def parse():
     ap.add_argument("--single-mode", action="store_true", help="do not also time the other mode")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-elems", type=int, default=2_000_000_000)
+    ap.add_argument("--cold", action="store_true",
+                    help="also time every step after streaming a 1 GiB scratch buffer (evicts the 256 MB "
+                         "Infinity Cache); matters only for sets that are not far larger than that cache")
     ap.add_argument("--copy-probe", action="store_true",
                     help="after the timed region also run 3 plain 1 GiB device copies (a kernel of known "
                          "traffic, used to scale rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
@@ -218,6 +221,19 @@ def main():
         return r
 
     main_r = timed(args.mode)
+    cold_ms = None
+    if args.cold:
+        scratch = torch.empty(1 << 28, dtype=torch.float32, device=dev)
+        ts = []
+        for _ in range(args.steps):
+            scratch.fill_(1.0)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            step(args.mode)
+            torch.cuda.synchronize()
+            ts.append(time.perf_counter() - t0)
+        cold_ms = float(np.mean(ts)) * 1e3
+        del scratch
     other_mode = "fused" if args.mode == "calls" else "calls"
     other = None if args.single_mode else timed(other_mode)
 
@@ -315,6 +331,9 @@ def main():
     macs = synth.layer_macs(tables[args.workload]())
     out["bops_cut_layers_kept_fp32"] = {str(t): qb.qv2_bops_select(last["order"], macs, float(t))[1]
                                         for t in (60, 50, 40, 30, 20)}
+    if cold_ms is not None:
+        out["cold"] = {"ms_per_step": round(cold_ms, 4), "hbm_GBps": round(moved / cold_ms / 1e6, 2),
+                       "note": "each step timed alone after a 1 GiB fill; the default figure times steps back to back"}
     if extras:
         out["extras"] = extras
     if other is not None:
