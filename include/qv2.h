@@ -148,6 +148,8 @@ typedef struct qv2_plan qv2_plan;
  * not dividing numel (or != 1 for per-tensor schemes), more than 2^31-1 tiles
  * or segments -> ERR_SHAPE; unknown scheme -> ERR_SCHEME; x (or qrun) not
  * 4-byte aligned -> ERR_ALIGN; x NULL -> ERR_NULL. */
+/* Tile lengths can be overridden for tuning with the environment variables QV2_TILE_ELEMS
+ * (read-only sweeps) and QV2_QUANT_TILE_ELEMS (quantize sweeps), read here. */
 qv2_status qv2_plan_create(const qv2_tensor* h_tensors, int32_t n_tensors, qv2_plan** out);
 void qv2_plan_destroy(qv2_plan* plan);
 

@@ -140,6 +140,27 @@ def test_degenerate_and_special_values(fused):
     assert np.all(res.pair["sum_d2"] == 0.0) and np.all(np.isinf(res.pair_sqnr))   # identical pairs
 
 
+@pytest.mark.parametrize("fused", [False, True, "single"])
+def test_many_small_tiles(fused, monkeypatch):
+    """Tile lengths forced down to 512 / 256 elements (tuning knobs read when a plan is made):
+    medium tensors then span hundreds to thousands of tiles, so the one-wavefront and the
+    whole-workgroup folds, ragged last tiles and per-channel rows cut into several tiles are all
+    exercised on inputs the oracle still finishes in seconds."""
+    monkeypatch.setenv("QV2_TILE_ELEMS", "512")
+    monkeypatch.setenv("QV2_QUANT_TILE_ELEMS", "256")
+    items = []
+    for i, n in enumerate([1, 255, 256, 257, 511, 513, 9_999, 65_537, 300_001, 1_000_003]):
+        x = _rand(n + 4, 600 + i)[i % 4: i % 4 + n]
+        q = x * 0.99 + 0.002 if i % 3 != 1 else None
+        items.append(H.Item(f"t{n}", x, A if i % 2 else S, 1, 1, len(items), qrun=q, codes_offset=i % 4))
+    for i, (c, inner) in enumerate([(3, 8193), (5, 20_001), (2, 70_001), (40, 300)]):
+        x = _rand(c * inner + 4, 700 + i, 0.2)[1: 1 + c * inner]
+        items.append(H.Item(f"rows{c}x{inner}", x, C, c, 0, len(items), qrun=x * 1.01 if i % 2 == 0 else None))
+    res = H.run_gpu(items, fused=fused)
+    assert res.plan.num_quant_tiles > 6000
+    H.check_all(items, res)
+
+
 def test_cached_params_clip_both_ends():
     """Parameters handed in by the caller (the calibration cache) instead of calibrating:
     a range narrower than the data saturates codes at -128 and 127."""
