@@ -83,7 +83,7 @@ typedef struct {
 } qv2_tensor;
 
 /* Per segment (a whole tensor, or one output channel).  This array is the
- * "calibration cache" of Sec. 5: it may be saved and handed back to
+ * calibration cache of Sec. 5: it may be saved and handed back to
  * qv2_fakequant_metrics without recalibrating. */
 typedef struct {
   float min, max;          /* -0.0 is reported as +0.0                            */
@@ -364,8 +364,8 @@ qv2_status qv2_bops_select(const int32_t* order, const double* macs, int32_t n_l
                            double target_pct, uint8_t* keep_fp32_out, int32_t* n_keep_out,
                            double* achieved_pct_out);
 
-/* Fusion-aware adjustment of a sensitivity list (Sec. 6.5 says only that positions of
- * fusion-capable operators "can be adjusted"; this is the reading taken): layers with the
+/* Fusion-aware adjustment of a sensitivity list (Sec. 6.5 only allows the positions of
+ * fusion-capable operators to change and gives no rule; this is the reading taken): layers with the
  * same group_id (a convolution and the BN / Add / ReLU neighbours it fuses with) keep one
  * precision, so each group moves as a block to the position of its most sensitive member;
  * list order is kept inside a block and between blocks.  order_out may not alias order.

@@ -11,6 +11,11 @@ Per-segment conventions: a tensor is one segment (per-tensor schemes) or
 the paper does not mention per-channel quantization -- Sec. 4 Eq. 4 is applied
 to each output channel on its own, and a tensor's MSE / SQNR are formed from
 the sums of its channels' sums).
+
+Parity unpinned (the paper prints no value or rule to check against; the functions are pinned
+to their stated readings only): the default gains alpha_w = 0.6 / alpha_a = 0.4 of
+``rank_layers``, the smoothing constant ``eps`` of ``kl_divergence`` (no default), the histogram
+binning rule of ``histogram``, and the block-move rule of ``regroup_for_fusion``.
 """
 from __future__ import annotations
 
@@ -294,7 +299,7 @@ def pair_metrics(ref, qrun) -> PairMetrics:
 # ----------------------------------------------------------------------------
 @dataclass
 class RankConfig:
-    alpha_w: float = 0.6       # gain of the weight SQNR delta ("more" than activation; value not printed)
+    alpha_w: float = 0.6       # gain of the weight SQNR delta (larger than the activation's; the value is not printed)
     alpha_a: float = 0.4       # gain of the activation SQNR delta
     mse_factor: float = 5.0    # Algorithm 2: MSE above 5x the mean is an outlier
     mse_source: int = 0        # 0 activation-pair MSE, 1 weight MSE, 2 either (each vs its own mean)
@@ -473,8 +478,8 @@ def bn_fold(w, gamma, var, mean, beta, bias=None):
 
 
 def regroup_for_fusion(order, group_id):
-    """Sec. 6.5 says only that positions of fusion-capable operators "can be adjusted".
-    Reading taken: layers with the same group id (a conv and the BN / Add / ReLU neighbours it
+    """Sec. 6.5 only allows the list positions of fusion-capable operators to change and gives no
+    rule.  Reading taken: layers with the same group id (a conv and the BN / Add / ReLU neighbours it
     fuses with) keep one precision, so a group moves as a block to the position of its most
     sensitive member; inside the block and between blocks the list order is kept."""
     n = len(order)
