@@ -78,8 +78,8 @@ typedef struct {
   int32_t channels;    /* QV2_SYM_CHANNEL: number of dim-0 slices, must divide
                           numel; other schemes: must be 1                           */
   int32_t scheme;      /* qv2_scheme                                                */
-  int32_t kind;        /* 0 weight, 1 activation; informational                     */
-  int32_t layer;       /* layer index this tensor belongs to; informational         */
+  int32_t kind;        /* 0 weight, 1 activation; used by qv2_rank_tensors only     */
+  int32_t layer;       /* layer index this tensor belongs to; qv2_rank_tensors only */
 } qv2_tensor;
 
 /* Per segment (a whole tensor, or one output channel).  This array is the
@@ -334,6 +334,21 @@ qv2_status qv2_rank(const double* w_sqnr_db, const double* a_sqnr_db,
                     const double* w_mse, const double* a_mse,
                     const int32_t* layer_pos, int32_t n_layers,
                     const qv2_rank_config* cfg, int32_t* order_out, double* score_out);
+
+/* Step 4 straight from the per-tensor records of a plan (qv2_tensor_sums_fold and the pair
+ * sums): the layer table's `kind` and `layer` fields route every tensor to its layer's series -
+ * a weight (kind 0) gives the layer's weight SQNR / MSE (Eq. 6-7 against its own dequantized
+ * form), an activation (kind 1) with qrun gives the activation SQNR / MSE (fp32 run against
+ * quantized run); activations without qrun are ignored - and qv2_rank does the rest.
+ * A series must have an entry for every layer 0..n_layers-1 or for none (then it is left out,
+ * as a NULL series of qv2_rank; cfg->mse_source must then name the other one).
+ * h_tensor_sums[num_tensors], h_pair_sums[num_tensors] (may be NULL when no tensor has qrun).
+ * Errors: as qv2_rank, plus ERR_SHAPE for a layer index outside 0..n_layers-1, two tensors
+ * of one kind in a layer, or a series with gaps. */
+qv2_status qv2_rank_tensors(const qv2_plan* plan, const qv2_tensor_sums* h_tensor_sums,
+                            const qv2_pair_sums* h_pair_sums, const int32_t* layer_pos,
+                            int32_t n_layers, const qv2_rank_config* cfg, int32_t* order_out,
+                            double* score_out);
 
 /* ---- after the ranking: baselines and the BOPs cut (Sec. 7; need no GPU) ---- */
 

@@ -31,7 +31,7 @@ EXPORTS = (
     "qv2_plan_set_timing", "qv2_plan_kernel_ms", "qv2_plan_kernels_ms", "qv2_histogram_workspace_bytes", "qv2_histogram",
     "qv2_kl_divergence", "qv2_bn_fold", "qv2_regroup_for_fusion", "qv2_tensor_sums_fold",
     "qv2_finalize_tensors",
-    "qv2_finalize", "qv2_pair_finalize", "qv2_rank_config_default", "qv2_rank",
+    "qv2_finalize", "qv2_pair_finalize", "qv2_rank_config_default", "qv2_rank", "qv2_rank_tensors",
     "qv2_baseline_order", "qv2_bops_reduction_pct", "qv2_bops_select",
     "qv2_status_string",
 )
@@ -118,6 +118,7 @@ def lib():
         L.qv2_rank_config_default.argtypes = [ctypes.POINTER(qv2_rank_config)]
         L.qv2_rank_config_default.restype = None
         L.qv2_rank.argtypes = [vp, vp, vp, vp, vp, i32, ctypes.POINTER(qv2_rank_config), vp, vp]
+        L.qv2_rank_tensors.argtypes = [vp, vp, vp, vp, i32, ctypes.POINTER(qv2_rank_config), vp, vp]
         L.qv2_baseline_order.argtypes = [i32, vp, i32, vp]
         L.qv2_bops_reduction_pct.argtypes = [vp, vp, i32, vp]
         L.qv2_bops_select.argtypes = [vp, vp, i32, ctypes.c_double, vp, vp, vp]
@@ -399,6 +400,25 @@ def qv2_rank(w_sqnr_db, a_sqnr_db, w_mse, a_mse, layer_pos=None, cfg: Optional[q
     _check(lib().qv2_rank(_ptr(ws), _ptr(as_), _ptr(wm), _ptr(am), _ptr(pos), n_layers,
                           ctypes.byref(cfg) if cfg is not None else None,
                           order.ctypes.data, score.ctypes.data), "qv2_rank")
+    return order[:n_layers], score[:n_layers]
+
+
+def qv2_rank_tensors(plan: "Plan", h_tensor_sums, h_pair_sums, n_layers: int, layer_pos=None,
+                     cfg: Optional[qv2_rank_config] = None):
+    """Ranking straight from the per-tensor records (TENSOR_SUMS / PAIR_SUMS arrays of
+    plan.num_tensors entries).  Returns (order, score)."""
+    ts = np.ascontiguousarray(h_tensor_sums)
+    ps = None if h_pair_sums is None else np.ascontiguousarray(h_pair_sums)
+    if len(ts) != plan.num_tensors or (ps is not None and len(ps) != plan.num_tensors):
+        raise QV2Error(QV2_ERR_SHAPE, "qv2_rank_tensors")
+    pos = None if layer_pos is None else np.ascontiguousarray(layer_pos, dtype=np.int32)
+    if pos is not None and len(pos) != n_layers:
+        raise QV2Error(QV2_ERR_SHAPE, "qv2_rank_tensors")
+    order = np.zeros(max(n_layers, 1), np.int32)
+    score = np.zeros(max(n_layers, 1), np.float64)
+    _check(lib().qv2_rank_tensors(plan.handle, ts.ctypes.data, ps.ctypes.data if ps is not None else None,
+                                  _ptr(pos), n_layers, ctypes.byref(cfg) if cfg is not None else None,
+                                  order.ctypes.data, score.ctypes.data), "qv2_rank_tensors")
     return order[:n_layers], score[:n_layers]
 
 

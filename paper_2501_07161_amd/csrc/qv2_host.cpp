@@ -8,6 +8,7 @@
 #include <limits>
 #include <new>
 #include <numeric>
+#include <vector>
 
 #include "qv2_internal.h"
 
@@ -86,7 +87,8 @@ qv2_status qv2_plan_create(const qv2_tensor* h_tensors, int32_t n_tensors, qv2_p
     const int64_t nseg = per_channel ? in.channels : 1;
     const int64_t inner = in.numel / nseg;
     const int64_t seg0 = static_cast<int64_t>(p->segments.size());
-    p->info.push_back(TensorInfo{in.numel, static_cast<int32_t>(seg0), static_cast<int32_t>(nseg)});
+    p->info.push_back(TensorInfo{in.numel, static_cast<int32_t>(seg0), static_cast<int32_t>(nseg), in.kind,
+                                 in.layer, in.qrun != nullptr});
 
     PairTensor ft{};                         // this tensor's partials in the quantize numbering
     PairTensor st{};                         // ... in the calibration numbering (stream tiles only)
@@ -432,6 +434,42 @@ qv2_status qv2_rank(const double* w_sqnr_db, const double* a_sqnr_db, const doub
 // ---------------------------------------------------------------------------
 // Sec. 7: compile-time baseline orders and the BOPs reduction rate (Eq. 17).
 // ---------------------------------------------------------------------------
+// Per-layer series from the per-tensor records of a plan, then qv2_rank.
+qv2_status qv2_rank_tensors(const qv2_plan* plan, const qv2_tensor_sums* h_tensor_sums,
+                            const qv2_pair_sums* h_pair_sums, const int32_t* layer_pos, int32_t n_layers,
+                            const qv2_rank_config* cfg, int32_t* order_out, double* score_out) {
+  if (!plan || !h_tensor_sums || !order_out) return QV2_ERR_NULL;
+  if (n_layers <= 0) return QV2_ERR_SHAPE;
+  const double nan = std::numeric_limits<double>::quiet_NaN();
+  std::vector<double> w_sqnr(n_layers, nan), w_mse(n_layers, nan), a_sqnr(n_layers, nan), a_mse(n_layers, nan);
+  int32_t n_w = 0, n_a = 0;
+  for (size_t t = 0; t < plan->info.size(); ++t) {
+    const TensorInfo& d = plan->info[t];
+    if (d.layer < 0 || d.layer >= n_layers) return QV2_ERR_SHAPE;
+    if (d.kind == 0) {                                       // weight: Eq. 6-7 against its dequantized form
+      if (!std::isnan(w_mse[d.layer])) return QV2_ERR_SHAPE;  // two weights in one layer
+      const qv2_tensor_sums& u = h_tensor_sums[t];
+      if (u.n <= 0) return QV2_ERR_SHAPE;
+      w_mse[d.layer] = u.sum_e2 / static_cast<double>(u.n);
+      w_sqnr[d.layer] = sqnr_db_of(u.sum_x2, u.sum_e2);
+      ++n_w;
+    } else if (d.has_pair) {                                 // activation: fp32 run against quantized run
+      if (!h_pair_sums) return QV2_ERR_NULL;
+      if (!std::isnan(a_mse[d.layer])) return QV2_ERR_SHAPE;
+      const qv2_pair_sums& u = h_pair_sums[t];
+      if (u.n <= 0) return QV2_ERR_SHAPE;
+      a_mse[d.layer] = u.sum_d2 / static_cast<double>(u.n);
+      a_sqnr[d.layer] = sqnr_db_of(u.sum_ref2, u.sum_d2);
+      ++n_a;
+    }
+  }
+  // a series is used only when every layer has an entry in it
+  if ((n_w != 0 && n_w != n_layers) || (n_a != 0 && n_a != n_layers) || (n_w == 0 && n_a == 0))
+    return QV2_ERR_SHAPE;
+  return qv2_rank(n_w ? w_sqnr.data() : nullptr, n_a ? a_sqnr.data() : nullptr, n_w ? w_mse.data() : nullptr,
+                  n_a ? a_mse.data() : nullptr, layer_pos, n_layers, cfg, order_out, score_out);
+}
+
 qv2_status qv2_baseline_order(int32_t kind, const double* w_sqnr_db, int32_t n_layers,
                               int32_t* order_out) {
   if (!order_out) return QV2_ERR_NULL;

@@ -94,6 +94,8 @@ struct HistTensor {            // 16 B, one per tensor: its chunks of the histog
 struct TensorInfo {            // host only
   int64_t numel;
   int32_t seg0, nseg;
+  int32_t kind, layer;         // as given in the layer table (route results to per-layer series)
+  bool has_pair;
 };
 
 // Partial records the tile kernels leave in the workspace.

@@ -146,6 +146,7 @@ def run_gpu(items: List[Item], params_override: Optional[np.ndarray] = None,
     pm, ps = qb.qv2_pair_finalize(pair)
     res = GpuResult(plan, params, sums, pair, metrics, pm, ps)
     res.buffers = buf
+    res.tsums = tsums.cpu().numpy().view(qb.TENSOR_SUMS)
     res.cos_quant = res.cos_pair = None
     if cos:
         res.cos_quant, res.cos_pair = qb.qv2_cosine_finalize(plan, sums, seg_xxhat.cpu().numpy(), pair,
@@ -267,4 +268,9 @@ def check_ranking(items: List[Item], res: GpuResult, oracle_rows, cfg_kwargs=Non
                                        lst(o["a_mse"]), None, orc.RankConfig(**cfg_kwargs))
     assert order.tolist() == o_order, f"ranking differs:\n gpu    {order.tolist()}\n oracle {o_order}"
     assert np.allclose(score, o_score, rtol=0, atol=2 * SQNR_ATOL_DB)
+    if g["a_sqnr"] is not None and not np.isnan(g["w_sqnr"]).any():
+        # every layer has a weight and an activation pair: the one-call form must agree
+        order2, score2 = qb.qv2_rank_tensors(res.plan, res.tsums, res.pair, n_layers, None, cfg)
+        assert order2.tolist() == o_order
+        assert np.allclose(score2, o_score, rtol=0, atol=2 * SQNR_ATOL_DB)
     return order.tolist()

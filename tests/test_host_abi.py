@@ -40,8 +40,9 @@ def test_status_strings():
     assert b"unknown" in qb.lib().qv2_status_string(-99)
 
 
-def _row(numel, scheme=qb.QV2_ASYM_TENSOR, channels=1, x=FAKE, qrun=None, codes=None):
-    return qb.TensorArg(x=x, numel=numel, scheme=scheme, channels=channels, qrun=qrun, codes=codes)
+def _row(numel, scheme=qb.QV2_ASYM_TENSOR, channels=1, x=FAKE, qrun=None, codes=None, kind=0, layer=0):
+    return qb.TensorArg(x=x, numel=numel, scheme=scheme, channels=channels, qrun=qrun, codes=codes,
+                        kind=kind, layer=layer)
 
 
 @pytest.mark.parametrize("row,status", [
@@ -338,3 +339,62 @@ def test_regroup_for_fusion_matches_oracle():
     assert L.qv2_bn_fold(None, 4, 9, FAKE, FAKE, None, None, None, FAKE, None, None) == qb.QV2_ERR_NULL
     assert L.qv2_bn_fold(FAKE, 0, 9, FAKE, FAKE, None, None, None, FAKE, None, None) == qb.QV2_ERR_SHAPE
     assert L.qv2_bn_fold(FAKE, 4, 9, FAKE, FAKE, None, None, None, FAKE, FAKE, None) == qb.QV2_ERR_NULL
+
+
+def test_rank_tensors_routes_records_to_layers():
+    """qv2_rank_tensors against the manual route (finalize, scatter by layer, qv2_rank) and the
+    oracle's Algorithm 2, on made-up per-tensor records; and its shape errors."""
+    rng = np.random.default_rng(5)
+    n_layers = 17
+    rows, kinds, layers = [], [], []
+    for l in rng.permutation(n_layers):            # tensors in any order
+        rows.append(_row(1000 + int(l), layer=int(l), kind=0)); kinds.append(0); layers.append(int(l))
+        rows.append(_row(5000 + int(l), qrun=FAKE, layer=int(l), kind=1)); kinds.append(1); layers.append(int(l))
+    rows.append(_row(77, layer=3, kind=1)); kinds.append(1); layers.append(3)     # activation without a partner: ignored
+    p = qb.qv2_plan_create(rows)
+    nt = p.num_tensors
+    ts = np.zeros(nt, qb.TENSOR_SUMS)
+    ps = np.zeros(nt, qb.PAIR_SUMS)
+    for t in range(nt):
+        n = rows[t].numel
+        ts[t] = (0.1 * n, rng.uniform(1, 4) * n, rng.uniform(1e-5, 1e-3) * n, n, -1.0, 2.0, (0, 0))
+        if kinds[t] == 1 and t != nt - 1:
+            f = 40.0 if layers[t] == 11 else 1.0                                   # one MSE outlier
+            ps[t] = (rng.uniform(1, 4) * n, f * rng.uniform(1e-4, 2e-4) * n, n, 0)
+    order, score = qb.qv2_rank_tensors(p, ts, ps, n_layers)
+    met = qb.qv2_finalize_tensors(ts)
+    pm, psq = qb.qv2_pair_finalize(ps)
+    w_sqnr, w_mse, a_sqnr, a_mse = (np.empty(n_layers) for _ in range(4))
+    for t in range(nt - 1):
+        if kinds[t] == 0:
+            w_sqnr[layers[t]], w_mse[layers[t]] = met["sqnr_db"][t], met["mse"][t]
+        else:
+            a_sqnr[layers[t]], a_mse[layers[t]] = psq[t], pm[t]
+    order1, score1 = qb.qv2_rank(w_sqnr, a_sqnr, w_mse, a_mse)
+    assert order.tolist() == order1.tolist() and np.array_equal(score, score1)
+    o_order, _ = orc.rank_layers(list(w_sqnr), list(a_sqnr), list(w_mse), list(a_mse), None, orc.RankConfig())
+    assert order.tolist() == o_order and order[0] == 11
+    with pytest.raises(qb.QV2Error) as e:
+        qb.qv2_rank_tensors(p, ts, ps, n_layers - 1)                               # layer index out of range
+    assert e.value.status == qb.QV2_ERR_SHAPE
+    p.close()
+    # a series with a gap, and two weights in one layer
+    gap = qb.qv2_plan_create([_row(10, layer=0, kind=0), _row(10, layer=1, kind=0), _row(10, qrun=FAKE, layer=0, kind=1)])
+    with pytest.raises(qb.QV2Error) as e:
+        qb.qv2_rank_tensors(gap, ts[:3], ps[:3], 2)
+    assert e.value.status == qb.QV2_ERR_SHAPE
+    gap.close()
+    dup = qb.qv2_plan_create([_row(10, layer=0, kind=0), _row(10, layer=0, kind=0)])
+    with pytest.raises(qb.QV2Error) as e:
+        qb.qv2_rank_tensors(dup, ts[:2], None, 1)
+    assert e.value.status == qb.QV2_ERR_SHAPE
+    dup.close()
+    # weights only: the activation series is left out, the rule runs on the weight MSE
+    wonly = qb.qv2_plan_create([_row(10 + l, layer=l, kind=0) for l in range(5)])
+    cfg = qb.qv2_rank_config_default()
+    cfg.mse_source = 1
+    o5, _ = qb.qv2_rank_tensors(wonly, ts[:5], None, 5, None, cfg)
+    m5 = qb.qv2_finalize_tensors(ts[:5])
+    o5b, _ = qb.qv2_rank(m5["sqnr_db"], None, m5["mse"], None, None, cfg)
+    assert o5.tolist() == o5b.tolist()
+    wonly.close()
