@@ -368,6 +368,45 @@ void ranking() {
   CHECK(qv2_regroup_for_fusion(dup, dup, 3, o) == QV2_ERR_SHAPE);
 }
 
+void rank_from_records() {
+  std::mt19937_64 g(4242);
+  std::uniform_real_distribution<double> u(0.5, 2.0);
+  for (int rep = 0; rep < 50; ++rep) {
+    const int n = 1 + static_cast<int>(g() % 60);
+    std::vector<qv2_tensor> rows;
+    for (int l = 0; l < n; ++l)
+      for (int kind = 0; kind < 2; ++kind) {
+        qv2_tensor r{};
+        r.x = fake_f32(rows.size() * 4096); r.numel = 100 + l; r.channels = 1; r.scheme = QV2_ASYM_TENSOR;
+        r.qrun = kind ? fake_f32((int64_t{1} << 30) + rows.size() * 4096) : nullptr;
+        r.kind = kind; r.layer = l;
+        rows.push_back(r);
+      }
+    std::shuffle(rows.begin(), rows.end(), g);
+    qv2_plan* p = nullptr;
+    CHECK(qv2_plan_create(rows.data(), static_cast<int32_t>(rows.size()), &p) == QV2_OK);
+    std::vector<qv2_tensor_sums> ts(rows.size());
+    std::vector<qv2_pair_sums> ps(rows.size());
+    for (size_t t = 0; t < rows.size(); ++t) {
+      const double nn = static_cast<double>(rows[t].numel);
+      ts[t] = qv2_tensor_sums{0.0, u(g) * nn, 1e-4 * u(g) * nn, rows[t].numel, -1.0f, 1.0f, {0, 0}};
+      ps[t] = rows[t].qrun ? qv2_pair_sums{u(g) * nn, 1e-3 * u(g) * nn, rows[t].numel, 0} : qv2_pair_sums{0, 0, 0, 0};
+    }
+    std::vector<int32_t> order(n, -1);
+    std::vector<double> score(n);
+    CHECK(qv2_rank_tensors(p, ts.data(), ps.data(), nullptr, n, nullptr, order.data(), score.data()) == QV2_OK);
+    std::vector<int> seen(n, 0);
+    for (int i = 0; i < n; ++i) { CHECK(order[i] >= 0 && order[i] < n); ++seen[order[i]]; }
+    for (int i = 0; i < n; ++i) CHECK(seen[i] == 1);
+    CHECK(qv2_rank_tensors(p, ts.data(), nullptr, nullptr, n, nullptr, order.data(), nullptr) == QV2_ERR_NULL);
+    CHECK(qv2_rank_tensors(p, ts.data(), ps.data(), nullptr, n + 1, nullptr, order.data(), nullptr) == QV2_ERR_SHAPE);
+    if (n > 1)
+      CHECK(qv2_rank_tensors(p, ts.data(), ps.data(), nullptr, n - 1, nullptr, order.data(), nullptr) == QV2_ERR_SHAPE);
+    CHECK(qv2_rank_tensors(nullptr, ts.data(), ps.data(), nullptr, n, nullptr, order.data(), nullptr) == QV2_ERR_NULL);
+    delete p;
+  }
+}
+
 void small_host_functions() {
   std::mt19937_64 g(99);
   for (int nb : {1, 2, 7, 256, 2048, 4096}) {
@@ -406,6 +445,7 @@ void small_host_functions() {
 int main() {
   plans();
   ranking();
+  rank_from_records();
   small_host_functions();
   std::printf("host checks ok\n");
   return 0;
