@@ -377,3 +377,45 @@ def test_non_default_stream():
     with torch.cuda.stream(s):
         res = H.run_gpu([it])
     H.check_all([it], res)
+
+
+def test_device_calls_can_be_captured_in_a_graph():
+    """The device part of the pass (single call + per-tensor fold) captured in a HIP graph through
+    torch and replayed three times, with eager work and synchronisations in between: every replay
+    reproduces the eager records and codes bit for bit.  (The plan's tables are uploaded by the
+    eager call before the capture; the calls record no memset nodes and never synchronise.)"""
+    specs = synth.config_mobilenetv2(2) + synth.config_tiny()
+    items = H.items_from_specs(specs, DEV)
+    for it in items:
+        if it.kind == synth.ACTIVATION:
+            it.qrun = it.x * 0.98 + 0.003
+    res = H.run_gpu(items, fused="single")
+    plan, buf = res.plan, res.buffers
+    dev = torch.device(DEV)
+    tsums = torch.zeros(plan.num_tensors * qb.TENSOR_SUMS.itemsize, dtype=torch.uint8, device=dev)
+
+    def device_part():
+        qb.qv2_calibrate_fakequant_pair_metrics(plan, buf.params, buf.sums, buf.pair, buf.workspace)
+        qb.qv2_tensor_sums_fold(plan, buf.params, buf.sums, tsums)
+
+    device_part()
+    torch.cuda.synchronize()
+    want = [buf.params.clone(), buf.sums.clone(), buf.pair.clone(), tsums.clone()] + [it.codes.clone() for it in items]
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        device_part()
+    torch.cuda.current_stream().wait_stream(side)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        device_part()
+    for rep in range(3):
+        for t in (buf.params, buf.sums, buf.pair, tsums, buf.workspace):
+            t.fill_(0x5A)                                   # eager work between the replays
+        for it in items:
+            it.codes.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        got = [buf.params, buf.sums, buf.pair, tsums] + [it.codes for it in items]
+        assert all(torch.equal(a, b) for a, b in zip(got, want)), f"replay {rep}"
