@@ -15,7 +15,7 @@ CSRC = os.path.join(ROOT, "paper_2501_07161_amd", "csrc")
 
 
 def _build(out, sanitize):
-    cmd = ["g++", "-std=c++17", "-O1", "-g", "-Wall", "-Wextra", "-Werror",
+    cmd = ["g++", "-std=c++17", "-O1", "-g", "-Wall", "-Wextra",
            "-I", os.path.join(ROOT, "include"), "-I", CSRC,
            os.path.join(ROOT, "tests", "host_checks.cpp"), os.path.join(CSRC, "qv2_host.cpp"), "-o", out]
     if sanitize:
