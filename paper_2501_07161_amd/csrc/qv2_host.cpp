@@ -94,21 +94,36 @@ qv2_status qv2_plan_create(const qv2_tensor* h_tensors, int32_t n_tensors, qv2_p
     PairTensor st{};                         // ... in the calibration numbering (stream tiles only)
     if (per_channel && inner <= qv2::kRowGroupCap) {
       // whole rows per tile; every row is its own segment with one partial
-      // rows per tile: what fits the LDS copy, but no more than a few rounds of the row
-      // kernels (a round = one row per lane group of every wavefront), so that a tile of
-      // very short rows does not become the longest-running workgroup of the launch
-      int64_t lanes = 1;
-      while (lanes < inner && lanes < 64) lanes <<= 1;
-      const int64_t per_round = (qv2::kBlockRows / 64) * (64 / lanes);
-      const int64_t rpt = std::min<int64_t>({qv2::kRowGroupMaxRows, qv2::kRowGroupCap / inner,
-                                             qv2::kRowGroupRounds * per_round});
       ft.part0 = static_cast<int32_t>(row_part); ft.nparts = static_cast<int32_t>(nseg);
+      // rows of whole 16-byte vectors on 16-byte boundaries are held in registers: `lanes`
+      // lanes per row (each at most kRowRegVecs vectors), one round of rows per workgroup
+      const bool reg_form = inner % 4 == 0 && inner >= qv2::kRowRegMinInner &&
+                            (reinterpret_cast<uintptr_t>(in.x) & 15u) == 0 &&
+                            (!in.qrun || (reinterpret_cast<uintptr_t>(in.qrun) & 15u) == 0) &&
+                            (!in.codes || (reinterpret_cast<uintptr_t>(in.codes) & 3u) == 0);
+      int64_t lanes = 0, rpt = 0;
+      if (reg_form) {
+        lanes = qv2::kRowRegMinLanes;
+        while (lanes * 4 * qv2::kRowRegVecs < inner) lanes <<= 1;
+        rpt = qv2::kBlockRows / lanes;
+      } else {
+        // otherwise staged in LDS.  Rows per tile: what fits the LDS copy, but no more than a
+        // few rounds of the row kernels (a round = one row per lane group of every wavefront),
+        // so that a tile of very short rows does not become the longest-running workgroup
+        int64_t group = 1;
+        while (group < inner && group < 64) group <<= 1;
+        const int64_t per_round = (qv2::kBlockRows / 64) * (64 / group);
+        rpt = std::min<int64_t>({qv2::kRowGroupMaxRows, qv2::kRowGroupCap / inner,
+                                 qv2::kRowGroupRounds * per_round});
+      }
+      if (in.qrun) p->rows_have_pair = true;
       for (int64_t r0 = 0; r0 < nseg; r0 += rpt) {
         const int64_t rows = std::min(rpt, nseg - r0);
         Tile tl = make_tile(in, t, r0 * inner, rows * inner);
         tl.part0 = static_cast<int32_t>(row_part + r0); tl.rows = static_cast<int32_t>(rows);
         tl.seg0 = static_cast<int32_t>(seg0 + r0); tl.inner = static_cast<int32_t>(inner);
-        p->row_tiles.push_back(tl);
+        tl.lanes = static_cast<int32_t>(lanes);
+        (reg_form ? p->reg_tiles : p->row_tiles).push_back(tl);
       }
       for (int64_t r = 0; r < nseg; ++r) {
         Segment s{};
@@ -213,10 +228,10 @@ int64_t qv2_plan_segment_begin(const qv2_plan* plan, int32_t t) {
   return plan->info[t].seg0;
 }
 int64_t qv2_plan_num_tiles(const qv2_plan* plan) {
-  return plan ? static_cast<int64_t>(plan->read_tiles.size() + plan->row_tiles.size()) : 0;
+  return plan ? static_cast<int64_t>(plan->read_tiles.size() + plan->row_tiles.size() + plan->reg_tiles.size()) : 0;
 }
 int64_t qv2_plan_num_quant_tiles(const qv2_plan* plan) {
-  return plan ? static_cast<int64_t>(plan->quant_tiles.size() + plan->row_tiles.size()) : 0;
+  return plan ? static_cast<int64_t>(plan->quant_tiles.size() + plan->row_tiles.size() + plan->reg_tiles.size()) : 0;
 }
 int64_t qv2_plan_num_pair_tiles(const qv2_plan* plan) {
   return plan ? static_cast<int64_t>(plan->pair_tiles.size()) : 0;

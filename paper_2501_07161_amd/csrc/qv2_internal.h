@@ -35,6 +35,14 @@ constexpr int kRowGroupMaxRows = 1024;
 // of every wavefront): measured, a tile of 910 nine-element rows (29 rounds) alone made the
 // MobileNetV2 launch twice as long as four-round tiles do.
 constexpr int kRowGroupRounds = 4;
+// Register form of a row-group tile: a lane holds at most this many 16-byte vectors of its row
+// and a row takes the smallest power-of-two number of lanes that can hold it (at least
+// kRowRegMinLanes).  Measured on the VGG-16 and ResNet-50 weights: 16 vectors per lane (most
+// rows then live in one wavefront, with 16 loads in flight per lane) beat 4, 8 and 32.
+constexpr int kRowRegVecs = 16;
+constexpr int kRowRegMinLanes = 16;
+constexpr int kRowRegMinInner = 64;
+static_assert(kBlockRows * 4 * kRowRegVecs >= kRowGroupCap, "a whole row must fit the registers of one workgroup");
 // Stream-tile length of the read-only passes (128 KiB of fp32): long tiles amortise the
 // per-workgroup reduction.
 constexpr int kDefaultReadTile = 32768;
@@ -54,7 +62,9 @@ constexpr int kFoldWaveMax = 128;
 // workgroup needs one 64-byte scalar load before it can issue its data loads.
 //  rows == 0 : stream tile, part of ONE segment (seg0); yields one partial (part0).
 //  rows  > 0 : row-group tile, `rows` whole segments of `inner` elements each,
-//              starting at segment seg0; yields `rows` partials from part0.
+//              starting at segment seg0; yields `rows` partials from part0.  Two forms: staged
+//              in LDS (any alignment, any row length up to kRowGroupCap), or held in registers
+//              (`lanes` > 0: rows of a multiple of 4 elements on 16-byte boundaries).
 struct Tile {                  // 64 B
   const float* x;              // first element of the tile
   const float* q;              // same position in the quantized-run tensor, or null
@@ -65,7 +75,8 @@ struct Tile {                  // 64 B
   int32_t rows;
   int32_t inner;
   int32_t tensor;
-  int32_t _pad[4];
+  int32_t lanes;               // register-path row tiles: lanes that share one row (16 .. 512)
+  int32_t _pad[3];
 };
 static_assert(sizeof(Tile) == 64, "Tile must stay one 64-byte record");
 
@@ -111,7 +122,8 @@ struct qv2_plan {
   std::vector<qv2::TensorInfo> info;
   std::vector<qv2::Tile> read_tiles;     // calibration: stream tiles (read size)
   std::vector<qv2::Tile> quant_tiles;    // quantize passes: stream tiles (quantize size)
-  std::vector<qv2::Tile> row_tiles;      // row-group tiles, used by both
+  std::vector<qv2::Tile> row_tiles;      // row-group tiles staged in LDS, used by both
+  std::vector<qv2::Tile> reg_tiles;      // row-group tiles held in registers, used by both
   std::vector<qv2::Tile> pair_tiles;     // pair pass: stream tiles over tensors with qrun
   std::vector<qv2::Tile> hist_tiles;     // histogram pass: long chunks (part0 = chunk index)
   std::vector<qv2::HistTensor> hist_tensors;
@@ -127,6 +139,7 @@ struct qv2_plan {
   std::vector<int32_t> big_stat_pair_tensors;
   int32_t read_tile = qv2::kDefaultReadTile;
   int32_t quant_tile = qv2::kDefaultQuantTile;
+  bool rows_have_pair = false;           // some row-group tensor has a quantized-run partner
   int32_t n_row_parts = 0;               // partial slots 0 .. n_row_parts-1 belong to row-group segments
   size_t workspace_bytes = 0;
 
@@ -135,6 +148,7 @@ struct qv2_plan {
   qv2::Tile* d_read_tiles = nullptr;
   qv2::Tile* d_quant_tiles = nullptr;
   qv2::Tile* d_row_tiles = nullptr;
+  qv2::Tile* d_reg_tiles = nullptr;
   qv2::Tile* d_pair_tiles = nullptr;
   qv2::Tile* d_hist_tiles = nullptr;
   qv2::HistTensor* d_hist_tensors = nullptr;

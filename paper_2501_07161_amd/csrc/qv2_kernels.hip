@@ -923,6 +923,128 @@ __global__ __launch_bounds__(BLOCK) void k_quant_rows(const Tile* __restrict__ t
   }
 }
 
+// Row-group tiles, register form: rows of whole 16-byte vectors on 16-byte boundaries.  tl.lanes
+// lanes share a row (a power of two, 16 .. BLOCK), each holds at most kRowRegVecs vectors of it
+// in registers; a workgroup takes BLOCK / lanes rows, all at once.  Nothing is staged in LDS
+// (only the partial results of rows that span several wavefronts cross it), loads and code stores
+// are coalesced 16-byte / 4-byte accesses, and the arithmetic is the 4-wide form of the stream
+// kernels.
+//  ROLE 0: pass 1 (range, sum x, sum x^2 -> one StatPartial per row)
+//  ROLE 1: pass 2 (+3) with given parameters
+//  ROLE 2: both from the one copy in registers: the row is read from HBM once; writes the rows'
+//          parameter and sum records itself.
+template <int BLOCK, int ROLE, bool PAIR, bool COS>
+__global__ __launch_bounds__(BLOCK) void k_rows_reg(const Tile* __restrict__ tiles,
+                                                    const Segment* __restrict__ segs,
+                                                    const qv2_qparams* __restrict__ params,
+                                                    qv2_qparams* __restrict__ params_out,
+                                                    qv2_sums* __restrict__ sums_out,
+                                                    void* __restrict__ parts_any) {
+  constexpr int W = BLOCK / kWave;
+  constexpr int K = kRowRegVecs;
+  constexpr int NE = COS ? 5 : 3;
+  __shared__ float sf[2][W];
+  __shared__ double sd1[2][W], sd2[NE][W];
+  const Tile tl = tiles[blockIdx.x];
+  const int inner = tl.inner, nvec = inner >> 2, G = tl.lanes;
+  const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
+  RowMap m;
+  m.step = 0; m.rounds = 1; m.stride = G;
+  if (G >= kWave) {
+    m.w = kWave; m.wpr = G >> 6; m.part = wave % m.wpr;
+    m.gl = m.part * kWave + lane; m.row0 = wave / m.wpr;
+  } else {
+    m.w = G; m.wpr = 1; m.part = 0;
+    m.gl = lane & (G - 1); m.row0 = wave * (kWave / G) + lane / G;
+  }
+  const int r = m.row0;
+  const bool live = r < tl.rows;
+  const size_t row_off = static_cast<size_t>(live ? r : 0) * inner;
+  const gf4_ptr v4 = (gf4_ptr)(tl.x + row_off);
+  const gf4_ptr b4 = (gf4_ptr)(tl.q + row_off);
+  const bool has_b = PAIR && ROLE != 0 && tl.q != nullptr;
+
+  // all loads go out back to back: a lane whose vector lies past the row's end (or whose row
+  // is past the tile's end) reads the row's (or row 0's) last vector instead and ignores it
+  f4 xv[K], gv[K];
+  bool on[K];
+#pragma unroll
+  for (int k = 0; k < K; ++k) {
+    const int i = m.gl + k * G;
+    on[k] = live && i < nvec;
+    xv[k] = ld4(v4 + (i < nvec ? i : nvec - 1));
+  }
+  if (has_b) {                                   // uniform over the workgroup
+#pragma unroll
+    for (int k = 0; k < K; ++k) {
+      const int i = m.gl + k * G;
+      gv[k] = ld4(b4 + (i < nvec ? i : nvec - 1));
+    }
+  }
+
+  qv2_qparams qp;
+  QP q{1.0f, 1.0f, 0.0f};
+  double sx = 0.0;
+  if (ROLE != 1) {
+    float mn = INFINITY, mx = -INFINITY;
+    Acc4 as, as2;
+#pragma unroll
+    for (int k = 0; k < K; ++k) {
+      if (!on[k]) continue;
+      mn = fminf(fminf(mn, xv[k].x), fminf(fminf(xv[k].y, xv[k].z), xv[k].w));
+      mx = fmaxf(fmaxf(mx, xv[k].x), fmaxf(fmaxf(xv[k].y, xv[k].z), xv[k].w));
+      as.add(xv[k]);
+      if (ROLE == 0) as2.add_sq(xv[k].x, xv[k].y, xv[k].z, xv[k].w);
+    }
+    double v[2] = {as.total(), as2.total()};
+    row_join<W, 2, true>(m, mn, mx, v, sf, sd1);
+    if (ROLE == 0) {
+      if (live && m.gl == 0) {
+        StatPartial o;
+        o.mn = mn; o.mx = mx; o.sx = v[0]; o.sx2 = v[1];
+        static_cast<StatPartial*>(parts_any)[tl.part0 + r] = o;
+      }
+      return;
+    }
+    sx = v[0];
+    make_params(mn, mx, segs[tl.seg0].scheme, qp);           // one tensor, one scheme per tile
+    q = QP{qp.scale, qp.inv_scale, static_cast<float>(qp.zp)};
+  } else if (live) {
+    q = load_qp(params, tl.seg0 + r);
+  }
+
+  const gu32_ptr cw = (gu32_ptr)(tl.c + row_off);
+  const bool has_c = tl.c != nullptr;
+  Acc4 ae2, ax2, ad2, axh, axq;
+#pragma unroll
+  for (int k = 0; k < K; ++k) {
+    if (!on[k]) continue;
+    const uint32_t pk = quant4<COS>(xv[k], q, ae2, ax2, axh);
+    if (has_c) st_codes(cw + m.gl + k * G, pk);
+    if (has_b) {
+      ad2.add_sq(xv[k].x - gv[k].x, xv[k].y - gv[k].y, xv[k].z - gv[k].z, xv[k].w - gv[k].w);
+      if (COS) axq.add_prod(xv[k], gv[k]);
+    }
+  }
+  double e[NE];
+  e[0] = ax2.total(); e[1] = ae2.total(); e[2] = ad2.total();
+  if (COS) { e[NE - 2] = axh.total(); e[NE - 1] = axq.total(); }
+  float u0 = 0.0f, u1 = 0.0f;
+  row_join<W, NE, false>(m, u0, u1, e, sf, sd2);
+  if (live && m.gl == 0) {
+    typename ErrRec<COS>::type o;
+    o.sx2 = e[0]; o.se2 = e[1]; o.sd2 = e[2];
+    set_cross(o, COS ? e[NE - 2] : 0.0, COS ? e[NE - 1] : 0.0);
+    static_cast<typename ErrRec<COS>::type*>(parts_any)[tl.part0 + r] = o;
+    if (ROLE == 2) {
+      params_out[tl.seg0 + r] = qp;
+      qv2_sums u;
+      u.sum_x = sx; u.sum_x2 = e[0]; u.sum_e2 = e[1]; u.n = inner;
+      sums_out[tl.seg0 + r] = u;
+    }
+  }
+}
+
 // ---------------------------------------------------------------------------
 // pass 3 alone (Algorithm 2: CalculateSQNR / CalculateMSE on D[i] and Q[i])
 // ---------------------------------------------------------------------------
@@ -1167,6 +1289,7 @@ qv2_status ensure_uploaded(qv2_plan* p) {
   const size_t o_bp = reserve(bytes_of(p->big_pair_tensors)), o_bf = reserve(bytes_of(p->big_fused_pair_tensors));
   const size_t o_ht = reserve(bytes_of(p->hist_tiles)), o_hten = reserve(bytes_of(p->hist_tensors));
   const size_t o_st = reserve(bytes_of(p->stat_pair_tensors)), o_bst = reserve(bytes_of(p->big_stat_pair_tensors));
+  const size_t o_reg = reserve(bytes_of(p->reg_tiles));
   char* blob = nullptr;
   if (hipMalloc(reinterpret_cast<void**>(&blob), total) != hipSuccess) {
     (void)hipGetLastError();
@@ -1196,6 +1319,7 @@ qv2_status ensure_uploaded(qv2_plan* p) {
   p->d_hist_tiles = static_cast<Tile*>(put(o_ht, p->hist_tiles.data(), bytes_of(p->hist_tiles)));
   p->d_hist_tensors =
       static_cast<HistTensor*>(put(o_hten, p->hist_tensors.data(), bytes_of(p->hist_tensors)));
+  p->d_reg_tiles = static_cast<Tile*>(put(o_reg, p->reg_tiles.data(), bytes_of(p->reg_tiles)));
   p->d_stat_pair_tensors =
       static_cast<PairTensor*>(put(o_st, p->stat_pair_tensors.data(), bytes_of(p->stat_pair_tensors)));
   p->d_big_stat_pair_tensors = static_cast<int32_t*>(
@@ -1227,6 +1351,31 @@ struct Timed {
 
 int fold_grid(int n) { return (n + 3) / 4; }
 
+// row-group tiles of a quantize pass, both forms; d_params_out != null: with calibration
+template <bool PAIR, bool COS>
+void launch_rows(qv2_plan* plan, const qv2_qparams* d_params, qv2_qparams* d_params_out, qv2_sums* d_sums,
+                 typename ErrRec<COS>::type* parts, int n_rows, int n_regs, hipStream_t s) {
+  const bool calib = d_params_out != nullptr;
+  if (n_rows > 0) {
+    if (calib)
+      hipLaunchKernelGGL((k_quant_rows<kBlockRows, PAIR, COS, true>), dim3(n_rows), dim3(kBlockRows), 0, s,
+                         plan->d_row_tiles, plan->d_segments, d_params, d_params_out, d_sums, parts);
+    else
+      hipLaunchKernelGGL((k_quant_rows<kBlockRows, PAIR, COS, false>), dim3(n_rows), dim3(kBlockRows), 0, s,
+                         plan->d_row_tiles, plan->d_segments, d_params, d_params_out, d_sums, parts);
+  }
+  if (n_regs > 0) {
+    if (calib)
+      hipLaunchKernelGGL((k_rows_reg<kBlockRows, 2, PAIR, COS>), dim3(n_regs), dim3(kBlockRows), 0, s,
+                         plan->d_reg_tiles, plan->d_segments, d_params, d_params_out, d_sums,
+                         static_cast<void*>(parts));
+    else
+      hipLaunchKernelGGL((k_rows_reg<kBlockRows, 1, PAIR, COS>), dim3(n_regs), dim3(kBlockRows), 0, s,
+                         plan->d_reg_tiles, plan->d_segments, d_params, d_params_out, d_sums,
+                         static_cast<void*>(parts));
+  }
+}
+
 // quantize pass over stream and row-group tiles, then ONE fold launch for the segments'
 // error sums and (d_pair_sums != null) the tensors' pair sums.  d_params_out != null: the
 // row-group kernel also calibrates its rows (writes their parameter and sum records), and
@@ -1251,14 +1400,14 @@ void launch_quant(qv2_plan* plan, const qv2_qparams* d_params, qv2_sums* d_sums,
       hipLaunchKernelGGL((k_quant_stream<kBlockQuant, kVecQuant, false, COS>), dim3(n_stream),
                          dim3(kBlockQuant), 0, s, plan->d_quant_tiles, d_params, parts);
   }
-  if (n_rows > 0) {
+  const int n_regs = static_cast<int>(plan->reg_tiles.size());
+  if (n_rows + n_regs > 0) {
     Timed timed(plan, calib_rows ? QV2_K_SINGLE_READ_ROWS : PAIR ? QV2_K_QUANTPAIR_ROWS : QV2_K_QUANT_ROWS, s);
-    if (calib_rows)
-      hipLaunchKernelGGL((k_quant_rows<kBlockRows, PAIR, COS, true>), dim3(n_rows), dim3(kBlockRows), 0, s,
-                         plan->d_row_tiles, plan->d_segments, d_params, d_params_out, d_sums, parts);
+    // the pair form of the row kernels costs registers: only when a row tensor has a partner
+    if (PAIR && plan->rows_have_pair)
+      launch_rows<true, COS>(plan, d_params, d_params_out, d_sums, parts, n_rows, n_regs, s);
     else
-      hipLaunchKernelGGL((k_quant_rows<kBlockRows, PAIR, COS, false>), dim3(n_rows), dim3(kBlockRows), 0, s,
-                         plan->d_row_tiles, plan->d_segments, d_params, d_params_out, d_sums, parts);
+      launch_rows<false, COS>(plan, d_params, d_params_out, d_sums, parts, n_rows, n_regs, s);
   }
   QuantFoldArgs<P> a{};
   a.segs = plan->d_segments; a.nseg = static_cast<int>(plan->segments.size());
@@ -1294,10 +1443,17 @@ void launch_stats(qv2_plan* plan, qv2_qparams* d_params, qv2_sums* d_sums,
     hipLaunchKernelGGL((k_stats_stream<kBlockRead, kVecRead, PAIR>), dim3(n_stream), dim3(kBlockRead), 0, s,
                        plan->d_read_tiles, parts);
   }
-  if (with_rows && n_rows > 0) {
+  const int n_regs = static_cast<int>(plan->reg_tiles.size());
+  if (with_rows && n_rows + n_regs > 0) {
     Timed timed(plan, QV2_K_STATS_ROWS, s);
-    hipLaunchKernelGGL(k_stats_rows<kBlockRows>, dim3(n_rows), dim3(kBlockRows), 0, s,
-                       plan->d_row_tiles, reinterpret_cast<StatPartial*>(parts));
+    if (n_rows > 0)
+      hipLaunchKernelGGL(k_stats_rows<kBlockRows>, dim3(n_rows), dim3(kBlockRows), 0, s,
+                         plan->d_row_tiles, reinterpret_cast<StatPartial*>(parts));
+    if (n_regs > 0)
+      hipLaunchKernelGGL((k_rows_reg<kBlockRows, 0, false, false>), dim3(n_regs), dim3(kBlockRows), 0, s,
+                         plan->d_reg_tiles, plan->d_segments, static_cast<const qv2_qparams*>(nullptr),
+                         static_cast<qv2_qparams*>(nullptr), static_cast<qv2_sums*>(nullptr),
+                         static_cast<void*>(parts));
   }
   if (with_rows || n_stream > 0) {
     StatFoldArgs<REC> a{};

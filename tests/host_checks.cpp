@@ -83,8 +83,8 @@ void check_plan(const std::vector<qv2_tensor>& rows) {
       CHECK(p->segments[nseg + k].scheme == in.scheme);
     }
     nseg += s;
-    check_cover({&p->read_tiles, &p->row_tiles}, in, t, true);
-    check_cover({&p->quant_tiles, &p->row_tiles}, in, t, true);
+    check_cover({&p->read_tiles, &p->row_tiles, &p->reg_tiles}, in, t, true);
+    check_cover({&p->quant_tiles, &p->row_tiles, &p->reg_tiles}, in, t, true);
     check_cover({&p->hist_tiles}, in, t, true);
     check_cover({&p->pair_tiles}, in, t, in.qrun != nullptr);
     if (!in.qrun) {
@@ -96,8 +96,10 @@ void check_plan(const std::vector<qv2_tensor>& rows) {
   }
   CHECK(qv2_plan_num_segments(p) == nseg);
   CHECK(static_cast<int64_t>(p->segments.size()) == nseg);
-  CHECK(qv2_plan_num_tiles(p) == static_cast<int64_t>(p->read_tiles.size() + p->row_tiles.size()));
-  CHECK(qv2_plan_num_quant_tiles(p) == static_cast<int64_t>(p->quant_tiles.size() + p->row_tiles.size()));
+  CHECK(qv2_plan_num_tiles(p) ==
+        static_cast<int64_t>(p->read_tiles.size() + p->row_tiles.size() + p->reg_tiles.size()));
+  CHECK(qv2_plan_num_quant_tiles(p) ==
+        static_cast<int64_t>(p->quant_tiles.size() + p->row_tiles.size() + p->reg_tiles.size()));
   CHECK(qv2_plan_num_pair_tiles(p) == static_cast<int64_t>(p->pair_tiles.size()));
 
   // partial slots: every slot of a numbering is written by exactly one (tile, row), lies in
@@ -109,7 +111,8 @@ void check_plan(const std::vector<qv2_tensor>& rows) {
     CHECK(tl.seg0 >= 0 && tl.seg0 < nseg);
     if (tl.rows > 0) {
       CHECK(static_cast<int64_t>(tl.rows) * tl.inner == tl.len);
-      CHECK(tl.len <= qv2::kRowGroupCap && tl.rows <= qv2::kRowGroupMaxRows);
+      if (tl.lanes == 0) CHECK(tl.len <= qv2::kRowGroupCap && tl.rows <= qv2::kRowGroupMaxRows);   // LDS copy
+      else CHECK(tl.len <= qv2::kBlockRows * 4 * qv2::kRowRegVecs && tl.inner <= qv2::kRowGroupCap);
       CHECK(tl.seg0 + tl.rows <= nseg);
       CHECK(tl.part0 + tl.rows <= p->n_row_parts);
       for (int r = 0; r < tl.rows; ++r) {
@@ -134,7 +137,17 @@ void check_plan(const std::vector<qv2_tensor>& rows) {
   };
   for (const Tile& tl : p->read_tiles) { CHECK(tl.rows == 0 && tl.len <= p->read_tile); mark(tl, true, false); }
   for (const Tile& tl : p->quant_tiles) { CHECK(tl.rows == 0 && tl.len <= p->quant_tile); mark(tl, false, true); }
-  for (const Tile& tl : p->row_tiles) { CHECK(tl.rows > 0); mark(tl, true, true); }
+  for (const Tile& tl : p->row_tiles) { CHECK(tl.rows > 0 && tl.lanes == 0); mark(tl, true, true); }
+  for (const Tile& tl : p->reg_tiles) {
+    // register form: whole vectors on 16-byte boundaries, a row fits its lanes, the rows fit the workgroup
+    CHECK(tl.rows > 0 && tl.inner % 4 == 0 && tl.inner >= qv2::kRowRegMinInner);
+    CHECK(tl.lanes >= qv2::kRowRegMinLanes && tl.lanes <= qv2::kBlockRows && (tl.lanes & (tl.lanes - 1)) == 0);
+    CHECK(tl.lanes * 4 * qv2::kRowRegVecs >= tl.inner && tl.rows * tl.lanes <= qv2::kBlockRows);
+    CHECK((reinterpret_cast<uintptr_t>(tl.x) & 15u) == 0);
+    CHECK(tl.q == nullptr || (reinterpret_cast<uintptr_t>(tl.q) & 15u) == 0);
+    CHECK(tl.c == nullptr || (reinterpret_cast<uintptr_t>(tl.c) & 3u) == 0);
+    mark(tl, true, true);
+  }
   int64_t total_s = 0, total_e = 0;
   for (const Segment& sg : p->segments) { total_s += sg.snp; total_e += sg.enp; }
   for (int64_t i = 0; i < total_s; ++i) CHECK(hits_s[i] == 1);

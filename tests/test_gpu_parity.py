@@ -117,6 +117,25 @@ def test_per_channel_row_shapes(fused):
 
 
 @pytest.mark.parametrize("fused", [False, True, "single"])
+def test_per_channel_rows_held_in_registers(fused):
+    """Rows of a multiple of 4 elements (64 ... 8192) on 16-byte boundaries with 4-byte aligned
+    code buffers take the register form of the row kernels: 16 to 128 lanes per row, last vectors
+    only partly populated (68, 100, 1028, 4100, 8188), tiles whose last workgroup has fewer rows
+    than lanes groups, with and without partners, dead channels."""
+    items = []
+    shapes = [(9, 64), (7, 68), (5, 100), (33, 256), (600, 128), (3, 1020), (4, 1024), (6, 1028),
+              (35, 1024), (3, 4096), (2, 4100), (5, 4608), (3, 8188), (2, 8192), (1, 8192)]
+    for i, (c, inner) in enumerate(shapes):
+        x = _rand(c * inner, 800 + i, 0.1)
+        if i % 4 == 0:
+            x.view(c, inner)[c // 2] = 0.0
+        q = (x * 1.02 - 0.0005) if i % 2 == 0 else None
+        items.append(H.Item(f"reg{c}x{inner}", x, C, c, 0, len(items), qrun=q))
+    res = H.run_gpu(items, fused=fused)
+    H.check_all(items, res)
+
+
+@pytest.mark.parametrize("fused", [False, True, "single"])
 def test_degenerate_and_special_values(fused):
     z = torch.zeros(5000, device=DEV)
     const = torch.full((4097,), 3.25, device=DEV)
