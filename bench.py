@@ -41,7 +41,7 @@ ROCPROF_NAMES = {"k_statspair_stream": "k_stats_stream<512, 8, true>",
 # HBM bytes per launch of the dominant kernel on the resnet50 b256 workload from rocprofv3
 # --pmc (FETCH_SIZE and WRITE_SIZE runs, each scaled by a copy kernel of known size); see
 # profiles/sensitivity_pass_resnet50_b256.txt.
-TRAFFIC_BYTES = {"k_statspair_stream": 21_697_539_833, "k_pair_stream": 21_697_227_316,
+TRAFFIC_BYTES = {"k_statspair_stream": 21_697_537_538, "k_pair_stream": 21_697_224_407,
                  "k_quantpair_stream": 24_627_581_264}
 
 
