@@ -31,10 +31,11 @@ constexpr int kVecQuant = QV2_VEC_QUANT;
 constexpr int kRowGroupCap = 8192;
 // Most rows one row-group tile may hold.
 constexpr int kRowGroupMaxRows = 1024;
-// ... and most rounds of the row kernels one tile may take (a round = one row per lane group
-// of every wavefront): measured, a tile of 910 nine-element rows (29 rounds) alone made the
-// MobileNetV2 launch twice as long as four-round tiles do.
-constexpr int kRowGroupRounds = 4;
+// ... and most rounds of the LDS-form row kernels one tile may take (a round = one row per lane
+// group of every wavefront).  Short tiles keep the longest-running workgroup of the launch short:
+// measured, a tile of 910 nine-element rows (29 rounds) alone made the MobileNetV2 launch twice as
+// long as four-round tiles do, and one round is another 5-15 % better on all sets.
+constexpr int kRowGroupRounds = 1;
 // Register form of a row-group tile: a lane holds at most this many 16-byte vectors of its row
 // and a row takes the smallest power-of-two number of lanes that can hold it (at least
 // kRowRegMinLanes).  Measured on the VGG-16 and ResNet-50 weights: 16 vectors per lane (most

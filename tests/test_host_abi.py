@@ -80,16 +80,16 @@ def test_plan_tiling_counts():
     rows = [
         _row(200_704, qrun=FAKE),                               # 7 read tiles (6 full + 4096), 98 quantize tiles
         _row(9408),                                             # 1 read tile, 5 quantize tiles
-        _row(32 * 9, qb.QV2_SYM_CHANNEL, 32),                   # 1 row-group tile of 32 rows
+        _row(32 * 9, qb.QV2_SYM_CHANNEL, 32),                   # 16 lanes per row, 16 rows per 256-thread tile -> 2 tiles
         _row(4096 * 40000, qb.QV2_SYM_CHANNEL, 4096),           # rows longer than a tile: 2 / 20 tiles each
         _row(2048 * 512, qb.QV2_SYM_CHANNEL, 2048),             # aligned rows of 512: 16 lanes per row, 16 rows per 256-thread tile -> 128 tiles
-        _row(3000 * 3, qb.QV2_SYM_CHANNEL, 3000),               # 4 lanes per row: 4 rounds x 64 rows per tile -> 12 tiles
+        _row(3000 * 3, qb.QV2_SYM_CHANNEL, 3000),               # 4 lanes per row: 64 rows per tile -> 47 tiles
     ]
     p = qb.qv2_plan_create(rows)
     assert p.num_tensors == 6
     assert p.num_segments == 1 + 1 + 32 + 4096 + 2048 + 3000
     assert p.segment_begin == [0, 1, 2, 34, 34 + 4096, 34 + 4096 + 2048]
-    n_row_tiles = 1 + 128 + 12
+    n_row_tiles = 2 + 128 + 47
     assert p.num_tiles == 7 + 1 + 4096 * 2 + n_row_tiles
     assert p.num_quant_tiles == 98 + 5 + 4096 * 20 + n_row_tiles
     assert p.num_pair_tiles == 7
