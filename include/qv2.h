@@ -59,7 +59,8 @@ typedef enum {
   QV2_ERR_WORKSPACE = -4,  /* workspace smaller than qv2_workspace_bytes()       */
   QV2_ERR_NONFINITE = -5,  /* NaN / Inf where a finite value is required         */
   QV2_ERR_HIP = -6,        /* a HIP runtime call or kernel launch failed         */
-  QV2_ERR_ALIGN = -7       /* a device pointer is not aligned as required        */
+  QV2_ERR_ALIGN = -7,      /* a device pointer is not aligned as required        */
+  QV2_ERR_IO = -8          /* a file could not be created or written             */
 } qv2_status;
 
 typedef enum {
@@ -378,6 +379,16 @@ qv2_status qv2_bops_reduction_pct(const double* macs, const uint8_t* keep_fp32, 
 qv2_status qv2_bops_select(const int32_t* order, const double* macs, int32_t n_layers,
                            double target_pct, uint8_t* keep_fp32_out, int32_t* n_keep_out,
                            double* achieved_pct_out);
+
+/* Step 5 (Sec. 4): writes the configuration that states every layer's bit-width - 32 for the
+ * layers kept in fp32 (keep_fp32[i] != 0, e.g. from qv2_bops_select), 8 for the others - as a
+ * text table in layer order: a header line "layer,name,bits", then "<index>,<name>,<32|8>".
+ * The paper hands this file to its compiler and prints no format; this one is the library's.
+ * path: HOST file name, created or truncated.  layer_names: n_layers NUL-terminated names
+ * without commas or line breaks, or NULL (then "layer<index>").
+ * Errors: ERR_NULL, ERR_SHAPE (n_layers <= 0, a name with a comma or line break), ERR_IO. */
+qv2_status qv2_write_config(const char* path, const uint8_t* keep_fp32,
+                            const char* const* layer_names, int32_t n_layers);
 
 /* Fusion-aware adjustment of a sensitivity list (Sec. 6.5 only allows the positions of
  * fusion-capable operators to change and gives no rule; this is the reading taken): layers with the

@@ -15,7 +15,8 @@ the sums of its channels' sums).
 Parity unpinned (the paper prints no value or rule to check against; the functions are pinned
 to their stated readings only): the default gains alpha_w = 0.6 / alpha_a = 0.4 of
 ``rank_layers``, the smoothing constant ``eps`` of ``kl_divergence`` (no default), the histogram
-binning rule of ``histogram``, and the block-move rule of ``regroup_for_fusion``.
+binning rule of ``histogram``, the block-move rule of ``regroup_for_fusion``, and the text format
+of ``config_text``.
 """
 from __future__ import annotations
 
@@ -418,6 +419,21 @@ def bops_select(order, macs, target_pct: float):
             break
         kept += 1
     return keep, kept, bops_reduction_pct(macs, keep)
+
+
+def config_text(keep_fp32, names=None) -> str:
+    """Sec. 4 step 5: the configuration that states the bit-width of every layer - 32 for the
+    layers kept in fp32, 8 for the rest.  The paper hands it to its compiler and prints no
+    format; the one taken here is a text table, one line per layer in layer order:
+    a header line ``layer,name,bits`` and then ``<index>,<name>,<32|8>`` (name = ``layer<index>``
+    when none is given).  Parity of the format with the paper is unpinned."""
+    lines = ["layer,name,bits"]
+    for i, k in enumerate(keep_fp32):
+        name = names[i] if names is not None else f"layer{i}"
+        if any(c in name for c in ",\n\r"):
+            raise ValueError("a layer name holds a comma or a line break")
+        lines.append(f"{i},{name},{32 if k else 8}")
+    return "\n".join(lines) + "\n"
 
 
 # ----------------------------------------------------------------------------

@@ -19,7 +19,7 @@ LIB_PATH = os.environ.get("QV2_LIB_PATH") or os.path.join(_HERE, "libqv2.so")
 
 QV2_OK = 0
 QV2_ERR_NULL, QV2_ERR_SHAPE, QV2_ERR_SCHEME, QV2_ERR_WORKSPACE = -1, -2, -3, -4
-QV2_ERR_NONFINITE, QV2_ERR_HIP, QV2_ERR_ALIGN = -5, -6, -7
+QV2_ERR_NONFINITE, QV2_ERR_HIP, QV2_ERR_ALIGN, QV2_ERR_IO = -5, -6, -7, -8
 QV2_ASYM_TENSOR, QV2_SYM_TENSOR, QV2_SYM_CHANNEL = 0, 1, 2
 
 EXPORTS = (
@@ -31,7 +31,7 @@ EXPORTS = (
     "qv2_plan_set_timing", "qv2_plan_kernel_ms", "qv2_plan_kernels_ms", "qv2_histogram_workspace_bytes", "qv2_histogram",
     "qv2_kl_divergence", "qv2_bn_fold", "qv2_regroup_for_fusion", "qv2_tensor_sums_fold",
     "qv2_finalize_tensors",
-    "qv2_finalize", "qv2_pair_finalize", "qv2_rank_config_default", "qv2_rank", "qv2_rank_tensors",
+    "qv2_finalize", "qv2_pair_finalize", "qv2_rank_config_default", "qv2_rank", "qv2_rank_tensors", "qv2_write_config",
     "qv2_baseline_order", "qv2_bops_reduction_pct", "qv2_bops_select",
     "qv2_status_string",
 )
@@ -119,6 +119,7 @@ def lib():
         L.qv2_rank_config_default.restype = None
         L.qv2_rank.argtypes = [vp, vp, vp, vp, vp, i32, ctypes.POINTER(qv2_rank_config), vp, vp]
         L.qv2_rank_tensors.argtypes = [vp, vp, vp, vp, i32, ctypes.POINTER(qv2_rank_config), vp, vp]
+        L.qv2_write_config.argtypes = [ctypes.c_char_p, vp, vp, i32]
         L.qv2_baseline_order.argtypes = [i32, vp, i32, vp]
         L.qv2_bops_reduction_pct.argtypes = [vp, vp, i32, vp]
         L.qv2_bops_select.argtypes = [vp, vp, i32, ctypes.c_double, vp, vp, vp]
@@ -324,6 +325,18 @@ def qv2_bn_fold(d_w, channels: int, inner: int, d_gamma, d_var, d_w_out, d_bias=
     _check(lib().qv2_bn_fold(_ptr(d_w), int(channels), int(inner), _ptr(d_gamma), _ptr(d_var), _ptr(d_bias),
                              _ptr(d_mean), _ptr(d_beta), _ptr(d_w_out), _ptr(d_bias_out), _stream(stream)),
            "qv2_bn_fold")
+
+
+def qv2_write_config(path: str, keep_fp32, layer_names=None):
+    """Writes the per-layer bit-width table (32 for kept-in-fp32 layers, 8 otherwise)."""
+    keep = np.ascontiguousarray(keep_fp32, dtype=np.uint8)
+    n = len(keep)
+    names = None
+    if layer_names is not None:
+        if len(layer_names) != n:
+            raise QV2Error(QV2_ERR_SHAPE, "qv2_write_config")
+        names = (ctypes.c_char_p * n)(*[s.encode() for s in layer_names])
+    _check(lib().qv2_write_config(os.fsencode(path), keep.ctypes.data, names, n), "qv2_write_config")
 
 
 def qv2_regroup_for_fusion(order, group_id) -> np.ndarray:

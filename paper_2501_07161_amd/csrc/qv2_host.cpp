@@ -3,6 +3,7 @@
 // Sec. 6.4 Eq. 16 / Algorithm 2.  No GPU is needed by anything in this file.
 #include <algorithm>
 #include <cmath>
+#include <cstdio>
 #include <cstdlib>
 #include <cstring>
 #include <limits>
@@ -557,6 +558,28 @@ qv2_status qv2_bops_select(const int32_t* order, const double* macs, int32_t n_l
 
 // Sec. 6.5: layers of one fusion group move as a block to the position of the group's most
 // sensitive member; list order is kept inside a block and between blocks.
+// Sec. 4 step 5: bit-width per layer as a text table.
+qv2_status qv2_write_config(const char* path, const uint8_t* keep_fp32, const char* const* layer_names,
+                            int32_t n_layers) {
+  if (!path || !keep_fp32) return QV2_ERR_NULL;
+  if (n_layers <= 0) return QV2_ERR_SHAPE;
+  if (layer_names)
+    for (int32_t i = 0; i < n_layers; ++i) {
+      if (!layer_names[i]) return QV2_ERR_NULL;
+      if (std::strpbrk(layer_names[i], ",\n\r")) return QV2_ERR_SHAPE;
+    }
+  std::FILE* f = std::fopen(path, "w");
+  if (!f) return QV2_ERR_IO;
+  bool ok = std::fputs("layer,name,bits\n", f) >= 0;
+  for (int32_t i = 0; ok && i < n_layers; ++i) {
+    const int bits = keep_fp32[i] ? 32 : 8;
+    if (layer_names) ok = std::fprintf(f, "%d,%s,%d\n", i, layer_names[i], bits) > 0;
+    else ok = std::fprintf(f, "%d,layer%d,%d\n", i, i, bits) > 0;
+  }
+  if (std::fclose(f) != 0) ok = false;
+  return ok ? QV2_OK : QV2_ERR_IO;
+}
+
 qv2_status qv2_regroup_for_fusion(const int32_t* order, const int32_t* group_id, int32_t n_layers,
                                   int32_t* order_out) {
   if (!order || !group_id || !order_out) return QV2_ERR_NULL;
@@ -588,6 +611,7 @@ const char* qv2_status_string(qv2_status s) {
     case QV2_ERR_NONFINITE: return "non-finite value";
     case QV2_ERR_HIP: return "HIP runtime error";
     case QV2_ERR_ALIGN: return "misaligned pointer";
+    case QV2_ERR_IO: return "file could not be written";
   }
   return "unknown status";
 }

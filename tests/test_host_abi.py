@@ -35,8 +35,8 @@ def test_struct_layouts_match_header_sizes():
 
 
 def test_status_strings():
-    for st in range(-7, 1):
-        assert qb.lib().qv2_status_string(st)
+    for st in range(-8, 1):
+        assert qb.lib().qv2_status_string(st) and qb.lib().qv2_status_string(st) != b"unknown status"
     assert b"unknown" in qb.lib().qv2_status_string(-99)
 
 
@@ -398,3 +398,31 @@ def test_rank_tensors_routes_records_to_layers():
     o5b, _ = qb.qv2_rank(m5["sqnr_db"], None, m5["mse"], None, None, cfg)
     assert o5.tolist() == o5b.tolist()
     wonly.close()
+
+
+def test_write_config_matches_oracle_text(tmp_path):
+    """Sec. 4 step 5: the per-layer bit-width table, byte for byte the oracle's text; error paths."""
+    rng = np.random.default_rng(9)
+    n = 23
+    keep = (rng.random(n) < 0.3).astype(np.uint8)
+    names = [f"stage{i // 4}.conv{i % 4}" for i in range(n)]
+    p1, p2 = tmp_path / "with_names.csv", tmp_path / "without.csv"
+    qb.qv2_write_config(str(p1), keep, names)
+    qb.qv2_write_config(str(p2), keep)
+    assert p1.read_text() == orc.config_text(list(keep), names)
+    assert p2.read_text() == orc.config_text(list(keep))
+    assert p2.read_text().splitlines()[1] == f"0,layer0,{32 if keep[0] else 8}"
+    # from a ranking: the first layers of the list are the ones at 32 bits
+    order = rng.permutation(n).astype(np.int32)
+    macs = rng.uniform(1e6, 1e8, n)
+    flags, kept, pct = qb.qv2_bops_select(order, macs, 50.0)
+    qb.qv2_write_config(str(p1), flags)
+    bits = [int(l.split(",")[2]) for l in p1.read_text().splitlines()[1:]]
+    assert sorted(i for i, b in enumerate(bits) if b == 32) == sorted(order[:kept].tolist())
+    for bad, status in (((str(p1), keep, ["a,b"] + names[1:]), qb.QV2_ERR_SHAPE),
+                        ((str(tmp_path / "no_such_dir" / "x.csv"), keep, None), qb.QV2_ERR_IO)):
+        with pytest.raises(qb.QV2Error) as e:
+            qb.qv2_write_config(*bad)
+        assert e.value.status == status
+    assert qb.lib().qv2_write_config(None, keep.ctypes.data, None, n) == qb.QV2_ERR_NULL
+    assert qb.lib().qv2_write_config(str(p1).encode(), keep.ctypes.data, None, 0) == qb.QV2_ERR_SHAPE
