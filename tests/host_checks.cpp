@@ -12,6 +12,7 @@
 #include <limits>
 #include <map>
 #include <random>
+#include <string>
 #include <vector>
 
 #include "qv2_internal.h"
@@ -453,9 +454,30 @@ void small_host_functions() {
   for (int s = 1; s >= -9; --s) CHECK(qv2_status_string(static_cast<qv2_status>(s)) != nullptr);
 }
 
+void config_file(const char* dir) {
+  const std::string path = std::string(dir) + "/qv2_host_checks_config.csv";
+  const uint8_t keep[4] = {1, 0, 0, 7};
+  const char* names[4] = {"conv1", "layer1.0.conv1", "layer1.0.conv2", "fc"};
+  CHECK(qv2_write_config(path.c_str(), keep, names, 4) == QV2_OK);
+  std::FILE* f = std::fopen(path.c_str(), "r");
+  CHECK(f != nullptr);
+  char buf[256] = {};
+  const size_t got = std::fread(buf, 1, sizeof buf - 1, f);
+  std::fclose(f);
+  CHECK(std::string(buf, got) == "layer,name,bits\n0,conv1,32\n1,layer1.0.conv1,8\n2,layer1.0.conv2,8\n3,fc,32\n");
+  CHECK(qv2_write_config(path.c_str(), keep, nullptr, 2) == QV2_OK);
+  const char* bad[2] = {"a", "b\nc"};
+  CHECK(qv2_write_config(path.c_str(), keep, bad, 2) == QV2_ERR_SHAPE);
+  const char* hole[2] = {"a", nullptr};
+  CHECK(qv2_write_config(path.c_str(), keep, hole, 2) == QV2_ERR_NULL);
+  CHECK(qv2_write_config((std::string(dir) + "/no/such/dir/x").c_str(), keep, nullptr, 2) == QV2_ERR_IO);
+  std::remove(path.c_str());
+}
+
 }  // namespace
 
-int main() {
+int main(int argc, char** argv) {
+  config_file(argc > 1 ? argv[1] : "/tmp");
   plans();
   ranking();
   rank_from_records();

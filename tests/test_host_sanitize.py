@@ -32,7 +32,7 @@ def test_host_code_under_sanitizers(tmp_path):
         r = _build(exe, False)
     assert r.returncode == 0, r.stderr[-3000:]
     env = dict(os.environ, ASAN_OPTIONS="detect_leaks=1:abort_on_error=0", UBSAN_OPTIONS="print_stacktrace=1")
-    run = subprocess.run([exe], capture_output=True, text=True, env=env, timeout=600)
+    run = subprocess.run([exe, str(tmp_path)], capture_output=True, text=True, env=env, timeout=600)
     assert run.returncode == 0, (run.stdout + run.stderr)[-3000:]
     assert "host checks ok" in run.stdout
     print("sanitizers:", "address+undefined" if sanitized else "not available, plain build")
