@@ -259,6 +259,25 @@ def main():
                                           "GBps": round(hist_bytes / np.mean(t_h) / 1e6, 1)},
                   "fused_quantize_with_cosine": {"kernel_ms": round(float(np.mean(t_c)), 4)}}
         del hx, hq, hws
+        # quantize + dequantize + error of single batch-1 activations (the shapes of the paper's
+        # Q-DQ overhead table, Sec. 7; its 341-1518 us per tensor are from other hardware: context)
+        qdq = {}
+        for shp in ((1, 256, 56, 56), (1, 512, 28, 28), (1, 1024, 14, 14), (1, 2048, 7, 7)):
+            t1 = torch.randn(shp, device=dev).clamp_(min=0)
+            c1 = torch.empty(t1.numel(), dtype=torch.int8, device=dev)
+            p1 = qb.qv2_plan_create([qb.TensorArg(x=t1, numel=t1.numel(), codes=c1)])
+            b1 = qb.Buffers(p1, dev)
+            qb.qv2_calibrate(p1, b1.params, b1.sums, b1.workspace)            # cached parameters
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            for rep in range(2):
+                e0.record()
+                for _ in range(200):
+                    qb.qv2_fakequant_metrics(p1, b1.params, b1.sums, b1.workspace)
+                e1.record()
+                torch.cuda.synchronize()
+            qdq["x".join(map(str, shp))] = round(e0.elapsed_time(e1) / 200 * 1e3, 2)
+            p1.close()
+        extras["fakequant_single_tensor_us"] = qdq
 
     if args.copy_probe:
         src = torch.ones(1 << 28, dtype=torch.float32, device=dev)      # 1 GiB
