@@ -306,6 +306,10 @@ void plans() {
   CHECK(qv2_plan_create(&bad, 1, &p) == QV2_ERR_ALIGN);
   bad = r; bad.x = nullptr;
   CHECK(qv2_plan_create(&bad, 1, &p) == QV2_ERR_NULL);
+  bad = r; bad.numel = int64_t{1} << 43;                        // more quantize tiles than an int32 holds
+  CHECK(qv2_plan_create(&bad, 1, &p) == QV2_ERR_SHAPE);
+  bad = r; bad.scheme = QV2_SYM_CHANNEL; bad.channels = 1; bad.numel = int64_t{1} << 43;
+  CHECK(qv2_plan_create(&bad, 1, &p) == QV2_ERR_SHAPE);
 }
 
 void ranking() {
