@@ -246,7 +246,8 @@ def main():
         hws = torch.zeros(qb.qv2_histogram_workspace_bytes(plan, nb), dtype=torch.uint8, device=dev)
         sxh = torch.zeros(plan.num_segments, dtype=torch.float64, device=dev)
         pxq = torch.zeros(plan.num_tensors, dtype=torch.float64, device=dev)
-        t_h, t_c = [], []
+        t_h, t_c, t_s = [], [], []
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         for it in range(5):
             qb.qv2_histogram(plan, buf.params, nb, hx, hq, hws)
             qb.qv2_fakequant_pair_metrics_cos(plan, buf.params, buf.sums, buf.pair, sxh, pxq, buf.workspace)
@@ -254,10 +255,18 @@ def main():
             if it >= 1:
                 t_h.append(qb.qv2_plan_kernel_ms(plan, "k_hist"))
                 t_c.append(qb.qv2_plan_kernel_ms(plan, "k_quantpair_stream"))
+            e0.record()
+            qb.qv2_calibrate_fakequant_pair_metrics_cos(plan, buf.params, buf.sums, buf.pair, sxh, pxq,
+                                                        buf.workspace)
+            e1.record()
+            torch.cuda.synchronize()
+            if it >= 1:
+                t_s.append(e0.elapsed_time(e1))
         hist_bytes = 4 * n_all + 4 * n_pair
         extras = {"histogram_2048_bins": {"kernel_ms": round(float(np.mean(t_h)), 4),
                                           "GBps": round(hist_bytes / np.mean(t_h) / 1e6, 1)},
-                  "fused_quantize_with_cosine": {"kernel_ms": round(float(np.mean(t_c)), 4)}}
+                  "fused_quantize_with_cosine": {"kernel_ms": round(float(np.mean(t_c)), 4)},
+                  "single_call_with_cosine": {"call_ms": round(float(np.mean(t_s)), 4)}}
         del hx, hq, hws
         # quantize + dequantize + error of single batch-1 activations (the shapes of the paper's
         # Q-DQ overhead table, Sec. 7; its 341-1518 us per tensor are from other hardware: context)

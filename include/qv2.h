@@ -220,8 +220,9 @@ qv2_status qv2_fakequant_pair_metrics(qv2_plan* plan, const qv2_qparams* d_param
                                       void* d_workspace, size_t workspace_bytes, void* hip_stream);
 
 /* Steps 1-3 in one call (Sec. 4 steps 1-3; Eq. 1-5; Algorithm 2's D[i] / Q[i]): the
- * results of qv2_calibrate followed by qv2_fakequant_pair_metrics (parameters, codes and
- * per-segment sums bit for bit; pair sums up to fp64 summation order), with every tensor
+ * results of qv2_calibrate followed by qv2_fakequant_pair_metrics (parameters, codes, sum_x
+ * and sum_e2 bit for bit; sum_x2, which stays the calibration sweep's instead of being summed
+ * again, and the pair sums up to fp64 summation order), with every tensor
  * made of short segments (per-output-channel tensors whose channel has at most 8192
  * elements) read from HBM ONCE: a group of whole channels is staged in LDS, and range,
  * parameters, codes and energies of each channel are taken from that copy.  Longer
@@ -234,6 +235,17 @@ qv2_status qv2_calibrate_fakequant_pair_metrics(qv2_plan* plan, qv2_qparams* d_p
                                                 qv2_sums* d_sums, qv2_pair_sums* d_pair_sums,
                                                 void* d_workspace, size_t workspace_bytes,
                                                 void* hip_stream);
+
+/* qv2_calibrate_fakequant_pair_metrics that also accumulates the cross terms of the cosine
+ * similarity (Sec. 6.1 Eq. 8): d_seg_xxhat[num_segments] and d_pair_xq[num_tensors] as in
+ * qv2_fakequant_pair_metrics_cos (DEVICE, written, 8-byte aligned; all three of d_pair_sums,
+ * d_seg_xxhat and d_pair_xq are required).  sum x * qrun is taken in the read-only calibration
+ * sweep and sum x * xhat in the quantize sweep, so the cosine costs no extra pass over memory. */
+qv2_status qv2_calibrate_fakequant_pair_metrics_cos(qv2_plan* plan, qv2_qparams* d_params,
+                                                    qv2_sums* d_sums, qv2_pair_sums* d_pair_sums,
+                                                    double* d_seg_xxhat, double* d_pair_xq,
+                                                    void* d_workspace, size_t workspace_bytes,
+                                                    void* hip_stream);
 
 /* qv2_fakequant_pair_metrics that also accumulates the cross terms of the cosine
  * similarity (Sec. 6.1 Eq. 8, one of the paper's four candidate local metrics):

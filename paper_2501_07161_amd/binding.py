@@ -27,7 +27,8 @@ EXPORTS = (
     "qv2_plan_segment_begin", "qv2_plan_num_tiles", "qv2_plan_num_quant_tiles",
     "qv2_plan_num_pair_tiles",
     "qv2_workspace_bytes", "qv2_calibrate", "qv2_fakequant_metrics", "qv2_pair_metrics",
-    "qv2_fakequant_pair_metrics", "qv2_calibrate_fakequant_pair_metrics", "qv2_fakequant_pair_metrics_cos", "qv2_cosine_finalize",
+    "qv2_fakequant_pair_metrics", "qv2_calibrate_fakequant_pair_metrics", "qv2_calibrate_fakequant_pair_metrics_cos",
+    "qv2_fakequant_pair_metrics_cos", "qv2_cosine_finalize",
     "qv2_plan_set_timing", "qv2_plan_kernel_ms", "qv2_plan_kernels_ms", "qv2_histogram_workspace_bytes", "qv2_histogram",
     "qv2_kl_divergence", "qv2_bn_fold", "qv2_regroup_for_fusion", "qv2_tensor_sums_fold",
     "qv2_finalize_tensors",
@@ -101,6 +102,7 @@ def lib():
         L.qv2_fakequant_pair_metrics.argtypes = [vp, vp, vp, vp, vp, sz, vp]
         L.qv2_calibrate_fakequant_pair_metrics.argtypes = [vp, vp, vp, vp, vp, sz, vp]
         L.qv2_fakequant_pair_metrics_cos.argtypes = [vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.qv2_calibrate_fakequant_pair_metrics_cos.argtypes = [vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.qv2_cosine_finalize.argtypes = [vp, vp, vp, vp, vp, vp, vp]
         L.qv2_histogram_workspace_bytes.argtypes = [vp, i32]
         L.qv2_histogram_workspace_bytes.restype = sz
@@ -270,6 +272,14 @@ def qv2_calibrate_fakequant_pair_metrics(plan: Plan, d_params, d_sums, d_pair_su
     _check(lib().qv2_calibrate_fakequant_pair_metrics(
         plan.handle, _ptr(d_params), _ptr(d_sums), _ptr(d_pair_sums) if d_pair_sums is not None else None,
         _ptr(d_workspace), wb, _stream(stream)), "qv2_calibrate_fakequant_pair_metrics")
+
+
+def qv2_calibrate_fakequant_pair_metrics_cos(plan: Plan, d_params, d_sums, d_pair_sums, d_seg_xxhat, d_pair_xq,
+                                             d_workspace, workspace_bytes=None, stream=None):
+    wb = workspace_bytes if workspace_bytes is not None else d_workspace.numel() * d_workspace.element_size()
+    _check(lib().qv2_calibrate_fakequant_pair_metrics_cos(
+        plan.handle, _ptr(d_params), _ptr(d_sums), _ptr(d_pair_sums), _ptr(d_seg_xxhat), _ptr(d_pair_xq),
+        _ptr(d_workspace), wb, _stream(stream)), "qv2_calibrate_fakequant_pair_metrics_cos")
 
 
 def qv2_fakequant_pair_metrics_cos(plan: Plan, d_params, d_sums, d_pair_sums, d_seg_xxhat, d_pair_xq,

@@ -210,7 +210,7 @@ qv2_status qv2_plan_create(const qv2_tensor* h_tensors, int32_t n_tensors, qv2_p
     if (p->stat_pair_tensors[i].nparts > qv2::kFoldWaveMax)
       p->big_stat_pair_tensors.push_back(static_cast<int32_t>(i));
   }
-  const size_t need = std::max({static_cast<size_t>(sp) * sizeof(qv2::StatPairPartial),
+  const size_t need = std::max({static_cast<size_t>(sp) * sizeof(qv2::StatPairCosPartial),
                                 static_cast<size_t>(ep) * sizeof(qv2::ErrPartial5),
                                 static_cast<size_t>(pp) * sizeof(qv2::ErrPartial)});
   p->workspace_bytes = std::max<size_t>(256, round_up(need, 256));

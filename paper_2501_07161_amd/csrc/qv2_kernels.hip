@@ -177,7 +177,8 @@ __device__ __forceinline__ float quant1(float x, const QP& q, float& err, float&
 }
 
 // COS: also accumulate sum x*xhat (the cross term of the cosine similarity, Sec. 6.1 Eq. 8)
-template <bool COS>
+// X2 = false leaves sum x^2 out (the caller already has it from the calibration sweep)
+template <bool COS, bool X2 = true>
 __device__ __forceinline__ uint32_t quant4(const f4& v, const QP& q, Acc4& se2, Acc4& sx2, Acc4& sxh) {
   float e0, e1, e2, e3, h0, h1, h2, h3;
   const int c0 = static_cast<int>(quant1(v.x, q, e0, h0));
@@ -186,7 +187,7 @@ __device__ __forceinline__ uint32_t quant4(const f4& v, const QP& q, Acc4& se2, 
   const int c3 = static_cast<int>(quant1(v.w, q, e3, h3));
   const f4 h = {h0, h1, h2, h3};
   se2.add_sq(e0, e1, e2, e3);
-  sx2.add_sq(v.x, v.y, v.z, v.w);
+  if (X2) sx2.add_sq(v.x, v.y, v.z, v.w);
   if (COS) sxh.add_prod(v, h);
   return (static_cast<uint32_t>(c0) & 0xffu) | ((static_cast<uint32_t>(c1) & 0xffu) << 8) |
          ((static_cast<uint32_t>(c2) & 0xffu) << 16) | (static_cast<uint32_t>(c3) << 24);
@@ -201,15 +202,17 @@ __device__ __forceinline__ QP load_qp(const qv2_qparams* __restrict__ params, in
 // pass 1 (calibration stage, Sec. 5; x_min / x_max of Eq. 2): stream tiles
 // ---------------------------------------------------------------------------
 // partial record of the calibration pass: with the pair comparison it also carries sum (x - qrun)^2
-template <bool PAIR> struct StatRec { typedef StatPartial type; };
-template <> struct StatRec<true> { typedef StatPairPartial type; };
-__device__ __forceinline__ void set_pair_energy(StatPartial&, double) {}
-__device__ __forceinline__ void set_pair_energy(StatPairPartial& o, double sd2) { o.sd2 = sd2; }
+template <bool PAIR, bool COS = false> struct StatRec { typedef StatPartial type; };
+template <> struct StatRec<true, false> { typedef StatPairPartial type; };
+template <> struct StatRec<true, true> { typedef StatPairCosPartial type; };
+__device__ __forceinline__ void set_pair_energy(StatPartial&, double, double) {}
+__device__ __forceinline__ void set_pair_energy(StatPairPartial& o, double sd2, double) { o.sd2 = sd2; }
+__device__ __forceinline__ void set_pair_energy(StatPairCosPartial& o, double sd2, double sxq) { o.sd2 = sd2; o.sxq = sxq; }
 
 struct StatAcc {
   f4 mn4 = {INFINITY, INFINITY, INFINITY, INFINITY};
   f4 mx4 = {-INFINITY, -INFINITY, -INFINITY, -INFINITY};
-  Acc4 s, s2, d2;
+  Acc4 s, s2, d2, xq;
   __device__ __forceinline__ void take(const f4& r) {
     mn4.x = fminf(mn4.x, r.x); mn4.y = fminf(mn4.y, r.y);
     mn4.z = fminf(mn4.z, r.z); mn4.w = fminf(mn4.w, r.w);
@@ -220,7 +223,7 @@ struct StatAcc {
 };
 
 // vector body of a calibration tile; WITHB: a second stream (qrun) is compared in the same visit
-template <int BLOCK, int V, bool WITHB>
+template <int BLOCK, int V, bool WITHB, bool COS>
 __device__ __forceinline__ void stats_body(gf4_ptr v4, gf4_ptr b4, int nvec, StatAcc& a) {
   const int tid = threadIdx.x;
   int base = 0;
@@ -235,6 +238,7 @@ __device__ __forceinline__ void stats_body(gf4_ptr v4, gf4_ptr b4, int nvec, Sta
     for (int u = 0; u < V; ++u) {
       a.take(r[u]);
       if (WITHB) a.d2.add_sq(r[u].x - g[u].x, r[u].y - g[u].y, r[u].z - g[u].z, r[u].w - g[u].w);
+      if (WITHB && COS) a.xq.add_prod(r[u], g[u]);
     }
   }
   for (int i = base + tid; i < nvec; i += BLOCK) {
@@ -243,15 +247,17 @@ __device__ __forceinline__ void stats_body(gf4_ptr v4, gf4_ptr b4, int nvec, Sta
     if (WITHB) {
       const f4 g = ld4(b4 + i);
       a.d2.add_sq(r.x - g.x, r.y - g.y, r.z - g.z, r.w - g.w);
+      if (COS) a.xq.add_prod(r, g);
     }
   }
 }
 
 // PAIR: tiles whose tensor has a quantized-run partner also yield sum (x - qrun)^2 (Algorithm 2's
 // D[i] against Q[i]) from the same visit: 8 B read per element, nothing but the partial written.
-template <int BLOCK, int V, bool PAIR>
+// COS: also sum x * qrun, the cross term of cos(x, qrun) (Sec. 6.1 Eq. 8).
+template <int BLOCK, int V, bool PAIR, bool COS>
 __global__ __launch_bounds__(BLOCK) void k_stats_stream(const Tile* __restrict__ tiles,
-                                                        typename StatRec<PAIR>::type* __restrict__ parts) {
+                                                        typename StatRec<PAIR, COS>::type* __restrict__ parts) {
   const Tile tl = tiles[blockIdx.x];
   const gf_ptr p = (gf_ptr)tl.x;
   const gf_ptr b = (gf_ptr)tl.q;
@@ -263,11 +269,13 @@ __global__ __launch_bounds__(BLOCK) void k_stats_stream(const Tile* __restrict__
   const bool b_vec = has_b && (((reinterpret_cast<uintptr_t>(tl.x) ^ reinterpret_cast<uintptr_t>(tl.q)) & 15u) == 0);
 
   float mn = INFINITY, mx = -INFINITY;
-  double sx = 0.0, sx2 = 0.0, sd2 = 0.0;
+  double sx = 0.0, sx2 = 0.0, sd2 = 0.0, sxq = 0.0;
   if (has_b && !b_vec) {
     for (int i = tid; i < len; i += BLOCK) {
-      const double d = static_cast<double>(p[i] - b[i]);
+      const float xv = p[i], qv = b[i];
+      const double d = static_cast<double>(xv - qv);
       sd2 = fma(d, d, sd2);
+      if (COS) sxq = fma(static_cast<double>(xv), static_cast<double>(qv), sxq);
     }
   }
   for (int k = 0; k < 2; ++k) {
@@ -278,25 +286,32 @@ __global__ __launch_bounds__(BLOCK) void k_stats_stream(const Tile* __restrict__
     mn = fminf(mn, v); mx = fmaxf(mx, v);
     sx += v; sx2 += static_cast<double>(v) * v;
     if (b_vec) {
-      const float d = v - b[idx];
+      const float qv = b[idx], d = v - qv;
       sd2 += static_cast<double>(d) * d;
+      if (COS) sxq = fma(static_cast<double>(v), static_cast<double>(qv), sxq);
     }
   }
   const gf4_ptr v4 = (gf4_ptr)(tl.x + head);
   const gf4_ptr b4 = (gf4_ptr)(tl.q + head);
   StatAcc a;
-  if (PAIR && b_vec) stats_body<BLOCK, (V > 1 ? V / 2 : 1), true>(v4, b4, nvec, a);
-  else stats_body<BLOCK, V, false>(v4, b4, nvec, a);
-  sx += a.s.total(); sx2 += a.s2.total(); sd2 += a.d2.total();
+  if (PAIR && b_vec) stats_body<BLOCK, (V > 1 ? V / 2 : 1), true, COS>(v4, b4, nvec, a);
+  else stats_body<BLOCK, V, false, false>(v4, b4, nvec, a);
+  sx += a.s.total(); sx2 += a.s2.total(); sd2 += a.d2.total(); sxq += a.xq.total();
   mn = fminf(fminf(mn, a.mn4.x), fminf(fminf(a.mn4.y, a.mn4.z), a.mn4.w));
   mx = fmaxf(fmaxf(mx, a.mx4.x), fmaxf(fmaxf(a.mx4.y, a.mx4.z), a.mx4.w));
 
   block_minmax<BLOCK>(mn, mx);
-  block_sum3<BLOCK>(sx, sx2, sd2);
+  if (COS) {
+    double v[4] = {sx, sx2, sd2, sxq};
+    block_sum<BLOCK, 4>(v);
+    sx = v[0]; sx2 = v[1]; sd2 = v[2]; sxq = v[3];
+  } else {
+    block_sum3<BLOCK>(sx, sx2, sd2);
+  }
   if (tid == 0) {
-    typename StatRec<PAIR>::type o;
+    typename StatRec<PAIR, COS>::type o;
     o.mn = mn; o.mx = mx; o.sx = sx; o.sx2 = sx2;
-    set_pair_energy(o, sd2);
+    set_pair_energy(o, sd2, sxq);
     parts[tl.part0] = o;
   }
 }
@@ -542,24 +557,30 @@ __device__ __forceinline__ void fold_stats_item(const FoldIdx& f, const Segment*
 
 // pair energies of one tensor from calibration partials that carry them; tensors not listed
 // there (n == 0) are left to the fold after the quantize pass
+__device__ __forceinline__ double stat_cross(const StatPairPartial&) { return 0.0; }
+__device__ __forceinline__ double stat_cross(const StatPairCosPartial& p) { return p.sxq; }
+
+template <class REC>
 __device__ __forceinline__ void fold_statpair_item(const FoldIdx& f, const PairTensor* __restrict__ pt,
-                                                   const StatPairPartial* __restrict__ parts,
-                                                   qv2_pair_sums* __restrict__ out) {
+                                                   const REC* __restrict__ parts,
+                                                   qv2_pair_sums* __restrict__ out,
+                                                   double* __restrict__ pair_xq) {
   if (!f.active) return;
   const PairTensor p = pt[f.id];
   if (p.n == 0) return;
   if (!f.wide && p.nparts > kFoldWaveMax) return;
-  double sr2 = 0.0, sd2 = 0.0, unused = 0.0;
+  double sr2 = 0.0, sd2 = 0.0, sxq = 0.0;
 #pragma unroll 4
   for (int i = f.lane; i < p.nparts; i += f.stride) {
-    const StatPairPartial q = parts[p.part0 + i];
-    sr2 += q.sx2; sd2 += q.sd2;
+    const REC q = parts[p.part0 + i];
+    sr2 += q.sx2; sd2 += q.sd2; sxq += stat_cross(q);
   }
-  fold_sum3(f.wide, sr2, sd2, unused);
+  fold_sum3(f.wide, sr2, sd2, sxq);
   if (f.lane == 0) {
     qv2_pair_sums o;
     o.sum_ref2 = sr2; o.sum_d2 = sd2; o.n = p.n; o._pad = 0;
     out[f.id] = o;
+    if (pair_xq) pair_xq[f.id] = sxq;
   }
 }
 
@@ -568,13 +589,14 @@ struct StatFoldArgs {
   const Segment* segs; int nseg; const int* wide_segs; int n_wide_segs;
   const REC* parts; qv2_qparams* params; qv2_sums* sums; int skip_below;
   const PairTensor* pt; int nt; const int* wide_pt; int n_wide_pt;     // pair_out == null: none
-  qv2_pair_sums* pair_out;
+  qv2_pair_sums* pair_out; double* pair_xq;
   int seg_blocks;
 };
 
 __device__ __forceinline__ void fold_statpair_family(const StatFoldArgs<StatPartial>&, int) {}
-__device__ __forceinline__ void fold_statpair_family(const StatFoldArgs<StatPairPartial>& a, int b) {
-  fold_statpair_item(FoldIdx(b, a.wide_pt, a.n_wide_pt, a.nt), a.pt, a.parts, a.pair_out);
+template <class REC>
+__device__ __forceinline__ void fold_statpair_family(const StatFoldArgs<REC>& a, int b) {
+  fold_statpair_item<REC>(FoldIdx(b, a.wide_pt, a.n_wide_pt, a.nt), a.pt, a.parts, a.pair_out, a.pair_xq);
 }
 
 template <class REC>
@@ -602,11 +624,15 @@ __device__ __forceinline__ double pair_energy(const ErrPartial5& p) { return p.s
 template <class P>
 __device__ __forceinline__ void fold_err_item(const FoldIdx& f, const Segment* __restrict__ segs,
                                               const P* __restrict__ parts, qv2_sums* __restrict__ sums,
-                                              double* __restrict__ seg_xxhat, int skip_below) {
+                                              double* __restrict__ seg_xxhat, int skip_below,
+                                              bool keep_x2) {
   if (!f.active) return;
   const Segment sg = segs[f.id];
   if (!f.wide && sg.enp > kFoldWaveMax) return;
-  if (sg.ep0 < skip_below) return;
+  if (sg.ep0 < skip_below) {         // a row its kernel has finished: only the cross term is left to copy
+    if (seg_xxhat && f.lane == 0) seg_xxhat[f.id] = cross_xh(parts[sg.ep0]);
+    return;
+  }
   double sx2 = 0.0, se2 = 0.0, sxh = 0.0;
 #pragma unroll 4
   for (int i = f.lane; i < sg.enp; i += f.stride) {
@@ -615,7 +641,8 @@ __device__ __forceinline__ void fold_err_item(const FoldIdx& f, const Segment* _
   }
   fold_sum3(f.wide, sx2, se2, sxh);
   if (f.lane == 0) {
-    sums[f.id].sum_x2 = sx2; sums[f.id].sum_e2 = se2; sums[f.id].n = sg.n;
+    if (!keep_x2) sums[f.id].sum_x2 = sx2;         // else the calibration sweep's sum stays
+    sums[f.id].sum_e2 = se2; sums[f.id].n = sg.n;
     if (seg_xxhat) seg_xxhat[f.id] = sxh;
   }
 }
@@ -650,7 +677,7 @@ __device__ __forceinline__ void fold_pair_item(const FoldIdx& f, const PairTenso
 template <class P>
 struct QuantFoldArgs {
   const Segment* segs; int nseg; const int* wide_segs; int n_wide_segs;
-  qv2_sums* sums; double* seg_xxhat; int skip_below;
+  qv2_sums* sums; double* seg_xxhat; int skip_below; bool keep_x2;
   const PairTensor* pt; int nt; const int* wide_pt; int n_wide_pt;     // pair_out == null: none
   qv2_pair_sums* pair_out; double* pair_xq;
   const PairTensor* pair_done;               // tensors with n != 0 here are skipped (may be null)
@@ -663,7 +690,7 @@ __global__ __launch_bounds__(kFoldBlock) void k_fold_quant(const QuantFoldArgs<P
   const int b = blockIdx.x;
   if (b < a.seg_blocks) {
     fold_err_item<P>(FoldIdx(b, a.wide_segs, a.n_wide_segs, a.nseg), a.segs, a.parts, a.sums,
-                     a.seg_xxhat, a.skip_below);
+                     a.seg_xxhat, a.skip_below, a.keep_x2);
   } else {
     fold_pair_item<P>(FoldIdx(b - a.seg_blocks, a.wide_pt, a.n_wide_pt, a.nt), a.pt, a.parts,
                       a.pair_out, a.pair_xq, a.pair_done);
@@ -683,7 +710,7 @@ __global__ __launch_bounds__(kFoldBlock) void k_fold_pair(
 // Per element 4 B read + 1 B code written (+ 4 B of qrun read when PAIR).
 // ---------------------------------------------------------------------------
 // STORE: 0 no code buffer, 1 packed dwords, 2 single bytes (misaligned code buffer)
-template <int BLOCK, int V, int STORE, bool PAIR, bool COS>
+template <int BLOCK, int V, int STORE, bool PAIR, bool COS, bool X2>
 __device__ __forceinline__ void quant_body(gf4_ptr v4, gf4_ptr b4, gu32_ptr cw, gi8_ptr cb, int nvec,
                                            const QP& q, Acc4& ae2, Acc4& ax2, Acc4& ad2, Acc4& axh,
                                            Acc4& axq) {
@@ -707,14 +734,14 @@ __device__ __forceinline__ void quant_body(gf4_ptr v4, gf4_ptr b4, gu32_ptr cw, 
     }
 #pragma unroll
     for (int u = 0; u < V; ++u) {
-      put(base + u * BLOCK + tid, quant4<COS>(r[u], q, ae2, ax2, axh));
+      put(base + u * BLOCK + tid, quant4<COS, X2>(r[u], q, ae2, ax2, axh));
       if (PAIR) ad2.add_sq(r[u].x - g[u].x, r[u].y - g[u].y, r[u].z - g[u].z, r[u].w - g[u].w);
       if (PAIR && COS) axq.add_prod(r[u], g[u]);
     }
   }
   for (int i = base + tid; i < nvec; i += BLOCK) {
     const f4 r = ld4(v4 + i);
-    put(i, quant4<COS>(r, q, ae2, ax2, axh));
+    put(i, quant4<COS, X2>(r, q, ae2, ax2, axh));
     if (PAIR) {
       const f4 g = ld4(b4 + i);
       ad2.add_sq(r.x - g.x, r.y - g.y, r.z - g.z, r.w - g.w);
@@ -726,14 +753,17 @@ __device__ __forceinline__ void quant_body(gf4_ptr v4, gf4_ptr b4, gu32_ptr cw, 
 #ifndef QV2_QUANT_WAVES_PER_EU
 #define QV2_QUANT_WAVES_PER_EU 1    // occupancy floor asked of the register allocator
 #endif
+#ifndef QV2_QUANT_PLAIN_WAVES_PER_EU
+#define QV2_QUANT_PLAIN_WAVES_PER_EU 8
+#endif
 // partial record of a quantize pass: 3 energies, plus the 2 cross terms when COS
 template <bool COS> struct ErrRec { typedef ErrPartial3 type; };
 template <> struct ErrRec<true> { typedef ErrPartial5 type; };
 __device__ __forceinline__ void set_cross(ErrPartial3&, double, double) {}
 __device__ __forceinline__ void set_cross(ErrPartial5& o, double sxh, double sxq) { o.sxh = sxh; o.sxq = sxq; }
 
-template <int BLOCK, int V, bool PAIR, bool COS>
-__global__ __launch_bounds__(BLOCK, QV2_QUANT_WAVES_PER_EU) void k_quant_stream(
+template <int BLOCK, int V, bool PAIR, bool COS, bool X2 = true>
+__global__ __launch_bounds__(BLOCK, (PAIR ? QV2_QUANT_WAVES_PER_EU : QV2_QUANT_PLAIN_WAVES_PER_EU)) void k_quant_stream(
     const Tile* __restrict__ tiles, const qv2_qparams* __restrict__ params,
     typename ErrRec<COS>::type* __restrict__ parts) {
   // Workgroups go to the 8 XCDs in turn.  The plain sweep (one read stream, one store stream)
@@ -774,7 +804,7 @@ __global__ __launch_bounds__(BLOCK, QV2_QUANT_WAVES_PER_EU) void k_quant_stream(
     float e, h;
     const float code = quant1(v, q, e, h);
     if (has_c) c[idx] = static_cast<int8_t>(static_cast<int>(code));
-    sx2 += static_cast<double>(v) * v;
+    if (X2) sx2 += static_cast<double>(v) * v;
     se2 += static_cast<double>(e) * e;
     if (COS) sxh = fma(static_cast<double>(v), static_cast<double>(h), sxh);
     if (b_vec) {
@@ -790,13 +820,13 @@ __global__ __launch_bounds__(BLOCK, QV2_QUANT_WAVES_PER_EU) void k_quant_stream(
   const bool cw_ok = has_c && ((reinterpret_cast<uintptr_t>(tl.c + head) & 3u) == 0);
   Acc4 ae2, ax2, ad2, axh, axq;
   if (b_vec) {
-    if (cw_ok) quant_body<BLOCK, V, 1, PAIR, COS>(v4, b4, cw, cb, nvec, q, ae2, ax2, ad2, axh, axq);
-    else if (has_c) quant_body<BLOCK, V, 2, PAIR, COS>(v4, b4, cw, cb, nvec, q, ae2, ax2, ad2, axh, axq);
-    else quant_body<BLOCK, V, 0, PAIR, COS>(v4, b4, cw, cb, nvec, q, ae2, ax2, ad2, axh, axq);
+    if (cw_ok) quant_body<BLOCK, V, 1, PAIR, COS, X2>(v4, b4, cw, cb, nvec, q, ae2, ax2, ad2, axh, axq);
+    else if (has_c) quant_body<BLOCK, V, 2, PAIR, COS, X2>(v4, b4, cw, cb, nvec, q, ae2, ax2, ad2, axh, axq);
+    else quant_body<BLOCK, V, 0, PAIR, COS, X2>(v4, b4, cw, cb, nvec, q, ae2, ax2, ad2, axh, axq);
   } else {
-    if (cw_ok) quant_body<BLOCK, V, 1, false, COS>(v4, b4, cw, cb, nvec, q, ae2, ax2, ad2, axh, axq);
-    else if (has_c) quant_body<BLOCK, V, 2, false, COS>(v4, b4, cw, cb, nvec, q, ae2, ax2, ad2, axh, axq);
-    else quant_body<BLOCK, V, 0, false, COS>(v4, b4, cw, cb, nvec, q, ae2, ax2, ad2, axh, axq);
+    if (cw_ok) quant_body<BLOCK, V, 1, false, COS, X2>(v4, b4, cw, cb, nvec, q, ae2, ax2, ad2, axh, axq);
+    else if (has_c) quant_body<BLOCK, V, 2, false, COS, X2>(v4, b4, cw, cb, nvec, q, ae2, ax2, ad2, axh, axq);
+    else quant_body<BLOCK, V, 0, false, COS, X2>(v4, b4, cw, cb, nvec, q, ae2, ax2, ad2, axh, axq);
   }
   se2 += ae2.total(); sx2 += ax2.total(); sd2 += ad2.total();
   typename ErrRec<COS>::type o;
@@ -805,6 +835,10 @@ __global__ __launch_bounds__(BLOCK, QV2_QUANT_WAVES_PER_EU) void k_quant_stream(
     block_sum<BLOCK, 5>(v);
     o.sx2 = v[0]; o.se2 = v[1]; o.sd2 = v[2];
     set_cross(o, v[3], v[4]);
+  } else if (!X2 && !PAIR) {
+    double v[1] = {se2};                            // the only energy this form takes
+    block_sum<BLOCK, 1>(v);
+    o.sx2 = 0.0; o.se2 = v[0]; o.sd2 = 0.0;
   } else {
     block_sum3<BLOCK>(sx2, se2, sd2);
     o.sx2 = sx2; o.se2 = se2; o.sd2 = sd2;
@@ -1399,6 +1433,9 @@ void launch_quant(qv2_plan* plan, const qv2_qparams* d_params, qv2_sums* d_sums,
     if (PAIR && !pair_in_stats)
       hipLaunchKernelGGL((k_quant_stream<kBlockQuant, kVecQuant, PAIR, COS>), dim3(n_stream),
                          dim3(kBlockQuant), 0, s, plan->d_quant_tiles, d_params, parts);
+    else if (calib_rows)      // the calibration sweep of this same call already summed x^2
+      hipLaunchKernelGGL((k_quant_stream<kBlockQuant, kVecQuant, false, COS, false>), dim3(n_stream),
+                         dim3(kBlockQuant), 0, s, plan->d_quant_tiles, d_params, parts);
     else
       hipLaunchKernelGGL((k_quant_stream<kBlockQuant, kVecQuant, false, COS>), dim3(n_stream),
                          dim3(kBlockQuant), 0, s, plan->d_quant_tiles, d_params, parts);
@@ -1416,6 +1453,7 @@ void launch_quant(qv2_plan* plan, const qv2_qparams* d_params, qv2_sums* d_sums,
   a.segs = plan->d_segments; a.nseg = static_cast<int>(plan->segments.size());
   a.wide_segs = plan->d_big_err_segments; a.n_wide_segs = static_cast<int>(plan->big_err_segments.size());
   a.sums = d_sums; a.seg_xxhat = d_seg_xxhat; a.skip_below = calib_rows ? plan->n_row_parts : 0;
+  a.keep_x2 = calib_rows && (!PAIR || pair_in_stats);
   a.parts = parts;
   a.seg_blocks = fold_blocks(a.n_wide_segs, a.nseg);
   int blocks = a.seg_blocks;
@@ -1433,17 +1471,17 @@ void launch_quant(qv2_plan* plan, const qv2_qparams* d_params, qv2_sums* d_sums,
 // calibration over the stream tiles (and the row-group tiles unless their own single-read
 // kernel will calibrate them), then the statistics fold.  PAIR: the same sweep compares the
 // stream tensors with their quantized-run partners and the fold writes their pair sums.
-template <bool PAIR>
+template <bool PAIR, bool COS = false>
 void launch_stats(qv2_plan* plan, qv2_qparams* d_params, qv2_sums* d_sums,
-                  typename StatRec<PAIR>::type* parts, bool with_rows, qv2_pair_sums* d_pair_sums,
-                  hipStream_t s) {
-  typedef typename StatRec<PAIR>::type REC;
+                  typename StatRec<PAIR, COS>::type* parts, bool with_rows, qv2_pair_sums* d_pair_sums,
+                  double* d_pair_xq, hipStream_t s) {
+  typedef typename StatRec<PAIR, COS>::type REC;
   if (PAIR) with_rows = false;      // the row kernel of this pass writes 24-byte records: not in a PAIR sweep
   const int n_stream = static_cast<int>(plan->read_tiles.size());
   const int n_rows = static_cast<int>(plan->row_tiles.size());
   if (n_stream > 0) {
     Timed timed(plan, PAIR ? QV2_K_STATSPAIR_STREAM : QV2_K_STATS_STREAM, s);
-    hipLaunchKernelGGL((k_stats_stream<kBlockRead, kVecRead, PAIR>), dim3(n_stream), dim3(kBlockRead), 0, s,
+    hipLaunchKernelGGL((k_stats_stream<kBlockRead, kVecRead, PAIR, COS>), dim3(n_stream), dim3(kBlockRead), 0, s,
                        plan->d_read_tiles, parts);
   }
   const int n_regs = static_cast<int>(plan->reg_tiles.size());
@@ -1470,7 +1508,7 @@ void launch_stats(qv2_plan* plan, qv2_qparams* d_params, qv2_sums* d_sums,
       a.pt = plan->d_stat_pair_tensors; a.nt = static_cast<int>(plan->stat_pair_tensors.size());
       a.wide_pt = plan->d_big_stat_pair_tensors;
       a.n_wide_pt = static_cast<int>(plan->big_stat_pair_tensors.size());
-      a.pair_out = d_pair_sums;
+      a.pair_out = d_pair_sums; a.pair_xq = d_pair_xq;
       blocks += fold_blocks(a.n_wide_pt, a.nt);
     }
     hipLaunchKernelGGL(k_fold_stats<REC>, dim3(blocks), dim3(kFoldBlock), 0, s, a);
@@ -1534,7 +1572,7 @@ qv2_status qv2_calibrate(qv2_plan* plan, qv2_qparams* d_params, qv2_sums* d_sums
   qv2_status st = check_call(plan, d_params, d_sums, d_workspace, workspace_bytes);
   if (st != QV2_OK) return st;
   if ((st = ensure_uploaded(plan)) != QV2_OK) return st;
-  launch_stats<false>(plan, d_params, d_sums, static_cast<StatPartial*>(d_workspace), true, nullptr,
+  launch_stats<false>(plan, d_params, d_sums, static_cast<StatPartial*>(d_workspace), true, nullptr, nullptr,
                       static_cast<hipStream_t>(hip_stream));
   return launch_status();
 }
@@ -1597,12 +1635,33 @@ qv2_status qv2_calibrate_fakequant_pair_metrics(qv2_plan* plan, qv2_qparams* d_p
   // the workspace
   ErrPartial3* parts = static_cast<ErrPartial3*>(d_workspace);
   if (d_pair_sums) {
-    launch_stats<true>(plan, d_params, d_sums, static_cast<StatPairPartial*>(d_workspace), false, d_pair_sums, s);
+    launch_stats<true>(plan, d_params, d_sums, static_cast<StatPairPartial*>(d_workspace), false, d_pair_sums,
+                       nullptr, s);
     launch_quant<true, false>(plan, d_params, d_sums, parts, nullptr, d_pair_sums, nullptr, s, d_params, true);
   } else {
-    launch_stats<false>(plan, d_params, d_sums, static_cast<StatPartial*>(d_workspace), false, nullptr, s);
+    launch_stats<false>(plan, d_params, d_sums, static_cast<StatPartial*>(d_workspace), false, nullptr, nullptr, s);
     launch_quant<false, false>(plan, d_params, d_sums, parts, nullptr, nullptr, nullptr, s, d_params);
   }
+  return launch_status();
+}
+
+qv2_status qv2_calibrate_fakequant_pair_metrics_cos(qv2_plan* plan, qv2_qparams* d_params, qv2_sums* d_sums,
+                                                    qv2_pair_sums* d_pair_sums, double* d_seg_xxhat,
+                                                    double* d_pair_xq, void* d_workspace,
+                                                    size_t workspace_bytes, void* hip_stream) {
+  qv2_status st = check_call(plan, d_params, d_sums, d_workspace, workspace_bytes);
+  if (st != QV2_OK) return st;
+  if (!d_pair_sums || !d_seg_xxhat || !d_pair_xq) return QV2_ERR_NULL;
+  if ((reinterpret_cast<uintptr_t>(d_pair_sums) | reinterpret_cast<uintptr_t>(d_seg_xxhat) |
+       reinterpret_cast<uintptr_t>(d_pair_xq)) & 7u) return QV2_ERR_ALIGN;
+  if ((st = ensure_uploaded(plan)) != QV2_OK) return st;
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  // as the call without the cross terms: sum x * qrun rides on the read-only sweep, sum x * xhat
+  // on the quantize sweep
+  launch_stats<true, true>(plan, d_params, d_sums, static_cast<StatPairCosPartial*>(d_workspace), false,
+                           d_pair_sums, d_pair_xq, s);
+  launch_quant<true, true>(plan, d_params, d_sums, static_cast<ErrPartial5*>(d_workspace), d_seg_xxhat,
+                           d_pair_sums, d_pair_xq, s, d_params, true);
   return launch_status();
 }
 

@@ -109,7 +109,7 @@ def run_gpu(items: List[Item], params_override: Optional[np.ndarray] = None,
     plan = qb.qv2_plan_create(rows)
     buf = qb.Buffers(plan, dev)
     single = fused == "single"
-    assert not (single and (params_override is not None or cos or not do_calibrate))
+    assert not (single and (params_override is not None or not do_calibrate))
     if do_calibrate and not single:
         qb.qv2_calibrate(plan, buf.params, buf.sums, buf.workspace)
     if params_override is not None:
@@ -119,8 +119,12 @@ def run_gpu(items: List[Item], params_override: Optional[np.ndarray] = None,
     if cos:
         seg_xxhat = torch.zeros(plan.num_segments, dtype=torch.float64, device=dev)
         pair_xq = torch.zeros(plan.num_tensors, dtype=torch.float64, device=dev)
-        qb.qv2_fakequant_pair_metrics_cos(plan, buf.params, buf.sums, buf.pair, seg_xxhat, pair_xq,
-                                          buf.workspace)
+        if single:
+            qb.qv2_calibrate_fakequant_pair_metrics_cos(plan, buf.params, buf.sums, buf.pair, seg_xxhat,
+                                                        pair_xq, buf.workspace)
+        else:
+            qb.qv2_fakequant_pair_metrics_cos(plan, buf.params, buf.sums, buf.pair, seg_xxhat, pair_xq,
+                                              buf.workspace)
     elif single:
         qb.qv2_calibrate_fakequant_pair_metrics(plan, buf.params, buf.sums, buf.pair, buf.workspace)
     elif fused:
@@ -274,3 +278,13 @@ def check_ranking(items: List[Item], res: GpuResult, oracle_rows, cfg_kwargs=Non
         assert order2.tolist() == o_order
         assert np.allclose(score2, o_score, rtol=0, atol=2 * SQNR_ATOL_DB)
     return order.tolist()
+
+
+def same_sums_single_call(single: np.ndarray, other: np.ndarray):
+    """Per-segment sums of the single call against those of the separate calls: sum x, sum e^2 and
+    n bit for bit; sum x^2 up to fp64 summation order for segments cut into stream tiles (the
+    single call keeps the calibration sweep's sum instead of summing x^2 again while it
+    quantizes), bit for bit for the others."""
+    for f in ("sum_x", "sum_e2", "n"):
+        assert np.array_equal(single[f], other[f], equal_nan=True), f
+    assert np.allclose(single["sum_x2"], other["sum_x2"], rtol=1e-12, atol=0, equal_nan=True)

@@ -255,8 +255,8 @@ def test_fused_call_equals_the_two_separate_calls():
 
 def test_single_call_pass_equals_the_separate_calls():
     """qv2_calibrate_fakequant_pair_metrics (row-group tensors read from HBM once) against
-    qv2_calibrate + qv2_fakequant_pair_metrics: parameters, sums and codes equal bit for bit,
-    pair sums up to fp64 summation order; without pair sums it equals qv2_calibrate +
+    qv2_calibrate + qv2_fakequant_pair_metrics: parameters, codes, sum x and sum e^2 equal bit for
+    bit, sum x^2 and the pair sums up to fp64 summation order; without pair sums it equals qv2_calibrate +
     qv2_fakequant_metrics."""
     specs = synth.config_mobilenetv2(2) + synth.config_resnet50(2) + synth.config_tiny()
     items = H.items_from_specs(specs, DEV)
@@ -270,7 +270,7 @@ def test_single_call_pass_equals_the_separate_calls():
     r2 = H.run_gpu(items, fused="single")
     assert r2.plan.num_tiles > r2.plan.num_tensors          # row-group and stream tiles both present
     assert r1.params.tobytes() == r2.params.tobytes()
-    assert r1.sums.tobytes() == r2.sums.tobytes()
+    H.same_sums_single_call(r2.sums, r1.sums)
     assert np.array_equal(r1.pair["n"], r2.pair["n"])
     for f in ("sum_ref2", "sum_d2"):        # taken in the calibration sweep: other tile lengths
         assert np.allclose(r1.pair[f], r2.pair[f], rtol=1e-12, atol=0)
@@ -283,7 +283,8 @@ def test_single_call_pass_equals_the_separate_calls():
     qb.qv2_calibrate_fakequant_pair_metrics(r3.plan, buf.params, buf.sums, None, buf.workspace)
     torch.cuda.synchronize()
     params, sums, _ = buf.host()
-    assert params.tobytes() == r3.params.tobytes() and sums.tobytes() == r3.sums.tobytes()
+    assert params.tobytes() == r3.params.tobytes()
+    H.same_sums_single_call(sums, r3.sums)
     assert all(torch.equal(a, it.codes) for a, it in zip(c1, items))
 
 
@@ -306,6 +307,14 @@ def test_cosine_similarity_variant():
     r2 = H.run_gpu(items, cos=True)
     H.check_all(items, r2)
     assert r1.sums.tobytes() == r2.sums.tobytes() and r1.pair.tobytes() == r2.pair.tobytes()
+    assert all(torch.equal(a, it.codes) for a, it in zip(c1, items))
+    # the single call with the cross terms: same cosines, against the oracle again
+    r3 = H.run_gpu(items, fused="single", cos=True)
+    H.check_all(items, r3)
+    assert r3.params.tobytes() == r2.params.tobytes()
+    H.same_sums_single_call(r3.sums, r2.sums)
+    assert np.allclose(r3.cos_quant, r2.cos_quant, rtol=0, atol=1e-12, equal_nan=True)
+    assert np.allclose(r3.cos_pair, r2.cos_pair, rtol=0, atol=1e-12, equal_nan=True)
     assert all(torch.equal(a, it.codes) for a, it in zip(c1, items))
     names = [it.name for it in items]
     assert r2.cos_quant[names.index("zeros")] == 1.0 and r2.cos_pair[names.index("zeros")] == 1.0
