@@ -35,13 +35,13 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0   # MI355X published HBM3E bandwidth
-ROCPROF_NAMES = {"k_statspair_stream": "k_stats_stream<512, 8, true>",
+ROCPROF_NAMES = {"k_statspair_stream": "k_stats_stream<512, 8, true, false>",
                  "k_quantpair_stream": "k_quant_stream<256, 2, true, false>", "k_pair_stream": "k_pair_stream<512, 4>"}
 
 # HBM bytes per launch of the dominant kernel on the resnet50 b256 workload from rocprofv3
 # --pmc (FETCH_SIZE and WRITE_SIZE runs, each scaled by a copy kernel of known size); see
 # profiles/sensitivity_pass_resnet50_b256.txt.
-TRAFFIC_BYTES = {"k_statspair_stream": 21_697_537_538, "k_pair_stream": 21_697_224_407,
+TRAFFIC_BYTES = {"k_statspair_stream": 21_697_424_997, "k_pair_stream": 21_697_111_049,
                  "k_quantpair_stream": 24_627_581_264}
 
 
@@ -63,6 +63,8 @@ def parse():
     ap.add_argument("--cold", action="store_true",
                     help="also time every step after streaming a 1 GiB scratch buffer (evicts the 256 MB "
                          "Infinity Cache); matters only for sets that are not far larger than that cache")
+    ap.add_argument("--no-single-tensor-extra", action="store_true",
+                    help="skip the 1600 tiny fake-quant calls of extras.fakequant_single_tensor_us (profiling runs)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="after the timed region also run 3 plain 1 GiB device copies (a kernel of known "
                          "traffic, used to scale rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
@@ -271,7 +273,9 @@ def main():
         # quantize + dequantize + error of single batch-1 activations (the shapes of the paper's
         # Q-DQ overhead table, Sec. 7; its 341-1518 us per tensor are from other hardware: context)
         qdq = {}
-        for shp in ((1, 256, 56, 56), (1, 512, 28, 28), (1, 1024, 14, 14), (1, 2048, 7, 7)):
+        shapes = () if args.no_single_tensor_extra else ((1, 256, 56, 56), (1, 512, 28, 28), (1, 1024, 14, 14),
+                                                         (1, 2048, 7, 7))
+        for shp in shapes:
             t1 = torch.randn(shp, device=dev).clamp_(min=0)
             c1 = torch.empty(t1.numel(), dtype=torch.int8, device=dev)
             p1 = qb.qv2_plan_create([qb.TensorArg(x=t1, numel=t1.numel(), codes=c1)])
@@ -286,7 +290,8 @@ def main():
                 torch.cuda.synchronize()
             qdq["x".join(map(str, shp))] = round(e0.elapsed_time(e1) / 200 * 1e3, 2)
             p1.close()
-        extras["fakequant_single_tensor_us"] = qdq
+        if qdq:
+            extras["fakequant_single_tensor_us"] = qdq
 
     if args.copy_probe:
         src = torch.ones(1 << 28, dtype=torch.float32, device=dev)      # 1 GiB
