@@ -180,6 +180,47 @@ def test_many_small_tiles(fused, monkeypatch):
     H.check_all(items, res)
 
 
+@pytest.mark.parametrize("seed", [11, 12, 13])
+def test_random_layer_tables(seed):
+    """Randomly drawn layer tables: sizes from 1 to 300 K elements, any scheme, channel counts and
+    row lengths on both sides of every path's limits (LDS rows, register rows, rows as stream
+    tiles), bases and code buffers at random offsets, partners present, absent or misaligned against
+    x, some tensors without code buffers.  Every call form against the oracle."""
+    rng = np.random.default_rng(seed)
+    items = []
+    for i in range(28):
+        kind = int(rng.integers(0, 4))
+        if kind == 0:
+            c, inner = 1, int(rng.integers(1, 300_000))
+            scheme = A if rng.random() < 0.5 else S
+        elif kind == 1:                      # short rows
+            c, inner = int(rng.integers(1, 400)), int(rng.integers(1, 130))
+            scheme = C
+        elif kind == 2:                      # rows around the register / LDS forms
+            inner = int(rng.choice([64, 128, 132, 576, 1000, 1024, 2048, 4100, 4608, 8188, 8192])) + int(rng.choice([0, 0, 0, 1, 3]))
+            c, scheme = int(rng.integers(1, 12)), C
+        else:                                # rows longer than the row-group limit
+            c, inner, scheme = int(rng.integers(1, 5)), int(rng.integers(8193, 60_000)), C
+        n = c * inner
+        off = int(rng.choice([0, 0, 0, 1, 2, 3]))
+        x = _rand(n + 8, 1000 * seed + i, float(rng.choice([1e-3, 0.1, 1.0, 30.0])))[off: off + n]
+        if rng.random() < 0.3:
+            x = x.clamp(min=0)
+        r = rng.random()
+        if r < 0.4:
+            q = None
+        elif r < 0.85:
+            q = _rand(n + 8, 5000 * seed + i, 0.01)[off: off + n] + x
+        else:                                # partner at another offset inside 16 bytes
+            qo = (off + 1 + int(rng.integers(0, 3))) % 4
+            q = _rand(n + 8, 5000 * seed + i, 0.01)[qo: qo + n] + x
+        items.append(H.Item(f"r{i}.{c}x{inner}.off{off}", x, scheme, c, int(rng.integers(0, 2)), len(items), qrun=q,
+                            want_codes=bool(rng.random() < 0.85), codes_offset=int(rng.choice([0, 0, 1, 2, 3]))))
+    for form in (False, True, "single"):
+        res = H.run_gpu(items, fused=form)
+        H.check_all(items, res)
+
+
 def test_cached_params_clip_both_ends():
     """Parameters handed in by the caller (the calibration cache) instead of calibrating:
     a range narrower than the data saturates codes at -128 and 127."""
