@@ -145,14 +145,12 @@ def main():
     bytes_cal, bytes_fq, bytes_pair = 4 * n_all, 5 * n_all, 8 * n_pair
     bytes_pass = bytes_cal + bytes_fq + bytes_pair
 
-    w_idx = [t for t, s in enumerate(specs) if s.kind == synth.WEIGHT]
-    a_idx = [t for t, s in enumerate(specs) if s.kind == synth.ACTIVATION]
-    w_layer = np.array([specs[t].layer for t in w_idx])
-    a_layer = np.array([specs[t].layer for t in a_idx])
     # pinned host mirrors of the small result records
     d_tsums = torch.zeros(plan.num_tensors * qb.TENSOR_SUMS.itemsize, dtype=torch.uint8, device=dev)
     h_tsums = torch.empty(d_tsums.shape, dtype=torch.uint8, pin_memory=True)
     h_pair = torch.empty(buf.pair.shape, dtype=torch.uint8, pin_memory=True)
+    h_tsums_np = h_tsums.numpy().view(qb.TENSOR_SUMS)
+    h_pair_np = h_pair.numpy().view(qb.PAIR_SUMS)
     last = {}
 
     def step(mode, events=None):
@@ -182,14 +180,11 @@ def main():
         torch.cuda.current_stream().synchronize()
         if events:       # per-kernel durations from the library's HIP events on the same stream
             kernel_log.append(qb.qv2_plan_kernels_ms(plan).copy())
-        met = qb.qv2_finalize_tensors(h_tsums.numpy().view(qb.TENSOR_SUMS))
-        pmse, psqnr = qb.qv2_pair_finalize(h_pair.numpy().view(qb.PAIR_SUMS))
-        w_sqnr = np.empty(n_layers); w_mse = np.empty(n_layers)
-        a_sqnr = np.empty(n_layers); a_mse = np.empty(n_layers)
-        w_sqnr[w_layer], w_mse[w_layer] = met["sqnr_db"][w_idx], met["mse"][w_idx]
-        a_sqnr[a_layer], a_mse[a_layer] = psqnr[a_idx], pmse[a_idx]
-        order, score = qb.qv2_rank(w_sqnr, a_sqnr, w_mse, a_mse)
-        last.update(order=order, score=score, met=met)
+        ts, ps = h_tsums_np, h_pair_np
+        met = qb.qv2_finalize_tensors(ts)                    # per tensor: MSE, SQNR, mean, var, absmax
+        pmse, psqnr = qb.qv2_pair_finalize(ps)               # per activation pair: MSE, SQNR
+        order, score = qb.qv2_rank_tensors(plan, ts, ps, n_layers)   # per-layer series, Eq. 16, Algorithm 2
+        last.update(order=order, score=score, met=met, pmse=pmse, psqnr=psqnr)
 
     kernel_ms, kernel_log = {}, []
     qb.qv2_plan_set_timing(plan, True)
