@@ -146,11 +146,14 @@ def main():
     bytes_pass = bytes_cal + bytes_fq + bytes_pair
 
     # pinned host mirrors of the small result records
-    d_tsums = torch.zeros(plan.num_tensors * qb.TENSOR_SUMS.itemsize, dtype=torch.uint8, device=dev)
-    h_tsums = torch.empty(d_tsums.shape, dtype=torch.uint8, pin_memory=True)
-    h_pair = torch.empty(buf.pair.shape, dtype=torch.uint8, pin_memory=True)
-    h_tsums_np = h_tsums.numpy().view(qb.TENSOR_SUMS)
-    h_pair_np = h_pair.numpy().view(qb.PAIR_SUMS)
+    # per-tensor records and pair sums share one device buffer, so one copy brings both back
+    n_ts = plan.num_tensors * qb.TENSOR_SUMS.itemsize
+    d_out = torch.zeros(n_ts + plan.num_tensors * qb.PAIR_SUMS.itemsize, dtype=torch.uint8, device=dev)
+    d_tsums, d_pair = d_out[:n_ts], d_out[n_ts:]
+    h_out = torch.empty(d_out.shape, dtype=torch.uint8, pin_memory=True)
+    h_tsums_np = h_out[:n_ts].numpy().view(qb.TENSOR_SUMS)
+    h_pair_np = h_out[n_ts:].numpy().view(qb.PAIR_SUMS)
+    buf.pair = d_pair
     last = {}
 
     def step(mode, events=None):
@@ -175,8 +178,7 @@ def main():
             events[3].record()
         # per-tensor records are folded on the device: a few KB go to the host, not every segment
         qb.qv2_tensor_sums_fold(plan, buf.params, buf.sums, d_tsums)
-        h_tsums.copy_(d_tsums, non_blocking=True)
-        h_pair.copy_(buf.pair, non_blocking=True)
+        h_out.copy_(d_out, non_blocking=True)
         torch.cuda.current_stream().synchronize()
         if events:       # per-kernel durations from the library's HIP events on the same stream
             kernel_log.append(qb.qv2_plan_kernels_ms(plan).copy())
