@@ -26,6 +26,9 @@
  *    void*; NULL = the default stream) and never synchronise it, except that
  *    the first device call on a plan uploads the plan's tables with a blocking
  *    copy.  Outputs are valid once the caller has synchronised the stream.
+ *  - A plan serves one thread at a time (the first device call uploads its tables
+ *    and the optional timing events belong to it); different plans are independent,
+ *    and calls on one plan that may overlap on the GPU need separate workspaces.
  *  - Every call returns a qv2_status.  Arguments are validated on the host
  *    before anything is launched; nothing aborts or throws across the ABI.
  *  - Identical inputs give bit-identical outputs (no floating-point atomics;
