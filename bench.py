@@ -49,7 +49,7 @@ def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="resnet50", choices=["resnet50", "resnet18", "vgg16", "mobilenetv2"])
     ap.add_argument("--batch", type=int, default=None, help="override the workload's batch (smaller = not the headline config)")
     ap.add_argument("--fused", action="store_true", help="BN-folded weight variant of resnet50")
@@ -59,6 +59,9 @@ def parse():
                          "calls: calibrate, fake-quant and pair as three calls")
     ap.add_argument("--single-mode", action="store_true", help="do not also time the other mode")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--checksums", action="store_true",
+                    help="print one checksum line per input tensor to stderr (the JSON line always carries "
+                         "their combination as config.inputs_checksum)")
     ap.add_argument("--cpu-sample-elems", type=int, default=2_000_000_000)
     ap.add_argument("--cold", action="store_true",
                     help="also time every step after streaming a 1 GiB scratch buffer (evicts the 256 MB "
@@ -202,12 +205,16 @@ def main():
             step(mode)
         torch.cuda.synchronize()
         t0 = time.perf_counter()
+        marks = [t0]
         for k in range(args.steps):
-            step(mode, ev[k])
+            step(mode, ev[k])          # ends with the ranking on the host, so each step is complete here
+            marks.append(time.perf_counter())
         torch.cuda.synchronize()
         dt = time.perf_counter() - t0
+        per_step = np.diff(marks) * 1e3
         kernel_ms.update({n: [row[qb.KERNEL_IDS[n]] for row in kernel_log] for n in names})
-        r = {"ms_per_step": dt / args.steps * 1e3, "order": last["order"].tolist(),
+        r = {"ms_per_step": dt / args.steps * 1e3, "ms_median": float(np.median(per_step)),
+             "ms_min": float(np.min(per_step)), "order": last["order"].tolist(),
              "kernels_ms": {n: round(float(np.mean(v)), 4) for n, v in kernel_ms.items()},
              "ms_cal": float(np.mean([e[0].elapsed_time(e[1]) for e in ev]))}
         if mode == "single":
@@ -336,7 +343,8 @@ def main():
     out = {
         "metric": "sensitivity_pass_GBps", "value": round(value, 2), "unit": "GB/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
+        "ms_per_step": round(ms_per_step, 4), "ms_per_step_median": round(main_r["ms_median"], 4),
+        "ms_per_step_min": round(main_r["ms_min"], 4), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"{args.workload}_b{batch}" + ("_bnfold" if args.fused else ""),
                    "pass": {"single": "calibrate/fakequant/pair in one call + finalize + rank",
@@ -344,7 +352,7 @@ def main():
                             "calls": "calibrate + fakequant + pair + finalize + rank"}[args.mode],
                    "tensors": len(specs), "layers": n_layers, "weight_elements": n_w,
                    "activation_elements": n_a, "algorithmic_bytes_per_pass": bytes_pass,
-                   "moved_bytes_per_pass": moved},
+                   "moved_bytes_per_pass": moved, "inputs_checksum": inputs_checksum(specs, xs, qruns, args.checksums)},
         "value_note": "algorithmic bytes of the three calls (4 + 5 + 8 B per element with a partner, fixed "
                       "numerators) / time; it can exceed the HBM rate because the pass visits tensors fewer "
                       "times than three separate calls would. Bytes actually moved / time is hbm_GBps.",
@@ -378,14 +386,36 @@ def main():
                              "calls": calls_of(other), "kernels_ms": other["kernels_ms"], "same_order": other["order"] == main_r["order"]}
 
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(specs, xs, qruns, args.cpu_sample_elems)
+        out["cpu_baseline"], out["cpu_baseline_all_cores"] = cpu_baseline(specs, xs, qruns, args.cpu_sample_elems)
         out["oracle_speedup"] = round(value / out["cpu_baseline"]["value"], 1)
     print(json.dumps(out), flush=True)
 
 
+def inputs_checksum(specs, xs, qruns, verbose):
+    """Identity of the synthetic inputs: per tensor the wrapping 64-bit sum of its fp32 bit
+    patterns (and of its partner's), combined position-dependently into one hex string.  The
+    device generator's stream is not promised stable across torch versions, so runs that are
+    to be compared can compare this instead of trusting the seeds."""
+    import torch
+    acc = 0
+    for t, (s, x, q) in enumerate(zip(specs, xs, qruns)):
+        cx = int(x.view(-1).view(torch.int32).sum(dtype=torch.int64)) & 0xFFFFFFFFFFFFFFFF
+        cq = 0 if q is None else int(q.view(-1).view(torch.int32).sum(dtype=torch.int64)) & 0xFFFFFFFFFFFFFFFF
+        if verbose:
+            print(f"checksum tensor {t:3d} layer {s.layer:3d} kind {s.kind} numel {s.numel:10d} "
+                  f"x {cx:016x} qrun {cq:016x}", file=sys.stderr)
+        acc = (acc * 0x100000001B3 + cx) & 0xFFFFFFFFFFFFFFFF
+        acc = (acc * 0x100000001B3 + cq) & 0xFFFFFFFFFFFFFFFF
+    return f"{acc:016x}"
+
+
 def cpu_baseline(specs, xs, qruns, budget):
-    """The CPU oracle as it stands (one thread), timed on a bounded sample of the same
-    workload: tensors taken in table order while they fit the element budget."""
+    """The CPU oracle as it stands, timed on a bounded sample of the same workload (tensors
+    taken in table order while they fit the element budget): first on one thread, then the same
+    unchanged functions with the sample's tensors handed out, largest first, to one thread per
+    host core this process may use.  Returns the two records."""
+    import os
+    from concurrent.futures import ThreadPoolExecutor
     from oracle import reference as orc
     from paper_2501_07161_amd import synth
     orc.lib()
@@ -394,25 +424,42 @@ def cpu_baseline(specs, xs, qruns, budget):
         if s.numel <= left:
             picked.append(t)
             left -= s.numel
-    host = [(xs[t].cpu().numpy().reshape(-1), None if qruns[t] is None else qruns[t].cpu().numpy().reshape(-1))
-            for t in picked]
-    nbytes, t0 = 0, time.perf_counter()
-    for t, (x, q) in zip(picked, host):
-        s = specs[t]
+    host = {t: (xs[t].cpu().numpy().reshape(-1), None if qruns[t] is None else qruns[t].cpu().numpy().reshape(-1))
+            for t in picked}
+
+    def one(t):
+        s, (x, q) = specs[t], host[t]
         cal = orc.calibrate(x, s.scheme, s.channels)
         fq = orc.fakequant(x, cal, s.scheme, s.channels)
         orc.tensor_metrics(x, cal, fq)
-        nbytes += 9 * x.size
         if q is not None:
             orc.pair_metrics(x, q)
-            nbytes += 8 * x.size
+        return (9 if q is None else 17) * x.size
+
+    t0 = time.perf_counter()
+    nbytes = sum(one(t) for t in picked)
     dt = time.perf_counter() - t0
     n_w = sum(1 for t in picked if specs[t].kind == synth.WEIGHT)
-    return {"value": round(nbytes / dt / 1e9, 4), "unit": "GB/s", "cores": 1, "kind": "oracle",
-            "seconds": round(dt, 2),
-            "sample": f"{len(picked)} of {len(specs)} tensors of the same workload in table order within "
-                      f"{budget} elements ({n_w} weights, {len(picked) - n_w} activations with pairs, "
-                      f"{sum(specs[t].numel for t in picked)} elements)"}
+    sample = (f"{len(picked)} of {len(specs)} tensors of the same workload in table order within "
+              f"{budget} elements ({n_w} weights, {len(picked) - n_w} activations with pairs, "
+              f"{sum(specs[t].numel for t in picked)} elements)")
+    serial = {"value": round(nbytes / dt / 1e9, 4), "unit": "GB/s", "cores": 1, "kind": "oracle",
+              "seconds": round(dt, 2), "sample": sample}
+
+    cores = len(os.sched_getaffinity(0)) if hasattr(os, "sched_getaffinity") else (os.cpu_count() or 1)
+    env = os.environ.get("OMP_NUM_THREADS", "")
+    if env.isdigit() and int(env) > 0:           # the share of the host this job was given
+        cores = min(cores, int(env))
+    threads = max(1, min(cores, len(picked)))
+    by_size = sorted(picked, key=lambda t: -specs[t].numel)
+    t0 = time.perf_counter()
+    with ThreadPoolExecutor(threads) as pool:    # the oracle's C loops run outside the interpreter lock
+        nbytes_mt = sum(pool.map(one, by_size))
+    dt_mt = time.perf_counter() - t0
+    threaded = {"value": round(nbytes_mt / dt_mt / 1e9, 4), "unit": "GB/s", "cores": threads, "kind": "oracle",
+                "seconds": round(dt_mt, 2), "host_cores_visible": os.cpu_count(),
+                "sample": sample + "; one tensor per task, largest first, so the largest tensor bounds the time"}
+    return serial, threaded
 
 
 if __name__ == "__main__":
