@@ -1,4 +1,6 @@
-"""Full-size parity in the launch configuration the benchmark times: the ResNet-50 v1
+"""Full-size parity in the launch configuration the benchmark times.  The MobileNetV2
+batch-64 and VGG-16 batch-16 sets go through the single call and are compared element by
+element.  The ResNet-50 v1
 batch-256 set (54 per-channel weights, 54 activations of 10.8 GB with oracle-made
 quantized-run partners) goes through ONE plan, as in bench.py, and every tensor is
 compared with the CPU oracle: parameters and all 2.7 G int8 codes bit-exact, sums, MSE,
@@ -47,6 +49,37 @@ def test_resnet50_batch256_full_pass():
     assert all(torch.equal(a, it.codes) for a, it in zip(codes2, items))
     del items
     torch.cuda.empty_cache()
+
+
+def _full_set_single_call(specs, n_layers):
+    """One plan over a whole set at its stated batch, through the single call (the pass the
+    benchmark times), every element against the oracle."""
+    items = H.items_from_specs(specs, "cuda")
+    print("oracle: calibrate + fake-quant + quantized-run partners ...", flush=True)
+    H.attach_pairs(items, specs)
+    print("gpu pass (single call) ...", flush=True)
+    res = H.run_gpu(items, fused="single")
+    print("compare ...", flush=True)
+    rows = H.check_all(items, res)
+    order = H.check_ranking(items, res, rows)
+    assert sorted(order) == list(range(n_layers))
+    del items, res
+    torch.cuda.empty_cache()
+
+
+@pytest.mark.timeout(600)
+def test_mobilenetv2_batch64_full_pass():
+    """MobileNetV2 at batch 64: 53 per-channel weights (rows of 9 ... 1280 elements) and 53
+    activations of 427 M elements with ReLU6 clipping, partners made by the oracle."""
+    _full_set_single_call(synth.config_mobilenetv2(64), 53)
+
+
+@pytest.mark.timeout(600)
+@pytest.mark.parametrize("per_channel", [False, True])
+def test_vgg16_batch16_full_pass(per_channel):
+    """VGG-16 at batch 16: 138 M weight elements (fc6 alone 411 MB; per-channel rows of up to
+    25088 elements) and 217 M activation elements."""
+    _full_set_single_call(synth.config_vgg16(16, per_channel), 16)
 
 
 @pytest.mark.timeout(900)
