@@ -63,7 +63,8 @@ typedef enum {
   QV2_ERR_NONFINITE = -5,  /* NaN / Inf where a finite value is required         */
   QV2_ERR_HIP = -6,        /* a HIP runtime call or kernel launch failed         */
   QV2_ERR_ALIGN = -7,      /* a device pointer is not aligned as required        */
-  QV2_ERR_IO = -8          /* a file could not be created or written             */
+  QV2_ERR_IO = -8,         /* a file could not be created or written             */
+  QV2_ERR_NOMEM = -9       /* host memory for the plan or a work list ran out    */
 } qv2_status;
 
 typedef enum {
@@ -151,7 +152,9 @@ typedef struct qv2_plan qv2_plan;
  * Errors: NULL table or out -> ERR_NULL; n_tensors <= 0, numel <= 0, channels
  * not dividing numel (or != 1 for per-tensor schemes), more than 2^31-1 tiles
  * or segments -> ERR_SHAPE; unknown scheme -> ERR_SCHEME; x (or qrun) not
- * 4-byte aligned -> ERR_ALIGN; x NULL -> ERR_NULL. */
+ * 4-byte aligned -> ERR_ALIGN; x NULL -> ERR_NULL; no host memory for the tile
+ * tables -> ERR_NOMEM (the host functions below that build work lists - qv2_rank,
+ * qv2_rank_tensors, qv2_bops_select, qv2_regroup_for_fusion - return it too). */
 /* Tile lengths can be overridden for tuning with the environment variables QV2_TILE_ELEMS
  * (read-only sweeps) and QV2_QUANT_TILE_ELEMS (quantize sweeps), read here. */
 qv2_status qv2_plan_create(const qv2_tensor* h_tensors, int32_t n_tensors, qv2_plan** out);

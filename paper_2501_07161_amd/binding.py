@@ -19,7 +19,7 @@ LIB_PATH = os.environ.get("QV2_LIB_PATH") or os.path.join(_HERE, "libqv2.so")
 
 QV2_OK = 0
 QV2_ERR_NULL, QV2_ERR_SHAPE, QV2_ERR_SCHEME, QV2_ERR_WORKSPACE = -1, -2, -3, -4
-QV2_ERR_NONFINITE, QV2_ERR_HIP, QV2_ERR_ALIGN, QV2_ERR_IO = -5, -6, -7, -8
+QV2_ERR_NONFINITE, QV2_ERR_HIP, QV2_ERR_ALIGN, QV2_ERR_IO, QV2_ERR_NOMEM = -5, -6, -7, -8, -9
 QV2_ASYM_TENSOR, QV2_SYM_TENSOR, QV2_SYM_CHANNEL = 0, 1, 2
 
 EXPORTS = (

@@ -32,14 +32,36 @@ int32_t tile_from_env(const char* name, int32_t dflt) {
   return static_cast<int32_t>(v / 4 * 4);
 }
 
+// Runs a host entry point's body; an allocation failure inside it becomes a status.
+template <class F>
+qv2_status guarded(F&& body) {
+  try {
+    return body();
+  } catch (...) {            // only allocations can throw in these bodies
+    return QV2_ERR_NOMEM;
+  }
+}
+
 }  // namespace
 
 extern "C" {
+
+static qv2_status plan_create(const qv2_tensor* h_tensors, int32_t n_tensors, qv2_plan* p);
 
 qv2_status qv2_plan_create(const qv2_tensor* h_tensors, int32_t n_tensors, qv2_plan** out) {
   if (!h_tensors || !out) return QV2_ERR_NULL;
   *out = nullptr;
   if (n_tensors <= 0) return QV2_ERR_SHAPE;
+  qv2_plan* p = new (std::nothrow) qv2_plan();
+  if (!p) return QV2_ERR_NOMEM;
+  // the tile tables grow with the input: a failed allocation must not leave as an exception
+  const qv2_status st = guarded([&]() -> qv2_status { return plan_create(h_tensors, n_tensors, p); });
+  if (st != QV2_OK) { delete p; return st; }
+  *out = p;
+  return QV2_OK;
+}
+
+static qv2_status plan_create(const qv2_tensor* h_tensors, int32_t n_tensors, qv2_plan* p) {
   const int64_t kMax = std::numeric_limits<int32_t>::max();
 
   // validate, and count the row-group partials: they are numbered first
@@ -61,8 +83,6 @@ qv2_status qv2_plan_create(const qv2_tensor* h_tensors, int32_t n_tensors, qv2_p
     if (n_segments > kMax) return QV2_ERR_SHAPE;
   }
 
-  qv2_plan* p = new (std::nothrow) qv2_plan();
-  if (!p) return QV2_ERR_HIP;
   p->read_tile = tile_from_env("QV2_TILE_ELEMS", qv2::kDefaultReadTile);
   p->quant_tile = tile_from_env("QV2_QUANT_TILE_ELEMS", qv2::kDefaultQuantTile);
   const int64_t TR = p->read_tile, TQ = p->quant_tile;
@@ -175,7 +195,7 @@ qv2_status qv2_plan_create(const qv2_tensor* h_tensors, int32_t n_tensors, qv2_p
     }
     p->pair_tensors.push_back(pt);
   }
-  if (err != QV2_OK) { delete p; return err; }
+  if (err != QV2_OK) return err;
 
   // histogram pass: about kHistChunks long chunks over all tensors
   {
@@ -189,7 +209,7 @@ qv2_status qv2_plan_create(const qv2_tensor* h_tensors, int32_t n_tensors, qv2_p
       const int64_t nc = (in.numel + chunk - 1) / chunk;
       qv2::HistTensor ht{static_cast<int32_t>(p->hist_tiles.size()), static_cast<int32_t>(nc),
                          p->info[t].seg0, p->info[t].nseg};
-      if (static_cast<int64_t>(p->hist_tiles.size()) + nc > kMax) { delete p; return QV2_ERR_SHAPE; }
+      if (static_cast<int64_t>(p->hist_tiles.size()) + nc > kMax) return QV2_ERR_SHAPE;
       for (int64_t k = 0; k < nc; ++k) {
         Tile tl = make_tile(in, t, k * chunk, std::min<int64_t>(chunk, in.numel - k * chunk));
         tl.part0 = static_cast<int32_t>(p->hist_tiles.size());
@@ -214,7 +234,6 @@ qv2_status qv2_plan_create(const qv2_tensor* h_tensors, int32_t n_tensors, qv2_p
                                 static_cast<size_t>(ep) * sizeof(qv2::ErrPartial5),
                                 static_cast<size_t>(pp) * sizeof(qv2::ErrPartial)});
   p->workspace_bytes = std::max<size_t>(256, round_up(need, 256));
-  *out = p;
   return QV2_OK;
 }
 
@@ -396,55 +415,57 @@ static bool sqnr_delta_series(const double* sqnr, const int32_t* pos, int32_t n,
 qv2_status qv2_rank(const double* w_sqnr_db, const double* a_sqnr_db, const double* w_mse,
                     const double* a_mse, const int32_t* layer_pos, int32_t n_layers,
                     const qv2_rank_config* cfg, int32_t* order_out, double* score_out) {
-  if (!order_out || (!w_sqnr_db && !a_sqnr_db)) return QV2_ERR_NULL;
-  if (n_layers <= 0) return QV2_ERR_SHAPE;
-  qv2_rank_config c;
-  if (cfg) c = *cfg; else qv2_rank_config_default(&c);
-  if (c.mse_source < 0 || c.mse_source > 2) return QV2_ERR_SHAPE;
-  const double* src[2] = {nullptr, nullptr};
-  int nsrc = 0;
-  if (c.mse_source == 1 || c.mse_source == 2) src[nsrc++] = w_mse;
-  if (c.mse_source == 0 || c.mse_source == 2) src[nsrc++] = a_mse;
-  for (int k = 0; k < nsrc; ++k) if (!src[k]) return QV2_ERR_NULL;
-  if (layer_pos)
-    for (int32_t i = 1; i < n_layers; ++i)
-      if (layer_pos[i] <= layer_pos[i - 1]) return QV2_ERR_SHAPE;
+  return guarded([&]() -> qv2_status {
+    if (!order_out || (!w_sqnr_db && !a_sqnr_db)) return QV2_ERR_NULL;
+    if (n_layers <= 0) return QV2_ERR_SHAPE;
+    qv2_rank_config c;
+    if (cfg) c = *cfg; else qv2_rank_config_default(&c);
+    if (c.mse_source < 0 || c.mse_source > 2) return QV2_ERR_SHAPE;
+    const double* src[2] = {nullptr, nullptr};
+    int nsrc = 0;
+    if (c.mse_source == 1 || c.mse_source == 2) src[nsrc++] = w_mse;
+    if (c.mse_source == 0 || c.mse_source == 2) src[nsrc++] = a_mse;
+    for (int k = 0; k < nsrc; ++k) if (!src[k]) return QV2_ERR_NULL;
+    if (layer_pos)
+      for (int32_t i = 1; i < n_layers; ++i)
+        if (layer_pos[i] <= layer_pos[i - 1]) return QV2_ERR_SHAPE;
 
-  const int32_t n = n_layers;
-  std::vector<double> dw, da, score(n), key(n, 0.0);
-  if (!sqnr_delta_series(w_sqnr_db, layer_pos, n, c.sqnr_cap_db, dw) ||
-      !sqnr_delta_series(a_sqnr_db, layer_pos, n, c.sqnr_cap_db, da)) return QV2_ERR_NONFINITE;
-  for (int32_t i = 0; i < n; ++i) score[i] = c.alpha_w * dw[i] + c.alpha_a * da[i];
+    const int32_t n = n_layers;
+    std::vector<double> dw, da, score(n), key(n, 0.0);
+    if (!sqnr_delta_series(w_sqnr_db, layer_pos, n, c.sqnr_cap_db, dw) ||
+        !sqnr_delta_series(a_sqnr_db, layer_pos, n, c.sqnr_cap_db, da)) return QV2_ERR_NONFINITE;
+    for (int32_t i = 0; i < n; ++i) score[i] = c.alpha_w * dw[i] + c.alpha_a * da[i];
 
-  // outliers: MSE strictly above mse_factor x the arithmetic mean of its list
-  std::vector<char> outlier(n, 0);
-  for (int k = 0; k < nsrc; ++k) {
-    const double* m = src[k];
-    double total = 0.0;
-    for (int32_t i = 0; i < n; ++i) {
-      if (!std::isfinite(m[i]) || m[i] < 0.0) return QV2_ERR_NONFINITE;
-      total += m[i];
+    // outliers: MSE strictly above mse_factor x the arithmetic mean of its list
+    std::vector<char> outlier(n, 0);
+    for (int k = 0; k < nsrc; ++k) {
+      const double* m = src[k];
+      double total = 0.0;
+      for (int32_t i = 0; i < n; ++i) {
+        if (!std::isfinite(m[i]) || m[i] < 0.0) return QV2_ERR_NONFINITE;
+        total += m[i];
+      }
+      const double mean = total / static_cast<double>(n);
+      for (int32_t i = 0; i < n; ++i) {
+        if (m[i] > c.mse_factor * mean) outlier[i] = 1;
+        // one list: order outliers by their MSE; two lists: by MSE relative to the list's mean
+        const double kk = nsrc == 1 ? m[i] : (mean > 0.0 ? m[i] / mean : 0.0);
+        key[i] = std::max(key[i], kk);
+      }
     }
-    const double mean = total / static_cast<double>(n);
-    for (int32_t i = 0; i < n; ++i) {
-      if (m[i] > c.mse_factor * mean) outlier[i] = 1;
-      // one list: order outliers by their MSE; two lists: by MSE relative to the list's mean
-      const double kk = nsrc == 1 ? m[i] : (mean > 0.0 ? m[i] / mean : 0.0);
-      key[i] = std::max(key[i], kk);
-    }
-  }
 
-  std::vector<int32_t> front, rest;
-  for (int32_t i = 0; i < n; ++i) (outlier[i] ? front : rest).push_back(i);
-  std::stable_sort(front.begin(), front.end(),
-                   [&](int32_t a, int32_t b) { return key[a] > key[b]; });
-  std::stable_sort(rest.begin(), rest.end(),
-                   [&](int32_t a, int32_t b) { return score[a] < score[b]; });
-  int32_t w = 0;
-  for (int32_t i : front) order_out[w++] = i;
-  for (int32_t i : rest) order_out[w++] = i;
-  if (score_out) std::memcpy(score_out, score.data(), sizeof(double) * n);
-  return QV2_OK;
+    std::vector<int32_t> front, rest;
+    for (int32_t i = 0; i < n; ++i) (outlier[i] ? front : rest).push_back(i);
+    std::stable_sort(front.begin(), front.end(),
+                     [&](int32_t a, int32_t b) { return key[a] > key[b]; });
+    std::stable_sort(rest.begin(), rest.end(),
+                     [&](int32_t a, int32_t b) { return score[a] < score[b]; });
+    int32_t w = 0;
+    for (int32_t i : front) order_out[w++] = i;
+    for (int32_t i : rest) order_out[w++] = i;
+    if (score_out) std::memcpy(score_out, score.data(), sizeof(double) * n);
+    return QV2_OK;
+  });
 }
 
 // ---------------------------------------------------------------------------
@@ -454,36 +475,38 @@ qv2_status qv2_rank(const double* w_sqnr_db, const double* a_sqnr_db, const doub
 qv2_status qv2_rank_tensors(const qv2_plan* plan, const qv2_tensor_sums* h_tensor_sums,
                             const qv2_pair_sums* h_pair_sums, const int32_t* layer_pos, int32_t n_layers,
                             const qv2_rank_config* cfg, int32_t* order_out, double* score_out) {
-  if (!plan || !h_tensor_sums || !order_out) return QV2_ERR_NULL;
-  if (n_layers <= 0) return QV2_ERR_SHAPE;
-  const double nan = std::numeric_limits<double>::quiet_NaN();
-  std::vector<double> w_sqnr(n_layers, nan), w_mse(n_layers, nan), a_sqnr(n_layers, nan), a_mse(n_layers, nan);
-  int32_t n_w = 0, n_a = 0;
-  for (size_t t = 0; t < plan->info.size(); ++t) {
-    const TensorInfo& d = plan->info[t];
-    if (d.layer < 0 || d.layer >= n_layers) return QV2_ERR_SHAPE;
-    if (d.kind == 0) {                                       // weight: Eq. 6-7 against its dequantized form
-      if (!std::isnan(w_mse[d.layer])) return QV2_ERR_SHAPE;  // two weights in one layer
-      const qv2_tensor_sums& u = h_tensor_sums[t];
-      if (u.n <= 0) return QV2_ERR_SHAPE;
-      w_mse[d.layer] = u.sum_e2 / static_cast<double>(u.n);
-      w_sqnr[d.layer] = sqnr_db_of(u.sum_x2, u.sum_e2);
-      ++n_w;
-    } else if (d.has_pair) {                                 // activation: fp32 run against quantized run
-      if (!h_pair_sums) return QV2_ERR_NULL;
-      if (!std::isnan(a_mse[d.layer])) return QV2_ERR_SHAPE;
-      const qv2_pair_sums& u = h_pair_sums[t];
-      if (u.n <= 0) return QV2_ERR_SHAPE;
-      a_mse[d.layer] = u.sum_d2 / static_cast<double>(u.n);
-      a_sqnr[d.layer] = sqnr_db_of(u.sum_ref2, u.sum_d2);
-      ++n_a;
+  return guarded([&]() -> qv2_status {
+    if (!plan || !h_tensor_sums || !order_out) return QV2_ERR_NULL;
+    if (n_layers <= 0) return QV2_ERR_SHAPE;
+    const double nan = std::numeric_limits<double>::quiet_NaN();
+    std::vector<double> w_sqnr(n_layers, nan), w_mse(n_layers, nan), a_sqnr(n_layers, nan), a_mse(n_layers, nan);
+    int32_t n_w = 0, n_a = 0;
+    for (size_t t = 0; t < plan->info.size(); ++t) {
+      const TensorInfo& d = plan->info[t];
+      if (d.layer < 0 || d.layer >= n_layers) return QV2_ERR_SHAPE;
+      if (d.kind == 0) {                                       // weight: Eq. 6-7 against its dequantized form
+        if (!std::isnan(w_mse[d.layer])) return QV2_ERR_SHAPE;  // two weights in one layer
+        const qv2_tensor_sums& u = h_tensor_sums[t];
+        if (u.n <= 0) return QV2_ERR_SHAPE;
+        w_mse[d.layer] = u.sum_e2 / static_cast<double>(u.n);
+        w_sqnr[d.layer] = sqnr_db_of(u.sum_x2, u.sum_e2);
+        ++n_w;
+      } else if (d.has_pair) {                                 // activation: fp32 run against quantized run
+        if (!h_pair_sums) return QV2_ERR_NULL;
+        if (!std::isnan(a_mse[d.layer])) return QV2_ERR_SHAPE;
+        const qv2_pair_sums& u = h_pair_sums[t];
+        if (u.n <= 0) return QV2_ERR_SHAPE;
+        a_mse[d.layer] = u.sum_d2 / static_cast<double>(u.n);
+        a_sqnr[d.layer] = sqnr_db_of(u.sum_ref2, u.sum_d2);
+        ++n_a;
+      }
     }
-  }
-  // a series is used only when every layer has an entry in it
-  if ((n_w != 0 && n_w != n_layers) || (n_a != 0 && n_a != n_layers) || (n_w == 0 && n_a == 0))
-    return QV2_ERR_SHAPE;
-  return qv2_rank(n_w ? w_sqnr.data() : nullptr, n_a ? a_sqnr.data() : nullptr, n_w ? w_mse.data() : nullptr,
-                  n_a ? a_mse.data() : nullptr, layer_pos, n_layers, cfg, order_out, score_out);
+    // a series is used only when every layer has an entry in it
+    if ((n_w != 0 && n_w != n_layers) || (n_a != 0 && n_a != n_layers) || (n_w == 0 && n_a == 0))
+      return QV2_ERR_SHAPE;
+    return qv2_rank(n_w ? w_sqnr.data() : nullptr, n_a ? a_sqnr.data() : nullptr, n_w ? w_mse.data() : nullptr,
+                    n_a ? a_mse.data() : nullptr, layer_pos, n_layers, cfg, order_out, score_out);
+  });
 }
 
 qv2_status qv2_baseline_order(int32_t kind, const double* w_sqnr_db, int32_t n_layers,
@@ -532,32 +555,32 @@ qv2_status qv2_bops_reduction_pct(const double* macs, const uint8_t* keep_fp32, 
 qv2_status qv2_bops_select(const int32_t* order, const double* macs, int32_t n_layers,
                            double target_pct, uint8_t* keep_fp32_out, int32_t* n_keep_out,
                            double* achieved_pct_out) {
-  if (!order || !macs || !keep_fp32_out) return QV2_ERR_NULL;
-  if (n_layers <= 0) return QV2_ERR_SHAPE;
-  std::vector<char> seen(n_layers, 0);
-  bool any = false;
-  for (int32_t i = 0; i < n_layers; ++i) {
-    if (order[i] < 0 || order[i] >= n_layers || seen[order[i]]) return QV2_ERR_SHAPE;
-    seen[order[i]] = 1;
-    if (!std::isfinite(macs[i]) || macs[i] < 0.0) return QV2_ERR_NONFINITE;
-    any = any || macs[i] > 0.0;
-  }
-  if (!any || std::isnan(target_pct)) return QV2_ERR_NONFINITE;
-  std::memset(keep_fp32_out, 0, static_cast<size_t>(n_layers));
-  int32_t kept = 0;
-  for (int32_t k = 0; k < n_layers; ++k) {
-    const int32_t l = order[k];
-    keep_fp32_out[l] = 1;
-    if (bops_reduction(macs, keep_fp32_out, n_layers) < target_pct) { keep_fp32_out[l] = 0; break; }
-    ++kept;
-  }
-  if (n_keep_out) *n_keep_out = kept;
-  if (achieved_pct_out) *achieved_pct_out = bops_reduction(macs, keep_fp32_out, n_layers);
-  return QV2_OK;
+  return guarded([&]() -> qv2_status {
+    if (!order || !macs || !keep_fp32_out) return QV2_ERR_NULL;
+    if (n_layers <= 0) return QV2_ERR_SHAPE;
+    std::vector<char> seen(n_layers, 0);
+    bool any = false;
+    for (int32_t i = 0; i < n_layers; ++i) {
+      if (order[i] < 0 || order[i] >= n_layers || seen[order[i]]) return QV2_ERR_SHAPE;
+      seen[order[i]] = 1;
+      if (!std::isfinite(macs[i]) || macs[i] < 0.0) return QV2_ERR_NONFINITE;
+      any = any || macs[i] > 0.0;
+    }
+    if (!any || std::isnan(target_pct)) return QV2_ERR_NONFINITE;
+    std::memset(keep_fp32_out, 0, static_cast<size_t>(n_layers));
+    int32_t kept = 0;
+    for (int32_t k = 0; k < n_layers; ++k) {
+      const int32_t l = order[k];
+      keep_fp32_out[l] = 1;
+      if (bops_reduction(macs, keep_fp32_out, n_layers) < target_pct) { keep_fp32_out[l] = 0; break; }
+      ++kept;
+    }
+    if (n_keep_out) *n_keep_out = kept;
+    if (achieved_pct_out) *achieved_pct_out = bops_reduction(macs, keep_fp32_out, n_layers);
+    return QV2_OK;
+  });
 }
 
-// Sec. 6.5: layers of one fusion group move as a block to the position of the group's most
-// sensitive member; list order is kept inside a block and between blocks.
 // Sec. 4 step 5: bit-width per layer as a text table.
 qv2_status qv2_write_config(const char* path, const uint8_t* keep_fp32, const char* const* layer_names,
                             int32_t n_layers) {
@@ -580,25 +603,29 @@ qv2_status qv2_write_config(const char* path, const uint8_t* keep_fp32, const ch
   return ok ? QV2_OK : QV2_ERR_IO;
 }
 
+// Sec. 6.5: layers of one fusion group move as a block to the position of the group's most
+// sensitive member; list order is kept inside a block and between blocks.
 qv2_status qv2_regroup_for_fusion(const int32_t* order, const int32_t* group_id, int32_t n_layers,
                                   int32_t* order_out) {
-  if (!order || !group_id || !order_out) return QV2_ERR_NULL;
-  if (n_layers <= 0) return QV2_ERR_SHAPE;
-  std::vector<char> seen(n_layers, 0), placed(n_layers, 0);
-  for (int32_t i = 0; i < n_layers; ++i) {
-    if (order[i] < 0 || order[i] >= n_layers || seen[order[i]]) return QV2_ERR_SHAPE;
-    seen[order[i]] = 1;
-  }
-  int32_t w = 0;
-  for (int32_t i = 0; i < n_layers; ++i) {
-    if (placed[order[i]]) continue;
-    const int32_t g = group_id[order[i]];
-    for (int32_t k = i; k < n_layers; ++k) {
-      const int32_t l = order[k];
-      if (!placed[l] && group_id[l] == g) { order_out[w++] = l; placed[l] = 1; }
+  return guarded([&]() -> qv2_status {
+    if (!order || !group_id || !order_out) return QV2_ERR_NULL;
+    if (n_layers <= 0) return QV2_ERR_SHAPE;
+    std::vector<char> seen(n_layers, 0), placed(n_layers, 0);
+    for (int32_t i = 0; i < n_layers; ++i) {
+      if (order[i] < 0 || order[i] >= n_layers || seen[order[i]]) return QV2_ERR_SHAPE;
+      seen[order[i]] = 1;
     }
-  }
-  return QV2_OK;
+    int32_t w = 0;
+    for (int32_t i = 0; i < n_layers; ++i) {
+      if (placed[order[i]]) continue;
+      const int32_t g = group_id[order[i]];
+      for (int32_t k = i; k < n_layers; ++k) {
+        const int32_t l = order[k];
+        if (!placed[l] && group_id[l] == g) { order_out[w++] = l; placed[l] = 1; }
+      }
+    }
+    return QV2_OK;
+  });
 }
 
 const char* qv2_status_string(qv2_status s) {
@@ -612,6 +639,7 @@ const char* qv2_status_string(qv2_status s) {
     case QV2_ERR_HIP: return "HIP runtime error";
     case QV2_ERR_ALIGN: return "misaligned pointer";
     case QV2_ERR_IO: return "file could not be written";
+    case QV2_ERR_NOMEM: return "out of host memory";
   }
   return "unknown status";
 }

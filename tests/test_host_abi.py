@@ -35,7 +35,7 @@ def test_struct_layouts_match_header_sizes():
 
 
 def test_status_strings():
-    for st in range(-8, 1):
+    for st in range(-9, 1):
         assert qb.lib().qv2_status_string(st) and qb.lib().qv2_status_string(st) != b"unknown status"
     assert b"unknown" in qb.lib().qv2_status_string(-99)
 
