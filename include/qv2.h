@@ -26,6 +26,9 @@
  *    void*; NULL = the default stream) and never synchronise it, except that
  *    the first device call on a plan uploads the plan's tables with a blocking
  *    copy.  Outputs are valid once the caller has synchronised the stream.
+ *    The tables stay on the device that was current at that first call; a later
+ *    call with another device current returns QV2_ERR_HIP.  A stream capture
+ *    (HIP graph) may record any device call after the first one on its plan.
  *  - A plan serves one thread at a time (the first device call uploads its tables
  *    and the optional timing events belong to it); different plans are independent,
  *    and calls on one plan that may overlap on the GPU need separate workspaces.

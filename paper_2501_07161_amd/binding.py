@@ -147,6 +147,37 @@ def _ptr(buf) -> Optional[int]:
     return buf.data_ptr()
 
 
+def _dev(buf, need_bytes: int, what: str, elem_size: Optional[int] = None, optional: bool = False):
+    """Address of a device buffer after checking what can be checked on the host: a torch
+    tensor must live on the GPU, be contiguous and hold at least `need_bytes` (and have
+    `elem_size`-byte elements when given).  A kernel handed a short or host buffer would fault
+    the GPU, so these are refused here.  Raw integer addresses are passed through unchecked."""
+    if buf is None:
+        if optional:
+            return None
+        raise QV2Error(QV2_ERR_NULL, what)
+    if isinstance(buf, int):
+        return buf
+    if not getattr(buf, "is_cuda", False):
+        raise QV2Error(QV2_ERR_NULL, f"{what}: not a device tensor")
+    if not buf.is_contiguous():
+        raise QV2Error(QV2_ERR_SHAPE, f"{what}: not contiguous")
+    if elem_size is not None and buf.element_size() != elem_size:
+        raise QV2Error(QV2_ERR_SHAPE, f"{what}: {buf.element_size()}-byte elements, {elem_size} expected")
+    have = buf.numel() * buf.element_size()
+    if have < need_bytes:
+        raise QV2Error(QV2_ERR_SHAPE, f"{what}: holds {have} bytes, {need_bytes} needed")
+    return buf.data_ptr()
+
+
+def _ws(plan, d_workspace, workspace_bytes, where: str):
+    """(address, byte count) of a workspace argument."""
+    if workspace_bytes is None:
+        workspace_bytes = d_workspace.numel() * d_workspace.element_size()
+    return _dev(d_workspace, 0 if isinstance(d_workspace, int) else workspace_bytes, f"{where}: workspace"), \
+        workspace_bytes
+
+
 def _stream(stream) -> Optional[int]:
     if stream is None:
         import torch
@@ -201,8 +232,11 @@ def qv2_plan_create(rows: Sequence[TensorArg]) -> Plan:
     n = len(rows)
     arr = (qv2_tensor * max(n, 1))()
     for i, r in enumerate(rows):
-        arr[i] = qv2_tensor(_ptr(r.x), _ptr(r.qrun), _ptr(r.codes), int(r.numel), int(r.channels),
-                            int(r.scheme), int(r.kind), int(r.layer))
+        nel = int(r.numel)
+        arr[i] = qv2_tensor(_dev(r.x, 4 * nel, f"qv2_plan_create: x of tensor {i}", 4),
+                            _dev(r.qrun, 4 * nel, f"qv2_plan_create: qrun of tensor {i}", 4, optional=True),
+                            _dev(r.codes, nel, f"qv2_plan_create: codes of tensor {i}", 1, optional=True),
+                            nel, int(r.channels), int(r.scheme), int(r.kind), int(r.layer))
     h = ctypes.c_void_p()
     _check(lib().qv2_plan_create(arr, n, ctypes.byref(h)), "qv2_plan_create")
     return Plan(h.value, rows)
@@ -239,55 +273,73 @@ def qv2_workspace_bytes(plan: Plan) -> int:
     return lib().qv2_workspace_bytes(plan.handle)
 
 
+def _seg_args(plan: Plan, d_params, d_sums, where: str):
+    return (_dev(d_params, plan.num_segments * QPARAMS.itemsize, f"{where}: d_params"),
+            _dev(d_sums, plan.num_segments * SUMS.itemsize, f"{where}: d_sums"))
+
+
+def _pair_arg(plan: Plan, d_pair_sums, where: str, optional: bool = False):
+    return _dev(d_pair_sums, plan.num_tensors * PAIR_SUMS.itemsize, f"{where}: d_pair_sums", optional=optional)
+
+
+def _cos_args(plan: Plan, d_seg_xxhat, d_pair_xq, where: str):
+    return (_dev(d_seg_xxhat, plan.num_segments * 8, f"{where}: d_seg_xxhat"),
+            _dev(d_pair_xq, plan.num_tensors * 8, f"{where}: d_pair_xq"))
+
+
 def qv2_calibrate(plan: Plan, d_params, d_sums, d_workspace, workspace_bytes=None, stream=None):
-    wb = workspace_bytes if workspace_bytes is not None else d_workspace.numel() * d_workspace.element_size()
-    _check(lib().qv2_calibrate(plan.handle, _ptr(d_params), _ptr(d_sums), _ptr(d_workspace), wb,
-                               _stream(stream)), "qv2_calibrate")
+    w = "qv2_calibrate"
+    ws, wb = _ws(plan, d_workspace, workspace_bytes, w)
+    _check(lib().qv2_calibrate(plan.handle, *_seg_args(plan, d_params, d_sums, w), ws, wb, _stream(stream)), w)
 
 
 def qv2_fakequant_metrics(plan: Plan, d_params, d_sums, d_workspace, workspace_bytes=None, stream=None):
-    wb = workspace_bytes if workspace_bytes is not None else d_workspace.numel() * d_workspace.element_size()
-    _check(lib().qv2_fakequant_metrics(plan.handle, _ptr(d_params), _ptr(d_sums), _ptr(d_workspace), wb,
-                                       _stream(stream)), "qv2_fakequant_metrics")
+    w = "qv2_fakequant_metrics"
+    ws, wb = _ws(plan, d_workspace, workspace_bytes, w)
+    _check(lib().qv2_fakequant_metrics(plan.handle, *_seg_args(plan, d_params, d_sums, w), ws, wb,
+                                       _stream(stream)), w)
 
 
 def qv2_pair_metrics(plan: Plan, d_pair_sums, d_workspace, workspace_bytes=None, stream=None):
-    wb = workspace_bytes if workspace_bytes is not None else d_workspace.numel() * d_workspace.element_size()
-    _check(lib().qv2_pair_metrics(plan.handle, _ptr(d_pair_sums), _ptr(d_workspace), wb,
-                                  _stream(stream)), "qv2_pair_metrics")
+    w = "qv2_pair_metrics"
+    ws, wb = _ws(plan, d_workspace, workspace_bytes, w)
+    _check(lib().qv2_pair_metrics(plan.handle, _pair_arg(plan, d_pair_sums, w), ws, wb, _stream(stream)), w)
 
 
 def qv2_fakequant_pair_metrics(plan: Plan, d_params, d_sums, d_pair_sums, d_workspace,
                                workspace_bytes=None, stream=None):
-    wb = workspace_bytes if workspace_bytes is not None else d_workspace.numel() * d_workspace.element_size()
-    _check(lib().qv2_fakequant_pair_metrics(plan.handle, _ptr(d_params), _ptr(d_sums), _ptr(d_pair_sums),
-                                            _ptr(d_workspace), wb, _stream(stream)),
-           "qv2_fakequant_pair_metrics")
+    w = "qv2_fakequant_pair_metrics"
+    ws, wb = _ws(plan, d_workspace, workspace_bytes, w)
+    _check(lib().qv2_fakequant_pair_metrics(plan.handle, *_seg_args(plan, d_params, d_sums, w),
+                                            _pair_arg(plan, d_pair_sums, w), ws, wb, _stream(stream)), w)
 
 
 def qv2_calibrate_fakequant_pair_metrics(plan: Plan, d_params, d_sums, d_pair_sums, d_workspace,
                                          workspace_bytes=None, stream=None):
     """d_pair_sums may be None (no comparison with qrun)."""
-    wb = workspace_bytes if workspace_bytes is not None else d_workspace.numel() * d_workspace.element_size()
+    w = "qv2_calibrate_fakequant_pair_metrics"
+    ws, wb = _ws(plan, d_workspace, workspace_bytes, w)
     _check(lib().qv2_calibrate_fakequant_pair_metrics(
-        plan.handle, _ptr(d_params), _ptr(d_sums), _ptr(d_pair_sums) if d_pair_sums is not None else None,
-        _ptr(d_workspace), wb, _stream(stream)), "qv2_calibrate_fakequant_pair_metrics")
+        plan.handle, *_seg_args(plan, d_params, d_sums, w), _pair_arg(plan, d_pair_sums, w, optional=True),
+        ws, wb, _stream(stream)), w)
 
 
 def qv2_calibrate_fakequant_pair_metrics_cos(plan: Plan, d_params, d_sums, d_pair_sums, d_seg_xxhat, d_pair_xq,
                                              d_workspace, workspace_bytes=None, stream=None):
-    wb = workspace_bytes if workspace_bytes is not None else d_workspace.numel() * d_workspace.element_size()
+    w = "qv2_calibrate_fakequant_pair_metrics_cos"
+    ws, wb = _ws(plan, d_workspace, workspace_bytes, w)
     _check(lib().qv2_calibrate_fakequant_pair_metrics_cos(
-        plan.handle, _ptr(d_params), _ptr(d_sums), _ptr(d_pair_sums), _ptr(d_seg_xxhat), _ptr(d_pair_xq),
-        _ptr(d_workspace), wb, _stream(stream)), "qv2_calibrate_fakequant_pair_metrics_cos")
+        plan.handle, *_seg_args(plan, d_params, d_sums, w), _pair_arg(plan, d_pair_sums, w),
+        *_cos_args(plan, d_seg_xxhat, d_pair_xq, w), ws, wb, _stream(stream)), w)
 
 
 def qv2_fakequant_pair_metrics_cos(plan: Plan, d_params, d_sums, d_pair_sums, d_seg_xxhat, d_pair_xq,
                                    d_workspace, workspace_bytes=None, stream=None):
-    wb = workspace_bytes if workspace_bytes is not None else d_workspace.numel() * d_workspace.element_size()
-    _check(lib().qv2_fakequant_pair_metrics_cos(plan.handle, _ptr(d_params), _ptr(d_sums), _ptr(d_pair_sums),
-                                                _ptr(d_seg_xxhat), _ptr(d_pair_xq), _ptr(d_workspace), wb,
-                                                _stream(stream)), "qv2_fakequant_pair_metrics_cos")
+    w = "qv2_fakequant_pair_metrics_cos"
+    ws, wb = _ws(plan, d_workspace, workspace_bytes, w)
+    _check(lib().qv2_fakequant_pair_metrics_cos(
+        plan.handle, *_seg_args(plan, d_params, d_sums, w), _pair_arg(plan, d_pair_sums, w),
+        *_cos_args(plan, d_seg_xxhat, d_pair_xq, w), ws, wb, _stream(stream)), w)
 
 
 def qv2_cosine_finalize(plan: Plan, h_sums, h_seg_xxhat, h_pair, h_pair_xq, strict: bool = True):
@@ -314,9 +366,13 @@ def qv2_histogram_workspace_bytes(plan: Plan, nbins: int) -> int:
 
 def qv2_histogram(plan: Plan, d_params, nbins: int, d_hist_x, d_hist_q, d_workspace, workspace_bytes=None,
                   stream=None):
-    wb = workspace_bytes if workspace_bytes is not None else d_workspace.numel() * d_workspace.element_size()
-    _check(lib().qv2_histogram(plan.handle, _ptr(d_params), int(nbins), _ptr(d_hist_x), _ptr(d_hist_q),
-                               _ptr(d_workspace), wb, _stream(stream)), "qv2_histogram")
+    w = "qv2_histogram"
+    ws, wb = _ws(plan, d_workspace, workspace_bytes, w)
+    hb = plan.num_tensors * max(int(nbins), 0) * 8
+    _check(lib().qv2_histogram(plan.handle,
+                               _dev(d_params, plan.num_segments * QPARAMS.itemsize, f"{w}: d_params"), int(nbins),
+                               _dev(d_hist_x, hb, f"{w}: d_hist_x", 8),
+                               _dev(d_hist_q, hb, f"{w}: d_hist_q", 8, optional=True), ws, wb, _stream(stream)), w)
 
 
 def qv2_kl_divergence(hist_p, hist_q, eps: float = 0.0) -> float:
@@ -332,9 +388,14 @@ def qv2_kl_divergence(hist_p, hist_q, eps: float = 0.0) -> float:
 
 def qv2_bn_fold(d_w, channels: int, inner: int, d_gamma, d_var, d_w_out, d_bias=None, d_mean=None,
                 d_beta=None, d_bias_out=None, stream=None):
-    _check(lib().qv2_bn_fold(_ptr(d_w), int(channels), int(inner), _ptr(d_gamma), _ptr(d_var), _ptr(d_bias),
-                             _ptr(d_mean), _ptr(d_beta), _ptr(d_w_out), _ptr(d_bias_out), _stream(stream)),
-           "qv2_bn_fold")
+    w, c, n = "qv2_bn_fold", max(int(channels), 0), max(int(channels), 0) * max(int(inner), 0)
+    _check(lib().qv2_bn_fold(_dev(d_w, 4 * n, f"{w}: d_w", 4), int(channels), int(inner),
+                             _dev(d_gamma, 4 * c, f"{w}: d_gamma", 4), _dev(d_var, 4 * c, f"{w}: d_var", 4),
+                             _dev(d_bias, 4 * c, f"{w}: d_bias", 4, optional=True),
+                             _dev(d_mean, 4 * c, f"{w}: d_mean", 4, optional=True),
+                             _dev(d_beta, 4 * c, f"{w}: d_beta", 4, optional=True),
+                             _dev(d_w_out, 4 * n, f"{w}: d_w_out", 4),
+                             _dev(d_bias_out, 4 * c, f"{w}: d_bias_out", 4, optional=True), _stream(stream)), w)
 
 
 def qv2_write_config(path: str, keep_fp32, layer_names=None):
@@ -361,8 +422,10 @@ def qv2_regroup_for_fusion(order, group_id) -> np.ndarray:
 
 
 def qv2_tensor_sums_fold(plan: Plan, d_params, d_sums, d_tensor_sums, stream=None):
-    _check(lib().qv2_tensor_sums_fold(plan.handle, _ptr(d_params), _ptr(d_sums), _ptr(d_tensor_sums),
-                                      _stream(stream)), "qv2_tensor_sums_fold")
+    w = "qv2_tensor_sums_fold"
+    _check(lib().qv2_tensor_sums_fold(plan.handle, *_seg_args(plan, d_params, d_sums, w),
+                                      _dev(d_tensor_sums, plan.num_tensors * TENSOR_SUMS.itemsize,
+                                           f"{w}: d_tensor_sums"), _stream(stream)), w)
 
 
 def qv2_finalize_tensors(h_tensor_sums: np.ndarray, strict: bool = True) -> np.ndarray:

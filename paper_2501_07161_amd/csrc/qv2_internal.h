@@ -147,6 +147,7 @@ struct qv2_plan {
 
   // device copy (made by the first device call, on the device current then)
   void* d_blob = nullptr;
+  int device = -1;               // the device that holds d_blob (current at the first device call)
   qv2::Tile* d_read_tiles = nullptr;
   qv2::Tile* d_quant_tiles = nullptr;
   qv2::Tile* d_row_tiles = nullptr;

@@ -1315,7 +1315,11 @@ size_t bytes_of(const std::vector<T>& v) { return v.size() * sizeof(T); }
 
 // First device call on a plan: one allocation holding all tables, blocking copies.
 qv2_status ensure_uploaded(qv2_plan* p) {
-  if (p->d_blob) return QV2_OK;
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess) { (void)hipGetLastError(); return QV2_ERR_HIP; }
+  // the tables live on one device: a later call with another device current would hand its
+  // kernels pointers they cannot use
+  if (p->d_blob) return dev == p->device ? QV2_OK : QV2_ERR_HIP;
   size_t total = 256;
   auto reserve = [&](size_t n) { const size_t at = total; total += align256(n); return at; };
   const size_t o_read = reserve(bytes_of(p->read_tiles)), o_quant = reserve(bytes_of(p->quant_tiles));
@@ -1363,6 +1367,7 @@ qv2_status ensure_uploaded(qv2_plan* p) {
       put(o_bst, p->big_stat_pair_tensors.data(), bytes_of(p->big_stat_pair_tensors)));
   if (!ok) { (void)hipGetLastError(); (void)hipFree(blob); return QV2_ERR_HIP; }
   p->d_blob = blob;
+  p->device = dev;
   return QV2_OK;
 }
 
@@ -1532,14 +1537,15 @@ void qv2_plan_destroy(qv2_plan* plan) {
 qv2_status qv2_plan_set_timing(qv2_plan* plan, int32_t enable) {
   if (!plan) return QV2_ERR_NULL;
   if (enable && !plan->ev_start[0]) {
-    for (int k = 0; k < QV2_K_COUNT; ++k) {
-      hipEvent_t a = nullptr, b = nullptr;
-      if (hipEventCreate(&a) != hipSuccess || hipEventCreate(&b) != hipSuccess) {
+    hipEvent_t ev[2 * QV2_K_COUNT] = {};
+    for (int k = 0; k < 2 * QV2_K_COUNT; ++k) {
+      if (hipEventCreate(&ev[k]) != hipSuccess) {      // all or none
         (void)hipGetLastError();
+        for (int j = 0; j < k; ++j) (void)hipEventDestroy(ev[j]);
         return QV2_ERR_HIP;
       }
-      plan->ev_start[k] = a; plan->ev_stop[k] = b;
     }
+    for (int k = 0; k < QV2_K_COUNT; ++k) { plan->ev_start[k] = ev[2 * k]; plan->ev_stop[k] = ev[2 * k + 1]; }
   }
   plan->timing = enable != 0;
   return QV2_OK;

@@ -119,6 +119,79 @@ def test_device_calls_validate_before_touching_the_gpu():
     assert one(p.handle, FAKE, FAKE, FAKE + 4, FAKE, ws, None) == qb.QV2_ERR_ALIGN
 
 
+def test_binding_refuses_buffers_a_kernel_could_not_use():
+    """Host tensors, short buffers, wrong element sizes and non-contiguous views never reach the
+    library: the Python layer raises before any pointer is taken."""
+    import torch
+    host = torch.zeros(100)
+    with pytest.raises(qb.QV2Error) as e:
+        qb.qv2_plan_create([_row(100, x=host)])
+    assert e.value.status == qb.QV2_ERR_NULL and "not a device tensor" in str(e.value)
+
+    class FakeDev:                       # stands in for a device tensor (no GPU in this test)
+        is_cuda = True
+
+        def __init__(self, n, size=4, contiguous=True):
+            self.n, self.size, self.c = n, size, contiguous
+
+        def is_contiguous(self):
+            return self.c
+
+        def element_size(self):
+            return self.size
+
+        def numel(self):
+            return self.n
+
+        def data_ptr(self):
+            return FAKE
+
+    for bad, what in ((dict(x=FakeDev(99)), "holds 396 bytes, 400 needed"),
+                      (dict(x=FakeDev(100, size=8)), "8-byte elements"),
+                      (dict(x=FakeDev(100, contiguous=False)), "not contiguous"),
+                      (dict(qrun=FakeDev(50)), "qrun of tensor 0"),
+                      (dict(codes=FakeDev(100, size=4)), "codes of tensor 0"),
+                      (dict(codes=FakeDev(99, size=1)), "holds 99 bytes, 100 needed")):
+        with pytest.raises(qb.QV2Error) as e:
+            qb.qv2_plan_create([_row(100, **bad)])
+        assert e.value.status == qb.QV2_ERR_SHAPE and what in str(e.value), str(e.value)
+
+    p = qb.qv2_plan_create([_row(64 * 9, qb.QV2_SYM_CHANNEL, 64, x=FakeDev(64 * 9), qrun=FakeDev(64 * 9),
+                                 codes=FakeDev(64 * 9, size=1))])
+    ok_params, ok_sums = FakeDev(64 * 24, 1), FakeDev(64 * 32, 1)
+    ws = FakeDev(p.workspace_bytes, 1)
+    cases = [
+        (qb.qv2_calibrate, (FakeDev(64 * 24 - 1, 1), ok_sums, ws), "d_params"),
+        (qb.qv2_calibrate, (ok_params, FakeDev(63 * 32, 1), ws), "d_sums"),
+        (qb.qv2_fakequant_metrics, (ok_params, host, ws), "not a device tensor"),
+        (qb.qv2_pair_metrics, (FakeDev(31, 1), ws), "d_pair_sums"),
+        (qb.qv2_fakequant_pair_metrics, (ok_params, ok_sums, FakeDev(8, 1), ws), "d_pair_sums"),
+        (qb.qv2_calibrate_fakequant_pair_metrics, (ok_params, ok_sums, FakeDev(8, 1), ws), "d_pair_sums"),
+        (qb.qv2_calibrate_fakequant_pair_metrics_cos,
+         (ok_params, ok_sums, FakeDev(32, 1), FakeDev(63, 8), FakeDev(1, 8), ws), "d_seg_xxhat"),
+        (qb.qv2_fakequant_pair_metrics_cos,
+         (ok_params, ok_sums, FakeDev(32, 1), FakeDev(64, 8), FakeDev(0, 8), ws), "d_pair_xq"),
+        (qb.qv2_tensor_sums_fold, (ok_params, ok_sums, FakeDev(47, 1)), "d_tensor_sums"),
+        (qb.qv2_histogram, (ok_params, 16, FakeDev(15, 8), None, ws), "d_hist_x"),
+        (qb.qv2_histogram, (ok_params, 16, FakeDev(16, 4), None, ws), "8 expected"),
+    ]
+    for fn, args, what in cases:
+        with pytest.raises(qb.QV2Error) as e:
+            fn(p, *args, stream=0)
+        assert what in str(e.value), (fn.__name__, str(e.value))
+    # a workspace smaller than the plan needs is the library's own check
+    with pytest.raises(qb.QV2Error) as e:
+        qb.qv2_calibrate(p, ok_params, ok_sums, FakeDev(p.workspace_bytes - 1, 1), stream=0)
+    assert e.value.status == qb.QV2_ERR_WORKSPACE
+    with pytest.raises(qb.QV2Error) as e:
+        qb.qv2_bn_fold(FakeDev(64 * 9 - 1), 64, 9, FakeDev(64), FakeDev(64), FakeDev(64 * 9), stream=0)
+    assert "d_w" in str(e.value)
+    with pytest.raises(qb.QV2Error) as e:
+        qb.qv2_bn_fold(FakeDev(64 * 9), 64, 9, FakeDev(63), FakeDev(64), FakeDev(64 * 9), stream=0)
+    assert "d_gamma" in str(e.value)
+    p.close()
+
+
 # ----------------------------------------------------------------------------
 # finalize (Eq. 6-7) against the oracle on oracle-made sums
 # ----------------------------------------------------------------------------
