@@ -180,7 +180,7 @@ def test_many_small_tiles(fused, monkeypatch):
     H.check_all(items, res)
 
 
-@pytest.mark.parametrize("seed", [11, 12, 13])
+@pytest.mark.parametrize("seed", [11, 12, 13, 14, 15, 16, 17, 18])
 def test_random_layer_tables(seed):
     """Randomly drawn layer tables: sizes from 1 to 300 K elements, any scheme, channel counts and
     row lengths on both sides of every path's limits (LDS rows, register rows, rows as stream
