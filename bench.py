@@ -268,11 +268,31 @@ def main():
             torch.cuda.synchronize()
             if it >= 1:
                 t_s.append(e0.elapsed_time(e1))
+        # the same single call for a caller that wants the metrics only (no code buffers): the
+        # quantize sweep then stores nothing and runs over long read-only tiles
+        rows_m = [qb.TensorArg(x=r.x, numel=r.numel, scheme=r.scheme, channels=r.channels, qrun=r.qrun,
+                               kind=r.kind, layer=r.layer) for r in rows]
+        plan_m = qb.qv2_plan_create(rows_m)
+        buf_m = qb.Buffers(plan_m, dev)
+        t_m = []
+        for it in range(5):
+            e0.record()
+            qb.qv2_calibrate_fakequant_pair_metrics(plan_m, buf_m.params, buf_m.sums, buf_m.pair, buf_m.workspace)
+            e1.record()
+            torch.cuda.synchronize()
+            if it >= 1:
+                t_m.append(e0.elapsed_time(e1))
+        plan_m.close()
+        del buf_m
         hist_bytes = 4 * n_all + 4 * n_pair
         extras = {"histogram_2048_bins": {"kernel_ms": round(float(np.mean(t_h)), 4),
                                           "GBps": round(hist_bytes / np.mean(t_h) / 1e6, 1)},
                   "fused_quantize_with_cosine": {"kernel_ms": round(float(np.mean(t_c)), 4)},
-                  "single_call_with_cosine": {"call_ms": round(float(np.mean(t_s)), 4)}}
+                  "single_call_with_cosine": {"call_ms": round(float(np.mean(t_s)), 4)},
+                  "single_call_metrics_only": {"call_ms": round(float(np.mean(t_m)), 4),
+                                               "moved_bytes": 8 * n_all + 4 * n_pair - 4 * n_rowgroup,
+                                               "GBps": round((8 * n_all + 4 * n_pair - 4 * n_rowgroup)
+                                                             / np.mean(t_m) / 1e6, 1)}}
         del hx, hq, hws
         # quantize + dequantize + error of single batch-1 activations (the shapes of the paper's
         # Q-DQ overhead table, Sec. 7; its 341-1518 us per tensor are from other hardware: context)

@@ -81,7 +81,8 @@ typedef struct {
   const float* x;      /* DEVICE, contiguous fp32, 4-byte aligned (16-byte: fast path) */
   const float* qrun;   /* DEVICE or NULL: the same tensor taken from the quantized
                           inference (Algorithm 2's Q[i]); enables pair metrics      */
-  int8_t* codes;       /* DEVICE or NULL: receives numel int8 codes                 */
+  int8_t* codes;       /* DEVICE or NULL: receives numel int8 codes.  NULL = metrics
+                          only: the quantize sweep then stores nothing (4 B/element) */
   int64_t numel;       /* > 0                                                       */
   int32_t channels;    /* QV2_SYM_CHANNEL: number of dim-0 slices, must divide
                           numel; other schemes: must be 1                           */
@@ -152,7 +153,7 @@ typedef struct qv2_plan qv2_plan;
 
 /* Validates the layer table and cuts it into tiles: one flat tile table over all
  * tensors, so that one launch covers every layer whatever its size.
- * Errors: NULL table or out -> ERR_NULL; n_tensors <= 0, numel <= 0, channels
+ * Errors: NULL table or out -> ERR_NULL; n_tensors <= 0, numel <= 0 or > 2^36, channels
  * not dividing numel (or != 1 for per-tensor schemes), more than 2^31-1 tiles
  * or segments -> ERR_SHAPE; unknown scheme -> ERR_SCHEME; x (or qrun) not
  * 4-byte aligned -> ERR_ALIGN; x NULL -> ERR_NULL; no host memory for the tile

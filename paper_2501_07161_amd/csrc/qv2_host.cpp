@@ -69,7 +69,7 @@ static qv2_status plan_create(const qv2_tensor* h_tensors, int32_t n_tensors, qv
   for (int32_t t = 0; t < n_tensors; ++t) {
     const qv2_tensor& in = h_tensors[t];
     if (!in.x) return QV2_ERR_NULL;
-    if (in.numel <= 0) return QV2_ERR_SHAPE;
+    if (in.numel <= 0 || in.numel > qv2::kMaxNumel) return QV2_ERR_SHAPE;
     if (in.scheme != QV2_ASYM_TENSOR && in.scheme != QV2_SYM_TENSOR && in.scheme != QV2_SYM_CHANNEL)
       return QV2_ERR_SCHEME;
     const bool per_channel = in.scheme == QV2_SYM_CHANNEL;
@@ -154,7 +154,9 @@ static qv2_status plan_create(const qv2_tensor* h_tensors, int32_t n_tensors, qv
       }
       row_part += nseg;
     } else {
-      const int64_t n_read = (inner + TR - 1) / TR, n_quant = (inner + TQ - 1) / TQ;
+      // without a code buffer the quantize sweep stores nothing: long tiles, as for a read-only pass
+      const int64_t TQt = in.codes ? TQ : TR;
+      const int64_t n_read = (inner + TR - 1) / TR, n_quant = (inner + TQt - 1) / TQt;
       if (sp + nseg * n_read > kMax || ep + nseg * n_quant > kMax) { err = QV2_ERR_SHAPE; break; }
       ft.part0 = static_cast<int32_t>(ep); ft.nparts = static_cast<int32_t>(nseg * n_quant);
       st.part0 = static_cast<int32_t>(sp); st.nparts = static_cast<int32_t>(nseg * n_read);
@@ -171,9 +173,9 @@ static qv2_status plan_create(const qv2_tensor* h_tensors, int32_t n_tensors, qv
           p->read_tiles.push_back(tl);
         }
         for (int64_t k = 0; k < n_quant; ++k) {
-          Tile tl = make_tile(in, t, s * inner + k * TQ, std::min<int64_t>(TQ, inner - k * TQ));
+          Tile tl = make_tile(in, t, s * inner + k * TQt, std::min<int64_t>(TQt, inner - k * TQt));
           tl.part0 = static_cast<int32_t>(ep++); tl.seg0 = static_cast<int32_t>(seg0 + s);
-          p->quant_tiles.push_back(tl);
+          (in.codes ? p->quant_tiles : p->quant_ro_tiles).push_back(tl);
         }
       }
     }
@@ -251,7 +253,8 @@ int64_t qv2_plan_num_tiles(const qv2_plan* plan) {
   return plan ? static_cast<int64_t>(plan->read_tiles.size() + plan->row_tiles.size() + plan->reg_tiles.size()) : 0;
 }
 int64_t qv2_plan_num_quant_tiles(const qv2_plan* plan) {
-  return plan ? static_cast<int64_t>(plan->quant_tiles.size() + plan->row_tiles.size() + plan->reg_tiles.size()) : 0;
+  return plan ? static_cast<int64_t>(plan->quant_tiles.size() + plan->quant_ro_tiles.size() +
+                                     plan->row_tiles.size() + plan->reg_tiles.size()) : 0;
 }
 int64_t qv2_plan_num_pair_tiles(const qv2_plan* plan) {
   return plan ? static_cast<int64_t>(plan->pair_tiles.size()) : 0;

@@ -51,6 +51,10 @@ constexpr int kDefaultReadTile = 32768;
 // (block x kVecQuant x 4 elements).  A kernel that mixes code stores into the read stream
 // runs fastest when all in-flight workgroups sweep a narrow address window.
 constexpr int kDefaultQuantTile = kBlockQuant * kVecQuant * 4;
+// Largest tensor a plan accepts: 2^36 elements (256 GiB of fp32, about all of the device memory); keeps
+// the host tile tables of a nonsense length from being built at all.
+constexpr int64_t kMaxNumel = int64_t{1} << 36;
+
 // Histogram pass: a chunk is at least this long; the plan aims at about kHistChunks chunks.
 constexpr int kHistMinChunk = 65536;
 constexpr int kHistChunks = 4096;
@@ -124,6 +128,8 @@ struct qv2_plan {
   std::vector<qv2::TensorInfo> info;
   std::vector<qv2::Tile> read_tiles;     // calibration: stream tiles (read size)
   std::vector<qv2::Tile> quant_tiles;    // quantize passes: stream tiles (quantize size)
+  std::vector<qv2::Tile> quant_ro_tiles; // ... of tensors without a code buffer: the sweep only reads
+                                         // them, so they are cut like the read-only passes' tiles
   std::vector<qv2::Tile> row_tiles;      // row-group tiles staged in LDS, used by both
   std::vector<qv2::Tile> reg_tiles;      // row-group tiles held in registers, used by both
   std::vector<qv2::Tile> pair_tiles;     // pair pass: stream tiles over tensors with qrun
@@ -150,6 +156,7 @@ struct qv2_plan {
   int device = -1;               // the device that holds d_blob (current at the first device call)
   qv2::Tile* d_read_tiles = nullptr;
   qv2::Tile* d_quant_tiles = nullptr;
+  qv2::Tile* d_quant_ro_tiles = nullptr;
   qv2::Tile* d_row_tiles = nullptr;
   qv2::Tile* d_reg_tiles = nullptr;
   qv2::Tile* d_pair_tiles = nullptr;

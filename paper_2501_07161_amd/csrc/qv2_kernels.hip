@@ -50,6 +50,10 @@ constexpr int kWave = 64;
 #define QV2_NT_STORES 1
 #endif
 constexpr int kVecRead = QV2_VEC_READ;
+#ifndef QV2_VEC_QUANT_RO
+#define QV2_VEC_QUANT_RO 4
+#endif
+constexpr int kVecQuantRO = QV2_VEC_QUANT_RO;     // 16-byte loads per lane in flight, quantize sweep without codes
 constexpr int kFoldBlock = 1024;    // workgroup that folds one segment with many partials
 
 // 16-byte streaming load of data that is read once per pass.
@@ -762,7 +766,8 @@ template <> struct ErrRec<true> { typedef ErrPartial5 type; };
 __device__ __forceinline__ void set_cross(ErrPartial3&, double, double) {}
 __device__ __forceinline__ void set_cross(ErrPartial5& o, double sxh, double sxq) { o.sxh = sxh; o.sxq = sxq; }
 
-template <int BLOCK, int V, bool PAIR, bool COS, bool X2 = true>
+// RO: tiles of tensors without a code buffer (no store is compiled in; long tiles).
+template <int BLOCK, int V, bool PAIR, bool COS, bool X2 = true, bool RO = false>
 __global__ __launch_bounds__(BLOCK, (PAIR ? QV2_QUANT_WAVES_PER_EU : QV2_QUANT_PLAIN_WAVES_PER_EU)) void k_quant_stream(
     const Tile* __restrict__ tiles, const qv2_qparams* __restrict__ params,
     typename ErrRec<COS>::type* __restrict__ parts) {
@@ -779,7 +784,7 @@ __global__ __launch_bounds__(BLOCK, (PAIR ? QV2_QUANT_WAVES_PER_EU : QV2_QUANT_P
   const gf_ptr p = (gf_ptr)tl.x;
   const gf_ptr b = (gf_ptr)tl.q;
   const gi8_ptr c = (gi8_ptr)tl.c;
-  const bool has_c = tl.c != nullptr;
+  const bool has_c = !RO && tl.c != nullptr;
   const bool has_b = PAIR && tl.q != nullptr;
   const int len = tl.len, tid = threadIdx.x;
   double sx2 = 0.0, se2 = 0.0, sd2 = 0.0, sxh = 0.0, sxq = 0.0;
@@ -1330,7 +1335,7 @@ qv2_status ensure_uploaded(qv2_plan* p) {
   const size_t o_bp = reserve(bytes_of(p->big_pair_tensors)), o_bf = reserve(bytes_of(p->big_fused_pair_tensors));
   const size_t o_ht = reserve(bytes_of(p->hist_tiles)), o_hten = reserve(bytes_of(p->hist_tensors));
   const size_t o_st = reserve(bytes_of(p->stat_pair_tensors)), o_bst = reserve(bytes_of(p->big_stat_pair_tensors));
-  const size_t o_reg = reserve(bytes_of(p->reg_tiles));
+  const size_t o_reg = reserve(bytes_of(p->reg_tiles)), o_qro = reserve(bytes_of(p->quant_ro_tiles));
   char* blob = nullptr;
   if (hipMalloc(reinterpret_cast<void**>(&blob), total) != hipSuccess) {
     (void)hipGetLastError();
@@ -1361,6 +1366,7 @@ qv2_status ensure_uploaded(qv2_plan* p) {
   p->d_hist_tensors =
       static_cast<HistTensor*>(put(o_hten, p->hist_tensors.data(), bytes_of(p->hist_tensors)));
   p->d_reg_tiles = static_cast<Tile*>(put(o_reg, p->reg_tiles.data(), bytes_of(p->reg_tiles)));
+  p->d_quant_ro_tiles = static_cast<Tile*>(put(o_qro, p->quant_ro_tiles.data(), bytes_of(p->quant_ro_tiles)));
   p->d_stat_pair_tensors =
       static_cast<PairTensor*>(put(o_st, p->stat_pair_tensors.data(), bytes_of(p->stat_pair_tensors)));
   p->d_big_stat_pair_tensors = static_cast<int32_t*>(
@@ -1418,6 +1424,18 @@ void launch_rows(qv2_plan* plan, const qv2_qparams* d_params, qv2_qparams* d_par
   }
 }
 
+// the stream tiles of a quantize pass: those with a code buffer, then those without
+template <bool PAIR, bool COS, bool X2>
+void launch_quant_stream(qv2_plan* plan, int n_stream, int n_ro, const qv2_qparams* d_params,
+                         typename ErrRec<COS>::type* parts, hipStream_t s) {
+  if (n_stream > 0)
+    hipLaunchKernelGGL((k_quant_stream<kBlockQuant, kVecQuant, PAIR, COS, X2>), dim3(n_stream),
+                       dim3(kBlockQuant), 0, s, plan->d_quant_tiles, d_params, parts);
+  if (n_ro > 0)
+    hipLaunchKernelGGL((k_quant_stream<kBlockRead, kVecQuantRO, PAIR, COS, X2, true>), dim3(n_ro),
+                       dim3(kBlockRead), 0, s, plan->d_quant_ro_tiles, d_params, parts);
+}
+
 // quantize pass over stream and row-group tiles, then ONE fold launch for the segments'
 // error sums and (d_pair_sums != null) the tensors' pair sums.  d_params_out != null: the
 // row-group kernel also calibrates its rows (writes their parameter and sum records), and
@@ -1430,20 +1448,18 @@ void launch_quant(qv2_plan* plan, const qv2_qparams* d_params, qv2_sums* d_sums,
   typedef typename ErrRec<COS>::type P;
   const bool calib_rows = d_params_out != nullptr;
   const int n_stream = static_cast<int>(plan->quant_tiles.size());
+  const int n_ro = static_cast<int>(plan->quant_ro_tiles.size());
   const int n_rows = static_cast<int>(plan->row_tiles.size());
-  if (n_stream > 0) {
+  if (n_stream + n_ro > 0) {
     // pair_in_stats: the calibration sweep already compared the stream tensors with their
     // partners, so the plain quantize kernel serves them
     Timed timed(plan, PAIR && !pair_in_stats ? QV2_K_QUANTPAIR_STREAM : QV2_K_QUANT_STREAM, s);
     if (PAIR && !pair_in_stats)
-      hipLaunchKernelGGL((k_quant_stream<kBlockQuant, kVecQuant, PAIR, COS>), dim3(n_stream),
-                         dim3(kBlockQuant), 0, s, plan->d_quant_tiles, d_params, parts);
+      launch_quant_stream<PAIR, COS, true>(plan, n_stream, n_ro, d_params, parts, s);
     else if (calib_rows)      // the calibration sweep of this same call already summed x^2
-      hipLaunchKernelGGL((k_quant_stream<kBlockQuant, kVecQuant, false, COS, false>), dim3(n_stream),
-                         dim3(kBlockQuant), 0, s, plan->d_quant_tiles, d_params, parts);
+      launch_quant_stream<false, COS, false>(plan, n_stream, n_ro, d_params, parts, s);
     else
-      hipLaunchKernelGGL((k_quant_stream<kBlockQuant, kVecQuant, false, COS>), dim3(n_stream),
-                         dim3(kBlockQuant), 0, s, plan->d_quant_tiles, d_params, parts);
+      launch_quant_stream<false, COS, true>(plan, n_stream, n_ro, d_params, parts, s);
   }
   const int n_regs = static_cast<int>(plan->reg_tiles.size());
   if (n_rows + n_regs > 0) {

@@ -85,7 +85,7 @@ void check_plan(const std::vector<qv2_tensor>& rows) {
     }
     nseg += s;
     check_cover({&p->read_tiles, &p->row_tiles, &p->reg_tiles}, in, t, true);
-    check_cover({&p->quant_tiles, &p->row_tiles, &p->reg_tiles}, in, t, true);
+    check_cover({&p->quant_tiles, &p->quant_ro_tiles, &p->row_tiles, &p->reg_tiles}, in, t, true);
     check_cover({&p->hist_tiles}, in, t, true);
     check_cover({&p->pair_tiles}, in, t, in.qrun != nullptr);
     if (!in.qrun) {
@@ -100,7 +100,7 @@ void check_plan(const std::vector<qv2_tensor>& rows) {
   CHECK(qv2_plan_num_tiles(p) ==
         static_cast<int64_t>(p->read_tiles.size() + p->row_tiles.size() + p->reg_tiles.size()));
   CHECK(qv2_plan_num_quant_tiles(p) ==
-        static_cast<int64_t>(p->quant_tiles.size() + p->row_tiles.size() + p->reg_tiles.size()));
+        static_cast<int64_t>(p->quant_tiles.size() + p->quant_ro_tiles.size() + p->row_tiles.size() + p->reg_tiles.size()));
   CHECK(qv2_plan_num_pair_tiles(p) == static_cast<int64_t>(p->pair_tiles.size()));
 
   // partial slots: every slot of a numbering is written by exactly one (tile, row), lies in
@@ -137,7 +137,8 @@ void check_plan(const std::vector<qv2_tensor>& rows) {
     }
   };
   for (const Tile& tl : p->read_tiles) { CHECK(tl.rows == 0 && tl.len <= p->read_tile); mark(tl, true, false); }
-  for (const Tile& tl : p->quant_tiles) { CHECK(tl.rows == 0 && tl.len <= p->quant_tile); mark(tl, false, true); }
+  for (const Tile& tl : p->quant_tiles) { CHECK(tl.rows == 0 && tl.len <= p->quant_tile && tl.c); mark(tl, false, true); }
+  for (const Tile& tl : p->quant_ro_tiles) { CHECK(tl.rows == 0 && tl.len <= p->read_tile && !tl.c); mark(tl, false, true); }
   for (const Tile& tl : p->row_tiles) { CHECK(tl.rows > 0 && tl.lanes == 0); mark(tl, true, true); }
   for (const Tile& tl : p->reg_tiles) {
     // register form: whole vectors on 16-byte boundaries, a row fits its lanes, the rows fit the workgroup
@@ -306,9 +307,9 @@ void plans() {
   CHECK(qv2_plan_create(&bad, 1, &p) == QV2_ERR_ALIGN);
   bad = r; bad.x = nullptr;
   CHECK(qv2_plan_create(&bad, 1, &p) == QV2_ERR_NULL);
-  bad = r; bad.numel = int64_t{1} << 43;                        // more quantize tiles than an int32 holds
+  bad = r; bad.numel = (int64_t{1} << 36) + 1;                  // beyond the largest tensor a plan takes
   CHECK(qv2_plan_create(&bad, 1, &p) == QV2_ERR_SHAPE);
-  bad = r; bad.scheme = QV2_SYM_CHANNEL; bad.channels = 1; bad.numel = int64_t{1} << 43;
+  bad.scheme = QV2_SYM_CHANNEL; bad.channels = 1; bad.codes = reinterpret_cast<int8_t*>(0x2000);
   CHECK(qv2_plan_create(&bad, 1, &p) == QV2_ERR_SHAPE);
 }
 

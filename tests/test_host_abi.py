@@ -78,10 +78,10 @@ def test_plan_rejects_empty_and_null():
 def test_plan_tiling_counts():
     TR, TQ = 32768, 2048                                        # default read / quantize stream tiles
     rows = [
-        _row(200_704, qrun=FAKE),                               # 7 read tiles (6 full + 4096), 98 quantize tiles
-        _row(9408),                                             # 1 read tile, 5 quantize tiles
+        _row(200_704, qrun=FAKE, codes=FAKE),                   # 7 read tiles (6 full + 4096), 98 quantize tiles
+        _row(9408, codes=FAKE),                                 # 1 read tile, 5 quantize tiles
         _row(32 * 9, qb.QV2_SYM_CHANNEL, 32),                   # 16 lanes per row, 16 rows per 256-thread tile -> 2 tiles
-        _row(4096 * 40000, qb.QV2_SYM_CHANNEL, 4096),           # rows longer than a tile: 2 / 20 tiles each
+        _row(4096 * 40000, qb.QV2_SYM_CHANNEL, 4096, codes=FAKE),   # rows longer than a tile: 2 / 20 tiles each
         _row(2048 * 512, qb.QV2_SYM_CHANNEL, 2048),             # aligned rows of 512: 16 lanes per row, 16 rows per 256-thread tile -> 128 tiles
         _row(3000 * 3, qb.QV2_SYM_CHANNEL, 3000),               # 4 lanes per row: 64 rows per tile -> 47 tiles
     ]
@@ -98,6 +98,11 @@ def test_plan_tiling_counts():
     assert qb.lib().qv2_plan_segment_begin(p.handle, 6) == -1
     p.close()
     assert (200_704 + TR - 1) // TR == 7 and (200_704 + TQ - 1) // TQ == 98 and (40000 + TQ - 1) // TQ == 20
+    # without a code buffer the quantize sweep stores nothing and its tiles are as long as the read tiles
+    p = qb.qv2_plan_create([_row(200_704, qrun=FAKE), _row(9408), _row(4 * 40000, qb.QV2_SYM_CHANNEL, 4),
+                            _row(9408, codes=FAKE)])
+    assert p.num_tiles == 7 + 1 + 4 * 2 + 1 and p.num_quant_tiles == 7 + 1 + 4 * 2 + 5
+    p.close()
 
 
 def test_device_calls_validate_before_touching_the_gpu():
