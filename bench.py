@@ -41,7 +41,7 @@ ROCPROF_NAMES = {"k_statspair_stream": "k_stats_stream<512, 8, true, false>",
 # HBM bytes per launch of the dominant kernel on the resnet50 b256 workload from rocprofv3
 # --pmc (FETCH_SIZE and WRITE_SIZE runs, each scaled by a copy kernel of known size); see
 # profiles/sensitivity_pass_resnet50_b256.txt.
-TRAFFIC_BYTES = {"k_statspair_stream": 21_697_424_997, "k_pair_stream": 21_697_111_049,
+TRAFFIC_BYTES = {"k_statspair_stream": 21_697_364_277, "k_pair_stream": 21_697_202_899,
                  "k_quantpair_stream": 24_627_581_264}
 
 
