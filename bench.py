@@ -36,7 +36,7 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBPS = 8000.0   # MI355X published HBM3E bandwidth
 ROCPROF_NAMES = {"k_statspair_stream": "k_stats_stream<512, 8, true, false>",
-                 "k_quantpair_stream": "k_quant_stream<256, 2, true, false>", "k_pair_stream": "k_pair_stream<512, 4>"}
+                 "k_quantpair_stream": "k_quant_stream<256, 2, true, false, true, false>", "k_pair_stream": "k_pair_stream<512, 4>"}
 
 # HBM bytes per launch of the dominant kernel on the resnet50 b256 workload from rocprofv3
 # --pmc (FETCH_SIZE and WRITE_SIZE runs, each scaled by a copy kernel of known size); see
