@@ -221,6 +221,11 @@ static qv2_status plan_create(const qv2_tensor* h_tensors, int32_t n_tensors, qv
     }
   }
 
+  // launch order: longest chunks first, so the last workgroups to start are the short
+  // remainders (a chunk's partial slot is its part0, not its place in this table)
+  std::stable_sort(p->hist_tiles.begin(), p->hist_tiles.end(),
+                   [](const Tile& a, const Tile& b) { return a.len > b.len; });
+
   for (size_t i = 0; i < p->segments.size(); ++i) {
     if (p->segments[i].snp > qv2::kFoldWaveMax) p->big_stat_segments.push_back(static_cast<int32_t>(i));
     if (p->segments[i].enp > qv2::kFoldWaveMax) p->big_err_segments.push_back(static_cast<int32_t>(i));

@@ -65,7 +65,8 @@ __device__ __forceinline__ f4 ld4(gf4_ptr p) {
 #endif
 }
 
-// Packed int8 codes are written once and not read again by this library.
+// Dword written once and not read again by the kernel that writes it: packed int8 codes, and
+// the histogram pass's partial counts.
 __device__ __forceinline__ void st_codes(gu32_ptr p, uint32_t v) {
 #if QV2_NT_STORES
   __builtin_nontemporal_store(v, p);
@@ -1225,8 +1226,9 @@ __global__ __launch_bounds__(BLOCK) void k_hist(const Tile* __restrict__ tiles,
   hist_stream<BLOCK>(tl.x, tl.len, b, h[0]);
   if (tl.q) hist_stream<BLOCK>(tl.q, tl.len, b, h[1]);
   __syncthreads();
-  uint32_t* out = partial + static_cast<size_t>(tl.part0) * 2 * nbins;
-  for (int i = threadIdx.x; i < nbins; i += BLOCK) { out[i] = h[0][i]; out[nbins + i] = h[1][i]; }
+  // non-temporal: these few stores ride in a read-only stream and cost it least that way
+  const gu32_ptr out = (gu32_ptr)(partial + static_cast<size_t>(tl.part0) * 2 * nbins);
+  for (int i = threadIdx.x; i < nbins; i += BLOCK) { st_codes(out + i, h[0][i]); st_codes(out + nbins + i, h[1][i]); }
 }
 
 // Sums a tensor's chunk histograms: ceil(nbins / 256) workgroups per tensor.

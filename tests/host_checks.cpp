@@ -191,10 +191,21 @@ void check_plan(const std::vector<qv2_tensor>& rows) {
   CHECK(bp == p->big_pair_tensors && bf == p->big_fused_pair_tensors);
 
   // histogram chunks
+  {
+    std::vector<char> seen(p->hist_tiles.size(), 0);
+    for (const Tile& tl : p->hist_tiles) {
+      CHECK(tl.part0 >= 0 && tl.part0 < static_cast<int32_t>(seen.size()) && !seen[tl.part0]);
+      seen[tl.part0] = 1;
+    }
+    for (size_t i = 1; i < p->hist_tiles.size(); ++i) CHECK(p->hist_tiles[i - 1].len >= p->hist_tiles[i].len);
+  }
   for (int32_t t = 0; t < nt; ++t) {
     const qv2::HistTensor& ht = p->hist_tensors[t];
     CHECK(ht.seg0 == p->info[t].seg0 && ht.nseg == p->info[t].nseg && ht.nchunks >= 1);
-    for (int32_t k = 0; k < ht.nchunks; ++k) CHECK(p->hist_tiles[ht.chunk0 + k].tensor == t);
+    int32_t mine = 0;                      // the tensor's chunks own exactly its range of partial slots
+    for (const Tile& tl : p->hist_tiles)
+      if (tl.tensor == t) { CHECK(tl.part0 >= ht.chunk0 && tl.part0 < ht.chunk0 + ht.nchunks); ++mine; }
+    CHECK(mine == ht.nchunks);
   }
   CHECK(qv2_histogram_workspace_bytes(p, 0) == 0 && qv2_histogram_workspace_bytes(p, qv2::kHistMaxBins + 1) == 0);
   CHECK(qv2_histogram_workspace_bytes(p, 2048) >= p->hist_tiles.size() * 2048 * sizeof(uint32_t));
