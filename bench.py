@@ -63,9 +63,12 @@ def parse():
                     help="print one checksum line per input tensor to stderr (the JSON line always carries "
                          "their combination as config.inputs_checksum)")
     ap.add_argument("--cpu-sample-elems", type=int, default=2_000_000_000)
-    ap.add_argument("--cold", action="store_true",
-                    help="also time every step after streaming a 1 GiB scratch buffer (evicts the 256 MB "
-                         "Infinity Cache); matters only for sets that are not far larger than that cache")
+    ap.add_argument("--no-cold", dest="cold", action="store_false",
+                    help="skip the second timing in which every step follows a 1 GiB fill that evicts the "
+                         "256 MB Infinity Cache (reported as `cold`; it matters only for sets that are not "
+                         "far larger than that cache)")
+    ap.add_argument("--cold", dest="cold", action="store_true", help="(default) see --no-cold")
+    ap.set_defaults(cold=True)
     ap.add_argument("--no-single-tensor-extra", action="store_true",
                     help="skip the 1600 tiny fake-quant calls of extras.fakequant_single_tensor_us (profiling runs)")
     ap.add_argument("--copy-probe", action="store_true",
