@@ -1,0 +1,45 @@
+"""The benchmark's command line: one GPU only, and - on the GPU - one JSON line with the fields
+the measurement contract names."""
+import json
+import os
+import subprocess
+import sys
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_more_than_one_gpu_is_refused_with_a_message():
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True,
+                       text=True, timeout=120)
+    assert r.returncode != 0 and "ONE GPU" in r.stderr and r.stdout.strip() == ""
+
+
+@pytest.mark.gpu
+def test_json_line_of_a_small_run():
+    """ResNet-18 batch 32 (a parity-test set, not the headline workload): every field of the
+    contract is present and consistent."""
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--workload", "resnet18", "--steps", "5",
+                        "--warmup", "2", "--cpu-sample-elems", "20000000", "--no-single-tensor-extra"],
+                       capture_output=True, text=True, timeout=300)
+    assert r.returncode == 0, r.stderr[-2000:]
+    lines = [l for l in r.stdout.splitlines() if l.startswith("{")]
+    assert len(lines) == 1
+    d = json.loads(lines[0])
+    for k in ("metric", "value", "unit", "n_gpus", "steps", "warmup", "ms_per_step", "higher_is_better", "scaling",
+              "vs_baseline", "dtype", "data", "config", "roofline", "cpu_baseline"):
+        assert k in d, k
+    assert d["n_gpus"] == 1 and d["steps"] == 5 and d["warmup"] == 2 and d["unit"] == "GB/s"
+    assert d["vs_baseline"] is None and d["dtype"] == "f32" and d["data"] == "synthetic"
+    assert d["config"]["workload"] == "resnet18_b32" and "model" not in d["config"]
+    rf = d["roofline"]
+    assert rf["bound"] == "hbm" and rf["peak"] == 8000.0 and rf["unit"] == "GB/s"
+    assert abs(rf["frac"] - rf["achieved"] / rf["peak"]) < 1e-3 and 0.0 < rf["frac"] < 1.0
+    assert rf["traffic"] is None                       # counters were taken on the headline workload only
+    cb = d["cpu_baseline"]
+    assert cb["kind"] == "oracle" and cb["cores"] == 1 and cb["value"] > 0 and cb["sample"]
+    assert d["cpu_baseline_all_cores"]["cores"] >= 1
+    assert abs(d["value"] - d["config"]["algorithmic_bytes_per_pass"] / d["ms_per_step"] / 1e6) < 0.01 * d["value"]
+    assert d["other_pass"]["same_order"] is True
+    assert d["ms_per_step_min"] <= d["ms_per_step_median"] and d["cold"]["ms_per_step"] > 0
