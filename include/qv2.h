@@ -16,6 +16,7 @@
  *      (Algorithm 2, RankLayersBySensitivity)               -> qv2_rank
  * Steps 1-3 are also available as one call that visits every tensor as few
  * times as the method allows       -> qv2_calibrate_fakequant_pair_metrics
+ * and steps 1-4 as one host call   -> qv2_sensitivity_pass
  *
  * Conventions
  *  - Pointers named d_* are DEVICE pointers, h_* are HOST pointers.  Every
@@ -372,6 +373,27 @@ qv2_status qv2_rank_tensors(const qv2_plan* plan, const qv2_tensor_sums* h_tenso
                             const qv2_pair_sums* h_pair_sums, const int32_t* layer_pos,
                             int32_t n_layers, const qv2_rank_config* cfg, int32_t* order_out,
                             double* score_out);
+
+/* Steps 1-4 in one host call: qv2_calibrate_fakequant_pair_metrics, qv2_tensor_sums_fold,
+ * ONE copy of the per-tensor records to the host, Eq. 6-7 for every tensor and pair, and
+ * qv2_rank_tensors.  Unlike the device calls above it waits for hip_stream (the ranking needs
+ * the records), so it returns with every output valid.
+ * d_records / h_records: num_tensors qv2_tensor_sums followed by num_tensors qv2_pair_sums
+ *   (80 bytes per tensor), DEVICE and HOST, 8-byte aligned; both are written.  Pinned host
+ *   memory lets the copy run without a staging buffer.
+ * d_params / d_sums / d_workspace / hip_stream: as in qv2_calibrate_fakequant_pair_metrics.
+ * layer_pos / n_layers / cfg / order_out / score_out: as in qv2_rank_tensors.
+ * h_metrics[num_tensors], h_pair_mse[num_tensors], h_pair_sqnr_db[num_tensors]: each may be
+ *   NULL; entries of tensors without qrun hold MSE 0 and SQNR +inf.
+ * Errors: those of the calls it makes; non-finite sums are reported (ERR_NONFINITE) only after
+ * every output has been written. */
+qv2_status qv2_sensitivity_pass(qv2_plan* plan, qv2_qparams* d_params, qv2_sums* d_sums,
+                                void* d_records, void* h_records, void* d_workspace,
+                                size_t workspace_bytes, void* hip_stream,
+                                const int32_t* layer_pos, int32_t n_layers,
+                                const qv2_rank_config* cfg, qv2_metrics* h_metrics,
+                                double* h_pair_mse, double* h_pair_sqnr_db, int32_t* order_out,
+                                double* score_out);
 
 /* ---- after the ranking: baselines and the BOPs cut (Sec. 7; need no GPU) ---- */
 

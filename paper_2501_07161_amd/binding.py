@@ -32,7 +32,7 @@ EXPORTS = (
     "qv2_plan_set_timing", "qv2_plan_kernel_ms", "qv2_plan_kernels_ms", "qv2_histogram_workspace_bytes", "qv2_histogram",
     "qv2_kl_divergence", "qv2_bn_fold", "qv2_regroup_for_fusion", "qv2_tensor_sums_fold",
     "qv2_finalize_tensors",
-    "qv2_finalize", "qv2_pair_finalize", "qv2_rank_config_default", "qv2_rank", "qv2_rank_tensors", "qv2_write_config",
+    "qv2_finalize", "qv2_pair_finalize", "qv2_rank_config_default", "qv2_rank", "qv2_rank_tensors", "qv2_sensitivity_pass", "qv2_write_config",
     "qv2_baseline_order", "qv2_bops_reduction_pct", "qv2_bops_select",
     "qv2_status_string",
 )
@@ -121,6 +121,8 @@ def lib():
         L.qv2_rank_config_default.restype = None
         L.qv2_rank.argtypes = [vp, vp, vp, vp, vp, i32, ctypes.POINTER(qv2_rank_config), vp, vp]
         L.qv2_rank_tensors.argtypes = [vp, vp, vp, vp, i32, ctypes.POINTER(qv2_rank_config), vp, vp]
+        L.qv2_sensitivity_pass.argtypes = [vp, vp, vp, vp, vp, vp, sz, vp, vp, i32, ctypes.POINTER(qv2_rank_config),
+                                           vp, vp, vp, vp, vp]
         L.qv2_write_config.argtypes = [ctypes.c_char_p, vp, vp, i32]
         L.qv2_baseline_order.argtypes = [i32, vp, i32, vp]
         L.qv2_bops_reduction_pct.argtypes = [vp, vp, i32, vp]
@@ -506,6 +508,47 @@ def qv2_rank_tensors(plan: "Plan", h_tensor_sums, h_pair_sums, n_layers: int, la
                                   _ptr(pos), n_layers, ctypes.byref(cfg) if cfg is not None else None,
                                   order.ctypes.data, score.ctypes.data), "qv2_rank_tensors")
     return order[:n_layers], score[:n_layers]
+
+
+class PassOutputs:
+    """Reusable host-side outputs of qv2_sensitivity_pass for one plan: a pinned mirror of the
+    per-tensor records and numpy arrays for the metrics and the list."""
+
+    def __init__(self, plan: "Plan", n_layers: int, device="cuda"):
+        import torch
+        nt = plan.num_tensors
+        self.n_layers = int(n_layers)
+        self.n_ts = nt * TENSOR_SUMS.itemsize
+        self.d_records = torch.zeros(self.n_ts + nt * PAIR_SUMS.itemsize, dtype=torch.uint8, device=device)
+        self.h_records = torch.zeros(self.d_records.shape, dtype=torch.uint8, pin_memory=True)
+        self.tensor_sums = self.h_records[:self.n_ts].numpy().view(TENSOR_SUMS)
+        self.pair_sums = self.h_records[self.n_ts:].numpy().view(PAIR_SUMS)
+        self.metrics = np.zeros(nt, dtype=METRICS)
+        self.pair_mse = np.zeros(nt, np.float64)
+        self.pair_sqnr_db = np.zeros(nt, np.float64)
+        self.order = np.zeros(max(self.n_layers, 1), np.int32)
+        self.score = np.zeros(max(self.n_layers, 1), np.float64)
+
+
+def qv2_sensitivity_pass(plan: "Plan", d_params, d_sums, out: PassOutputs, d_workspace, workspace_bytes=None,
+                         stream=None, layer_pos=None, cfg: Optional[qv2_rank_config] = None, strict: bool = True):
+    """Steps 1-4 in one native call (synchronises the stream).  Fills `out`; returns (order, score)."""
+    w = "qv2_sensitivity_pass"
+    ws, wb = _ws(plan, d_workspace, workspace_bytes, w)
+    pos = None if layer_pos is None else np.ascontiguousarray(layer_pos, dtype=np.int32)
+    if pos is not None and len(pos) != out.n_layers:
+        raise QV2Error(QV2_ERR_SHAPE, w)
+    need = plan.num_tensors * (TENSOR_SUMS.itemsize + PAIR_SUMS.itemsize)
+    if out.h_records.numel() < need or out.metrics.size < plan.num_tensors:
+        raise QV2Error(QV2_ERR_SHAPE, f"{w}: outputs made for another plan")
+    st = lib().qv2_sensitivity_pass(
+        plan.handle, *_seg_args(plan, d_params, d_sums, w), _dev(out.d_records, need, f"{w}: d_records"),
+        out.h_records.data_ptr(), ws, wb, _stream(stream), _ptr(pos), out.n_layers,
+        ctypes.byref(cfg) if cfg is not None else None, out.metrics.ctypes.data, out.pair_mse.ctypes.data,
+        out.pair_sqnr_db.ctypes.data, out.order.ctypes.data, out.score.ctypes.data)
+    if st != QV2_OK and (strict or st != QV2_ERR_NONFINITE):
+        raise QV2Error(st, w)
+    return out.order[:out.n_layers], out.score[:out.n_layers]
 
 
 QV2_ORDER_INORDER, QV2_ORDER_WEIGHT_SQNR = 0, 1

@@ -437,6 +437,48 @@ qv2_status qv2_tensor_sums_fold(qv2_plan* plan, const qv2_qparams* d_params, con
   return launch_status();
 }
 
+qv2_status qv2_sensitivity_pass(qv2_plan* plan, qv2_qparams* d_params, qv2_sums* d_sums, void* d_records,
+                                void* h_records, void* d_workspace, size_t workspace_bytes, void* hip_stream,
+                                const int32_t* layer_pos, int32_t n_layers, const qv2_rank_config* cfg,
+                                qv2_metrics* h_metrics, double* h_pair_mse, double* h_pair_sqnr_db,
+                                int32_t* order_out, double* score_out) {
+  if (!plan || !d_records || !h_records || !order_out) return QV2_ERR_NULL;
+  if ((reinterpret_cast<uintptr_t>(d_records) | reinterpret_cast<uintptr_t>(h_records)) & 7u) return QV2_ERR_ALIGN;
+  if (n_layers <= 0) return QV2_ERR_SHAPE;
+  const int32_t nt = static_cast<int32_t>(plan->info.size());
+  const size_t ts_bytes = static_cast<size_t>(nt) * sizeof(qv2_tensor_sums);
+  const size_t bytes = ts_bytes + static_cast<size_t>(nt) * sizeof(qv2_pair_sums);
+  qv2_tensor_sums* d_ts = static_cast<qv2_tensor_sums*>(d_records);
+  qv2_pair_sums* d_pair = reinterpret_cast<qv2_pair_sums*>(static_cast<char*>(d_records) + ts_bytes);
+  const qv2_tensor_sums* h_ts = static_cast<const qv2_tensor_sums*>(h_records);
+  const qv2_pair_sums* h_pair = reinterpret_cast<const qv2_pair_sums*>(static_cast<const char*>(h_records) + ts_bytes);
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+
+  qv2_status st = qv2_calibrate_fakequant_pair_metrics(plan, d_params, d_sums, d_pair, d_workspace,
+                                                       workspace_bytes, hip_stream);
+  if (st != QV2_OK) return st;
+  if ((st = qv2_tensor_sums_fold(plan, d_params, d_sums, d_ts, hip_stream)) != QV2_OK) return st;
+  if (hipMemcpyAsync(h_records, d_records, bytes, hipMemcpyDeviceToHost, s) != hipSuccess ||
+      hipStreamSynchronize(s) != hipSuccess) {
+    (void)hipGetLastError();
+    return QV2_ERR_HIP;
+  }
+  bool finite = true;
+  if (h_metrics) {
+    st = qv2_finalize_tensors(h_ts, nt, h_metrics);
+    if (st == QV2_ERR_NONFINITE) finite = false; else if (st != QV2_OK) return st;
+  }
+  if (h_pair_mse && h_pair_sqnr_db) {
+    st = qv2_pair_finalize(h_pair, nt, h_pair_mse, h_pair_sqnr_db);
+    if (st == QV2_ERR_NONFINITE) finite = false; else if (st != QV2_OK) return st;
+  } else if (h_pair_mse || h_pair_sqnr_db) {
+    return QV2_ERR_NULL;                   // the two pair outputs come together
+  }
+  st = qv2_rank_tensors(plan, h_ts, h_pair, layer_pos, n_layers, cfg, order_out, score_out);
+  if (st != QV2_OK) return st;
+  return finite ? QV2_OK : QV2_ERR_NONFINITE;
+}
+
 qv2_status qv2_bn_fold(const float* d_w, int32_t channels, int64_t inner, const float* d_gamma,
                        const float* d_var, const float* d_bias, const float* d_mean,
                        const float* d_beta, float* d_w_out, float* d_bias_out, void* hip_stream) {

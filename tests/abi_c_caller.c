@@ -188,6 +188,30 @@ static int gpu_mode(const char* path) {
   }
   REQUIRE(fclose(f) == 0);
 
+  /* the same again as ONE host call (it waits for the stream itself): same parameters, same list */
+  {
+    const size_t rec_bytes = NT * (sizeof(qv2_tensor_sums) + sizeof(qv2_pair_sums));
+    void *d_rec, *h_rec = malloc(rec_bytes);
+    qv2_qparams* params2 = (qv2_qparams*)malloc((size_t)nseg * sizeof(qv2_qparams));
+    qv2_metrics met2[NT];
+    double pmse2[NT], psqnr2[NT], score2[NL];
+    int32_t order2[NL];
+    REQUIRE(h_rec && params2);
+    HIP(hipMalloc(&d_rec, rec_bytes));
+    HIP(hipMemset(d_params, 0, (size_t)nseg * sizeof(qv2_qparams)));
+    QV2(qv2_sensitivity_pass(plan, d_params, d_sums, d_rec, h_rec, d_ws, ws_bytes, stream, NULL, NL, NULL, met2,
+                             pmse2, psqnr2, order2, score2));
+    HIP(hipMemcpy(params2, d_params, (size_t)nseg * sizeof(qv2_qparams), hipMemcpyDeviceToHost));
+    REQUIRE(memcmp(params2, params, (size_t)nseg * sizeof(qv2_qparams)) == 0);
+    REQUIRE(memcmp(order2, order, sizeof order) == 0);
+    for (int t = 0; t < NT; ++t) {
+      REQUIRE(met2[t].min == met[t].min && met2[t].max == met[t].max);
+      REQUIRE(met2[t].mse == met[t].mse && pmse2[t] == pmse[t]);   /* same kernels, same order of sums */
+    }
+    HIP(hipFree(d_rec));
+    free(h_rec); free(params2);
+  }
+
   qv2_plan_destroy(plan);
   HIP(hipStreamDestroy(stream));
   for (int t = 0; t < NT; ++t) {

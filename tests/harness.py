@@ -277,6 +277,18 @@ def check_ranking(items: List[Item], res: GpuResult, oracle_rows, cfg_kwargs=Non
         order2, score2 = qb.qv2_rank_tensors(res.plan, res.tsums, res.pair, n_layers, None, cfg)
         assert order2.tolist() == o_order
         assert np.allclose(score2, o_score, rtol=0, atol=2 * SQNR_ATOL_DB)
+        # ... and so must the whole pass as ONE native call, run again on the same plan
+        buf = qb.Buffers(res.plan, items[0].x.device)
+        out = qb.PassOutputs(res.plan, n_layers, items[0].x.device)
+        order3, score3 = qb.qv2_sensitivity_pass(res.plan, buf.params, buf.sums, out, buf.workspace, cfg=cfg)
+        assert order3.tolist() == o_order
+        assert np.allclose(score3, o_score, rtol=0, atol=2 * SQNR_ATOL_DB)
+        p3, s3, _ = buf.host()
+        assert p3.tobytes() == res.params.tobytes()                        # same parameters, bit for bit
+        assert np.array_equal(s3["sum_e2"], res.sums["sum_e2"]) and np.array_equal(s3["n"], res.sums["n"])
+        assert np.allclose(out.metrics["mse"], res.metrics["mse"], rtol=1e-12, atol=0)
+        assert np.allclose(out.pair_mse, res.pair_mse, rtol=1e-12, atol=0)
+        assert np.array_equal(out.pair_sums["n"], res.pair["n"])
     return order.tolist()
 
 

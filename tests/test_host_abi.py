@@ -122,6 +122,17 @@ def test_device_calls_validate_before_touching_the_gpu():
     assert one(p.handle, FAKE, FAKE, None, None, ws, None) == qb.QV2_ERR_NULL      # workspace
     assert one(p.handle, FAKE, FAKE, None, FAKE, ws - 1, None) == qb.QV2_ERR_WORKSPACE
     assert one(p.handle, FAKE, FAKE, FAKE + 4, FAKE, ws, None) == qb.QV2_ERR_ALIGN
+    whole = L.qv2_sensitivity_pass
+    order = (ctypes.c_int32 * 1)()
+    tail = (None, 1, None, None, None, None, order, None)
+    assert whole(p.handle, FAKE, FAKE, None, FAKE, FAKE, ws, None, *tail) == qb.QV2_ERR_NULL      # d_records
+    assert whole(p.handle, FAKE, FAKE, FAKE, None, FAKE, ws, None, *tail) == qb.QV2_ERR_NULL      # h_records
+    assert whole(p.handle, FAKE, FAKE, FAKE + 4, FAKE, FAKE, ws, None, *tail) == qb.QV2_ERR_ALIGN
+    assert whole(p.handle, FAKE, FAKE, FAKE, FAKE, FAKE, ws - 1, None, *tail) == qb.QV2_ERR_WORKSPACE
+    assert whole(p.handle, FAKE, FAKE, FAKE, FAKE, FAKE, ws, None, None, 0, None, None, None, None, order,
+                 None) == qb.QV2_ERR_SHAPE
+    assert whole(p.handle, FAKE, FAKE, FAKE, FAKE, FAKE, ws, None, None, 1, None, None, None, None, None,
+                 None) == qb.QV2_ERR_NULL                                                         # order_out
 
 
 def test_binding_refuses_buffers_a_kernel_could_not_use():
