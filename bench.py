@@ -387,6 +387,9 @@ def main():
         "value_note": "algorithmic bytes of the three calls (4 + 5 + 8 B per element with a partner, fixed "
                       "numerators) / time; it can exceed the HBM rate because the pass visits tensors fewer "
                       "times than three separate calls would. Bytes actually moved / time is hbm_GBps.",
+        "paper_context": "the paper reports 2.99-18.99 s per model for its sensitivity list (ResNet50v1: 18.994 s) "
+                         "on an Intel i7-12700K + NVIDIA RTX 3090 Ti inside the Glow compiler, including its two "
+                         "inferences on real data; another machine and another scope, so no ratio is formed",
         "hbm_GBps": round(moved / (ms_per_step * 1e-3) / 1e9, 2),
         "frac_of_hbm_peak": round(moved / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
         "layers_per_s": round(n_layers / (ms_per_step * 1e-3), 1),
