@@ -235,8 +235,9 @@ qv2_status qv2_fakequant_pair_metrics(qv2_plan* plan, const qv2_qparams* d_param
  * and sum_e2 bit for bit; sum_x2, which stays the calibration sweep's instead of being summed
  * again, and the pair sums up to fp64 summation order), with every tensor
  * made of short segments (per-output-channel tensors whose channel has at most 8192
- * elements) read from HBM ONCE: a group of whole channels is staged in LDS, and range,
- * parameters, codes and energies of each channel are taken from that copy.  Longer
+ * elements) read from HBM ONCE: a group of whole channels is held in registers (or staged
+ * in LDS), and range, parameters, codes and energies of each channel are taken from that
+ * copy.  Longer
  * segments still need two reads (their scale depends on the global range); the comparison
  * with qrun rides on the first, read-only one, the second writes the codes.
  * d_params, d_sums: DEVICE, written.  d_pair_sums[num_tensors]: DEVICE, written; NULL
