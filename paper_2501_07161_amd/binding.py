@@ -149,7 +149,8 @@ def _ptr(buf) -> Optional[int]:
     return buf.data_ptr()
 
 
-def _dev(buf, need_bytes: int, what: str, elem_size: Optional[int] = None, optional: bool = False):
+def _dev(buf, need_bytes: int, what: str, elem_size: Optional[int] = None, optional: bool = False,
+         dtype: Optional[str] = None):
     """Address of a device buffer after checking what can be checked on the host: a torch
     tensor must live on the GPU, be contiguous and hold at least `need_bytes` (and have
     `elem_size`-byte elements when given).  A kernel handed a short or host buffer would fault
@@ -166,6 +167,8 @@ def _dev(buf, need_bytes: int, what: str, elem_size: Optional[int] = None, optio
         raise QV2Error(QV2_ERR_SHAPE, f"{what}: not contiguous")
     if elem_size is not None and buf.element_size() != elem_size:
         raise QV2Error(QV2_ERR_SHAPE, f"{what}: {buf.element_size()}-byte elements, {elem_size} expected")
+    if dtype is not None and str(getattr(buf, "dtype", dtype)) != dtype:
+        raise QV2Error(QV2_ERR_SHAPE, f"{what}: dtype {buf.dtype}, {dtype} expected")
     have = buf.numel() * buf.element_size()
     if have < need_bytes:
         raise QV2Error(QV2_ERR_SHAPE, f"{what}: holds {have} bytes, {need_bytes} needed")
@@ -235,8 +238,9 @@ def qv2_plan_create(rows: Sequence[TensorArg]) -> Plan:
     arr = (qv2_tensor * max(n, 1))()
     for i, r in enumerate(rows):
         nel = int(r.numel)
-        arr[i] = qv2_tensor(_dev(r.x, 4 * nel, f"qv2_plan_create: x of tensor {i}", 4),
-                            _dev(r.qrun, 4 * nel, f"qv2_plan_create: qrun of tensor {i}", 4, optional=True),
+        arr[i] = qv2_tensor(_dev(r.x, 4 * nel, f"qv2_plan_create: x of tensor {i}", 4, dtype="torch.float32"),
+                            _dev(r.qrun, 4 * nel, f"qv2_plan_create: qrun of tensor {i}", 4, optional=True,
+                                 dtype="torch.float32"),
                             _dev(r.codes, nel, f"qv2_plan_create: codes of tensor {i}", 1, optional=True),
                             nel, int(r.channels), int(r.scheme), int(r.kind), int(r.layer))
     h = ctypes.c_void_p()

@@ -162,7 +162,11 @@ def test_binding_refuses_buffers_a_kernel_could_not_use():
         def data_ptr(self):
             return FAKE
 
+    class FakeInt32(FakeDev):
+        dtype = "torch.int32"
+
     for bad, what in ((dict(x=FakeDev(99)), "holds 396 bytes, 400 needed"),
+                      (dict(x=FakeInt32(100)), "torch.float32 expected"),
                       (dict(x=FakeDev(100, size=8)), "8-byte elements"),
                       (dict(x=FakeDev(100, contiguous=False)), "not contiguous"),
                       (dict(qrun=FakeDev(50)), "qrun of tensor 0"),
