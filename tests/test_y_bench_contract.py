@@ -43,3 +43,18 @@ def test_json_line_of_a_small_run():
     assert abs(d["value"] - d["config"]["algorithmic_bytes_per_pass"] / d["ms_per_step"] / 1e6) < 0.01 * d["value"]
     assert d["other_pass"]["same_order"] is True
     assert d["ms_per_step_min"] <= d["ms_per_step_median"] and d["cold"]["ms_per_step"] > 0
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("mode,kernel", [("fused", "k_quantpair_stream"), ("calls", "k_pair_stream")])
+def test_other_pass_forms_report_their_own_dominant_kernel(mode, kernel):
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--workload", "resnet18", "--steps", "5",
+                        "--warmup", "2", "--mode", mode, "--single-mode", "--no-cpu-baseline", "--no-cold"],
+                       capture_output=True, text=True, timeout=300)
+    assert r.returncode == 0, r.stderr[-2000:]
+    d = json.loads([l for l in r.stdout.splitlines() if l.startswith("{")][0])
+    assert d["roofline"]["kernel"] == kernel and d["roofline"]["avg_launch_ms"] > 0
+    assert "cpu_baseline" not in d and "cold" not in d and "other_pass" not in d
+    assert set(d["calls"]) == ({"calibrate", "fakequant_pair_metrics"} if mode == "fused"
+                               else {"calibrate", "fakequant_metrics", "pair_metrics"})
+
