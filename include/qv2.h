@@ -22,7 +22,8 @@
  *  - Pointers named d_* are DEVICE pointers, h_* are HOST pointers.  Every
  *    device buffer (tensors, codes, params, sums, workspace) is allocated and
  *    freed by the caller.  The library owns only the opaque qv2_plan (host
- *    tables plus a small device copy of them, released by qv2_plan_destroy).
+ *    tables plus a device copy of them - qv2_plan_device_bytes() says how large - released
+ *    by qv2_plan_destroy).
  *  - Device calls only enqueue work on `hip_stream` (a hipStream_t passed as
  *    void*; NULL = the default stream) and never synchronise it, except that
  *    the first device call on a plan uploads the plan's tables with a blocking
@@ -179,6 +180,15 @@ int64_t qv2_plan_num_pair_tiles(const qv2_plan* plan);
 /* Bytes of device workspace any device call on this plan needs (256-byte
  * aligned base).  Calls that may overlap in time need separate workspaces. */
 size_t qv2_workspace_bytes(const qv2_plan* plan);
+
+/* Puts the plan's tables on the current device now: one device allocation of
+ * qv2_plan_device_bytes(plan) bytes and host-to-device copies on hip_stream, which is waited for
+ * before the call returns.  Optional - every device call does the same on first use (on the
+ * default stream).  A plan that is already on the current device is
+ * left alone; one that sits on another device gives ERR_HIP. */
+qv2_status qv2_plan_upload(qv2_plan* plan, void* hip_stream);
+/* Size of that device allocation in bytes (0 for a NULL plan); needs no GPU. */
+size_t qv2_plan_device_bytes(const qv2_plan* plan);
 
 /* Optional timing of the tile kernels (for benchmarks).  When enabled, every
  * launch of a tile kernel is bracketed by two HIP events on the call's stream;

@@ -25,7 +25,7 @@ QV2_ASYM_TENSOR, QV2_SYM_TENSOR, QV2_SYM_CHANNEL = 0, 1, 2
 EXPORTS = (
     "qv2_plan_create", "qv2_plan_destroy", "qv2_plan_num_tensors", "qv2_plan_num_segments",
     "qv2_plan_segment_begin", "qv2_plan_num_tiles", "qv2_plan_num_quant_tiles",
-    "qv2_plan_num_pair_tiles",
+    "qv2_plan_num_pair_tiles", "qv2_plan_upload", "qv2_plan_device_bytes",
     "qv2_workspace_bytes", "qv2_calibrate", "qv2_fakequant_metrics", "qv2_pair_metrics",
     "qv2_fakequant_pair_metrics", "qv2_calibrate_fakequant_pair_metrics", "qv2_calibrate_fakequant_pair_metrics_cos",
     "qv2_fakequant_pair_metrics_cos", "qv2_cosine_finalize",
@@ -96,6 +96,9 @@ def lib():
         L.qv2_plan_segment_begin.restype = i64
         L.qv2_workspace_bytes.argtypes = [vp]
         L.qv2_workspace_bytes.restype = sz
+        L.qv2_plan_upload.argtypes = [vp, vp]
+        L.qv2_plan_device_bytes.argtypes = [vp]
+        L.qv2_plan_device_bytes.restype = sz
         L.qv2_calibrate.argtypes = [vp, vp, vp, vp, sz, vp]
         L.qv2_fakequant_metrics.argtypes = [vp, vp, vp, vp, sz, vp]
         L.qv2_pair_metrics.argtypes = [vp, vp, vp, sz, vp]
@@ -273,6 +276,15 @@ def qv2_plan_kernels_ms(plan: Plan, out=None):
         out = np.zeros(len(KERNEL_IDS), dtype=np.float32)
     _check(lib().qv2_plan_kernels_ms(plan.handle, out.ctypes.data), "qv2_plan_kernels_ms")
     return out
+
+
+def qv2_plan_upload(plan: Plan, stream=None):
+    """Puts the plan's tables on the current device now (device calls do it on first use otherwise)."""
+    _check(lib().qv2_plan_upload(plan.handle, _stream(stream)), "qv2_plan_upload")
+
+
+def qv2_plan_device_bytes(plan: Plan) -> int:
+    return lib().qv2_plan_device_bytes(plan.handle)
 
 
 def qv2_workspace_bytes(plan: Plan) -> int:

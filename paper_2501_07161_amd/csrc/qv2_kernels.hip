@@ -40,64 +40,82 @@ size_t align256(size_t v) { return (v + 255) & ~static_cast<size_t>(255); }
 template <class T>
 size_t bytes_of(const std::vector<T>& v) { return v.size() * sizeof(T); }
 
-// First device call on a plan: one allocation holding all tables, blocking copies.
-qv2_status ensure_uploaded(qv2_plan* p) {
+// Where every table of the plan sits in its device blob (256-byte aligned sections).
+struct BlobLayout {
+  size_t read, quant, row, pair, seg, pt, ft, bs, be, bp, bf, ht, hten, st, bst, reg, qro, total;
+};
+
+BlobLayout blob_layout(const qv2_plan* p) {
+  BlobLayout o{};
+  size_t total = 256;
+  auto reserve = [&](size_t n) { const size_t at = total; total += align256(n); return at; };
+  o.read = reserve(bytes_of(p->read_tiles)); o.quant = reserve(bytes_of(p->quant_tiles));
+  o.row = reserve(bytes_of(p->row_tiles)); o.pair = reserve(bytes_of(p->pair_tiles));
+  o.seg = reserve(bytes_of(p->segments)); o.pt = reserve(bytes_of(p->pair_tensors));
+  o.ft = reserve(bytes_of(p->fused_pair_tensors));
+  o.bs = reserve(bytes_of(p->big_stat_segments)); o.be = reserve(bytes_of(p->big_err_segments));
+  o.bp = reserve(bytes_of(p->big_pair_tensors)); o.bf = reserve(bytes_of(p->big_fused_pair_tensors));
+  o.ht = reserve(bytes_of(p->hist_tiles)); o.hten = reserve(bytes_of(p->hist_tensors));
+  o.st = reserve(bytes_of(p->stat_pair_tensors)); o.bst = reserve(bytes_of(p->big_stat_pair_tensors));
+  o.reg = reserve(bytes_of(p->reg_tiles)); o.qro = reserve(bytes_of(p->quant_ro_tiles));
+  o.total = total;
+  return o;
+}
+
+// Puts the plan's tables on the current device: one allocation, the tables copied section by
+// section on `s`, which is then waited for (the host vectors are pageable, so the copies are
+// not asynchronous anyway).  A plan that is already on this device is left alone.
+qv2_status upload(qv2_plan* p, hipStream_t s) {
   int dev = -1;
   if (hipGetDevice(&dev) != hipSuccess) { (void)hipGetLastError(); return QV2_ERR_HIP; }
   // the tables live on one device: a later call with another device current would hand its
   // kernels pointers they cannot use
   if (p->d_blob) return dev == p->device ? QV2_OK : QV2_ERR_HIP;
-  size_t total = 256;
-  auto reserve = [&](size_t n) { const size_t at = total; total += align256(n); return at; };
-  const size_t o_read = reserve(bytes_of(p->read_tiles)), o_quant = reserve(bytes_of(p->quant_tiles));
-  const size_t o_row = reserve(bytes_of(p->row_tiles)), o_pair = reserve(bytes_of(p->pair_tiles));
-  const size_t o_seg = reserve(bytes_of(p->segments)), o_pt = reserve(bytes_of(p->pair_tensors));
-  const size_t o_ft = reserve(bytes_of(p->fused_pair_tensors));
-  const size_t o_bs = reserve(bytes_of(p->big_stat_segments)), o_be = reserve(bytes_of(p->big_err_segments));
-  const size_t o_bp = reserve(bytes_of(p->big_pair_tensors)), o_bf = reserve(bytes_of(p->big_fused_pair_tensors));
-  const size_t o_ht = reserve(bytes_of(p->hist_tiles)), o_hten = reserve(bytes_of(p->hist_tensors));
-  const size_t o_st = reserve(bytes_of(p->stat_pair_tensors)), o_bst = reserve(bytes_of(p->big_stat_pair_tensors));
-  const size_t o_reg = reserve(bytes_of(p->reg_tiles)), o_qro = reserve(bytes_of(p->quant_ro_tiles));
+  const BlobLayout o = blob_layout(p);
   char* blob = nullptr;
-  if (hipMalloc(reinterpret_cast<void**>(&blob), total) != hipSuccess) {
+  if (hipMalloc(reinterpret_cast<void**>(&blob), o.total) != hipSuccess) {
     (void)hipGetLastError();
     return QV2_ERR_HIP;
   }
   bool ok = true;
   auto put = [&](size_t off, const void* h, size_t n) {
-    if (n && hipMemcpy(blob + off, h, n, hipMemcpyHostToDevice) != hipSuccess) ok = false;
+    if (n && hipMemcpyAsync(blob + off, h, n, hipMemcpyHostToDevice, s) != hipSuccess) ok = false;
     return static_cast<void*>(blob + off);
   };
-  p->d_read_tiles = static_cast<Tile*>(put(o_read, p->read_tiles.data(), bytes_of(p->read_tiles)));
-  p->d_quant_tiles = static_cast<Tile*>(put(o_quant, p->quant_tiles.data(), bytes_of(p->quant_tiles)));
-  p->d_row_tiles = static_cast<Tile*>(put(o_row, p->row_tiles.data(), bytes_of(p->row_tiles)));
-  p->d_pair_tiles = static_cast<Tile*>(put(o_pair, p->pair_tiles.data(), bytes_of(p->pair_tiles)));
-  p->d_segments = static_cast<Segment*>(put(o_seg, p->segments.data(), bytes_of(p->segments)));
-  p->d_pair_tensors = static_cast<PairTensor*>(put(o_pt, p->pair_tensors.data(), bytes_of(p->pair_tensors)));
+  p->d_read_tiles = static_cast<Tile*>(put(o.read, p->read_tiles.data(), bytes_of(p->read_tiles)));
+  p->d_quant_tiles = static_cast<Tile*>(put(o.quant, p->quant_tiles.data(), bytes_of(p->quant_tiles)));
+  p->d_row_tiles = static_cast<Tile*>(put(o.row, p->row_tiles.data(), bytes_of(p->row_tiles)));
+  p->d_pair_tiles = static_cast<Tile*>(put(o.pair, p->pair_tiles.data(), bytes_of(p->pair_tiles)));
+  p->d_segments = static_cast<Segment*>(put(o.seg, p->segments.data(), bytes_of(p->segments)));
+  p->d_pair_tensors = static_cast<PairTensor*>(put(o.pt, p->pair_tensors.data(), bytes_of(p->pair_tensors)));
   p->d_fused_pair_tensors =
-      static_cast<PairTensor*>(put(o_ft, p->fused_pair_tensors.data(), bytes_of(p->fused_pair_tensors)));
+      static_cast<PairTensor*>(put(o.ft, p->fused_pair_tensors.data(), bytes_of(p->fused_pair_tensors)));
   p->d_big_stat_segments =
-      static_cast<int32_t*>(put(o_bs, p->big_stat_segments.data(), bytes_of(p->big_stat_segments)));
+      static_cast<int32_t*>(put(o.bs, p->big_stat_segments.data(), bytes_of(p->big_stat_segments)));
   p->d_big_err_segments =
-      static_cast<int32_t*>(put(o_be, p->big_err_segments.data(), bytes_of(p->big_err_segments)));
+      static_cast<int32_t*>(put(o.be, p->big_err_segments.data(), bytes_of(p->big_err_segments)));
   p->d_big_pair_tensors =
-      static_cast<int32_t*>(put(o_bp, p->big_pair_tensors.data(), bytes_of(p->big_pair_tensors)));
+      static_cast<int32_t*>(put(o.bp, p->big_pair_tensors.data(), bytes_of(p->big_pair_tensors)));
   p->d_big_fused_pair_tensors = static_cast<int32_t*>(
-      put(o_bf, p->big_fused_pair_tensors.data(), bytes_of(p->big_fused_pair_tensors)));
-  p->d_hist_tiles = static_cast<Tile*>(put(o_ht, p->hist_tiles.data(), bytes_of(p->hist_tiles)));
+      put(o.bf, p->big_fused_pair_tensors.data(), bytes_of(p->big_fused_pair_tensors)));
+  p->d_hist_tiles = static_cast<Tile*>(put(o.ht, p->hist_tiles.data(), bytes_of(p->hist_tiles)));
   p->d_hist_tensors =
-      static_cast<HistTensor*>(put(o_hten, p->hist_tensors.data(), bytes_of(p->hist_tensors)));
-  p->d_reg_tiles = static_cast<Tile*>(put(o_reg, p->reg_tiles.data(), bytes_of(p->reg_tiles)));
-  p->d_quant_ro_tiles = static_cast<Tile*>(put(o_qro, p->quant_ro_tiles.data(), bytes_of(p->quant_ro_tiles)));
+      static_cast<HistTensor*>(put(o.hten, p->hist_tensors.data(), bytes_of(p->hist_tensors)));
+  p->d_reg_tiles = static_cast<Tile*>(put(o.reg, p->reg_tiles.data(), bytes_of(p->reg_tiles)));
+  p->d_quant_ro_tiles = static_cast<Tile*>(put(o.qro, p->quant_ro_tiles.data(), bytes_of(p->quant_ro_tiles)));
   p->d_stat_pair_tensors =
-      static_cast<PairTensor*>(put(o_st, p->stat_pair_tensors.data(), bytes_of(p->stat_pair_tensors)));
+      static_cast<PairTensor*>(put(o.st, p->stat_pair_tensors.data(), bytes_of(p->stat_pair_tensors)));
   p->d_big_stat_pair_tensors = static_cast<int32_t*>(
-      put(o_bst, p->big_stat_pair_tensors.data(), bytes_of(p->big_stat_pair_tensors)));
+      put(o.bst, p->big_stat_pair_tensors.data(), bytes_of(p->big_stat_pair_tensors)));
+  if (hipStreamSynchronize(s) != hipSuccess) ok = false;
   if (!ok) { (void)hipGetLastError(); (void)hipFree(blob); return QV2_ERR_HIP; }
   p->d_blob = blob;
   p->device = dev;
   return QV2_OK;
 }
+
+// First device call on a plan that was not uploaded explicitly.
+qv2_status ensure_uploaded(qv2_plan* p) { return upload(p, nullptr); }
 
 qv2_status check_call(const qv2_plan* plan, const void* a, const void* b, const void* ws,
                       size_t ws_bytes) {
@@ -258,6 +276,24 @@ void launch_stats(qv2_plan* plan, qv2_qparams* d_params, qv2_sums* d_sums,
   }
 }
 
+// steps 1-3 of the single call, on a workspace of at least plan->workspace_bytes
+void single_call(qv2_plan* plan, qv2_qparams* d_params, qv2_sums* d_sums, qv2_pair_sums* d_pair_sums,
+                 void* d_workspace, hipStream_t s) {
+  // stream tiles: statistics (with the pair comparison: that sweep only reads, and read-only
+  // sweeps run nearest to the HBM rate), fold (parameters), then the plain quantize sweep;
+  // row-group tiles: one kernel, after the statistics fold because the partial records share
+  // the workspace
+  ErrPartial3* parts = static_cast<ErrPartial3*>(d_workspace);
+  if (d_pair_sums) {
+    launch_stats<true>(plan, d_params, d_sums, static_cast<StatPairPartial*>(d_workspace), false, d_pair_sums,
+                       nullptr, s);
+    launch_quant<true, false>(plan, d_params, d_sums, parts, nullptr, d_pair_sums, nullptr, s, d_params, true);
+  } else {
+    launch_stats<false>(plan, d_params, d_sums, static_cast<StatPartial*>(d_workspace), false, nullptr, nullptr, s);
+    launch_quant<false, false>(plan, d_params, d_sums, parts, nullptr, nullptr, nullptr, s, d_params);
+  }
+}
+
 }  // namespace
 
 extern "C" {
@@ -271,6 +307,13 @@ void qv2_plan_destroy(qv2_plan* plan) {
   }
   delete plan;
 }
+
+qv2_status qv2_plan_upload(qv2_plan* plan, void* hip_stream) {
+  if (!plan) return QV2_ERR_NULL;
+  return upload(plan, static_cast<hipStream_t>(hip_stream));
+}
+
+size_t qv2_plan_device_bytes(const qv2_plan* plan) { return plan ? blob_layout(plan).total : 0; }
 
 qv2_status qv2_plan_set_timing(qv2_plan* plan, int32_t enable) {
   if (!plan) return QV2_ERR_NULL;
@@ -372,20 +415,7 @@ qv2_status qv2_calibrate_fakequant_pair_metrics(qv2_plan* plan, qv2_qparams* d_p
   if (st != QV2_OK) return st;
   if (d_pair_sums && (reinterpret_cast<uintptr_t>(d_pair_sums) & 7u)) return QV2_ERR_ALIGN;
   if ((st = ensure_uploaded(plan)) != QV2_OK) return st;
-  hipStream_t s = static_cast<hipStream_t>(hip_stream);
-  // stream tiles: statistics (with the pair comparison: that sweep only reads, and read-only
-  // sweeps run nearest to the HBM rate), fold (parameters), then the plain quantize sweep;
-  // row-group tiles: one kernel, after the statistics fold because the partial records share
-  // the workspace
-  ErrPartial3* parts = static_cast<ErrPartial3*>(d_workspace);
-  if (d_pair_sums) {
-    launch_stats<true>(plan, d_params, d_sums, static_cast<StatPairPartial*>(d_workspace), false, d_pair_sums,
-                       nullptr, s);
-    launch_quant<true, false>(plan, d_params, d_sums, parts, nullptr, d_pair_sums, nullptr, s, d_params, true);
-  } else {
-    launch_stats<false>(plan, d_params, d_sums, static_cast<StatPartial*>(d_workspace), false, nullptr, nullptr, s);
-    launch_quant<false, false>(plan, d_params, d_sums, parts, nullptr, nullptr, nullptr, s, d_params);
-  }
+  single_call(plan, d_params, d_sums, d_pair_sums, d_workspace, static_cast<hipStream_t>(hip_stream));
   return launch_status();
 }
 

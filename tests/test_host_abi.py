@@ -122,6 +122,8 @@ def test_device_calls_validate_before_touching_the_gpu():
     assert one(p.handle, FAKE, FAKE, None, None, ws, None) == qb.QV2_ERR_NULL      # workspace
     assert one(p.handle, FAKE, FAKE, None, FAKE, ws - 1, None) == qb.QV2_ERR_WORKSPACE
     assert one(p.handle, FAKE, FAKE, FAKE + 4, FAKE, ws, None) == qb.QV2_ERR_ALIGN
+    assert L.qv2_plan_upload(None, None) == qb.QV2_ERR_NULL
+    assert L.qv2_plan_device_bytes(None) == 0 and L.qv2_plan_device_bytes(p.handle) >= 256
     whole = L.qv2_sensitivity_pass
     order = (ctypes.c_int32 * 1)()
     tail = (None, 1, None, None, None, None, order, None)
