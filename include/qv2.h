@@ -69,7 +69,8 @@ typedef enum {
   QV2_ERR_HIP = -6,        /* a HIP runtime call or kernel launch failed         */
   QV2_ERR_ALIGN = -7,      /* a device pointer is not aligned as required        */
   QV2_ERR_IO = -8,         /* a file could not be created or written             */
-  QV2_ERR_NOMEM = -9       /* host memory for the plan or a work list ran out    */
+  QV2_ERR_NOMEM = -9,      /* host memory for the plan or a work list ran out    */
+  QV2_ERR_STATE = -10      /* the plan's tables are not on the device yet (qv2_plan_upload) */
 } qv2_status;
 
 typedef enum {
@@ -184,7 +185,8 @@ size_t qv2_workspace_bytes(const qv2_plan* plan);
 /* Puts the plan's tables on the current device now: one device allocation of
  * qv2_plan_device_bytes(plan) bytes and host-to-device copies on hip_stream, which is waited for
  * before the call returns.  Optional - every device call does the same on first use (on the
- * default stream).  A plan that is already on the current device is
+ * default stream) - except for qv2_calibrate_fakequant_pair_metrics_noalloc, which never
+ * allocates and so needs the tables in place.  A plan that is already on the current device is
  * left alone; one that sits on another device gives ERR_HIP. */
 qv2_status qv2_plan_upload(qv2_plan* plan, void* hip_stream);
 /* Size of that device allocation in bytes (0 for a NULL plan); needs no GPU. */
@@ -257,6 +259,25 @@ qv2_status qv2_calibrate_fakequant_pair_metrics(qv2_plan* plan, qv2_qparams* d_p
                                                 qv2_sums* d_sums, qv2_pair_sums* d_pair_sums,
                                                 void* d_workspace, size_t workspace_bytes,
                                                 void* hip_stream);
+
+/* For callers that cannot allocate - code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc: qv2_calibrate_fakequant_pair_metrics without a workspace
+ * argument and without any allocation, by this library or a library it calls.  The partial
+ * records go to a fixed array in device memory that belongs to the library (QV2_STATIC_SCRATCH_BYTES,
+ * one copy per GPU, held until the process ends); outputs and results are those of
+ * qv2_calibrate_fakequant_pair_metrics, bit for bit.
+ * The plan must already be on the current device (qv2_plan_upload, or any earlier device call
+ * on it): otherwise ERR_STATE.  A plan whose qv2_workspace_bytes() exceeds
+ * QV2_STATIC_SCRATCH_BYTES is refused with ERR_WORKSPACE.  Every call on a GPU shares that GPU's
+ * array: calls that may overlap in time on one GPU (two streams, two threads, two plans) race
+ * and must use the entry point with a workspace argument instead.  Nothing in the array has to
+ * be cleared between calls (each call writes every record it later reads).
+ * Other errors: ERR_NULL, ERR_ALIGN, ERR_HIP (another device current than the plan's; the
+ * array's address could not be obtained; a launch failed). */
+#define QV2_STATIC_SCRATCH_BYTES ((size_t)64 << 20)
+qv2_status qv2_calibrate_fakequant_pair_metrics_noalloc(qv2_plan* plan, qv2_qparams* d_params,
+                                                        qv2_sums* d_sums, qv2_pair_sums* d_pair_sums,
+                                                        void* hip_stream);
 
 /* qv2_calibrate_fakequant_pair_metrics that also accumulates the cross terms of the cosine
  * similarity (Sec. 6.1 Eq. 8): d_seg_xxhat[num_segments] and d_pair_xq[num_tensors] as in

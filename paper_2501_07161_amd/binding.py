@@ -19,13 +19,15 @@ LIB_PATH = os.environ.get("QV2_LIB_PATH") or os.path.join(_HERE, "libqv2.so")
 
 QV2_OK = 0
 QV2_ERR_NULL, QV2_ERR_SHAPE, QV2_ERR_SCHEME, QV2_ERR_WORKSPACE = -1, -2, -3, -4
-QV2_ERR_NONFINITE, QV2_ERR_HIP, QV2_ERR_ALIGN, QV2_ERR_IO, QV2_ERR_NOMEM = -5, -6, -7, -8, -9
+QV2_ERR_NONFINITE, QV2_ERR_HIP, QV2_ERR_ALIGN, QV2_ERR_IO, QV2_ERR_NOMEM, QV2_ERR_STATE = -5, -6, -7, -8, -9, -10
+QV2_STATIC_SCRATCH_BYTES = 64 << 20
 QV2_ASYM_TENSOR, QV2_SYM_TENSOR, QV2_SYM_CHANNEL = 0, 1, 2
 
 EXPORTS = (
     "qv2_plan_create", "qv2_plan_destroy", "qv2_plan_num_tensors", "qv2_plan_num_segments",
     "qv2_plan_segment_begin", "qv2_plan_num_tiles", "qv2_plan_num_quant_tiles",
     "qv2_plan_num_pair_tiles", "qv2_plan_upload", "qv2_plan_device_bytes",
+    "qv2_calibrate_fakequant_pair_metrics_noalloc",
     "qv2_workspace_bytes", "qv2_calibrate", "qv2_fakequant_metrics", "qv2_pair_metrics",
     "qv2_fakequant_pair_metrics", "qv2_calibrate_fakequant_pair_metrics", "qv2_calibrate_fakequant_pair_metrics_cos",
     "qv2_fakequant_pair_metrics_cos", "qv2_cosine_finalize",
@@ -99,6 +101,7 @@ def lib():
         L.qv2_plan_upload.argtypes = [vp, vp]
         L.qv2_plan_device_bytes.argtypes = [vp]
         L.qv2_plan_device_bytes.restype = sz
+        L.qv2_calibrate_fakequant_pair_metrics_noalloc.argtypes = [vp, vp, vp, vp, vp]
         L.qv2_calibrate.argtypes = [vp, vp, vp, vp, sz, vp]
         L.qv2_fakequant_metrics.argtypes = [vp, vp, vp, vp, sz, vp]
         L.qv2_pair_metrics.argtypes = [vp, vp, vp, sz, vp]
@@ -340,6 +343,15 @@ def qv2_calibrate_fakequant_pair_metrics(plan: Plan, d_params, d_sums, d_pair_su
     _check(lib().qv2_calibrate_fakequant_pair_metrics(
         plan.handle, *_seg_args(plan, d_params, d_sums, w), _pair_arg(plan, d_pair_sums, w, optional=True),
         ws, wb, _stream(stream)), w)
+
+
+def qv2_calibrate_fakequant_pair_metrics_noalloc(plan: Plan, d_params, d_sums, d_pair_sums, stream=None):
+    """The single call on the library's own fixed device array: no workspace, no allocation.
+    The plan must have been uploaded (qv2_plan_upload or an earlier device call)."""
+    w = "qv2_calibrate_fakequant_pair_metrics_noalloc"
+    _check(lib().qv2_calibrate_fakequant_pair_metrics_noalloc(
+        plan.handle, *_seg_args(plan, d_params, d_sums, w), _pair_arg(plan, d_pair_sums, w, optional=True),
+        _stream(stream)), w)
 
 
 def qv2_calibrate_fakequant_pair_metrics_cos(plan: Plan, d_params, d_sums, d_pair_sums, d_seg_xxhat, d_pair_xq,

@@ -24,6 +24,8 @@
 // unit); this file holds the launches and the extern "C" device entry points.
 #include <hip/hip_runtime.h>
 
+#include <mutex>
+
 #include "qv2_dev_common.h"   // loads / stores, reductions, the quantizer
 #include "qv2_dev_calib.h"    // pass 1: k_stats_stream, k_stats_rows
 #include "qv2_dev_fold.h"     // k_fold_stats, k_fold_quant, k_fold_pair
@@ -39,6 +41,31 @@ size_t align256(size_t v) { return (v + 255) & ~static_cast<size_t>(255); }
 
 template <class T>
 size_t bytes_of(const std::vector<T>& v) { return v.size() * sizeof(T); }
+
+// Workspace of the one entry point that allocates nothing
+// (qv2_calibrate_fakequant_pair_metrics_noalloc): a fixed array in device memory, one copy per
+// GPU the library runs on, held until the process ends.  In host code the array's name only
+// stands for the symbol; its device address is looked up once per device and kept.
+constexpr size_t kStaticScratchBytes = QV2_STATIC_SCRATCH_BYTES;
+static __device__ __attribute__((used)) __align__(256) unsigned char scratch[kStaticScratchBytes];
+constexpr int kMaxDevices = 64;
+void* g_scratch_ptr[kMaxDevices] = {};
+std::mutex g_scratch_mu;
+
+// Device address of `scratch` on device `dev`, which must be the current device; null on failure.
+void* scratch_on_device(int dev) {
+  if (dev < 0 || dev >= kMaxDevices) return nullptr;
+  std::lock_guard<std::mutex> lock(g_scratch_mu);
+  if (!g_scratch_ptr[dev]) {
+    void* ptr = nullptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess) {
+      (void)hipGetLastError();
+      return nullptr;
+    }
+    g_scratch_ptr[dev] = ptr;
+  }
+  return g_scratch_ptr[dev];
+}
 
 // Where every table of the plan sits in its device blob (256-byte aligned sections).
 struct BlobLayout {
@@ -111,6 +138,7 @@ qv2_status upload(qv2_plan* p, hipStream_t s) {
   if (!ok) { (void)hipGetLastError(); (void)hipFree(blob); return QV2_ERR_HIP; }
   p->d_blob = blob;
   p->device = dev;
+  (void)scratch_on_device(dev);      // set-up time: the entry point that allocates nothing finds it ready
   return QV2_OK;
 }
 
@@ -416,6 +444,26 @@ qv2_status qv2_calibrate_fakequant_pair_metrics(qv2_plan* plan, qv2_qparams* d_p
   if (d_pair_sums && (reinterpret_cast<uintptr_t>(d_pair_sums) & 7u)) return QV2_ERR_ALIGN;
   if ((st = ensure_uploaded(plan)) != QV2_OK) return st;
   single_call(plan, d_params, d_sums, d_pair_sums, d_workspace, static_cast<hipStream_t>(hip_stream));
+  return launch_status();
+}
+
+qv2_status qv2_calibrate_fakequant_pair_metrics_noalloc(qv2_plan* plan, qv2_qparams* d_params,
+                                                        qv2_sums* d_sums, qv2_pair_sums* d_pair_sums,
+                                                        void* hip_stream) {
+  if (!plan || !d_params || !d_sums) return QV2_ERR_NULL;
+  if ((reinterpret_cast<uintptr_t>(d_params) | reinterpret_cast<uintptr_t>(d_sums) |
+       reinterpret_cast<uintptr_t>(d_pair_sums)) & 7u) return QV2_ERR_ALIGN;
+  if (plan->workspace_bytes > kStaticScratchBytes) return QV2_ERR_WORKSPACE;
+  // the tables must already be on this device: putting them there allocates
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess) { (void)hipGetLastError(); return QV2_ERR_HIP; }
+  if (!plan->d_blob) return QV2_ERR_STATE;
+  if (dev != plan->device) return QV2_ERR_HIP;
+  void* ws = scratch_on_device(dev);
+  if (!ws) return QV2_ERR_HIP;
+  // every partial record the folds read is written by this call's own sweeps first, so what the
+  // previous call left in the array needs no clearing
+  single_call(plan, d_params, d_sums, d_pair_sums, ws, static_cast<hipStream_t>(hip_stream));
   return launch_status();
 }
 

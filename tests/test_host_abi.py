@@ -35,7 +35,7 @@ def test_struct_layouts_match_header_sizes():
 
 
 def test_status_strings():
-    for st in range(-9, 1):
+    for st in range(-10, 1):
         assert qb.lib().qv2_status_string(st) and qb.lib().qv2_status_string(st) != b"unknown status"
     assert b"unknown" in qb.lib().qv2_status_string(-99)
 
@@ -122,6 +122,17 @@ def test_device_calls_validate_before_touching_the_gpu():
     assert one(p.handle, FAKE, FAKE, None, None, ws, None) == qb.QV2_ERR_NULL      # workspace
     assert one(p.handle, FAKE, FAKE, None, FAKE, ws - 1, None) == qb.QV2_ERR_WORKSPACE
     assert one(p.handle, FAKE, FAKE, FAKE + 4, FAKE, ws, None) == qb.QV2_ERR_ALIGN
+    # the entry point that allocates nothing: argument checks come before any GPU call, and a
+    # plan whose partial records would not fit the library's fixed array is refused
+    na = L.qv2_calibrate_fakequant_pair_metrics_noalloc
+    assert na(None, FAKE, FAKE, None, None) == qb.QV2_ERR_NULL
+    assert na(p.handle, None, FAKE, None, None) == qb.QV2_ERR_NULL
+    assert na(p.handle, FAKE, FAKE + 4, None, None) == qb.QV2_ERR_ALIGN
+    assert na(p.handle, FAKE, FAKE, FAKE + 4, None) == qb.QV2_ERR_ALIGN
+    big = qb.qv2_plan_create([_row(1 << 32, codes=FAKE)])           # 2 Mi quantize tiles
+    assert big.workspace_bytes > qb.QV2_STATIC_SCRATCH_BYTES
+    assert na(big.handle, FAKE, FAKE, None, None) == qb.QV2_ERR_WORKSPACE
+    big.close()
     assert L.qv2_plan_upload(None, None) == qb.QV2_ERR_NULL
     assert L.qv2_plan_device_bytes(None) == 0 and L.qv2_plan_device_bytes(p.handle) >= 256
     whole = L.qv2_sensitivity_pass
