@@ -70,7 +70,8 @@ typedef enum {
   QV2_ERR_ALIGN = -7,      /* a device pointer is not aligned as required        */
   QV2_ERR_IO = -8,         /* a file could not be created or written             */
   QV2_ERR_NOMEM = -9,      /* host memory for the plan or a work list ran out    */
-  QV2_ERR_STATE = -10      /* the plan's tables are not on the device yet (qv2_plan_upload) */
+  QV2_ERR_STATE = -10      /* the plan is not in the state the call needs (its tables not on
+                              the device yet; no pass begun in that slot)          */
 } qv2_status;
 
 typedef enum {
@@ -204,6 +205,10 @@ typedef enum {
   QV2_K_COUNT = 10
 } qv2_kernel_id;
 qv2_status qv2_plan_set_timing(qv2_plan* plan, int32_t enable);
+/* Restricts the bracketing to one kernel (a qv2_kernel_id; -1 = all again): every pair of events
+ * between two dependent launches costs a few microseconds of device time, which matters on small
+ * tensor sets.  Forgets the durations recorded so far. */
+qv2_status qv2_plan_time_only(qv2_plan* plan, int32_t kernel);
 qv2_status qv2_plan_kernel_ms(const qv2_plan* plan, int32_t kernel, float* ms_out);
 /* All QV2_K_COUNT durations in one call: ms_out[QV2_K_COUNT], HOST, written. */
 qv2_status qv2_plan_kernels_ms(const qv2_plan* plan, float* ms_out);
@@ -426,6 +431,25 @@ qv2_status qv2_sensitivity_pass(qv2_plan* plan, qv2_qparams* d_params, qv2_sums*
                                 const qv2_rank_config* cfg, qv2_metrics* h_metrics,
                                 double* h_pair_mse, double* h_pair_sqnr_db, int32_t* order_out,
                                 double* score_out);
+
+/* qv2_sensitivity_pass in two halves, so that a caller who runs pass after pass (a calibration
+ * service; a sweep over rank configurations) can overlap the host half of one pass with the device
+ * half of the next.  _begin enqueues the device work and the copy of the records on hip_stream
+ * and marks its end with one of the plan's two completion events (slot 0 or 1; created on first
+ * use); it does not wait.  _end waits for that mark, then finalizes and ranks as
+ * qv2_sensitivity_pass does, from the same h_records.  Two passes may be in flight on one plan
+ * when they use different slots and different h_records (which should be pinned, or the copy
+ * blocks); they share the device buffers, which is safe on one stream.  Arguments and errors as
+ * in qv2_sensitivity_pass; slot outside 0..1 -> ERR_SHAPE; _end on a slot that never began ->
+ * ERR_STATE. */
+qv2_status qv2_sensitivity_pass_begin(qv2_plan* plan, qv2_qparams* d_params, qv2_sums* d_sums,
+                                      void* d_records, void* h_records, void* d_workspace,
+                                      size_t workspace_bytes, void* hip_stream, int32_t slot);
+qv2_status qv2_sensitivity_pass_end(qv2_plan* plan, const void* h_records, int32_t slot,
+                                    const int32_t* layer_pos, int32_t n_layers,
+                                    const qv2_rank_config* cfg, qv2_metrics* h_metrics,
+                                    double* h_pair_mse, double* h_pair_sqnr_db, int32_t* order_out,
+                                    double* score_out);
 
 /* ---- after the ranking: baselines and the BOPs cut (Sec. 7; need no GPU) ---- */
 

@@ -31,7 +31,8 @@ EXPORTS = (
     "qv2_workspace_bytes", "qv2_calibrate", "qv2_fakequant_metrics", "qv2_pair_metrics",
     "qv2_fakequant_pair_metrics", "qv2_calibrate_fakequant_pair_metrics", "qv2_calibrate_fakequant_pair_metrics_cos",
     "qv2_fakequant_pair_metrics_cos", "qv2_cosine_finalize",
-    "qv2_plan_set_timing", "qv2_plan_kernel_ms", "qv2_plan_kernels_ms", "qv2_histogram_workspace_bytes", "qv2_histogram",
+    "qv2_plan_set_timing", "qv2_plan_time_only", "qv2_sensitivity_pass_begin", "qv2_sensitivity_pass_end",
+    "qv2_plan_kernel_ms", "qv2_plan_kernels_ms", "qv2_histogram_workspace_bytes", "qv2_histogram",
     "qv2_kl_divergence", "qv2_bn_fold", "qv2_regroup_for_fusion", "qv2_tensor_sums_fold",
     "qv2_finalize_tensors",
     "qv2_finalize", "qv2_pair_finalize", "qv2_rank_config_default", "qv2_rank", "qv2_rank_tensors", "qv2_sensitivity_pass", "qv2_write_config",
@@ -119,6 +120,10 @@ def lib():
         L.qv2_tensor_sums_fold.argtypes = [vp, vp, vp, vp, vp]
         L.qv2_finalize_tensors.argtypes = [vp, i32, vp]
         L.qv2_plan_set_timing.argtypes = [vp, i32]
+        L.qv2_plan_time_only.argtypes = [vp, i32]
+        L.qv2_sensitivity_pass_begin.argtypes = [vp, vp, vp, vp, vp, vp, sz, vp, i32]
+        L.qv2_sensitivity_pass_end.argtypes = [vp, vp, i32, vp, i32, ctypes.POINTER(qv2_rank_config),
+                                               vp, vp, vp, vp, vp]
         L.qv2_plan_kernel_ms.argtypes = [vp, i32, ctypes.POINTER(ctypes.c_float)]
         L.qv2_plan_kernels_ms.argtypes = [vp, vp]
         L.qv2_finalize.argtypes = [vp, vp, vp, vp]
@@ -261,6 +266,12 @@ KERNEL_IDS = {"k_stats_stream": 0, "k_stats_rows": 1, "k_quant_stream": 2, "k_qu
 
 def qv2_plan_set_timing(plan: Plan, enable: bool):
     _check(lib().qv2_plan_set_timing(plan.handle, int(bool(enable))), "qv2_plan_set_timing")
+
+
+def qv2_plan_time_only(plan: Plan, kernel):
+    """Bracket only this tile kernel (name or id) with events; None = all of them again."""
+    kid = -1 if kernel is None else KERNEL_IDS[kernel] if isinstance(kernel, str) else int(kernel)
+    _check(lib().qv2_plan_time_only(plan.handle, kid), "qv2_plan_time_only")
 
 
 def qv2_plan_kernel_ms(plan: Plan, kernel) -> float:
@@ -577,6 +588,56 @@ def qv2_sensitivity_pass(plan: "Plan", d_params, d_sums, out: PassOutputs, d_wor
     if st != QV2_OK and (strict or st != QV2_ERR_NONFINITE):
         raise QV2Error(st, w)
     return out.order[:out.n_layers], out.score[:out.n_layers]
+
+
+class PreparedPass:
+    """qv2_sensitivity_pass (and its two halves) with every argument checked and converted once,
+    for callers that run the same pass many times: each call is then one foreign call.
+    `outs`: one PassOutputs for run(), two for begin(slot) / end(slot) with two passes in flight."""
+
+    def __init__(self, plan: "Plan", d_params, d_sums, outs, d_workspace, workspace_bytes=None, stream=None,
+                 layer_pos=None, cfg: Optional[qv2_rank_config] = None):
+        w = "qv2_sensitivity_pass"
+        self.plan, self.cfg = plan, cfg
+        self.outs = list(outs) if isinstance(outs, (list, tuple)) else [outs]
+        ws, wb = _ws(plan, d_workspace, workspace_bytes, w)
+        self._keep = (d_params, d_sums, d_workspace)
+        self._pos = None if layer_pos is None else np.ascontiguousarray(layer_pos, dtype=np.int32)
+        need = plan.num_tensors * (TENSOR_SUMS.itemsize + PAIR_SUMS.itemsize)
+        for o in self.outs:
+            if o.h_records.numel() < need or o.metrics.size < plan.num_tensors:
+                raise QV2Error(QV2_ERR_SHAPE, f"{w}: outputs made for another plan")
+            if self._pos is not None and len(self._pos) != o.n_layers:
+                raise QV2Error(QV2_ERR_SHAPE, w)
+        cfgp = ctypes.byref(cfg) if cfg is not None else None
+        st = _stream(stream)
+        dev = [(plan.handle, *_seg_args(plan, d_params, d_sums, w), _dev(o.d_records, need, f"{w}: d_records"),
+                o.h_records.data_ptr(), ws, wb, st) for o in self.outs]
+        host = [(_ptr(self._pos), o.n_layers, cfgp, o.metrics.ctypes.data, o.pair_mse.ctypes.data,
+                 o.pair_sqnr_db.ctypes.data, o.order.ctypes.data, o.score.ctypes.data) for o in self.outs]
+        self._run = dev[0] + host[0]
+        self._begin = [d + (k,) for k, d in enumerate(dev[:2])]
+        self._end = [(plan.handle, o.h_records.data_ptr(), k) + h for k, (o, h) in enumerate(zip(self.outs[:2], host))]
+        L = lib()
+        self._f_run, self._f_begin, self._f_end = L.qv2_sensitivity_pass, L.qv2_sensitivity_pass_begin, \
+            L.qv2_sensitivity_pass_end
+
+    def run(self, strict: bool = True):
+        st = self._f_run(*self._run)
+        if st != QV2_OK and (strict or st != QV2_ERR_NONFINITE):
+            raise QV2Error(st, "qv2_sensitivity_pass")
+        return self.outs[0]
+
+    def begin(self, slot: int):
+        st = self._f_begin(*self._begin[slot])
+        if st != QV2_OK:
+            raise QV2Error(st, "qv2_sensitivity_pass_begin")
+
+    def end(self, slot: int, strict: bool = True):
+        st = self._f_end(*self._end[slot])
+        if st != QV2_OK and (strict or st != QV2_ERR_NONFINITE):
+            raise QV2Error(st, "qv2_sensitivity_pass_end")
+        return self.outs[slot]
 
 
 QV2_ORDER_INORDER, QV2_ORDER_WEIGHT_SQNR = 0, 1

@@ -648,7 +648,7 @@ const char* qv2_status_string(qv2_status s) {
     case QV2_ERR_ALIGN: return "misaligned pointer";
     case QV2_ERR_IO: return "file could not be written";
     case QV2_ERR_NOMEM: return "out of host memory";
-    case QV2_ERR_STATE: return "plan not uploaded to the device";
+    case QV2_ERR_STATE: return "plan not in the state this call needs";
   }
   return "unknown status";
 }

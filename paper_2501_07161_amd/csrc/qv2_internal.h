@@ -177,4 +177,7 @@ struct qv2_plan {
   void* ev_start[QV2_K_COUNT] = {};
   void* ev_stop[QV2_K_COUNT] = {};
   bool ev_used[QV2_K_COUNT] = {};
+  int time_only = -1;            // >= 0: only this kernel's launches are bracketed
+  // completion marks of the two passes qv2_sensitivity_pass_begin may have in flight
+  void* ev_done[2] = {};
 };

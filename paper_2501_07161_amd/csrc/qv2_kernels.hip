@@ -159,10 +159,12 @@ qv2_status launch_status() { return hipGetLastError() == hipSuccess ? QV2_OK : Q
 // Brackets one kernel launch with the plan's HIP events when timing is enabled.
 struct Timed {
   qv2_plan* p; int k; hipStream_t s;
-  Timed(qv2_plan* plan, int kernel, hipStream_t st) : p(plan), k(kernel), s(st) {
-    if (p->timing) { (void)hipEventRecord(static_cast<hipEvent_t>(p->ev_start[k]), s); p->ev_used[k] = true; }
+  bool on;
+  Timed(qv2_plan* plan, int kernel, hipStream_t st)
+      : p(plan), k(kernel), s(st), on(plan->timing && (plan->time_only < 0 || plan->time_only == kernel)) {
+    if (on) { (void)hipEventRecord(static_cast<hipEvent_t>(p->ev_start[k]), s); p->ev_used[k] = true; }
   }
-  ~Timed() { if (p->timing) (void)hipEventRecord(static_cast<hipEvent_t>(p->ev_stop[k]), s); }
+  ~Timed() { if (on) (void)hipEventRecord(static_cast<hipEvent_t>(p->ev_stop[k]), s); }
 };
 
 int fold_grid(int n) { return (n + 3) / 4; }
@@ -333,6 +335,8 @@ void qv2_plan_destroy(qv2_plan* plan) {
     if (plan->ev_start[k]) (void)hipEventDestroy(static_cast<hipEvent_t>(plan->ev_start[k]));
     if (plan->ev_stop[k]) (void)hipEventDestroy(static_cast<hipEvent_t>(plan->ev_stop[k]));
   }
+  for (int k = 0; k < 2; ++k)
+    if (plan->ev_done[k]) (void)hipEventDestroy(static_cast<hipEvent_t>(plan->ev_done[k]));
   delete plan;
 }
 
@@ -357,6 +361,14 @@ qv2_status qv2_plan_set_timing(qv2_plan* plan, int32_t enable) {
     for (int k = 0; k < QV2_K_COUNT; ++k) { plan->ev_start[k] = ev[2 * k]; plan->ev_stop[k] = ev[2 * k + 1]; }
   }
   plan->timing = enable != 0;
+  return QV2_OK;
+}
+
+qv2_status qv2_plan_time_only(qv2_plan* plan, int32_t kernel) {
+  if (!plan) return QV2_ERR_NULL;
+  if (kernel < -1 || kernel >= QV2_K_COUNT) return QV2_ERR_SHAPE;
+  plan->time_only = kernel;
+  for (int k = 0; k < QV2_K_COUNT; ++k) plan->ev_used[k] = false;
   return QV2_OK;
 }
 
@@ -515,33 +527,40 @@ qv2_status qv2_tensor_sums_fold(qv2_plan* plan, const qv2_qparams* d_params, con
   return launch_status();
 }
 
-qv2_status qv2_sensitivity_pass(qv2_plan* plan, qv2_qparams* d_params, qv2_sums* d_sums, void* d_records,
-                                void* h_records, void* d_workspace, size_t workspace_bytes, void* hip_stream,
-                                const int32_t* layer_pos, int32_t n_layers, const qv2_rank_config* cfg,
-                                qv2_metrics* h_metrics, double* h_pair_mse, double* h_pair_sqnr_db,
-                                int32_t* order_out, double* score_out) {
-  if (!plan || !d_records || !h_records || !order_out) return QV2_ERR_NULL;
+namespace {
+
+// device part of qv2_sensitivity_pass: the single call, the per-tensor fold and the copy of the
+// per-tensor records to the host, all enqueued on hip_stream
+qv2_status pass_enqueue(qv2_plan* plan, qv2_qparams* d_params, qv2_sums* d_sums, void* d_records,
+                        void* h_records, void* d_workspace, size_t workspace_bytes, void* hip_stream) {
+  if (!plan || !d_records || !h_records) return QV2_ERR_NULL;
   if ((reinterpret_cast<uintptr_t>(d_records) | reinterpret_cast<uintptr_t>(h_records)) & 7u) return QV2_ERR_ALIGN;
-  if (n_layers <= 0) return QV2_ERR_SHAPE;
-  const int32_t nt = static_cast<int32_t>(plan->info.size());
-  const size_t ts_bytes = static_cast<size_t>(nt) * sizeof(qv2_tensor_sums);
-  const size_t bytes = ts_bytes + static_cast<size_t>(nt) * sizeof(qv2_pair_sums);
+  const size_t nt = plan->info.size();
+  const size_t ts_bytes = nt * sizeof(qv2_tensor_sums);
   qv2_tensor_sums* d_ts = static_cast<qv2_tensor_sums*>(d_records);
   qv2_pair_sums* d_pair = reinterpret_cast<qv2_pair_sums*>(static_cast<char*>(d_records) + ts_bytes);
-  const qv2_tensor_sums* h_ts = static_cast<const qv2_tensor_sums*>(h_records);
-  const qv2_pair_sums* h_pair = reinterpret_cast<const qv2_pair_sums*>(static_cast<const char*>(h_records) + ts_bytes);
-  hipStream_t s = static_cast<hipStream_t>(hip_stream);
-
   qv2_status st = qv2_calibrate_fakequant_pair_metrics(plan, d_params, d_sums, d_pair, d_workspace,
                                                        workspace_bytes, hip_stream);
   if (st != QV2_OK) return st;
   if ((st = qv2_tensor_sums_fold(plan, d_params, d_sums, d_ts, hip_stream)) != QV2_OK) return st;
-  if (hipMemcpyAsync(h_records, d_records, bytes, hipMemcpyDeviceToHost, s) != hipSuccess ||
-      hipStreamSynchronize(s) != hipSuccess) {
+  if (hipMemcpyAsync(h_records, d_records, ts_bytes + nt * sizeof(qv2_pair_sums), hipMemcpyDeviceToHost,
+                     static_cast<hipStream_t>(hip_stream)) != hipSuccess) {
     (void)hipGetLastError();
     return QV2_ERR_HIP;
   }
+  return QV2_OK;
+}
+
+// host part: Eq. 6-7 for every tensor and pair, Eq. 16 and Algorithm 2, from records that have arrived
+qv2_status pass_finish(const qv2_plan* plan, const void* h_records, const int32_t* layer_pos, int32_t n_layers,
+                       const qv2_rank_config* cfg, qv2_metrics* h_metrics, double* h_pair_mse,
+                       double* h_pair_sqnr_db, int32_t* order_out, double* score_out) {
+  const int32_t nt = static_cast<int32_t>(plan->info.size());
+  const qv2_tensor_sums* h_ts = static_cast<const qv2_tensor_sums*>(h_records);
+  const qv2_pair_sums* h_pair = reinterpret_cast<const qv2_pair_sums*>(
+      static_cast<const char*>(h_records) + static_cast<size_t>(nt) * sizeof(qv2_tensor_sums));
   bool finite = true;
+  qv2_status st;
   if (h_metrics) {
     st = qv2_finalize_tensors(h_ts, nt, h_metrics);
     if (st == QV2_ERR_NONFINITE) finite = false; else if (st != QV2_OK) return st;
@@ -549,12 +568,69 @@ qv2_status qv2_sensitivity_pass(qv2_plan* plan, qv2_qparams* d_params, qv2_sums*
   if (h_pair_mse && h_pair_sqnr_db) {
     st = qv2_pair_finalize(h_pair, nt, h_pair_mse, h_pair_sqnr_db);
     if (st == QV2_ERR_NONFINITE) finite = false; else if (st != QV2_OK) return st;
-  } else if (h_pair_mse || h_pair_sqnr_db) {
-    return QV2_ERR_NULL;                   // the two pair outputs come together
   }
   st = qv2_rank_tensors(plan, h_ts, h_pair, layer_pos, n_layers, cfg, order_out, score_out);
   if (st != QV2_OK) return st;
   return finite ? QV2_OK : QV2_ERR_NONFINITE;
+}
+
+}  // namespace
+
+qv2_status qv2_sensitivity_pass(qv2_plan* plan, qv2_qparams* d_params, qv2_sums* d_sums, void* d_records,
+                                void* h_records, void* d_workspace, size_t workspace_bytes, void* hip_stream,
+                                const int32_t* layer_pos, int32_t n_layers, const qv2_rank_config* cfg,
+                                qv2_metrics* h_metrics, double* h_pair_mse, double* h_pair_sqnr_db,
+                                int32_t* order_out, double* score_out) {
+  if (!plan || !d_records || !h_records || !order_out) return QV2_ERR_NULL;
+  if ((h_pair_mse == nullptr) != (h_pair_sqnr_db == nullptr)) return QV2_ERR_NULL;   // the two come together
+  if (n_layers <= 0) return QV2_ERR_SHAPE;
+  qv2_status st = pass_enqueue(plan, d_params, d_sums, d_records, h_records, d_workspace, workspace_bytes,
+                               hip_stream);
+  if (st != QV2_OK) return st;
+  if (hipStreamSynchronize(static_cast<hipStream_t>(hip_stream)) != hipSuccess) {
+    (void)hipGetLastError();
+    return QV2_ERR_HIP;
+  }
+  return pass_finish(plan, h_records, layer_pos, n_layers, cfg, h_metrics, h_pair_mse, h_pair_sqnr_db,
+                     order_out, score_out);
+}
+
+qv2_status qv2_sensitivity_pass_begin(qv2_plan* plan, qv2_qparams* d_params, qv2_sums* d_sums, void* d_records,
+                                      void* h_records, void* d_workspace, size_t workspace_bytes,
+                                      void* hip_stream, int32_t slot) {
+  if (!plan) return QV2_ERR_NULL;
+  if (slot < 0 || slot > 1) return QV2_ERR_SHAPE;
+  if (!plan->ev_done[slot]) {
+    hipEvent_t ev;
+    if (hipEventCreateWithFlags(&ev, hipEventDisableTiming) != hipSuccess) { (void)hipGetLastError(); return QV2_ERR_HIP; }
+    plan->ev_done[slot] = ev;
+  }
+  qv2_status st = pass_enqueue(plan, d_params, d_sums, d_records, h_records, d_workspace, workspace_bytes,
+                               hip_stream);
+  if (st != QV2_OK) return st;
+  if (hipEventRecord(static_cast<hipEvent_t>(plan->ev_done[slot]), static_cast<hipStream_t>(hip_stream)) !=
+      hipSuccess) {
+    (void)hipGetLastError();
+    return QV2_ERR_HIP;
+  }
+  return QV2_OK;
+}
+
+qv2_status qv2_sensitivity_pass_end(qv2_plan* plan, const void* h_records, int32_t slot, const int32_t* layer_pos,
+                                    int32_t n_layers, const qv2_rank_config* cfg, qv2_metrics* h_metrics,
+                                    double* h_pair_mse, double* h_pair_sqnr_db, int32_t* order_out,
+                                    double* score_out) {
+  if (!plan || !h_records || !order_out) return QV2_ERR_NULL;
+  if ((h_pair_mse == nullptr) != (h_pair_sqnr_db == nullptr)) return QV2_ERR_NULL;
+  if (slot < 0 || slot > 1 || n_layers <= 0) return QV2_ERR_SHAPE;
+  if (reinterpret_cast<uintptr_t>(h_records) & 7u) return QV2_ERR_ALIGN;
+  if (!plan->ev_done[slot]) return QV2_ERR_STATE;              // no pass was begun in this slot
+  if (hipEventSynchronize(static_cast<hipEvent_t>(plan->ev_done[slot])) != hipSuccess) {
+    (void)hipGetLastError();
+    return QV2_ERR_HIP;
+  }
+  return pass_finish(plan, h_records, layer_pos, n_layers, cfg, h_metrics, h_pair_mse, h_pair_sqnr_db,
+                     order_out, score_out);
 }
 
 qv2_status qv2_bn_fold(const float* d_w, int32_t channels, int64_t inner, const float* d_gamma,

@@ -10,6 +10,22 @@ import pytest
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
+def test_traffic_figure_comes_from_the_committed_counter_summary():
+    """roofline.traffic is read from profiles/ (not pasted into bench.py): the summary holds a
+    line per profiled kernel, and each figure is the kernel's algorithmic bytes plus a few
+    per cent of tables and partial records at most."""
+    sys.path.insert(0, ROOT)
+    import bench
+    n_act = 2_710_562_816                               # activation elements of ResNet-50 at batch 256
+    for kernel, alg in (("k_statspair_stream", 8 * n_act), ("k_pair_stream", 8 * n_act),
+                        ("k_quantpair_stream", 9 * n_act)):
+        t = bench.traffic_from_profile(bench.ROCPROF_NAMES[kernel])
+        assert t is not None, kernel
+        assert alg <= t <= 1.02 * alg, (kernel, t, alg)
+    assert bench.traffic_from_profile("no_such_kernel") is None
+    assert bench.traffic_from_profile(bench.ROCPROF_NAMES["k_pair_stream"], "/nonexistent") is None
+
+
 def test_more_than_one_gpu_is_refused_with_a_message():
     r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True,
                        text=True, timeout=120)
@@ -40,7 +56,15 @@ def test_json_line_of_a_small_run():
     cb = d["cpu_baseline"]
     assert cb["kind"] == "oracle" and cb["cores"] == 1 and cb["value"] > 0 and cb["sample"]
     assert d["cpu_baseline_all_cores"]["cores"] >= 1
-    assert abs(d["value"] - d["config"]["algorithmic_bytes_per_pass"] / d["ms_per_step"] / 1e6) < 0.01 * d["value"]
+    # the headline rate is bytes actually moved over time: it cannot exceed the HBM peak
+    assert abs(d["value"] - d["config"]["moved_bytes_per_pass"] / d["ms_per_step"] / 1e6) < 0.01 * d["value"]
+    assert 0 < d["value"] < 8000.0 and abs(d["frac_of_hbm_peak"] - d["value"] / 8000.0) < 1e-3
+    assert d["three_call_equivalent_GBps"] > d["value"]
+    assert cb["elements_covered"] <= 20000000 < cb["elements_total"]
+    sp = d["oracle_speedup"]
+    assert sp["vs_1_core"] > sp["vs_all_cores"] > 1 and sp["cores"] == d["cpu_baseline_all_cores"]["cores"]
+    assert d["pipelined"]["same_order"] is True and 0 < d["pipelined"]["ms_per_step"] <= d["ms_per_step"] * 1.05
+    assert "workloads" not in d                        # only the default workload carries the other sets
     assert d["other_pass"]["same_order"] is True
     assert d["ms_per_step_min"] <= d["ms_per_step_median"] and d["cold"]["ms_per_step"] > 0
 
