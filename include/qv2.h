@@ -158,13 +158,17 @@ typedef struct qv2_plan qv2_plan;
 /* Validates the layer table and cuts it into tiles: one flat tile table over all
  * tensors, so that one launch covers every layer whatever its size.
  * Errors: NULL table or out -> ERR_NULL; n_tensors <= 0, numel <= 0 or > 2^36, channels
- * not dividing numel (or != 1 for per-tensor schemes), more than 2^31-1 tiles
- * or segments -> ERR_SHAPE; unknown scheme -> ERR_SCHEME; x (or qrun) not
+ * not dividing numel (or != 1 for per-tensor schemes), more than 2^31-1 segments, or more tiles
+ * than one launch can take (a sweep is one launch of at most 2^32-1 threads: 2^24-1 quantize
+ * tiles of 2048 elements over all tensors with a code buffer, i.e. just under 2^35 elements of
+ * them; 2^23-1 read tiles of 32768 elements) -> ERR_SHAPE; unknown scheme -> ERR_SCHEME; x (or qrun) not
  * 4-byte aligned -> ERR_ALIGN; x NULL -> ERR_NULL; no host memory for the tile
  * tables -> ERR_NOMEM (the host functions below that build work lists - qv2_rank,
  * qv2_rank_tensors, qv2_bops_select, qv2_regroup_for_fusion - return it too). */
-/* Tile lengths can be overridden for tuning with the environment variables QV2_TILE_ELEMS
- * (read-only sweeps) and QV2_QUANT_TILE_ELEMS (quantize sweeps), read here. */
+/* Test hooks, not part of the interface: the environment variables QV2_TILE_ELEMS (read-only
+ * sweeps) and QV2_QUANT_TILE_ELEMS (quantize sweeps), read here, override the tile lengths so that
+ * tests can force many tiles onto small tensors and tuning runs can sweep them.  The defaults are
+ * the measured best; production callers leave both unset. */
 qv2_status qv2_plan_create(const qv2_tensor* h_tensors, int32_t n_tensors, qv2_plan** out);
 void qv2_plan_destroy(qv2_plan* plan);
 

@@ -8,9 +8,9 @@ namespace {
 // pass 3 alone (Algorithm 2: CalculateSQNR / CalculateMSE on D[i] and Q[i])
 // ---------------------------------------------------------------------------
 template <int BLOCK, int V>
-__global__ __launch_bounds__(BLOCK) void k_pair_stream(const Tile* __restrict__ tiles,
+__global__ __launch_bounds__(BLOCK) void k_pair_stream(const StreamView tiles,
                                                        ErrPartial* __restrict__ parts) {
-  const Tile tl = tiles[blockIdx.x];
+  const TileRef tl = decode_tile(tiles, blockIdx.x);
   const gf_ptr a = (gf_ptr)tl.x;
   const gf_ptr b = (gf_ptr)tl.q;
   const int len = tl.len, tid = threadIdx.x;

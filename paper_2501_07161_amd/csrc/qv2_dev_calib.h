@@ -63,9 +63,9 @@ __device__ __forceinline__ void stats_body(gf4_ptr v4, gf4_ptr b4, int nvec, Sta
 // D[i] against Q[i]) from the same visit: 8 B read per element, nothing but the partial written.
 // COS: also sum x * qrun, the cross term of cos(x, qrun) (Sec. 6.1 Eq. 8).
 template <int BLOCK, int V, bool PAIR, bool COS>
-__global__ __launch_bounds__(BLOCK) void k_stats_stream(const Tile* __restrict__ tiles,
+__global__ __launch_bounds__(BLOCK) void k_stats_stream(const StreamView tiles,
                                                         typename StatRec<PAIR, COS>::type* __restrict__ parts) {
-  const Tile tl = tiles[blockIdx.x];
+  const TileRef tl = decode_tile(tiles, blockIdx.x);
   const gf_ptr p = (gf_ptr)tl.x;
   const gf_ptr b = (gf_ptr)tl.q;
   const int len = tl.len, tid = threadIdx.x;

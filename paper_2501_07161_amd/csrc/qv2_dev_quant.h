@@ -67,7 +67,7 @@ __device__ __forceinline__ void set_cross(ErrPartial5& o, double sxh, double sxq
 // RO: tiles of tensors without a code buffer (no store is compiled in; long tiles).
 template <int BLOCK, int V, bool PAIR, bool COS, bool X2 = true, bool RO = false>
 __global__ __launch_bounds__(BLOCK, (PAIR ? QV2_QUANT_WAVES_PER_EU : QV2_QUANT_PLAIN_WAVES_PER_EU)) void k_quant_stream(
-    const Tile* __restrict__ tiles, const qv2_qparams* __restrict__ params,
+    const StreamView tiles, const qv2_qparams* __restrict__ params,
     typename ErrRec<COS>::type* __restrict__ parts) {
   // Workgroups go to the 8 XCDs in turn.  The plain sweep (one read stream, one store stream)
   // runs 1.5 % faster (6 % without codes) when each XCD works through one contiguous eighth
@@ -77,7 +77,7 @@ __global__ __launch_bounds__(BLOCK, (PAIR ? QV2_QUANT_WAVES_PER_EU : QV2_QUANT_P
     const int per = gridDim.x >> 3;
     if (bt < (per << 3)) bt = (bt & 7) * per + (bt >> 3);
   }
-  const Tile tl = tiles[bt];
+  const TileRef tl = decode_tile(tiles, bt);
   const QP q = load_qp(params, tl.seg0);
   const gf_ptr p = (gf_ptr)tl.x;
   const gf_ptr b = (gf_ptr)tl.q;

@@ -14,7 +14,9 @@
 #include "qv2_internal.h"
 
 using qv2::PairTensor;
+using qv2::Run;
 using qv2::Segment;
+using qv2::StreamTable;
 using qv2::TensorInfo;
 using qv2::Tile;
 
@@ -31,6 +33,42 @@ int32_t tile_from_env(const char* name, int32_t dflt) {
   if (v > (1L << 22)) v = 1L << 22;
   return static_cast<int32_t>(v / 4 * 4);
 }
+
+// Appends the stream tiles of one tensor (nseg segments of `inner` elements, cut into tiles of T
+// elements, partial slots from part0) to a table; returns the number of tiles added.
+int64_t add_run(StreamTable& tab, const qv2_tensor& in, int32_t t, int64_t nseg, int64_t inner, int64_t T,
+                int64_t seg0, int64_t part0) {
+  const int64_t per_seg = (inner + T - 1) / T;
+  Run r{};
+  r.x = in.x; r.q = in.qrun; r.c = in.codes;
+  r.inner = inner;
+  r.tile0 = static_cast<int32_t>(tab.n_tiles);
+  r.tiles_per_seg = static_cast<int32_t>(per_seg);
+  r.seg0 = static_cast<int32_t>(seg0);
+  r.part0 = static_cast<int32_t>(part0);
+  r.tile_len = static_cast<int32_t>(T);
+  r.tensor = t;
+  tab.runs.push_back(r);
+  tab.n_tiles += nseg * per_seg;
+  return nseg * per_seg;
+}
+
+// The lookup table from blocks of 2^shift tile indices to runs.
+void finish_table(StreamTable& tab) {
+  tab.shift = 0;
+  while ((tab.n_tiles >> tab.shift) + 1 > qv2::kCoarseMax) ++tab.shift;
+  const int64_t n = (tab.n_tiles >> tab.shift) + 1;
+  tab.coarse.assign(static_cast<size_t>(n), 0);
+  size_t r = 0;
+  for (int64_t b = 0; b < n; ++b) {
+    const int64_t k = b << tab.shift;
+    while (r + 1 < tab.runs.size() && tab.runs[r + 1].tile0 <= k) ++r;
+    tab.coarse[static_cast<size_t>(b)] = static_cast<int32_t>(r);
+  }
+}
+
+// A launch of n workgroups of `block` threads must stay within 2^32 - 1 threads in all.
+bool launchable(int64_t n, int64_t block) { return n * block <= int64_t{0xFFFFFFFF}; }
 
 // Runs a host entry point's body; an allocation failure inside it becomes a status.
 template <class F>
@@ -161,22 +199,17 @@ static qv2_status plan_create(const qv2_tensor* h_tensors, int32_t n_tensors, qv
       ft.part0 = static_cast<int32_t>(ep); ft.nparts = static_cast<int32_t>(nseg * n_quant);
       st.part0 = static_cast<int32_t>(sp); st.nparts = static_cast<int32_t>(nseg * n_read);
       if (in.qrun) st.n = in.numel;
+      // the tensor's tiles: segment after segment, each segment's tiles in element order, one
+      // partial slot per tile in that same order
+      add_run(p->read_tiles, in, t, nseg, inner, TR, seg0, sp);
+      add_run(in.codes ? p->quant_tiles : p->quant_ro_tiles, in, t, nseg, inner, TQt, seg0, ep);
       for (int64_t s = 0; s < nseg; ++s) {
         Segment sg{};
         sg.n = inner; sg.scheme = in.scheme;
         sg.sp0 = static_cast<int32_t>(sp); sg.snp = static_cast<int32_t>(n_read);
         sg.ep0 = static_cast<int32_t>(ep); sg.enp = static_cast<int32_t>(n_quant);
         p->segments.push_back(sg);
-        for (int64_t k = 0; k < n_read; ++k) {
-          Tile tl = make_tile(in, t, s * inner + k * TR, std::min<int64_t>(TR, inner - k * TR));
-          tl.part0 = static_cast<int32_t>(sp++); tl.seg0 = static_cast<int32_t>(seg0 + s);
-          p->read_tiles.push_back(tl);
-        }
-        for (int64_t k = 0; k < n_quant; ++k) {
-          Tile tl = make_tile(in, t, s * inner + k * TQt, std::min<int64_t>(TQt, inner - k * TQt));
-          tl.part0 = static_cast<int32_t>(ep++); tl.seg0 = static_cast<int32_t>(seg0 + s);
-          (in.codes ? p->quant_tiles : p->quant_ro_tiles).push_back(tl);
-        }
+        sp += n_read; ep += n_quant;
       }
     }
     if (in.qrun) ft.n = in.numel; else ft = PairTensor{};
@@ -189,15 +222,19 @@ static qv2_status plan_create(const qv2_tensor* h_tensors, int32_t n_tensors, qv
       const int64_t nt = (in.numel + TR - 1) / TR;
       if (pp + nt > kMax) { err = QV2_ERR_SHAPE; break; }
       pt.n = in.numel; pt.part0 = static_cast<int32_t>(pp); pt.nparts = static_cast<int32_t>(nt);
-      for (int64_t k = 0; k < nt; ++k) {
-        Tile tl = make_tile(in, t, k * TR, std::min<int64_t>(TR, in.numel - k * TR));
-        tl.part0 = static_cast<int32_t>(pp++);
-        p->pair_tiles.push_back(tl);
-      }
+      pp += add_run(p->pair_tiles, in, t, 1, in.numel, TR, seg0, pp);     // the whole tensor as one range
     }
     p->pair_tensors.push_back(pt);
   }
   if (err != QV2_OK) return err;
+  // every sweep is one launch: its tile count times its workgroup size has to fit a launch
+  if (!launchable(p->read_tiles.n_tiles, qv2::kBlockRead) || !launchable(p->pair_tiles.n_tiles, qv2::kBlockRead) ||
+      !launchable(p->quant_ro_tiles.n_tiles, qv2::kBlockRead) ||
+      !launchable(p->quant_tiles.n_tiles, qv2::kBlockQuant) ||
+      !launchable(static_cast<int64_t>(std::max(p->row_tiles.size(), p->reg_tiles.size())), qv2::kBlockRows))
+    return QV2_ERR_SHAPE;
+  finish_table(p->read_tiles); finish_table(p->quant_tiles);
+  finish_table(p->quant_ro_tiles); finish_table(p->pair_tiles);
 
   // histogram pass: about kHistChunks long chunks over all tensors
   {
@@ -255,14 +292,14 @@ int64_t qv2_plan_segment_begin(const qv2_plan* plan, int32_t t) {
   return plan->info[t].seg0;
 }
 int64_t qv2_plan_num_tiles(const qv2_plan* plan) {
-  return plan ? static_cast<int64_t>(plan->read_tiles.size() + plan->row_tiles.size() + plan->reg_tiles.size()) : 0;
+  return plan ? plan->read_tiles.n_tiles + static_cast<int64_t>(plan->row_tiles.size() + plan->reg_tiles.size()) : 0;
 }
 int64_t qv2_plan_num_quant_tiles(const qv2_plan* plan) {
-  return plan ? static_cast<int64_t>(plan->quant_tiles.size() + plan->quant_ro_tiles.size() +
-                                     plan->row_tiles.size() + plan->reg_tiles.size()) : 0;
+  return plan ? plan->quant_tiles.n_tiles + plan->quant_ro_tiles.n_tiles +
+                    static_cast<int64_t>(plan->row_tiles.size() + plan->reg_tiles.size()) : 0;
 }
 int64_t qv2_plan_num_pair_tiles(const qv2_plan* plan) {
-  return plan ? static_cast<int64_t>(plan->pair_tiles.size()) : 0;
+  return plan ? plan->pair_tiles.n_tiles : 0;
 }
 size_t qv2_workspace_bytes(const qv2_plan* plan) { return plan ? plan->workspace_bytes : 0; }
 

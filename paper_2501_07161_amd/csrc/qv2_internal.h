@@ -63,13 +63,20 @@ constexpr int kHistMaxBins = 4096;
 // 1024-thread workgroup instead of one wavefront.
 constexpr int kFoldWaveMax = 128;
 
-// A tile is a contiguous element range of one tensor, addressed absolutely so that a
-// workgroup needs one 64-byte scalar load before it can issue its data loads.
-//  rows == 0 : stream tile, part of ONE segment (seg0); yields one partial (part0).
+// Host code and kernels share the tile addressing below.
+#if defined(__HIPCC__)
+#define QV2_HD __host__ __device__
+#else
+#define QV2_HD
+#endif
+
+// A row-group tile (and a histogram chunk) is a contiguous element range of one tensor,
+// addressed absolutely: a workgroup needs one 64-byte scalar load before it can issue its data loads.
 //  rows  > 0 : row-group tile, `rows` whole segments of `inner` elements each,
 //              starting at segment seg0; yields `rows` partials from part0.  Two forms: staged
 //              in LDS (any alignment, any row length up to kRowGroupCap), or held in registers
 //              (`lanes` > 0: rows of a multiple of 4 elements on 16-byte boundaries).
+//  rows == 0 : a histogram chunk (part0 = chunk index), or a stream tile decoded from a Run.
 struct Tile {                  // 64 B
   const float* x;              // first element of the tile
   const float* q;              // same position in the quantized-run tensor, or null
@@ -84,6 +91,91 @@ struct Tile {                  // 64 B
   int32_t _pad[3];
 };
 static_assert(sizeof(Tile) == 64, "Tile must stay one 64-byte record");
+
+// Stream tiles (the sweeps over long segments) are not stored at all: a tensor's tiles form a
+// Run, and workgroup k of a launch finds its tile by arithmetic.  A run's segments all have
+// `inner` elements and are cut into `tiles_per_seg` tiles of `tile_len` elements (the last one of
+// a segment shorter); tile j of the run belongs to segment seg0 + j / tiles_per_seg and owns
+// partial slot part0 + j.  The tables a kernel touches before its data loads are therefore a few
+// KB that stay in the scalar cache, instead of one 64-byte record per tile streamed from memory
+// (85 MB for the 1.3 M quantize tiles of the ResNet-50 batch-256 activations).
+struct Run {                   // 64 B, one per tensor of a stream-tile table
+  const float* x;              // first element of the tensor
+  const float* q;              // ... of its quantized-run partner, or null
+  int8_t* c;                   // ... of its code buffer, or null
+  int64_t inner;               // elements per segment
+  int32_t tile0;               // index of the run's first tile in the launch
+  int32_t tiles_per_seg;
+  int32_t seg0;                // first segment of the tensor
+  int32_t part0;               // partial slot of the run's first tile
+  int32_t tile_len;
+  int32_t tensor;
+  int32_t _pad[2];
+};
+static_assert(sizeof(Run) == 64, "Run must stay one 64-byte record");
+
+// What a kernel is handed: the runs in launch order, and for every block of 2^shift consecutive
+// tile indices the run that holds the block's first tile (so the search is one lookup and, where
+// a block spans several small tensors, a short walk).
+struct StreamView {
+  const Run* runs;
+  const int32_t* coarse;
+  int32_t n_runs;
+  int32_t shift;
+};
+
+struct TileRef {               // one decoded stream tile
+  const float* x;
+  const float* q;
+  int8_t* c;
+  int32_t len, part0, seg0, tensor;
+};
+
+QV2_HD inline TileRef decode_tile(const StreamView& v, int32_t k) {
+  int32_t r = v.coarse[k >> v.shift];
+  while (r + 1 < v.n_runs && v.runs[r + 1].tile0 <= k) ++r;
+  const Run& rn = v.runs[r];
+  const int32_t j = k - rn.tile0;
+  const int32_t s = j / rn.tiles_per_seg, i = j - s * rn.tiles_per_seg;
+  const int64_t in_seg = static_cast<int64_t>(i) * rn.tile_len;
+  const int64_t off = static_cast<int64_t>(s) * rn.inner + in_seg;
+  const int64_t left = rn.inner - in_seg;
+  TileRef t;
+  t.x = rn.x + off;
+  t.q = rn.q ? rn.q + off : nullptr;
+  t.c = rn.c ? rn.c + off : nullptr;
+  t.len = static_cast<int32_t>(left < rn.tile_len ? left : rn.tile_len);
+  t.part0 = rn.part0 + j;
+  t.seg0 = rn.seg0 + s;
+  t.tensor = rn.tensor;
+  return t;
+}
+
+// Host side of a stream-tile table.
+struct StreamTable {
+  std::vector<Run> runs;
+  std::vector<int32_t> coarse;
+  int32_t shift = 0;
+  int64_t n_tiles = 0;
+  StreamView view() const {
+    return StreamView{runs.data(), coarse.data(), static_cast<int32_t>(runs.size()), shift};
+  }
+  // all tiles, decoded the way the kernels decode them (tests, diagnostics)
+  std::vector<Tile> expand() const {
+    std::vector<Tile> out;
+    out.reserve(static_cast<size_t>(n_tiles));
+    const StreamView v = view();
+    for (int64_t k = 0; k < n_tiles; ++k) {
+      const TileRef r = decode_tile(v, static_cast<int32_t>(k));
+      Tile t{};
+      t.x = r.x; t.q = r.q; t.c = r.c; t.len = r.len; t.part0 = r.part0; t.seg0 = r.seg0; t.tensor = r.tensor;
+      out.push_back(t);
+    }
+    return out;
+  }
+};
+// Most entries a coarse table may have (it is sized to the launch: 2^shift tiles per entry).
+constexpr int64_t kCoarseMax = 2048;
 
 // Partial slots come in two numberings: `sp` for the calibration pass (read tiles) and
 // `ep` for the quantize passes (quantize tiles).  Row-group partials have the same index
@@ -126,13 +218,13 @@ struct ErrPartial5 { double sx2, se2, sd2, sxh, sxq; }; // quantize pass with co
 
 struct qv2_plan {
   std::vector<qv2::TensorInfo> info;
-  std::vector<qv2::Tile> read_tiles;     // calibration: stream tiles (read size)
-  std::vector<qv2::Tile> quant_tiles;    // quantize passes: stream tiles (quantize size)
-  std::vector<qv2::Tile> quant_ro_tiles; // ... of tensors without a code buffer: the sweep only reads
+  qv2::StreamTable read_tiles;           // calibration: stream tiles (read size)
+  qv2::StreamTable quant_tiles;          // quantize passes: stream tiles (quantize size)
+  qv2::StreamTable quant_ro_tiles;       // ... of tensors without a code buffer: the sweep only reads
                                          // them, so they are cut like the read-only passes' tiles
   std::vector<qv2::Tile> row_tiles;      // row-group tiles staged in LDS, used by both
   std::vector<qv2::Tile> reg_tiles;      // row-group tiles held in registers, used by both
-  std::vector<qv2::Tile> pair_tiles;     // pair pass: stream tiles over tensors with qrun
+  qv2::StreamTable pair_tiles;           // pair pass: stream tiles over tensors with qrun
   std::vector<qv2::Tile> hist_tiles;     // histogram pass: long chunks (part0 = chunk index)
   std::vector<qv2::HistTensor> hist_tensors;
   std::vector<qv2::Segment> segments;
@@ -154,12 +246,12 @@ struct qv2_plan {
   // device copy (made by the first device call, on the device current then)
   void* d_blob = nullptr;
   int device = -1;               // the device that holds d_blob (current at the first device call)
-  qv2::Tile* d_read_tiles = nullptr;
-  qv2::Tile* d_quant_tiles = nullptr;
-  qv2::Tile* d_quant_ro_tiles = nullptr;
+  qv2::StreamView d_read_tiles = {};     // device views of the four stream-tile tables
+  qv2::StreamView d_quant_tiles = {};
+  qv2::StreamView d_quant_ro_tiles = {};
+  qv2::StreamView d_pair_tiles = {};
   qv2::Tile* d_row_tiles = nullptr;
   qv2::Tile* d_reg_tiles = nullptr;
-  qv2::Tile* d_pair_tiles = nullptr;
   qv2::Tile* d_hist_tiles = nullptr;
   qv2::HistTensor* d_hist_tensors = nullptr;
   qv2::Segment* d_segments = nullptr;

@@ -24,6 +24,7 @@
 // unit); this file holds the launches and the extern "C" device entry points.
 #include <hip/hip_runtime.h>
 
+#include <cstring>
 #include <mutex>
 
 #include "qv2_dev_common.h"   // loads / stores, reductions, the quantizer
@@ -67,75 +68,105 @@ void* scratch_on_device(int dev) {
   return g_scratch_ptr[dev];
 }
 
-// Where every table of the plan sits in its device blob (256-byte aligned sections).
-struct BlobLayout {
-  size_t read, quant, row, pair, seg, pt, ft, bs, be, bp, bf, ht, hten, st, bst, reg, qro, total;
+// The plan's device blob: every table in one allocation, 256-byte aligned sections.  The host
+// image is assembled first, so that one copy brings it over.
+struct BlobBuilder {
+  std::vector<char> image;
+  BlobBuilder() : image(256, 0) {}
+  template <class T>
+  size_t put(const std::vector<T>& v) {
+    const size_t at = image.size();
+    image.resize(at + align256(v.size() * sizeof(T)), 0);
+    if (!v.empty()) std::memcpy(image.data() + at, v.data(), v.size() * sizeof(T));
+    return at;
+  }
 };
 
-BlobLayout blob_layout(const qv2_plan* p) {
+struct BlobLayout {
+  size_t run[4], coarse[4], row, reg, seg, pt, ft, st, bs, be, bp, bf, bst, ht, hten;
+};
+
+const StreamTable* stream_tables(const qv2_plan* p, int i) {
+  const StreamTable* t[4] = {&p->read_tiles, &p->quant_tiles, &p->quant_ro_tiles, &p->pair_tiles};
+  return t[i];
+}
+
+BlobLayout build_blob(const qv2_plan* p, BlobBuilder& b) {
   BlobLayout o{};
-  size_t total = 256;
-  auto reserve = [&](size_t n) { const size_t at = total; total += align256(n); return at; };
-  o.read = reserve(bytes_of(p->read_tiles)); o.quant = reserve(bytes_of(p->quant_tiles));
-  o.row = reserve(bytes_of(p->row_tiles)); o.pair = reserve(bytes_of(p->pair_tiles));
-  o.seg = reserve(bytes_of(p->segments)); o.pt = reserve(bytes_of(p->pair_tensors));
-  o.ft = reserve(bytes_of(p->fused_pair_tensors));
-  o.bs = reserve(bytes_of(p->big_stat_segments)); o.be = reserve(bytes_of(p->big_err_segments));
-  o.bp = reserve(bytes_of(p->big_pair_tensors)); o.bf = reserve(bytes_of(p->big_fused_pair_tensors));
-  o.ht = reserve(bytes_of(p->hist_tiles)); o.hten = reserve(bytes_of(p->hist_tensors));
-  o.st = reserve(bytes_of(p->stat_pair_tensors)); o.bst = reserve(bytes_of(p->big_stat_pair_tensors));
-  o.reg = reserve(bytes_of(p->reg_tiles)); o.qro = reserve(bytes_of(p->quant_ro_tiles));
-  o.total = total;
+  for (int i = 0; i < 4; ++i) {
+    o.run[i] = b.put(stream_tables(p, i)->runs);
+    o.coarse[i] = b.put(stream_tables(p, i)->coarse);
+  }
+  o.row = b.put(p->row_tiles); o.reg = b.put(p->reg_tiles);
+  o.seg = b.put(p->segments); o.pt = b.put(p->pair_tensors); o.ft = b.put(p->fused_pair_tensors);
+  o.st = b.put(p->stat_pair_tensors);
+  o.bs = b.put(p->big_stat_segments); o.be = b.put(p->big_err_segments);
+  o.bp = b.put(p->big_pair_tensors); o.bf = b.put(p->big_fused_pair_tensors);
+  o.bst = b.put(p->big_stat_pair_tensors);
+  o.ht = b.put(p->hist_tiles); o.hten = b.put(p->hist_tensors);
   return o;
 }
 
-// Puts the plan's tables on the current device: one allocation, the tables copied section by
-// section on `s`, which is then waited for (the host vectors are pageable, so the copies are
-// not asynchronous anyway).  A plan that is already on this device is left alone.
+size_t blob_bytes(const qv2_plan* p) {
+  auto sec = [](size_t n) { return align256(n); };
+  size_t total = 256;
+  for (int i = 0; i < 4; ++i)
+    total += sec(bytes_of(stream_tables(p, i)->runs)) + sec(bytes_of(stream_tables(p, i)->coarse));
+  total += sec(bytes_of(p->row_tiles)) + sec(bytes_of(p->reg_tiles)) + sec(bytes_of(p->segments)) +
+           sec(bytes_of(p->pair_tensors)) + sec(bytes_of(p->fused_pair_tensors)) +
+           sec(bytes_of(p->stat_pair_tensors)) + sec(bytes_of(p->big_stat_segments)) +
+           sec(bytes_of(p->big_err_segments)) + sec(bytes_of(p->big_pair_tensors)) +
+           sec(bytes_of(p->big_fused_pair_tensors)) + sec(bytes_of(p->big_stat_pair_tensors)) +
+           sec(bytes_of(p->hist_tiles)) + sec(bytes_of(p->hist_tensors));
+  return total;
+}
+
+// Puts the plan's tables on the current device: one allocation and one copy on `s`, which is
+// then waited for.  A plan that is already on this device is left alone.
 qv2_status upload(qv2_plan* p, hipStream_t s) {
   int dev = -1;
   if (hipGetDevice(&dev) != hipSuccess) { (void)hipGetLastError(); return QV2_ERR_HIP; }
   // the tables live on one device: a later call with another device current would hand its
   // kernels pointers they cannot use
   if (p->d_blob) return dev == p->device ? QV2_OK : QV2_ERR_HIP;
-  const BlobLayout o = blob_layout(p);
+  BlobBuilder b;
+  BlobLayout o;
+  try {
+    o = build_blob(p, b);
+  } catch (...) {
+    return QV2_ERR_NOMEM;
+  }
   char* blob = nullptr;
-  if (hipMalloc(reinterpret_cast<void**>(&blob), o.total) != hipSuccess) {
+  if (hipMalloc(reinterpret_cast<void**>(&blob), b.image.size()) != hipSuccess) {
     (void)hipGetLastError();
     return QV2_ERR_HIP;
   }
-  bool ok = true;
-  auto put = [&](size_t off, const void* h, size_t n) {
-    if (n && hipMemcpyAsync(blob + off, h, n, hipMemcpyHostToDevice, s) != hipSuccess) ok = false;
-    return static_cast<void*>(blob + off);
-  };
-  p->d_read_tiles = static_cast<Tile*>(put(o.read, p->read_tiles.data(), bytes_of(p->read_tiles)));
-  p->d_quant_tiles = static_cast<Tile*>(put(o.quant, p->quant_tiles.data(), bytes_of(p->quant_tiles)));
-  p->d_row_tiles = static_cast<Tile*>(put(o.row, p->row_tiles.data(), bytes_of(p->row_tiles)));
-  p->d_pair_tiles = static_cast<Tile*>(put(o.pair, p->pair_tiles.data(), bytes_of(p->pair_tiles)));
-  p->d_segments = static_cast<Segment*>(put(o.seg, p->segments.data(), bytes_of(p->segments)));
-  p->d_pair_tensors = static_cast<PairTensor*>(put(o.pt, p->pair_tensors.data(), bytes_of(p->pair_tensors)));
-  p->d_fused_pair_tensors =
-      static_cast<PairTensor*>(put(o.ft, p->fused_pair_tensors.data(), bytes_of(p->fused_pair_tensors)));
-  p->d_big_stat_segments =
-      static_cast<int32_t*>(put(o.bs, p->big_stat_segments.data(), bytes_of(p->big_stat_segments)));
-  p->d_big_err_segments =
-      static_cast<int32_t*>(put(o.be, p->big_err_segments.data(), bytes_of(p->big_err_segments)));
-  p->d_big_pair_tensors =
-      static_cast<int32_t*>(put(o.bp, p->big_pair_tensors.data(), bytes_of(p->big_pair_tensors)));
-  p->d_big_fused_pair_tensors = static_cast<int32_t*>(
-      put(o.bf, p->big_fused_pair_tensors.data(), bytes_of(p->big_fused_pair_tensors)));
-  p->d_hist_tiles = static_cast<Tile*>(put(o.ht, p->hist_tiles.data(), bytes_of(p->hist_tiles)));
-  p->d_hist_tensors =
-      static_cast<HistTensor*>(put(o.hten, p->hist_tensors.data(), bytes_of(p->hist_tensors)));
-  p->d_reg_tiles = static_cast<Tile*>(put(o.reg, p->reg_tiles.data(), bytes_of(p->reg_tiles)));
-  p->d_quant_ro_tiles = static_cast<Tile*>(put(o.qro, p->quant_ro_tiles.data(), bytes_of(p->quant_ro_tiles)));
-  p->d_stat_pair_tensors =
-      static_cast<PairTensor*>(put(o.st, p->stat_pair_tensors.data(), bytes_of(p->stat_pair_tensors)));
-  p->d_big_stat_pair_tensors = static_cast<int32_t*>(
-      put(o.bst, p->big_stat_pair_tensors.data(), bytes_of(p->big_stat_pair_tensors)));
-  if (hipStreamSynchronize(s) != hipSuccess) ok = false;
-  if (!ok) { (void)hipGetLastError(); (void)hipFree(blob); return QV2_ERR_HIP; }
+  if (hipMemcpyAsync(blob, b.image.data(), b.image.size(), hipMemcpyHostToDevice, s) != hipSuccess ||
+      hipStreamSynchronize(s) != hipSuccess) {
+    (void)hipGetLastError();
+    (void)hipFree(blob);
+    return QV2_ERR_HIP;
+  }
+  StreamView* views[4] = {&p->d_read_tiles, &p->d_quant_tiles, &p->d_quant_ro_tiles, &p->d_pair_tiles};
+  for (int i = 0; i < 4; ++i) {
+    const StreamTable* t = stream_tables(p, i);
+    *views[i] = StreamView{reinterpret_cast<const Run*>(blob + o.run[i]),
+                           reinterpret_cast<const int32_t*>(blob + o.coarse[i]),
+                           static_cast<int32_t>(t->runs.size()), t->shift};
+  }
+  p->d_row_tiles = reinterpret_cast<Tile*>(blob + o.row);
+  p->d_reg_tiles = reinterpret_cast<Tile*>(blob + o.reg);
+  p->d_segments = reinterpret_cast<Segment*>(blob + o.seg);
+  p->d_pair_tensors = reinterpret_cast<PairTensor*>(blob + o.pt);
+  p->d_fused_pair_tensors = reinterpret_cast<PairTensor*>(blob + o.ft);
+  p->d_stat_pair_tensors = reinterpret_cast<PairTensor*>(blob + o.st);
+  p->d_big_stat_segments = reinterpret_cast<int32_t*>(blob + o.bs);
+  p->d_big_err_segments = reinterpret_cast<int32_t*>(blob + o.be);
+  p->d_big_pair_tensors = reinterpret_cast<int32_t*>(blob + o.bp);
+  p->d_big_fused_pair_tensors = reinterpret_cast<int32_t*>(blob + o.bf);
+  p->d_big_stat_pair_tensors = reinterpret_cast<int32_t*>(blob + o.bst);
+  p->d_hist_tiles = reinterpret_cast<Tile*>(blob + o.ht);
+  p->d_hist_tensors = reinterpret_cast<HistTensor*>(blob + o.hten);
   p->d_blob = blob;
   p->device = dev;
   (void)scratch_on_device(dev);      // set-up time: the entry point that allocates nothing finds it ready
@@ -217,8 +248,8 @@ void launch_quant(qv2_plan* plan, const qv2_qparams* d_params, qv2_sums* d_sums,
                   bool pair_in_stats = false) {
   typedef typename ErrRec<COS>::type P;
   const bool calib_rows = d_params_out != nullptr;
-  const int n_stream = static_cast<int>(plan->quant_tiles.size());
-  const int n_ro = static_cast<int>(plan->quant_ro_tiles.size());
+  const int n_stream = static_cast<int>(plan->quant_tiles.n_tiles);
+  const int n_ro = static_cast<int>(plan->quant_ro_tiles.n_tiles);
   const int n_rows = static_cast<int>(plan->row_tiles.size());
   if (n_stream + n_ro > 0) {
     // pair_in_stats: the calibration sweep already compared the stream tensors with their
@@ -268,7 +299,7 @@ void launch_stats(qv2_plan* plan, qv2_qparams* d_params, qv2_sums* d_sums,
                   double* d_pair_xq, hipStream_t s) {
   typedef typename StatRec<PAIR, COS>::type REC;
   if (PAIR) with_rows = false;      // the row kernel of this pass writes 24-byte records: not in a PAIR sweep
-  const int n_stream = static_cast<int>(plan->read_tiles.size());
+  const int n_stream = static_cast<int>(plan->read_tiles.n_tiles);
   const int n_rows = static_cast<int>(plan->row_tiles.size());
   if (n_stream > 0) {
     Timed timed(plan, PAIR ? QV2_K_STATSPAIR_STREAM : QV2_K_STATS_STREAM, s);
@@ -345,7 +376,7 @@ qv2_status qv2_plan_upload(qv2_plan* plan, void* hip_stream) {
   return upload(plan, static_cast<hipStream_t>(hip_stream));
 }
 
-size_t qv2_plan_device_bytes(const qv2_plan* plan) { return plan ? blob_layout(plan).total : 0; }
+size_t qv2_plan_device_bytes(const qv2_plan* plan) { return plan ? blob_bytes(plan) : 0; }
 
 qv2_status qv2_plan_set_timing(qv2_plan* plan, int32_t enable) {
   if (!plan) return QV2_ERR_NULL;
@@ -421,7 +452,7 @@ qv2_status qv2_pair_metrics(qv2_plan* plan, qv2_pair_sums* d_pair_sums, void* d_
   if ((st = ensure_uploaded(plan)) != QV2_OK) return st;
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   ErrPartial* parts = static_cast<ErrPartial*>(d_workspace);
-  const int n_tiles = static_cast<int>(plan->pair_tiles.size());
+  const int n_tiles = static_cast<int>(plan->pair_tiles.n_tiles);
   const int nt = static_cast<int>(plan->pair_tensors.size());
   if (n_tiles > 0) {
     Timed timed(plan, QV2_K_PAIR_STREAM, s);

@@ -1,8 +1,9 @@
 // Host-only checks of the plan builder and the host functions of the qv2 C ABI, meant to be
 // built with -fsanitize=address,undefined (tests/test_host_sanitize.py does that) and linked
 // with csrc/qv2_host.cpp alone: no GPU, no HIP.  It builds many layer tables and verifies the
-// invariants the kernels rely on (every element covered exactly once by every tile table, partial
-// slots unique and inside the workspace, fold lists complete), then drives finalize, rank, BOPs,
+// invariants the kernels rely on (every element covered exactly once by every tile table - the
+// stream tiles decoded from their runs by the very function the kernels use -, partial slots
+// unique and inside the workspace, fold lists complete), then drives finalize, rank, BOPs,
 // KL and regrouping over random and hostile inputs.  Prints "host checks ok" and exits 0.
 #include <algorithm>
 #include <cmath>
@@ -61,10 +62,37 @@ void check_cover(const std::vector<const std::vector<Tile>*>& tables, const qv2_
   CHECK(at == in.x + in.numel);
 }
 
+// A stream-tile table as the kernels see it: workgroup k decodes tile k from the runs.
+std::vector<Tile> decoded(const qv2::StreamTable& tab, int64_t block) {
+  CHECK(tab.n_tiles >= 0 && tab.n_tiles * block <= int64_t{0xFFFFFFFF});        // one launch
+  CHECK(tab.shift >= 0 && static_cast<int64_t>(tab.coarse.size()) == (tab.n_tiles >> tab.shift) + 1);
+  CHECK(static_cast<int64_t>(tab.coarse.size()) <= qv2::kCoarseMax);
+  int64_t at = 0;
+  for (size_t r = 0; r < tab.runs.size(); ++r) {
+    const qv2::Run& rn = tab.runs[r];
+    CHECK(rn.tile0 == at && rn.tiles_per_seg > 0 && rn.tile_len > 0 && rn.inner > 0);
+    CHECK(rn.tiles_per_seg == (rn.inner + rn.tile_len - 1) / rn.tile_len);
+    at += r + 1 < tab.runs.size() ? tab.runs[r + 1].tile0 - rn.tile0 : tab.n_tiles - rn.tile0;
+    CHECK((at - rn.tile0) % rn.tiles_per_seg == 0 && at > rn.tile0);
+  }
+  CHECK(at == tab.n_tiles);
+  for (size_t b = 0; b < tab.coarse.size() && !tab.runs.empty(); ++b) {
+    // the walk from the coarse entry must start at or before the right run
+    const int32_t r = tab.coarse[b];
+    CHECK(r >= 0 && r < static_cast<int32_t>(tab.runs.size()));
+    CHECK(tab.runs[r].tile0 <= static_cast<int64_t>(b) << tab.shift || r == 0);
+  }
+  return tab.expand();
+}
+
 void check_plan(const std::vector<qv2_tensor>& rows) {
   qv2_plan* p = nullptr;
   CHECK(qv2_plan_create(rows.data(), static_cast<int32_t>(rows.size()), &p) == QV2_OK);
   CHECK(p != nullptr);
+  const std::vector<Tile> read_tiles = decoded(p->read_tiles, qv2::kBlockRead);
+  const std::vector<Tile> quant_tiles = decoded(p->quant_tiles, qv2::kBlockQuant);
+  const std::vector<Tile> quant_ro_tiles = decoded(p->quant_ro_tiles, qv2::kBlockRead);
+  const std::vector<Tile> pair_tiles = decoded(p->pair_tiles, qv2::kBlockRead);
   const int32_t nt = static_cast<int32_t>(rows.size());
   CHECK(qv2_plan_num_tensors(p) == nt);
   CHECK(static_cast<int32_t>(p->info.size()) == nt);
@@ -84,12 +112,12 @@ void check_plan(const std::vector<qv2_tensor>& rows) {
       CHECK(p->segments[nseg + k].scheme == in.scheme);
     }
     nseg += s;
-    check_cover({&p->read_tiles, &p->row_tiles, &p->reg_tiles}, in, t, true);
-    check_cover({&p->quant_tiles, &p->quant_ro_tiles, &p->row_tiles, &p->reg_tiles}, in, t, true);
+    check_cover({&read_tiles, &p->row_tiles, &p->reg_tiles}, in, t, true);
+    check_cover({&quant_tiles, &quant_ro_tiles, &p->row_tiles, &p->reg_tiles}, in, t, true);
     check_cover({&p->hist_tiles}, in, t, true);
-    check_cover({&p->pair_tiles}, in, t, in.qrun != nullptr);
+    check_cover({&pair_tiles}, in, t, in.qrun != nullptr);
     if (!in.qrun) {
-      for (const Tile& tl : p->pair_tiles) CHECK(tl.tensor != t);
+      for (const Tile& tl : pair_tiles) CHECK(tl.tensor != t);
       CHECK(p->pair_tensors[t].n == 0 && p->fused_pair_tensors[t].n == 0);
     } else {
       CHECK(p->pair_tensors[t].n == in.numel && p->fused_pair_tensors[t].n == in.numel);
@@ -98,10 +126,10 @@ void check_plan(const std::vector<qv2_tensor>& rows) {
   CHECK(qv2_plan_num_segments(p) == nseg);
   CHECK(static_cast<int64_t>(p->segments.size()) == nseg);
   CHECK(qv2_plan_num_tiles(p) ==
-        static_cast<int64_t>(p->read_tiles.size() + p->row_tiles.size() + p->reg_tiles.size()));
+        static_cast<int64_t>(read_tiles.size() + p->row_tiles.size() + p->reg_tiles.size()));
   CHECK(qv2_plan_num_quant_tiles(p) ==
-        static_cast<int64_t>(p->quant_tiles.size() + p->quant_ro_tiles.size() + p->row_tiles.size() + p->reg_tiles.size()));
-  CHECK(qv2_plan_num_pair_tiles(p) == static_cast<int64_t>(p->pair_tiles.size()));
+        static_cast<int64_t>(quant_tiles.size() + quant_ro_tiles.size() + p->row_tiles.size() + p->reg_tiles.size()));
+  CHECK(qv2_plan_num_pair_tiles(p) == static_cast<int64_t>(pair_tiles.size()));
 
   // partial slots: every slot of a numbering is written by exactly one (tile, row), lies in
   // its segment's range and inside the workspace
@@ -136,9 +164,9 @@ void check_plan(const std::vector<qv2_tensor>& rows) {
       }
     }
   };
-  for (const Tile& tl : p->read_tiles) { CHECK(tl.rows == 0 && tl.len <= p->read_tile); mark(tl, true, false); }
-  for (const Tile& tl : p->quant_tiles) { CHECK(tl.rows == 0 && tl.len <= p->quant_tile && tl.c); mark(tl, false, true); }
-  for (const Tile& tl : p->quant_ro_tiles) { CHECK(tl.rows == 0 && tl.len <= p->read_tile && !tl.c); mark(tl, false, true); }
+  for (const Tile& tl : read_tiles) { CHECK(tl.rows == 0 && tl.len <= p->read_tile); mark(tl, true, false); }
+  for (const Tile& tl : quant_tiles) { CHECK(tl.rows == 0 && tl.len <= p->quant_tile && tl.c); mark(tl, false, true); }
+  for (const Tile& tl : quant_ro_tiles) { CHECK(tl.rows == 0 && tl.len <= p->read_tile && !tl.c); mark(tl, false, true); }
   for (const Tile& tl : p->row_tiles) { CHECK(tl.rows > 0 && tl.lanes == 0); mark(tl, true, true); }
   for (const Tile& tl : p->reg_tiles) {
     // register form: whole vectors on 16-byte boundaries, a row fits its lanes, the rows fit the workgroup
@@ -173,9 +201,9 @@ void check_plan(const std::vector<qv2_tensor>& rows) {
       CHECK(ft.part0 == lo && ft.nparts == cnt);
     }
   }
-  CHECK(static_cast<int64_t>(p->pair_tiles.size()) == pp);
+  CHECK(static_cast<int64_t>(pair_tiles.size()) == pp);
   CHECK(static_cast<size_t>(pp) * sizeof(qv2::ErrPartial) <= ws);
-  for (size_t i = 0; i < p->pair_tiles.size(); ++i) CHECK(p->pair_tiles[i].part0 == static_cast<int32_t>(i));
+  for (size_t i = 0; i < pair_tiles.size(); ++i) CHECK(pair_tiles[i].part0 == static_cast<int32_t>(i));
 
   // fold lists
   std::vector<int32_t> bs, be, bp, bf;
@@ -322,6 +350,17 @@ void plans() {
   CHECK(qv2_plan_create(&bad, 1, &p) == QV2_ERR_SHAPE);
   bad.scheme = QV2_SYM_CHANNEL; bad.channels = 1; bad.codes = reinterpret_cast<int8_t*>(0x2000);
   CHECK(qv2_plan_create(&bad, 1, &p) == QV2_ERR_SHAPE);
+  // a sweep is one launch of at most 2^32 - 1 threads: 2^24 quantize tiles of 256 threads are one
+  // too many, the same tensor without a code buffer (long read-only tiles) fits
+  bad = r; bad.numel = int64_t{1} << 35; bad.codes = reinterpret_cast<int8_t*>(0x2000);
+  CHECK(qv2_plan_create(&bad, 1, &p) == QV2_ERR_SHAPE && p == nullptr);
+  bad.numel -= qv2::kDefaultQuantTile;
+  CHECK(qv2_plan_create(&bad, 1, &p) == QV2_OK && p != nullptr);
+  CHECK(qv2_plan_num_quant_tiles(p) == (int64_t{1} << 24) - 1);
+  delete p; p = nullptr;
+  bad.numel = int64_t{1} << 35; bad.codes = nullptr;
+  CHECK(qv2_plan_create(&bad, 1, &p) == QV2_OK && p != nullptr);
+  delete p; p = nullptr;
 }
 
 void ranking() {
