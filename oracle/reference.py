@@ -346,7 +346,7 @@ def rank_layers(w_sqnr, a_sqnr, w_mse, a_mse, pos=None, cfg: RankConfig | None =
         if any(math.isnan(m) or math.isinf(m) or m < 0 for m in M):
             raise ValueError("non-finite MSE")
         total = 0.0
-        for m in M:                 # CalculateAverage: plain running sum
+        for m in M:                 # the mean MSE of Algorithm 2: plain running sum over the layers
             total += m
         mean = total / n if n else 0.0
         for i in range(n):
@@ -355,10 +355,10 @@ def rank_layers(w_sqnr, a_sqnr, w_mse, a_mse, pos=None, cfg: RankConfig | None =
             k = M[i] if len(sources) == 1 else (M[i] / mean if mean > 0 else 0.0)
             key[i] = max(key[i], k)
 
-    # L_low <- sort(G, ascending); equal values keep layer order
+    # the list by score, largest SQNR drop (most negative score) first; equal scores keep layer order
     order = sorted(range(n), key=lambda i: (G[i], i))
-    # for l in L_mse: remove from the list, prepend.  L_mse is walked in ascending
-    # MSE so that the largest outlier ends up first; equal values: lower index first.
+    # every MSE outlier is then moved to the head of that list.  They are taken in ascending MSE,
+    # so the largest one is moved last and ends up first; of equal ones the lower index leads.
     outliers = sorted((i for i in range(n) if is_out[i]), key=lambda i: (key[i], -i))
     for l in outliers:
         if l in order:
