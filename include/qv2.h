@@ -426,8 +426,11 @@ qv2_status qv2_rank_tensors(const qv2_plan* plan, const qv2_tensor_sums* h_tenso
  * layer_pos / n_layers / cfg / order_out / score_out: as in qv2_rank_tensors.
  * h_metrics[num_tensors], h_pair_mse[num_tensors], h_pair_sqnr_db[num_tensors]: each may be
  *   NULL; entries of tensors without qrun hold MSE 0 and SQNR +inf.
- * Errors: those of the calls it makes; non-finite sums are reported (ERR_NONFINITE) only after
- * every output has been written. */
+ * Errors: those of the calls it makes.  Non-finite sums (a NaN or Inf among the inputs) are
+ * reported as ERR_NONFINITE only after every output has been written: the metrics of every
+ * tensor (those of the tensors without such values are unaffected), and the list - which is the
+ * true list when the affected tensors are not part of a series the ranking uses, and otherwise
+ * (the ranking cannot order a NaN) layer order 0..n_layers-1 with NaN scores. */
 qv2_status qv2_sensitivity_pass(qv2_plan* plan, qv2_qparams* d_params, qv2_sums* d_sums,
                                 void* d_records, void* h_records, void* d_workspace,
                                 size_t workspace_bytes, void* hip_stream,

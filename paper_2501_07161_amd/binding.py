@@ -491,12 +491,13 @@ def qv2_finalize(plan: Plan, h_params: np.ndarray, h_sums: np.ndarray, strict: b
     return out
 
 
-def qv2_pair_finalize(h_pair: np.ndarray):
+def qv2_pair_finalize(h_pair: np.ndarray, strict: bool = True):
     hp = np.ascontiguousarray(h_pair, dtype=PAIR_SUMS)
     mse = np.zeros(hp.size, np.float64)
     sqnr = np.zeros(hp.size, np.float64)
-    _check(lib().qv2_pair_finalize(hp.ctypes.data, hp.size, mse.ctypes.data, sqnr.ctypes.data),
-           "qv2_pair_finalize")
+    st = lib().qv2_pair_finalize(hp.ctypes.data, hp.size, mse.ctypes.data, sqnr.ctypes.data)
+    if st != QV2_OK and (strict or st != QV2_ERR_NONFINITE):
+        raise QV2Error(st, "qv2_pair_finalize")
     return mse, sqnr
 
 

@@ -7,6 +7,28 @@ namespace {
 // ---------------------------------------------------------------------------
 // pass 3 alone (Algorithm 2: CalculateSQNR / CalculateMSE on D[i] and Q[i])
 // ---------------------------------------------------------------------------
+// vector body of a pair tile (BAL: the partner's vectors are 16-byte aligned; otherwise only 4-byte)
+template <int BLOCK, int V, bool BAL>
+__device__ __forceinline__ void pair_body(gf4_ptr a4, gf_ptr b, int nvec, Acc4& ar2, Acc4& ad2) {
+  const int tid = threadIdx.x;
+  int base = 0;
+  for (; base + V * BLOCK <= nvec; base += V * BLOCK) {
+    f4 ra[V], rb[V];
+#pragma unroll
+    for (int u = 0; u < V; ++u) { ra[u] = ld4(a4 + base + u * BLOCK + tid); rb[u] = ld4b<BAL>(b, base + u * BLOCK + tid); }
+#pragma unroll
+    for (int u = 0; u < V; ++u) {
+      ar2.add_sq(ra[u].x, ra[u].y, ra[u].z, ra[u].w);
+      ad2.add_sq(ra[u].x - rb[u].x, ra[u].y - rb[u].y, ra[u].z - rb[u].z, ra[u].w - rb[u].w);
+    }
+  }
+  for (int i = base + tid; i < nvec; i += BLOCK) {
+    const f4 x = ld4(a4 + i), y = ld4b<BAL>(b, i);
+    ar2.add_sq(x.x, x.y, x.z, x.w);
+    ad2.add_sq(x.x - y.x, x.y - y.y, x.z - y.z, x.w - y.w);
+  }
+}
+
 template <int BLOCK, int V>
 __global__ __launch_bounds__(BLOCK) void k_pair_stream(const StreamView tiles,
                                                        ErrPartial* __restrict__ parts) {
@@ -16,46 +38,25 @@ __global__ __launch_bounds__(BLOCK) void k_pair_stream(const StreamView tiles,
   const int len = tl.len, tid = threadIdx.x;
   double sr2 = 0.0, sd2 = 0.0, unused = 0.0;
 
-  if (((reinterpret_cast<uintptr_t>(tl.x) ^ reinterpret_cast<uintptr_t>(tl.q)) & 15u) != 0) {
-    // the two tensors sit at different offsets within 16 bytes: element loads
-    for (int i = tid; i < len; i += BLOCK) {
-      const float x = a[i], d = x - b[i];
-      sr2 = fma(static_cast<double>(x), static_cast<double>(x), sr2);
-      sd2 = fma(static_cast<double>(d), static_cast<double>(d), sd2);
-    }
-  } else {
-    const int head = head_elems(tl.x, len);
-    const int body = len - head, nvec = body >> 2, tail = body & 3;
-    if (tid < head) {
-      const float x = a[tid], d = x - b[tid];
-      sr2 += static_cast<double>(x) * x; sd2 += static_cast<double>(d) * d;
-    }
-    if (tid < tail) {
-      const int idx = head + (nvec << 2) + tid;
-      const float x = a[idx], d = x - b[idx];
-      sr2 += static_cast<double>(x) * x; sd2 += static_cast<double>(d) * d;
-    }
-    const gf4_ptr a4 = (gf4_ptr)(tl.x + head);
-    const gf4_ptr b4 = (gf4_ptr)(tl.q + head);
-    Acc4 ar2, ad2;
-    int base = 0;
-    for (; base + V * BLOCK <= nvec; base += V * BLOCK) {
-      f4 ra[V], rb[V];
-#pragma unroll
-      for (int u = 0; u < V; ++u) { ra[u] = ld4(a4 + base + u * BLOCK + tid); rb[u] = ld4(b4 + base + u * BLOCK + tid); }
-#pragma unroll
-      for (int u = 0; u < V; ++u) {
-        ar2.add_sq(ra[u].x, ra[u].y, ra[u].z, ra[u].w);
-        ad2.add_sq(ra[u].x - rb[u].x, ra[u].y - rb[u].y, ra[u].z - rb[u].z, ra[u].w - rb[u].w);
-      }
-    }
-    for (int i = base + tid; i < nvec; i += BLOCK) {
-      const f4 x = ld4(a4 + i), y = ld4(b4 + i);
-      ar2.add_sq(x.x, x.y, x.z, x.w);
-      ad2.add_sq(x.x - y.x, x.y - y.y, x.z - y.z, x.w - y.w);
-    }
-    sr2 += ar2.total(); sd2 += ad2.total();
+  // the vectors start where x's alignment puts them; when the partner sits at another offset
+  // inside 16 bytes its vectors are loaded from 4-byte aligned addresses
+  const bool b_al = ((reinterpret_cast<uintptr_t>(tl.x) ^ reinterpret_cast<uintptr_t>(tl.q)) & 15u) == 0;
+  const int head = head_elems(tl.x, len);
+  const int body = len - head, nvec = body >> 2, tail = body & 3;
+  if (tid < head) {
+    const float x = a[tid], d = x - b[tid];
+    sr2 += static_cast<double>(x) * x; sd2 += static_cast<double>(d) * d;
   }
+  if (tid < tail) {
+    const int idx = head + (nvec << 2) + tid;
+    const float x = a[idx], d = x - b[idx];
+    sr2 += static_cast<double>(x) * x; sd2 += static_cast<double>(d) * d;
+  }
+  const gf4_ptr a4 = (gf4_ptr)(tl.x + head);
+  Acc4 ar2, ad2;
+  if (b_al) pair_body<BLOCK, V, true>(a4, b + head, nvec, ar2, ad2);
+  else pair_body<BLOCK, V, false>(a4, b + head, nvec, ar2, ad2);
+  sr2 += ar2.total(); sd2 += ad2.total();
   block_sum3<BLOCK>(sr2, sd2, unused);
   if (tid == 0) {
     ErrPartial o;

@@ -30,8 +30,9 @@ struct StatAcc {
 };
 
 // vector body of a calibration tile; WITHB: a second stream (qrun) is compared in the same visit
-template <int BLOCK, int V, bool WITHB, bool COS>
-__device__ __forceinline__ void stats_body(gf4_ptr v4, gf4_ptr b4, int nvec, StatAcc& a) {
+// (BAL: its vectors are 16-byte aligned like x's; otherwise only 4-byte aligned)
+template <int BLOCK, int V, bool WITHB, bool COS, bool BAL>
+__device__ __forceinline__ void stats_body(gf4_ptr v4, gf_ptr b, int nvec, StatAcc& a) {
   const int tid = threadIdx.x;
   int base = 0;
   for (; base + V * BLOCK <= nvec; base += V * BLOCK) {          // uniform: whole batches
@@ -39,7 +40,7 @@ __device__ __forceinline__ void stats_body(gf4_ptr v4, gf4_ptr b4, int nvec, Sta
 #pragma unroll
     for (int u = 0; u < V; ++u) {
       r[u] = ld4(v4 + base + u * BLOCK + tid);
-      if (WITHB) g[u] = ld4(b4 + base + u * BLOCK + tid);
+      if (WITHB) g[u] = ld4b<BAL>(b, base + u * BLOCK + tid);
     }
 #pragma unroll
     for (int u = 0; u < V; ++u) {
@@ -52,7 +53,7 @@ __device__ __forceinline__ void stats_body(gf4_ptr v4, gf4_ptr b4, int nvec, Sta
     const f4 r = ld4(v4 + i);
     a.take(r);
     if (WITHB) {
-      const f4 g = ld4(b4 + i);
+      const f4 g = ld4b<BAL>(b, i);
       a.d2.add_sq(r.x - g.x, r.y - g.y, r.z - g.z, r.w - g.w);
       if (COS) a.xq.add_prod(r, g);
     }
@@ -72,19 +73,12 @@ __global__ __launch_bounds__(BLOCK) void k_stats_stream(const StreamView tiles,
   const int head = head_elems(tl.x, len);
   const int body = len - head, nvec = body >> 2, tail = body & 3;
   const bool has_b = PAIR && tl.q != nullptr;
-  // qrun at a different offset inside 16 bytes than x: its energy is taken element-wise
-  const bool b_vec = has_b && (((reinterpret_cast<uintptr_t>(tl.x) ^ reinterpret_cast<uintptr_t>(tl.q)) & 15u) == 0);
+  // qrun at a different offset inside 16 bytes than x: its vectors are loaded from 4-byte
+  // aligned addresses (the vectors start where x's alignment puts them)
+  const bool b_al = ((reinterpret_cast<uintptr_t>(tl.x) ^ reinterpret_cast<uintptr_t>(tl.q)) & 15u) == 0;
 
   float mn = INFINITY, mx = -INFINITY;
   double sx = 0.0, sx2 = 0.0, sd2 = 0.0, sxq = 0.0;
-  if (has_b && !b_vec) {
-    for (int i = tid; i < len; i += BLOCK) {
-      const float xv = p[i], qv = b[i];
-      const double d = static_cast<double>(xv - qv);
-      sd2 = fma(d, d, sd2);
-      if (COS) sxq = fma(static_cast<double>(xv), static_cast<double>(qv), sxq);
-    }
-  }
   for (int k = 0; k < 2; ++k) {
     const bool on = k == 0 ? tid < head : tid < tail;
     if (!on) continue;
@@ -92,17 +86,20 @@ __global__ __launch_bounds__(BLOCK) void k_stats_stream(const StreamView tiles,
     const float v = p[idx];
     mn = fminf(mn, v); mx = fmaxf(mx, v);
     sx += v; sx2 += static_cast<double>(v) * v;
-    if (b_vec) {
+    if (has_b) {
       const float qv = b[idx], d = v - qv;
       sd2 += static_cast<double>(d) * d;
       if (COS) sxq = fma(static_cast<double>(v), static_cast<double>(qv), sxq);
     }
   }
   const gf4_ptr v4 = (gf4_ptr)(tl.x + head);
-  const gf4_ptr b4 = (gf4_ptr)(tl.q + head);
   StatAcc a;
-  if (PAIR && b_vec) stats_body<BLOCK, (V > 1 ? V / 2 : 1), true, COS>(v4, b4, nvec, a);
-  else stats_body<BLOCK, V, false, false>(v4, b4, nvec, a);
+  if (PAIR && has_b) {
+    if (b_al) stats_body<BLOCK, (V > 1 ? V / 2 : 1), true, COS, true>(v4, b + head, nvec, a);
+    else stats_body<BLOCK, (V > 1 ? V / 2 : 1), true, COS, false>(v4, b + head, nvec, a);
+  } else {
+    stats_body<BLOCK, V, false, false, true>(v4, b, nvec, a);
+  }
   sx += a.s.total(); sx2 += a.s2.total(); sd2 += a.d2.total(); sxq += a.xq.total();
   mn = fminf(fminf(mn, a.mn4.x), fminf(fminf(a.mn4.y, a.mn4.z), a.mn4.w));
   mx = fmaxf(fmaxf(mx, a.mx4.x), fmaxf(fmaxf(a.mx4.y, a.mx4.z), a.mx4.w));

@@ -17,6 +17,10 @@ namespace {
 
 typedef float f4 __attribute__((ext_vector_type(4)));
 typedef const QV2_GLOBAL f4* gf4_ptr;
+// the same 16-byte vector at an address that is only 4-byte aligned: the partner stream of a pair
+// whose two tensors sit at different offsets inside 16 bytes (x decides where the vectors start)
+typedef f4 f4u __attribute__((aligned(4)));
+typedef const QV2_GLOBAL f4u* gf4u_ptr;
 typedef const QV2_GLOBAL float* gf_ptr;
 typedef QV2_GLOBAL uint32_t* gu32_ptr;
 typedef QV2_GLOBAL int8_t* gi8_ptr;
@@ -44,6 +48,18 @@ __device__ __forceinline__ f4 ld4(gf4_ptr p) {
   return __builtin_nontemporal_load(p);
 #else
   return *p;
+#endif
+}
+
+// Vector i of the partner stream that starts at float address b.  AL: the address is 16-byte
+// aligned; otherwise only 4-byte aligned, which a dwordx4 load takes as well.
+template <bool AL>
+__device__ __forceinline__ f4 ld4b(gf_ptr b, int i) {
+  if (AL) return ld4((gf4_ptr)b + i);
+#if QV2_NT_LOADS
+  return __builtin_nontemporal_load((gf4u_ptr)b + i);
+#else
+  return *((gf4u_ptr)b + i);
 #endif
 }
 

@@ -12,8 +12,8 @@ namespace {
 // Per element 4 B read + 1 B code written (+ 4 B of qrun read when PAIR).
 // ---------------------------------------------------------------------------
 // STORE: 0 no code buffer, 1 packed dwords, 2 single bytes (misaligned code buffer)
-template <int BLOCK, int V, int STORE, bool PAIR, bool COS, bool X2>
-__device__ __forceinline__ void quant_body(gf4_ptr v4, gf4_ptr b4, gu32_ptr cw, gi8_ptr cb, int nvec,
+template <int BLOCK, int V, int STORE, bool PAIR, bool COS, bool X2, bool BAL>
+__device__ __forceinline__ void quant_body(gf4_ptr v4, gf_ptr b, gu32_ptr cw, gi8_ptr cb, int nvec,
                                            const QP& q, Acc4& ae2, Acc4& ax2, Acc4& ad2, Acc4& axh,
                                            Acc4& axq) {
   const int tid = threadIdx.x;
@@ -32,7 +32,7 @@ __device__ __forceinline__ void quant_body(gf4_ptr v4, gf4_ptr b4, gu32_ptr cw, 
 #pragma unroll
     for (int u = 0; u < V; ++u) {
       r[u] = ld4(v4 + base + u * BLOCK + tid);
-      if (PAIR) g[u] = ld4(b4 + base + u * BLOCK + tid);
+      if (PAIR) g[u] = ld4b<BAL>(b, base + u * BLOCK + tid);
     }
 #pragma unroll
     for (int u = 0; u < V; ++u) {
@@ -45,7 +45,7 @@ __device__ __forceinline__ void quant_body(gf4_ptr v4, gf4_ptr b4, gu32_ptr cw, 
     const f4 r = ld4(v4 + i);
     put(i, quant4<COS, X2>(r, q, ae2, ax2, axh));
     if (PAIR) {
-      const f4 g = ld4(b4 + i);
+      const f4 g = ld4b<BAL>(b, i);
       ad2.add_sq(r.x - g.x, r.y - g.y, r.z - g.z, r.w - g.w);
       if (COS) axq.add_prod(r, g);
     }
@@ -87,16 +87,9 @@ __global__ __launch_bounds__(BLOCK, (PAIR ? QV2_QUANT_WAVES_PER_EU : QV2_QUANT_P
   const int len = tl.len, tid = threadIdx.x;
   double sx2 = 0.0, se2 = 0.0, sd2 = 0.0, sxh = 0.0, sxq = 0.0;
 
-  // qrun at a different offset inside 16 bytes than x: its energy is taken element-wise
-  const bool b_vec = has_b && (((reinterpret_cast<uintptr_t>(tl.x) ^ reinterpret_cast<uintptr_t>(tl.q)) & 15u) == 0);
-  if (has_b && !b_vec) {
-    for (int i = tid; i < len; i += BLOCK) {
-      const float xv = p[i], qv = b[i];
-      const double d = static_cast<double>(xv - qv);
-      sd2 = fma(d, d, sd2);
-      if (COS) sxq = fma(static_cast<double>(xv), static_cast<double>(qv), sxq);
-    }
-  }
+  // qrun at a different offset inside 16 bytes than x: its vectors are loaded from 4-byte
+  // aligned addresses (the vectors start where x's alignment puts them)
+  const bool b_al = ((reinterpret_cast<uintptr_t>(tl.x) ^ reinterpret_cast<uintptr_t>(tl.q)) & 15u) == 0;
   const int head = head_elems(tl.x, len);
   const int body = len - head, nvec = body >> 2, tail = body & 3;
   for (int k = 0; k < 2; ++k) {
@@ -110,26 +103,30 @@ __global__ __launch_bounds__(BLOCK, (PAIR ? QV2_QUANT_WAVES_PER_EU : QV2_QUANT_P
     if (X2) sx2 += static_cast<double>(v) * v;
     se2 += static_cast<double>(e) * e;
     if (COS) sxh = fma(static_cast<double>(v), static_cast<double>(h), sxh);
-    if (b_vec) {
+    if (has_b) {
       const float qv = b[idx], d = v - qv;
       sd2 += static_cast<double>(d) * d;
       if (COS) sxq = fma(static_cast<double>(v), static_cast<double>(qv), sxq);
     }
   }
   const gf4_ptr v4 = (gf4_ptr)(tl.x + head);
-  const gf4_ptr b4 = (gf4_ptr)(tl.q + head);
+  const gf_ptr bh = b + head;
   const gi8_ptr cb = c + head;
   const gu32_ptr cw = (gu32_ptr)(tl.c + head);
   const bool cw_ok = has_c && ((reinterpret_cast<uintptr_t>(tl.c + head) & 3u) == 0);
   Acc4 ae2, ax2, ad2, axh, axq;
-  if (b_vec) {
-    if (cw_ok) quant_body<BLOCK, V, 1, PAIR, COS, X2>(v4, b4, cw, cb, nvec, q, ae2, ax2, ad2, axh, axq);
-    else if (has_c) quant_body<BLOCK, V, 2, PAIR, COS, X2>(v4, b4, cw, cb, nvec, q, ae2, ax2, ad2, axh, axq);
-    else quant_body<BLOCK, V, 0, PAIR, COS, X2>(v4, b4, cw, cb, nvec, q, ae2, ax2, ad2, axh, axq);
+  if (has_b && b_al) {
+    if (cw_ok) quant_body<BLOCK, V, 1, PAIR, COS, X2, true>(v4, bh, cw, cb, nvec, q, ae2, ax2, ad2, axh, axq);
+    else if (has_c) quant_body<BLOCK, V, 2, PAIR, COS, X2, true>(v4, bh, cw, cb, nvec, q, ae2, ax2, ad2, axh, axq);
+    else quant_body<BLOCK, V, 0, PAIR, COS, X2, true>(v4, bh, cw, cb, nvec, q, ae2, ax2, ad2, axh, axq);
+  } else if (has_b) {
+    if (cw_ok) quant_body<BLOCK, V, 1, PAIR, COS, X2, false>(v4, bh, cw, cb, nvec, q, ae2, ax2, ad2, axh, axq);
+    else if (has_c) quant_body<BLOCK, V, 2, PAIR, COS, X2, false>(v4, bh, cw, cb, nvec, q, ae2, ax2, ad2, axh, axq);
+    else quant_body<BLOCK, V, 0, PAIR, COS, X2, false>(v4, bh, cw, cb, nvec, q, ae2, ax2, ad2, axh, axq);
   } else {
-    if (cw_ok) quant_body<BLOCK, V, 1, false, COS, X2>(v4, b4, cw, cb, nvec, q, ae2, ax2, ad2, axh, axq);
-    else if (has_c) quant_body<BLOCK, V, 2, false, COS, X2>(v4, b4, cw, cb, nvec, q, ae2, ax2, ad2, axh, axq);
-    else quant_body<BLOCK, V, 0, false, COS, X2>(v4, b4, cw, cb, nvec, q, ae2, ax2, ad2, axh, axq);
+    if (cw_ok) quant_body<BLOCK, V, 1, false, COS, X2, true>(v4, bh, cw, cb, nvec, q, ae2, ax2, ad2, axh, axq);
+    else if (has_c) quant_body<BLOCK, V, 2, false, COS, X2, true>(v4, bh, cw, cb, nvec, q, ae2, ax2, ad2, axh, axq);
+    else quant_body<BLOCK, V, 0, false, COS, X2, true>(v4, bh, cw, cb, nvec, q, ae2, ax2, ad2, axh, axq);
   }
   se2 += ae2.total(); sx2 += ax2.total(); sd2 += ad2.total();
   typename ErrRec<COS>::type o;

@@ -25,6 +25,7 @@
 #include <hip/hip_runtime.h>
 
 #include <cstring>
+#include <limits>
 #include <mutex>
 
 #include "qv2_dev_common.h"   // loads / stores, reductions, the quantizer
@@ -601,6 +602,14 @@ qv2_status pass_finish(const qv2_plan* plan, const void* h_records, const int32_
     if (st == QV2_ERR_NONFINITE) finite = false; else if (st != QV2_OK) return st;
   }
   st = qv2_rank_tensors(plan, h_ts, h_pair, layer_pos, n_layers, cfg, order_out, score_out);
+  if (st == QV2_ERR_NONFINITE) {
+    // a NaN SQNR or a non-finite MSE in a series the ranking needs: no list can be made.  The
+    // outputs still hold something defined - layer order and NaN scores.
+    for (int32_t i = 0; i < n_layers; ++i) {
+      order_out[i] = i;
+      if (score_out) score_out[i] = std::numeric_limits<double>::quiet_NaN();
+    }
+  }
   if (st != QV2_OK) return st;
   return finite ? QV2_OK : QV2_ERR_NONFINITE;
 }

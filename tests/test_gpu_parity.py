@@ -488,3 +488,155 @@ def test_device_calls_can_be_captured_in_a_graph():
         torch.cuda.synchronize()
         got = [buf.params, buf.sums, buf.pair, tsums] + [it.codes for it in items]
         assert all(torch.equal(a, b) for a, b in zip(got, want)), f"replay {rep}"
+
+
+# ----------------------------------------------------------------------------
+# what the header promises beyond finite inputs and one call at a time
+# ----------------------------------------------------------------------------
+def _poisoned_set():
+    """Two layers, each a weight and an activation with a partner, plus a lone activation and a
+    per-channel weight.  NaN and +-Inf entries sit at a tensor's first element, inside the vector
+    body, in the scalar tail and in single channels."""
+    nan, inf = float("nan"), float("inf")
+    w0 = _rand(9408, 301, 0.05)
+    a0 = torch.relu(_rand(200_707, 302))
+    a0[0] = nan; a0[70_001] = nan; a0[-1] = nan
+    w1 = _rand(640, 303, 0.1)
+    w1[5] = inf; w1[333] = -inf
+    a1 = torch.relu(_rand(50_176, 304))
+    lone = _rand(33_001, 305)                        # no partner: takes no part in the ranking
+    lone[12_345] = nan
+    pc = _rand(64 * 576, 306, 0.1)                   # 64 channels in the row kernels
+    pc.view(64, 576)[3, 7] = nan
+    pc.view(64, 576)[40, 0] = inf
+    pl = _rand(6 * 20_001, 307, 0.1)                 # 6 channels as stream tiles
+    pl.view(6, 20_001)[2, 19_999] = nan
+    items = [H.Item("w0", w0, A, 1, synth.WEIGHT, 0), H.Item("a0.nan", a0, A, 1, synth.ACTIVATION, 0, qrun=a0 * 0.99),
+             H.Item("w1.inf", w1, S, 1, synth.WEIGHT, 1), H.Item("a1", a1, A, 1, synth.ACTIVATION, 1, qrun=a1 * 0.98 + 0.01),
+             H.Item("lone.nan", lone, A, 1, synth.ACTIVATION, 2), H.Item("pc.rows", pc, C, 64, synth.ACTIVATION, 3),
+             H.Item("pc.long", pl, C, 6, synth.ACTIVATION, 4)]
+    return items
+
+
+@pytest.mark.parametrize("fused", [False, True, "single"])
+def test_nan_and_inf_inputs(fused):
+    """Inputs must be finite; what happens otherwise is still defined: NaNs are ignored by min / max
+    and poison the sums of their own segment only; finalize reports ERR_NONFINITE and still writes
+    every metric.  Range and n against the oracle for every tensor, everything for the clean ones."""
+    items = _poisoned_set()
+    res = H.run_gpu(items, fused=fused)
+    for t, it in enumerate(items):
+        x = it.x.cpu().numpy().reshape(-1)
+        cal = orc.calibrate(x, it.scheme, it.channels)
+        s0 = res.plan.segment_begin[t]
+        n_seg = it.channels if it.scheme == C else 1
+        P, U = res.params[s0:s0 + n_seg], res.sums[s0:s0 + n_seg]
+        assert np.array_equal(P["min"].view(np.uint32), cal.min.view(np.uint32)), it.name
+        assert np.array_equal(P["max"].view(np.uint32), cal.max.view(np.uint32)), it.name
+        assert np.array_equal(U["n"], cal.n), it.name
+        seg = x.reshape(n_seg, -1)
+        dirty = ~np.isfinite(seg).all(axis=1)
+        assert np.all(~np.isfinite(U["sum_x2"][dirty]) | ~np.isfinite(U["sum_e2"][dirty])), it.name
+        clean = np.nonzero(~dirty)[0]
+        fq = orc.fakequant(x, cal, it.scheme, it.channels)
+        assert np.array_equal(P["scale"][clean].view(np.uint32), cal.scale[clean].view(np.uint32)), it.name
+        assert np.array_equal(P["zp"][clean], cal.zp[clean]), it.name
+        assert np.all(np.abs(U["sum_e2"][clean] - fq.sum_e2[clean]) <= H.MSE_RTOL * fq.sum_e2[clean]), it.name
+        assert np.all(np.abs(U["sum_x2"][clean] - fq.sum_x2[clean]) <= H.SX2_RTOL * fq.sum_x2[clean]), it.name
+        codes = it.codes.cpu().numpy().reshape(n_seg, -1)
+        assert np.array_equal(codes[clean], fq.codes.reshape(n_seg, -1)[clean]), it.name
+        if not dirty.any():
+            H.check_item(t, it, res)
+    # the host half says so, and writes every record anyway
+    with pytest.raises(qb.QV2Error) as e:
+        qb.qv2_finalize(res.plan, res.params, res.sums)
+    assert e.value.status == qb.QV2_ERR_NONFINITE
+    assert np.isfinite(res.metrics["mse"][[0, 3]]).all() and np.isnan(res.metrics["mse"][1])
+    assert np.isnan(res.pair_mse[1]) and np.isfinite(res.pair_mse[3])
+
+
+def test_sensitivity_pass_reports_nonfinite_after_writing_every_output():
+    """One native call over a set with NaN / Inf entries: ERR_NONFINITE, every metric written.  With
+    the bad values outside the series the ranking uses the list is the true one; with a NaN SQNR
+    inside them no list can be made and the outputs hold layer order and NaN scores."""
+    def run(items):
+        res = H.run_gpu(items, fused="single")
+        n_layers = max(it.layer for it in items) + 1
+        buf = qb.Buffers(res.plan, DEV)
+        out = qb.PassOutputs(res.plan, n_layers, DEV)
+        out.order[:] = -7
+        out.score[:] = -7.0
+        with pytest.raises(qb.QV2Error) as e:
+            qb.qv2_sensitivity_pass(res.plan, buf.params, buf.sums, out, buf.workspace)
+        assert e.value.status == qb.QV2_ERR_NONFINITE
+        assert np.array_equal(out.metrics["mse"], res.metrics["mse"], equal_nan=True)
+        assert np.array_equal(out.pair_mse, res.pair_mse, equal_nan=True)
+        return res, out
+
+    # (1) only the lone activation (no partner, so in no series) is poisoned: the list is the true one
+    items = [it for it in _poisoned_set()[:5]]
+    items[1] = H.Item("a0", torch.relu(_rand(200_707, 302)), A, 1, synth.ACTIVATION, 0)
+    items[1].qrun = items[1].x * 0.99
+    items[2] = H.Item("w1", _rand(640, 303, 0.1), S, 1, synth.WEIGHT, 1)
+    items[4].layer = 1
+    res, out = run(items)
+    rows = [H.check_item(t, it, res) for t, it in enumerate(items[:4])]
+    o_order, _ = orc.rank_layers([rows[0]["w_sqnr"], rows[2]["w_sqnr"]], [rows[1]["p_sqnr"], rows[3]["p_sqnr"]],
+                                 [rows[0]["w_mse"], rows[2]["w_mse"]], [rows[1]["p_mse"], rows[3]["p_mse"]])
+    assert out.order[:2].tolist() == o_order and np.isfinite(out.score[:2]).all()
+    assert np.isnan(out.metrics["mse"][4])
+    # (2) a NaN inside a ranked activation: layer order, NaN scores
+    items = _poisoned_set()[:4]
+    res, out = run(items)
+    assert out.order[:2].tolist() == [0, 1] and np.isnan(out.score[:2]).all()
+
+
+def test_two_plans_on_two_streams_at_once():
+    """Different plans are independent: two of them, each with its own workspace and outputs, run
+    at the same time on two streams, several passes each, and reproduce their serial results bit
+    for bit (parameters, sums, pair sums, codes)."""
+    sets = [synth.config_resnet18(4), synth.config_mobilenetv2(4)]
+    jobs = []
+    for specs in sets:
+        items = H.items_from_specs(specs, DEV)
+        for it in items:
+            if it.kind == synth.ACTIVATION:
+                it.qrun = it.x * 0.97 + 0.002
+        res = H.run_gpu(items, fused="single")                     # serial reference
+        want = [res.buffers.params.clone(), res.buffers.sums.clone(), res.buffers.pair.clone()] + \
+               [it.codes.clone() for it in items]
+        jobs.append((items, res, want, qb.Buffers(res.plan, DEV), torch.cuda.Stream()))
+    torch.cuda.synchronize()
+    for rep in range(3):
+        for items, res, want, buf, st in jobs:
+            for it in items:
+                it.codes.fill_(0x11)
+            for b in (buf.params, buf.sums, buf.pair, buf.workspace):
+                b.fill_(0x5A)
+        torch.cuda.synchronize()
+        for k in range(4):                                         # interleaved: both streams stay busy
+            for items, res, want, buf, st in jobs:
+                qb.qv2_calibrate_fakequant_pair_metrics(res.plan, buf.params, buf.sums, buf.pair, buf.workspace,
+                                                        stream=st)
+        torch.cuda.synchronize()
+        for j, (items, res, want, buf, st) in enumerate(jobs):
+            got = [buf.params, buf.sums, buf.pair] + [it.codes for it in items]
+            assert all(torch.equal(a, b) for a, b in zip(got, want)), f"plan {j}, round {rep}"
+
+
+@pytest.mark.parametrize("fused", [False, True, "single"])
+def test_large_pair_at_different_offsets_inside_16_bytes(fused):
+    """x and its partner start at different offsets inside 16 bytes (every combination), long
+    enough for many tiles: the partner is read as vectors from 4-byte aligned addresses."""
+    n = 1_000_003
+    items = []
+    for ox in range(4):
+        for oq in range(4):
+            if ox == oq:
+                continue
+            x = torch.relu(_rand(n + 8, 700 + ox)[ox: ox + n])
+            q = _rand(n + 8, 710 + 4 * ox + oq)[oq: oq + n] * 0.01 + x
+            items.append(H.Item(f"x+{ox}.q+{oq}", x, A, 1, synth.ACTIVATION, len(items), qrun=q,
+                                codes_offset=(ox + oq) % 4))
+    res = H.run_gpu(items, fused=fused)
+    H.check_all(items, res)

@@ -47,7 +47,32 @@ def test_resnet50_batch256_full_pass():
         assert np.allclose(res3.pair[f], res2.pair[f], rtol=1e-12, atol=0)
     assert np.array_equal(res3.pair["n"], res2.pair["n"])
     assert all(torch.equal(a, it.codes) for a, it in zip(codes2, items))
-    del items
+    # the fused-IR variant of the same set at the same batch (Sec. 6.3 Eq. 10-12: BN folded into
+    # the weights): its 54 weights differ, its activations and partners are these very tensors.
+    # One plan of 108 tensors through the single call again; the folded weights element by
+    # element against the oracle, the activations against the records and codes just checked.
+    print("BN-folded variant, single call ...", flush=True)
+    fspecs = synth.config_resnet50(256, fused=True)
+    fitems = []
+    for it, sp in zip(items, fspecs):
+        assert sp.name == it.name
+        if sp.kind == synth.WEIGHT:
+            fitems.append(H.Item(sp.name, synth.materialize(sp, "cuda"), sp.scheme, sp.channels, sp.kind, sp.layer))
+        else:
+            fitems.append(it)
+    res4 = H.run_gpu(fitems, fused="single")       # fresh code buffers for every tensor
+    w_idx = [t for t, sp in enumerate(fspecs) if sp.kind == synth.WEIGHT]
+    a_idx = [t for t, sp in enumerate(fspecs) if sp.kind == synth.ACTIVATION]
+    assert any(not torch.equal(fitems[t].x, synth.materialize(specs[t], "cuda")) for t in w_idx[:3])
+    for t in w_idx:
+        H.check_item(t, fitems[t], res4)
+    for t in a_idx:
+        s0 = res4.plan.segment_begin[t]
+        assert res4.params[s0].tobytes() == res3.params[s0].tobytes()
+        assert res4.sums[s0].tobytes() == res3.sums[s0].tobytes()
+        assert res4.pair[t].tobytes() == res3.pair[t].tobytes()
+        assert torch.equal(fitems[t].codes, codes2[t])
+    del items, fitems
     torch.cuda.empty_cache()
 
 

@@ -45,6 +45,8 @@ MUTATIONS = [
     (PY, "if bops_reduction_pct(macs, keep) < target_pct:", "if bops_reduction_pct(macs, keep) <= target_pct:"),
     (PY, "return list(range(n - 1, -1, -1))", "return list(range(n))"),                  # InOrder direction
     (PY, "kl += pa * math.log(pa / qb_)", "kl += qb_ * math.log(qb_ / pa)"),             # KL(Q || P)
+    (PY, 'lines.append(f"{i},{name},{32 if k else 8}")', 'lines.append(f"{i},{name},{8 if k else 32}")'),   # bit-widths swapped
+    (PY, 'lines = ["layer,name,bits"]', 'lines = ["layer,bits,name"]'),                   # header line
     (PY, "out.extend(m for m in order if group_id[m] == g)", "out.extend(sorted(m for m in order if group_id[m] == g))"),
 ]
 

@@ -452,6 +452,23 @@ def test_bops_select_hand_worked_and_bruteforce():
         orc.bops_select([0, 1], [0.0, 0.0], 50.0)
 
 
+def test_config_text_literal():
+    """Sec. 4 step 5: the per-layer bit-width table.  The paper prints no format; the one this
+    build states (a header line, then index, name and 32 or 8 per layer, in layer order) is
+    written out here by hand, so a swapped bit-width, a changed header or a lost line shows."""
+    want = ("layer,name,bits\n"
+            "0,conv1,8\n"
+            "1,layer1.0.conv1,32\n"
+            "2,layer1.0.conv2,8\n"
+            "3,fc,32\n")
+    assert orc.config_text([False, True, False, True], ["conv1", "layer1.0.conv1", "layer1.0.conv2", "fc"]) == want
+    assert orc.config_text([1, 0]) == "layer,name,bits\n0,layer0,32\n1,layer1,8\n"
+    assert orc.config_text([]) == "layer,name,bits\n"
+    for bad in ("a,b", "a\nb", "a\rb"):
+        with pytest.raises(ValueError):
+            orc.config_text([True], [bad])
+
+
 def test_baseline_orders():
     w = [40.0, 38.0, 45.0, 30.0, 38.0]
     assert orc.baseline_order(orc.INORDER, n=5) == [4, 3, 2, 1, 0]
