@@ -22,10 +22,19 @@ __device__ __forceinline__ void pair_body(gf4_ptr a4, gf_ptr b, int nvec, Acc4& 
       ad2.add_sq(ra[u].x - rb[u].x, ra[u].y - rb[u].y, ra[u].z - rb[u].z, ra[u].w - rb[u].w);
     }
   }
-  for (int i = base + tid; i < nvec; i += BLOCK) {
-    const f4 x = ld4(a4 + i), y = ld4b<BAL>(b, i);
-    ar2.add_sq(x.x, x.y, x.z, x.w);
-    ad2.add_sq(x.x - y.x, x.y - y.y, x.z - y.z, x.w - y.w);
+  if (base < nvec) {        // the last, partial batch, loaded like a whole one
+    f4 ra[V], rb[V];
+#pragma unroll
+    for (int u = 0; u < V; ++u) {
+      const int i = base + u * BLOCK + tid, j = i < nvec ? i : nvec - 1;
+      ra[u] = ld4(a4 + j); rb[u] = ld4b<BAL>(b, j);
+    }
+#pragma unroll
+    for (int u = 0; u < V; ++u) {
+      if (base + u * BLOCK + tid >= nvec) continue;
+      ar2.add_sq(ra[u].x, ra[u].y, ra[u].z, ra[u].w);
+      ad2.add_sq(ra[u].x - rb[u].x, ra[u].y - rb[u].y, ra[u].z - rb[u].z, ra[u].w - rb[u].w);
+    }
   }
 }
 

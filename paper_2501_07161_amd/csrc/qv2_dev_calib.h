@@ -49,13 +49,22 @@ __device__ __forceinline__ void stats_body(gf4_ptr v4, gf_ptr b, int nvec, StatA
       if (WITHB && COS) a.xq.add_prod(r[u], g[u]);
     }
   }
-  for (int i = base + tid; i < nvec; i += BLOCK) {
-    const f4 r = ld4(v4 + i);
-    a.take(r);
-    if (WITHB) {
-      const f4 g = ld4b<BAL>(b, i);
-      a.d2.add_sq(r.x - g.x, r.y - g.y, r.z - g.z, r.w - g.w);
-      if (COS) a.xq.add_prod(r, g);
+  if (base < nvec) {
+    // the last, partial batch: its loads go out together like a whole batch's; a lane whose
+    // vector lies past the end reads the last vector instead and leaves it out
+    f4 r[V], g[V];
+#pragma unroll
+    for (int u = 0; u < V; ++u) {
+      const int i = base + u * BLOCK + tid, j = i < nvec ? i : nvec - 1;
+      r[u] = ld4(v4 + j);
+      if (WITHB) g[u] = ld4b<BAL>(b, j);
+    }
+#pragma unroll
+    for (int u = 0; u < V; ++u) {
+      if (base + u * BLOCK + tid >= nvec) continue;
+      a.take(r[u]);
+      if (WITHB) a.d2.add_sq(r[u].x - g[u].x, r[u].y - g[u].y, r[u].z - g[u].z, r[u].w - g[u].w);
+      if (WITHB && COS) a.xq.add_prod(r[u], g[u]);
     }
   }
 }
