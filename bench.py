@@ -156,9 +156,15 @@ class Workload:
         self.n_a = sum(s.numel for s in specs if s.kind == synth.ACTIVATION)
         self.n_pair = sum(s.numel for s, q in zip(specs, qruns) if q is not None)
         self.n_all = self.n_w + self.n_a
-        is_row = lambda s: s.scheme == synth.SYM_CHANNEL and s.numel // s.channels <= 8192
-        self.n_rowgroup = sum(s.numel for s in specs if is_row(s))
-        self.n_pair_stream = sum(s.numel for s, q in zip(specs, qruns) if q is not None and not is_row(s))
+        # elements of the tensors the single call reads once (channels short enough to stay on chip)
+        once = []
+        for r in self.rows:
+            probe = qb.qv2_plan_create([r])
+            once.append(probe.num_single_read_elements > 0)
+            probe.close()
+        self.single_read = once
+        self.n_rowgroup = sum(s.numel for s, o in zip(specs, once) if o)
+        self.n_pair_stream = sum(s.numel for s, q, o in zip(specs, qruns, once) if q is not None and not o)
         # bytes a pass has to move through HBM, per form
         self.bytes_cal, self.bytes_fq, self.bytes_pair = 4 * self.n_all, 5 * self.n_all, 8 * self.n_pair
         self.bytes_fqpair = 5 * self.n_all + 4 * self.n_pair           # x read once for steps a3 + a4
@@ -646,8 +652,7 @@ def cpu_baseline(wl, budget):
 
     def moved_bytes(t):
         s = specs[t]
-        short = s.scheme == synth.SYM_CHANNEL and s.numel // s.channels <= 8192
-        return (5 if short else 9) * s.numel + (4 * s.numel if qruns[t] is not None else 0)
+        return (5 if wl.single_read[t] else 9) * s.numel + (4 * s.numel if qruns[t] is not None else 0)
 
     def one(t, x, q):
         s = specs[t]

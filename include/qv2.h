@@ -183,6 +183,9 @@ int64_t qv2_plan_segment_begin(const qv2_plan* plan, int32_t t);
 int64_t qv2_plan_num_tiles(const qv2_plan* plan);
 int64_t qv2_plan_num_quant_tiles(const qv2_plan* plan);
 int64_t qv2_plan_num_pair_tiles(const qv2_plan* plan);
+/* Elements of the tensors that qv2_calibrate_fakequant_pair_metrics reads from HBM once (their
+ * channels are short enough to be held on chip, see there); for byte accounting. */
+int64_t qv2_plan_num_single_read_elements(const qv2_plan* plan);
 /* Bytes of device workspace any device call on this plan needs (256-byte
  * aligned base).  Calls that may overlap in time need separate workspaces. */
 size_t qv2_workspace_bytes(const qv2_plan* plan);
@@ -256,9 +259,10 @@ qv2_status qv2_fakequant_pair_metrics(qv2_plan* plan, const qv2_qparams* d_param
  * and sum_e2 bit for bit; sum_x2, which stays the calibration sweep's instead of being summed
  * again, and the pair sums up to fp64 summation order), with every tensor
  * made of short segments (per-output-channel tensors whose channel has at most 8192
- * elements) read from HBM ONCE: a group of whole channels is held in registers (or staged
- * in LDS), and range, parameters, codes and energies of each channel are taken from that
- * copy.  Longer
+ * elements - at most 32768 when the channels are whole 16-byte vectors on 16-byte boundaries
+ * and the code buffer is 4-byte aligned) read from HBM ONCE: a group of whole channels is held
+ * in registers (or staged in LDS), and range, parameters, codes and energies of each channel
+ * are taken from that copy.  Longer
  * segments still need two reads (their scale depends on the global range); the comparison
  * with qrun rides on the first, read-only one, the second writes the codes.
  * d_params, d_sums: DEVICE, written.  d_pair_sums[num_tensors]: DEVICE, written; NULL

@@ -26,7 +26,7 @@ QV2_ASYM_TENSOR, QV2_SYM_TENSOR, QV2_SYM_CHANNEL = 0, 1, 2
 EXPORTS = (
     "qv2_plan_create", "qv2_plan_destroy", "qv2_plan_num_tensors", "qv2_plan_num_segments",
     "qv2_plan_segment_begin", "qv2_plan_num_tiles", "qv2_plan_num_quant_tiles",
-    "qv2_plan_num_pair_tiles", "qv2_plan_upload", "qv2_plan_device_bytes",
+    "qv2_plan_num_pair_tiles", "qv2_plan_num_single_read_elements", "qv2_plan_upload", "qv2_plan_device_bytes",
     "qv2_calibrate_fakequant_pair_metrics_noalloc",
     "qv2_workspace_bytes", "qv2_calibrate", "qv2_fakequant_metrics", "qv2_pair_metrics",
     "qv2_fakequant_pair_metrics", "qv2_calibrate_fakequant_pair_metrics", "qv2_calibrate_fakequant_pair_metrics_cos",
@@ -92,7 +92,7 @@ def lib():
         L.qv2_plan_num_tensors.argtypes = [vp]
         L.qv2_plan_num_tensors.restype = i32
         for n in ("qv2_plan_num_segments", "qv2_plan_num_tiles", "qv2_plan_num_quant_tiles",
-                  "qv2_plan_num_pair_tiles"):
+                  "qv2_plan_num_pair_tiles", "qv2_plan_num_single_read_elements"):
             getattr(L, n).argtypes = [vp]
             getattr(L, n).restype = i64
         L.qv2_plan_segment_begin.argtypes = [vp, i32]
@@ -229,6 +229,7 @@ class Plan:
         self.num_tiles = L.qv2_plan_num_tiles(handle)
         self.num_quant_tiles = L.qv2_plan_num_quant_tiles(handle)
         self.num_pair_tiles = L.qv2_plan_num_pair_tiles(handle)
+        self.num_single_read_elements = L.qv2_plan_num_single_read_elements(handle)
         self.workspace_bytes = L.qv2_workspace_bytes(handle)
         self.segment_begin = [L.qv2_plan_segment_begin(handle, t) for t in range(self.num_tensors)]
 

@@ -185,35 +185,15 @@ __global__ __launch_bounds__(256) void k_hist_fold(const HistTensor* __restrict_
   if (hist_q) hist_q[static_cast<size_t>(t) * nbins + i] = b;
 }
 
-// Per-tensor fold of the per-segment results: one 256-thread workgroup per tensor (thread-
-// strided over the segments, butterfly per wavefront, then the four wavefronts in order).
-__global__ __launch_bounds__(256) void k_tensor_fold(const HistTensor* __restrict__ ht, int n,
-                                                     const qv2_qparams* __restrict__ params,
-                                                     const qv2_sums* __restrict__ sums,
-                                                     qv2_tensor_sums* __restrict__ out) {
-  __shared__ long long scnt[256 / kWave];
-  const int t = blockIdx.x, tid = threadIdx.x;
-  const HistTensor h = ht[t];
-  float mn = INFINITY, mx = -INFINITY;
-  double sx = 0.0, sx2 = 0.0, se2 = 0.0;
-  long long cnt = 0;
-  for (int i = tid; i < h.nseg; i += 256) {
-    const qv2_qparams p = params[h.seg0 + i];
-    const qv2_sums u = sums[h.seg0 + i];
-    mn = fminf(mn, p.min); mx = fmaxf(mx, p.max);
-    sx += u.sum_x; sx2 += u.sum_x2; se2 += u.sum_e2; cnt += u.n;
-  }
-  for (int o = kWave >> 1; o > 0; o >>= 1) cnt += __shfl_xor(cnt, o);
-  if ((tid & (kWave - 1)) == 0) scnt[tid >> 6] = cnt;
-  block_minmax<256>(mn, mx);                       // holds a barrier: scnt is visible after it
-  block_sum3<256>(sx, sx2, se2);
-  if (tid == 0) {
-    qv2_tensor_sums o;
-    o.sum_x = sx; o.sum_x2 = sx2; o.sum_e2 = se2; o.min = mn; o.max = mx;
-    o.n = scnt[0] + scnt[1] + scnt[2] + scnt[3];
-    o._pad[0] = o._pad[1] = 0;
-    out[t] = o;
-  }
+// Per-tensor fold of the per-segment results: one workgroup per tensor; `list` (may be null)
+// names the tensors to fold, else all n of them.
+__global__ __launch_bounds__(kFoldBlock) void k_tensor_fold(const HistTensor* __restrict__ ht,
+                                                            const int* __restrict__ list,
+                                                            const qv2_qparams* __restrict__ params,
+                                                            const qv2_sums* __restrict__ sums,
+                                                            qv2_tensor_sums* __restrict__ out) {
+  const int t = list ? list[blockIdx.x] : blockIdx.x;
+  tensor_record(ht[t], params, sums, out + t);
 }
 
 // ---------------------------------------------------------------------------

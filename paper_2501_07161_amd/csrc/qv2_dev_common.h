@@ -187,25 +187,28 @@ __device__ __forceinline__ int head_elems(const void* p, int len) {
 struct QP { float scale, inv, zpf; };
 
 // Returns the code as a float in [-128,127]; xhat is the dequantized value, err = x - xhat.
+// ZP0: the zero-point is known to be 0 (a symmetric scheme whose parameters the kernel has just
+// made itself), so its add and subtract are left out; codes, xhat and err^2 are the same.
+template <bool ZP0 = false>
 __device__ __forceinline__ float quant1(float x, const QP& q, float& err, float& xhat) {
   const float t = x * q.inv;                       // fp32 multiply
   const float r = rintf(t);                        // round half to even
   // integer add of the zero-point: exact in fp32 below 2^24, saturates above
-  const float c = fminf(fmaxf(r + q.zpf, -128.0f), 127.0f);
-  xhat = (c - q.zpf) * q.scale;                    // exact difference, one multiply
+  const float c = fminf(fmaxf(ZP0 ? r : r + q.zpf, -128.0f), 127.0f);
+  xhat = (ZP0 ? c : c - q.zpf) * q.scale;          // exact difference, one multiply
   err = x - xhat;
   return c;
 }
 
 // COS: also accumulate sum x*xhat (the cross term of the cosine similarity, Sec. 6.1 Eq. 8)
 // X2 = false leaves sum x^2 out (the caller already has it from the calibration sweep)
-template <bool COS, bool X2 = true>
+template <bool COS, bool X2 = true, bool ZP0 = false>
 __device__ __forceinline__ uint32_t quant4(const f4& v, const QP& q, Acc4& se2, Acc4& sx2, Acc4& sxh) {
   float e0, e1, e2, e3, h0, h1, h2, h3;
-  const int c0 = static_cast<int>(quant1(v.x, q, e0, h0));
-  const int c1 = static_cast<int>(quant1(v.y, q, e1, h1));
-  const int c2 = static_cast<int>(quant1(v.z, q, e2, h2));
-  const int c3 = static_cast<int>(quant1(v.w, q, e3, h3));
+  const int c0 = static_cast<int>(quant1<ZP0>(v.x, q, e0, h0));
+  const int c1 = static_cast<int>(quant1<ZP0>(v.y, q, e1, h1));
+  const int c2 = static_cast<int>(quant1<ZP0>(v.z, q, e2, h2));
+  const int c3 = static_cast<int>(quant1<ZP0>(v.w, q, e3, h3));
   const f4 h = {h0, h1, h2, h3};
   se2.add_sq(e0, e1, e2, e3);
   if (X2) sx2.add_sq(v.x, v.y, v.z, v.w);

@@ -139,12 +139,46 @@ __device__ __forceinline__ double pair_energy(const ErrPartial& p) { return p.se
 __device__ __forceinline__ double pair_energy(const ErrPartial3& p) { return p.sd2; }
 __device__ __forceinline__ double pair_energy(const ErrPartial5& p) { return p.sd2; }
 
-// error energies of one segment
+// One tensor's record from its segments' records, by one workgroup of kFoldBlock threads: thread-
+// strided over the segments, a butterfly per wavefront, then the wavefronts in order.
+__device__ __forceinline__ void tensor_record(const HistTensor h, const qv2_qparams* __restrict__ params,
+                                              const qv2_sums* __restrict__ sums,
+                                              qv2_tensor_sums* __restrict__ out_rec) {
+  __shared__ long long scnt[kFoldBlock / kWave];
+  const int tid = threadIdx.x;
+  float mn = INFINITY, mx = -INFINITY;
+  double sx = 0.0, sx2 = 0.0, se2 = 0.0;
+  long long cnt = 0;
+  for (int i = tid; i < h.nseg; i += kFoldBlock) {
+    const qv2_qparams p = params[h.seg0 + i];
+    const qv2_sums u = sums[h.seg0 + i];
+    mn = fminf(mn, p.min); mx = fmaxf(mx, p.max);
+    sx += u.sum_x; sx2 += u.sum_x2; se2 += u.sum_e2; cnt += u.n;
+  }
+  for (int o = kWave >> 1; o > 0; o >>= 1) cnt += __shfl_xor(cnt, o);
+  if ((tid & (kWave - 1)) == 0) scnt[tid >> 6] = cnt;
+  block_minmax<kFoldBlock>(mn, mx);                // holds a barrier: scnt is visible after it
+  block_sum3<kFoldBlock>(sx, sx2, se2);
+  if (tid == 0) {
+    qv2_tensor_sums o;
+    o.sum_x = sx; o.sum_x2 = sx2; o.sum_e2 = se2; o.min = mn; o.max = mx;
+    long long n = 0;
+    for (int w = 0; w < kFoldBlock / kWave; ++w) n += scnt[w];
+    o.n = n;
+    o._pad[0] = o._pad[1] = 0;
+    *out_rec = o;
+  }
+}
+
+// error energies of one segment.  ts != null (the last fold of a whole pass): a tensor that is this
+// one segment gets its per-tensor record here as well - the same values tensor_record would give.
 template <class P>
 __device__ __forceinline__ void fold_err_item(const FoldIdx& f, const Segment* __restrict__ segs,
                                               const P* __restrict__ parts, qv2_sums* __restrict__ sums,
                                               double* __restrict__ seg_xxhat, int skip_below,
-                                              bool keep_x2) {
+                                              bool keep_x2, qv2_tensor_sums* __restrict__ ts = nullptr,
+                                              const qv2_qparams* __restrict__ params = nullptr,
+                                              const HistTensor* __restrict__ ht = nullptr) {
   if (!f.active) return;
   const Segment sg = segs[f.id];
   if (!f.wide && sg.enp > kFoldWaveMax) return;
@@ -163,6 +197,14 @@ __device__ __forceinline__ void fold_err_item(const FoldIdx& f, const Segment* _
     if (!keep_x2) sums[f.id].sum_x2 = sx2;         // else the calibration sweep's sum stays
     sums[f.id].sum_e2 = se2; sums[f.id].n = sg.n;
     if (seg_xxhat) seg_xxhat[f.id] = sxh;
+    if (ts && ht[sg.tensor].nseg == 1) {
+      const qv2_qparams p = params[f.id];
+      qv2_tensor_sums o;                           // sums of one term; 0.0 + v as a fold would form it
+      o.sum_x = 0.0 + sums[f.id].sum_x; o.sum_x2 = 0.0 + (keep_x2 ? sums[f.id].sum_x2 : sx2);
+      o.sum_e2 = 0.0 + se2; o.n = sg.n; o.min = p.min; o.max = p.max;
+      o._pad[0] = o._pad[1] = 0;
+      ts[sg.tensor] = o;
+    }
   }
 }
 
@@ -202,6 +244,10 @@ struct QuantFoldArgs {
   const PairTensor* pair_done;               // tensors with n != 0 here are skipped (may be null)
   const P* parts;
   int seg_blocks;
+  // the last fold of a whole pass also leaves the per-tensor records (ts != null): single-segment
+  // tensors with their segment, tensors made of row-group tiles by one more workgroup each
+  qv2_tensor_sums* ts; const qv2_qparams* params; const HistTensor* ht;
+  const int* row_tensors; int pair_blocks;
 };
 
 template <class P>
@@ -209,10 +255,13 @@ __global__ __launch_bounds__(kFoldBlock) void k_fold_quant(const QuantFoldArgs<P
   const int b = blockIdx.x;
   if (b < a.seg_blocks) {
     fold_err_item<P>(FoldIdx(b, a.wide_segs, a.n_wide_segs, a.nseg), a.segs, a.parts, a.sums,
-                     a.seg_xxhat, a.skip_below, a.keep_x2);
-  } else {
+                     a.seg_xxhat, a.skip_below, a.keep_x2, a.ts, a.params, a.ht);
+  } else if (b < a.seg_blocks + a.pair_blocks) {
     fold_pair_item<P>(FoldIdx(b - a.seg_blocks, a.wide_pt, a.n_wide_pt, a.nt), a.pt, a.parts,
                       a.pair_out, a.pair_xq, a.pair_done);
+  } else {
+    const int t = a.row_tensors[b - a.seg_blocks - a.pair_blocks];
+    tensor_record(a.ht[t], a.params, a.sums, a.ts + t);
   }
 }
 

@@ -321,7 +321,7 @@ __global__ __launch_bounds__(BLOCK) void k_rows_reg(const Tile* __restrict__ til
 
   qv2_qparams qp;
   QP q{1.0f, 1.0f, 0.0f};
-  double sx = 0.0;
+  double sx = 0.0, sx2_first = 0.0;
   if (ROLE != 1) {
     float mn = INFINITY, mx = -INFINITY;
     Acc4 as, as2;
@@ -331,7 +331,9 @@ __global__ __launch_bounds__(BLOCK) void k_rows_reg(const Tile* __restrict__ til
       mn = fminf(fminf(mn, xv[k].x), fminf(fminf(xv[k].y, xv[k].z), xv[k].w));
       mx = fmaxf(fmaxf(mx, xv[k].x), fmaxf(fmaxf(xv[k].y, xv[k].z), xv[k].w));
       as.add(xv[k]);
-      if (ROLE == 0) as2.add_sq(xv[k].x, xv[k].y, xv[k].z, xv[k].w);
+      // sum x^2 rides on the same conversion of x to fp64 (ROLE 2: the quantize step below then
+      // leaves it out; same accumulators, same order, same bits as summing it there)
+      if (ROLE != 1) as2.add_sq(xv[k].x, xv[k].y, xv[k].z, xv[k].w);
     }
     double v[2] = {as.total(), as2.total()};
     row_join<W, 2, true>(m, mn, mx, v, sf, sd1);
@@ -343,9 +345,10 @@ __global__ __launch_bounds__(BLOCK) void k_rows_reg(const Tile* __restrict__ til
       }
       return;
     }
-    sx = v[0];
-    make_params(mn, mx, segs[tl.seg0].scheme, qp);           // one tensor, one scheme per tile
-    q = QP{qp.scale, qp.inv_scale, static_cast<float>(qp.zp)};
+    sx = v[0]; sx2_first = v[1];
+    // rows are segments of a per-output-channel tensor: the scheme is symmetric and the zero-point 0
+    make_params(mn, mx, QV2_SYM_CHANNEL, qp);
+    q = QP{qp.scale, qp.inv_scale, 0.0f};
   } else if (live) {
     q = load_qp(params, tl.seg0 + r);
   }
@@ -356,7 +359,8 @@ __global__ __launch_bounds__(BLOCK) void k_rows_reg(const Tile* __restrict__ til
 #pragma unroll
   for (int k = 0; k < K; ++k) {
     if (!on[k]) continue;
-    const uint32_t pk = quant4<COS>(xv[k], q, ae2, ax2, axh);
+    const uint32_t pk = ROLE == 2 ? quant4<COS, false, true>(xv[k], q, ae2, ax2, axh)
+                                  : quant4<COS>(xv[k], q, ae2, ax2, axh);
     if (has_c) st_codes(cw + m.gl + k * G, pk);
     if (has_b) {
       ad2.add_sq(xv[k].x - gv[k].x, xv[k].y - gv[k].y, xv[k].z - gv[k].z, xv[k].w - gv[k].w);
@@ -368,6 +372,7 @@ __global__ __launch_bounds__(BLOCK) void k_rows_reg(const Tile* __restrict__ til
   if (COS) { e[NE - 2] = axh.total(); e[NE - 1] = axq.total(); }
   float u0 = 0.0f, u1 = 0.0f;
   row_join<W, NE, false>(m, u0, u1, e, sf, sd2);
+  if (ROLE == 2) e[0] = sx2_first;
   if (live && m.gl == 0) {
     typename ErrRec<COS>::type o;
     o.sx2 = e[0]; o.se2 = e[1]; o.sd2 = e[2];

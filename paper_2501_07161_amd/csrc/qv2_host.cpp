@@ -67,6 +67,19 @@ void finish_table(StreamTable& tab) {
   }
 }
 
+// How the rows of a per-channel tensor are handled: as stream tiles, staged in LDS, or held in
+// registers (rows of whole 16-byte vectors on 16-byte boundaries, coded through whole dwords).
+qv2::RowForm row_form(const qv2_tensor& in, int64_t inner) {
+  if (in.scheme != QV2_SYM_CHANNEL) return qv2::kRowStream;
+  const bool reg_ok = inner % 4 == 0 && inner >= qv2::kRowRegMinInner &&
+                      (reinterpret_cast<uintptr_t>(in.x) & 15u) == 0 &&
+                      (!in.qrun || (reinterpret_cast<uintptr_t>(in.qrun) & 15u) == 0) &&
+                      (!in.codes || (reinterpret_cast<uintptr_t>(in.codes) & 3u) == 0);
+  if (reg_ok && inner <= int64_t{qv2::kBlockRows} * 4 * qv2::kRowRegVecs) return qv2::kRowReg;
+  if (reg_ok && inner <= qv2::kRowRegCap) return qv2::kRowRegWide;
+  return inner <= qv2::kRowGroupCap ? qv2::kRowLds : qv2::kRowStream;
+}
+
 // A launch of n workgroups of `block` threads must stay within 2^32 - 1 threads in all.
 bool launchable(int64_t n, int64_t block) { return n * block <= int64_t{0xFFFFFFFF}; }
 
@@ -117,7 +130,7 @@ static qv2_status plan_create(const qv2_tensor* h_tensors, int32_t n_tensors, qv
         (in.qrun && (reinterpret_cast<uintptr_t>(in.qrun) & 3u))) return QV2_ERR_ALIGN;
     const int64_t nseg = per_channel ? in.channels : 1;
     n_segments += nseg;
-    if (per_channel && in.numel / nseg <= qv2::kRowGroupCap) n_row_parts += nseg;
+    if (row_form(in, in.numel / nseg) != qv2::kRowStream) n_row_parts += nseg;
     if (n_segments > kMax) return QV2_ERR_SHAPE;
   }
 
@@ -151,20 +164,19 @@ static qv2_status plan_create(const qv2_tensor* h_tensors, int32_t n_tensors, qv
 
     PairTensor ft{};                         // this tensor's partials in the quantize numbering
     PairTensor st{};                         // ... in the calibration numbering (stream tiles only)
-    if (per_channel && inner <= qv2::kRowGroupCap) {
+    const qv2::RowForm form = row_form(in, inner);
+    if (form != qv2::kRowStream) {
       // whole rows per tile; every row is its own segment with one partial
       ft.part0 = static_cast<int32_t>(row_part); ft.nparts = static_cast<int32_t>(nseg);
+      p->n_single_read += in.numel;
       // rows of whole 16-byte vectors on 16-byte boundaries are held in registers: `lanes`
       // lanes per row (each at most kRowRegVecs vectors), one round of rows per workgroup
-      const bool reg_form = inner % 4 == 0 && inner >= qv2::kRowRegMinInner &&
-                            (reinterpret_cast<uintptr_t>(in.x) & 15u) == 0 &&
-                            (!in.qrun || (reinterpret_cast<uintptr_t>(in.qrun) & 15u) == 0) &&
-                            (!in.codes || (reinterpret_cast<uintptr_t>(in.codes) & 3u) == 0);
+      const bool reg_form = form != qv2::kRowLds;
       int64_t lanes = 0, rpt = 0;
       if (reg_form) {
         lanes = qv2::kRowRegMinLanes;
         while (lanes * 4 * qv2::kRowRegVecs < inner) lanes <<= 1;
-        rpt = qv2::kBlockRows / lanes;
+        rpt = (form == qv2::kRowRegWide ? qv2::kBlockRowsWide : qv2::kBlockRows) / lanes;
       } else {
         // otherwise staged in LDS.  Rows per tile: what fits the LDS copy, but no more than a
         // few rounds of the row kernels (a round = one row per lane group of every wavefront),
@@ -182,14 +194,15 @@ static qv2_status plan_create(const qv2_tensor* h_tensors, int32_t n_tensors, qv
         tl.part0 = static_cast<int32_t>(row_part + r0); tl.rows = static_cast<int32_t>(rows);
         tl.seg0 = static_cast<int32_t>(seg0 + r0); tl.inner = static_cast<int32_t>(inner);
         tl.lanes = static_cast<int32_t>(lanes);
-        (reg_form ? p->reg_tiles : p->row_tiles).push_back(tl);
+        (form == qv2::kRowRegWide ? p->wide_tiles : reg_form ? p->reg_tiles : p->row_tiles).push_back(tl);
       }
       for (int64_t r = 0; r < nseg; ++r) {
         Segment s{};
-        s.n = inner; s.scheme = in.scheme;
+        s.n = inner; s.scheme = in.scheme; s.tensor = t;
         s.sp0 = s.ep0 = static_cast<int32_t>(row_part + r); s.snp = s.enp = 1;
         p->segments.push_back(s);
       }
+      p->row_tensors.push_back(t);
       row_part += nseg;
     } else {
       // without a code buffer the quantize sweep stores nothing: long tiles, as for a read-only pass
@@ -203,9 +216,10 @@ static qv2_status plan_create(const qv2_tensor* h_tensors, int32_t n_tensors, qv
       // partial slot per tile in that same order
       add_run(p->read_tiles, in, t, nseg, inner, TR, seg0, sp);
       add_run(in.codes ? p->quant_tiles : p->quant_ro_tiles, in, t, nseg, inner, TQt, seg0, ep);
+      if (nseg > 1) p->late_tensors.push_back(t);
       for (int64_t s = 0; s < nseg; ++s) {
         Segment sg{};
-        sg.n = inner; sg.scheme = in.scheme;
+        sg.n = inner; sg.scheme = in.scheme; sg.tensor = t;
         sg.sp0 = static_cast<int32_t>(sp); sg.snp = static_cast<int32_t>(n_read);
         sg.ep0 = static_cast<int32_t>(ep); sg.enp = static_cast<int32_t>(n_quant);
         p->segments.push_back(sg);
@@ -231,7 +245,8 @@ static qv2_status plan_create(const qv2_tensor* h_tensors, int32_t n_tensors, qv
   if (!launchable(p->read_tiles.n_tiles, qv2::kBlockRead) || !launchable(p->pair_tiles.n_tiles, qv2::kBlockRead) ||
       !launchable(p->quant_ro_tiles.n_tiles, qv2::kBlockRead) ||
       !launchable(p->quant_tiles.n_tiles, qv2::kBlockQuant) ||
-      !launchable(static_cast<int64_t>(std::max(p->row_tiles.size(), p->reg_tiles.size())), qv2::kBlockRows))
+      !launchable(static_cast<int64_t>(std::max(p->row_tiles.size(), p->reg_tiles.size())), qv2::kBlockRows) ||
+      !launchable(static_cast<int64_t>(p->wide_tiles.size()), qv2::kBlockRowsWide))
     return QV2_ERR_SHAPE;
   finish_table(p->read_tiles); finish_table(p->quant_tiles);
   finish_table(p->quant_ro_tiles); finish_table(p->pair_tiles);
@@ -292,15 +307,17 @@ int64_t qv2_plan_segment_begin(const qv2_plan* plan, int32_t t) {
   return plan->info[t].seg0;
 }
 int64_t qv2_plan_num_tiles(const qv2_plan* plan) {
-  return plan ? plan->read_tiles.n_tiles + static_cast<int64_t>(plan->row_tiles.size() + plan->reg_tiles.size()) : 0;
+  return plan ? plan->read_tiles.n_tiles + static_cast<int64_t>(plan->row_tiles.size() + plan->reg_tiles.size() +
+                                                                plan->wide_tiles.size()) : 0;
 }
 int64_t qv2_plan_num_quant_tiles(const qv2_plan* plan) {
   return plan ? plan->quant_tiles.n_tiles + plan->quant_ro_tiles.n_tiles +
-                    static_cast<int64_t>(plan->row_tiles.size() + plan->reg_tiles.size()) : 0;
+                    static_cast<int64_t>(plan->row_tiles.size() + plan->reg_tiles.size() + plan->wide_tiles.size()) : 0;
 }
 int64_t qv2_plan_num_pair_tiles(const qv2_plan* plan) {
   return plan ? plan->pair_tiles.n_tiles : 0;
 }
+int64_t qv2_plan_num_single_read_elements(const qv2_plan* plan) { return plan ? plan->n_single_read : 0; }
 size_t qv2_workspace_bytes(const qv2_plan* plan) { return plan ? plan->workspace_bytes : 0; }
 
 size_t qv2_histogram_workspace_bytes(const qv2_plan* plan, int32_t nbins) {

@@ -44,6 +44,14 @@ constexpr int kRowRegVecs = 16;
 constexpr int kRowRegMinLanes = 16;
 constexpr int kRowRegMinInner = 64;
 static_assert(kBlockRows * 4 * kRowRegVecs >= kRowGroupCap, "a whole row must fit the registers of one workgroup");
+// The register form also takes rows the LDS copy could not hold: up to kBlockRows * 64 elements
+// with the row kernels' usual workgroup (one row per workgroup), and up to kRowRegCap with a
+// workgroup of kBlockRowsWide threads.  A per-channel weight with rows that long (the first
+// fully connected layer of VGG-16: 4096 rows of 25088) is then read from HBM once, too.
+constexpr int kBlockRowsWide = 512;
+constexpr int kRowRegCap = kBlockRowsWide * 4 * kRowRegVecs;          // 32768 elements
+// How a per-channel tensor's rows are handled.
+enum RowForm { kRowStream = 0, kRowLds = 1, kRowReg = 2, kRowRegWide = 3 };
 // Stream-tile length of the read-only passes (128 KiB of fp32): long tiles amortise the
 // per-workgroup reduction.
 constexpr int kDefaultReadTile = 32768;
@@ -185,7 +193,7 @@ struct Segment {               // 32 B
   int32_t sp0, snp;            // calibration partials, in element order
   int32_t ep0, enp;            // quantize partials, in element order
   int32_t scheme;
-  int32_t _pad;
+  int32_t tensor;              // the tensor the segment belongs to
 };
 
 struct PairTensor {            // 16 B, one per tensor of the plan
@@ -224,6 +232,8 @@ struct qv2_plan {
                                          // them, so they are cut like the read-only passes' tiles
   std::vector<qv2::Tile> row_tiles;      // row-group tiles staged in LDS, used by both
   std::vector<qv2::Tile> reg_tiles;      // row-group tiles held in registers, used by both
+  std::vector<qv2::Tile> wide_tiles;     // ... one long row each, held by a workgroup of kBlockRowsWide threads
+  int64_t n_single_read = 0;             // elements of the tensors made of row-group tiles
   qv2::StreamTable pair_tiles;           // pair pass: stream tiles over tensors with qrun
   std::vector<qv2::Tile> hist_tiles;     // histogram pass: long chunks (part0 = chunk index)
   std::vector<qv2::HistTensor> hist_tensors;
@@ -237,6 +247,11 @@ struct qv2_plan {
   std::vector<int32_t> big_pair_tensors;
   std::vector<int32_t> big_fused_pair_tensors;
   std::vector<int32_t> big_stat_pair_tensors;
+  // per-tensor records made inside the last fold of a pass instead of by a launch of their own:
+  std::vector<int32_t> row_tensors;         // tensors made of row-group tiles (their segment records are
+                                            // final when that fold starts): one workgroup each
+  std::vector<int32_t> late_tensors;        // tensors of several stream segments, whose records that same
+                                            // fold launch only just writes: a small launch after it
   int32_t read_tile = qv2::kDefaultReadTile;
   int32_t quant_tile = qv2::kDefaultQuantTile;
   bool rows_have_pair = false;           // some row-group tensor has a quantized-run partner
@@ -252,6 +267,7 @@ struct qv2_plan {
   qv2::StreamView d_pair_tiles = {};
   qv2::Tile* d_row_tiles = nullptr;
   qv2::Tile* d_reg_tiles = nullptr;
+  qv2::Tile* d_wide_tiles = nullptr;
   qv2::Tile* d_hist_tiles = nullptr;
   qv2::HistTensor* d_hist_tensors = nullptr;
   qv2::Segment* d_segments = nullptr;
@@ -263,6 +279,8 @@ struct qv2_plan {
   int32_t* d_big_pair_tensors = nullptr;
   int32_t* d_big_fused_pair_tensors = nullptr;
   int32_t* d_big_stat_pair_tensors = nullptr;
+  int32_t* d_row_tensors = nullptr;
+  int32_t* d_late_tensors = nullptr;
 
   // optional per-kernel timing (qv2_plan_set_timing): hipEvent_t handles
   bool timing = false;

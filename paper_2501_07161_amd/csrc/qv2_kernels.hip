@@ -84,7 +84,7 @@ struct BlobBuilder {
 };
 
 struct BlobLayout {
-  size_t run[4], coarse[4], row, reg, seg, pt, ft, st, bs, be, bp, bf, bst, ht, hten;
+  size_t run[4], coarse[4], row, reg, wide, seg, pt, ft, st, bs, be, bp, bf, bst, ht, hten, rowt, latet;
 };
 
 const StreamTable* stream_tables(const qv2_plan* p, int i) {
@@ -98,13 +98,14 @@ BlobLayout build_blob(const qv2_plan* p, BlobBuilder& b) {
     o.run[i] = b.put(stream_tables(p, i)->runs);
     o.coarse[i] = b.put(stream_tables(p, i)->coarse);
   }
-  o.row = b.put(p->row_tiles); o.reg = b.put(p->reg_tiles);
+  o.row = b.put(p->row_tiles); o.reg = b.put(p->reg_tiles); o.wide = b.put(p->wide_tiles);
   o.seg = b.put(p->segments); o.pt = b.put(p->pair_tensors); o.ft = b.put(p->fused_pair_tensors);
   o.st = b.put(p->stat_pair_tensors);
   o.bs = b.put(p->big_stat_segments); o.be = b.put(p->big_err_segments);
   o.bp = b.put(p->big_pair_tensors); o.bf = b.put(p->big_fused_pair_tensors);
   o.bst = b.put(p->big_stat_pair_tensors);
   o.ht = b.put(p->hist_tiles); o.hten = b.put(p->hist_tensors);
+  o.rowt = b.put(p->row_tensors); o.latet = b.put(p->late_tensors);
   return o;
 }
 
@@ -113,12 +114,14 @@ size_t blob_bytes(const qv2_plan* p) {
   size_t total = 256;
   for (int i = 0; i < 4; ++i)
     total += sec(bytes_of(stream_tables(p, i)->runs)) + sec(bytes_of(stream_tables(p, i)->coarse));
-  total += sec(bytes_of(p->row_tiles)) + sec(bytes_of(p->reg_tiles)) + sec(bytes_of(p->segments)) +
+  total += sec(bytes_of(p->row_tiles)) + sec(bytes_of(p->reg_tiles)) + sec(bytes_of(p->wide_tiles)) +
+           sec(bytes_of(p->segments)) +
            sec(bytes_of(p->pair_tensors)) + sec(bytes_of(p->fused_pair_tensors)) +
            sec(bytes_of(p->stat_pair_tensors)) + sec(bytes_of(p->big_stat_segments)) +
            sec(bytes_of(p->big_err_segments)) + sec(bytes_of(p->big_pair_tensors)) +
            sec(bytes_of(p->big_fused_pair_tensors)) + sec(bytes_of(p->big_stat_pair_tensors)) +
-           sec(bytes_of(p->hist_tiles)) + sec(bytes_of(p->hist_tensors));
+           sec(bytes_of(p->hist_tiles)) + sec(bytes_of(p->hist_tensors)) + sec(bytes_of(p->row_tensors)) +
+           sec(bytes_of(p->late_tensors));
   return total;
 }
 
@@ -157,6 +160,7 @@ qv2_status upload(qv2_plan* p, hipStream_t s) {
   }
   p->d_row_tiles = reinterpret_cast<Tile*>(blob + o.row);
   p->d_reg_tiles = reinterpret_cast<Tile*>(blob + o.reg);
+  p->d_wide_tiles = reinterpret_cast<Tile*>(blob + o.wide);
   p->d_segments = reinterpret_cast<Segment*>(blob + o.seg);
   p->d_pair_tensors = reinterpret_cast<PairTensor*>(blob + o.pt);
   p->d_fused_pair_tensors = reinterpret_cast<PairTensor*>(blob + o.ft);
@@ -168,6 +172,8 @@ qv2_status upload(qv2_plan* p, hipStream_t s) {
   p->d_big_stat_pair_tensors = reinterpret_cast<int32_t*>(blob + o.bst);
   p->d_hist_tiles = reinterpret_cast<Tile*>(blob + o.ht);
   p->d_hist_tensors = reinterpret_cast<HistTensor*>(blob + o.hten);
+  p->d_row_tensors = reinterpret_cast<int32_t*>(blob + o.rowt);
+  p->d_late_tensors = reinterpret_cast<int32_t*>(blob + o.latet);
   p->d_blob = blob;
   p->device = dev;
   (void)scratch_on_device(dev);      // set-up time: the entry point that allocates nothing finds it ready
@@ -201,11 +207,14 @@ struct Timed {
 
 int fold_grid(int n) { return (n + 3) / 4; }
 
-// row-group tiles of a quantize pass, both forms; d_params_out != null: with calibration
+// row-group tiles of a quantize pass, all forms; d_params_out != null: with calibration
 template <bool PAIR, bool COS>
 void launch_rows(qv2_plan* plan, const qv2_qparams* d_params, qv2_qparams* d_params_out, qv2_sums* d_sums,
-                 typename ErrRec<COS>::type* parts, int n_rows, int n_regs, hipStream_t s) {
+                 typename ErrRec<COS>::type* parts, hipStream_t s) {
   const bool calib = d_params_out != nullptr;
+  const int n_rows = static_cast<int>(plan->row_tiles.size());
+  const int n_regs = static_cast<int>(plan->reg_tiles.size());
+  const int n_wide = static_cast<int>(plan->wide_tiles.size());
   if (n_rows > 0) {
     if (calib)
       hipLaunchKernelGGL((k_quant_rows<kBlockRows, PAIR, COS, true>), dim3(n_rows), dim3(kBlockRows), 0, s,
@@ -222,6 +231,16 @@ void launch_rows(qv2_plan* plan, const qv2_qparams* d_params, qv2_qparams* d_par
     else
       hipLaunchKernelGGL((k_rows_reg<kBlockRows, 1, PAIR, COS>), dim3(n_regs), dim3(kBlockRows), 0, s,
                          plan->d_reg_tiles, plan->d_segments, d_params, d_params_out, d_sums,
+                         static_cast<void*>(parts));
+  }
+  if (n_wide > 0) {
+    if (calib)
+      hipLaunchKernelGGL((k_rows_reg<kBlockRowsWide, 2, PAIR, COS>), dim3(n_wide), dim3(kBlockRowsWide), 0, s,
+                         plan->d_wide_tiles, plan->d_segments, d_params, d_params_out, d_sums,
+                         static_cast<void*>(parts));
+    else
+      hipLaunchKernelGGL((k_rows_reg<kBlockRowsWide, 1, PAIR, COS>), dim3(n_wide), dim3(kBlockRowsWide), 0, s,
+                         plan->d_wide_tiles, plan->d_segments, d_params, d_params_out, d_sums,
                          static_cast<void*>(parts));
   }
 }
@@ -246,12 +265,12 @@ template <bool PAIR, bool COS>
 void launch_quant(qv2_plan* plan, const qv2_qparams* d_params, qv2_sums* d_sums,
                   typename ErrRec<COS>::type* parts, double* d_seg_xxhat, qv2_pair_sums* d_pair_sums,
                   double* d_pair_xq, hipStream_t s, qv2_qparams* d_params_out = nullptr,
-                  bool pair_in_stats = false) {
+                  bool pair_in_stats = false, qv2_tensor_sums* d_ts = nullptr) {
   typedef typename ErrRec<COS>::type P;
   const bool calib_rows = d_params_out != nullptr;
   const int n_stream = static_cast<int>(plan->quant_tiles.n_tiles);
   const int n_ro = static_cast<int>(plan->quant_ro_tiles.n_tiles);
-  const int n_rows = static_cast<int>(plan->row_tiles.size());
+  const int n_rows = static_cast<int>(plan->row_tiles.size() + plan->reg_tiles.size() + plan->wide_tiles.size());
   if (n_stream + n_ro > 0) {
     // pair_in_stats: the calibration sweep already compared the stream tensors with their
     // partners, so the plain quantize kernel serves them
@@ -263,14 +282,13 @@ void launch_quant(qv2_plan* plan, const qv2_qparams* d_params, qv2_sums* d_sums,
     else
       launch_quant_stream<false, COS, true>(plan, n_stream, n_ro, d_params, parts, s);
   }
-  const int n_regs = static_cast<int>(plan->reg_tiles.size());
-  if (n_rows + n_regs > 0) {
+  if (n_rows > 0) {
     Timed timed(plan, calib_rows ? QV2_K_SINGLE_READ_ROWS : PAIR ? QV2_K_QUANTPAIR_ROWS : QV2_K_QUANT_ROWS, s);
     // the pair form of the row kernels costs registers: only when a row tensor has a partner
     if (PAIR && plan->rows_have_pair)
-      launch_rows<true, COS>(plan, d_params, d_params_out, d_sums, parts, n_rows, n_regs, s);
+      launch_rows<true, COS>(plan, d_params, d_params_out, d_sums, parts, s);
     else
-      launch_rows<false, COS>(plan, d_params, d_params_out, d_sums, parts, n_rows, n_regs, s);
+      launch_rows<false, COS>(plan, d_params, d_params_out, d_sums, parts, s);
   }
   QuantFoldArgs<P> a{};
   a.segs = plan->d_segments; a.nseg = static_cast<int>(plan->segments.size());
@@ -286,9 +304,20 @@ void launch_quant(qv2_plan* plan, const qv2_qparams* d_params, qv2_sums* d_sums,
     a.n_wide_pt = static_cast<int>(plan->big_fused_pair_tensors.size());
     a.pair_out = d_pair_sums; a.pair_xq = d_pair_xq;
     a.pair_done = pair_in_stats ? plan->d_stat_pair_tensors : nullptr;
-    blocks += fold_blocks(a.n_wide_pt, a.nt);
+    a.pair_blocks = fold_blocks(a.n_wide_pt, a.nt);
+    blocks += a.pair_blocks;
+  }
+  if (d_ts) {
+    // the whole pass: this fold also leaves the per-tensor records.  The rows' segment records
+    // are final by now (calib_rows), so the tensors made of them get one workgroup each here.
+    a.ts = d_ts; a.params = d_params; a.ht = plan->d_hist_tensors; a.row_tensors = plan->d_row_tensors;
+    blocks += static_cast<int>(plan->row_tensors.size());
   }
   hipLaunchKernelGGL(k_fold_quant<P>, dim3(blocks), dim3(kFoldBlock), 0, s, a);
+  // tensors of several stream segments: their segment records were written by that very launch
+  if (d_ts && !plan->late_tensors.empty())
+    hipLaunchKernelGGL(k_tensor_fold, dim3(static_cast<int>(plan->late_tensors.size())), dim3(kFoldBlock), 0, s,
+                       plan->d_hist_tensors, plan->d_late_tensors, d_params, d_sums, d_ts);
 }
 
 // calibration over the stream tiles (and the row-group tiles unless their own single-read
@@ -308,7 +337,8 @@ void launch_stats(qv2_plan* plan, qv2_qparams* d_params, qv2_sums* d_sums,
                        plan->d_read_tiles, parts);
   }
   const int n_regs = static_cast<int>(plan->reg_tiles.size());
-  if (with_rows && n_rows + n_regs > 0) {
+  const int n_wide = static_cast<int>(plan->wide_tiles.size());
+  if (with_rows && n_rows + n_regs + n_wide > 0) {
     Timed timed(plan, QV2_K_STATS_ROWS, s);
     if (n_rows > 0)
       hipLaunchKernelGGL(k_stats_rows<kBlockRows>, dim3(n_rows), dim3(kBlockRows), 0, s,
@@ -316,6 +346,11 @@ void launch_stats(qv2_plan* plan, qv2_qparams* d_params, qv2_sums* d_sums,
     if (n_regs > 0)
       hipLaunchKernelGGL((k_rows_reg<kBlockRows, 0, false, false>), dim3(n_regs), dim3(kBlockRows), 0, s,
                          plan->d_reg_tiles, plan->d_segments, static_cast<const qv2_qparams*>(nullptr),
+                         static_cast<qv2_qparams*>(nullptr), static_cast<qv2_sums*>(nullptr),
+                         static_cast<void*>(parts));
+    if (n_wide > 0)
+      hipLaunchKernelGGL((k_rows_reg<kBlockRowsWide, 0, false, false>), dim3(n_wide), dim3(kBlockRowsWide), 0, s,
+                         plan->d_wide_tiles, plan->d_segments, static_cast<const qv2_qparams*>(nullptr),
                          static_cast<qv2_qparams*>(nullptr), static_cast<qv2_sums*>(nullptr),
                          static_cast<void*>(parts));
   }
@@ -338,9 +373,10 @@ void launch_stats(qv2_plan* plan, qv2_qparams* d_params, qv2_sums* d_sums,
   }
 }
 
-// steps 1-3 of the single call, on a workspace of at least plan->workspace_bytes
+// steps 1-3 of the single call, on a workspace of at least plan->workspace_bytes; d_ts != null
+// (needs d_pair_sums): the per-tensor records as well, made inside the last fold
 void single_call(qv2_plan* plan, qv2_qparams* d_params, qv2_sums* d_sums, qv2_pair_sums* d_pair_sums,
-                 void* d_workspace, hipStream_t s) {
+                 void* d_workspace, hipStream_t s, qv2_tensor_sums* d_ts = nullptr) {
   // stream tiles: statistics (with the pair comparison: that sweep only reads, and read-only
   // sweeps run nearest to the HBM rate), fold (parameters), then the plain quantize sweep;
   // row-group tiles: one kernel, after the statistics fold because the partial records share
@@ -349,7 +385,8 @@ void single_call(qv2_plan* plan, qv2_qparams* d_params, qv2_sums* d_sums, qv2_pa
   if (d_pair_sums) {
     launch_stats<true>(plan, d_params, d_sums, static_cast<StatPairPartial*>(d_workspace), false, d_pair_sums,
                        nullptr, s);
-    launch_quant<true, false>(plan, d_params, d_sums, parts, nullptr, d_pair_sums, nullptr, s, d_params, true);
+    launch_quant<true, false>(plan, d_params, d_sums, parts, nullptr, d_pair_sums, nullptr, s, d_params, true,
+                              d_ts);
   } else {
     launch_stats<false>(plan, d_params, d_sums, static_cast<StatPartial*>(d_workspace), false, nullptr, nullptr, s);
     launch_quant<false, false>(plan, d_params, d_sums, parts, nullptr, nullptr, nullptr, s, d_params);
@@ -554,8 +591,8 @@ qv2_status qv2_tensor_sums_fold(qv2_plan* plan, const qv2_qparams* d_params, con
   qv2_status st = ensure_uploaded(plan);
   if (st != QV2_OK) return st;
   const int nt = static_cast<int>(plan->info.size());
-  hipLaunchKernelGGL(k_tensor_fold, dim3(nt), dim3(256), 0, static_cast<hipStream_t>(hip_stream),
-                     plan->d_hist_tensors, nt, d_params, d_sums, d_tensor_sums);
+  hipLaunchKernelGGL(k_tensor_fold, dim3(nt), dim3(kFoldBlock), 0, static_cast<hipStream_t>(hip_stream),
+                     plan->d_hist_tensors, static_cast<const int*>(nullptr), d_params, d_sums, d_tensor_sums);
   return launch_status();
 }
 
@@ -571,10 +608,12 @@ qv2_status pass_enqueue(qv2_plan* plan, qv2_qparams* d_params, qv2_sums* d_sums,
   const size_t ts_bytes = nt * sizeof(qv2_tensor_sums);
   qv2_tensor_sums* d_ts = static_cast<qv2_tensor_sums*>(d_records);
   qv2_pair_sums* d_pair = reinterpret_cast<qv2_pair_sums*>(static_cast<char*>(d_records) + ts_bytes);
-  qv2_status st = qv2_calibrate_fakequant_pair_metrics(plan, d_params, d_sums, d_pair, d_workspace,
-                                                       workspace_bytes, hip_stream);
+  qv2_status st = check_call(plan, d_params, d_sums, d_workspace, workspace_bytes);
   if (st != QV2_OK) return st;
-  if ((st = qv2_tensor_sums_fold(plan, d_params, d_sums, d_ts, hip_stream)) != QV2_OK) return st;
+  if ((st = ensure_uploaded(plan)) != QV2_OK) return st;
+  // the single call; its last fold also makes the per-tensor records
+  single_call(plan, d_params, d_sums, d_pair, d_workspace, static_cast<hipStream_t>(hip_stream), d_ts);
+  if ((st = launch_status()) != QV2_OK) return st;
   if (hipMemcpyAsync(h_records, d_records, ts_bytes + nt * sizeof(qv2_pair_sums), hipMemcpyDeviceToHost,
                      static_cast<hipStream_t>(hip_stream)) != hipSuccess) {
     (void)hipGetLastError();

@@ -112,8 +112,8 @@ void check_plan(const std::vector<qv2_tensor>& rows) {
       CHECK(p->segments[nseg + k].scheme == in.scheme);
     }
     nseg += s;
-    check_cover({&read_tiles, &p->row_tiles, &p->reg_tiles}, in, t, true);
-    check_cover({&quant_tiles, &quant_ro_tiles, &p->row_tiles, &p->reg_tiles}, in, t, true);
+    check_cover({&read_tiles, &p->row_tiles, &p->reg_tiles, &p->wide_tiles}, in, t, true);
+    check_cover({&quant_tiles, &quant_ro_tiles, &p->row_tiles, &p->reg_tiles, &p->wide_tiles}, in, t, true);
     check_cover({&p->hist_tiles}, in, t, true);
     check_cover({&pair_tiles}, in, t, in.qrun != nullptr);
     if (!in.qrun) {
@@ -126,9 +126,10 @@ void check_plan(const std::vector<qv2_tensor>& rows) {
   CHECK(qv2_plan_num_segments(p) == nseg);
   CHECK(static_cast<int64_t>(p->segments.size()) == nseg);
   CHECK(qv2_plan_num_tiles(p) ==
-        static_cast<int64_t>(read_tiles.size() + p->row_tiles.size() + p->reg_tiles.size()));
+        static_cast<int64_t>(read_tiles.size() + p->row_tiles.size() + p->reg_tiles.size() + p->wide_tiles.size()));
   CHECK(qv2_plan_num_quant_tiles(p) ==
-        static_cast<int64_t>(quant_tiles.size() + quant_ro_tiles.size() + p->row_tiles.size() + p->reg_tiles.size()));
+        static_cast<int64_t>(quant_tiles.size() + quant_ro_tiles.size() + p->row_tiles.size() + p->reg_tiles.size() +
+                             p->wide_tiles.size()));
   CHECK(qv2_plan_num_pair_tiles(p) == static_cast<int64_t>(pair_tiles.size()));
 
   // partial slots: every slot of a numbering is written by exactly one (tile, row), lies in
@@ -141,7 +142,7 @@ void check_plan(const std::vector<qv2_tensor>& rows) {
     if (tl.rows > 0) {
       CHECK(static_cast<int64_t>(tl.rows) * tl.inner == tl.len);
       if (tl.lanes == 0) CHECK(tl.len <= qv2::kRowGroupCap && tl.rows <= qv2::kRowGroupMaxRows);   // LDS copy
-      else CHECK(tl.len <= qv2::kBlockRows * 4 * qv2::kRowRegVecs && tl.inner <= qv2::kRowGroupCap);
+      else CHECK(tl.len <= qv2::kRowRegCap && tl.inner <= qv2::kRowRegCap);
       CHECK(tl.seg0 + tl.rows <= nseg);
       CHECK(tl.part0 + tl.rows <= p->n_row_parts);
       for (int r = 0; r < tl.rows; ++r) {
@@ -168,11 +169,15 @@ void check_plan(const std::vector<qv2_tensor>& rows) {
   for (const Tile& tl : quant_tiles) { CHECK(tl.rows == 0 && tl.len <= p->quant_tile && tl.c); mark(tl, false, true); }
   for (const Tile& tl : quant_ro_tiles) { CHECK(tl.rows == 0 && tl.len <= p->read_tile && !tl.c); mark(tl, false, true); }
   for (const Tile& tl : p->row_tiles) { CHECK(tl.rows > 0 && tl.lanes == 0); mark(tl, true, true); }
-  for (const Tile& tl : p->reg_tiles) {
+  for (int wide = 0; wide < 2; ++wide)
+  for (const Tile& tl : wide ? p->wide_tiles : p->reg_tiles) {
     // register form: whole vectors on 16-byte boundaries, a row fits its lanes, the rows fit the workgroup
+    const int block = wide ? qv2::kBlockRowsWide : qv2::kBlockRows;
     CHECK(tl.rows > 0 && tl.inner % 4 == 0 && tl.inner >= qv2::kRowRegMinInner);
-    CHECK(tl.lanes >= qv2::kRowRegMinLanes && tl.lanes <= qv2::kBlockRows && (tl.lanes & (tl.lanes - 1)) == 0);
-    CHECK(tl.lanes * 4 * qv2::kRowRegVecs >= tl.inner && tl.rows * tl.lanes <= qv2::kBlockRows);
+    CHECK(tl.lanes >= qv2::kRowRegMinLanes && tl.lanes <= block && (tl.lanes & (tl.lanes - 1)) == 0);
+    CHECK(tl.lanes * 4 * qv2::kRowRegVecs >= tl.inner && tl.rows * tl.lanes <= block);
+    CHECK(wide == (tl.inner > qv2::kBlockRows * 4 * qv2::kRowRegVecs));
+    CHECK(static_cast<int64_t>(tl.rows) * tl.inner == tl.len);
     CHECK((reinterpret_cast<uintptr_t>(tl.x) & 15u) == 0);
     CHECK(tl.q == nullptr || (reinterpret_cast<uintptr_t>(tl.q) & 15u) == 0);
     CHECK(tl.c == nullptr || (reinterpret_cast<uintptr_t>(tl.c) & 3u) == 0);

@@ -136,6 +136,34 @@ def test_per_channel_rows_held_in_registers(fused):
 
 
 @pytest.mark.parametrize("fused", [False, True, "single"])
+def test_long_per_channel_rows_held_in_registers(fused):
+    """Rows beyond what the LDS copy holds: 8196 ... 16384 elements take one row per 256-thread
+    workgroup, 16388 ... 32768 (the 25088 of VGG-16's first fully connected layer among them)
+    one row per 512-thread workgroup; 32772 is a stream row again.  With and without partners,
+    last vectors partly populated, a dead channel; plus the same lengths where the register form
+    does not apply (base 4 bytes off a 16-byte boundary, code buffer 1 byte off)."""
+    items = []
+    shapes = [(3, 8196), (5, 12288), (2, 16384), (3, 16388), (4, 25088), (2, 32764), (2, 32768), (2, 32772)]
+    for i, (c, inner) in enumerate(shapes):
+        x = _rand(c * inner, 850 + i, 0.1)
+        if i % 3 == 0:
+            x.view(c, inner)[c // 2] = 0.0
+        q = (x * 0.98 + 0.0007) if i % 2 == 0 else None
+        items.append(H.Item(f"long{c}x{inner}", x, C, c, 0, len(items), qrun=q))
+    for i, (c, inner) in enumerate([(2, 12288), (2, 25088)]):
+        base = _rand(c * inner + 4, 870 + i, 0.1)
+        items.append(H.Item(f"long{c}x{inner}.off1", base[1: 1 + c * inner], C, c, 0, len(items)))
+        items.append(H.Item(f"long{c}x{inner}.codes1", _rand(c * inner, 880 + i, 0.1), C, c, 0, len(items),
+                            codes_offset=1))
+    res = H.run_gpu(items, fused=fused)
+    H.check_all(items, res)
+    # the forms the plan chose: 256-thread rows, 512-thread rows, stream tiles
+    once = [qb.qv2_plan_create([qb.TensorArg(x=it.x, numel=it.x.numel(), scheme=C, channels=it.channels,
+                                             codes=it.codes)]).num_single_read_elements > 0 for it in items]
+    assert once == [True] * 7 + [False] + [False] * 4
+
+
+@pytest.mark.parametrize("fused", [False, True, "single"])
 def test_degenerate_and_special_values(fused):
     z = torch.zeros(5000, device=DEV)
     const = torch.full((4097,), 3.25, device=DEV)
@@ -640,3 +668,48 @@ def test_large_pair_at_different_offsets_inside_16_bytes(fused):
                                 codes_offset=(ox + oq) % 4))
     res = H.run_gpu(items, fused=fused)
     H.check_all(items, res)
+
+
+def test_pass_records_equal_single_call_plus_tensor_fold():
+    """qv2_sensitivity_pass makes its per-tensor records inside its last fold launch (single-segment
+    tensors with their segment, row-group tensors by one more workgroup each, tensors of several
+    stream segments by a small launch after it); they must be, bit for bit, what the single call
+    followed by qv2_tensor_sums_fold gives, and so must parameters, sums and codes."""
+    specs = synth.config_mobilenetv2(2)
+    items = H.items_from_specs(specs, DEV)
+    for it in items:
+        if it.kind == synth.ACTIVATION:
+            it.qrun = it.x * 0.98 + 0.003
+    n0 = len(items)
+    # rows held by 512-thread workgroups, rows cut into stream tiles (odd length: several segments
+    # per tensor), a one-channel row tensor, a weight with a partner in the row kernels
+    extra = [H.Item("wide", _rand(5 * 25088, 901, 0.1), C, 5, synth.WEIGHT, 0),
+             H.Item("late", _rand(3 * 20001, 902, 0.1), C, 3, synth.WEIGHT, 0),
+             H.Item("one-row", _rand(576, 903, 0.1), C, 1, synth.WEIGHT, 0),
+             H.Item("row+pair", _rand(64 * 576, 904, 0.1), C, 64, synth.WEIGHT, 0)]
+    extra[3].qrun = extra[3].x * 1.01
+    n_layers = max(it.layer for it in items[:n0]) + 2
+    for it in extra[:3]:
+        it.kind, it.layer = 2, 0                   # neither weight nor activation: not ranked
+    extra[3].layer = n_layers - 1                  # one more layer: this weight and an activation
+    act = H.Item("extra.out", torch.relu(_rand(40_000, 905)), A, 1, synth.ACTIVATION, n_layers - 1)
+    act.qrun = act.x * 0.99
+    items += extra + [act]
+    res = H.run_gpu(items, fused="single")
+    want_codes = [it.codes.clone() for it in items]
+    buf = qb.Buffers(res.plan, DEV)
+    out = qb.PassOutputs(res.plan, n_layers, DEV)
+    for it in items:
+        it.codes.fill_(0x33)
+    qb.qv2_sensitivity_pass(res.plan, buf.params, buf.sums, out, buf.workspace)
+    p, s, _ = buf.host()
+    assert p.tobytes() == res.params.tobytes() and s.tobytes() == res.sums.tobytes()
+    assert out.tensor_sums.tobytes() == res.tsums.tobytes()
+    assert out.pair_sums.tobytes() == res.pair.tobytes()
+    assert all(torch.equal(it.codes, w) for it, w in zip(items, want_codes))
+    # and the two halves of the pass give the same again
+    prep = qb.PreparedPass(res.plan, buf.params, buf.sums, [out, qb.PassOutputs(res.plan, n_layers, DEV)],
+                           buf.workspace)
+    prep.begin(1)
+    o1 = prep.end(1)
+    assert o1.tensor_sums.tobytes() == res.tsums.tobytes() and o1.order.tolist() == out.order.tolist()
