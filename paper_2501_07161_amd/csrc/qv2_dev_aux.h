@@ -191,9 +191,10 @@ __global__ __launch_bounds__(kFoldBlock) void k_tensor_fold(const HistTensor* __
                                                             const int* __restrict__ list,
                                                             const qv2_qparams* __restrict__ params,
                                                             const qv2_sums* __restrict__ sums,
-                                                            qv2_tensor_sums* __restrict__ out) {
+                                                            qv2_tensor_sums* __restrict__ out,
+                                                            ptrdiff_t mirror) {
   const int t = list ? list[blockIdx.x] : blockIdx.x;
-  tensor_record(ht[t], params, sums, out + t);
+  tensor_record(ht[t], params, sums, out + t, mirror);
 }
 
 // ---------------------------------------------------------------------------

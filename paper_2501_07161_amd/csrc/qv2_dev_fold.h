@@ -14,6 +14,15 @@ namespace {
 // ---------------------------------------------------------------------------
 constexpr int kFoldPerBlock = kFoldBlock / kWave;
 
+// A result record goes to its place in device memory and, when `mirror` is not 0, also to the
+// address that many bytes further on: the same record in pinned host memory, mapped into the
+// device's address space, so that a caller's results arrive without a copy after the kernels.
+template <class T>
+__device__ __forceinline__ void put_record(T* dst, const T& o, ptrdiff_t mirror) {
+  *dst = o;
+  if (mirror) *reinterpret_cast<T*>(reinterpret_cast<char*>(dst) + mirror) = o;
+}
+
 struct FoldIdx {
   int id, lane, stride;
   bool wide, active;
@@ -83,7 +92,7 @@ template <class REC>
 __device__ __forceinline__ void fold_statpair_item(const FoldIdx& f, const PairTensor* __restrict__ pt,
                                                    const REC* __restrict__ parts,
                                                    qv2_pair_sums* __restrict__ out,
-                                                   double* __restrict__ pair_xq) {
+                                                   double* __restrict__ pair_xq, ptrdiff_t mirror) {
   if (!f.active) return;
   const PairTensor p = pt[f.id];
   if (p.n == 0) return;
@@ -98,7 +107,7 @@ __device__ __forceinline__ void fold_statpair_item(const FoldIdx& f, const PairT
   if (f.lane == 0) {
     qv2_pair_sums o;
     o.sum_ref2 = sr2; o.sum_d2 = sd2; o.n = p.n; o._pad = 0;
-    out[f.id] = o;
+    put_record(out + f.id, o, mirror);
     if (pair_xq) pair_xq[f.id] = sxq;
   }
 }
@@ -110,12 +119,14 @@ struct StatFoldArgs {
   const PairTensor* pt; int nt; const int* wide_pt; int n_wide_pt;     // pair_out == null: none
   qv2_pair_sums* pair_out; double* pair_xq;
   int seg_blocks;
+  ptrdiff_t mirror;                          // see put_record; 0 = none
 };
 
 __device__ __forceinline__ void fold_statpair_family(const StatFoldArgs<StatPartial>&, int) {}
 template <class REC>
 __device__ __forceinline__ void fold_statpair_family(const StatFoldArgs<REC>& a, int b) {
-  fold_statpair_item<REC>(FoldIdx(b, a.wide_pt, a.n_wide_pt, a.nt), a.pt, a.parts, a.pair_out, a.pair_xq);
+  fold_statpair_item<REC>(FoldIdx(b, a.wide_pt, a.n_wide_pt, a.nt), a.pt, a.parts, a.pair_out, a.pair_xq,
+                          a.mirror);
 }
 
 template <class REC>
@@ -128,7 +139,11 @@ __global__ __launch_bounds__(kFoldBlock) void k_fold_stats(const StatFoldArgs<RE
     fold_statpair_family(a, b - a.seg_blocks);
 }
 
-// cross terms of a partial record (0 where the record has none)
+// fields of a partial record (0 where the record has none)
+__device__ __forceinline__ double part_sx2(const ErrPartial1&) { return 0.0; }
+__device__ __forceinline__ double part_sx2(const ErrPartial3& p) { return p.sx2; }
+__device__ __forceinline__ double part_sx2(const ErrPartial5& p) { return p.sx2; }
+__device__ __forceinline__ double cross_xh(const ErrPartial1&) { return 0.0; }
 __device__ __forceinline__ double cross_xh(const ErrPartial3&) { return 0.0; }
 __device__ __forceinline__ double cross_xh(const ErrPartial5& p) { return p.sxh; }
 __device__ __forceinline__ double cross_xq(const ErrPartial&) { return 0.0; }
@@ -143,7 +158,7 @@ __device__ __forceinline__ double pair_energy(const ErrPartial5& p) { return p.s
 // strided over the segments, a butterfly per wavefront, then the wavefronts in order.
 __device__ __forceinline__ void tensor_record(const HistTensor h, const qv2_qparams* __restrict__ params,
                                               const qv2_sums* __restrict__ sums,
-                                              qv2_tensor_sums* __restrict__ out_rec) {
+                                              qv2_tensor_sums* __restrict__ out_rec, ptrdiff_t mirror) {
   __shared__ long long scnt[kFoldBlock / kWave];
   const int tid = threadIdx.x;
   float mn = INFINITY, mx = -INFINITY;
@@ -166,19 +181,22 @@ __device__ __forceinline__ void tensor_record(const HistTensor h, const qv2_qpar
     for (int w = 0; w < kFoldBlock / kWave; ++w) n += scnt[w];
     o.n = n;
     o._pad[0] = o._pad[1] = 0;
-    *out_rec = o;
+    put_record(out_rec, o, mirror);
   }
 }
 
 // error energies of one segment.  ts != null (the last fold of a whole pass): a tensor that is this
 // one segment gets its per-tensor record here as well - the same values tensor_record would give.
-template <class P>
+// P: the records of the row-group tiles; SP: those of the stream tiles (the same type, except
+// in the last fold of a whole pass, whose quantize sweep leaves only one energy per tile).
+template <class P, class SP>
 __device__ __forceinline__ void fold_err_item(const FoldIdx& f, const Segment* __restrict__ segs,
-                                              const P* __restrict__ parts, qv2_sums* __restrict__ sums,
+                                              const P* __restrict__ parts, const SP* __restrict__ sparts,
+                                              qv2_sums* __restrict__ sums,
                                               double* __restrict__ seg_xxhat, int skip_below,
                                               bool keep_x2, qv2_tensor_sums* __restrict__ ts = nullptr,
                                               const qv2_qparams* __restrict__ params = nullptr,
-                                              const HistTensor* __restrict__ ht = nullptr) {
+                                              const HistTensor* __restrict__ ht = nullptr, ptrdiff_t mirror = 0) {
   if (!f.active) return;
   const Segment sg = segs[f.id];
   if (!f.wide && sg.enp > kFoldWaveMax) return;
@@ -189,8 +207,8 @@ __device__ __forceinline__ void fold_err_item(const FoldIdx& f, const Segment* _
   double sx2 = 0.0, se2 = 0.0, sxh = 0.0;
 #pragma unroll 4
   for (int i = f.lane; i < sg.enp; i += f.stride) {
-    const P q = parts[sg.ep0 + i];
-    sx2 += q.sx2; se2 += q.se2; sxh += cross_xh(q);
+    const SP q = sparts[sg.ep0 + i];
+    sx2 += part_sx2(q); se2 += q.se2; sxh += cross_xh(q);
   }
   fold_sum3(f.wide, sx2, se2, sxh);
   if (f.lane == 0) {
@@ -203,7 +221,7 @@ __device__ __forceinline__ void fold_err_item(const FoldIdx& f, const Segment* _
       o.sum_x = 0.0 + sums[f.id].sum_x; o.sum_x2 = 0.0 + (keep_x2 ? sums[f.id].sum_x2 : sx2);
       o.sum_e2 = 0.0 + se2; o.n = sg.n; o.min = p.min; o.max = p.max;
       o._pad[0] = o._pad[1] = 0;
-      ts[sg.tensor] = o;
+      put_record(ts + sg.tensor, o, mirror);
     }
   }
 }
@@ -213,7 +231,8 @@ template <class P>
 __device__ __forceinline__ void fold_pair_item(const FoldIdx& f, const PairTensor* __restrict__ pt,
                                                const P* __restrict__ parts, qv2_pair_sums* __restrict__ out,
                                                double* __restrict__ pair_xq,
-                                               const PairTensor* __restrict__ done = nullptr) {
+                                               const PairTensor* __restrict__ done = nullptr,
+                                               ptrdiff_t mirror = 0) {
   if (!f.active) return;
   if (done && done[f.id].n != 0) return;           // already folded from the calibration partials
   const PairTensor p = pt[f.id];
@@ -228,7 +247,7 @@ __device__ __forceinline__ void fold_pair_item(const FoldIdx& f, const PairTenso
   if (f.lane == 0) {
     qv2_pair_sums o;
     o.sum_ref2 = sr2; o.sum_d2 = sd2; o.n = p.n; o._pad = 0;
-    out[f.id] = o;
+    put_record(out + f.id, o, mirror);
     if (pair_xq) pair_xq[f.id] = sxq;
   }
 }
@@ -242,26 +261,29 @@ struct QuantFoldArgs {
   const PairTensor* pt; int nt; const int* wide_pt; int n_wide_pt;     // pair_out == null: none
   qv2_pair_sums* pair_out; double* pair_xq;
   const PairTensor* pair_done;               // tensors with n != 0 here are skipped (may be null)
-  const P* parts;
+  const P* parts;                            // all records, or those of the row-group tiles when ...
+  const void* sparts;                        // ... the stream tiles' are of another type (else == parts)
   int seg_blocks;
   // the last fold of a whole pass also leaves the per-tensor records (ts != null): single-segment
   // tensors with their segment, tensors made of row-group tiles by one more workgroup each
   qv2_tensor_sums* ts; const qv2_qparams* params; const HistTensor* ht;
   const int* row_tensors; int pair_blocks;
+  ptrdiff_t mirror;                          // see put_record; 0 = none
 };
 
-template <class P>
+template <class P, class SP>
 __global__ __launch_bounds__(kFoldBlock) void k_fold_quant(const QuantFoldArgs<P> a) {
   const int b = blockIdx.x;
   if (b < a.seg_blocks) {
-    fold_err_item<P>(FoldIdx(b, a.wide_segs, a.n_wide_segs, a.nseg), a.segs, a.parts, a.sums,
-                     a.seg_xxhat, a.skip_below, a.keep_x2, a.ts, a.params, a.ht);
+    fold_err_item<P, SP>(FoldIdx(b, a.wide_segs, a.n_wide_segs, a.nseg), a.segs, a.parts,
+                         static_cast<const SP*>(a.sparts), a.sums,
+                         a.seg_xxhat, a.skip_below, a.keep_x2, a.ts, a.params, a.ht, a.mirror);
   } else if (b < a.seg_blocks + a.pair_blocks) {
     fold_pair_item<P>(FoldIdx(b - a.seg_blocks, a.wide_pt, a.n_wide_pt, a.nt), a.pt, a.parts,
-                      a.pair_out, a.pair_xq, a.pair_done);
+                      a.pair_out, a.pair_xq, a.pair_done, a.mirror);
   } else {
     const int t = a.row_tensors[b - a.seg_blocks - a.pair_blocks];
-    tensor_record(a.ht[t], a.params, a.sums, a.ts + t);
+    tensor_record(a.ht[t], a.params, a.sums, a.ts + t, a.mirror);
   }
 }
 

@@ -64,14 +64,26 @@ __device__ __forceinline__ void quant_body(gf4_ptr v4, gf_ptr b, gu32_ptr cw, gi
 // partial record of a quantize pass: 3 energies, plus the 2 cross terms when COS
 template <bool COS> struct ErrRec { typedef ErrPartial3 type; };
 template <> struct ErrRec<true> { typedef ErrPartial5 type; };
+// ... of its stream tiles: the same, except that the sweep which takes the error energy only
+// (no partner, no cross terms, sum x^2 kept from the first sweep) leaves just that one double
+template <bool PAIR, bool COS, bool X2> struct StreamRec { typedef typename ErrRec<COS>::type type; };
+template <> struct StreamRec<false, false, false> { typedef ErrPartial1 type; };
+__device__ __forceinline__ void set_cross(ErrPartial1&, double, double) {}
 __device__ __forceinline__ void set_cross(ErrPartial3&, double, double) {}
+__device__ __forceinline__ void set_energies(ErrPartial1& o, double, double se2, double) { o.se2 = se2; }
+__device__ __forceinline__ void set_energies(ErrPartial3& o, double sx2, double se2, double sd2) {
+  o.sx2 = sx2; o.se2 = se2; o.sd2 = sd2;
+}
+__device__ __forceinline__ void set_energies(ErrPartial5& o, double sx2, double se2, double sd2) {
+  o.sx2 = sx2; o.se2 = se2; o.sd2 = sd2;
+}
 __device__ __forceinline__ void set_cross(ErrPartial5& o, double sxh, double sxq) { o.sxh = sxh; o.sxq = sxq; }
 
 // RO: tiles of tensors without a code buffer (no store is compiled in; long tiles).
 template <int BLOCK, int V, bool PAIR, bool COS, bool X2 = true, bool RO = false>
 __global__ __launch_bounds__(BLOCK, (PAIR ? QV2_QUANT_WAVES_PER_EU : QV2_QUANT_PLAIN_WAVES_PER_EU)) void k_quant_stream(
     const StreamView tiles, const qv2_qparams* __restrict__ params,
-    typename ErrRec<COS>::type* __restrict__ parts) {
+    typename StreamRec<PAIR, COS, X2>::type* __restrict__ parts) {
   // Workgroups go to the 8 XCDs in turn.  The plain sweep (one read stream, one store stream)
   // runs 1.5 % faster (6 % without codes) when each XCD works through one contiguous eighth
   // of the tile table instead of every eighth tile; with qrun as a third stream it does not.
@@ -132,19 +144,19 @@ __global__ __launch_bounds__(BLOCK, (PAIR ? QV2_QUANT_WAVES_PER_EU : QV2_QUANT_P
     else quant_body<BLOCK, V, 0, false, COS, X2, true>(v4, bh, cw, cb, nvec, q, ae2, ax2, ad2, axh, axq);
   }
   se2 += ae2.total(); sx2 += ax2.total(); sd2 += ad2.total();
-  typename ErrRec<COS>::type o;
+  typename StreamRec<PAIR, COS, X2>::type o;
   if (COS) {
     double v[5] = {sx2, se2, sd2, sxh + axh.total(), sxq + axq.total()};
     block_sum<BLOCK, 5>(v);
-    o.sx2 = v[0]; o.se2 = v[1]; o.sd2 = v[2];
+    set_energies(o, v[0], v[1], v[2]);
     set_cross(o, v[3], v[4]);
   } else if (!X2 && !PAIR) {
     double v[1] = {se2};                            // the only energy this form takes
     block_sum<BLOCK, 1>(v);
-    o.sx2 = 0.0; o.se2 = v[0]; o.sd2 = 0.0;
+    set_energies(o, 0.0, v[0], 0.0);
   } else {
     block_sum3<BLOCK>(sx2, se2, sd2);
-    o.sx2 = sx2; o.se2 = se2; o.sd2 = sd2;
+    set_energies(o, sx2, se2, sd2);
   }
   if (tid == 0) st_record<RO>(&parts[tl.part0], o);
 }

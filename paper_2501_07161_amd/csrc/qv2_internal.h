@@ -219,6 +219,8 @@ struct StatPartial { float mn, mx; double sx, sx2; };   // calibrate, 24 B
 struct StatPairPartial { float mn, mx; double sx, sx2, sd2; };  // calibrate + pair comparison, 32 B
 struct StatPairCosPartial { float mn, mx; double sx, sx2, sd2, sxq; };  // ... + cosine cross term, 40 B
 struct ErrPartial { double sx2, se2; };                 // pair pass, 16 B
+struct ErrPartial1 { double se2; };                     // quantize sweep of a whole pass (the other energies
+                                                        // were taken by its first sweep), 8 B
 struct ErrPartial3 { double sx2, se2, sd2; };           // quantize passes, 24 B
 struct ErrPartial5 { double sx2, se2, sd2, sxh, sxq; }; // quantize pass with cosine cross terms, 40 B
 

@@ -248,7 +248,7 @@ void launch_rows(qv2_plan* plan, const qv2_qparams* d_params, qv2_qparams* d_par
 // the stream tiles of a quantize pass: those with a code buffer, then those without
 template <bool PAIR, bool COS, bool X2>
 void launch_quant_stream(qv2_plan* plan, int n_stream, int n_ro, const qv2_qparams* d_params,
-                         typename ErrRec<COS>::type* parts, hipStream_t s) {
+                         typename StreamRec<PAIR, COS, X2>::type* parts, hipStream_t s) {
   if (n_stream > 0)
     hipLaunchKernelGGL((k_quant_stream<kBlockQuant, kVecQuant, PAIR, COS, X2>), dim3(n_stream),
                        dim3(kBlockQuant), 0, s, plan->d_quant_tiles, d_params, parts);
@@ -265,9 +265,17 @@ template <bool PAIR, bool COS>
 void launch_quant(qv2_plan* plan, const qv2_qparams* d_params, qv2_sums* d_sums,
                   typename ErrRec<COS>::type* parts, double* d_seg_xxhat, qv2_pair_sums* d_pair_sums,
                   double* d_pair_xq, hipStream_t s, qv2_qparams* d_params_out = nullptr,
-                  bool pair_in_stats = false, qv2_tensor_sums* d_ts = nullptr) {
+                  bool pair_in_stats = false, qv2_tensor_sums* d_ts = nullptr, ptrdiff_t mirror = 0) {
   typedef typename ErrRec<COS>::type P;
+  typedef typename StreamRec<false, COS, false>::type SP;       // records of the sweep that keeps sum x^2
   const bool calib_rows = d_params_out != nullptr;
+  const bool lean = calib_rows && (!PAIR || pair_in_stats);     // ... which is the sweep of this call
+  // Where that sweep's records differ in size from the row-group tiles' (one double against
+  // three) they start behind the rows' range of slots; slot numbers stay what the plan gave.
+  SP* sparts = reinterpret_cast<SP*>(parts);
+  if (sizeof(SP) != sizeof(P))
+    sparts = reinterpret_cast<SP*>(reinterpret_cast<char*>(parts) + sizeof(P) * static_cast<size_t>(plan->n_row_parts)) -
+             plan->n_row_parts;
   const int n_stream = static_cast<int>(plan->quant_tiles.n_tiles);
   const int n_ro = static_cast<int>(plan->quant_ro_tiles.n_tiles);
   const int n_rows = static_cast<int>(plan->row_tiles.size() + plan->reg_tiles.size() + plan->wide_tiles.size());
@@ -278,7 +286,7 @@ void launch_quant(qv2_plan* plan, const qv2_qparams* d_params, qv2_sums* d_sums,
     if (PAIR && !pair_in_stats)
       launch_quant_stream<PAIR, COS, true>(plan, n_stream, n_ro, d_params, parts, s);
     else if (calib_rows)      // the calibration sweep of this same call already summed x^2
-      launch_quant_stream<false, COS, false>(plan, n_stream, n_ro, d_params, parts, s);
+      launch_quant_stream<false, COS, false>(plan, n_stream, n_ro, d_params, sparts, s);
     else
       launch_quant_stream<false, COS, true>(plan, n_stream, n_ro, d_params, parts, s);
   }
@@ -295,7 +303,7 @@ void launch_quant(qv2_plan* plan, const qv2_qparams* d_params, qv2_sums* d_sums,
   a.wide_segs = plan->d_big_err_segments; a.n_wide_segs = static_cast<int>(plan->big_err_segments.size());
   a.sums = d_sums; a.seg_xxhat = d_seg_xxhat; a.skip_below = calib_rows ? plan->n_row_parts : 0;
   a.keep_x2 = calib_rows && (!PAIR || pair_in_stats);
-  a.parts = parts;
+  a.parts = parts; a.sparts = lean ? static_cast<const void*>(sparts) : static_cast<const void*>(parts);
   a.seg_blocks = fold_blocks(a.n_wide_segs, a.nseg);
   int blocks = a.seg_blocks;
   if (d_pair_sums) {
@@ -311,13 +319,15 @@ void launch_quant(qv2_plan* plan, const qv2_qparams* d_params, qv2_sums* d_sums,
     // the whole pass: this fold also leaves the per-tensor records.  The rows' segment records
     // are final by now (calib_rows), so the tensors made of them get one workgroup each here.
     a.ts = d_ts; a.params = d_params; a.ht = plan->d_hist_tensors; a.row_tensors = plan->d_row_tensors;
+    a.mirror = mirror;
     blocks += static_cast<int>(plan->row_tensors.size());
   }
-  hipLaunchKernelGGL(k_fold_quant<P>, dim3(blocks), dim3(kFoldBlock), 0, s, a);
+  if (lean) hipLaunchKernelGGL((k_fold_quant<P, SP>), dim3(blocks), dim3(kFoldBlock), 0, s, a);
+  else hipLaunchKernelGGL((k_fold_quant<P, P>), dim3(blocks), dim3(kFoldBlock), 0, s, a);
   // tensors of several stream segments: their segment records were written by that very launch
   if (d_ts && !plan->late_tensors.empty())
     hipLaunchKernelGGL(k_tensor_fold, dim3(static_cast<int>(plan->late_tensors.size())), dim3(kFoldBlock), 0, s,
-                       plan->d_hist_tensors, plan->d_late_tensors, d_params, d_sums, d_ts);
+                       plan->d_hist_tensors, plan->d_late_tensors, d_params, d_sums, d_ts, mirror);
 }
 
 // calibration over the stream tiles (and the row-group tiles unless their own single-read
@@ -326,7 +336,7 @@ void launch_quant(qv2_plan* plan, const qv2_qparams* d_params, qv2_sums* d_sums,
 template <bool PAIR, bool COS = false>
 void launch_stats(qv2_plan* plan, qv2_qparams* d_params, qv2_sums* d_sums,
                   typename StatRec<PAIR, COS>::type* parts, bool with_rows, qv2_pair_sums* d_pair_sums,
-                  double* d_pair_xq, hipStream_t s) {
+                  double* d_pair_xq, hipStream_t s, ptrdiff_t mirror = 0) {
   typedef typename StatRec<PAIR, COS>::type REC;
   if (PAIR) with_rows = false;      // the row kernel of this pass writes 24-byte records: not in a PAIR sweep
   const int n_stream = static_cast<int>(plan->read_tiles.n_tiles);
@@ -366,7 +376,7 @@ void launch_stats(qv2_plan* plan, qv2_qparams* d_params, qv2_sums* d_sums,
       a.pt = plan->d_stat_pair_tensors; a.nt = static_cast<int>(plan->stat_pair_tensors.size());
       a.wide_pt = plan->d_big_stat_pair_tensors;
       a.n_wide_pt = static_cast<int>(plan->big_stat_pair_tensors.size());
-      a.pair_out = d_pair_sums; a.pair_xq = d_pair_xq;
+      a.pair_out = d_pair_sums; a.pair_xq = d_pair_xq; a.mirror = mirror;
       blocks += fold_blocks(a.n_wide_pt, a.nt);
     }
     hipLaunchKernelGGL(k_fold_stats<REC>, dim3(blocks), dim3(kFoldBlock), 0, s, a);
@@ -376,7 +386,7 @@ void launch_stats(qv2_plan* plan, qv2_qparams* d_params, qv2_sums* d_sums,
 // steps 1-3 of the single call, on a workspace of at least plan->workspace_bytes; d_ts != null
 // (needs d_pair_sums): the per-tensor records as well, made inside the last fold
 void single_call(qv2_plan* plan, qv2_qparams* d_params, qv2_sums* d_sums, qv2_pair_sums* d_pair_sums,
-                 void* d_workspace, hipStream_t s, qv2_tensor_sums* d_ts = nullptr) {
+                 void* d_workspace, hipStream_t s, qv2_tensor_sums* d_ts = nullptr, ptrdiff_t mirror = 0) {
   // stream tiles: statistics (with the pair comparison: that sweep only reads, and read-only
   // sweeps run nearest to the HBM rate), fold (parameters), then the plain quantize sweep;
   // row-group tiles: one kernel, after the statistics fold because the partial records share
@@ -384,9 +394,9 @@ void single_call(qv2_plan* plan, qv2_qparams* d_params, qv2_sums* d_sums, qv2_pa
   ErrPartial3* parts = static_cast<ErrPartial3*>(d_workspace);
   if (d_pair_sums) {
     launch_stats<true>(plan, d_params, d_sums, static_cast<StatPairPartial*>(d_workspace), false, d_pair_sums,
-                       nullptr, s);
+                       nullptr, s, d_ts ? mirror : 0);
     launch_quant<true, false>(plan, d_params, d_sums, parts, nullptr, d_pair_sums, nullptr, s, d_params, true,
-                              d_ts);
+                              d_ts, d_ts ? mirror : 0);
   } else {
     launch_stats<false>(plan, d_params, d_sums, static_cast<StatPartial*>(d_workspace), false, nullptr, nullptr, s);
     launch_quant<false, false>(plan, d_params, d_sums, parts, nullptr, nullptr, nullptr, s, d_params);
@@ -592,11 +602,25 @@ qv2_status qv2_tensor_sums_fold(qv2_plan* plan, const qv2_qparams* d_params, con
   if (st != QV2_OK) return st;
   const int nt = static_cast<int>(plan->info.size());
   hipLaunchKernelGGL(k_tensor_fold, dim3(nt), dim3(kFoldBlock), 0, static_cast<hipStream_t>(hip_stream),
-                     plan->d_hist_tensors, static_cast<const int*>(nullptr), d_params, d_sums, d_tensor_sums);
+                     plan->d_hist_tensors, static_cast<const int*>(nullptr), d_params, d_sums, d_tensor_sums,
+                     static_cast<ptrdiff_t>(0));
   return launch_status();
 }
 
 namespace {
+
+// The device-side address of a host buffer when that buffer is pinned host memory the current
+// device can write (hipHostMalloc), else null.  Asked anew at every call: an address that was
+// pinned memory once may be something else by now.
+const char* host_alias(void* h) {
+  hipPointerAttribute_t attr;
+  if (hipPointerGetAttributes(&attr, h) != hipSuccess) {
+    (void)hipGetLastError();                     // ordinary host memory is not known to the runtime
+    return nullptr;
+  }
+  if (attr.type != hipMemoryTypeHost || !attr.devicePointer) return nullptr;
+  return static_cast<const char*>(attr.devicePointer);
+}
 
 // device part of qv2_sensitivity_pass: the single call, the per-tensor fold and the copy of the
 // per-tensor records to the host, all enqueued on hip_stream
@@ -611,11 +635,15 @@ qv2_status pass_enqueue(qv2_plan* plan, qv2_qparams* d_params, qv2_sums* d_sums,
   qv2_status st = check_call(plan, d_params, d_sums, d_workspace, workspace_bytes);
   if (st != QV2_OK) return st;
   if ((st = ensure_uploaded(plan)) != QV2_OK) return st;
-  // the single call; its last fold also makes the per-tensor records
-  single_call(plan, d_params, d_sums, d_pair, d_workspace, static_cast<hipStream_t>(hip_stream), d_ts);
+  // the single call; its last fold also makes the per-tensor records.  When h_records is pinned
+  // host memory the device can address, the folds write every record there as well and no copy
+  // follows; otherwise one copy brings them over.
+  const char* alias = host_alias(h_records);
+  const ptrdiff_t mirror = alias ? alias - static_cast<const char*>(d_records) : 0;
+  single_call(plan, d_params, d_sums, d_pair, d_workspace, static_cast<hipStream_t>(hip_stream), d_ts, mirror);
   if ((st = launch_status()) != QV2_OK) return st;
-  if (hipMemcpyAsync(h_records, d_records, ts_bytes + nt * sizeof(qv2_pair_sums), hipMemcpyDeviceToHost,
-                     static_cast<hipStream_t>(hip_stream)) != hipSuccess) {
+  if (!mirror && hipMemcpyAsync(h_records, d_records, ts_bytes + nt * sizeof(qv2_pair_sums),
+                                hipMemcpyDeviceToHost, static_cast<hipStream_t>(hip_stream)) != hipSuccess) {
     (void)hipGetLastError();
     return QV2_ERR_HIP;
   }

@@ -707,6 +707,19 @@ def test_pass_records_equal_single_call_plus_tensor_fold():
     assert out.tensor_sums.tobytes() == res.tsums.tobytes()
     assert out.pair_sums.tobytes() == res.pair.tobytes()
     assert all(torch.equal(it.codes, w) for it, w in zip(items, want_codes))
+    # h_records in ordinary (pageable) host memory: the records come over by a copy instead of being
+    # written there by the folds; same bytes
+    import ctypes
+    nt = res.plan.num_tensors
+    h_plain = np.zeros(nt * (qb.TENSOR_SUMS.itemsize + qb.PAIR_SUMS.itemsize), np.uint8)
+    order = np.zeros(n_layers, np.int32)
+    st = qb.lib().qv2_sensitivity_pass(res.plan.handle, buf.params.data_ptr(), buf.sums.data_ptr(),
+                                       out.d_records.data_ptr(), h_plain.ctypes.data, buf.workspace.data_ptr(),
+                                       buf.workspace.numel(), None, None, n_layers, None, None, None, None,
+                                       order.ctypes.data, None)
+    assert st == qb.QV2_OK and order.tolist() == out.order.tolist()
+    assert h_plain.tobytes() == out.h_records.numpy().tobytes()
+    assert out.d_records.cpu().numpy().tobytes() == h_plain.tobytes()       # the device copy is written too
     # and the two halves of the pass give the same again
     prep = qb.PreparedPass(res.plan, buf.params, buf.sums, [out, qb.PassOutputs(res.plan, n_layers, DEV)],
                            buf.workspace)
