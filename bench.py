@@ -90,6 +90,12 @@ def parse():
     ap.set_defaults(cold=True)
     ap.add_argument("--no-single-tensor-extra", action="store_true",
                     help="skip the 1600 tiny fake-quant calls of extras.fakequant_single_tensor_us (profiling runs)")
+    ap.add_argument("--second-read-probe", action="store_true",
+                    help="instead of the benchmark: for single tensors of 8 MB ... 800 MB time the quantize sweep "
+                         "right after the calibration sweep of the same tensor and again after a 1 GiB fill in "
+                         "between (does the second read of x come from the 256 MB memory-side cache?), and a "
+                         "read-only sweep repeated on the same tensor; one JSON line.  Run it with the in-tree "
+                         "library (non-temporal loads) and with a QV2_NT_LOADS=0 build named by QV2_LIB_PATH")
     ap.add_argument("--copy-probe", action="store_true",
                     help="after the timed region also run 3 plain 1 GiB device copies (a kernel of known "
                          "traffic, used to scale rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
@@ -332,6 +338,50 @@ class Runner:
         return float(np.mean(ts)) * 1e3
 
 
+def second_read_probe(dev):
+    """Per tensor size: the calibration sweep, then the quantize sweep of the same tensor, (warm) back
+    to back, (cold) with a 1 GiB fill between the two, (requant) the quantize sweep alone repeated;
+    and the calibration sweep alone repeated.  Kernel durations from the library's HIP events."""
+    import numpy as np
+    import torch
+    from paper_2501_07161_amd import binding as qb
+    flush = torch.empty(1 << 28, dtype=torch.float32, device=dev)
+    out = {"library": os.path.basename(qb.LIB_PATH), "sizes": {}}
+    for mb in (8, 16, 32, 64, 96, 128, 160, 200, 256, 400, 800):
+        n = mb * 1024 * 1024 // 4
+        x = torch.randn(n, device=dev).clamp_(min=0)
+        c = torch.empty(n, dtype=torch.int8, device=dev)
+        plan = qb.qv2_plan_create([qb.TensorArg(x=x, numel=n, codes=c)])
+        buf = qb.Buffers(plan, dev)
+        qb.qv2_plan_set_timing(plan, True)
+        rec = {}
+        for mode in ("warm", "cold", "requant"):
+            ts, tq = [], []
+            for it in range(8):
+                if mode != "requant":
+                    flush.fill_(1.0)
+                    qb.qv2_calibrate(plan, buf.params, buf.sums, buf.workspace)
+                if mode == "cold":
+                    flush.fill_(1.0)
+                qb.qv2_fakequant_metrics(plan, buf.params, buf.sums, buf.workspace)
+                torch.cuda.synchronize()
+                if it >= 2:
+                    ts.append(qb.qv2_plan_kernel_ms(plan, "k_stats_stream"))
+                    tq.append(qb.qv2_plan_kernel_ms(plan, "k_quant_stream"))
+            rec[mode] = {"stats_us": round(float(np.median(ts)) * 1e3, 1), "quant_us": round(float(np.median(tq)) * 1e3, 1)}
+        ts = []
+        for it in range(8):
+            qb.qv2_calibrate(plan, buf.params, buf.sums, buf.workspace)
+            torch.cuda.synchronize()
+            if it >= 2:
+                ts.append(qb.qv2_plan_kernel_ms(plan, "k_stats_stream"))
+        rec["restats_us"] = round(float(np.median(ts)) * 1e3, 1)
+        out["sizes"][f"{mb}MB"] = rec
+        plan.close()
+        del x, c, buf
+    return out
+
+
 def gbps(nbytes, ms):
     return nbytes / (ms * 1e-3) / 1e9
 
@@ -367,10 +417,14 @@ def side_workloads(args, dev, head):
             ("vgg16", {"per_channel": False}), ("resnet50", {"bnfold": True, "share": head})]
     for name, kw in todo:
         wl = Workload(name, DEFAULT_BATCH[name], dev, **kw)
-        rn = Runner(wl, dev, args.steps, args.warmup)
+        # a pass over these sets takes a fraction of a millisecond: ten times the steps, so that the
+        # timed region is not a few milliseconds of a clock that is still ramping
+        steps = args.steps * (1 if kw.get("bnfold") else 10)
+        rn = Runner(wl, dev, steps, args.warmup)
         r = rn.timed("single")
         pipe = rn.timed_pipelined()
         rec = summarize(wl, r, pipe, "single")
+        rec["steps"] = steps
         rn.step("calls")
         rec["same_order_as_three_calls"] = [int(v) for v in rn.last["order"]] == r["order"]
         out[wl.tag] = rec
@@ -399,6 +453,10 @@ def main():
     qb.lib()                                  # raises if libqv2.so has not been built
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+
+    if args.second_read_probe:
+        print(json.dumps(second_read_probe(dev)), flush=True)
+        return
 
     batch = args.batch or DEFAULT_BATCH[args.workload]
     wl = Workload(args.workload, batch, dev, bnfold=args.fused, per_channel=not args.per_tensor)

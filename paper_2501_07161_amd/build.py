@@ -30,4 +30,10 @@ def build_lib(verbose: bool = False, defines=(), out: str = LIB) -> str:
 
 
 if __name__ == "__main__":
-    build_lib(verbose=True)
+    import argparse
+    ap = argparse.ArgumentParser(description="build libqv2.so, or a variant of it for a measurement")
+    ap.add_argument("--define", action="append", default=[], metavar="NAME=VALUE",
+                    help="extra -D option, e.g. QV2_NT_LOADS=0 (plain instead of non-temporal loads)")
+    ap.add_argument("--out", default=LIB, help="output file (default: the in-tree library)")
+    a = ap.parse_args()
+    build_lib(verbose=True, defines=a.define, out=a.out)
