@@ -92,7 +92,7 @@ __global__ __launch_bounds__(BLOCK, (PAIR ? QV2_QUANT_WAVES_PER_EU : QV2_QUANT_P
     const int per = gridDim.x >> 3;
     if (bt < (per << 3)) bt = (bt & 7) * per + (bt >> 3);
   }
-  const TileRef tl = decode_tile(tiles, bt);
+  const TileRef tl = decode_tile<(!PAIR && !COS && !X2 && !RO)>(tiles, bt);
   const QP q = load_qp(params, tl.seg0);
   const gf_ptr p = (gf_ptr)tl.x;
   const gf_ptr b = (gf_ptr)tl.q;

@@ -48,6 +48,7 @@ int64_t add_run(StreamTable& tab, const qv2_tensor& in, int32_t t, int64_t nseg,
   r.part0 = static_cast<int32_t>(part0);
   r.tile_len = static_cast<int32_t>(T);
   r.tensor = t;
+  r.tile_end = static_cast<int32_t>(tab.n_tiles + nseg * per_seg);
   tab.runs.push_back(r);
   tab.n_tiles += nseg * per_seg;
   return nseg * per_seg;

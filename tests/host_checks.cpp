@@ -73,7 +73,7 @@ std::vector<Tile> decoded(const qv2::StreamTable& tab, int64_t block) {
     CHECK(rn.tile0 == at && rn.tiles_per_seg > 0 && rn.tile_len > 0 && rn.inner > 0);
     CHECK(rn.tiles_per_seg == (rn.inner + rn.tile_len - 1) / rn.tile_len);
     at += r + 1 < tab.runs.size() ? tab.runs[r + 1].tile0 - rn.tile0 : tab.n_tiles - rn.tile0;
-    CHECK((at - rn.tile0) % rn.tiles_per_seg == 0 && at > rn.tile0);
+    CHECK((at - rn.tile0) % rn.tiles_per_seg == 0 && at > rn.tile0 && rn.tile_end == at);
   }
   CHECK(at == tab.n_tiles);
   for (size_t b = 0; b < tab.coarse.size() && !tab.runs.empty(); ++b) {
@@ -82,7 +82,9 @@ std::vector<Tile> decoded(const qv2::StreamTable& tab, int64_t block) {
     CHECK(r >= 0 && r < static_cast<int32_t>(tab.runs.size()));
     CHECK(tab.runs[r].tile0 <= static_cast<int64_t>(b) << tab.shift || r == 0);
   }
-  return tab.expand();
+  std::vector<Tile> out = tab.expand();              // decodes every tile both ways; empty if they differ
+  CHECK(static_cast<int64_t>(out.size()) == tab.n_tiles);
+  return out;
 }
 
 void check_plan(const std::vector<qv2_tensor>& rows) {
