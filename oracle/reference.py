@@ -355,16 +355,12 @@ def rank_layers(w_sqnr, a_sqnr, w_mse, a_mse, pos=None, cfg: RankConfig | None =
             k = M[i] if len(sources) == 1 else (M[i] / mean if mean > 0 else 0.0)
             key[i] = max(key[i], k)
 
-    # the list by score, largest SQNR drop (most negative score) first; equal scores keep layer order
-    order = sorted(range(n), key=lambda i: (G[i], i))
-    # every MSE outlier is then moved to the head of that list.  They are taken in ascending MSE,
-    # so the largest one is moved last and ends up first; of equal ones the lower index leads.
-    outliers = sorted((i for i in range(n) if is_out[i]), key=lambda i: (key[i], -i))
-    for l in outliers:
-        if l in order:
-            order.remove(l)
-            order.insert(0, l)
-    return order, G
+    # Algorithm 2 ends with two groups.  The MSE outliers lead, the largest first (equal ones in
+    # layer order); every other layer follows by score, the largest SQNR drop (most negative
+    # score) first, equal scores in layer order.
+    head = sorted((i for i in range(n) if is_out[i]), key=lambda i: (-key[i], i))
+    rest = sorted((i for i in range(n) if not is_out[i]), key=lambda i: (G[i], i))
+    return head + rest, G
 
 
 # ----------------------------------------------------------------------------

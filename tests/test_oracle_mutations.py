@@ -39,8 +39,8 @@ MUTATIONS = [
     (PY, "out[i] = (s[i] - s[i - 1]) / dl", "out[i] = (s[i] - s[i - 1]) * dl"),          # position gap
     (PY, "if M[i] > cfg.mse_factor * mean:", "if M[i] >= cfg.mse_factor * mean:"),       # strict >
     (PY, "mean = total / n if n else 0.0", "mean = total / (n - 1) if n > 1 else 0.0"),
-    (PY, "order = sorted(range(n), key=lambda i: (G[i], i))", "order = sorted(range(n), key=lambda i: (-G[i], i))"),
-    (PY, "key=lambda i: (key[i], -i))", "key=lambda i: (-key[i], i))"),                   # largest outlier last
+    (PY, "if not is_out[i]), key=lambda i: (G[i], i))", "if not is_out[i]), key=lambda i: (-G[i], i))"),    # list by descending score
+    (PY, "if is_out[i]), key=lambda i: (-key[i], i))", "if is_out[i]), key=lambda i: (key[i], i))"),   # largest outlier last
     (PY, "mixed += (32.0 if k else 8.0) * float(m)", "mixed += (32.0 if k else 8.0) ** 2 / 32.0 * float(m)"),
     (PY, "if bops_reduction_pct(macs, keep) < target_pct:", "if bops_reduction_pct(macs, keep) <= target_pct:"),
     (PY, "return list(range(n - 1, -1, -1))", "return list(range(n))"),                  # InOrder direction
