@@ -419,13 +419,15 @@ qv2_status qv2_rank_tensors(const qv2_plan* plan, const qv2_tensor_sums* h_tenso
                             int32_t n_layers, const qv2_rank_config* cfg, int32_t* order_out,
                             double* score_out);
 
-/* Steps 1-4 in one host call: qv2_calibrate_fakequant_pair_metrics, qv2_tensor_sums_fold,
- * ONE copy of the per-tensor records to the host, Eq. 6-7 for every tensor and pair, and
- * qv2_rank_tensors.  Unlike the device calls above it waits for hip_stream (the ranking needs
- * the records), so it returns with every output valid.
+/* Steps 1-4 in one host call: the device work of qv2_calibrate_fakequant_pair_metrics, whose
+ * last fold here also makes the per-tensor records of qv2_tensor_sums_fold (same bits), then
+ * Eq. 6-7 for every tensor and pair and qv2_rank_tensors on the host.  Unlike the device calls
+ * above it waits for hip_stream (the ranking needs the records), so it returns with every
+ * output valid.
  * d_records / h_records: num_tensors qv2_tensor_sums followed by num_tensors qv2_pair_sums
- *   (80 bytes per tensor), DEVICE and HOST, 8-byte aligned; both are written.  Pinned host
- *   memory lets the copy run without a staging buffer.
+ *   (80 bytes per tensor), DEVICE and HOST, 8-byte aligned; both are written.  When h_records
+ *   is pinned host memory that the device can address (hipHostMalloc), the fold kernels write
+ *   every record there as well and no copy follows; otherwise one copy brings them over.
  * d_params / d_sums / d_workspace / hip_stream: as in qv2_calibrate_fakequant_pair_metrics.
  * layer_pos / n_layers / cfg / order_out / score_out: as in qv2_rank_tensors.
  * h_metrics[num_tensors], h_pair_mse[num_tensors], h_pair_sqnr_db[num_tensors]: each may be
@@ -445,9 +447,9 @@ qv2_status qv2_sensitivity_pass(qv2_plan* plan, qv2_qparams* d_params, qv2_sums*
 
 /* qv2_sensitivity_pass in two halves, so that a caller who runs pass after pass (a calibration
  * service; a sweep over rank configurations) can overlap the host half of one pass with the device
- * half of the next.  _begin enqueues the device work and the copy of the records on hip_stream
- * and marks its end with one of the plan's two completion events (slot 0 or 1; created on first
- * use); it does not wait.  _end waits for that mark, then finalizes and ranks as
+ * half of the next.  _begin enqueues the device work (and the copy of the records, where
+ * h_records is not pinned) on hip_stream and marks its end with one of the plan's two
+ * completion events (slot 0 or 1; created on first use); it does not wait.  _end waits for that mark, then finalizes and ranks as
  * qv2_sensitivity_pass does, from the same h_records.  Two passes may be in flight on one plan
  * when they use different slots and different h_records (which should be pinned, or the copy
  * blocks); they share the device buffers, which is safe on one stream.  Arguments and errors as

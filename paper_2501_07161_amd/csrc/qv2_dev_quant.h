@@ -284,7 +284,6 @@ __global__ __launch_bounds__(BLOCK) void k_quant_rows(const Tile* __restrict__ t
 //          parameter and sum records itself.
 template <int BLOCK, int ROLE, bool PAIR, bool COS>
 __global__ __launch_bounds__(BLOCK) void k_rows_reg(const Tile* __restrict__ tiles,
-                                                    const Segment* __restrict__ segs,
                                                     const qv2_qparams* __restrict__ params,
                                                     qv2_qparams* __restrict__ params_out,
                                                     qv2_sums* __restrict__ sums_out,

@@ -226,21 +226,21 @@ void launch_rows(qv2_plan* plan, const qv2_qparams* d_params, qv2_qparams* d_par
   if (n_regs > 0) {
     if (calib)
       hipLaunchKernelGGL((k_rows_reg<kBlockRows, 2, PAIR, COS>), dim3(n_regs), dim3(kBlockRows), 0, s,
-                         plan->d_reg_tiles, plan->d_segments, d_params, d_params_out, d_sums,
+                         plan->d_reg_tiles, d_params, d_params_out, d_sums,
                          static_cast<void*>(parts));
     else
       hipLaunchKernelGGL((k_rows_reg<kBlockRows, 1, PAIR, COS>), dim3(n_regs), dim3(kBlockRows), 0, s,
-                         plan->d_reg_tiles, plan->d_segments, d_params, d_params_out, d_sums,
+                         plan->d_reg_tiles, d_params, d_params_out, d_sums,
                          static_cast<void*>(parts));
   }
   if (n_wide > 0) {
     if (calib)
       hipLaunchKernelGGL((k_rows_reg<kBlockRowsWide, 2, PAIR, COS>), dim3(n_wide), dim3(kBlockRowsWide), 0, s,
-                         plan->d_wide_tiles, plan->d_segments, d_params, d_params_out, d_sums,
+                         plan->d_wide_tiles, d_params, d_params_out, d_sums,
                          static_cast<void*>(parts));
     else
       hipLaunchKernelGGL((k_rows_reg<kBlockRowsWide, 1, PAIR, COS>), dim3(n_wide), dim3(kBlockRowsWide), 0, s,
-                         plan->d_wide_tiles, plan->d_segments, d_params, d_params_out, d_sums,
+                         plan->d_wide_tiles, d_params, d_params_out, d_sums,
                          static_cast<void*>(parts));
   }
 }
@@ -355,12 +355,12 @@ void launch_stats(qv2_plan* plan, qv2_qparams* d_params, qv2_sums* d_sums,
                          plan->d_row_tiles, reinterpret_cast<StatPartial*>(parts));
     if (n_regs > 0)
       hipLaunchKernelGGL((k_rows_reg<kBlockRows, 0, false, false>), dim3(n_regs), dim3(kBlockRows), 0, s,
-                         plan->d_reg_tiles, plan->d_segments, static_cast<const qv2_qparams*>(nullptr),
+                         plan->d_reg_tiles, static_cast<const qv2_qparams*>(nullptr),
                          static_cast<qv2_qparams*>(nullptr), static_cast<qv2_sums*>(nullptr),
                          static_cast<void*>(parts));
     if (n_wide > 0)
       hipLaunchKernelGGL((k_rows_reg<kBlockRowsWide, 0, false, false>), dim3(n_wide), dim3(kBlockRowsWide), 0, s,
-                         plan->d_wide_tiles, plan->d_segments, static_cast<const qv2_qparams*>(nullptr),
+                         plan->d_wide_tiles, static_cast<const qv2_qparams*>(nullptr),
                          static_cast<qv2_qparams*>(nullptr), static_cast<qv2_sums*>(nullptr),
                          static_cast<void*>(parts));
   }
