@@ -249,6 +249,34 @@ def test_random_layer_tables(seed):
         H.check_all(items, res)
 
 
+@pytest.mark.parametrize("fused", [False, "single"])
+def test_thousands_of_tensors(fused):
+    """A layer table of 3000 tensors, most of them a fraction of one tile, a few long ones in
+    between: the table from tile index to tensor then has fewer entries than there are tensors,
+    so finding a tile walks over several records, and the fold launches see thousands of one-record
+    segments."""
+    rng = np.random.default_rng(77)
+    items = []
+    for i in range(3000):
+        r = rng.random()
+        if i % 750 == 400:
+            c, inner, scheme = 1, 150_001 + i, A
+        elif r < 0.6:
+            c, inner, scheme = 1, int(rng.integers(1, 2500)), (A if rng.random() < 0.5 else S)
+        elif r < 0.9:
+            c, inner, scheme = int(rng.integers(1, 9)), int(rng.integers(1, 200)), C
+        else:
+            c, inner, scheme = int(rng.integers(1, 4)), int(rng.choice([64, 128, 576, 1024])), C
+        n = c * inner
+        x = _rand(n, 90_000 + i, float(rng.choice([0.05, 1.0, 8.0])))
+        q = x * 0.98 + 0.001 if rng.random() < 0.5 else None
+        items.append(H.Item(f"n{i}.{c}x{inner}", x, scheme, c, int(rng.integers(0, 2)), len(items), qrun=q,
+                            want_codes=bool(rng.random() < 0.9)))
+    res = H.run_gpu(items, fused=fused)
+    assert res.plan.num_tensors == 3000
+    H.check_all(items, res)
+
+
 def test_cached_params_clip_both_ends():
     """Parameters handed in by the caller (the calibration cache) instead of calibrating:
     a range narrower than the data saturates codes at -128 and 127."""
