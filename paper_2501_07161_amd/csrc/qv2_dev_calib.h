@@ -75,7 +75,11 @@ __device__ __forceinline__ void stats_body(gf4_ptr v4, gf_ptr b, int nvec, StatA
 template <int BLOCK, int V, bool PAIR, bool COS>
 __global__ __launch_bounds__(BLOCK) void k_stats_stream(const StreamView tiles,
                                                         typename StatRec<PAIR, COS>::type* __restrict__ parts) {
-  const TileRef tl = decode_tile(tiles, blockIdx.x);
+  // XCD-aware tile order (see xcd_blocked) for the sweep that also reads qrun: -2 %.  The sweep
+  // over x alone is 1 % faster in table order.
+  int bt = blockIdx.x;
+  if (PAIR) bt = xcd_blocked(bt, static_cast<int>(gridDim.x), kXcdBlockRead);
+  const TileRef tl = decode_tile(tiles, bt);
   const gf_ptr p = (gf_ptr)tl.x;
   const gf_ptr b = (gf_ptr)tl.q;
   const int len = tl.len, tid = threadIdx.x;

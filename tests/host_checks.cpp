@@ -538,12 +538,31 @@ void config_file(const char* dir) {
 
 }  // namespace
 
+// the XCD-aware tile order of the sweeps is a permutation of the tile indices for any launch size
+void tile_order() {
+  for (int block : {1, 16, 256}) {
+    for (int n : {1, 7, 8, 127, 128, 129, 2047, 2048, 2049, 4095, 4096, 12345, 82720, 1323517}) {
+      std::vector<uint8_t> seen(static_cast<size_t>(n), 0);
+      for (int k = 0; k < n; ++k) {
+        const int t = qv2::xcd_blocked(k, n, block);
+        CHECK(t >= 0 && t < n);
+        CHECK(!seen[static_cast<size_t>(t)]);
+        seen[static_cast<size_t>(t)] = 1;
+      }
+      // consecutive workgroups of one XCD (k, k + 8, ...) take neighbouring tiles inside a whole group
+      if (n >= 16 * block && block > 1)
+        CHECK(qv2::xcd_blocked(8, n, block) == qv2::xcd_blocked(0, n, block) + 1);
+    }
+  }
+}
+
 int main(int argc, char** argv) {
   config_file(argc > 1 ? argv[1] : "/tmp");
   plans();
   ranking();
   rank_from_records();
   small_host_functions();
+  tile_order();
   std::printf("host checks ok\n");
   return 0;
 }
