@@ -20,7 +20,8 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
 
 
 def build_lib(verbose: bool = False, defines=(), out: str = LIB) -> str:
-    """defines: extra -D options (tuning knobs QV2_UNROLL, QV2_NT_LOADS, QV2_BLOCK)."""
+    """defines: extra -D options (the tuning knobs of csrc/: QV2_BLOCK_READ, QV2_VEC_READ, QV2_NT_LOADS,
+    QV2_XCD_BLOCK_READ, ...)."""
     cmd = ["hipcc", *FLAGS, *[f"-D{d}" for d in defines], "-I", os.path.join(ROOT, "include"),
            "-I", CSRC, "-x", "hip", *SOURCES, "-o", out]
     if verbose:
